@@ -1,0 +1,286 @@
+/*
+ * CPU oracle for the OCS-expanded quantized layer (Zhao et al., "Improving Neural
+ * Network Quantization without Retraining using Outlier Channel Splitting").
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, literal statement of what the
+ * method computes; the GPU library never calls it, links it or shares a line with it.
+ * Everything here works on host pointers, one element at a time, in the order the
+ * paper describes the method:
+ *
+ *   Sec. 3.4   split budget ceil(r*C); splits are made one at a time, each on the
+ *              channel that currently holds the largest |value| in the layer
+ *   Sec. 3.2   Eq. 3 (duplicate the channel, halve both weight copies) and Eq. 4
+ *              (duplicate the channel, halve both activation copies)
+ *   Sec. 3.1   Eq. 1, symmetric k-bit linear grid with 2^k - 1 points
+ *   Sec. 1     clipping = narrowing the grid, i.e. saturating beyond a threshold
+ *   Sec. 5.2   OCS first, clip afterwards
+ *   Sec. 3.2   Eq. 2, the linear layer, evaluated on the integer codes
+ *
+ * Precision.  A code is an integer decided by floating point, so the decision is taken
+ * in the arithmetic the GPU kernels use: fp32, one correctly rounded division
+ * qmax / T, one multiply, round-half-to-even, saturate.  Halving is exact in any
+ * binary format.  The dequantized output is evaluated in fp64.
+ *
+ * Parity pins live in tests/test_oracle_pins.py (functional identity of the split
+ * layer, halving of every split channel's maximum, greedy == brute force, the grid's
+ * definition, the s = 0 case against a library matmul, the w = 3 example of Sec. 3.3,
+ * Table 4's weight-size row).  Unpinned: nothing in this file; the paper's accuracy
+ * tables are not reproduced (datasets and trained weights are needed for those).
+ *
+ * Build: gcc -O2 -std=c99 -ffp-contract=off -fno-fast-math -fopenmp -shared -fPIC
+ * OpenMP only partitions independent rows over threads; it changes no arithmetic.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#include <omp.h>
+
+#define REF_OK 0
+#define REF_E_ARG (-1)
+#define REF_E_OVERFLOW (-2)
+#define REF_E_NOMEM (-3)
+
+#define REF_MODE_HALVE 0 /* Eq. 3: greedy selection on this tensor, both copies halved   */
+#define REF_MODE_DUP 1   /* Eq. 4, weight side: selection given, copies left un-halved   */
+
+void ref_set_threads(int n) {
+    if (n > 0) omp_set_num_threads(n);
+}
+
+int ref_get_threads(void) { return omp_get_max_threads(); }
+
+/* Sec. 3.4: a layer with C channels receives ceil(r*C) splits. */
+int ref_num_splits(int C, double r) {
+    if (C <= 0 || !(r > 0.0)) return 0;
+    return (int)ceil(r * (double)C);
+}
+
+/*
+ * Sec. 3.4 + Eq. 3 / Eq. 4 (weight side), done literally.
+ *
+ * T is [rows, C*g] row-major with leading dimension ld; channel c owns columns
+ * c*g .. c*g+g-1 (a 2-D filter of an im2col'd convolution, or one column of an FC
+ * layer).  T_out is [rows, (C+s)*g] with leading dimension ldo and always receives
+ * the expanded tensor.
+ *
+ * MODE_HALVE: for each of the s steps, scan every element of the current expanded
+ * tensor, take the channel holding the largest magnitude (lowest expanded index on
+ * ties), append a copy of that channel at index C+i and multiply both copies by one
+ * half.  split_src[i] receives the expanded index that step i split.
+ * MODE_DUP: split_src is an input; the chosen channel is copied without scaling
+ * (the halving is applied to the activations instead).
+ *
+ * chan_src[j]  = original channel that expanded channel j descends from.
+ * chan_depth[j] = number of halvings that expanded channel j has gone through.
+ * max_out      = largest magnitude in the expanded tensor (may be NULL).
+ */
+int ref_split_weights(const float *T, int64_t rows, int C, int g, int64_t ld, int s, int mode,
+                      int32_t *split_src, int32_t *chan_src, int32_t *chan_depth, float *T_out,
+                      int64_t ldo, float *max_out) {
+    if (!T || !T_out || !chan_src || !chan_depth || (s > 0 && !split_src)) return REF_E_ARG;
+    if (rows <= 0 || C <= 0 || g <= 0 || s < 0) return REF_E_ARG;
+    if (ld < (int64_t)C * g || ldo < (int64_t)(C + s) * g) return REF_E_ARG;
+
+    for (int64_t n = 0; n < rows; ++n)
+        for (int64_t k = 0; k < (int64_t)C * g; ++k) T_out[n * ldo + k] = T[n * ld + k];
+    for (int j = 0; j < C; ++j) {
+        chan_src[j] = j;
+        chan_depth[j] = 0;
+    }
+
+    for (int i = 0; i < s; ++i) {
+        int cur = C + i; /* channels present before this step */
+        int pick;
+        if (mode == REF_MODE_HALVE) {
+            float best = -1.0f;
+            pick = 0;
+            for (int j = 0; j < cur; ++j)
+                for (int64_t n = 0; n < rows; ++n)
+                    for (int t = 0; t < g; ++t) {
+                        float a = fabsf(T_out[n * ldo + (int64_t)j * g + t]);
+                        if (a > best) {
+                            best = a;
+                            pick = j;
+                        }
+                    }
+            split_src[i] = pick;
+        } else {
+            pick = split_src[i];
+            if (pick < 0 || pick >= cur) return REF_E_ARG;
+        }
+        for (int64_t n = 0; n < rows; ++n)
+            for (int t = 0; t < g; ++t) {
+                float v = T_out[n * ldo + (int64_t)pick * g + t];
+                if (mode == REF_MODE_HALVE) v = v * 0.5f;
+                T_out[n * ldo + (int64_t)pick * g + t] = v;
+                T_out[n * ldo + (int64_t)cur * g + t] = v;
+            }
+        chan_depth[pick] += 1;
+        chan_src[cur] = chan_src[pick];
+        chan_depth[cur] = chan_depth[pick];
+    }
+
+    if (max_out) {
+        float m = 0.0f;
+        for (int64_t n = 0; n < rows; ++n)
+            for (int64_t k = 0; k < (int64_t)(C + s) * g; ++k) {
+                float a = fabsf(T_out[n * ldo + k]);
+                if (a > m) m = a;
+            }
+        *max_out = m;
+    }
+    return REF_OK;
+}
+
+/* One value onto the grid of Eq. 1 with range [-T, T]: fp32 decision (see header). */
+static int8_t code_of(float v, float inv_step, float qmax) {
+    float p = v * inv_step;
+    float r = nearbyintf(p); /* round-half-to-even under the default rounding mode */
+    if (r > qmax) r = qmax;
+    if (r < -qmax) r = -qmax;
+    return (int8_t)r;
+}
+
+static float inv_step_of(float T, float qmax) { return T > 0.0f ? qmax / T : 0.0f; }
+
+/*
+ * Eq. 1 with an optional clip threshold (Sec. 1; Sec. 5.2 for clip-after-OCS).
+ * x [rows, cols] (ld ldx) -> codes q [rows, ldq], columns cols..ldq-1 set to zero.
+ * threshold != NULL: T = *threshold.  Otherwise T = clip_ratio * max|x|.
+ * scale_out = {T, T / qmax}.
+ */
+int ref_quantize(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bits,
+                 const float *threshold, float clip_ratio, int8_t *q, int64_t ldq,
+                 float *scale_out) {
+    if (!x || !q || !scale_out) return REF_E_ARG;
+    if (rows <= 0 || cols <= 0 || ldx < cols || ldq < cols) return REF_E_ARG;
+    if (bits < 2 || bits > 8) return REF_E_ARG;
+    float qmax = (float)((1 << (bits - 1)) - 1);
+    float T;
+    if (threshold) {
+        T = *threshold;
+    } else {
+        float m = 0.0f;
+        for (int64_t i = 0; i < rows; ++i)
+            for (int64_t k = 0; k < cols; ++k) {
+                float a = fabsf(x[i * ldx + k]);
+                if (a > m) m = a;
+            }
+        T = clip_ratio * m;
+    }
+    float inv = inv_step_of(T, qmax);
+    scale_out[0] = T;
+    scale_out[1] = T / qmax;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i) {
+        for (int64_t k = 0; k < cols; ++k) q[i * ldq + k] = code_of(x[i * ldx + k], inv, qmax);
+        for (int64_t k = cols; k < ldq; ++k) q[i * ldq + k] = 0;
+    }
+    return REF_OK;
+}
+
+/*
+ * The activation side of Eq. 3 / Eq. 4 followed by Eq. 1 (Sec. 3.5: a layer that copies
+ * and scales the chosen channels).  Expanded channel j of the output reads original
+ * channel chan_src[j]; with chan_depth != NULL it is multiplied by 2^-chan_depth[j]
+ * (Eq. 4), with chan_depth == NULL it is copied as is (Eq. 3: the weights carry the
+ * halving).  Xf (may be NULL) receives the expanded fp32 activations [M, (C+s)*g].
+ * Threshold: *threshold if given, else clip_ratio * max|expanded activations|.
+ */
+int ref_split_act(const float *X, int64_t M, int C, int g, int64_t ldx, const int32_t *chan_src,
+                  const int32_t *chan_depth, int s, int bits, const float *threshold,
+                  float clip_ratio, int8_t *Xq, int64_t ldq, float *scale_out, float *Xf,
+                  int64_t ldf) {
+    if (!X || !Xq || !scale_out || (s > 0 && !chan_src)) return REF_E_ARG;
+    if (M <= 0 || C <= 0 || g <= 0 || s < 0) return REF_E_ARG;
+    int64_t K = (int64_t)C * g, Ke = (int64_t)(C + s) * g;
+    if (ldx < K || ldq < Ke || (Xf && ldf < Ke)) return REF_E_ARG;
+    if (bits < 2 || bits > 8) return REF_E_ARG;
+    for (int j = 0; j < C + s; ++j) {
+        int src = chan_src ? chan_src[j] : j;
+        if (src < 0 || src >= C) return REF_E_ARG;
+        if (chan_depth && chan_depth[j] < 0) return REF_E_ARG;
+    }
+    float qmax = (float)((1 << (bits - 1)) - 1);
+
+    float *E = (float *)malloc((size_t)M * (size_t)Ke * sizeof(float));
+    if (!E) return REF_E_NOMEM;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i)
+        for (int j = 0; j < C + s; ++j) {
+            int src = chan_src ? chan_src[j] : j;
+            float f = chan_depth ? ldexpf(1.0f, -chan_depth[j]) : 1.0f;
+            for (int t = 0; t < g; ++t)
+                E[i * Ke + (int64_t)j * g + t] = X[i * ldx + (int64_t)src * g + t] * f;
+        }
+
+    float T;
+    if (threshold) {
+        T = *threshold;
+    } else {
+        float m = 0.0f;
+        for (int64_t e = 0; e < M * Ke; ++e) {
+            float a = fabsf(E[e]);
+            if (a > m) m = a;
+        }
+        T = clip_ratio * m;
+    }
+    float inv = inv_step_of(T, qmax);
+    scale_out[0] = T;
+    scale_out[1] = T / qmax;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t k = 0; k < Ke; ++k) {
+            Xq[i * ldq + k] = code_of(E[i * Ke + k], inv, qmax);
+            if (Xf) Xf[i * ldf + k] = E[i * Ke + k];
+        }
+        for (int64_t k = Ke; k < ldq; ++k) Xq[i * ldq + k] = 0;
+    }
+    free(E);
+    return REF_OK;
+}
+
+/*
+ * Eq. 2 on the codes of the expanded layer: acc[i,n] = sum_k Xq[i,k] * Wq[n,k],
+ * accumulated in 64 bits and required to fit in 32; then the trailing factors of
+ * Eq. 1 for both operands, in fp64: Y = acc * step_x * step_w.
+ * acc_out and Y may each be NULL.
+ */
+int ref_qgemm(const int8_t *Xq, int64_t ldx, const int8_t *Wq, int64_t ldw, int64_t M, int64_t N,
+              int64_t Kexp, float step_x, float step_w, int32_t *acc_out, int64_t ldacc, double *Y,
+              int64_t ldy) {
+    if (!Xq || !Wq) return REF_E_ARG;
+    if (M <= 0 || N <= 0 || Kexp <= 0 || ldx < Kexp || ldw < Kexp) return REF_E_ARG;
+    if ((acc_out && ldacc < N) || (Y && ldy < N)) return REF_E_ARG;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t a = 0;
+            for (int64_t k = 0; k < Kexp; ++k)
+                a += (int64_t)Xq[i * ldx + k] * (int64_t)Wq[n * ldw + k];
+            if (a > INT32_MAX || a < INT32_MIN) bad |= 1;
+            if (acc_out) acc_out[i * ldacc + n] = (int32_t)a;
+            if (Y) Y[i * ldy + n] = (double)a * ((double)step_x * (double)step_w);
+        }
+    return bad ? REF_E_OVERFLOW : REF_OK;
+}
+
+/*
+ * Eq. 2 itself on real-valued operands, in fp64: Y[i,n] = sum_k X[i,k] * W[n,k].
+ * Used to state the functional identity of Eq. 3 / Eq. 4 (split layer == unsplit layer).
+ */
+int ref_layer_f64(const float *X, int64_t ldx, const float *W, int64_t ldw, int64_t M, int64_t N,
+                  int64_t K, double *Y, int64_t ldy) {
+    if (!X || !W || !Y || M <= 0 || N <= 0 || K <= 0) return REF_E_ARG;
+    if (ldx < K || ldw < K || ldy < N) return REF_E_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t n = 0; n < N; ++n) {
+            double a = 0.0;
+            for (int64_t k = 0; k < K; ++k) a += (double)X[i * ldx + k] * (double)W[n * ldw + k];
+            Y[i * ldy + n] = a;
+        }
+    return REF_OK;
+}

@@ -1,0 +1,156 @@
+"""ctypes front end of oracle/ocs_ref.c (host numpy arrays in, host numpy arrays out).
+
+Test infrastructure only: the GPU library and its Python binding never import this module.
+Argument marshalling only; every arithmetic step is in the C file, which cites the
+sections and equations of the paper it follows.
+"""
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ocs_ref.c")
+_LIB = os.path.join(_HERE, "libocs_ref.so")
+
+MODE_HALVE = 0
+MODE_DUP = 1
+
+CFLAGS = ["-O2", "-std=c99", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-shared", "-fPIC"]
+
+
+def build(force=False):
+    """Compile the oracle with gcc (plain C, no contraction, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", *CFLAGS, _SRC, "-o", _LIB, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.ref_num_splits.restype = C.c_int
+        _lib.ref_num_splits.argtypes = [C.c_int, C.c_double]
+        _lib.ref_get_threads.restype = C.c_int
+    return _lib
+
+
+def _p(a, t):
+    return a.ctypes.data_as(C.POINTER(t)) if a is not None else None
+
+
+def set_threads(n):
+    lib().ref_set_threads(C.c_int(int(n)))
+
+
+def get_threads():
+    return int(lib().ref_get_threads())
+
+
+def num_splits(Cn, r):
+    return int(lib().ref_num_splits(int(Cn), float(r)))
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise RuntimeError(f"{what} failed with code {rc}")
+
+
+def split_weights(T, Cn, g, s, mode=MODE_HALVE, split_src=None):
+    """Literal one-split-at-a-time OCS on T [rows, C*g].
+
+    Returns dict(split_src, chan_src, chan_depth, T_out [rows,(C+s)*g], max)."""
+    T = np.ascontiguousarray(T, dtype=np.float32)
+    rows = T.shape[0]
+    assert T.shape[1] == Cn * g
+    if mode == MODE_DUP:
+        ss = np.ascontiguousarray(split_src, dtype=np.int32).copy()
+        assert ss.shape[0] == s
+    else:
+        ss = np.zeros(max(s, 1), dtype=np.int32)
+    cs = np.zeros(Cn + s, dtype=np.int32)
+    cd = np.zeros(Cn + s, dtype=np.int32)
+    out = np.zeros((rows, (Cn + s) * g), dtype=np.float32)
+    mx = np.zeros(1, dtype=np.float32)
+    rc = lib().ref_split_weights(
+        _p(T, C.c_float), C.c_int64(rows), C.c_int(Cn), C.c_int(g), C.c_int64(T.shape[1]),
+        C.c_int(s), C.c_int(mode), _p(ss, C.c_int32), _p(cs, C.c_int32), _p(cd, C.c_int32),
+        _p(out, C.c_float), C.c_int64(out.shape[1]), _p(mx, C.c_float))
+    _check(rc, "ref_split_weights")
+    return dict(split_src=ss[:s], chan_src=cs, chan_depth=cd, T_out=out, max=float(mx[0]))
+
+
+def quantize(x, bits, threshold=None, clip_ratio=1.0, ldq=None):
+    """Eq. 1 (+ clip).  Returns (codes [rows, ldq] int8, scale float32[2] = {T, step})."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    rows, cols = x.shape
+    ldq = cols if ldq is None else int(ldq)
+    q = np.full((rows, ldq), 99, dtype=np.int8)
+    sc = np.zeros(2, dtype=np.float32)
+    th = None if threshold is None else np.array([threshold], dtype=np.float32)
+    rc = lib().ref_quantize(
+        _p(x, C.c_float), C.c_int64(rows), C.c_int64(cols), C.c_int64(cols), C.c_int(bits),
+        _p(th, C.c_float), C.c_float(clip_ratio), _p(q, C.c_int8), C.c_int64(ldq),
+        _p(sc, C.c_float))
+    _check(rc, "ref_quantize")
+    return q, sc
+
+
+def split_act(X, Cn, g, chan_src, chan_depth, s, bits, threshold=None, clip_ratio=1.0,
+              ldq=None, want_f32=False):
+    """Activation side of Eq. 3 (chan_depth None) / Eq. 4, then Eq. 1.
+
+    Returns (codes [M, ldq] int8, scale float32[2], expanded fp32 activations or None)."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    M = X.shape[0]
+    assert X.shape[1] == Cn * g
+    Ke = (Cn + s) * g
+    ldq = Ke if ldq is None else int(ldq)
+    cs = None if chan_src is None else np.ascontiguousarray(chan_src, dtype=np.int32)
+    cd = None if chan_depth is None else np.ascontiguousarray(chan_depth, dtype=np.int32)
+    q = np.full((M, ldq), 99, dtype=np.int8)
+    sc = np.zeros(2, dtype=np.float32)
+    th = None if threshold is None else np.array([threshold], dtype=np.float32)
+    Xf = np.zeros((M, Ke), dtype=np.float32) if want_f32 else None
+    rc = lib().ref_split_act(
+        _p(X, C.c_float), C.c_int64(M), C.c_int(Cn), C.c_int(g), C.c_int64(X.shape[1]),
+        _p(cs, C.c_int32), _p(cd, C.c_int32), C.c_int(s), C.c_int(bits), _p(th, C.c_float),
+        C.c_float(clip_ratio), _p(q, C.c_int8), C.c_int64(ldq), _p(sc, C.c_float),
+        _p(Xf, C.c_float), C.c_int64(Ke))
+    _check(rc, "ref_split_act")
+    return q, sc, Xf
+
+
+def qgemm(Xq, Wq, Kexp, step_x, step_w, want_acc=True, want_y=True):
+    """Eq. 2 on codes.  Returns (acc int32 [M,N] or None, Y float64 [M,N] or None)."""
+    Xq = np.ascontiguousarray(Xq, dtype=np.int8)
+    Wq = np.ascontiguousarray(Wq, dtype=np.int8)
+    M, N = Xq.shape[0], Wq.shape[0]
+    acc = np.zeros((M, N), dtype=np.int32) if want_acc else None
+    Y = np.zeros((M, N), dtype=np.float64) if want_y else None
+    rc = lib().ref_qgemm(
+        _p(Xq, C.c_int8), C.c_int64(Xq.shape[1]), _p(Wq, C.c_int8), C.c_int64(Wq.shape[1]),
+        C.c_int64(M), C.c_int64(N), C.c_int64(Kexp), C.c_float(step_x), C.c_float(step_w),
+        _p(acc, C.c_int32), C.c_int64(N), _p(Y, C.c_double), C.c_int64(N))
+    _check(rc, "ref_qgemm")
+    return acc, Y
+
+
+def layer_f64(X, W):
+    """Eq. 2 on real operands in fp64: Y = X @ W.T."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    M, K = X.shape
+    N = W.shape[0]
+    assert W.shape[1] == K
+    Y = np.zeros((M, N), dtype=np.float64)
+    rc = lib().ref_layer_f64(
+        _p(X, C.c_float), C.c_int64(K), _p(W, C.c_float), C.c_int64(K), C.c_int64(M),
+        C.c_int64(N), C.c_int64(K), _p(Y, C.c_double), C.c_int64(N))
+    _check(rc, "ref_layer_f64")
+    return Y

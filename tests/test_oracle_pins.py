@@ -1,0 +1,375 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (CPU only).
+
+Each test names the passage it pins.  None of them re-types the oracle's own formula:
+they use numpy's fp64 matmul / integer matmul as the library routine, closed forms,
+brute force over every split sequence, invariants, and the values the paper prints.
+"""
+import heapq
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import ref
+from paper_1901_09504_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _read_table(name):
+    rows = []
+    with open(os.path.join(GOLDEN, name)) as f:
+        lines = [l.strip() for l in f if l.strip() and not l.startswith("#")]
+    hdr = lines[0].split()
+    for l in lines[1:]:
+        rows.append(dict(zip(hdr, l.split())))
+    return rows
+
+
+def _rand_layer(rng, M, C, g, N, outliers=True):
+    X = rng.standard_normal((M, C * g)).astype(np.float32)
+    W = (rng.standard_normal((N, C * g)) * 0.05).astype(np.float32)
+    if outliers:
+        mask = rng.random((N, C * g)) < 0.01
+        W = np.where(mask, W * 8, W).astype(np.float32)
+    return X, W
+
+
+def _expand_cols(chan_src, g):
+    return (np.asarray(chan_src)[:, None] * g + np.arange(g)[None, :]).reshape(-1)
+
+
+# ---- Sec. 3.4: split budget --------------------------------------------------------------
+
+def test_budget_values():
+    # ceil(r*C) evaluated as a real-number formula
+    expect = {256: (3, 6, 13, 26), 1024: (11, 21, 52, 103), 2048: (21, 41, 103, 205),
+              64: (1, 2, 4, 7), 128: (2, 3, 7, 13), 512: (6, 11, 26, 52), 3: (1, 1, 1, 1)}
+    for C, vals in expect.items():
+        for r, v in zip((0.01, 0.02, 0.05, 0.1), vals):
+            assert ref.num_splits(C, r) == v, (C, r)
+    assert ref.num_splits(3000, 0.05) == 150
+    assert ref.num_splits(100, 0.0) == 0
+
+
+def test_budget_single_split_for_narrow_layers():
+    # Sec. 5.1: with widths in the tens to hundreds, r = 0.01 is a single split
+    for C in range(1, 101):
+        assert ref.num_splits(C, 0.01) == 1
+    assert ref.num_splits(101, 0.01) == 2
+
+
+def test_budget_table4_weight_row():
+    # Table 4: relative weight size of ResNet-50 with OCS, first conv left out (Sec. 5)
+    convs = wl.resnet50_convs(1)[1:]
+    assert len(convs) == 52
+    for row in _read_table("table4_resnet50_rel_weight_size.txt"):
+        r = float(row["r"])
+        base = sum(ci * k * k * co for _, ci, co, k, _ in convs)
+        grown = sum((ci + ref.num_splits(ci, r)) * k * k * co for _, ci, co, k, _ in convs)
+        rel = grown / base
+        assert r <= rel - 1.0 < r + 0.005          # Sec. 5.4: r is a lower bound, and close
+        assert f"{rel:.2f}".rstrip("0") == row["rel_weight_size"].rstrip("0"), (r, rel)
+
+
+# ---- Eq. 3 / Eq. 4: the split layer is the same function ----------------------------------
+
+@pytest.mark.parametrize("g", [1, 4, 9])
+def test_weight_ocs_functional_identity(g):
+    rng = np.random.default_rng(100 + g)
+    M, C, N, s = 7, 12, 5, 6
+    X, W = _rand_layer(rng, M, C, g, N)
+    sp = ref.split_weights(W, C, g, s)
+    Xe = X[:, _expand_cols(sp["chan_src"], g)]           # Eq. 3: activations are duplicated
+    y_split = ref.layer_f64(Xe, sp["T_out"])
+    y_plain = X.astype(np.float64) @ W.astype(np.float64).T   # library routine, unsplit layer
+    np.testing.assert_allclose(y_split, y_plain, rtol=1e-12, atol=1e-14)
+
+
+def test_weight_ocs_identity_bit_exact_on_integers():
+    # integer-valued fp32 operands (weights multiples of 2^s): every product and partial sum
+    # is exact, so the split and unsplit layers must agree to the last bit
+    rng = np.random.default_rng(7)
+    M, C, g, N, s = 5, 9, 2, 4, 5
+    X = rng.integers(-8, 9, (M, C * g)).astype(np.float32)
+    W = (rng.integers(-50, 51, (N, C * g)) * 2 ** s).astype(np.float32)
+    sp = ref.split_weights(W, C, g, s)
+    Xe = X[:, _expand_cols(sp["chan_src"], g)]
+    y_split = ref.layer_f64(Xe, sp["T_out"])
+    y_plain = X.astype(np.int64) @ W.astype(np.int64).T
+    assert np.array_equal(y_split, y_plain.astype(np.float64))
+
+
+def test_activation_ocs_functional_identity():
+    rng = np.random.default_rng(11)
+    M, C, g, N, s = 6, 10, 3, 4, 5
+    X, W = _rand_layer(rng, M, C, g, N)
+    X[2, 7] = 40.0
+    sel = ref.split_weights(X, C, g, s)                  # channel choice made on activations
+    dup = ref.split_weights(W, C, g, s, mode=ref.MODE_DUP, split_src=sel["split_src"])
+    assert np.array_equal(dup["chan_src"], sel["chan_src"])
+    assert np.array_equal(dup["chan_depth"], sel["chan_depth"])
+    # Eq. 4: weights are copied un-halved
+    assert np.array_equal(dup["T_out"], W[:, _expand_cols(dup["chan_src"], g)])
+    _, _, Xf = ref.split_act(X, C, g, sel["chan_src"], sel["chan_depth"], s, 8, want_f32=True)
+    # expansion through (chan_src, chan_depth) == one-at-a-time halving of the tensor itself
+    assert np.array_equal(Xf, sel["T_out"])
+    y_split = ref.layer_f64(Xf, dup["T_out"])
+    y_plain = X.astype(np.float64) @ W.astype(np.float64).T
+    np.testing.assert_allclose(y_split, y_plain, rtol=1e-12, atol=1e-14)
+
+
+def test_copies_sum_to_one():
+    # Eq. 3 / Eq. 4 applied repeatedly: the copies of one channel carry weights 2^-depth
+    # that add up to exactly one
+    rng = np.random.default_rng(5)
+    C, g, N, s = 6, 1, 8, 9
+    _, W = _rand_layer(rng, 2, C, g, N)
+    W[:, 2] *= 50                                         # forces repeated splits of channel 2
+    sp = ref.split_weights(W, C, g, s)
+    assert sp["chan_depth"].max() >= 2
+    tot = np.zeros(C)
+    for src, d in zip(sp["chan_src"], sp["chan_depth"]):
+        tot[src] += 2.0 ** (-int(d))
+    assert np.array_equal(tot, np.ones(C))
+    assert np.array_equal(sp["chan_src"][:C], np.arange(C))
+
+
+# ---- Sec. 3.2 / 3.4: every split halves the largest channel -------------------------------
+
+def test_each_split_halves_the_max():
+    rng = np.random.default_rng(3)
+    C, g, N, S = 8, 4, 6, 7
+    _, W = _rand_layer(rng, 2, C, g, N)
+    prev = W
+    for s in range(1, S + 1):
+        sp = ref.split_weights(W, C, g, s)
+        cur = sp["T_out"]
+        j = int(sp["split_src"][s - 1])
+        before = np.abs(prev).max()
+        assert np.abs(prev[:, j * g:(j + 1) * g]).max() == before
+        assert np.abs(cur[:, j * g:(j + 1) * g]).max() == 0.5 * before
+        assert np.abs(cur[:, (C + s - 1) * g:(C + s) * g]).max() == 0.5 * before
+        assert np.array_equal(cur[:, (C + s - 1) * g:], cur[:, j * g:(j + 1) * g])
+        # untouched channels are bit-identical to the previous state
+        keep = [c for c in range(C + s - 1) if c != j]
+        for c in keep:
+            assert np.array_equal(cur[:, c * g:(c + 1) * g], prev[:, c * g:(c + 1) * g])
+        assert sp["max"] == np.abs(cur).max()
+        prev = cur
+
+
+# ---- Sec. 3.4: greedy choice == brute force ------------------------------------------------
+
+def _simulate(maxima, seq):
+    m = list(maxima)
+    for j in seq:
+        m[j] = m[j] / 2
+        m.append(m[j])
+    return m
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_greedy_matches_brute_force(seed):
+    rng = np.random.default_rng(200 + seed)
+    C = int(rng.integers(2, 7))
+    s = int(rng.integers(1, 5))
+    g = int(rng.integers(1, 4))
+    N = 3
+    if seed % 2:
+        # power-of-two structured values so that ties occur between different channels
+        W = (2.0 ** rng.integers(-3, 3, (N, C * g)) * rng.choice([-1, 1], (N, C * g))).astype(np.float32)
+    else:
+        W = rng.standard_normal((N, C * g)).astype(np.float32)
+    sp = ref.split_weights(W, C, g, s)
+    # (i) every step took the channel that a scan over all elements finds (lowest index on ties)
+    state = W.copy()
+    for i in range(s):
+        absmax_per_chan = np.abs(state).reshape(N, C + i, g).max(axis=(0, 2))
+        assert int(sp["split_src"][i]) == int(np.argmax(absmax_per_chan))   # argmax: first max
+        state = ref.split_weights(W, C, g, i + 1)["T_out"]
+    # (ii) no sequence of s splits ends with a smaller layer maximum
+    maxima = np.abs(W).reshape(N, C, g).max(axis=(0, 2)).astype(np.float64)
+    greedy_final = max(_simulate(maxima, sp["split_src"]))
+    assert greedy_final == np.abs(sp["T_out"]).max()
+    best = min(max(_simulate(maxima, seq))
+               for seq in itertools.product(*[range(C + i) for i in range(s)]))
+    assert greedy_final == best
+    # (iii) closed form: s rounds of pop-max, halve, push twice
+    heap = [-v for v in maxima]
+    heapq.heapify(heap)
+    for _ in range(s):
+        v = -heapq.heappop(heap) / 2
+        heapq.heappush(heap, -v)
+        heapq.heappush(heap, -v)
+    final = np.abs(sp["T_out"]).reshape(N, C + s, g).max(axis=(0, 2))
+    assert sorted(final.tolist()) == sorted(-v for v in heap)
+
+
+def test_greedy_tie_break_and_resplit():
+    # two equal maxima: the lower index goes first; the halves of a split channel are equal,
+    # and the original slot is split again before its copy
+    W = np.array([[8.0, 1.0, -8.0, 0.5]], dtype=np.float32)
+    sp = ref.split_weights(W, 4, 1, 4)
+    assert sp["split_src"].tolist() == [0, 2, 0, 2]
+    assert sp["T_out"].tolist() == [[2.0, 1.0, -2.0, 0.5, 4.0, -4.0, 2.0, -2.0]]
+    assert sp["chan_src"].tolist() == [0, 1, 2, 3, 0, 2, 0, 2]
+    assert sp["chan_depth"].tolist() == [2, 0, 2, 0, 1, 1, 2, 2]
+
+
+# ---- Eq. 1: the grid ---------------------------------------------------------------------
+
+@pytest.mark.parametrize("bits", [2, 3, 4, 5, 6, 7, 8])
+def test_grid_definition(bits):
+    rng = np.random.default_rng(bits)
+    x = rng.standard_normal((37, 53)).astype(np.float32)
+    x[3, 4] = 0.0
+    q, sc = ref.quantize(x, bits)
+    qmax = 2 ** (bits - 1) - 1
+    T, step = float(sc[0]), float(sc[1])
+    assert T == np.abs(x).max()                           # the grid spans the whole range
+    assert abs(step - T / qmax) <= 1e-7 * step
+    assert q.min() >= -qmax and q.max() <= qmax           # 2^k - 1 points, -2^(k-1) unused
+    assert len(np.unique(q)) <= 2 ** bits - 1
+    i = np.unravel_index(np.argmax(np.abs(x)), x.shape)
+    assert abs(int(q[i])) == qmax and np.sign(q[i]) == np.sign(x[i])
+    assert q[3, 4] == 0
+    # error of at most half an increment (the fp32 evaluation may add an ulp or so)
+    err = np.abs(x.astype(np.float64) - q.astype(np.float64) * (T / qmax))
+    assert err.max() <= 0.5 * (T / qmax) * (1 + 1e-5)
+    # nearest grid point, decided in exact arithmetic, except within rounding of a tie
+    p = x.astype(np.float64) * qmax / T
+    far = np.abs(p - np.floor(p) - 0.5) > 1e-4
+    assert np.array_equal(q[far], np.rint(p[far]).astype(np.int8))
+    # symmetric and monotone
+    qn, _ = ref.quantize(-x, bits)
+    assert np.array_equal(qn, -q)
+    order = np.argsort(x.reshape(-1), kind="stable")
+    assert np.all(np.diff(q.reshape(-1)[order].astype(np.int32)) >= 0)
+
+
+def test_grid_ties_round_to_even():
+    # T = qmax makes the increment exactly 1, so x + 0.5 are exact ties
+    bits = 5
+    qmax = 15
+    x = np.array([[0.5, 1.5, 2.5, 3.5, -0.5, -1.5, -2.5, 14.5, -14.5, 15.0, 0.49999997, 1.5000001]],
+                 dtype=np.float32)
+    q, sc = ref.quantize(x, bits, threshold=float(qmax))
+    assert sc.tolist() == [15.0, 1.0]
+    assert q.tolist() == [[0, 2, 2, 4, 0, -2, -2, 14, -14, 15, 0, 2]]
+
+
+def test_clipping_saturates():
+    # Sec. 1: clipping == thresholding the outliers, then the linear grid
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((20, 30)).astype(np.float32)
+    x[0, 0] = 9.0
+    x[1, 1] = -9.0
+    bits, qmax = 4, 7
+    q1, s1 = ref.quantize(x, bits, clip_ratio=1.0)
+    q0, s0 = ref.quantize(x, bits)
+    assert np.array_equal(q1, q0) and np.array_equal(s1, s0)
+    qc, sc = ref.quantize(x, bits, clip_ratio=0.25)
+    T = float(sc[0])
+    assert T == np.float32(0.25) * np.float32(9.0)
+    assert np.all(qc[np.abs(x) >= T] == (np.sign(x[np.abs(x) >= T]) * qmax))
+    assert qc[0, 0] == qmax and qc[1, 1] == -qmax
+    # same as saturating the values first and then quantizing without clipping
+    xs = np.clip(x, -T, T)
+    qs, ss = ref.quantize(xs, bits)
+    assert np.array_equal(qs, qc) and ss[0] == sc[0]
+    # a caller-given threshold behaves the same way
+    qt, st = ref.quantize(x, bits, threshold=T)
+    assert np.array_equal(qt, qc) and np.array_equal(st, sc)
+
+
+def test_zero_tensor_and_padding():
+    x = np.zeros((3, 5), dtype=np.float32)
+    q, sc = ref.quantize(x, 8, ldq=16)
+    assert sc.tolist() == [0.0, 0.0]
+    assert not q.any()
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((4, 5)).astype(np.float32)
+    q, _ = ref.quantize(x, 8, ldq=16)
+    assert not q[:, 5:].any() and q[:, :5].any()
+
+
+# ---- Sec. 3.3: the naive split's worked example --------------------------------------------
+
+def test_naive_split_w3_example():
+    row = _read_table("sec3_3_naive_split_w3.txt")[0]
+    w, half, Qw, ssum = float(row["w"]), float(row["half"]), int(row["Qw"]), int(row["sum_of_rounded_halves"])
+    W = np.array([[w, 0.25]], dtype=np.float32)
+    sp = ref.split_weights(W, 2, 1, 1)
+    assert sp["split_src"].tolist() == [0]
+    assert sp["T_out"].tolist() == [[half, 0.25, half]]
+    # grid of increment 1: T = qmax
+    q_before, _ = ref.quantize(W, 4, threshold=7.0)
+    q_after, _ = ref.quantize(sp["T_out"], 4, threshold=7.0)
+    assert int(q_before[0, 0]) == Qw
+    assert int(q_after[0, 0]) + int(q_after[0, 2]) == ssum
+    assert ssum != Qw          # the quantized split layer is legitimately not the unsplit one
+
+
+# ---- Eq. 2 on codes ---------------------------------------------------------------------
+
+def test_no_split_is_plain_symmetric_int_gemm():
+    rng = np.random.default_rng(21)
+    M, K, N = 9, 37, 6                                   # all different: catches a transposition
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    W = rng.standard_normal((N, K)).astype(np.float32) * 0.1
+    Xq, sx = ref.quantize(X, 8, ldq=64)
+    Wq, sw = ref.quantize(W, 6, ldq=64)
+    acc, Y = ref.qgemm(Xq, Wq, K, sx[1], sw[1])
+    acc_lib = Xq[:, :K].astype(np.int64) @ Wq[:, :K].astype(np.int64).T
+    assert np.array_equal(acc, acc_lib)
+    y_lib = acc_lib.astype(np.float64) * float(sx[1]) * float(sw[1])
+    np.testing.assert_allclose(Y, y_lib, rtol=1e-15)
+    # and the dequantized result approximates the real layer to within the grid error
+    y_real = X.astype(np.float64) @ W.astype(np.float64).T
+    bound = K * (0.5 * sx[1] * np.abs(W).max() + 0.5 * sw[1] * np.abs(X).max() + 0.25 * sx[1] * sw[1])
+    assert np.abs(Y - y_real).max() <= bound
+
+
+def test_qgemm_overflow_is_reported():
+    K = 140000
+    Xq = np.full((1, K), 127, dtype=np.int8)
+    Wq = np.full((1, K), 127, dtype=np.int8)
+    with pytest.raises(RuntimeError):
+        ref.qgemm(Xq, Wq, K, 1.0, 1.0)
+
+
+def test_weight_ocs_integer_domain():
+    # Eq. 3 on codes: the duplicated activation columns are byte copies of their sources
+    rng = np.random.default_rng(33)
+    M, C, g, N, s = 11, 16, 4, 5, 5
+    X, W = _rand_layer(rng, M, C, g, N)
+    sp = ref.split_weights(W, C, g, s)
+    Xq, sx, _ = ref.split_act(X, C, g, sp["chan_src"], None, s, 8, ldq=128)
+    Xq0, sx0 = ref.quantize(X, 8)
+    assert np.array_equal(sx, sx0)
+    assert np.array_equal(Xq[:, :C * g], Xq0)
+    assert np.array_equal(Xq[:, :(C + s) * g], Xq0[:, _expand_cols(sp["chan_src"], g)])
+    assert not Xq[:, (C + s) * g:].any()
+    # whole chain against library routines on the oracle's own codes
+    Wq, sw = ref.quantize(sp["T_out"], 8, ldq=128)
+    acc, Y = ref.qgemm(Xq, Wq, (C + s) * g, sx[1], sw[1])
+    assert np.array_equal(acc, Xq.astype(np.int64) @ Wq.astype(np.int64).T)
+    y_real = X.astype(np.float64) @ W.astype(np.float64).T
+    assert np.abs(Y - y_real).max() < 0.05 * np.abs(y_real).max()
+
+
+def test_activation_ocs_threshold_follows_split_tensor():
+    # Sec. 5.2 order (split first, then the grid): the dynamic threshold is taken on the
+    # halved activations, so it is smaller than the unsplit maximum
+    rng = np.random.default_rng(44)
+    M, C, g, s = 8, 10, 2, 3
+    X = rng.standard_normal((M, C * g)).astype(np.float32)
+    X[3, 5] = 30.0
+    sel = ref.split_weights(X, C, g, s)
+    Xq, sx, Xf = ref.split_act(X, C, g, sel["chan_src"], sel["chan_depth"], s, 6, want_f32=True)
+    assert sx[0] == np.abs(Xf).max() == sel["max"]
+    assert sx[0] < np.abs(X).max()
+    q2, s2 = ref.quantize(Xf, 6)
+    assert np.array_equal(q2, Xq) and np.array_equal(s2, sx)
