@@ -1,0 +1,181 @@
+/*
+ * ocs.h - C ABI of the OCS-expanded quantized layer for AMD MI355X (gfx950).
+ *
+ * Outlier channel splitting (Zhao et al., "Improving Neural Network Quantization without
+ * Retraining using Outlier Channel Splitting"): input channels that hold outliers are
+ * duplicated and halved (Sec. 3.2, Eq. 3 and Eq. 4), chosen greedily one at a time
+ * (Sec. 3.4); weights and activations are put on a symmetric k-bit linear grid (Sec. 3.1,
+ * Eq. 1), optionally narrowed by a clip threshold (Sec. 1, Sec. 5.2); the expanded layer
+ * (Eq. 2 over the expanded channel set) then runs as an integer GEMM with 32-bit
+ * accumulation followed by the trailing scale factors of Eq. 1.
+ *
+ * Conventions (all entry points unless stated otherwise)
+ *  - Return value: OCS_OK (0) or a negative OCS_E_* code; nothing is thrown across the ABI.
+ *    ocs_strerror() turns a code into text.  Arguments are validated on the host before any
+ *    device work, so every argument error is reported without touching the GPU.
+ *  - Every tensor / index / scale pointer is a DEVICE pointer owned by the caller.  The
+ *    library allocates nothing; scratch space comes from the caller's `workspace`
+ *    (device memory, 256-byte aligned), at least ocs_workspace_bytes() bytes.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *    enqueue work on that stream and never synchronise; results (including scalar results
+ *    such as thresholds) are written to device memory so that the chain
+ *    split -> quantize -> gemm needs no host round trip.
+ *  - Layout: a tensor T of a layer is [rows, C*g] row-major with a leading dimension in
+ *    elements; K-columns are channel-major: input channel c owns columns c*g .. c*g+g-1
+ *    (g = 1 for a fully connected layer or a 1x1 convolution, g = kh*kw for a convolution
+ *    lowered by im2col; Sec. 3.2: a split duplicates a whole 2-D activation channel and
+ *    every 2-D filter attached to it).  Activations X are [M, C*g], weights W are [N, C*g]
+ *    (both operands K-contiguous), outputs Y are [M, N].
+ *  - Code tensors (int8) have a leading dimension that is a multiple of OCS_KALIGN and a
+ *    16-byte aligned base; the producer writes zeros into every pad column
+ *    (columns (C+s)*g .. ld-1) and ocs_qgemm relies on those zeros.
+ *  - fp32 inputs may have any leading dimension >= the row length; 16-byte aligned bases
+ *    with a leading dimension that is a multiple of 4 take the vectorised path.
+ *  - NaN / Inf inputs give unspecified codes (no fault).  Index arrays read from device
+ *    memory are clamped into range before use, so bad indices cannot cause a fault.
+ *  - Two calls that share a workspace or an output must be ordered on one stream.
+ */
+#ifndef OCS_H
+#define OCS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define OCS_KALIGN 64 /* leading dimension of int8 code tensors is a multiple of this */
+
+#define OCS_OK 0
+#define OCS_E_NULL (-1)      /* a required pointer is NULL                                  */
+#define OCS_E_SHAPE (-2)     /* non-positive dimension, leading dimension too small, too big */
+#define OCS_E_ALIGN (-3)     /* code tensor base / leading dimension / workspace misaligned  */
+#define OCS_E_BITS (-4)      /* bit width outside 2..8                                       */
+#define OCS_E_SPLITS (-5)    /* num_splits negative or beyond the supported maximum          */
+#define OCS_E_OVERFLOW (-6)  /* Kexp * qmax_x * qmax_w does not fit a 32-bit accumulator     */
+#define OCS_E_WORKSPACE (-7) /* workspace NULL or smaller than ocs_workspace_bytes()         */
+#define OCS_E_HIP (-8)       /* a HIP call failed; ocs_last_hip_error() has the text         */
+#define OCS_E_MODE (-9)      /* unknown mode                                                 */
+
+#define OCS_MODE_HALVE 0 /* choose channels on this tensor and halve both copies (Eq. 3)     */
+#define OCS_MODE_DUP 1   /* channel choice given; copy channels un-halved (Eq. 4, weights)   */
+
+#define OCS_MAX_EXPANDED_CHANNELS 8000  /* C + num_splits may not exceed this                */
+
+/* Text for an OCS_E_* code (static storage, never NULL). */
+const char *ocs_strerror(int code);
+
+/* Text of the last HIP error seen by the calling thread ("" if none). */
+const char *ocs_last_hip_error(void);
+
+/*
+ * Split budget of Sec. 3.4: ceil(r * C), evaluated in double precision.
+ * r <= 0 or C <= 0 gives 0.  Host-only, no device work.
+ */
+int ocs_num_splits(int C, double r);
+
+/* Leading dimension of the code tensor of an expanded layer: (C+s)*g rounded up to OCS_KALIGN. */
+int64_t ocs_padded_cols(int64_t cols);
+
+/*
+ * Scratch bytes that any call below needs for a tensor of `rows` x `cols` fp32 elements
+ * (cols = C*g of the unexpanded tensor).  Host-only.  Returns 0 for non-positive sizes.
+ */
+size_t ocs_workspace_bytes(int64_t rows, int64_t cols);
+
+/*
+ * Channel selection of Sec. 3.4 on a tensor T [rows, C*g]: num_splits times, take the
+ * expanded channel that currently holds the largest magnitude (lowest expanded index on
+ * ties; the two halves of a split channel are equal, so ties always occur), halve it, and
+ * append its copy at expanded index C+i.
+ *   split_src  [num_splits]   out: expanded index split at step i
+ *   chan_src   [C+num_splits] out: original channel that expanded channel j descends from
+ *   chan_depth [C+num_splits] out: number of halvings applied to expanded channel j
+ *   max_out    device float   out: largest magnitude after all splits (may be NULL)
+ * T is only read.  Used on weights (weight OCS) or on a batch of activations
+ * (activation OCS with the channels chosen on that batch, Sec. 5.3).
+ */
+int ocs_select_channels(const float *T, int64_t rows, int C, int g, int64_t ld, int num_splits,
+                        int32_t *split_src, int32_t *chan_src, int32_t *chan_depth,
+                        float *max_out, void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * Weight side of OCS (Sec. 3.2 Eq. 3 / Eq. 4, Sec. 3.4), done off-line per Sec. 3.5.
+ *   mode OCS_MODE_HALVE: select channels on W as ocs_select_channels does, then
+ *        W'[n, j*g+t] = W[n, chan_src[j]*g+t] * 2^-chan_depth[j]        (Eq. 3)
+ *        split_src, chan_src, chan_depth are outputs.
+ *   mode OCS_MODE_DUP:   split_src [num_splits] is an INPUT (chosen on activations);
+ *        W'[n, j*g+t] = W[n, chan_src[j]*g+t]                            (Eq. 4)
+ *        chan_src, chan_depth are outputs.
+ * Optional outputs (each may be NULL):
+ *   W_out [N, (C+s)*g] fp32, leading dimension ldo: the expanded weights.
+ *   wmax_out device float: max|W'|.
+ *   Wq [N, ldq] int8 codes of W' on the `bits`-bit grid with threshold
+ *        clip_ratio * max|W'| (Eq. 1; clip after OCS as in Sec. 5.2), pad columns zero;
+ *        scale_w_out device float[2] = {threshold, threshold / qmax} (required with Wq).
+ * W is only read.
+ */
+int ocs_split_weights(const float *W, int64_t N, int C, int g, int64_t ldw, int num_splits,
+                      int mode, int32_t *split_src, int32_t *chan_src, int32_t *chan_depth,
+                      float *W_out, int64_t ldo, float *wmax_out, int bits, float clip_ratio,
+                      int8_t *Wq, int64_t ldq, float *scale_w_out, void *workspace,
+                      size_t ws_bytes, void *stream);
+
+/*
+ * Linear quantization of Sec. 3.1 Eq. 1 with optional clipping (Sec. 1).
+ *   x [rows, cols] fp32 -> q [rows, ldq] int8, q = clamp(rne(x * (qmax / T)), -qmax, qmax),
+ *   qmax = 2^(bits-1) - 1 (a grid of 2^bits - 1 points), columns cols .. ldq-1 zero.
+ *   threshold != NULL: T = *threshold (device float, T >= 0; a static or clipped grid).
+ *   threshold == NULL: T = clip_ratio * max|x| (clip_ratio = 1 spans the whole range).
+ *   T == 0 gives all-zero codes and a zero step.
+ *   scale_out device float[2] = {T, T / qmax}.
+ * Arithmetic contract: qmax / T is one correctly rounded fp32 division, x * (qmax / T) one
+ * fp32 multiply, rne = round half to even.
+ */
+int ocs_quantize(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bits,
+                 const float *threshold, float clip_ratio, int8_t *q, int64_t ldq,
+                 float *scale_out, void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * Activation side of OCS, per batch (Sec. 3.5: a layer that copies and scales the chosen
+ * channels), fused with Eq. 1:
+ *   Xq[i, j*g+t] = Q( X[i, chan_src[j]*g+t] * f_j ),  j < C+num_splits,  pad columns zero,
+ *   f_j = 1 when chan_depth == NULL (Eq. 3: the weights carry the halving) and
+ *   f_j = 2^-chan_depth[j] otherwise (Eq. 4).
+ * chan_src may be NULL only when num_splits == 0.
+ * Threshold as in ocs_quantize; with threshold == NULL it is clip_ratio times the largest
+ * magnitude of the EXPANDED activations (i.e. after halving).
+ *   scale_out device float[2] = {T, T / qmax}.
+ */
+int ocs_split_act(const float *X, int64_t M, int C, int g, int64_t ldx, const int32_t *chan_src,
+                  const int32_t *chan_depth, int num_splits, int bits, const float *threshold,
+                  float clip_ratio, int8_t *Xq, int64_t ldq, float *scale_out, void *workspace,
+                  size_t ws_bytes, void *stream);
+
+/*
+ * The expanded layer of Eq. 2 on integer codes, then the trailing factors of Eq. 1:
+ *   acc[i,n] = sum_{k < Kexp} Xq[i,k] * Wq[n,k]   (int8 x int8 -> int32, exact)
+ *   Y[i,n]   = float(acc[i,n]) * (scale_x[1] * scale_w[1])
+ * Xq [M, ldx], Wq [N, ldw] int8 with zero pad columns up to the next multiple of
+ * OCS_KALIGN; scale_x, scale_w are the device float[2] written by the producers;
+ * bits_x / bits_w are the grids' bit widths, used only for the overflow check
+ * Kexp * qmax_x * qmax_w < 2^31.  acc_out [M, ldacc] int32 is optional (NULL = not
+ * stored); Y [M, ldy] fp32 is required.  workspace may be NULL (none is needed).
+ */
+int ocs_qgemm(const int8_t *Xq, int64_t ldx, const int8_t *Wq, int64_t ldw, int64_t M, int64_t N,
+              int64_t Kexp, int bits_x, int bits_w, const float *scale_x, const float *scale_w,
+              int32_t *acc_out, int64_t ldacc, float *Y, int64_t ldy, void *workspace,
+              size_t ws_bytes, void *stream);
+
+/*
+ * Launch-shape overrides for benchmarking (no passage of the paper; results never depend
+ * on them).  key: "act_rows_per_block", "gemm_tile" ...; value < 0 restores the default.
+ * Returns OCS_OK or OCS_E_MODE for an unknown key.  Not thread-safe.
+ */
+int ocs_tune(const char *key, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OCS_H */

@@ -30,6 +30,7 @@
  * Build: gcc -O2 -std=c99 -ffp-contract=off -fno-fast-math -fopenmp -shared -fPIC
  * OpenMP only partitions independent rows over threads; it changes no arithmetic.
  */
+#include <float.h>
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -142,7 +143,13 @@ static int8_t code_of(float v, float inv_step, float qmax) {
     return (int8_t)r;
 }
 
-static float inv_step_of(float T, float qmax) { return T > 0.0f ? qmax / T : 0.0f; }
+/* qmax / T, kept finite: for T below about 1e-36 the fp32 quotient overflows, and an
+ * infinite factor would send the value 0 to NaN although Eq. 1 maps 0 to the grid point 0. */
+static float inv_step_of(float T, float qmax) {
+    if (!(T > 0.0f)) return 0.0f;
+    float inv = qmax / T;
+    return inv > FLT_MAX ? FLT_MAX : inv;
+}
 
 /*
  * Eq. 1 with an optional clip threshold (Sec. 1; Sec. 5.2 for clip-after-OCS).

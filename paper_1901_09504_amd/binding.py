@@ -1,0 +1,155 @@
+"""Thin Python binding of libocs.so (ctypes): argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI declared in include/ocs.h;
+PyTorch supplies device memory and the stream, nothing else.  There is no fallback: if the
+library is missing or a call fails, an exception is raised.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libocs.so")
+
+KALIGN = 64
+MODE_HALVE = 0
+MODE_DUP = 1
+MAX_EXPANDED_CHANNELS = 8000
+
+
+class OcsError(RuntimeError):
+    def __init__(self, code, what):
+        self.code = code
+        msg = lib().ocs_strerror(code).decode()
+        hip = lib().ocs_last_hip_error().decode()
+        super().__init__(f"{what}: {msg} (code {code})" + (f" [{hip}]" if code == -8 and hip else ""))
+
+
+_lib = None
+_vp, _i64, _i32, _f32, _sz = C.c_void_p, C.c_int64, C.c_int, C.c_float, C.c_size_t
+
+
+def lib():
+    """Load libocs.so (built in-tree by paper_1901_09504_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_1901_09504_amd.build` "
+            "(there is no CPU fallback)")
+    L = C.CDLL(LIB_PATH)
+    L.ocs_strerror.restype = C.c_char_p
+    L.ocs_strerror.argtypes = [_i32]
+    L.ocs_last_hip_error.restype = C.c_char_p
+    L.ocs_last_hip_error.argtypes = []
+    L.ocs_num_splits.restype = _i32
+    L.ocs_num_splits.argtypes = [_i32, C.c_double]
+    L.ocs_padded_cols.restype = _i64
+    L.ocs_padded_cols.argtypes = [_i64]
+    L.ocs_workspace_bytes.restype = _sz
+    L.ocs_workspace_bytes.argtypes = [_i64, _i64]
+    L.ocs_select_channels.restype = _i32
+    L.ocs_select_channels.argtypes = [_vp, _i64, _i32, _i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    L.ocs_split_weights.restype = _i32
+    L.ocs_split_weights.argtypes = [_vp, _i64, _i32, _i32, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _i64,
+                                    _vp, _i32, _f32, _vp, _i64, _vp, _vp, _sz, _vp]
+    L.ocs_quantize.restype = _i32
+    L.ocs_quantize.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _f32, _vp, _i64, _vp, _vp, _sz, _vp]
+    L.ocs_split_act.restype = _i32
+    L.ocs_split_act.argtypes = [_vp, _i64, _i32, _i32, _i64, _vp, _vp, _i32, _i32, _vp, _f32, _vp, _i64,
+                                _vp, _vp, _sz, _vp]
+    L.ocs_qgemm.restype = _i32
+    L.ocs_qgemm.argtypes = [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _vp, _vp, _vp, _i64, _vp,
+                            _i64, _vp, _sz, _vp]
+    L.ocs_tune.restype = _i32
+    L.ocs_tune.argtypes = [C.c_char_p, _i32]
+    _lib = L
+    return L
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    return C.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise OcsError(rc, what)
+
+
+# ---- host-only helpers ----------------------------------------------------------------------
+
+def ocs_num_splits(Cn, r):
+    return int(lib().ocs_num_splits(int(Cn), float(r)))
+
+
+def ocs_padded_cols(cols):
+    return int(lib().ocs_padded_cols(int(cols)))
+
+
+def ocs_workspace_bytes(rows, cols):
+    return int(lib().ocs_workspace_bytes(int(rows), int(cols)))
+
+
+def ocs_tune(key, value):
+    _check(lib().ocs_tune(key.encode(), int(value)), "ocs_tune")
+
+
+def alloc_workspace(rows, cols, device="cuda"):
+    """A device buffer large enough for any call on a [rows, cols] fp32 tensor."""
+    return torch.empty(max(256, ocs_workspace_bytes(rows, cols)), dtype=torch.uint8, device=device)
+
+
+# ---- device calls (same names and argument order as the C ABI) ------------------------------
+
+def ocs_select_channels(T, rows, Cn, g, ld, num_splits, split_src, chan_src, chan_depth, max_out,
+                        workspace, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib().ocs_select_channels(_ptr(T), rows, Cn, g, ld, num_splits, _ptr(split_src),
+                                     _ptr(chan_src), _ptr(chan_depth), _ptr(max_out), w, wb,
+                                     _stream(stream)), "ocs_select_channels")
+
+
+def ocs_split_weights(W, N, Cn, g, ldw, num_splits, mode, split_src, chan_src, chan_depth, W_out, ldo,
+                      wmax_out, bits, clip_ratio, Wq, ldq, scale_w_out, workspace, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib().ocs_split_weights(_ptr(W), N, Cn, g, ldw, num_splits, mode, _ptr(split_src),
+                                   _ptr(chan_src), _ptr(chan_depth), _ptr(W_out), ldo,
+                                   _ptr(wmax_out), bits, clip_ratio, _ptr(Wq), ldq,
+                                   _ptr(scale_w_out), w, wb, _stream(stream)), "ocs_split_weights")
+
+
+def ocs_quantize(x, rows, cols, ldx, bits, threshold, clip_ratio, q, ldq, scale_out, workspace,
+                 stream=None):
+    w, wb = _ws(workspace)
+    _check(lib().ocs_quantize(_ptr(x), rows, cols, ldx, bits, _ptr(threshold), clip_ratio, _ptr(q),
+                              ldq, _ptr(scale_out), w, wb, _stream(stream)), "ocs_quantize")
+
+
+def ocs_split_act(X, M, Cn, g, ldx, chan_src, chan_depth, num_splits, bits, threshold, clip_ratio, Xq,
+                  ldq, scale_out, workspace, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib().ocs_split_act(_ptr(X), M, Cn, g, ldx, _ptr(chan_src), _ptr(chan_depth), num_splits,
+                               bits, _ptr(threshold), clip_ratio, _ptr(Xq), ldq, _ptr(scale_out), w,
+                               wb, _stream(stream)), "ocs_split_act")
+
+
+def ocs_qgemm(Xq, ldx, Wq, ldw, M, N, Kexp, bits_x, bits_w, scale_x, scale_w, acc_out, ldacc, Y, ldy,
+              workspace=None, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib().ocs_qgemm(_ptr(Xq), ldx, _ptr(Wq), ldw, M, N, Kexp, bits_x, bits_w, _ptr(scale_x),
+                           _ptr(scale_w), _ptr(acc_out), ldacc, _ptr(Y), ldy, w, wb,
+                           _stream(stream)), "ocs_qgemm")

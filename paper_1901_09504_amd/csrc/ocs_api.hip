@@ -1,0 +1,264 @@
+// C ABI of libocs.so: argument validation (host only, before any device work), workspace
+// carving, and the launch sequences.  See include/ocs.h for the contract of each call.
+#include <string.h>
+
+#include <string>
+
+#include "../../include/ocs.h"
+#include "ocs_internal.h"
+
+namespace ocs {
+
+Tuning& tuning() {
+    static Tuning t;
+    return t;
+}
+
+static thread_local std::string g_hip_error;
+
+static int hip_fail(hipError_t e) {
+    g_hip_error = hipGetErrorString(e);
+    return OCS_E_HIP;
+}
+
+static bool bits_ok(int bits) { return bits >= 2 && bits <= 8; }
+static float qmax_of(int bits) { return (float)((1 << (bits - 1)) - 1); }
+static bool aligned(const void* p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a == 0; }
+
+static int check_codes(const void* q, int64_t ldq, int64_t cols) {
+    if (ldq < cols) return OCS_E_SHAPE;
+    if (ldq % OCS_KALIGN != 0 || !aligned(q, 16)) return OCS_E_ALIGN;
+    return OCS_OK;
+}
+
+static int check_workspace(const void* ws, size_t ws_bytes, int64_t rows, int64_t cols) {
+    if (ws == nullptr || ws_bytes < plan_workspace(rows, cols).total) return OCS_E_WORKSPACE;
+    if (!aligned(ws, 256)) return OCS_E_ALIGN;
+    return OCS_OK;
+}
+
+static int check_layer(int64_t rows, int C, int g, int64_t ld, int num_splits) {
+    if (rows <= 0 || C <= 0 || g <= 0) return OCS_E_SHAPE;
+    if ((int64_t)C * g > (int64_t)1 << 30 || rows > (int64_t)1 << 31) return OCS_E_SHAPE;
+    if (ld < (int64_t)C * g) return OCS_E_SHAPE;
+    if (num_splits < 0) return OCS_E_SPLITS;
+    if ((int64_t)C + num_splits > OCS_MAX_EXPANDED_CHANNELS) return OCS_E_SPLITS;
+    return OCS_OK;
+}
+
+}  // namespace ocs
+
+using namespace ocs;
+
+extern "C" {
+
+const char* ocs_strerror(int code) {
+    switch (code) {
+        case OCS_OK: return "ok";
+        case OCS_E_NULL: return "a required pointer is NULL";
+        case OCS_E_SHAPE: return "bad shape: non-positive or too large dimension, or leading dimension too small";
+        case OCS_E_ALIGN: return "misaligned code tensor, leading dimension or workspace";
+        case OCS_E_BITS: return "bit width outside 2..8";
+        case OCS_E_SPLITS: return "num_splits negative, or C + num_splits above OCS_MAX_EXPANDED_CHANNELS";
+        case OCS_E_OVERFLOW: return "Kexp * qmax_x * qmax_w does not fit a 32-bit accumulator";
+        case OCS_E_WORKSPACE: return "workspace NULL or smaller than ocs_workspace_bytes()";
+        case OCS_E_HIP: return "a HIP call failed (see ocs_last_hip_error)";
+        case OCS_E_MODE: return "unknown mode or key";
+        default: return "unknown error code";
+    }
+}
+
+const char* ocs_last_hip_error(void) { return g_hip_error.c_str(); }
+
+int ocs_num_splits(int C, double r) {
+    if (C <= 0 || !(r > 0.0)) return 0;
+    double v = r * (double)C;
+    int s = (int)v;
+    if ((double)s < v) ++s;
+    return s;
+}
+
+int64_t ocs_padded_cols(int64_t cols) { return cols <= 0 ? 0 : round_up(cols, OCS_KALIGN); }
+
+size_t ocs_workspace_bytes(int64_t rows, int64_t cols) {
+    if (rows <= 0 || cols <= 0) return 0;
+    return plan_workspace(rows, cols).total;
+}
+
+int ocs_select_channels(const float* T, int64_t rows, int C, int g, int64_t ld, int num_splits,
+                        int32_t* split_src, int32_t* chan_src, int32_t* chan_depth,
+                        float* max_out, void* workspace, size_t ws_bytes, void* stream) {
+    if (!T || !chan_src || !chan_depth || (num_splits > 0 && !split_src)) return OCS_E_NULL;
+    int rc = check_layer(rows, C, g, ld, num_splits);
+    if (rc) return rc;
+    const int64_t K = (int64_t)C * g;
+    rc = check_workspace(workspace, ws_bytes, rows, K);
+    if (rc) return rc;
+    Workspace w = plan_workspace(rows, K);
+    char* base = static_cast<char*>(workspace);
+    float* colmax = reinterpret_cast<float*>(base + w.colmax_off);
+    float* partial = reinterpret_cast<float*>(base + w.partial_off);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = launch_colmax(T, rows, K, ld, colmax, partial, st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = launch_select(colmax, C, g, num_splits, 0, nullptr, split_src, chan_src, chan_depth,
+                      max_out, 1.0f, 1.0f, nullptr, st);
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
+int ocs_split_weights(const float* W, int64_t N, int C, int g, int64_t ldw, int num_splits,
+                      int mode, int32_t* split_src, int32_t* chan_src, int32_t* chan_depth,
+                      float* W_out, int64_t ldo, float* wmax_out, int bits, float clip_ratio,
+                      int8_t* Wq, int64_t ldq, float* scale_w_out, void* workspace,
+                      size_t ws_bytes, void* stream) {
+    if (!W || !chan_src || !chan_depth || (num_splits > 0 && !split_src)) return OCS_E_NULL;
+    if (Wq && !scale_w_out) return OCS_E_NULL;
+    if (mode != OCS_MODE_HALVE && mode != OCS_MODE_DUP) return OCS_E_MODE;
+    int rc = check_layer(N, C, g, ldw, num_splits);
+    if (rc) return rc;
+    const int64_t K = (int64_t)C * g, Ke = (int64_t)(C + num_splits) * g;
+    if (W_out && ldo < Ke) return OCS_E_SHAPE;
+    if (Wq) {
+        rc = check_codes(Wq, ldq, Ke);
+        if (rc) return rc;
+        if (!bits_ok(bits)) return OCS_E_BITS;
+    }
+    rc = check_workspace(workspace, ws_bytes, N, K);
+    if (rc) return rc;
+
+    Workspace w = plan_workspace(N, K);
+    char* base = static_cast<char*>(workspace);
+    float* colmax = reinterpret_cast<float*>(base + w.colmax_off);
+    float* partial = reinterpret_cast<float*>(base + w.partial_off);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    // W1: channel maxima.  W2: selection (or replay of the given list).  The selector also
+    // emits max|W'| and, when codes are wanted, the threshold and step of the weight grid.
+    hipError_t e = launch_colmax(W, N, K, ldw, colmax, partial, st);
+    if (e != hipSuccess) return hip_fail(e);
+    const float qmax = Wq ? qmax_of(bits) : 1.0f;
+    e = launch_select(colmax, C, g, num_splits, mode, split_src, split_src, chan_src, chan_depth,
+                      wmax_out, clip_ratio, qmax, Wq ? scale_w_out : nullptr, st);
+    if (e != hipSuccess) return hip_fail(e);
+
+    // W3: materialise, as fp32 and / or straight to codes
+    const int halve = mode == OCS_MODE_HALVE;
+    if (W_out) {
+        e = launch_expand_f32(W, ldw, N, C, g, num_splits, chan_src, chan_depth, halve, W_out,
+                              ldo, st);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    if (Wq) {
+        e = launch_expand_quantize(W, ldw, N, C, g, num_splits, chan_src,
+                                   halve ? chan_depth : nullptr, scale_w_out, qmax, Wq, ldq,
+                                   nullptr, st);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return OCS_OK;
+}
+
+int ocs_quantize(const float* x, int64_t rows, int64_t cols, int64_t ldx, int bits,
+                 const float* threshold, float clip_ratio, int8_t* q, int64_t ldq,
+                 float* scale_out, void* workspace, size_t ws_bytes, void* stream) {
+    if (!x || !q || !scale_out) return OCS_E_NULL;
+    if (rows <= 0 || cols <= 0 || cols > (int64_t)1 << 30 || rows > (int64_t)1 << 31 || ldx < cols)
+        return OCS_E_SHAPE;
+    int rc = check_codes(q, ldq, cols);
+    if (rc) return rc;
+    if (!bits_ok(bits)) return OCS_E_BITS;
+    const float qmax = qmax_of(bits);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (threshold == nullptr) {
+        rc = check_workspace(workspace, ws_bytes, rows, cols);
+        if (rc) return rc;
+        Workspace w = plan_workspace(rows, cols);
+        char* base = static_cast<char*>(workspace);
+        float* colmax = reinterpret_cast<float*>(base + w.colmax_off);
+        float* partial = reinterpret_cast<float*>(base + w.partial_off);
+        e = launch_colmax(x, rows, cols, ldx, colmax, partial, st);
+        if (e != hipSuccess) return hip_fail(e);
+        e = launch_threshold(colmax, (int)cols, 1, 0, nullptr, nullptr, clip_ratio, qmax, scale_out, st);
+        if (e != hipSuccess) return hip_fail(e);
+        e = launch_expand_quantize(x, ldx, rows, (int)cols, 1, 0, nullptr, nullptr, scale_out, qmax,
+                                   q, ldq, nullptr, st);
+    } else {
+        e = launch_expand_quantize(x, ldx, rows, (int)cols, 1, 0, nullptr, nullptr, threshold, qmax,
+                                   q, ldq, scale_out, st);
+    }
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
+int ocs_split_act(const float* X, int64_t M, int C, int g, int64_t ldx, const int32_t* chan_src,
+                  const int32_t* chan_depth, int num_splits, int bits, const float* threshold,
+                  float clip_ratio, int8_t* Xq, int64_t ldq, float* scale_out, void* workspace,
+                  size_t ws_bytes, void* stream) {
+    if (!X || !Xq || !scale_out || (num_splits > 0 && !chan_src)) return OCS_E_NULL;
+    int rc = check_layer(M, C, g, ldx, num_splits);
+    if (rc) return rc;
+    const int64_t K = (int64_t)C * g, Ke = (int64_t)(C + num_splits) * g;
+    rc = check_codes(Xq, ldq, Ke);
+    if (rc) return rc;
+    if (!bits_ok(bits)) return OCS_E_BITS;
+    const float qmax = qmax_of(bits);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (threshold == nullptr) {
+        // X1: the dynamic grid needs max|expanded activations| before the streaming pass
+        rc = check_workspace(workspace, ws_bytes, M, K);
+        if (rc) return rc;
+        Workspace w = plan_workspace(M, K);
+        char* base = static_cast<char*>(workspace);
+        float* colmax = reinterpret_cast<float*>(base + w.colmax_off);
+        float* partial = reinterpret_cast<float*>(base + w.partial_off);
+        e = launch_colmax(X, M, K, ldx, colmax, partial, st);
+        if (e != hipSuccess) return hip_fail(e);
+        e = launch_threshold(colmax, C, g, num_splits, chan_src, chan_depth, clip_ratio, qmax,
+                             scale_out, st);
+        if (e != hipSuccess) return hip_fail(e);
+        e = launch_expand_quantize(X, ldx, M, C, g, num_splits, chan_src, chan_depth, scale_out,
+                                   qmax, Xq, ldq, nullptr, st);
+    } else {
+        // X2 alone: one pass
+        e = launch_expand_quantize(X, ldx, M, C, g, num_splits, chan_src, chan_depth, threshold,
+                                   qmax, Xq, ldq, scale_out, st);
+    }
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
+int ocs_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M, int64_t N,
+              int64_t Kexp, int bits_x, int bits_w, const float* scale_x, const float* scale_w,
+              int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy, void* workspace,
+              size_t ws_bytes, void* stream) {
+    (void)workspace;
+    (void)ws_bytes;
+    if (!Xq || !Wq || !scale_x || !scale_w || !Y) return OCS_E_NULL;
+    if (M <= 0 || N <= 0 || Kexp <= 0) return OCS_E_SHAPE;
+    if (M > (int64_t)1 << 30 || N > (int64_t)1 << 30 || Kexp > (int64_t)1 << 30) return OCS_E_SHAPE;
+    const int64_t Kpad = round_up(Kexp, OCS_KALIGN);
+    if (ldx < Kpad || ldw < Kpad || ldy < N || (acc_out && ldacc < N)) return OCS_E_SHAPE;
+    if (ldx % OCS_KALIGN != 0 || ldw % OCS_KALIGN != 0 || !aligned(Xq, 16) || !aligned(Wq, 16))
+        return OCS_E_ALIGN;
+    if (!bits_ok(bits_x) || !bits_ok(bits_w)) return OCS_E_BITS;
+    const int64_t qx = (1 << (bits_x - 1)) - 1, qw = (1 << (bits_w - 1)) - 1;
+    if (Kexp * qx * qw >= (int64_t)1 << 31) return OCS_E_OVERFLOW;
+    hipError_t e = launch_qgemm(Xq, ldx, Wq, ldw, M, N, Kpad, scale_x, scale_w, acc_out, ldacc, Y,
+                                ldy, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
+int ocs_tune(const char* key, int value) {
+    if (!key) return OCS_E_NULL;
+    Tuning& t = tuning();
+    if (!strcmp(key, "act_rows_per_block")) t.act_rows_per_block = value;
+    else if (!strcmp(key, "act_tx")) t.act_tx = value;
+    else if (!strcmp(key, "gemm_tile")) t.gemm_tile = value;
+    else return OCS_E_MODE;
+    return OCS_OK;
+}
+
+}  // extern "C"

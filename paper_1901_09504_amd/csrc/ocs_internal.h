@@ -1,0 +1,87 @@
+// Internal declarations shared by the translation units of libocs.so (device side only).
+// Nothing in here is part of the ABI; see include/ocs.h for that.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ocs {
+
+constexpr int kThreads = 256;      // every kernel here runs 256-thread workgroups (4 wave64)
+constexpr int kMaxExpanded = 8000;  // C + s limit of the single-workgroup greedy selector
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+
+inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Shape of the two-stage column-maximum reduction over a [rows, cols] fp32 tensor.
+// Stage 1 writes partial[row_blocks][cols]; stage 2 folds the row blocks into colmax[cols].
+struct ReducePlan {
+    int vec;            // 4: float4 loads over cols/4 groups (+ scalar pass on cols%4), 1: scalar
+    int tx, ty;         // workgroup shape, tx*ty == kThreads
+    int col_strips;     // grid.x of the vector pass
+    int row_blocks;     // grid.y == number of partial rows
+    int rows_per_block; // rows each workgroup walks
+};
+
+ReducePlan plan_reduce(int64_t rows, int64_t cols, bool vec_ok);
+
+// Workspace layout (byte offsets from a 256-byte aligned base).
+struct Workspace {
+    size_t colmax_off;   // float[round_up(cols, 64)]
+    size_t partial_off;  // float[row_blocks * cols]
+    size_t total;
+};
+Workspace plan_workspace(int64_t rows, int64_t cols);
+
+// ---- launchers (each returns the hipError_t of its launches) ---------------------------------
+
+// colmax[c] = max_r |T[r, c]| for c < cols.  Two stages, no atomics, deterministic.
+hipError_t launch_colmax(const float* T, int64_t rows, int64_t cols, int64_t ld, float* colmax,
+                         float* partial, hipStream_t stream);
+
+// Greedy channel selection (mode 0) or replay of a given split list (mode 1) on the C
+// channel maxima derived from colmax[C*g].  Optionally writes max_out and
+// scale_out = {clip*max, clip*max/qmax}.
+hipError_t launch_select(const float* colmax, int C, int g, int s, int mode,
+                         const int32_t* split_in, int32_t* split_src, int32_t* chan_src,
+                         int32_t* chan_depth, float* max_out, float clip_ratio, float qmax,
+                         float* scale_out, hipStream_t stream);
+
+// scale_out = {T, T/qmax} with T = clip * max over expanded channels j of
+// (max_t colmax[chan_src[j]*g+t]) * 2^-chan_depth[j]  (depth NULL: factor 1; src NULL: identity).
+hipError_t launch_threshold(const float* colmax, int C, int g, int s, const int32_t* chan_src,
+                            const int32_t* chan_depth, float clip_ratio, float qmax,
+                            float* scale_out, hipStream_t stream);
+
+// Fused gather / halve / quantize / pack: the streaming pass over activations (or weights).
+// thr: device float threshold.  scale_out (may be NULL): receives {T, T/qmax}.
+hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C, int g, int s,
+                                  const int32_t* chan_src, const int32_t* chan_depth,
+                                  const float* thr, float qmax, int8_t* Xq, int64_t ldq,
+                                  float* scale_out, hipStream_t stream);
+
+// fp32 expanded tensor: out[r, j*g+t] = T[r, chan_src[j]*g+t] * (halve ? 2^-chan_depth[j] : 1).
+hipError_t launch_expand_f32(const float* T, int64_t ld, int64_t rows, int C, int g, int s,
+                             const int32_t* chan_src, const int32_t* chan_depth, int halve,
+                             float* out, int64_t ldo, hipStream_t stream);
+
+// int8 x int8 -> int32 MFMA GEMM over Kpad (multiple of 64) with dequantizing epilogue.
+hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
+                        int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,
+                        int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy,
+                        hipStream_t stream);
+
+// Launch-shape overrides (benchmarking only); < 0 means "use the default".
+struct Tuning {
+    int act_rows_per_block = -1;
+    int act_tx = -1;
+    int gemm_tile = -1;
+};
+Tuning& tuning();
+
+}  // namespace ocs

@@ -1,0 +1,177 @@
+// Column-wise absolute maxima of an fp32 [rows, cols] tensor, and the threshold kernel.
+//
+// Sec. 3.4 needs, for every input channel, the largest magnitude it holds; Eq. 1 needs the
+// largest magnitude of a whole tensor.  Both come from colmax[c] = max_r |T[r,c]|.  The pass
+// is bound by HBM: every element is read once with 16-byte loads; the reduction runs in
+// registers along rows, through LDS across the rows of a workgroup, and through a small
+// partial[row_blocks][cols] buffer across workgroups (no atomics: deterministic, and no
+// cross-XCD read-modify-write traffic).
+#include "ocs_internal.h"
+
+namespace ocs {
+
+ReducePlan plan_reduce(int64_t rows, int64_t cols, bool vec_ok) {
+    ReducePlan p;
+    p.vec = (vec_ok && cols >= 4) ? 4 : 1;
+    int64_t units = cols / p.vec;
+    p.tx = units <= 16 ? 16 : (units <= 32 ? 32 : 64);
+    if (p.vec == 4 && units > 32) p.tx = 32;  // 32 lanes x 16 B = 512 B of one row per pass
+    p.ty = kThreads / p.tx;
+    p.col_strips = (int)ceil_div(units, p.tx);
+    // enough workgroups to fill 256 CUs several times over, but a partial buffer of at
+    // most ~1 MB so that stage 2 stays negligible
+    int64_t want_blocks = ceil_div(2048, p.col_strips);
+    int64_t cap_blocks = (int64_t)262144 / (cols > 0 ? cols : 1);
+    if (cap_blocks < 16) cap_blocks = 16;
+    int64_t rb = want_blocks < cap_blocks ? want_blocks : cap_blocks;
+    int64_t max_rb = ceil_div(rows, p.ty);
+    if (rb > max_rb) rb = max_rb;
+    if (rb < 1) rb = 1;
+    p.rows_per_block = (int)ceil_div(rows, rb);
+    p.row_blocks = (int)ceil_div(rows, p.rows_per_block);
+    return p;
+}
+
+Workspace plan_workspace(int64_t rows, int64_t cols) {
+    Workspace w;
+    // the plan with the most row blocks bounds both the vector and the scalar variant
+    ReducePlan a = plan_reduce(rows, cols, true);
+    ReducePlan b = plan_reduce(rows, cols, false);
+    int64_t rb = a.row_blocks > b.row_blocks ? a.row_blocks : b.row_blocks;
+    w.colmax_off = 0;
+    w.partial_off = (size_t)round_up(round_up(cols, 64) * 4, 256);
+    w.total = w.partial_off + (size_t)round_up(rb * cols * 4, 256);
+    return w;
+}
+
+// Stage 1.  Workgroup (tx, ty): lane tx owns VEC consecutive columns of strip blockIdx.x,
+// ty walks the rows of row block blockIdx.y with stride TY.
+template <int VEC>
+__global__ __launch_bounds__(kThreads) void colmax_partial_kernel(
+    const float* __restrict__ T, int64_t ld, int64_t rows, int64_t col0, int64_t units,
+    int rows_per_block, int64_t out_cols, float* __restrict__ partial) {
+    __shared__ float red[kThreads * VEC];
+    const int tx = threadIdx.x, ty = threadIdx.y, TX = blockDim.x, TY = blockDim.y;
+    const int64_t u = (int64_t)blockIdx.x * TX + tx;
+    const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
+    int64_t r1 = r0 + rows_per_block;
+    if (r1 > rows) r1 = rows;
+
+    float acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
+
+    if (u < units) {
+        const float* base = T + col0 + u * VEC;
+#pragma unroll 4
+        for (int64_t r = r0 + ty; r < r1; r += TY) {
+            if constexpr (VEC == 4) {
+                f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(base + r * ld));
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] = fmaxf(acc[e], fabsf(v[e]));
+            } else {
+                acc[0] = fmaxf(acc[0], fabsf(base[r * ld]));
+            }
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) red[(ty * TX + tx) * VEC + e] = acc[e];
+    __syncthreads();
+    if (ty == 0 && u < units) {
+        for (int y = 1; y < TY; ++y)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] = fmaxf(acc[e], red[(y * TX + tx) * VEC + e]);
+        float* dst = partial + (int64_t)blockIdx.y * out_cols + col0 + u * VEC;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) dst[e] = acc[e];
+    }
+}
+
+// Stage 2: colmax[c] = max over partial rows.  Workgroup = 64 columns x 4 row groups.
+__global__ __launch_bounds__(kThreads) void colmax_final_kernel(const float* __restrict__ partial,
+                                                                int row_blocks, int64_t cols,
+                                                                float* __restrict__ colmax) {
+    __shared__ float red[kThreads];
+    const int cx = threadIdx.x & 63, gy = threadIdx.x >> 6;
+    const int64_t c = (int64_t)blockIdx.x * 64 + cx;
+    float m = 0.0f;
+    if (c < cols)
+        for (int r = gy; r < row_blocks; r += 4) m = fmaxf(m, partial[(int64_t)r * cols + c]);
+    red[threadIdx.x] = m;
+    __syncthreads();
+    if (gy == 0 && c < cols) {
+        m = fmaxf(fmaxf(red[cx], red[64 + cx]), fmaxf(red[128 + cx], red[192 + cx]));
+        colmax[c] = m;
+    }
+}
+
+hipError_t launch_colmax(const float* T, int64_t rows, int64_t cols, int64_t ld, float* colmax,
+                         float* partial, hipStream_t stream) {
+    bool vec_ok = (reinterpret_cast<uintptr_t>(T) % 16 == 0) && (ld % 4 == 0);
+    ReducePlan p = plan_reduce(rows, cols, vec_ok);
+    dim3 block(p.tx, p.ty);
+    if (p.vec == 4) {
+        int64_t units = cols / 4;
+        dim3 grid(p.col_strips, p.row_blocks);
+        colmax_partial_kernel<4><<<grid, block, 0, stream>>>(T, ld, rows, 0, units,
+                                                             p.rows_per_block, cols, partial);
+        int64_t left = cols - units * 4;
+        if (left > 0) {  // the last cols % 4 columns, one lane each
+            dim3 grid1(1, p.row_blocks);
+            colmax_partial_kernel<1><<<grid1, block, 0, stream>>>(T, ld, rows, units * 4, left,
+                                                                  p.rows_per_block, cols, partial);
+        }
+    } else {
+        dim3 grid(p.col_strips, p.row_blocks);
+        colmax_partial_kernel<1><<<grid, block, 0, stream>>>(T, ld, rows, 0, cols,
+                                                             p.rows_per_block, cols, partial);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    colmax_final_kernel<<<(unsigned)ceil_div(cols, 64), kThreads, 0, stream>>>(partial, p.row_blocks,
+                                                                              cols, colmax);
+    return hipGetLastError();
+}
+
+// Threshold of Eq. 1 for an expanded activation tensor without materialising it:
+// max_j (channel maximum of chan_src[j]) * 2^-chan_depth[j], times the clip ratio.
+__global__ __launch_bounds__(kThreads) void threshold_kernel(
+    const float* __restrict__ colmax, int C, int g, int s, const int32_t* __restrict__ chan_src,
+    const int32_t* __restrict__ chan_depth, float clip_ratio, float qmax,
+    float* __restrict__ scale_out) {
+    __shared__ float red[kThreads];
+    float m = 0.0f;
+    if (chan_depth == nullptr) {
+        // copies do not change the maximum: plain maximum over all columns
+        for (int64_t c = threadIdx.x; c < (int64_t)C * g; c += kThreads) m = fmaxf(m, colmax[c]);
+    } else {
+        for (int j = threadIdx.x; j < C + s; j += kThreads) {
+            int src = chan_src ? chan_src[j] : j;
+            src = src < 0 ? 0 : (src >= C ? C - 1 : src);
+            float cm = 0.0f;
+            for (int t = 0; t < g; ++t) cm = fmaxf(cm, colmax[(int64_t)src * g + t]);
+            m = fmaxf(m, cm * ldexpf(1.0f, -chan_depth[j]));
+        }
+    }
+    red[threadIdx.x] = m;
+    __syncthreads();
+    for (int w = kThreads / 2; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + w]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        float T = clip_ratio * red[0];
+        scale_out[0] = T;
+        scale_out[1] = T / qmax;
+    }
+}
+
+hipError_t launch_threshold(const float* colmax, int C, int g, int s, const int32_t* chan_src,
+                            const int32_t* chan_depth, float clip_ratio, float qmax,
+                            float* scale_out, hipStream_t stream) {
+    threshold_kernel<<<1, kThreads, 0, stream>>>(colmax, C, g, s, chan_src, chan_depth, clip_ratio,
+                                                 qmax, scale_out);
+    return hipGetLastError();
+}
+
+}  // namespace ocs

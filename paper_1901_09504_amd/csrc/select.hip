@@ -1,0 +1,138 @@
+// Greedy channel selection of Sec. 3.4 on the channel maxima.
+//
+// The paper splits one channel at a time, always the one that currently holds the largest
+// magnitude in the layer.  Halving a channel halves its maximum exactly and its copy has the
+// same maximum, so the whole sequence of choices depends only on the C channel maxima: the
+// tensor itself is never re-scanned.  One workgroup keeps the (growing) list of maxima in
+// LDS; each of its 256 lanes caches the best entry among the slots it owns (slot j belongs to
+// lane j mod 256), so a step is one cross-lane arg-max plus a re-scan by the at most two lanes
+// whose slots changed.  Ties go to the lowest expanded index: the key packs the value's bit
+// pattern (non-negative floats order like unsigned integers) above the complemented index.
+#include "ocs_internal.h"
+
+namespace ocs {
+
+__device__ inline unsigned long long key_of(float v, int j) {
+    return ((unsigned long long)__float_as_uint(v) << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)j);
+}
+
+__device__ inline unsigned long long wave_max_u64(unsigned long long k) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        unsigned long long o = __shfl_xor(k, off, 64);
+        k = o > k ? o : k;
+    }
+    return k;
+}
+
+__global__ __launch_bounds__(kThreads) void select_kernel(
+    const float* __restrict__ colmax, int C, int g, int s, int mode,
+    const int32_t* split_in, int32_t* split_src,
+    int32_t* __restrict__ chan_src, int32_t* __restrict__ chan_depth, float* __restrict__ max_out,
+    float clip_ratio, float qmax, float* __restrict__ scale_out) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int E = C + s;
+    // 8 bytes per expanded channel: 8000 channels stay below the 64 KB a workgroup may use
+    // without opting in to more
+    float* vals = reinterpret_cast<float*>(smem);
+    unsigned short* src = reinterpret_cast<unsigned short*>(vals + E);
+    unsigned short* dep = src + E;
+    __shared__ unsigned long long wkey[kThreads / 64];
+    __shared__ float red[kThreads];
+    const int tid = threadIdx.x;
+
+    for (int j = tid; j < C; j += kThreads) {
+        float m = 0.0f;
+        for (int t = 0; t < g; ++t) m = fmaxf(m, colmax[(int64_t)j * g + t]);
+        vals[j] = m;
+        src[j] = (unsigned short)j;
+        dep[j] = 0;
+    }
+    __syncthreads();
+
+    if (mode == 0) {
+        unsigned long long local = 0;
+        for (int j = tid; j < C; j += kThreads) {
+            unsigned long long k = key_of(vals[j], j);
+            local = k > local ? k : local;
+        }
+        for (int i = 0; i < s; ++i) {
+            const int cur = C + i;
+            unsigned long long k = wave_max_u64(local);
+            if ((tid & 63) == 0) wkey[tid >> 6] = k;
+            __syncthreads();
+            k = wkey[0];
+#pragma unroll
+            for (int w = 1; w < kThreads / 64; ++w) k = wkey[w] > k ? wkey[w] : k;
+            const int jstar = (int)(0xFFFFFFFFu - (unsigned)(k & 0xFFFFFFFFull));
+            const float half = __uint_as_float((unsigned)(k >> 32)) * 0.5f;
+            const bool owns_old = (jstar % kThreads) == tid;
+            const bool owns_new = (cur % kThreads) == tid;
+            if (owns_old) {
+                vals[jstar] = half;
+                unsigned short d = (unsigned short)(dep[jstar] + 1);
+                dep[jstar] = d;
+                vals[cur] = half;
+                src[cur] = src[jstar];
+                dep[cur] = d;
+                split_src[i] = jstar;
+            }
+            __syncthreads();
+            if (owns_old || owns_new) {
+                local = 0;
+                for (int j = tid; j <= cur; j += kThreads) {
+                    unsigned long long kk = key_of(vals[j], j);
+                    local = kk > local ? kk : local;
+                }
+            }
+        }
+    } else {
+        if (tid == 0) {
+            for (int i = 0; i < s; ++i) {
+                const int cur = C + i;
+                int j = split_in[i];
+                j = j < 0 ? 0 : (j >= cur ? cur - 1 : j);
+                unsigned short d = (unsigned short)(dep[j] + 1);
+                dep[j] = d;
+                vals[cur] = vals[j];  // copies are not halved: the maximum stays
+                src[cur] = src[j];
+                dep[cur] = d;
+            }
+        }
+    }
+    __syncthreads();
+
+    float m = 0.0f;
+    for (int j = tid; j < E; j += kThreads) {
+        chan_src[j] = src[j];
+        chan_depth[j] = dep[j];
+        m = fmaxf(m, vals[j]);
+    }
+    red[tid] = m;
+    __syncthreads();
+    for (int w = kThreads / 2; w > 0; w >>= 1) {
+        if (tid < w) red[tid] = fmaxf(red[tid], red[tid + w]);
+        __syncthreads();
+    }
+    if (tid == 0) {
+        if (max_out) *max_out = red[0];
+        if (scale_out) {
+            float T = clip_ratio * red[0];
+            scale_out[0] = T;
+            scale_out[1] = T / qmax;
+        }
+    }
+}
+
+hipError_t launch_select(const float* colmax, int C, int g, int s, int mode,
+                         const int32_t* split_in, int32_t* split_src, int32_t* chan_src,
+                         int32_t* chan_depth, float* max_out, float clip_ratio, float qmax,
+                         float* scale_out, hipStream_t stream) {
+    size_t lds = (size_t)(C + s) * 8;  // C + s <= kMaxExpanded is checked by the caller
+    select_kernel<<<1, kThreads, lds, stream>>>(colmax, C, g, s, mode, split_in, split_src,
+                                                chan_src, chan_depth, max_out, clip_ratio, qmax,
+                                                scale_out);
+    return hipGetLastError();
+}
+
+}  // namespace ocs

@@ -1,0 +1,97 @@
+"""Buffer ownership and call order for one OCS-expanded quantized layer.
+
+A convenience over `binding`: it allocates the device buffers (PyTorch is the allocator),
+keeps the split lists and scales on the device, and issues the C-ABI calls in order.  No
+arithmetic happens here.
+
+  weight OCS (Sec. 3.2 Eq. 3, the variant the paper finds effective, Sec. 5.2):
+      prepare_weights(W)           off-line: select on W, halve, quantize        (W1-W3)
+      forward(X[, threshold])      per batch: duplicate channels + quantize, GEMM (X1/X2, G1, G2)
+  activation OCS (Eq. 4) with the channels chosen on the batch itself (Sec. 5.3):
+      forward_act_ocs(W, X)        select on X, duplicate weights, halve + quantize X, GEMM
+"""
+import torch
+
+from . import binding as B
+
+
+class ExpandedLayer:
+    def __init__(self, N, C, g, r, bits_w=8, bits_x=8, clip_ratio_w=1.0, clip_ratio_x=1.0,
+                 max_rows=None, device="cuda"):
+        self.N, self.C, self.g = int(N), int(C), int(g)
+        self.K = self.C * self.g
+        self.s = B.ocs_num_splits(self.C, r)
+        self.Ke = (self.C + self.s) * self.g
+        self.ldq = B.ocs_padded_cols(self.Ke)
+        self.bits_w, self.bits_x = int(bits_w), int(bits_x)
+        self.clip_ratio_w, self.clip_ratio_x = float(clip_ratio_w), float(clip_ratio_x)
+        self.device = device
+        E = self.C + self.s
+        i32 = dict(dtype=torch.int32, device=device)
+        self.split_src = torch.empty(max(self.s, 1), **i32)
+        self.chan_src = torch.empty(E, **i32)
+        self.chan_depth = torch.empty(E, **i32)
+        self.Wq = torch.empty((self.N, self.ldq), dtype=torch.int8, device=device)
+        self.scale_w = torch.empty(2, dtype=torch.float32, device=device)
+        self.scale_x = torch.empty(2, dtype=torch.float32, device=device)
+        self.wmax = torch.empty(1, dtype=torch.float32, device=device)
+        self.ws_w = B.alloc_workspace(self.N, self.K, device)
+        self._rows = 0
+        self.Xq = self.Y = self.ws_x = None
+        if max_rows:
+            self._ensure_rows(max_rows)
+
+    def _ensure_rows(self, M):
+        if M > self._rows:
+            self.Xq = torch.empty((M, self.ldq), dtype=torch.int8, device=self.device)
+            self.Y = torch.empty((M, self.N), dtype=torch.float32, device=self.device)
+            self.ws_x = B.alloc_workspace(M, self.K, self.device)
+            self._rows = M
+
+    # ---- off-line ---------------------------------------------------------------------------
+    def prepare_weights(self, W, W_out=None, clip_ratio_w=None, stream=None):
+        """W fp32 [N, C*g] on the device -> split lists, Wq, scale_w (and W' if W_out given)."""
+        assert W.dtype == torch.float32 and W.shape == (self.N, self.K)
+        clip = self.clip_ratio_w if clip_ratio_w is None else float(clip_ratio_w)
+        B.ocs_split_weights(W, self.N, self.C, self.g, W.stride(0), self.s, B.MODE_HALVE,
+                            self.split_src, self.chan_src, self.chan_depth, W_out,
+                            0 if W_out is None else W_out.stride(0), self.wmax, self.bits_w, clip,
+                            self.Wq, self.ldq, self.scale_w, self.ws_w, stream)
+
+    # ---- per batch --------------------------------------------------------------------------
+    def split_act(self, X, threshold=None, stream=None):
+        M = X.shape[0]
+        self._ensure_rows(M)
+        B.ocs_split_act(X, M, self.C, self.g, X.stride(0), self.chan_src, None, self.s, self.bits_x,
+                        threshold, self.clip_ratio_x, self.Xq, self.ldq, self.scale_x, self.ws_x,
+                        stream)
+
+    def qgemm(self, M, acc_out=None, stream=None):
+        B.ocs_qgemm(self.Xq, self.ldq, self.Wq, self.ldq, M, self.N, self.Ke, self.bits_x,
+                    self.bits_w, self.scale_x, self.scale_w, acc_out,
+                    0 if acc_out is None else acc_out.stride(0), self.Y, self.N, None, stream)
+
+    def forward(self, X, threshold=None, acc_out=None, stream=None):
+        """X fp32 [M, C*g] -> Y fp32 [M, N].  threshold: device float tensor for a static
+        activation grid (Sec. 5: fixed from profiling), None for a per-batch dynamic one."""
+        M = X.shape[0]
+        self.split_act(X, threshold, stream)
+        self.qgemm(M, acc_out, stream)
+        return self.Y[:M]
+
+    def forward_act_ocs(self, W, X, acc_out=None, stream=None):
+        """Activation OCS with the channel choice made on this batch (Eq. 4, Sec. 5.3)."""
+        M = X.shape[0]
+        self._ensure_rows(M)
+        xmax = torch.empty(1, dtype=torch.float32, device=self.device)
+        B.ocs_select_channels(X, M, self.C, self.g, X.stride(0), self.s, self.split_src,
+                              self.chan_src, self.chan_depth, xmax, self.ws_x, stream)
+        B.ocs_split_weights(W, self.N, self.C, self.g, W.stride(0), self.s, B.MODE_DUP,
+                            self.split_src, self.chan_src, self.chan_depth, None, 0, self.wmax,
+                            self.bits_w, self.clip_ratio_w, self.Wq, self.ldq, self.scale_w,
+                            self.ws_w, stream)
+        B.ocs_split_act(X, M, self.C, self.g, X.stride(0), self.chan_src, self.chan_depth, self.s,
+                        self.bits_x, None, self.clip_ratio_x, self.Xq, self.ldq, self.scale_x,
+                        self.ws_x, stream)
+        self.qgemm(M, acc_out, stream)
+        return self.Y[:M]

@@ -118,6 +118,23 @@ def activations(layer: Layer, row0: int = 0, rows: Optional[int] = None) -> np.n
     return out
 
 
+def activations_into(layer: Layer, out: np.ndarray, threads: int = 8) -> np.ndarray:
+    """Fill out[:layer.M] (fp32 [>=M, C*g], e.g. a pinned buffer) with the layer's activations,
+    drawing the independent row blocks on several threads."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    nblocks = (layer.M + ROW_BLOCK - 1) // ROW_BLOCK
+
+    def fill(b):
+        b0 = b * ROW_BLOCK
+        nb = min(ROW_BLOCK, layer.M - b0)
+        out[b0:b0 + nb] = _act_block(layer, b, nb)
+
+    with ThreadPoolExecutor(max_workers=max(1, threads)) as ex:
+        list(ex.map(fill, range(nblocks)))
+    return out
+
+
 # ---------------------------------------------------------------------------------------
 # The five configurations
 # ---------------------------------------------------------------------------------------

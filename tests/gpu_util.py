@@ -1,0 +1,108 @@
+"""Helpers shared by the GPU parity tests: run one call of the C ABI on device copies of
+host arrays and bring the results back.  The expected values always come from oracle/."""
+import numpy as np
+import torch
+
+from paper_1901_09504_amd import binding as B
+
+
+def require_gpu():
+    if not torch.cuda.is_available():
+        raise RuntimeError("GPU test selected but no GPU is visible")
+    B.lib()   # raises if libocs.so is missing: there is no fallback
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def gpu_quantize(x, bits, threshold=None, clip_ratio=1.0, ld_extra=0, misalign=False):
+    rows, cols = x.shape
+    ldx = cols + ld_extra
+    buf = torch.zeros(rows * ldx + 4, dtype=torch.float32, device="cuda")
+    off = 1 if misalign else 0
+    xv = buf[off:off + rows * ldx].view(rows, ldx)
+    xv[:, :cols] = dev(x)
+    ldq = B.ocs_padded_cols(cols)
+    q = torch.full((rows, ldq), 77, dtype=torch.int8, device="cuda")
+    sc = torch.zeros(2, dtype=torch.float32, device="cuda")
+    th = None if threshold is None else torch.tensor([threshold], dtype=torch.float32, device="cuda")
+    ws = B.alloc_workspace(rows, cols)
+    B.ocs_quantize(xv, rows, cols, ldx, bits, th, clip_ratio, q, ldq, sc, ws)
+    return host(q), host(sc)
+
+
+def gpu_select(T, Cn, g, s):
+    rows = T.shape[0]
+    Td = dev(T)
+    ss = torch.full((max(s, 1),), -7, dtype=torch.int32, device="cuda")
+    cs = torch.full((Cn + s,), -7, dtype=torch.int32, device="cuda")
+    cd = torch.full((Cn + s,), -7, dtype=torch.int32, device="cuda")
+    mx = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ws = B.alloc_workspace(rows, Cn * g)
+    B.ocs_select_channels(Td, rows, Cn, g, Td.stride(0), s, ss, cs, cd, mx, ws)
+    return dict(split_src=host(ss)[:s], chan_src=host(cs), chan_depth=host(cd), max=float(host(mx)[0]))
+
+
+def gpu_split_weights(W, Cn, g, s, mode=B.MODE_HALVE, split_src=None, bits=8, clip_ratio=1.0,
+                      want_f32=True, want_codes=True):
+    N = W.shape[0]
+    Wd = dev(W)
+    Ke = (Cn + s) * g
+    ldq = B.ocs_padded_cols(Ke)
+    if mode == B.MODE_DUP:
+        ss = dev(np.asarray(split_src, dtype=np.int32)) if s > 0 else torch.zeros(1, dtype=torch.int32, device="cuda")
+    else:
+        ss = torch.full((max(s, 1),), -7, dtype=torch.int32, device="cuda")
+    cs = torch.full((Cn + s,), -7, dtype=torch.int32, device="cuda")
+    cd = torch.full((Cn + s,), -7, dtype=torch.int32, device="cuda")
+    Wo = torch.full((N, Ke), 7.0, dtype=torch.float32, device="cuda") if want_f32 else None
+    Wq = torch.full((N, ldq), 77, dtype=torch.int8, device="cuda") if want_codes else None
+    sc = torch.zeros(2, dtype=torch.float32, device="cuda")
+    mx = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ws = B.alloc_workspace(N, Cn * g)
+    B.ocs_split_weights(Wd, N, Cn, g, Wd.stride(0), s, mode, ss, cs, cd, Wo, Ke, mx, bits, clip_ratio,
+                        Wq, ldq, sc if want_codes else None, ws)
+    return dict(split_src=host(ss)[:s], chan_src=host(cs), chan_depth=host(cd),
+                T_out=None if Wo is None else host(Wo), Wq=None if Wq is None else host(Wq),
+                scale=host(sc), max=float(host(mx)[0]))
+
+
+def gpu_split_act(X, Cn, g, chan_src, chan_depth, s, bits, threshold=None, clip_ratio=1.0):
+    M = X.shape[0]
+    Xd = dev(X)
+    ldq = B.ocs_padded_cols((Cn + s) * g)
+    cs = None if chan_src is None else dev(np.asarray(chan_src, dtype=np.int32))
+    cd = None if chan_depth is None else dev(np.asarray(chan_depth, dtype=np.int32))
+    q = torch.full((M, ldq), 77, dtype=torch.int8, device="cuda")
+    sc = torch.zeros(2, dtype=torch.float32, device="cuda")
+    th = None if threshold is None else torch.tensor([threshold], dtype=torch.float32, device="cuda")
+    ws = B.alloc_workspace(M, Cn * g)
+    B.ocs_split_act(Xd, M, Cn, g, Xd.stride(0), cs, cd, s, bits, th, clip_ratio, q, ldq, sc, ws)
+    return host(q), host(sc)
+
+
+def gpu_qgemm(Xq, Wq, Kexp, scale_x, scale_w, bits_x=8, bits_w=8, want_acc=True):
+    M, N = Xq.shape[0], Wq.shape[0]
+    Xd, Wd = dev(Xq), dev(Wq)
+    sx, sw = dev(np.asarray(scale_x, dtype=np.float32)), dev(np.asarray(scale_w, dtype=np.float32))
+    acc = torch.full((M, N), -7, dtype=torch.int32, device="cuda") if want_acc else None
+    Y = torch.full((M, N), -7.0, dtype=torch.float32, device="cuda")
+    B.ocs_qgemm(Xd, Xd.stride(0), Wd, Wd.stride(0), M, N, Kexp, bits_x, bits_w, sx, sw, acc,
+                N if want_acc else 0, Y, N)
+    return (host(acc) if want_acc else None), host(Y)
+
+
+def assert_y_close(Y_gpu, Y_ref, rel=1e-6):
+    """fp32 output against the fp64 oracle: 1e-6 relative, element by element."""
+    Y_gpu = Y_gpu.astype(np.float64)
+    err = np.abs(Y_gpu - Y_ref)
+    tol = rel * np.abs(Y_ref)
+    bad = err > tol
+    assert not bad.any(), f"{bad.sum()} of {bad.size} outputs off by more than {rel} relative; " \
+                          f"worst {np.max(err / np.maximum(np.abs(Y_ref), 1e-300))}"

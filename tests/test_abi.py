@@ -1,0 +1,102 @@
+"""Host-side checks of the C ABI (no GPU): the library loads, exports every symbol that
+include/ocs.h declares, and rejects bad arguments before any device work."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import ref
+from paper_1901_09504_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "ocs.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ocs_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    assert {"ocs_num_splits", "ocs_split_weights", "ocs_quantize", "ocs_split_act", "ocs_qgemm",
+            "ocs_select_channels", "ocs_workspace_bytes", "ocs_strerror"} <= set(names)
+    L = B.lib()
+    for n in names:
+        assert hasattr(L, n), n
+        assert hasattr(B, n) or n in ("ocs_strerror", "ocs_last_hip_error"), f"binding lacks {n}"
+
+
+def test_num_splits_matches_oracle_everywhere():
+    for Cn in list(range(1, 300)) + [512, 1000, 1024, 1500, 2048, 3000, 4096]:
+        for r in (0.0, 0.01, 0.02, 0.05, 0.1, 0.2, 0.25, 0.5, 1.0):
+            assert B.ocs_num_splits(Cn, r) == ref.num_splits(Cn, r), (Cn, r)
+    assert B.ocs_num_splits(0, 0.1) == 0 and B.ocs_num_splits(10, -1.0) == 0
+
+
+def test_padded_cols_and_workspace():
+    assert B.ocs_padded_cols(2358) == 2368
+    assert B.ocs_padded_cols(64) == 64 and B.ocs_padded_cols(65) == 128 and B.ocs_padded_cols(0) == 0
+    assert B.ocs_workspace_bytes(0, 10) == 0
+    for rows, cols in [(1, 1), (64, 256), (12544, 2304), (6000, 3000), (3211264, 147), (802816, 64)]:
+        wb = B.ocs_workspace_bytes(rows, cols)
+        assert wb >= 4 * cols and wb % 256 == 0
+        assert wb < 64 << 20
+
+
+A = 1 << 20  # a fake, suitably aligned "device address": validation never dereferences it
+
+
+def _call(fn, *args):
+    return getattr(B.lib(), fn)(*args)
+
+
+def test_argument_errors_are_reported_without_a_device():
+    L = B.lib()
+    ws = 1 << 24
+    # NULL pointers
+    assert L.ocs_quantize(None, 4, 4, 4, 8, None, 1.0, A, 64, A, A, ws, None) == -1
+    assert L.ocs_split_act(A, 4, 4, 1, 4, None, None, 2, 8, None, 1.0, A, 64, A, A, ws, None) == -1
+    assert L.ocs_split_weights(A, 4, 4, 1, 4, 1, 0, None, A, A, None, 0, None, 8, 1.0, None, 0, None, A, ws, None) == -1
+    assert L.ocs_split_weights(A, 4, 4, 1, 4, 1, 0, A, A, A, None, 0, None, 8, 1.0, A, 64, None, A, ws, None) == -1
+    assert L.ocs_qgemm(A, 64, A, 64, 4, 4, 4, 8, 8, A, A, None, 0, None, 4, None, 0, None) == -1
+    # shapes
+    assert L.ocs_quantize(A, 0, 4, 4, 8, A, 1.0, A, 64, A, A, ws, None) == -2
+    assert L.ocs_quantize(A, 4, 8, 4, 8, A, 1.0, A, 64, A, A, ws, None) == -2      # ldx < cols
+    assert L.ocs_quantize(A, 4, 100, 100, 8, A, 1.0, A, 64, A, A, ws, None) == -2   # ldq < cols
+    assert L.ocs_split_act(A, 4, 4, 0, 4, A, None, 0, 8, A, 1.0, A, 64, A, A, ws, None) == -2
+    assert L.ocs_qgemm(A, 64, A, 64, 4, 4, 100, 8, 8, A, A, None, 0, A, 4, None, 0, None) == -2  # ld < Kpad
+    assert L.ocs_qgemm(A, 64, A, 64, 4, 8, 4, 8, 8, A, A, None, 0, A, 4, None, 0, None) == -2    # ldy < N
+    # alignment
+    assert L.ocs_quantize(A, 4, 4, 4, 8, A, 1.0, A, 48, A, A, ws, None) == -3
+    assert L.ocs_quantize(A, 4, 4, 4, 8, A, 1.0, A + 4, 64, A, A, ws, None) == -3
+    assert L.ocs_qgemm(A + 1, 64, A, 64, 4, 4, 4, 8, 8, A, A, None, 0, A, 4, None, 0, None) == -3
+    assert L.ocs_quantize(A, 4, 4, 4, 8, None, 1.0, A, 64, A, A + 16, ws, None) == -3   # workspace
+    # bits
+    for bits in (1, 9, 0, -3):
+        assert L.ocs_quantize(A, 4, 4, 4, bits, A, 1.0, A, 64, A, A, ws, None) == -4
+    assert L.ocs_qgemm(A, 64, A, 64, 4, 4, 4, 8, 9, A, A, None, 0, A, 4, None, 0, None) == -4
+    # splits
+    assert L.ocs_split_act(A, 4, 4, 1, 4, A, None, -1, 8, A, 1.0, A, 64, A, A, ws, None) == -5
+    assert L.ocs_select_channels(A, 4, 7000, 1, 7000, 1001, A, A, A, None, A, ws, None) == -5
+    # overflow: 140000 * 127 * 127 >= 2^31, but fine at 4-bit weights
+    ld = 140032
+    assert L.ocs_qgemm(A, ld, A, ld, 4, 4, 140000, 8, 8, A, A, None, 0, A, 4, None, 0, None) == -6
+    # workspace
+    assert L.ocs_quantize(A, 4, 4, 4, 8, None, 1.0, A, 64, A, None, 0, None) == -7
+    assert L.ocs_quantize(A, 4, 4, 4, 8, None, 1.0, A, 64, A, A, 16, None) == -7
+    assert L.ocs_select_channels(A, 12544, 256, 9, 2304, 6, A, A, A, None, A, 1024, None) == -7
+    # mode / key
+    assert L.ocs_split_weights(A, 4, 4, 1, 4, 1, 7, A, A, A, None, 0, None, 8, 1.0, None, 0, None, A, ws, None) == -9
+    assert L.ocs_tune(b"no_such_key", 1) == -9
+    for code in range(-9, 1):
+        assert len(L.ocs_strerror(code)) > 1
+    assert L.ocs_strerror(-99) == b"unknown error code"
+
+
+def test_binding_raises_on_error():
+    with pytest.raises(B.OcsError) as e:
+        B._check(-4, "ocs_quantize")
+    assert "2..8" in str(e.value) and e.value.code == -4

@@ -1,0 +1,190 @@
+"""GPU parity on the five synthetic configurations, end to end through the C ABI:
+off-line weight path (select, halve, clip, quantize), per-batch activation path
+(duplicate / halve, quantize) and the expanded integer GEMM with its dequantizing epilogue.
+
+Every expected value comes from the CPU oracle on the same seeded inputs.  Where the layer
+is too large for the oracle's GEMM to finish in seconds, the GPU still runs the full layer in
+its normal launch configuration and the oracle recomputes a sample of complete rows (rows of
+the output are independent once the scales are fixed): the first and last row blocks, which
+hold the ragged edge, plus seeded random rows."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_1901_09504_amd import binding as B
+from paper_1901_09504_amd import workloads as wl
+from paper_1901_09504_amd.layer import ExpandedLayer
+
+from gpu_util import assert_y_close, dev, host, require_gpu
+
+pytestmark = pytest.mark.gpu
+
+FULL_ROWS = 13000      # up to this many rows the oracle recomputes every row
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    require_gpu()
+
+
+def _sample_rows(layer, n=1536):
+    M = layer.M
+    if M <= FULL_ROWS:
+        return np.arange(M)
+    rng = np.random.default_rng(layer.seed)
+    head = np.arange(0, 256)
+    tail = np.arange(M - 256, M)
+    mid = rng.choice(np.arange(256, M - 256), size=n - 512, replace=False)
+    return np.unique(np.concatenate([head, mid, tail]))
+
+
+def check_weight_path(layer, W, clip):
+    """W1-W3 on the GPU against the literal one-split-at-a-time oracle.  Returns both sides."""
+    L = ExpandedLayer(layer.N, layer.C, layer.g, layer.r, layer.bits_w, layer.bits_x, clip_ratio_w=clip)
+    assert L.s == ref.num_splits(layer.C, layer.r)
+    Wd = dev(W)
+    L.prepare_weights(Wd)
+    exp = ref.split_weights(W, layer.C, layer.g, L.s)
+    q_ref, sw_ref = ref.quantize(exp["T_out"], layer.bits_w, clip_ratio=clip, ldq=L.ldq)
+    assert np.array_equal(host(L.split_src)[:L.s], exp["split_src"])
+    assert np.array_equal(host(L.chan_src), exp["chan_src"])
+    assert np.array_equal(host(L.chan_depth), exp["chan_depth"])
+    assert host(L.wmax)[0] == exp["max"]
+    assert np.array_equal(host(L.scale_w), sw_ref)
+    assert np.array_equal(host(L.Wq), q_ref)
+    return L, exp, q_ref, sw_ref
+
+
+def check_forward(layer, L, exp, Wq_ref, sw_ref, X_dev, X_rows, rows, threshold):
+    """X2 + G1 + G2 on the GPU for the whole layer; the oracle recomputes `rows`."""
+    M = layer.M
+    th = None if threshold is None else torch.tensor([threshold], dtype=torch.float32, device="cuda")
+    acc = torch.empty((M, layer.N), dtype=torch.int32, device="cuda")
+    Y = L.forward(X_dev, threshold=th, acc_out=acc)
+    Xq_ref, sx_ref, _ = ref.split_act(X_rows, layer.C, layer.g, exp["chan_src"], None, L.s, layer.bits_x,
+                                      threshold=threshold, ldq=L.ldq)
+    rows_t = torch.from_numpy(rows).cuda()
+    assert np.array_equal(host(L.scale_x), sx_ref)
+    assert np.array_equal(host(L.Xq[:M][rows_t]), Xq_ref)
+    acc_ref, y_ref = ref.qgemm(Xq_ref, Wq_ref, L.Ke, sx_ref[1], sw_ref[1])
+    assert np.array_equal(host(acc[rows_t]), acc_ref)
+    assert_y_close(host(Y[rows_t]), y_ref)
+    # the timed configuration stores no accumulators: same outputs
+    Y1 = Y.clone()
+    Y2 = L.forward(X_dev, threshold=th)
+    assert torch.equal(Y1, Y2)
+    return sx_ref
+
+
+def run_layer(layer, clips=(1.0,), dynamic=True, static_threshold=None):
+    W = wl.weights(layer)
+    rows = _sample_rows(layer)
+    X = wl.activations(layer)
+    X_dev = dev(X)
+    first = True
+    for clip in clips:
+        L, exp, Wq_ref, sw_ref = check_weight_path(layer, W, clip)
+        if not first:
+            continue            # the activation path does not depend on the weight clip
+        first = False
+        if dynamic:
+            # the dynamic grid spans the whole batch: the oracle's threshold is its own max over
+            # all of X; the sampled rows are then requantized with that threshold
+            T = float(np.float32(np.abs(X).max()))
+            Xq_full, sx_full, _ = ref.split_act(X, layer.C, layer.g, exp["chan_src"], None, L.s,
+                                                layer.bits_x, ldq=L.ldq)
+            assert sx_full[0] == np.float32(T)
+            acc = torch.empty((layer.M, layer.N), dtype=torch.int32, device="cuda")
+            Y = L.forward(X_dev, threshold=None, acc_out=acc)
+            assert np.array_equal(host(L.scale_x), sx_full)
+            assert np.array_equal(host(L.Xq[:layer.M]), Xq_full)
+            acc_ref, y_ref = ref.qgemm(Xq_full[rows], Wq_ref, L.Ke, sx_full[1], sw_ref[1])
+            rows_t = torch.from_numpy(rows).cuda()
+            assert np.array_equal(host(acc[rows_t]), acc_ref)
+            assert_y_close(host(Y[rows_t]), y_ref)
+        if static_threshold is not None:
+            check_forward(layer, L, exp, Wq_ref, sw_ref, X_dev, X[rows], rows, static_threshold)
+    del X_dev
+    torch.cuda.empty_cache()
+
+
+# ---- config 1: single FC layer, weight OCS and activation OCS -------------------------------------
+
+def test_config1_weight_ocs():
+    (layer,) = wl.config(1)
+    run_layer(layer, dynamic=True, static_threshold=6.0)
+
+
+def test_config1_activation_ocs():
+    (layer,) = wl.config(1)
+    W, X = wl.weights(layer), wl.activations(layer)
+    L = ExpandedLayer(layer.N, layer.C, layer.g, layer.r, layer.bits_w, layer.bits_x)
+    acc = torch.empty((layer.M, layer.N), dtype=torch.int32, device="cuda")
+    Y = L.forward_act_ocs(dev(W), dev(X), acc_out=acc)
+    sel = ref.split_weights(X, layer.C, layer.g, L.s)                      # choice made on the batch
+    dup = ref.split_weights(W, layer.C, layer.g, L.s, mode=ref.MODE_DUP, split_src=sel["split_src"])
+    Xq_ref, sx_ref, _ = ref.split_act(X, layer.C, layer.g, sel["chan_src"], sel["chan_depth"], L.s,
+                                      layer.bits_x, ldq=L.ldq)
+    Wq_ref, sw_ref = ref.quantize(dup["T_out"], layer.bits_w, ldq=L.ldq)
+    assert sel["chan_depth"].max() >= 1 and sx_ref[0] < np.abs(X).max()     # outliers were split
+    assert np.array_equal(host(L.split_src)[:L.s], sel["split_src"])
+    assert np.array_equal(host(L.chan_src), sel["chan_src"])
+    assert np.array_equal(host(L.chan_depth), sel["chan_depth"])
+    assert np.array_equal(host(L.scale_x), sx_ref) and np.array_equal(host(L.scale_w), sw_ref)
+    assert np.array_equal(host(L.Xq[:layer.M]), Xq_ref)
+    assert np.array_equal(host(L.Wq), Wq_ref)
+    acc_ref, y_ref = ref.qgemm(Xq_ref, Wq_ref, L.Ke, sx_ref[1], sw_ref[1])
+    assert np.array_equal(host(acc), acc_ref)
+    assert_y_close(host(Y), y_ref)
+
+
+# ---- config 2: the 3x3 convolution as an im2col GEMM, full size, every row ----------------------
+
+def test_config2_full_size():
+    (layer,) = wl.config(2)
+    run_layer(layer, dynamic=True, static_threshold=5.5)
+
+
+# ---- config 3: 1x1 convolutions, three expand ratios, 6-bit weights -------------------------------
+
+@pytest.mark.parametrize("idx", range(9))
+def test_config3(idx):
+    layer = wl.config(3)[idx]
+    run_layer(layer, dynamic=(idx % 3 == 1), static_threshold=5.5)
+
+
+# ---- config 4: LSTM gate GEMMs, 5-bit weights -------------------------------------------------
+
+@pytest.mark.parametrize("idx", range(2))
+def test_config4(idx):
+    layer = wl.config(4)[idx]
+    run_layer(layer, dynamic=True, static_threshold=None)
+
+
+# ---- config 5: ResNet-50-shaped sweep, OCS then clip, 4-bit weights ------------------------------
+
+def _unique(layers):
+    seen = {}
+    for l in layers:
+        seen.setdefault((l.M, l.C, l.g, l.N), l)
+    return list(seen.values())
+
+
+def test_config5_weight_path_all_53_layers():
+    for layer in wl.config(5, batch=1):
+        W = wl.weights(layer)
+        for clip in layer.clip_ratios:
+            check_weight_path(layer, W, clip)
+
+
+@pytest.mark.parametrize("idx", range(20))
+def test_config5_forward_batch32(idx):
+    layer = _unique(wl.config(5, batch=32))[idx]
+    run_layer(layer, clips=(0.9,), dynamic=False, static_threshold=5.0)
+
+
+@pytest.mark.parametrize("name", ["stem_7x7", "s1b0_1x1b", "s4b0_3x3"])
+def test_config5_forward_batch256(name):
+    (layer,) = [l for l in wl.config(5, batch=256) if l.name == name]
+    run_layer(layer, clips=(0.8,), dynamic=False, static_threshold=5.0)

@@ -1,0 +1,208 @@
+"""GPU parity, call by call: every entry point of the C ABI against the CPU oracle on the
+same seeded inputs.  Integer results (codes, split lists, accumulators) must match bit for
+bit; fp32 scales must be identical; dequantized outputs agree within 1e-6 relative."""
+import numpy as np
+import pytest
+
+from oracle import ref
+from paper_1901_09504_amd import binding as B
+
+from gpu_util import (assert_y_close, gpu_qgemm, gpu_quantize, gpu_select, gpu_split_act,
+                      gpu_split_weights, require_gpu)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    require_gpu()
+
+
+def _tensor(rng, rows, cols, kind):
+    if kind == "normal":
+        x = rng.standard_normal((rows, cols)).astype(np.float32)
+    elif kind == "ties":   # multiples of 1/8 up to 16: many exact ties against a power-of-two grid
+        x = (rng.integers(-128, 129, (rows, cols)) / 8.0).astype(np.float32)
+    elif kind == "heavy":
+        x = rng.standard_t(2.0, (rows, cols)).astype(np.float32)
+    elif kind == "zero":
+        x = np.zeros((rows, cols), dtype=np.float32)
+    return x
+
+
+# ---- ocs_quantize -------------------------------------------------------------------------
+
+@pytest.mark.parametrize("rows,cols", [(1, 1), (3, 5), (7, 64), (33, 147), (130, 269), (65, 1000),
+                                       (257, 2304), (19, 4099)])
+@pytest.mark.parametrize("bits", [2, 5, 8])
+def test_quantize_dynamic(rows, cols, bits):
+    rng = np.random.default_rng(rows * 1000 + cols + bits)
+    x = _tensor(rng, rows, cols, "heavy")
+    q_ref, s_ref = ref.quantize(x, bits, ldq=B.ocs_padded_cols(cols))
+    q, s = gpu_quantize(x, bits)
+    assert np.array_equal(s, s_ref)
+    assert np.array_equal(q, q_ref)
+
+
+@pytest.mark.parametrize("kind,threshold,clip", [("ties", 16.0, 1.0), ("ties", 15.0, 1.0), ("normal", None, 0.8),
+                                                  ("normal", 2.5, 1.0), ("zero", None, 1.0), ("zero", 0.0, 1.0),
+                                                  ("heavy", None, 0.3)])
+@pytest.mark.parametrize("bits", [3, 4, 6, 7, 8])
+def test_quantize_thresholds_and_ties(kind, threshold, clip, bits):
+    rng = np.random.default_rng(bits)
+    x = _tensor(rng, 61, 333, kind)
+    q_ref, s_ref = ref.quantize(x, bits, threshold=threshold, clip_ratio=clip, ldq=B.ocs_padded_cols(333))
+    q, s = gpu_quantize(x, bits, threshold=threshold, clip_ratio=clip)
+    assert np.array_equal(s, s_ref)
+    assert np.array_equal(q, q_ref)
+
+
+@pytest.mark.parametrize("ld_extra,misalign", [(0, True), (1, False), (3, True), (4, False)])
+def test_quantize_unaligned_inputs(ld_extra, misalign):
+    rng = np.random.default_rng(5)
+    x = _tensor(rng, 45, 300, "normal")
+    q_ref, s_ref = ref.quantize(x, 8, ldq=B.ocs_padded_cols(300))
+    q, s = gpu_quantize(x, 8, ld_extra=ld_extra, misalign=misalign)
+    assert np.array_equal(s, s_ref) and np.array_equal(q, q_ref)
+
+
+def test_quantize_scalar_sequence_sweep():
+    # the arithmetic contract itself: many thresholds, values straddling every rounding boundary
+    rng = np.random.default_rng(77)
+    for bits in (4, 8):
+        qmax = 2 ** (bits - 1) - 1
+        for T in rng.uniform(0.01, 50.0, 12).astype(np.float32):
+            step = np.float32(T) / np.float32(qmax)
+            k = rng.integers(-qmax - 2, qmax + 2, (64, 256))
+            x = ((k + 0.5) * step).astype(np.float32)
+            x = np.nextafter(x, rng.choice([-np.inf, np.inf], x.shape).astype(np.float32))
+            x[::2] = ((k[::2] + 0.5) * step).astype(np.float32)
+            q_ref, s_ref = ref.quantize(x, bits, threshold=float(T))
+            q, s = gpu_quantize(x, bits, threshold=float(T))
+            assert np.array_equal(s, s_ref)
+            assert np.array_equal(q[:, :256], q_ref)
+
+
+def test_quantize_denormals():
+    x = np.array([[1e-40, -3e-39, 1e-38, 0.0, 5e-45, -1.4e-45, 2e-38, 1.1754944e-38]], dtype=np.float32)
+    q_ref, s_ref = ref.quantize(x, 8, ldq=64)
+    q, s = gpu_quantize(x, 8)
+    assert np.array_equal(s, s_ref) and np.array_equal(q, q_ref)
+
+
+# ---- ocs_select_channels ---------------------------------------------------------------------
+
+@pytest.mark.parametrize("rows,C,g,s", [(5, 4, 1, 4), (9, 16, 4, 7), (64, 256, 1, 13), (33, 256, 9, 6),
+                                        (17, 300, 3, 120), (40, 1024, 1, 103), (12, 2048, 1, 205),
+                                        (8, 3000, 1, 150), (3, 1, 2, 5), (6, 7, 1, 0)])
+@pytest.mark.parametrize("kind", ["heavy", "ties", "zero"])
+def test_select_channels(rows, C, g, s, kind):
+    rng = np.random.default_rng(rows + C + g + s)
+    T = _tensor(rng, rows, C * g, kind)
+    exp = ref.split_weights(T, C, g, s)
+    got = gpu_select(T, C, g, s)
+    assert np.array_equal(got["split_src"], exp["split_src"])
+    assert np.array_equal(got["chan_src"], exp["chan_src"])
+    assert np.array_equal(got["chan_depth"], exp["chan_depth"])
+    assert got["max"] == exp["max"]
+
+
+def test_select_resplits_one_dominant_channel():
+    rng = np.random.default_rng(2)
+    T = rng.standard_normal((10, 12)).astype(np.float32)
+    T[4, 7] = 1000.0
+    exp = ref.split_weights(T, 12, 1, 9)
+    got = gpu_select(T, 12, 1, 9)
+    assert exp["chan_depth"].max() >= 3
+    for k in ("split_src", "chan_src", "chan_depth"):
+        assert np.array_equal(got[k], exp[k])
+
+
+# ---- ocs_split_weights -----------------------------------------------------------------------
+
+@pytest.mark.parametrize("N,C,g,s", [(7, 12, 1, 5), (40, 64, 9, 4), (256, 256, 1, 13), (100, 37, 4, 6),
+                                     (64, 3, 49, 1), (33, 130, 1, 0)])
+@pytest.mark.parametrize("bits,clip", [(8, 1.0), (4, 0.8)])
+def test_split_weights_halve(N, C, g, s, bits, clip):
+    rng = np.random.default_rng(N + C + g + s)
+    W = (_tensor(rng, N, C * g, "heavy") * 0.05).astype(np.float32)
+    exp = ref.split_weights(W, C, g, s)
+    got = gpu_split_weights(W, C, g, s, bits=bits, clip_ratio=clip)
+    for k in ("split_src", "chan_src", "chan_depth"):
+        assert np.array_equal(got[k], exp[k]), k
+    assert np.array_equal(got["T_out"], exp["T_out"])
+    assert got["max"] == exp["max"]
+    q_ref, s_ref = ref.quantize(exp["T_out"], bits, clip_ratio=clip, ldq=B.ocs_padded_cols((C + s) * g))
+    assert np.array_equal(got["scale"], s_ref)
+    assert np.array_equal(got["Wq"], q_ref)
+
+
+def test_split_weights_dup_mode():
+    rng = np.random.default_rng(8)
+    N, C, g, s = 30, 20, 4, 6
+    W = _tensor(rng, N, C * g, "normal")
+    split_src = np.array([3, 3, 20, 7, 0, 23], dtype=np.int32)   # includes copies of copies
+    exp = ref.split_weights(W, C, g, s, mode=ref.MODE_DUP, split_src=split_src)
+    got = gpu_split_weights(W, C, g, s, mode=B.MODE_DUP, split_src=split_src, bits=6)
+    assert np.array_equal(got["chan_src"], exp["chan_src"])
+    assert np.array_equal(got["chan_depth"], exp["chan_depth"])
+    assert np.array_equal(got["T_out"], exp["T_out"])
+    assert got["max"] == exp["max"]
+    q_ref, s_ref = ref.quantize(exp["T_out"], 6, ldq=B.ocs_padded_cols((C + s) * g))
+    assert np.array_equal(got["scale"], s_ref) and np.array_equal(got["Wq"], q_ref)
+
+
+# ---- ocs_split_act ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("M,C,g,s", [(5, 8, 1, 3), (70, 64, 9, 4), (129, 256, 1, 13), (33, 37, 4, 6),
+                                     (300, 3, 49, 1), (64, 500, 1, 25), (17, 20, 3, 0)])
+@pytest.mark.parametrize("halve", [False, True])
+@pytest.mark.parametrize("threshold", [None, 3.0])
+def test_split_act(M, C, g, s, halve, threshold):
+    rng = np.random.default_rng(M + C + g + s)
+    X = _tensor(rng, M, C * g, "heavy")
+    sel = ref.split_weights(X if halve else _tensor(rng, 9, C * g, "heavy"), C, g, s)
+    cs, cd = sel["chan_src"], (sel["chan_depth"] if halve else None)
+    ldq = B.ocs_padded_cols((C + s) * g)
+    q_ref, s_ref, _ = ref.split_act(X, C, g, cs, cd, s, 8, threshold=threshold, clip_ratio=0.9, ldq=ldq)
+    q, sc = gpu_split_act(X, C, g, cs, cd, s, 8, threshold=threshold, clip_ratio=0.9)
+    assert np.array_equal(sc, s_ref)
+    assert np.array_equal(q, q_ref)
+
+
+# ---- ocs_qgemm -------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("tile", [0, 1, 2])
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (64, 256, 269), (130, 70, 64), (257, 129, 200), (700, 300, 1035),
+                                   (300, 520, 2358), (128, 128, 4842)])
+def test_qgemm(tile, M, N, K):
+    rng = np.random.default_rng(M + N + K)
+    ld = B.ocs_padded_cols(K)
+    Xq = np.zeros((M, ld), dtype=np.int8)
+    Wq = np.zeros((N, ld), dtype=np.int8)
+    Xq[:, :K] = rng.integers(-127, 128, (M, K))
+    Wq[:, :K] = rng.integers(-127, 128, (N, K))
+    sx = np.array([3.0, 3.0 / 127], dtype=np.float32)
+    sw = np.array([0.7, 0.7 / 127], dtype=np.float32)
+    acc_ref, y_ref = ref.qgemm(Xq, Wq, K, sx[1], sw[1])
+    B.ocs_tune("gemm_tile", tile)
+    try:
+        acc, Y = gpu_qgemm(Xq, Wq, K, sx, sw)
+        _, Y2 = gpu_qgemm(Xq, Wq, K, sx, sw, want_acc=False)
+    finally:
+        B.ocs_tune("gemm_tile", -1)
+    assert np.array_equal(acc, acc_ref)
+    assert_y_close(Y, y_ref)
+    assert np.array_equal(Y, Y2)
+
+
+def test_qgemm_extreme_codes_do_not_overflow():
+    K = 4096
+    Xq = np.full((40, K), 127, dtype=np.int8)
+    Wq = np.full((50, K), -127, dtype=np.int8)
+    Wq[::2] = 127
+    sx = np.array([1.0, 1.0 / 127], dtype=np.float32)
+    acc_ref, y_ref = ref.qgemm(Xq, Wq, K, sx[1], sx[1])
+    acc, Y = gpu_qgemm(Xq, Wq, K, sx, sx)
+    assert np.array_equal(acc, acc_ref)
+    assert_y_close(Y, y_ref)

@@ -295,6 +295,18 @@ def test_zero_tensor_and_padding():
     assert not q[:, 5:].any() and q[:, :5].any()
 
 
+def test_tiny_threshold_keeps_zero_on_the_grid():
+    # Eq. 1 maps 0 to the grid point 0 whatever the range; a range so small that qmax / T
+    # overflows fp32 must not turn 0 into something else
+    x = np.array([[1e-40, -3e-39, 0.0, 2e-38, -2e-38, 5e-45]], dtype=np.float32)
+    q, sc = ref.quantize(x, 8)
+    assert sc[0] == np.float32(2e-38)
+    assert q[0, 2] == 0
+    # the saturated factor keeps signs, order and range, although the grid is no longer spanned
+    assert np.all(q[0].astype(np.int32) * np.sign(x[0]) >= 0)
+    assert q[0, 3] == -q[0, 4] == q.max() and q[0, 1] < 0 <= q[0, 0] <= q[0, 3] <= 127
+
+
 # ---- Sec. 3.3: the naive split's worked example --------------------------------------------
 
 def test_naive_split_w3_example():
