@@ -1,0 +1,162 @@
+#!/usr/bin/env python3
+"""Benchmark of the OCS-expanded quantized layer on one MI355X.
+
+A step is one pass of the whole hot path over one batch of the ResNet-style 3x3 convolution
+(batch 64, 256->256 channels, 14x14, lowered by im2col: M=12544, K=2304, N=256, r=0.02,
+8-bit weights and activations):
+
+    ocs_split_weights   channel maxima of W, greedy selection, halve + quantize     (W1-W3)
+    ocs_act_threshold   max|X| for the per-batch activation grid                     (X1)
+    ocs_split_act       duplicate the chosen channels, quantize, pack               (X2)
+    ocs_qgemm           int8 MFMA GEMM over the expanded K, dequantizing epilogue   (G1, G2)
+
+Inputs are resident in HBM before the timed region.  The activations rotate through several
+copies so that no step finds its input in the 256 MB Infinity Cache.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
+METRIC = "expanded int8 GEMM TOPS (% MFMA peak); split+quantize GB/s (% HBM)"
+
+
+def cpu_baseline(layer, W, X, reps=3):
+    """The CPU oracle, as it stands, on the same workload on this machine's host cores."""
+    from oracle import ref
+
+    s = ref.num_splits(layer.C, layer.r)
+    Ke = (layer.C + s) * layer.g
+    ldq = (Ke + 63) // 64 * 64
+    best = None
+    for _ in range(reps):
+        t0 = time.perf_counter()
+        sp = ref.split_weights(W, layer.C, layer.g, s)
+        Wq, sw = ref.quantize(sp["T_out"], layer.bits_w, ldq=ldq)
+        Xq, sx, _ = ref.split_act(X, layer.C, layer.g, sp["chan_src"], None, s, layer.bits_x, ldq=ldq)
+        ref.qgemm(Xq, Wq, Ke, sx[1], sw[1], want_acc=False)
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+    tops = 2.0 * X.shape[0] * layer.N * Ke / best / 1e12
+    return {"value": tops, "unit": "TOPS", "cores": ref.get_threads(), "kind": "oracle",
+            "sample": f"whole step on all {X.shape[0]} rows of the workload, best of {reps}",
+            "seconds_per_step": best}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--copies", type=int, default=6, help="rotating copies of X (6 x 115.6 MB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_1901_09504_amd import binding as B
+    from paper_1901_09504_amd import workloads as wl
+    from paper_1901_09504_amd.layer import ExpandedLayer
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    B.lib()  # fails loudly when libocs.so is missing
+
+    (layer,) = wl.config(2)
+    M, N, K = layer.M, layer.N, layer.K
+    W = wl.weights(layer)
+    X = wl.activations(layer)
+    Wd = torch.from_numpy(W).cuda()
+    Xd = [torch.from_numpy(X).cuda() for _ in range(max(1, args.copies))]
+    L = ExpandedLayer(N, layer.C, layer.g, layer.r, layer.bits_w, layer.bits_x, max_rows=M)
+    Ke, ldq = L.Ke, L.ldq
+    stream = torch.cuda.current_stream()
+
+    def step(i, ev=None):
+        x = Xd[i % len(Xd)]
+        if ev: ev[0].record(stream)
+        L.prepare_weights(Wd)
+        if ev: ev[1].record(stream)
+        B.ocs_act_threshold(x, M, L.C, L.g, K, L.chan_src, None, L.s, L.bits_x, 1.0, L.scale_x, L.ws_x)
+        if ev: ev[2].record(stream)
+        B.ocs_split_act(x, M, L.C, L.g, K, L.chan_src, None, L.s, L.bits_x, L.scale_x, 1.0, L.Xq, ldq,
+                        L.scale_x, L.ws_x)
+        if ev: ev[3].record(stream)
+        L.qgemm(M)
+        if ev: ev[4].record(stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, events[i])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    ms_per_step = dt / args.steps * 1e3
+    phase = np.array([[e[k].elapsed_time(e[k + 1]) for k in range(4)] for e in events])  # ms
+    avg = phase.mean(axis=0)
+    names = ["split_weights", "act_threshold", "split_act", "qgemm"]
+
+    ops = 2.0 * M * N * Ke
+    x2_bytes = 4.0 * M * K + 1.0 * M * Ke                       # X2: read fp32 X, write codes
+    x1_bytes = 4.0 * M * K
+    w_bytes = 8.0 * N * K + 1.0 * N * Ke                        # W1 + W3
+    gemm_bytes = 1.0 * M * Ke + 1.0 * N * Ke + 4.0 * M * N
+    x2_gbs = x2_bytes / (avg[2] * 1e-3) / 1e9
+    gemm_tops = ops / (avg[3] * 1e-3) / 1e12
+    gemm_ai = ops / gemm_bytes
+    gemm_roof_tops = min(INT8_PEAK_TOPS, gemm_ai * HBM_PEAK_GBS / 1e3)
+
+    out = {
+        "metric": METRIC,
+        "value": ops / (ms_per_step * 1e-3) / 1e12,
+        "unit": "TOPS (2*M*N*K' of the expanded layer per second of whole-step time)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8 codes x int8 codes -> int32 (fp32 in, fp32 out)", "data": "synthetic",
+        "config": {"workload": "configs[1]: 3x3 conv 256->256, 14x14, batch 64 as im2col GEMM "
+                               f"M={M} K={K} N={N}, r={layer.r} (s={L.s}, K'={Ke}, padded {ldq}), "
+                               "8-bit weights and activations, weight OCS, per-batch activation grid",
+                   "x_copies_rotated": len(Xd)},
+        "gemm_tops": gemm_tops, "gemm_pct_mfma_peak": 100.0 * gemm_tops / INT8_PEAK_TOPS,
+        "split_quant_gbps": x2_gbs, "split_quant_pct_hbm": 100.0 * x2_gbs / HBM_PEAK_GBS,
+        "roofline": {"kernel": "expand_quantize_kernel (ocs_split_act, X2)", "bound": "hbm",
+                     "achieved": x2_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": x2_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": x2_bytes, "avg_launch_us": avg[2] * 1e3},
+        "phases": {n: {"avg_us": float(avg[k] * 1e3)} for k, n in enumerate(names)},
+    }
+    out["phases"]["split_weights"]["algorithmic_GBps"] = w_bytes / (avg[0] * 1e-3) / 1e9
+    out["phases"]["act_threshold"]["algorithmic_GBps"] = x1_bytes / (avg[1] * 1e-3) / 1e9
+    out["phases"]["split_act"]["algorithmic_GBps"] = x2_gbs
+    out["phases"]["qgemm"].update({
+        "tops": gemm_tops, "algorithmic_GBps": gemm_bytes / (avg[3] * 1e-3) / 1e9,
+        "arithmetic_intensity_op_per_byte": gemm_ai,
+        "regime": "hbm" if gemm_ai < INT8_PEAK_TOPS * 1e3 / HBM_PEAK_GBS else "mfma",
+        "roof_tops_min_mfma_hbm": gemm_roof_tops, "frac_of_that_roof": gemm_tops / gemm_roof_tops})
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(layer, W, X)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -154,6 +154,17 @@ int ocs_split_act(const float *X, int64_t M, int C, int g, int64_t ldx, const in
                   size_t ws_bytes, void *stream);
 
 /*
+ * The dynamic threshold of ocs_split_act on its own (Eq. 1's max|x| over the expanded
+ * activations, times clip_ratio): scale_out device float[2] = {T, T / qmax}.  Calling this
+ * and then ocs_split_act with threshold = scale_out is what ocs_split_act does by itself
+ * when its threshold is NULL; the split lets a caller reuse one threshold for several
+ * batches, or time the two passes separately.
+ */
+int ocs_act_threshold(const float *X, int64_t M, int C, int g, int64_t ldx, const int32_t *chan_src,
+                      const int32_t *chan_depth, int num_splits, int bits, float clip_ratio,
+                      float *scale_out, void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * The expanded layer of Eq. 2 on integer codes, then the trailing factors of Eq. 1:
  *   acc[i,n] = sum_{k < Kexp} Xq[i,k] * Wq[n,k]   (int8 x int8 -> int32, exact)
  *   Y[i,n]   = float(acc[i,n]) * (scale_x[1] * scale_w[1])
@@ -170,7 +181,7 @@ int ocs_qgemm(const int8_t *Xq, int64_t ldx, const int8_t *Wq, int64_t ldw, int6
 
 /*
  * Launch-shape overrides for benchmarking (no passage of the paper; results never depend
- * on them).  key: "act_rows_per_block", "gemm_tile" ...; value < 0 restores the default.
+ * on them).  key: "act_grid", "act_nt", "gemm_tile"; value < 0 restores the default.
  * Returns OCS_OK or OCS_E_MODE for an unknown key.  Not thread-safe.
  */
 int ocs_tune(const char *key, int value);

@@ -60,6 +60,8 @@ def lib():
     L.ocs_split_act.restype = _i32
     L.ocs_split_act.argtypes = [_vp, _i64, _i32, _i32, _i64, _vp, _vp, _i32, _i32, _vp, _f32, _vp, _i64,
                                 _vp, _vp, _sz, _vp]
+    L.ocs_act_threshold.restype = _i32
+    L.ocs_act_threshold.argtypes = [_vp, _i64, _i32, _i32, _i64, _vp, _vp, _i32, _i32, _f32, _vp, _vp, _sz, _vp]
     L.ocs_qgemm.restype = _i32
     L.ocs_qgemm.argtypes = [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _vp, _vp, _vp, _i64, _vp,
                             _i64, _vp, _sz, _vp]
@@ -145,6 +147,14 @@ def ocs_split_act(X, M, Cn, g, ldx, chan_src, chan_depth, num_splits, bits, thre
     _check(lib().ocs_split_act(_ptr(X), M, Cn, g, ldx, _ptr(chan_src), _ptr(chan_depth), num_splits,
                                bits, _ptr(threshold), clip_ratio, _ptr(Xq), ldq, _ptr(scale_out), w,
                                wb, _stream(stream)), "ocs_split_act")
+
+
+def ocs_act_threshold(X, M, Cn, g, ldx, chan_src, chan_depth, num_splits, bits, clip_ratio, scale_out,
+                      workspace, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib().ocs_act_threshold(_ptr(X), M, Cn, g, ldx, _ptr(chan_src), _ptr(chan_depth),
+                                   num_splits, bits, clip_ratio, _ptr(scale_out), w, wb,
+                                   _stream(stream)), "ocs_act_threshold")
 
 
 def ocs_qgemm(Xq, ldx, Wq, ldw, M, N, Kexp, bits_x, bits_w, scale_x, scale_w, acc_out, ldacc, Y, ldy,

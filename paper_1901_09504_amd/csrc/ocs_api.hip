@@ -191,6 +191,30 @@ int ocs_quantize(const float* x, int64_t rows, int64_t cols, int64_t ldx, int bi
     return OCS_OK;
 }
 
+int ocs_act_threshold(const float* X, int64_t M, int C, int g, int64_t ldx, const int32_t* chan_src,
+                      const int32_t* chan_depth, int num_splits, int bits, float clip_ratio,
+                      float* scale_out, void* workspace, size_t ws_bytes, void* stream) {
+    if (!X || !scale_out || (num_splits > 0 && !chan_src)) return OCS_E_NULL;
+    int rc = check_layer(M, C, g, ldx, num_splits);
+    if (rc) return rc;
+    if (!bits_ok(bits)) return OCS_E_BITS;
+    const int64_t K = (int64_t)C * g;
+    rc = check_workspace(workspace, ws_bytes, M, K);
+    if (rc) return rc;
+    // X1: column maxima of X, then the maximum over the expanded channels
+    Workspace w = plan_workspace(M, K);
+    char* base = static_cast<char*>(workspace);
+    float* colmax = reinterpret_cast<float*>(base + w.colmax_off);
+    float* partial = reinterpret_cast<float*>(base + w.partial_off);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = launch_colmax(X, M, K, ldx, colmax, partial, st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = launch_threshold(colmax, C, g, num_splits, chan_src, chan_depth, clip_ratio, qmax_of(bits),
+                         scale_out, st);
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
 int ocs_split_act(const float* X, int64_t M, int C, int g, int64_t ldx, const int32_t* chan_src,
                   const int32_t* chan_depth, int num_splits, int bits, const float* threshold,
                   float clip_ratio, int8_t* Xq, int64_t ldq, float* scale_out, void* workspace,
@@ -198,33 +222,24 @@ int ocs_split_act(const float* X, int64_t M, int C, int g, int64_t ldx, const in
     if (!X || !Xq || !scale_out || (num_splits > 0 && !chan_src)) return OCS_E_NULL;
     int rc = check_layer(M, C, g, ldx, num_splits);
     if (rc) return rc;
-    const int64_t K = (int64_t)C * g, Ke = (int64_t)(C + num_splits) * g;
+    const int64_t Ke = (int64_t)(C + num_splits) * g;
     rc = check_codes(Xq, ldq, Ke);
     if (rc) return rc;
     if (!bits_ok(bits)) return OCS_E_BITS;
     const float qmax = qmax_of(bits);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipError_t e;
     if (threshold == nullptr) {
         // X1: the dynamic grid needs max|expanded activations| before the streaming pass
-        rc = check_workspace(workspace, ws_bytes, M, K);
+        rc = ocs_act_threshold(X, M, C, g, ldx, chan_src, chan_depth, num_splits, bits, clip_ratio,
+                               scale_out, workspace, ws_bytes, stream);
         if (rc) return rc;
-        Workspace w = plan_workspace(M, K);
-        char* base = static_cast<char*>(workspace);
-        float* colmax = reinterpret_cast<float*>(base + w.colmax_off);
-        float* partial = reinterpret_cast<float*>(base + w.partial_off);
-        e = launch_colmax(X, M, K, ldx, colmax, partial, st);
-        if (e != hipSuccess) return hip_fail(e);
-        e = launch_threshold(colmax, C, g, num_splits, chan_src, chan_depth, clip_ratio, qmax,
-                             scale_out, st);
-        if (e != hipSuccess) return hip_fail(e);
-        e = launch_expand_quantize(X, ldx, M, C, g, num_splits, chan_src, chan_depth, scale_out,
-                                   qmax, Xq, ldq, nullptr, st);
-    } else {
-        // X2 alone: one pass
-        e = launch_expand_quantize(X, ldx, M, C, g, num_splits, chan_src, chan_depth, threshold,
-                                   qmax, Xq, ldq, scale_out, st);
+        threshold = scale_out;
     }
+    // X2: one streaming pass.  When the threshold already lives in scale_out the kernel must
+    // not rewrite it while other lanes read it.
+    hipError_t e = launch_expand_quantize(X, ldx, M, C, g, num_splits, chan_src, chan_depth,
+                                          threshold, qmax, Xq, ldq,
+                                          threshold == scale_out ? nullptr : scale_out, st);
     if (e != hipSuccess) return hip_fail(e);
     return OCS_OK;
 }
@@ -254,8 +269,8 @@ int ocs_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int6
 int ocs_tune(const char* key, int value) {
     if (!key) return OCS_E_NULL;
     Tuning& t = tuning();
-    if (!strcmp(key, "act_rows_per_block")) t.act_rows_per_block = value;
-    else if (!strcmp(key, "act_tx")) t.act_tx = value;
+    if (!strcmp(key, "act_grid")) t.act_grid = value;
+    else if (!strcmp(key, "act_nt")) t.act_nt = value < 0 ? 0 : value;
     else if (!strcmp(key, "gemm_tile")) t.gemm_tile = value;
     else return OCS_E_MODE;
     return OCS_OK;

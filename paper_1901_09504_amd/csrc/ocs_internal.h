@@ -78,8 +78,8 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
 
 // Launch-shape overrides (benchmarking only); < 0 means "use the default".
 struct Tuning {
-    int act_rows_per_block = -1;
-    int act_tx = -1;
+    int act_grid = -1;  // workgroups of the split+quantize pass
+    int act_nt = 0;     // non-temporal loads of X in that pass (off: appended columns re-read X through L2)
     int gemm_tile = -1;
 };
 Tuning& tuning();

@@ -12,16 +12,22 @@
 
 namespace ocs {
 
-// One value onto the grid: one fp32 multiply by qmax/T, round half to even, saturate.
-__device__ __forceinline__ int code_of(float v, float inv_step, float qmax) {
-    float r = __builtin_rintf(v * inv_step);
-    r = __builtin_fminf(__builtin_fmaxf(r, -qmax), qmax);
-    return (int)r;
+// One value onto the grid: one fp32 multiply by qmax/T, saturate, round half to even.
+// Saturating before rounding gives the same code as rounding first because qmax is an
+// integer.  Adding 1.5 * 2^23 rounds |p| <= 127 to an integer under the default rounding mode
+// (the sum's ulp is 1) and leaves that integer, in two's complement, in the low mantissa
+// bits: the low byte of the sum's bit pattern is the int8 code.
+__device__ __forceinline__ unsigned code_bits(float v, float inv_step, float qmax) {
+    float p = v * inv_step;
+    p = __builtin_amdgcn_fmed3f(p, -qmax, qmax);
+    return __float_as_uint(p + 12582912.0f);
 }
 
-__device__ __forceinline__ unsigned pack4(int a, int b, int c, int d) {
-    return (unsigned)(a & 0xFF) | ((unsigned)(b & 0xFF) << 8) | ((unsigned)(c & 0xFF) << 16) |
-           ((unsigned)d << 24);
+// low bytes of four words -> one dword (a in byte 0)
+__device__ __forceinline__ unsigned pack4(unsigned a, unsigned b, unsigned c, unsigned d) {
+    unsigned lo = __builtin_amdgcn_perm(b, a, 0x0c0c0400u);  // {a.b0, b.b0, 0, 0}
+    unsigned hi = __builtin_amdgcn_perm(d, c, 0x04000c0cu);  // {0, 0, c.b0, d.b0}
+    return lo | hi;
 }
 
 // qmax / T as one correctly rounded division, kept finite so that 0 * inv_step stays 0.
@@ -30,36 +36,102 @@ __device__ __forceinline__ float inv_step_of(float T, float qmax) {
     return __builtin_fminf(__fdiv_rn(qmax, T), 3.402823466e+38f);
 }
 
-// Workgroup (TX, TY): TY rows at a time, lane tx walks the packed dwords of a row with
-// stride TX.  main_units = number of leading dwords whose four inputs are the contiguous,
-// 16-byte aligned X[r, 4d .. 4d+3] (0 when X does not allow vector loads).
-template <bool HALVE>
+template <bool NT>
+__device__ __forceinline__ f32x4 load4(const f32x4* p) {
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
+
+// One lane per packed output dword, the whole output walked as ONE flat range with a grid
+// stride: lane i of the grid produces dwords i, i + G, i + 2G, ...  Consecutive lanes read
+// consecutive 16-byte groups of X and write consecutive dwords of Xq, and at any moment the
+// whole chip works inside one compact window that slides over X front to back, which is the
+// access pattern HBM serves fastest (measured against row-per-wave and row-per-workgroup
+// layouts with LDS staging of the appended columns; those were 10-15 % slower).
+//   d <  main_units: the dword's four inputs are the contiguous, 16-byte aligned
+//                    X[r, 4d .. 4d+3] (main_units = 0 when X does not allow vector loads);
+//   d >= main_units: leftover columns, appended channels (their source values were fetched
+//                    moments ago by neighbouring lanes, so the re-read is served by the
+//                    caches, not by HBM) and the zero padding.
+constexpr int kTailTable = 2048;  // appended + padded columns whose sources are kept in LDS
+
+template <bool HALVE, bool NT, typename Index>
 __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
     const float* __restrict__ X, int64_t ldx, int64_t M, int C, int g, int s,
     const int32_t* __restrict__ chan_src, const int32_t* __restrict__ chan_depth,
-    const float* thr, float qmax, int8_t* __restrict__ Xq, int64_t ldq, int main_units,
-    int rows_per_block, float* scale_out) {
-    const int tx = threadIdx.x, ty = threadIdx.y, TX = blockDim.x, TY = blockDim.y;
+    const float* thr, float qmax, int8_t* __restrict__ Xq, int D, int main_units,
+    float* scale_out) {
+    // Source column (or -1 for padding) and halving depth of every column past the vector
+    // region.  They do not depend on the row, so each workgroup resolves them once; a lane that
+    // lands on such a column then needs a single trip to memory, like every other lane.
+    __shared__ int tail_col[kTailTable];
+    __shared__ int tail_dep[HALVE ? kTailTable : 1];
+    const int Ke = (C + s) * g;
+    const int tail0 = 4 * main_units;              // first column of the gather region
+    const int tail_n = 4 * D - tail0;              // columns in it (appended, leftover, padding)
+    const bool use_table = tail_n <= kTailTable;
+    if (use_table) {
+        for (int e = threadIdx.x; e < tail_n; e += kThreads) {
+            const int k = tail0 + e;
+            int col = -1, dep = 0;
+            if (k < Ke) {
+                const int j = k / g, t = k - j * g;
+                int src = chan_src ? chan_src[j] : j;
+                src = src < 0 ? 0 : (src >= C ? C - 1 : src);
+                col = src * g + t;
+                if (HALVE) dep = chan_depth[j];
+            }
+            tail_col[e] = col;
+            if (HALVE) tail_dep[e] = dep;
+        }
+    }
+    const Index total = (Index)M * (Index)D;
+    const Index stride = (Index)gridDim.x * kThreads;
+    unsigned* __restrict__ out = reinterpret_cast<unsigned*>(Xq);
+
+    // position of output dword o, and its 16-byte input when it lies in the vector region
+    auto locate = [&](Index o, int64_t& row, int& d) {
+        const Index r = o / (Index)D;
+        row = (int64_t)r;
+        d = (int)(o - r * (Index)D);
+    };
+    auto fetch = [&](Index o, f32x4& v) {
+        if (o < total) {
+            int64_t row;
+            int d;
+            locate(o, row, d);
+            if (d < main_units) v = load4<NT>(reinterpret_cast<const f32x4*>(X + row * ldx) + d);
+        }
+    };
+
+    // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Renumber them
+    // so that neighbouring 1 KB pieces of a row are read through the same L2: the lanes that
+    // gather appended columns then find their source values in that L2 instead of asking
+    // HBM for the line a second time.
+    const unsigned nwg = gridDim.x, xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    const unsigned vwg = xcd * (nwg / 8) + (xcd < nwg % 8 ? xcd : nwg % 8) + slot;
+
+    // the first input is requested before anything waits on the threshold
+    Index o = (Index)vwg * kThreads + threadIdx.x;
+    f32x4 cur = {}, nxt = {};
+    fetch(o, cur);
     const float T = *thr;
     const float inv = inv_step_of(T, qmax);
-    if (scale_out != nullptr && blockIdx.x == 0 && tx == 0 && ty == 0) {
+    if (scale_out != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
         scale_out[0] = T;
         scale_out[1] = T / qmax;
     }
-    const int D = (int)(ldq >> 2);
-    const int Ke = (C + s) * g;
-    const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
-    int64_t r1 = r0 + rows_per_block;
-    if (r1 > M) r1 = M;
+    __syncthreads();
 
-    for (int64_t r = r0 + ty; r < r1; r += TY) {
-        const float* xrow = X + r * ldx;
-        unsigned* qrow = reinterpret_cast<unsigned*>(Xq + r * ldq);
-
-        // identity region: columns below C*g sit where they were
-#pragma unroll 4
-        for (int d = tx; d < main_units; d += TX) {
-            f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(xrow) + d);
+    for (; o < total; o += stride) {
+        fetch(o + stride, nxt);  // next trip's input is in flight while this one is processed
+        int64_t row;
+        int d;
+        locate(o, row, d);
+        const float* xrow = X + row * ldx;
+        unsigned q;
+        if (d < main_units) {
+            f32x4 v = cur;
             if (HALVE) {
                 int j = (4 * d) / g, t = 4 * d - j * g;
 #pragma unroll
@@ -68,30 +140,44 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
                     if (++t == g) { t = 0; ++j; }
                 }
             }
-            qrow[d] = pack4(code_of(v[0], inv, qmax), code_of(v[1], inv, qmax),
-                            code_of(v[2], inv, qmax), code_of(v[3], inv, qmax));
-        }
-
-        // gather region: leftover columns, the appended channels, and the zero padding
-        for (int d = main_units + tx; d < D; d += TX) {
-            int code[4];
-            int k = 4 * d;
-            int j = k / g, t = k - j * g;
+            q = pack4(code_bits(v[0], inv, qmax), code_bits(v[1], inv, qmax),
+                      code_bits(v[2], inv, qmax), code_bits(v[3], inv, qmax));
+        } else {
+            float v[4];
+            int dep[4];
+            const int e0 = 4 * (d - main_units);
+            if (use_table) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                int c = 0;
-                if (k + e < Ke) {
-                    int src = chan_src ? chan_src[j] : j;
-                    src = src < 0 ? 0 : (src >= C ? C - 1 : src);
-                    float v = xrow[(int64_t)src * g + t];
-                    if (HALVE) v = v * ldexpf(1.0f, -chan_depth[j]);
-                    c = code_of(v, inv, qmax);
+                for (int e = 0; e < 4; ++e) {
+                    const int col = tail_col[e0 + e];
+                    dep[e] = HALVE ? tail_dep[e0 + e] : 0;
+                    v[e] = col >= 0 ? xrow[col] : 0.0f;
                 }
-                code[e] = c;
-                if (++t == g) { t = 0; ++j; }
+            } else {
+                const int k = 4 * d;
+                int j = k / g, t = k - j * g;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[e] = 0.0f;
+                    dep[e] = 0;
+                    if (k + e < Ke) {
+                        int src = chan_src ? chan_src[j] : j;
+                        src = src < 0 ? 0 : (src >= C ? C - 1 : src);
+                        v[e] = xrow[(int64_t)src * g + t];
+                        if (HALVE) dep[e] = chan_depth[j];
+                    }
+                    if (++t == g) { t = 0; ++j; }
+                }
             }
-            qrow[d] = pack4(code[0], code[1], code[2], code[3]);
+            if (HALVE) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = v[e] * ldexpf(1.0f, -dep[e]);
+            }
+            q = pack4(code_bits(v[0], inv, qmax), code_bits(v[1], inv, qmax),
+                      code_bits(v[2], inv, qmax), code_bits(v[3], inv, qmax));
         }
+        out[o] = q;
+        cur = nxt;
     }
 }
 
@@ -100,35 +186,29 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
                                   const float* thr, float qmax, int8_t* Xq, int64_t ldq,
                                   float* scale_out, hipStream_t stream) {
     const int64_t K = (int64_t)C * g;
-    bool vec_ok = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 4 == 0);
-    int main_units = vec_ok ? (int)(K / 4) : 0;
+    const bool vec_ok = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 4 == 0);
+    const int main_units = vec_ok ? (int)(K / 4) : 0;
     const int D = (int)(ldq / 4);
+    const int64_t total = M * D;
+    const bool nt = tuning().act_nt != 0;
+    const bool halve = chan_depth != nullptr;
 
-    // lanes along the row: the power of two in {16, 32, 64} that wastes the fewest lanes
-    int tx = 64;
-    int64_t best = -1;
-    for (int cand = 64; cand >= 16; cand >>= 1) {
-        int64_t padded = ceil_div(D, cand) * cand;
-        if (best < 0 || padded < best) { best = padded; tx = cand; }
+    int64_t grid = 256 * 8;  // 8 workgroups of 4 waves on each of the 256 CUs
+    if (tuning().act_grid > 0) grid = tuning().act_grid;
+    if (grid > ceil_div(total, kThreads)) grid = ceil_div(total, kThreads);
+    const bool wide = total + grid * kThreads >= ((int64_t)1 << 32);
+
+#define OCS_LAUNCH_EQ(H, N_, I_)                                                                  \
+    expand_quantize_kernel<H, N_, I_><<<(unsigned)grid, kThreads, 0, stream>>>(                    \
+        X, ldx, M, C, g, s, chan_src, chan_depth, thr, qmax, Xq, D, main_units, scale_out)
+    if (wide) {
+        if (halve) { if (nt) OCS_LAUNCH_EQ(true, true, uint64_t); else OCS_LAUNCH_EQ(true, false, uint64_t); }
+        else       { if (nt) OCS_LAUNCH_EQ(false, true, uint64_t); else OCS_LAUNCH_EQ(false, false, uint64_t); }
+    } else {
+        if (halve) { if (nt) OCS_LAUNCH_EQ(true, true, uint32_t); else OCS_LAUNCH_EQ(true, false, uint32_t); }
+        else       { if (nt) OCS_LAUNCH_EQ(false, true, uint32_t); else OCS_LAUNCH_EQ(false, false, uint32_t); }
     }
-    if (tuning().act_tx > 0) tx = tuning().act_tx;
-    const int ty = kThreads / tx;
-
-    // rows per workgroup: a few passes over TY rows, and enough workgroups to fill the chip
-    int64_t rpb = (int64_t)ty * 2;
-    while (rpb > ty && ceil_div(M, rpb) < 2048) rpb -= ty;
-    if (tuning().act_rows_per_block > 0) rpb = tuning().act_rows_per_block;
-    const int64_t blocks = ceil_div(M, rpb);
-
-    dim3 block(tx, ty);
-    if (chan_depth != nullptr)
-        expand_quantize_kernel<true><<<(unsigned)blocks, block, 0, stream>>>(
-            X, ldx, M, C, g, s, chan_src, chan_depth, thr, qmax, Xq, ldq, main_units, (int)rpb,
-            scale_out);
-    else
-        expand_quantize_kernel<false><<<(unsigned)blocks, block, 0, stream>>>(
-            X, ldx, M, C, g, s, chan_src, chan_depth, thr, qmax, Xq, ldq, main_units, (int)rpb,
-            scale_out);
+#undef OCS_LAUNCH_EQ
     return hipGetLastError();
 }
 

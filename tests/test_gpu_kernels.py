@@ -155,7 +155,8 @@ def test_split_weights_dup_mode():
 # ---- ocs_split_act ---------------------------------------------------------------------------
 
 @pytest.mark.parametrize("M,C,g,s", [(5, 8, 1, 3), (70, 64, 9, 4), (129, 256, 1, 13), (33, 37, 4, 6),
-                                     (300, 3, 49, 1), (64, 500, 1, 25), (17, 20, 3, 0)])
+                                     (300, 3, 49, 1), (64, 500, 1, 25), (17, 20, 3, 0), (1000, 16, 1, 1),
+                                     (77, 2048, 1, 205), (50, 64, 4, 300), (9, 512, 9, 26)])
 @pytest.mark.parametrize("halve", [False, True])
 @pytest.mark.parametrize("threshold", [None, 3.0])
 def test_split_act(M, C, g, s, halve, threshold):
