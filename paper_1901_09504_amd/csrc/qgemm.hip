@@ -25,13 +25,14 @@ __device__ __forceinline__ unsigned xcd_remap(unsigned w, unsigned total) {
     return xcd * q + (xcd < r ? xcd : r) + local;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int P>
 __global__ __launch_bounds__(kThreads) void qgemm_kernel(
     const int8_t* __restrict__ Xq, int64_t ldx, const int8_t* __restrict__ Wq, int64_t ldw, int M,
     int N, int ktiles, const float* __restrict__ scale_x, const float* __restrict__ scale_w,
     int32_t* __restrict__ acc_out, int64_t ldacc, float* __restrict__ Y, int64_t ldy, int tiles_n,
     unsigned total_tiles) {
     static_assert(WAVES_M * WAVES_N == kThreads / 64, "4 waves");
+    static_assert(P % 2 == 0, "the LDS buffer index must be static in the unrolled loop");
     constexpr int BK = 64;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave tile
     constexpr int TM = WM / 32, TN = WN / 32;            // 32x32 MFMA tiles per wave
@@ -70,11 +71,24 @@ __global__ __launch_bounds__(kThreads) void qgemm_kernel(
         b_dst[u] = r * BK + swz(r, c) * 16;
     }
 
-    i32x4 a_reg[A_CHUNKS], b_reg[B_CHUNKS];
+    // P K-steps of both operands are in flight in registers at any time: a workgroup alone
+    // on its CU must cover the whole memory latency with its own outstanding loads.  Loads are
+    // unconditional (the K index is clamped to the last step, whose data is then simply
+    // fetched again) so that the unrolled loop body is straight-line code and the wait before
+    // each LDS write covers only the oldest stage, not every load in flight.
+    i32x4 a_reg[P][A_CHUNKS], b_reg[P][B_CHUNKS];
+    auto fetch = [&](int slot_kt, i32x4 (&ar)[A_CHUNKS], i32x4 (&br)[B_CHUNKS]) {
+        const int kl = slot_kt < ktiles ? slot_kt : ktiles - 1;
+        const int64_t koff = (int64_t)kl * BK;
 #pragma unroll
-    for (int u = 0; u < A_CHUNKS; ++u) a_reg[u] = *reinterpret_cast<const i32x4*>(a_src[u]);
+        for (int u = 0; u < A_CHUNKS; ++u)
+            ar[u] = *reinterpret_cast<const i32x4*>(a_src[u] + koff);
 #pragma unroll
-    for (int u = 0; u < B_CHUNKS; ++u) b_reg[u] = *reinterpret_cast<const i32x4*>(b_src[u]);
+        for (int u = 0; u < B_CHUNKS; ++u)
+            br[u] = *reinterpret_cast<const i32x4*>(b_src[u] + koff);
+    };
+#pragma unroll
+    for (int p = 0; p < P; ++p) fetch(p, a_reg[p], b_reg[p]);
 
     i32x16 acc[TM][TN];
 #pragma unroll
@@ -89,26 +103,19 @@ __global__ __launch_bounds__(kThreads) void qgemm_kernel(
     // consistent whatever order the hardware assigns to them inside the slice.
     const int frag_row = lane & 31, frag_half = lane >> 5;
 
-    for (int kt = 0; kt < ktiles; ++kt) {
-        const int buf = kt & 1;
+    // One K-step: registers -> LDS buffer `buf`, barrier, refill the registers, multiply.
+    // One barrier per step suffices: a wave that arrives at it has finished reading the other
+    // buffer (previous step), so that buffer may be overwritten right after the next barrier.
+    auto step = [&](int buf, i32x4 (&ar)[A_CHUNKS], i32x4 (&br)[B_CHUNKS], int refill_kt,
+                    bool refill) {
 #pragma unroll
         for (int u = 0; u < A_CHUNKS; ++u)
-            *reinterpret_cast<i32x4*>(&lds_a[buf][a_dst[u]]) = a_reg[u];
+            *reinterpret_cast<i32x4*>(&lds_a[buf][a_dst[u]]) = ar[u];
 #pragma unroll
         for (int u = 0; u < B_CHUNKS; ++u)
-            *reinterpret_cast<i32x4*>(&lds_b[buf][b_dst[u]]) = b_reg[u];
+            *reinterpret_cast<i32x4*>(&lds_b[buf][b_dst[u]]) = br[u];
         __syncthreads();
-
-        if (kt + 1 < ktiles) {
-            const int64_t koff = (int64_t)(kt + 1) * BK;
-#pragma unroll
-            for (int u = 0; u < A_CHUNKS; ++u)
-                a_reg[u] = *reinterpret_cast<const i32x4*>(a_src[u] + koff);
-#pragma unroll
-            for (int u = 0; u < B_CHUNKS; ++u)
-                b_reg[u] = *reinterpret_cast<const i32x4*>(b_src[u] + koff);
-        }
-
+        if (refill) fetch(refill_kt, ar, br);
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             i32x4 af[TM], bf[TN];
@@ -128,12 +135,20 @@ __global__ __launch_bounds__(kThreads) void qgemm_kernel(
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0,
+                                                                     0, 0);
         }
-        // the other buffer is free once every wave has finished reading it, which the
-        // barrier of the next iteration (after its writes to the other buffer) guarantees:
-        // buffer `buf` is next written two iterations from now, after that barrier.
+    };
+
+    int kt0 = 0;
+    for (; kt0 + P <= ktiles; kt0 += P) {
+#pragma unroll
+        for (int p = 0; p < P; ++p) step(p & 1, a_reg[p], b_reg[p], kt0 + p + P, true);
     }
+    // the last ktiles % P steps; their data is already in the registers
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+        if (kt0 + p < ktiles) step(p & 1, a_reg[p], b_reg[p], 0, false);
 
     // epilogue: accumulator register v of lane l holds row (v/4)*8 + (l/32)*4 + v%4 and
     // column l%32 of its 32x32 tile
@@ -155,17 +170,19 @@ __global__ __launch_bounds__(kThreads) void qgemm_kernel(
         }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int P>
 static hipError_t run(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
                       int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,
                       int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy, hipStream_t stream) {
     const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
     const int64_t total = tiles_m * tiles_n;
-    qgemm_kernel<BM, BN, WAVES_M, WAVES_N><<<(unsigned)total, kThreads, 0, stream>>>(
+    qgemm_kernel<BM, BN, WAVES_M, WAVES_N, P><<<(unsigned)total, kThreads, 0, stream>>>(
         Xq, ldx, Wq, ldw, (int)M, (int)N, (int)(Kpad / 64), scale_x, scale_w, acc_out, ldacc, Y,
         ldy, (int)tiles_n, (unsigned)total);
     return hipGetLastError();
 }
+
+#define OCS_GEMM_ARGS Xq, ldx, Wq, ldw, M, N, Kpad, scale_x, scale_w, acc_out, ldacc, Y, ldy, stream
 
 hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
                         int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,
@@ -179,15 +196,14 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
         if (N <= 64) tile = 2;
     }
     switch (tile) {
-        case 0:
-            return run<128, 128, 2, 2>(Xq, ldx, Wq, ldw, M, N, Kpad, scale_x, scale_w, acc_out,
-                                       ldacc, Y, ldy, stream);
-        case 1:
-            return run<128, 64, 2, 2>(Xq, ldx, Wq, ldw, M, N, Kpad, scale_x, scale_w, acc_out,
-                                      ldacc, Y, ldy, stream);
-        default:
-            return run<128, 64, 4, 1>(Xq, ldx, Wq, ldw, M, N, Kpad, scale_x, scale_w, acc_out,
-                                      ldacc, Y, ldy, stream);
+        case 0: return run<128, 128, 2, 2, 6>(OCS_GEMM_ARGS);
+        case 1: return run<128, 64, 2, 2, 8>(OCS_GEMM_ARGS);
+        case 2: return run<128, 64, 4, 1, 8>(OCS_GEMM_ARGS);
+        case 3: return run<64, 128, 2, 2, 8>(OCS_GEMM_ARGS);
+        case 4: return run<64, 256, 1, 4, 6>(OCS_GEMM_ARGS);
+        case 5: return run<128, 128, 2, 2, 2>(OCS_GEMM_ARGS);
+        case 6: return run<128, 64, 2, 2, 4>(OCS_GEMM_ARGS);
+        default: return run<64, 64, 2, 2, 8>(OCS_GEMM_ARGS);
     }
 }
 
