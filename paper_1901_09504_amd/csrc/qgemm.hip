@@ -13,8 +13,13 @@
 
 namespace ocs {
 
+// LDS rows are BK bytes = BK/16 chunks of 16 bytes.  The chunk index is XOR-ed with a function
+// of the row chosen so that the 16-byte reads of 8 (and of 16) consecutive rows at one K offset
+// land in distinct bank groups.
+template <int BK>
 __device__ __forceinline__ int swz(int row, int chunk) {
-    return chunk ^ (((row >> 2) & 3) ^ (row & 2));
+    if (BK == 64) return chunk ^ (((row >> 2) & 3) ^ (row & 2));
+    return chunk ^ (((row >> 1) & 7) ^ ((row & 1) << 2));
 }
 
 // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Renumber them so
@@ -25,22 +30,23 @@ __device__ __forceinline__ unsigned xcd_remap(unsigned w, unsigned total) {
     return xcd * q + (xcd < r ? xcd : r) + local;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int P>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int P>
 __global__ __launch_bounds__(kThreads) void qgemm_kernel(
     const int8_t* __restrict__ Xq, int64_t ldx, const int8_t* __restrict__ Wq, int64_t ldw, int M,
-    int N, int ktiles, const float* __restrict__ scale_x, const float* __restrict__ scale_w,
+    int N, int ksteps, const float* __restrict__ scale_x, const float* __restrict__ scale_w,
     int32_t* __restrict__ acc_out, int64_t ldacc, float* __restrict__ Y, int64_t ldy, int tiles_n,
     unsigned total_tiles) {
     static_assert(WAVES_M * WAVES_N == kThreads / 64, "4 waves");
-    static_assert(P % 2 == 0, "the LDS buffer index must be static in the unrolled loop");
-    constexpr int BK = 64;
+    static_assert(P % 3 == 0, "the LDS buffer index must be static in the unrolled loop");
+    static_assert(BK == 64 || BK == 128, "K-step of 64 or 128 bytes");
+    constexpr int CPR = BK / 16;                         // 16-byte chunks per LDS row
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave tile
     constexpr int TM = WM / 32, TN = WN / 32;            // 32x32 MFMA tiles per wave
-    constexpr int A_CHUNKS = BM * 4 / kThreads, B_CHUNKS = BN * 4 / kThreads;
+    constexpr int A_CHUNKS = BM * CPR / kThreads, B_CHUNKS = BN * CPR / kThreads;
     static_assert(A_CHUNKS >= 1 && B_CHUNKS >= 1, "tile too small");
 
-    __shared__ __align__(16) int8_t lds_a[2][BM * BK];
-    __shared__ __align__(16) int8_t lds_b[2][BN * BK];
+    __shared__ __align__(16) int8_t lds_a[3][BM * BK];
+    __shared__ __align__(16) int8_t lds_b[3][BN * BK];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -50,25 +56,25 @@ __global__ __launch_bounds__(kThreads) void qgemm_kernel(
     const int bm = (int)(tile / tiles_n), bn = (int)(tile % tiles_n);
     const int row0 = bm * BM, col0 = bn * BN;
 
-    // staging: chunk q = tid + u*256 -> tile row q/4, 16-byte chunk q%4
+    // staging: chunk q = tid + u*256 -> tile row q / CPR, 16-byte chunk q % CPR
     const int8_t* a_src[A_CHUNKS];
     const int8_t* b_src[B_CHUNKS];
     int a_dst[A_CHUNKS], b_dst[B_CHUNKS];
 #pragma unroll
     for (int u = 0; u < A_CHUNKS; ++u) {
-        int q = tid + u * kThreads, r = q >> 2, c = q & 3;
+        int q = tid + u * kThreads, r = q / CPR, c = q % CPR;
         int gr = row0 + r;
         gr = gr < M ? gr : M - 1;  // rows past the edge re-read the last row; never stored
         a_src[u] = Xq + (int64_t)gr * ldx + c * 16;
-        a_dst[u] = r * BK + swz(r, c) * 16;
+        a_dst[u] = r * BK + swz<BK>(r, c) * 16;
     }
 #pragma unroll
     for (int u = 0; u < B_CHUNKS; ++u) {
-        int q = tid + u * kThreads, r = q >> 2, c = q & 3;
+        int q = tid + u * kThreads, r = q / CPR, c = q % CPR;
         int gr = col0 + r;
         gr = gr < N ? gr : N - 1;
         b_src[u] = Wq + (int64_t)gr * ldw + c * 16;
-        b_dst[u] = r * BK + swz(r, c) * 16;
+        b_dst[u] = r * BK + swz<BK>(r, c) * 16;
     }
 
     // P K-steps of both operands are in flight in registers at any time: a workgroup alone
@@ -77,8 +83,8 @@ __global__ __launch_bounds__(kThreads) void qgemm_kernel(
     // fetched again) so that the unrolled loop body is straight-line code and the wait before
     // each LDS write covers only the oldest stage, not every load in flight.
     i32x4 a_reg[P][A_CHUNKS], b_reg[P][B_CHUNKS];
-    auto fetch = [&](int slot_kt, i32x4 (&ar)[A_CHUNKS], i32x4 (&br)[B_CHUNKS]) {
-        const int kl = slot_kt < ktiles ? slot_kt : ktiles - 1;
+    auto fetch = [&](int kt, i32x4 (&ar)[A_CHUNKS], i32x4 (&br)[B_CHUNKS]) {
+        const int kl = kt < ksteps ? kt : ksteps - 1;
         const int64_t koff = (int64_t)kl * BK;
 #pragma unroll
         for (int u = 0; u < A_CHUNKS; ++u)
@@ -102,53 +108,84 @@ __global__ __launch_bounds__(kThreads) void qgemm_kernel(
     // a 32-byte K slice.  A and B use the same mapping, so the pairing of K bytes is
     // consistent whatever order the hardware assigns to them inside the slice.
     const int frag_row = lane & 31, frag_half = lane >> 5;
+    constexpr int KS = BK / 32;  // 32-byte K slices per step (even)
 
-    // One K-step: registers -> LDS buffer `buf`, barrier, refill the registers, multiply.
-    // One barrier per step suffices: a wave that arrives at it has finished reading the other
-    // buffer (previous step), so that buffer may be overwritten right after the next barrier.
-    auto step = [&](int buf, i32x4 (&ar)[A_CHUNKS], i32x4 (&br)[B_CHUNKS], int refill_kt,
-                    bool refill) {
+    i32x4 af[2][TM], bf[2][TN];  // fragments of the slice being multiplied and of the next one
+    auto read_slice = [&](int buf, int ks, i32x4 (&a)[TM], i32x4 (&b)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            int r = wm * WM + i * 32 + frag_row;
+            a[i] = *reinterpret_cast<const i32x4*>(
+                &lds_a[buf][r * BK + swz<BK>(r, ks * 2 + frag_half) * 16]);
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            int r = wn * WN + j * 32 + frag_row;
+            b[j] = *reinterpret_cast<const i32x4*>(
+                &lds_b[buf][r * BK + swz<BK>(r, ks * 2 + frag_half) * 16]);
+        }
+    };
+    auto multiply = [&](i32x4 (&a)[TM], i32x4 (&b)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+    };
+    auto stage = [&](int buf, i32x4 (&ar)[A_CHUNKS], i32x4 (&br)[B_CHUNKS]) {
 #pragma unroll
         for (int u = 0; u < A_CHUNKS; ++u)
             *reinterpret_cast<i32x4*>(&lds_a[buf][a_dst[u]]) = ar[u];
 #pragma unroll
         for (int u = 0; u < B_CHUNKS; ++u)
             *reinterpret_cast<i32x4*>(&lds_b[buf][b_dst[u]]) = br[u];
-        __syncthreads();
-        if (refill) fetch(refill_kt, ar, br);
+    };
+
+    // Software pipeline over three LDS buffers.  Step kt multiplies out of buffer kt % 3.
+    //  - At its start it writes step kt+2 (waiting in registers) into buffer (kt+2) % 3, whose
+    //    last readers left at the previous barrier, and refills those registers with step
+    //    kt+2+P: the LDS write has a whole step of MFMAs to complete behind.
+    //  - While the matrix cores work on slice s, the LDS reads of slice s+1 are in flight.
+    //  - Before the last slice is multiplied, the step's one barrier is taken and slice 0 of
+    //    step kt+1 is requested from buffer (kt+1) % 3, which was written a full step ago; the
+    //    last slice's MFMAs cover that read.
+    // Every action is unconditional (loads are clamped, surplus writes land in a buffer nobody
+    // reads), so the unrolled body is straight-line code.
+    auto step = [&](int buf, i32x4 (&nar)[A_CHUNKS], i32x4 (&nbr)[B_CHUNKS], int refill_kt) {
+        stage((buf + 2) % 3, nar, nbr);
+        fetch(refill_kt, nar, nbr);
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            i32x4 af[TM], bf[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                int r = wm * WM + i * 32 + frag_row;
-                af[i] = *reinterpret_cast<const i32x4*>(
-                    &lds_a[buf][r * BK + swz(r, ks * 2 + frag_half) * 16]);
+        for (int ks = 0; ks < KS; ++ks) {
+            if (ks + 1 < KS) {
+                read_slice(buf, ks + 1, af[(ks + 1) & 1], bf[(ks + 1) & 1]);
+            } else {
+                __syncthreads();
+                read_slice((buf + 1) % 3, 0, af[0], bf[0]);
             }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                int r = wn * WN + j * 32 + frag_row;
-                bf[j] = *reinterpret_cast<const i32x4*>(
-                    &lds_b[buf][r * BK + swz(r, ks * 2 + frag_half) * 16]);
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0,
-                                                                     0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(af[ks & 1], bf[ks & 1]);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
+    // prologue: steps 0 and 1 into buffers 0 and 1, slice 0 of step 0 into the fragments
+    stage(0, a_reg[0], b_reg[0]);
+    stage(1, a_reg[1 % P], b_reg[1 % P]);
+    fetch(P, a_reg[0], b_reg[0]);
+    fetch(P + 1, a_reg[1 % P], b_reg[1 % P]);
+    __syncthreads();
+    read_slice(0, 0, af[0], bf[0]);
+
+    // Step kt lives in register slot kt % P; step kt stages slot (kt+2) % P.
     int kt0 = 0;
-    for (; kt0 + P <= ktiles; kt0 += P) {
+    for (; kt0 + P <= ksteps; kt0 += P) {
 #pragma unroll
-        for (int p = 0; p < P; ++p) step(p & 1, a_reg[p], b_reg[p], kt0 + p + P, true);
+        for (int p = 0; p < P; ++p)
+            step(p % 3, a_reg[(p + 2) % P], b_reg[(p + 2) % P], kt0 + p + 2 + P);
     }
-    // the last ktiles % P steps; their data is already in the registers
 #pragma unroll
     for (int p = 0; p < P; ++p)
-        if (kt0 + p < ktiles) step(p & 1, a_reg[p], b_reg[p], 0, false);
+        if (kt0 + p < ksteps) step(p % 3, a_reg[(p + 2) % P], b_reg[(p + 2) % P], kt0 + p + 2 + P);
 
     // epilogue: accumulator register v of lane l holds row (v/4)*8 + (l/32)*4 + v%4 and
     // column l%32 of its 32x32 tile
@@ -170,14 +207,17 @@ __global__ __launch_bounds__(kThreads) void qgemm_kernel(
         }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int P>
+// Kpad is a multiple of 64.  With a 128-byte K-step and Kpad % 128 == 64 the last step would
+// read 64 bytes past the row's padding, so such shapes run the tail through the leading
+// dimension only if it allows it; otherwise the 64-byte variant is used.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int P>
 static hipError_t run(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
                       int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,
                       int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy, hipStream_t stream) {
     const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
     const int64_t total = tiles_m * tiles_n;
-    qgemm_kernel<BM, BN, WAVES_M, WAVES_N, P><<<(unsigned)total, kThreads, 0, stream>>>(
-        Xq, ldx, Wq, ldw, (int)M, (int)N, (int)(Kpad / 64), scale_x, scale_w, acc_out, ldacc, Y,
+    qgemm_kernel<BM, BN, WAVES_M, WAVES_N, BK, P><<<(unsigned)total, kThreads, 0, stream>>>(
+        Xq, ldx, Wq, ldw, (int)M, (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y,
         ldy, (int)tiles_n, (unsigned)total);
     return hipGetLastError();
 }
@@ -195,15 +235,21 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
         tile = t128 >= 512 ? 0 : 1;
         if (N <= 64) tile = 2;
     }
+    // variants with a 128-byte K-step need the K extent to be a multiple of 128
+    if (tile >= 8 && Kpad % 128 != 0) tile -= 8;
     switch (tile) {
-        case 0: return run<128, 128, 2, 2, 6>(OCS_GEMM_ARGS);
-        case 1: return run<128, 64, 2, 2, 8>(OCS_GEMM_ARGS);
-        case 2: return run<128, 64, 4, 1, 8>(OCS_GEMM_ARGS);
-        case 3: return run<64, 128, 2, 2, 8>(OCS_GEMM_ARGS);
-        case 4: return run<64, 256, 1, 4, 6>(OCS_GEMM_ARGS);
-        case 5: return run<128, 128, 2, 2, 2>(OCS_GEMM_ARGS);
-        case 6: return run<128, 64, 2, 2, 4>(OCS_GEMM_ARGS);
-        default: return run<64, 64, 2, 2, 8>(OCS_GEMM_ARGS);
+        case 0: return run<128, 128, 2, 2, 64, 6>(OCS_GEMM_ARGS);
+        case 1: return run<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
+        case 2: return run<128, 64, 4, 1, 64, 6>(OCS_GEMM_ARGS);
+        case 3: return run<64, 128, 2, 2, 64, 6>(OCS_GEMM_ARGS);
+        case 4: return run<64, 256, 1, 4, 64, 6>(OCS_GEMM_ARGS);
+        case 5: return run<256, 128, 2, 2, 64, 3>(OCS_GEMM_ARGS);
+        case 6: return run<128, 64, 2, 2, 64, 3>(OCS_GEMM_ARGS);
+        case 7: return run<64, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
+        case 8: return run<128, 128, 2, 2, 128, 3>(OCS_GEMM_ARGS);
+        case 9: return run<128, 64, 2, 2, 128, 3>(OCS_GEMM_ARGS);
+        case 10: return run<256, 128, 2, 2, 128, 3>(OCS_GEMM_ARGS);
+        default: return run<64, 256, 1, 4, 128, 3>(OCS_GEMM_ARGS);
     }
 }
 
