@@ -207,6 +207,207 @@ __global__ __launch_bounds__(kThreads) void qgemm_kernel(
         }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Variant that moves the operands global -> LDS directly (global_load_lds_dwordx4): no staging
+// registers and no LDS write instructions, which on this chip cost as much LDS time as the
+// fragment reads (the LDS takes ~73 B/clk of writes against ~190 B/clk of 16-byte reads).
+// One such instruction fills 1 KB of LDS, lane l at byte 16*l of the wave's block (the block
+// base travels in M0 and is wave-uniform), so the XOR swizzle is applied on the global side:
+// the lane that fills chunk slot c of row r fetches chunk c ^ f(r) of that row.  NBUF LDS
+// buffers form the prefetch ring; a wave waits for its own loads of the next step with vmcnt
+// (loads return in order), and the step's barrier then makes every wave's part visible.
+// ---------------------------------------------------------------------------------------------
+template <int N_>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N_ >= 0 && N_ < 64, "vmcnt is a 6-bit counter");
+    // s_waitcnt simm16: vmcnt[3:0], expcnt[6:4], lgkmcnt[11:8], vmcnt[5:4] in bits 15:14
+    __builtin_amdgcn_s_waitcnt((N_ & 15) | (7 << 4) | (15 << 8) | ((N_ >> 4) << 14));
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF>
+__global__ __launch_bounds__(kThreads) void qgemm_dma_kernel(
+    const int8_t* __restrict__ Xq, int64_t ldx, const int8_t* __restrict__ Wq, int64_t ldw, int M,
+    int N, int ksteps, const float* __restrict__ scale_x, const float* __restrict__ scale_w,
+    int32_t* __restrict__ acc_out, int64_t ldacc, float* __restrict__ Y, int64_t ldy, int tiles_n,
+    unsigned total_tiles) {
+    static_assert(WAVES_M * WAVES_N == kThreads / 64, "4 waves");
+    static_assert(BK == 64 || BK == 128, "K-step of 64 or 128 bytes");
+    static_assert(NBUF >= 3, "ring of at least three buffers");
+    constexpr int CPR = BK / 16;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int A_LOADS = BM * CPR / kThreads, B_LOADS = BN * CPR / kThreads;  // per wave & step
+    constexpr int LPS = A_LOADS + B_LOADS;
+    static_assert(A_LOADS >= 1 && B_LOADS >= 1, "tile too small");
+    static_assert((NBUF - 2) * LPS < 64, "prefetch ring exceeds the vmcnt range");
+    constexpr int KS = BK / 32;
+
+    __shared__ __align__(1024) int8_t lds_a[NBUF][BM * BK];
+    __shared__ __align__(1024) int8_t lds_b[NBUF][BN * BK];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+    const unsigned tile = xcd_remap(blockIdx.x, total_tiles);
+    const int bm = (int)(tile / tiles_n), bn = (int)(tile % tiles_n);
+    const int row0 = bm * BM, col0 = bn * BN;
+
+    // Load u of this wave fills LDS block (u*4 + wave): slots p = block*64 + lane, row p / CPR,
+    // chunk slot p % CPR, which receives global chunk slot ^ f(row).
+    const int8_t* a_src[A_LOADS];
+    const int8_t* b_src[B_LOADS];
+#pragma unroll
+    for (int u = 0; u < A_LOADS; ++u) {
+        int pslot = (u * 4 + wave) * 64 + lane, r = pslot / CPR, c = pslot % CPR;
+        int gr = row0 + r;
+        gr = gr < M ? gr : M - 1;  // rows past the edge re-read the last row; never stored
+        a_src[u] = Xq + (int64_t)gr * ldx + swz<BK>(r, c) * 16;
+    }
+#pragma unroll
+    for (int u = 0; u < B_LOADS; ++u) {
+        int pslot = (u * 4 + wave) * 64 + lane, r = pslot / CPR, c = pslot % CPR;
+        int gr = col0 + r;
+        gr = gr < N ? gr : N - 1;
+        b_src[u] = Wq + (int64_t)gr * ldw + swz<BK>(r, c) * 16;
+    }
+
+    // The load is issued through inline assembly on purpose: issued through the compiler's
+    // builtin, every later LDS read is preceded by a wait for ALL outstanding loads (the
+    // compiler cannot tell which LDS bytes a load fills), which would serialise the ring.
+    // The waits are placed by hand instead (wait_vmcnt below); the kernel has no other loads
+    // in flight until the epilogue, which starts after a wait for zero.
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef __attribute__((address_space(3))) int8_t* lptr_t;
+    const unsigned lds_a0 = (unsigned)(uintptr_t)(lptr_t)&lds_a[0][0];  // LDS byte addresses
+    const unsigned lds_b0 = (unsigned)(uintptr_t)(lptr_t)&lds_b[0][0];
+#else
+    const unsigned lds_a0 = 0, lds_b0 = 0;
+#endif
+    auto dma16 = [&](const int8_t* g, unsigned lds_addr) {
+#if defined(__HIP_DEVICE_COMPILE__)
+        // the block base is the same for every lane of the wave; M0 wants it in a scalar register
+        const unsigned m0 = __builtin_amdgcn_readfirstlane(lds_addr);
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                     :
+                     : "v"(g), "s"(m0)
+                     : "memory");
+#else
+        (void)g;
+        (void)lds_addr;
+#endif
+    };
+    auto fetch = [&](int kt, int buf) {   // K index clamped: surplus steps refetch the last one
+        const int kl = kt < ksteps ? kt : ksteps - 1;
+        const int64_t koff = (int64_t)kl * BK;
+#pragma unroll
+        for (int u = 0; u < A_LOADS; ++u)
+            dma16(a_src[u] + koff, lds_a0 + buf * (BM * BK) + (u * 4 + wave) * 1024);
+#pragma unroll
+        for (int u = 0; u < B_LOADS; ++u)
+            dma16(b_src[u] + koff, lds_b0 + buf * (BN * BK) + (u * 4 + wave) * 1024);
+    };
+
+    i32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+    const int frag_row = lane & 31, frag_half = lane >> 5;
+    i32x4 af[2][TM], bf[2][TN];
+    auto read_slice = [&](int buf, int ks, i32x4 (&a)[TM], i32x4 (&b)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            int r = wm * WM + i * 32 + frag_row;
+            a[i] = *reinterpret_cast<const i32x4*>(
+                &lds_a[buf][r * BK + swz<BK>(r, ks * 2 + frag_half) * 16]);
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            int r = wn * WN + j * 32 + frag_row;
+            b[j] = *reinterpret_cast<const i32x4*>(
+                &lds_b[buf][r * BK + swz<BK>(r, ks * 2 + frag_half) * 16]);
+        }
+    };
+    auto multiply = [&](i32x4 (&a)[TM], i32x4 (&b)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+    };
+
+    // Step kt multiplies out of buffer kt % NBUF.  At its start it requests step kt+NBUF-1 into
+    // the buffer step kt-1 used (every wave finished reading it before the previous barrier).
+    // Before its last slice it waits until only the loads of steps kt+2.. are outstanding,
+    // takes the barrier, and requests slice 0 of step kt+1.
+    auto step = [&](int buf, int kt) {
+        fetch(kt + NBUF - 1, (buf + NBUF - 1) % NBUF);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            if (ks + 1 < KS) {
+                read_slice(buf, ks + 1, af[(ks + 1) & 1], bf[(ks + 1) & 1]);
+            } else {
+                wait_vmcnt<(NBUF - 2) * LPS>();
+                __syncthreads();
+                read_slice((buf + 1) % NBUF, 0, af[0], bf[0]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(af[ks & 1], bf[ks & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+#pragma unroll
+    for (int p = 0; p < NBUF - 1; ++p) fetch(p, p);
+    wait_vmcnt<(NBUF - 2) * LPS>();
+    __syncthreads();
+    read_slice(0, 0, af[0], bf[0]);
+
+    int kt0 = 0;
+    for (; kt0 + NBUF <= ksteps; kt0 += NBUF) {
+#pragma unroll
+        for (int p = 0; p < NBUF; ++p) step(p, kt0 + p);
+    }
+#pragma unroll
+    for (int p = 0; p < NBUF; ++p)
+        if (kt0 + p < ksteps) step(p, kt0 + p);
+    wait_vmcnt<0>();  // surplus (clamped) loads must land before the workgroup's LDS is released
+
+    const float scale = scale_x[1] * scale_w[1];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int c = col0 + wn * WN + j * 32 + (lane & 31);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int r = row0 + wm * WM + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+                if (r < M && c < N) {
+                    const int a = acc[i][j][v];
+                    Y[(int64_t)r * ldy + c] = (float)a * scale;
+                    if (acc_out) acc_out[(int64_t)r * ldacc + c] = a;
+                }
+            }
+        }
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF>
+static hipError_t run_dma(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
+                          int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,
+                          int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy,
+                          hipStream_t stream) {
+    const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
+    const int64_t total = tiles_m * tiles_n;
+    qgemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, BK, NBUF><<<(unsigned)total, kThreads, 0, stream>>>(
+        Xq, ldx, Wq, ldw, (int)M, (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y,
+        ldy, (int)tiles_n, (unsigned)total);
+    return hipGetLastError();
+}
+
 // Kpad is a multiple of 64.  With a 128-byte K-step and Kpad % 128 == 64 the last step would
 // read 64 bytes past the row's padding, so such shapes run the tail through the leading
 // dimension only if it allows it; otherwise the 64-byte variant is used.
@@ -230,26 +431,28 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
                         hipStream_t stream) {
     int tile = tuning().gemm_tile;
     if (tile < 0) {
-        // enough tiles to cover 256 CUs at least twice, else smaller tiles
+        // Measured on MI355X: a CU draws operands through its vector-memory path at only
+        // ~16-30 B/clk, so the largest tile that still gives most CUs a workgroup wins.
+        const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 128);
         const int64_t t128 = ceil_div(M, 128) * ceil_div(N, 128);
-        tile = t128 >= 512 ? 0 : 1;
-        if (N <= 64) tile = 2;
+        if (t256 >= 128 && Kpad >= 2048) tile = 4;  // short K: the epilogue dominates, keep more tiles
+        else if (t128 >= 48) tile = 2;
+        else tile = 6;
+        if (N <= 64) tile = 7;
     }
-    // variants with a 128-byte K-step need the K extent to be a multiple of 128
-    if (tile >= 8 && Kpad % 128 != 0) tile -= 8;
+    // a 128-byte K-step needs the K extent to be a multiple of 128
+    const bool k128 = Kpad % 128 == 0;
     switch (tile) {
-        case 0: return run<128, 128, 2, 2, 64, 6>(OCS_GEMM_ARGS);
-        case 1: return run<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
-        case 2: return run<128, 64, 4, 1, 64, 6>(OCS_GEMM_ARGS);
-        case 3: return run<64, 128, 2, 2, 64, 6>(OCS_GEMM_ARGS);
-        case 4: return run<64, 256, 1, 4, 64, 6>(OCS_GEMM_ARGS);
-        case 5: return run<256, 128, 2, 2, 64, 3>(OCS_GEMM_ARGS);
-        case 6: return run<128, 64, 2, 2, 64, 3>(OCS_GEMM_ARGS);
-        case 7: return run<64, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
-        case 8: return run<128, 128, 2, 2, 128, 3>(OCS_GEMM_ARGS);
-        case 9: return run<128, 64, 2, 2, 128, 3>(OCS_GEMM_ARGS);
-        case 10: return run<256, 128, 2, 2, 128, 3>(OCS_GEMM_ARGS);
-        default: return run<64, 256, 1, 4, 128, 3>(OCS_GEMM_ARGS);
+        case 0: return run<128, 128, 2, 2, 64, 6>(OCS_GEMM_ARGS);      // register-staged
+        case 1: return run<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);       // register-staged
+        case 2: return run_dma<128, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS);
+        case 3: return k128 ? run_dma<128, 128, 2, 2, 128, 3>(OCS_GEMM_ARGS)
+                            : run_dma<128, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS);
+        case 4: return k128 ? run_dma<256, 128, 2, 2, 128, 3>(OCS_GEMM_ARGS)
+                            : run_dma<256, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS);
+        case 5: return run_dma<256, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS);
+        case 6: return run_dma<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
+        default: return run_dma<64, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
     }
 }
 
