@@ -29,6 +29,20 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 METRIC = "expanded int8 GEMM TOPS (% MFMA peak); split+quantize GB/s (% HBM)"
 
+# HBM bytes per launch of the split+quantize kernel on this workload, from two rocprofv3 --pmc
+# runs (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for the plain
+# copy kernel of known size launched after the timed region (profiles/x2_config2_hbm_traffic.md).
+# Valid only for the kernel source it was measured on: reported as null once that file changes.
+X2_TRAFFIC = {"quantize_hip_sha256": "ab1208137231d7038cfe9b533458fd67442d9848ccfb3a4bf09381f3bdac9f6e",
+              "bytes_per_launch": 145615191}
+
+
+def x2_traffic():
+    import hashlib
+    src = os.path.join(ROOT, "paper_1901_09504_amd", "csrc", "quantize.hip")
+    digest = hashlib.sha256(open(src, "rb").read()).hexdigest()
+    return X2_TRAFFIC["bytes_per_launch"] if digest == X2_TRAFFIC["quantize_hip_sha256"] else None
+
 
 def cpu_baseline(layer, W, X, reps=3):
     """The CPU oracle, as it stands, on the same workload on this machine's host cores."""
@@ -59,6 +73,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--copies", type=int, default=6, help="rotating copies of X (6 x 115.6 MB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copies", type=int, default=6,
+                    help="plain copies of X launched after the timed region (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -114,6 +130,14 @@ def main():
     dt = time.perf_counter() - t0
 
     ms_per_step = dt / args.steps * 1e3
+
+    # after the timed region: plain copies of known size, so that a counter run of this same
+    # command also holds the reference the HBM byte counters are scaled by
+    if args.calib_copies > 0:
+        dst = torch.empty_like(Xd[0])
+        for i in range(args.calib_copies):
+            B.ocs_calib_copy(Xd[i % len(Xd)], dst, Xd[0].numel() * 4)
+        torch.cuda.synchronize()
     phase = np.array([[e[k].elapsed_time(e[k + 1]) for k in range(5)] for e in events])  # ms
     raw = phase.mean(axis=0)
     bracket_ms = float(raw[4])       # an empty event pair, measured in the same timed region
@@ -145,7 +169,7 @@ def main():
         "split_quant_gbps": x2_gbs, "split_quant_pct_hbm": 100.0 * x2_gbs / HBM_PEAK_GBS,
         "roofline": {"kernel": "expand_quantize_kernel (ocs_split_act, X2)", "bound": "hbm",
                      "achieved": x2_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": x2_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "frac": x2_gbs / HBM_PEAK_GBS, "traffic": x2_traffic(),
                      "algorithmic_bytes_per_launch": x2_bytes, "avg_launch_us": avg[2] * 1e3,
                      "timing": "HIP events around the launch on its stream, minus the live-measured "
                                "cost of an empty event pair",

@@ -180,6 +180,13 @@ int ocs_qgemm(const int8_t *Xq, int64_t ldx, const int8_t *Wq, int64_t ldw, int6
               size_t ws_bytes, void *stream);
 
 /*
+ * Measurement helper (no passage of the paper): a plain device-to-device copy of `bytes`
+ * bytes (multiple of 16, both pointers 16-byte aligned) with 16-byte accesses.  Profiling runs
+ * use it to scale HBM byte counters against a transfer of known size.
+ */
+int ocs_calib_copy(const void *src, void *dst, size_t bytes, void *stream);
+
+/*
  * Launch-shape overrides for benchmarking (no passage of the paper; results never depend
  * on them).  key: "act_grid", "act_nt", "gemm_tile"; value < 0 restores the default.
  * Returns OCS_OK or OCS_E_MODE for an unknown key.  Not thread-safe.

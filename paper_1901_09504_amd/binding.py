@@ -65,6 +65,8 @@ def lib():
     L.ocs_qgemm.restype = _i32
     L.ocs_qgemm.argtypes = [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _vp, _vp, _vp, _i64, _vp,
                             _i64, _vp, _sz, _vp]
+    L.ocs_calib_copy.restype = _i32
+    L.ocs_calib_copy.argtypes = [_vp, _vp, _sz, _vp]
     L.ocs_tune.restype = _i32
     L.ocs_tune.argtypes = [C.c_char_p, _i32]
     _lib = L
@@ -108,6 +110,10 @@ def ocs_workspace_bytes(rows, cols):
 
 def ocs_tune(key, value):
     _check(lib().ocs_tune(key.encode(), int(value)), "ocs_tune")
+
+
+def ocs_calib_copy(src, dst, nbytes, stream=None):
+    _check(lib().ocs_calib_copy(_ptr(src), _ptr(dst), int(nbytes), _stream(stream)), "ocs_calib_copy")
 
 
 def alloc_workspace(rows, cols, device="cuda"):

@@ -266,6 +266,15 @@ int ocs_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int6
     return OCS_OK;
 }
 
+int ocs_calib_copy(const void* src, void* dst, size_t bytes, void* stream) {
+    if (!src || !dst) return OCS_E_NULL;
+    if (bytes == 0 || bytes % 16 != 0) return OCS_E_SHAPE;
+    if (!aligned(src, 16) || !aligned(dst, 16)) return OCS_E_ALIGN;
+    hipError_t e = launch_calib_copy(src, dst, bytes, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
 int ocs_tune(const char* key, int value) {
     if (!key) return OCS_E_NULL;
     Tuning& t = tuning();

@@ -76,6 +76,9 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
                         int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy,
                         hipStream_t stream);
 
+// 16-byte copy of `bytes` (multiple of 16) device bytes: counter calibration only.
+hipError_t launch_calib_copy(const void* src, void* dst, size_t bytes, hipStream_t stream);
+
 // Launch-shape overrides (benchmarking only); < 0 means "use the default".
 struct Tuning {
     int act_grid = -1;  // workgroups of the split+quantize pass
