@@ -180,6 +180,18 @@ int ocs_qgemm(const int8_t *Xq, int64_t ldx, const int8_t *Wq, int64_t ldw, int6
               size_t ws_bytes, void *stream);
 
 /*
+ * Measurement helper (no passage of the paper).  Arms a pair of caller-created hipEvent_t
+ * (created with timing enabled) for the calling thread's NEXT launch of one kernel family:
+ * OCS_TIME_SPLIT_QUANTIZE (the streaming pass of ocs_split_act / ocs_quantize /
+ * ocs_split_weights) or OCS_TIME_GEMM (ocs_qgemm).  That launch stamps the events with the
+ * kernel's own begin and end, so hipEventElapsedTime(start, stop) is the kernel's duration
+ * as a profiler reports it.  The pair is used once.  Returns OCS_E_MODE for an unknown family.
+ */
+#define OCS_TIME_SPLIT_QUANTIZE 1
+#define OCS_TIME_GEMM 2
+int ocs_time_next(int family, void *start_event, void *stop_event);
+
+/*
  * Measurement helper (no passage of the paper): a plain device-to-device copy of `bytes`
  * bytes (multiple of 16, both pointers 16-byte aligned) with 16-byte accesses.  Profiling runs
  * use it to scale HBM byte counters against a transfer of known size.

@@ -65,6 +65,8 @@ def lib():
     L.ocs_qgemm.restype = _i32
     L.ocs_qgemm.argtypes = [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _vp, _vp, _vp, _i64, _vp,
                             _i64, _vp, _sz, _vp]
+    L.ocs_time_next.restype = _i32
+    L.ocs_time_next.argtypes = [_i32, _vp, _vp]
     L.ocs_calib_copy.restype = _i32
     L.ocs_calib_copy.argtypes = [_vp, _vp, _sz, _vp]
     L.ocs_tune.restype = _i32
@@ -110,6 +112,18 @@ def ocs_workspace_bytes(rows, cols):
 
 def ocs_tune(key, value):
     _check(lib().ocs_tune(key.encode(), int(value)), "ocs_tune")
+
+
+TIME_SPLIT_QUANTIZE = 1
+TIME_GEMM = 2
+
+
+def ocs_time_next(family, start_event, stop_event):
+    """start_event / stop_event: torch.cuda.Event(enable_timing=True) already recorded once
+    (so that their handles exist), or raw hipEvent_t values."""
+    a = getattr(start_event, "cuda_event", start_event)
+    b = getattr(stop_event, "cuda_event", stop_event)
+    _check(lib().ocs_time_next(int(family), C.c_void_p(a), C.c_void_p(b)), "ocs_time_next")
 
 
 def ocs_calib_copy(src, dst, nbytes, stream=None):

@@ -14,6 +14,11 @@ Tuning& tuning() {
     return t;
 }
 
+KernelTimer& kernel_timer() {
+    static thread_local KernelTimer t;
+    return t;
+}
+
 static thread_local std::string g_hip_error;
 
 static int hip_fail(hipError_t e) {
@@ -177,9 +182,8 @@ int ocs_quantize(const float* x, int64_t rows, int64_t cols, int64_t ldx, int bi
         char* base = static_cast<char*>(workspace);
         float* colmax = reinterpret_cast<float*>(base + w.colmax_off);
         float* partial = reinterpret_cast<float*>(base + w.partial_off);
-        e = launch_colmax(x, rows, cols, ldx, colmax, partial, st);
-        if (e != hipSuccess) return hip_fail(e);
-        e = launch_threshold(colmax, (int)cols, 1, 0, nullptr, nullptr, clip_ratio, qmax, scale_out, st);
+        (void)colmax;
+        e = launch_absmax_threshold(x, rows, cols, ldx, partial, clip_ratio, qmax, scale_out, st);
         if (e != hipSuccess) return hip_fail(e);
         e = launch_expand_quantize(x, ldx, rows, (int)cols, 1, 0, nullptr, nullptr, scale_out, qmax,
                                    q, ldq, nullptr, st);
@@ -207,11 +211,19 @@ int ocs_act_threshold(const float* X, int64_t M, int C, int g, int64_t ldx, cons
     float* colmax = reinterpret_cast<float*>(base + w.colmax_off);
     float* partial = reinterpret_cast<float*>(base + w.partial_off);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipError_t e = launch_colmax(X, M, K, ldx, colmax, partial, st);
-    if (e != hipSuccess) return hip_fail(e);
-    e = launch_threshold(colmax, C, g, num_splits, chan_src, chan_depth, clip_ratio, qmax_of(bits),
-                         scale_out, st);
-    if (e != hipSuccess) return hip_fail(e);
+    hipError_t e;
+    if (chan_depth == nullptr) {
+        // copies do not change the maximum: max|X| of the whole tensor is enough
+        (void)colmax;
+        e = launch_absmax_threshold(X, M, K, ldx, partial, clip_ratio, qmax_of(bits), scale_out, st);
+        if (e != hipSuccess) return hip_fail(e);
+    } else {
+        e = launch_colmax(X, M, K, ldx, colmax, partial, st);
+        if (e != hipSuccess) return hip_fail(e);
+        e = launch_threshold(colmax, C, g, num_splits, chan_src, chan_depth, clip_ratio,
+                             qmax_of(bits), scale_out, st);
+        if (e != hipSuccess) return hip_fail(e);
+    }
     return OCS_OK;
 }
 
@@ -263,6 +275,16 @@ int ocs_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int6
     hipError_t e = launch_qgemm(Xq, ldx, Wq, ldw, M, N, Kpad, scale_x, scale_w, acc_out, ldacc, Y,
                                 ldy, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
+int ocs_time_next(int family, void* start_event, void* stop_event) {
+    if (family != kTimeSplitQuantize && family != kTimeGemm) return OCS_E_MODE;
+    if (!start_event || !stop_event) return OCS_E_NULL;
+    KernelTimer& t = kernel_timer();
+    t.which = family;
+    t.start = static_cast<hipEvent_t>(start_event);
+    t.stop = static_cast<hipEvent_t>(stop_event);
     return OCS_OK;
 }
 

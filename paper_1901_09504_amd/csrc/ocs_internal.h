@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -33,7 +34,7 @@ ReducePlan plan_reduce(int64_t rows, int64_t cols, bool vec_ok);
 // Workspace layout (byte offsets from a 256-byte aligned base).
 struct Workspace {
     size_t colmax_off;   // float[round_up(cols, 64)]
-    size_t partial_off;  // float[row_blocks * cols]
+    size_t partial_off;  // float[row_blocks * (cols + 1)]
     size_t total;
 };
 Workspace plan_workspace(int64_t rows, int64_t cols);
@@ -43,6 +44,12 @@ Workspace plan_workspace(int64_t rows, int64_t cols);
 // colmax[c] = max_r |T[r, c]| for c < cols.  Two stages, no atomics, deterministic.
 hipError_t launch_colmax(const float* T, int64_t rows, int64_t cols, int64_t ld, float* colmax,
                          float* partial, hipStream_t stream);
+
+// scale_out = {T, T/qmax} with T = clip_ratio * max|T| over the whole tensor: the column pass
+// with one value per workgroup, then one small reduction (no per-column result).
+hipError_t launch_absmax_threshold(const float* T, int64_t rows, int64_t cols, int64_t ld,
+                                   float* partial, float clip_ratio, float qmax, float* scale_out,
+                                   hipStream_t stream);
 
 // Greedy channel selection (mode 0) or replay of a given split list (mode 1) on the C
 // channel maxima derived from colmax[C*g].  Optionally writes max_out and
@@ -78,6 +85,30 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
 
 // 16-byte copy of `bytes` (multiple of 16) device bytes: counter calibration only.
 hipError_t launch_calib_copy(const void* src, void* dst, size_t bytes, hipStream_t stream);
+
+// A pair of caller-owned events armed for the next launch of one kernel family on this thread:
+// that launch goes through hipExtLaunchKernel, which stamps the events with the dispatch's own
+// begin and end (what a profiler reports), not with the time of markers around it.
+constexpr int kTimeSplitQuantize = 1;
+constexpr int kTimeGemm = 2;
+struct KernelTimer {
+    int which = 0;
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+KernelTimer& kernel_timer();
+
+template <typename F, typename... Args>
+inline hipError_t launch_kernel(int family, F kernel, dim3 grid, dim3 block, unsigned lds,
+                                hipStream_t stream, Args... args) {
+    KernelTimer& t = kernel_timer();
+    if (t.which == family && t.start != nullptr && t.stop != nullptr) {
+        t.which = 0;
+        hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, t.start, t.stop, 0, args...);
+    } else {
+        kernel<<<grid, block, lds, stream>>>(args...);
+    }
+    return hipGetLastError();
+}
 
 // Launch-shape overrides (benchmarking only); < 0 means "use the default".
 struct Tuning {

@@ -402,10 +402,10 @@ static hipError_t run_dma(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64
                           hipStream_t stream) {
     const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
     const int64_t total = tiles_m * tiles_n;
-    qgemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, BK, NBUF><<<(unsigned)total, kThreads, 0, stream>>>(
-        Xq, ldx, Wq, ldw, (int)M, (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y,
-        ldy, (int)tiles_n, (unsigned)total);
-    return hipGetLastError();
+    return launch_kernel(kTimeGemm, qgemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, BK, NBUF>,
+                         dim3((unsigned)total), dim3(kThreads), 0, stream, Xq, ldx, Wq, ldw, (int)M,
+                         (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y, ldy,
+                         (int)tiles_n, (unsigned)total);
 }
 
 // Kpad is a multiple of 64.  With a 128-byte K-step and Kpad % 128 == 64 the last step would
@@ -417,10 +417,10 @@ static hipError_t run(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t l
                       int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy, hipStream_t stream) {
     const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
     const int64_t total = tiles_m * tiles_n;
-    qgemm_kernel<BM, BN, WAVES_M, WAVES_N, BK, P><<<(unsigned)total, kThreads, 0, stream>>>(
-        Xq, ldx, Wq, ldw, (int)M, (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y,
-        ldy, (int)tiles_n, (unsigned)total);
-    return hipGetLastError();
+    return launch_kernel(kTimeGemm, qgemm_kernel<BM, BN, WAVES_M, WAVES_N, BK, P>,
+                         dim3((unsigned)total), dim3(kThreads), 0, stream, Xq, ldx, Wq, ldw, (int)M,
+                         (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y, ldy,
+                         (int)tiles_n, (unsigned)total);
 }
 
 #define OCS_GEMM_ARGS Xq, ldx, Wq, ldw, M, N, Kpad, scale_x, scale_w, acc_out, ldacc, Y, ldy, stream

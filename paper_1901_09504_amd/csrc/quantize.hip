@@ -198,9 +198,11 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
     if (grid > ceil_div(total, kThreads)) grid = ceil_div(total, kThreads);
     const bool wide = total + grid * kThreads >= ((int64_t)1 << 32);
 
+    hipError_t err = hipSuccess;
 #define OCS_LAUNCH_EQ(H, N_, I_)                                                                  \
-    expand_quantize_kernel<H, N_, I_><<<(unsigned)grid, kThreads, 0, stream>>>(                    \
-        X, ldx, M, C, g, s, chan_src, chan_depth, thr, qmax, Xq, D, main_units, scale_out)
+    err = launch_kernel(kTimeSplitQuantize, expand_quantize_kernel<H, N_, I_>, dim3((unsigned)grid), \
+                  dim3(kThreads), 0, stream, X, ldx, M, C, g, s, chan_src, chan_depth, thr, qmax,  \
+                  Xq, D, main_units, scale_out)
     if (wide) {
         if (halve) { if (nt) OCS_LAUNCH_EQ(true, true, uint64_t); else OCS_LAUNCH_EQ(true, false, uint64_t); }
         else       { if (nt) OCS_LAUNCH_EQ(false, true, uint64_t); else OCS_LAUNCH_EQ(false, false, uint64_t); }
@@ -209,7 +211,7 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
         else       { if (nt) OCS_LAUNCH_EQ(false, true, uint32_t); else OCS_LAUNCH_EQ(false, false, uint32_t); }
     }
 #undef OCS_LAUNCH_EQ
-    return hipGetLastError();
+    return err;
 }
 
 // fp32 expanded tensor (Eq. 3 with halve != 0, the weight side of Eq. 4 with halve == 0).

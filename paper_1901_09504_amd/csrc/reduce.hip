@@ -40,13 +40,15 @@ Workspace plan_workspace(int64_t rows, int64_t cols) {
     int64_t rb = a.row_blocks > b.row_blocks ? a.row_blocks : b.row_blocks;
     w.colmax_off = 0;
     w.partial_off = (size_t)round_up(round_up(cols, 64) * 4, 256);
-    w.total = w.partial_off + (size_t)round_up(rb * cols * 4, 256);
+    w.total = w.partial_off + (size_t)round_up(rb * (cols + 1) * 4, 256);
     return w;
 }
 
 // Stage 1.  Workgroup (tx, ty): lane tx owns VEC consecutive columns of strip blockIdx.x,
 // ty walks the rows of row block blockIdx.y with stride TY.
-template <int VEC>
+// With SCALAR the workgroup folds its columns as well and writes one value,
+// partial[blockIdx.y * gridDim.x + blockIdx.x]: enough when only the tensor's maximum is wanted.
+template <int VEC, bool SCALAR>
 __global__ __launch_bounds__(kThreads) void colmax_partial_kernel(
     const float* __restrict__ T, int64_t ld, int64_t rows, int64_t col0, int64_t units,
     int rows_per_block, int64_t out_cols, float* __restrict__ partial) {
@@ -77,6 +79,21 @@ __global__ __launch_bounds__(kThreads) void colmax_partial_kernel(
 #pragma unroll
     for (int e = 0; e < VEC; ++e) red[(ty * TX + tx) * VEC + e] = acc[e];
     __syncthreads();
+    if (SCALAR) {
+        float m = 0.0f;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) m = fmaxf(m, acc[e]);
+        const int t = ty * TX + tx;
+        __syncthreads();
+        red[t] = m;
+        __syncthreads();
+        for (int w = kThreads / 2; w > 0; w >>= 1) {
+            if (t < w) red[t] = fmaxf(red[t], red[t + w]);
+            __syncthreads();
+        }
+        if (t == 0) partial[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = red[0];
+        return;
+    }
     if (ty == 0 && u < units) {
         for (int y = 1; y < TY; ++y)
 #pragma unroll
@@ -105,31 +122,86 @@ __global__ __launch_bounds__(kThreads) void colmax_final_kernel(const float* __r
     }
 }
 
+static hipError_t launch_partials(const float* T, int64_t rows, int64_t cols, int64_t ld,
+                                  float* partial, bool scalar, const ReducePlan& p, int* entries,
+                                  hipStream_t stream) {
+    dim3 block(p.tx, p.ty);
+    int n = 0;
+    if (p.vec == 4) {
+        int64_t units = cols / 4;
+        dim3 grid(p.col_strips, p.row_blocks);
+        if (scalar)
+            colmax_partial_kernel<4, true><<<grid, block, 0, stream>>>(T, ld, rows, 0, units,
+                                                                       p.rows_per_block, cols, partial);
+        else
+            colmax_partial_kernel<4, false><<<grid, block, 0, stream>>>(T, ld, rows, 0, units,
+                                                                        p.rows_per_block, cols, partial);
+        n = p.col_strips * p.row_blocks;
+        int64_t left = cols - units * 4;
+        if (left > 0) {  // the last cols % 4 columns, one lane each
+            dim3 grid1(1, p.row_blocks);
+            if (scalar)
+                colmax_partial_kernel<1, true><<<grid1, block, 0, stream>>>(
+                    T, ld, rows, units * 4, left, p.rows_per_block, cols, partial + n);
+            else
+                colmax_partial_kernel<1, false><<<grid1, block, 0, stream>>>(
+                    T, ld, rows, units * 4, left, p.rows_per_block, cols, partial);
+            n += p.row_blocks;
+        }
+    } else {
+        dim3 grid(p.col_strips, p.row_blocks);
+        if (scalar)
+            colmax_partial_kernel<1, true><<<grid, block, 0, stream>>>(T, ld, rows, 0, cols,
+                                                                       p.rows_per_block, cols, partial);
+        else
+            colmax_partial_kernel<1, false><<<grid, block, 0, stream>>>(T, ld, rows, 0, cols,
+                                                                        p.rows_per_block, cols, partial);
+        n = p.col_strips * p.row_blocks;
+    }
+    if (entries) *entries = n;
+    return hipGetLastError();
+}
+
 hipError_t launch_colmax(const float* T, int64_t rows, int64_t cols, int64_t ld, float* colmax,
                          float* partial, hipStream_t stream) {
     bool vec_ok = (reinterpret_cast<uintptr_t>(T) % 16 == 0) && (ld % 4 == 0);
     ReducePlan p = plan_reduce(rows, cols, vec_ok);
-    dim3 block(p.tx, p.ty);
-    if (p.vec == 4) {
-        int64_t units = cols / 4;
-        dim3 grid(p.col_strips, p.row_blocks);
-        colmax_partial_kernel<4><<<grid, block, 0, stream>>>(T, ld, rows, 0, units,
-                                                             p.rows_per_block, cols, partial);
-        int64_t left = cols - units * 4;
-        if (left > 0) {  // the last cols % 4 columns, one lane each
-            dim3 grid1(1, p.row_blocks);
-            colmax_partial_kernel<1><<<grid1, block, 0, stream>>>(T, ld, rows, units * 4, left,
-                                                                  p.rows_per_block, cols, partial);
-        }
-    } else {
-        dim3 grid(p.col_strips, p.row_blocks);
-        colmax_partial_kernel<1><<<grid, block, 0, stream>>>(T, ld, rows, 0, cols,
-                                                             p.rows_per_block, cols, partial);
-    }
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch_partials(T, rows, cols, ld, partial, false, p, nullptr, stream);
     if (e != hipSuccess) return e;
     colmax_final_kernel<<<(unsigned)ceil_div(cols, 64), kThreads, 0, stream>>>(partial, p.row_blocks,
                                                                               cols, colmax);
+    return hipGetLastError();
+}
+
+// scale_out = {T, T/qmax}, T = clip_ratio * max(v[0..n)).  One workgroup.
+__global__ __launch_bounds__(kThreads) void threshold_scalar_kernel(const float* __restrict__ v, int n,
+                                                                    float clip_ratio, float qmax,
+                                                                    float* __restrict__ scale_out) {
+    __shared__ float red[kThreads];
+    float m = 0.0f;
+    for (int i = threadIdx.x; i < n; i += kThreads) m = fmaxf(m, v[i]);
+    red[threadIdx.x] = m;
+    __syncthreads();
+    for (int w = kThreads / 2; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + w]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        float T = clip_ratio * red[0];
+        scale_out[0] = T;
+        scale_out[1] = T / qmax;
+    }
+}
+
+hipError_t launch_absmax_threshold(const float* T, int64_t rows, int64_t cols, int64_t ld,
+                                   float* partial, float clip_ratio, float qmax, float* scale_out,
+                                   hipStream_t stream) {
+    bool vec_ok = (reinterpret_cast<uintptr_t>(T) % 16 == 0) && (ld % 4 == 0);
+    ReducePlan p = plan_reduce(rows, cols, vec_ok);
+    int n = 0;
+    hipError_t e = launch_partials(T, rows, cols, ld, partial, true, p, &n, stream);
+    if (e != hipSuccess) return e;
+    threshold_scalar_kernel<<<1, kThreads, 0, stream>>>(partial, n, clip_ratio, qmax, scale_out);
     return hipGetLastError();
 }
 
