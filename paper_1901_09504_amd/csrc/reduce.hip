@@ -112,8 +112,10 @@ __global__ __launch_bounds__(kThreads) void colmax_final_kernel(const float* __r
     const int cx = threadIdx.x & 63, gy = threadIdx.x >> 6;
     const int64_t c = (int64_t)blockIdx.x * 64 + cx;
     float m = 0.0f;
-    if (c < cols)
+    if (c < cols) {
+#pragma unroll 8
         for (int r = gy; r < row_blocks; r += 4) m = fmaxf(m, partial[(int64_t)r * cols + c]);
+    }
     red[threadIdx.x] = m;
     __syncthreads();
     if (gy == 0 && c < cols) {

@@ -41,12 +41,20 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     __shared__ float red[kThreads];
     const int tid = threadIdx.x;
 
+    // channel maxima: one coalesced, independent load per column, folded per channel with LDS
+    // atomics on the bit pattern (non-negative floats order like unsigned integers)
     for (int j = tid; j < C; j += kThreads) {
-        float m = 0.0f;
-        for (int t = 0; t < g; ++t) m = fmaxf(m, colmax[(int64_t)j * g + t]);
-        vals[j] = m;
+        vals[j] = 0.0f;
         src[j] = (unsigned short)j;
         dep[j] = 0;
+    }
+    __syncthreads();
+    {
+        const int K = C * g;
+        unsigned* vbits = reinterpret_cast<unsigned*>(vals);
+#pragma unroll 8
+        for (int k = tid; k < K; k += kThreads)
+            atomicMax(&vbits[k / g], __float_as_uint(colmax[k]));
     }
     __syncthreads();
 
