@@ -55,12 +55,12 @@ __device__ __forceinline__ f32x4 load4(const f32x4* p) {
 //                    caches, not by HBM) and the zero padding.
 constexpr int kTailTable = 2048;  // appended + padded columns whose sources are kept in LDS
 
-template <bool HALVE, bool NT, typename Index>
+template <bool HALVE, bool NT, int UN, typename Index>
 __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
     const float* __restrict__ X, int64_t ldx, int64_t M, int C, int g, int s,
     const int32_t* __restrict__ chan_src, const int32_t* __restrict__ chan_depth,
     const float* thr, float qmax, int8_t* __restrict__ Xq, int D, int main_units,
-    float* scale_out) {
+    unsigned magic, float* scale_out) {
     // Source column (or -1 for padding) and halving depth of every column past the vector
     // region.  They do not depend on the row, so each workgroup resolves them once; a lane that
     // lands on such a column then needs a single trip to memory, like every other lane.
@@ -89,18 +89,28 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
     const Index stride = (Index)gridDim.x * kThreads;
     unsigned* __restrict__ out = reinterpret_cast<unsigned*>(Xq);
 
-    // position of output dword o, and its 16-byte input when it lies in the vector region
-    auto locate = [&](Index o, int64_t& row, int& d) {
-        const Index r = o / (Index)D;
-        row = (int64_t)r;
-        d = (int)(o - r * (Index)D);
+    // Position of output dword o.  With 32-bit indices the division by D is a multiply by
+    // magic = floor(2^32 / D) and one correction step (the estimate is never more than one low).
+    auto locate = [&](Index o, Index& row, int& d) {
+        if (sizeof(Index) == 4) {
+            unsigned q = __umulhi((unsigned)o, magic);
+            unsigned r = (unsigned)o - q * (unsigned)D;
+            if (r >= (unsigned)D) { ++q; r -= (unsigned)D; }
+            row = (Index)q;
+            d = (int)r;
+        } else {
+            row = o / (Index)D;
+            d = (int)(o - row * (Index)D);
+        }
     };
-    auto fetch = [&](Index o, f32x4& v) {
+    // requests the 16-byte input of item o (if it has one) and remembers where the item lives
+    auto fetch = [&](Index o, f32x4& v, Index& row, int& d) {
+        row = 0;
+        d = 0;
         if (o < total) {
-            int64_t row;
-            int d;
             locate(o, row, d);
-            if (d < main_units) v = load4<NT>(reinterpret_cast<const f32x4*>(X + row * ldx) + d);
+            if (d < main_units)
+                v = load4<NT>(reinterpret_cast<const f32x4*>(X + (int64_t)row * ldx) + d);
         }
     };
 
@@ -111,27 +121,13 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
     const unsigned nwg = gridDim.x, xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
     const unsigned vwg = xcd * (nwg / 8) + (xcd < nwg % 8 ? xcd : nwg % 8) + slot;
 
-    // the first input is requested before anything waits on the threshold
-    Index o = (Index)vwg * kThreads + threadIdx.x;
-    f32x4 cur = {}, nxt = {};
-    fetch(o, cur);
-    const float T = *thr;
-    const float inv = inv_step_of(T, qmax);
-    if (scale_out != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
-        scale_out[0] = T;
-        scale_out[1] = T / qmax;
-    }
-    __syncthreads();
-
-    for (; o < total; o += stride) {
-        fetch(o + stride, nxt);  // next trip's input is in flight while this one is processed
-        int64_t row;
-        int d;
-        locate(o, row, d);
-        const float* xrow = X + row * ldx;
+    // One item: quantize, pack and store output dword o (row, d), whose 16-byte input, if it
+    // has one, is already in v.
+    auto emit = [&](Index o, Index row, int d, const f32x4& vin, float inv) {
+        const float* xrow = X + (int64_t)row * ldx;
         unsigned q;
         if (d < main_units) {
-            f32x4 v = cur;
+            f32x4 v = vin;
             if (HALVE) {
                 int j = (4 * d) / g, t = 4 * d - j * g;
 #pragma unroll
@@ -177,7 +173,38 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
                       code_bits(v[2], inv, qmax), code_bits(v[3], inv, qmax));
         }
         out[o] = q;
-        cur = nxt;
+    };
+
+    // Each trip of a lane covers UN items, stride apart; the inputs of the next trip are
+    // requested before this trip's items are processed.  The first inputs are requested before
+    // anything waits on the threshold.
+    Index o = (Index)vwg * kThreads + threadIdx.x;
+    f32x4 cur[UN] = {}, nxt[UN] = {};
+    Index row[UN] = {}, nrow[UN] = {};
+    int d[UN] = {}, nd[UN] = {};
+#pragma unroll
+    for (int u = 0; u < UN; ++u) fetch(o + (Index)u * stride, cur[u], row[u], d[u]);
+    const float T = *thr;
+    const float inv = inv_step_of(T, qmax);
+    if (scale_out != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
+        scale_out[0] = T;
+        scale_out[1] = T / qmax;
+    }
+    __syncthreads();
+
+    for (; o < total; o += (Index)UN * stride) {
+#pragma unroll
+        for (int u = 0; u < UN; ++u)
+            fetch(o + (Index)(UN + u) * stride, nxt[u], nrow[u], nd[u]);
+#pragma unroll
+        for (int u = 0; u < UN; ++u)
+            if (o + (Index)u * stride < total) emit(o + (Index)u * stride, row[u], d[u], cur[u], inv);
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            cur[u] = nxt[u];
+            row[u] = nrow[u];
+            d[u] = nd[u];
+        }
     }
 }
 
@@ -196,13 +223,14 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
     int64_t grid = 256 * 8;  // 8 workgroups of 4 waves on each of the 256 CUs
     if (tuning().act_grid > 0) grid = tuning().act_grid;
     if (grid > ceil_div(total, kThreads)) grid = ceil_div(total, kThreads);
-    const bool wide = total + grid * kThreads >= ((int64_t)1 << 32);
+    const bool wide = total + 4 * grid * kThreads >= ((int64_t)1 << 32);
+    const unsigned magic = (unsigned)((((uint64_t)1) << 32) / (uint64_t)D);  // D >= 16
 
     hipError_t err = hipSuccess;
 #define OCS_LAUNCH_EQ(H, N_, I_)                                                                  \
-    err = launch_kernel(kTimeSplitQuantize, expand_quantize_kernel<H, N_, I_>, dim3((unsigned)grid), \
+    err = launch_kernel(kTimeSplitQuantize, expand_quantize_kernel<H, N_, 1, I_>, dim3((unsigned)grid), \
                   dim3(kThreads), 0, stream, X, ldx, M, C, g, s, chan_src, chan_depth, thr, qmax,  \
-                  Xq, D, main_units, scale_out)
+                  Xq, D, main_units, magic, scale_out)
     if (wide) {
         if (halve) { if (nt) OCS_LAUNCH_EQ(true, true, uint64_t); else OCS_LAUNCH_EQ(true, false, uint64_t); }
         else       { if (nt) OCS_LAUNCH_EQ(false, true, uint64_t); else OCS_LAUNCH_EQ(false, false, uint64_t); }
