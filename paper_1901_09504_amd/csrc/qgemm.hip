@@ -225,18 +225,20 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF>
-__global__ __launch_bounds__(kThreads) void qgemm_dma_kernel(
+__global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
     const int8_t* __restrict__ Xq, int64_t ldx, const int8_t* __restrict__ Wq, int64_t ldw, int M,
     int N, int ksteps, const float* __restrict__ scale_x, const float* __restrict__ scale_w,
     int32_t* __restrict__ acc_out, int64_t ldacc, float* __restrict__ Y, int64_t ldy, int tiles_n,
     unsigned total_tiles) {
-    static_assert(WAVES_M * WAVES_N == kThreads / 64, "4 waves");
+    constexpr int NW = WAVES_M * WAVES_N;  // waves per workgroup (4 or 8)
+    constexpr int NT = NW * 64;
+    static_assert(NW == 4 || NW == 8, "4 or 8 waves");
     static_assert(BK == 64 || BK == 128, "K-step of 64 or 128 bytes");
     static_assert(NBUF >= 3, "ring of at least three buffers");
     constexpr int CPR = BK / 16;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int A_LOADS = BM * CPR / kThreads, B_LOADS = BN * CPR / kThreads;  // per wave & step
+    constexpr int A_LOADS = BM * CPR / NT, B_LOADS = BN * CPR / NT;  // per wave & step
     constexpr int LPS = A_LOADS + B_LOADS;
     static_assert(A_LOADS >= 1 && B_LOADS >= 1, "tile too small");
     static_assert((NBUF - 2) * LPS < 64, "prefetch ring exceeds the vmcnt range");
@@ -259,14 +261,14 @@ __global__ __launch_bounds__(kThreads) void qgemm_dma_kernel(
     const int8_t* b_src[B_LOADS];
 #pragma unroll
     for (int u = 0; u < A_LOADS; ++u) {
-        int pslot = (u * 4 + wave) * 64 + lane, r = pslot / CPR, c = pslot % CPR;
+        int pslot = (u * NW + wave) * 64 + lane, r = pslot / CPR, c = pslot % CPR;
         int gr = row0 + r;
         gr = gr < M ? gr : M - 1;  // rows past the edge re-read the last row; never stored
         a_src[u] = Xq + (int64_t)gr * ldx + swz<BK>(r, c) * 16;
     }
 #pragma unroll
     for (int u = 0; u < B_LOADS; ++u) {
-        int pslot = (u * 4 + wave) * 64 + lane, r = pslot / CPR, c = pslot % CPR;
+        int pslot = (u * NW + wave) * 64 + lane, r = pslot / CPR, c = pslot % CPR;
         int gr = col0 + r;
         gr = gr < N ? gr : N - 1;
         b_src[u] = Wq + (int64_t)gr * ldw + swz<BK>(r, c) * 16;
@@ -302,10 +304,10 @@ __global__ __launch_bounds__(kThreads) void qgemm_dma_kernel(
         const int64_t koff = (int64_t)kl * BK;
 #pragma unroll
         for (int u = 0; u < A_LOADS; ++u)
-            dma16(a_src[u] + koff, lds_a0 + buf * (BM * BK) + (u * 4 + wave) * 1024);
+            dma16(a_src[u] + koff, lds_a0 + buf * (BM * BK) + (u * NW + wave) * 1024);
 #pragma unroll
         for (int u = 0; u < B_LOADS; ++u)
-            dma16(b_src[u] + koff, lds_b0 + buf * (BN * BK) + (u * 4 + wave) * 1024);
+            dma16(b_src[u] + koff, lds_b0 + buf * (BN * BK) + (u * NW + wave) * 1024);
     };
 
     i32x16 acc[TM][TN];
@@ -400,10 +402,12 @@ static hipError_t run_dma(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64
                           int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,
                           int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy,
                           hipStream_t stream) {
+    // the kernel clamps its K index to ksteps - 1: it must never be launched with no K-step
+    if (Kpad < BK || Kpad % BK != 0) return hipErrorInvalidValue;
     const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
     const int64_t total = tiles_m * tiles_n;
     return launch_kernel(kTimeGemm, qgemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, BK, NBUF>,
-                         dim3((unsigned)total), dim3(kThreads), 0, stream, Xq, ldx, Wq, ldw, (int)M,
+                         dim3((unsigned)total), dim3(WAVES_M * WAVES_N * 64), 0, stream, Xq, ldx, Wq, ldw, (int)M,
                          (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y, ldy,
                          (int)tiles_n, (unsigned)total);
 }
@@ -415,6 +419,8 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int P>
 static hipError_t run(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
                       int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,
                       int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy, hipStream_t stream) {
+    // the kernel clamps its K index to ksteps - 1: it must never be launched with no K-step
+    if (Kpad < BK || Kpad % BK != 0) return hipErrorInvalidValue;
     const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
     const int64_t total = tiles_m * tiles_n;
     return launch_kernel(kTimeGemm, qgemm_kernel<BM, BN, WAVES_M, WAVES_N, BK, P>,
@@ -432,11 +438,12 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
     int tile = tuning().gemm_tile;
     if (tile < 0) {
         // Measured on MI355X: a CU draws operands through its vector-memory path at only
-        // ~16-30 B/clk, so the largest tile that still gives most CUs a workgroup wins.
+        // ~16-30 B/clk, rising with the number of waves that issue loads, so the largest tile
+        // that still gives most CUs a workgroup wins, and workgroups of 8 waves beat 4.
         const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 128);
         const int64_t t128 = ceil_div(M, 128) * ceil_div(N, 128);
-        if (t256 >= 128 && Kpad >= 2048) tile = 4;  // short K: the epilogue dominates, keep more tiles
-        else if (t128 >= 48) tile = 2;
+        if (t256 >= 128 && Kpad >= 2048) tile = 11;  // short K: the epilogue dominates, keep more tiles
+        else if (t128 >= 48) tile = 9;
         else tile = 6;
         if (N <= 64) tile = 7;
     }
@@ -452,6 +459,12 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
                             : run_dma<256, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS);
         case 5: return run_dma<256, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS);
         case 6: return run_dma<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
+        case 7: return run_dma<64, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
+        case 8: return run_dma<128, 128, 2, 4, 64, 4>(OCS_GEMM_ARGS);    // 8 waves
+        case 9: return run_dma<128, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);    // 8 waves
+        case 10: return run_dma<256, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);   // 8 waves
+        case 11: return k128 ? run_dma<256, 128, 4, 2, 128, 3>(OCS_GEMM_ARGS)  // 8 waves
+                             : run_dma<256, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);
         default: return run_dma<64, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
     }
 }
