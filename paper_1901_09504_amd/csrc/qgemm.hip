@@ -230,9 +230,9 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
     int N, int ksteps, const float* __restrict__ scale_x, const float* __restrict__ scale_w,
     int32_t* __restrict__ acc_out, int64_t ldacc, float* __restrict__ Y, int64_t ldy, int tiles_n,
     unsigned total_tiles) {
-    constexpr int NW = WAVES_M * WAVES_N;  // waves per workgroup (4 or 8)
+    constexpr int NW = WAVES_M * WAVES_N;  // waves per workgroup (4, 8 or 16)
     constexpr int NT = NW * 64;
-    static_assert(NW == 4 || NW == 8, "4 or 8 waves");
+    static_assert(NW == 4 || NW == 8 || NW == 16, "4, 8 or 16 waves");
     static_assert(BK == 64 || BK == 128, "K-step of 64 or 128 bytes");
     static_assert(NBUF >= 3, "ring of at least three buffers");
     constexpr int CPR = BK / 16;
@@ -442,7 +442,9 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
         // that still gives most CUs a workgroup wins, and workgroups of 8 waves beat 4.
         const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 128);
         const int64_t t128 = ceil_div(M, 128) * ceil_div(N, 128);
-        if (t256 >= 128 && Kpad >= 2048) tile = 11;  // short K: the epilogue dominates, keep more tiles
+        const int64_t t256sq = ceil_div(M, 256) * ceil_div(N, 256);
+        if (t256sq >= 512 && Kpad >= 2048) tile = 12;  // two full rounds of the largest tile
+        else if (t256 >= 128 && Kpad >= 2048) tile = 11;  // short K: the epilogue dominates, keep more tiles
         else if (t128 >= 48) tile = 9;
         else tile = 6;
         if (N <= 64) tile = 7;
@@ -464,6 +466,11 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
         case 9: return run_dma<128, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);    // 8 waves
         case 10: return run_dma<256, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);   // 8 waves
         case 11: return k128 ? run_dma<256, 128, 4, 2, 128, 3>(OCS_GEMM_ARGS)  // 8 waves
+                             : run_dma<256, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);
+        case 12: return run_dma<256, 256, 2, 4, 64, 4>(OCS_GEMM_ARGS);   // 8 waves
+        case 13: return run_dma<256, 256, 4, 2, 64, 4>(OCS_GEMM_ARGS);   // 8 waves
+        case 14: return run_dma<256, 256, 4, 4, 64, 4>(OCS_GEMM_ARGS);   // 16 waves
+        case 15: return k128 ? run_dma<256, 128, 4, 4, 128, 3>(OCS_GEMM_ARGS)  // 16 waves
                              : run_dma<256, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);
         default: return run_dma<64, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
     }
