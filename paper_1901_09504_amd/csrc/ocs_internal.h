@@ -113,6 +113,8 @@ inline hipError_t launch_kernel(int family, F kernel, dim3 grid, dim3 block, uns
 // Launch-shape overrides (benchmarking only); < 0 means "use the default".
 struct Tuning {
     int act_grid = -1;  // workgroups of the split+quantize pass
+    int act_map = -1;   // lanes of that pass dealt over the output (0), over the input (1), by row shape (-1)
+    int act_un = -1;    // items in flight per lane in that pass (1, 2 or 4)
     int act_nt = 0;     // non-temporal loads of X in that pass (off: appended columns re-read X through L2)
     int gemm_tile = -1;
 };

@@ -208,6 +208,122 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
     }
 }
 
+// The same pass with the lanes dealt over the INPUT instead: one lane per 16-byte group of X,
+// the whole of X walked as one flat range, so every lane of every load instruction carries
+// data (in the output-ordered kernel above the lanes that land on appended columns and on the
+// padding load nothing, which for narrow rows is half of them).  Lane (row, d) writes output
+// dword d of its row and, when d < TD = D - Q, also dword Q + d: an appended or padding dword,
+// whose sources it gathers from the same row.  Requires 16-byte loads of X (Q = K/4 groups
+// per row) and TD <= Q.
+template <bool HALVE, typename Index>
+__global__ __launch_bounds__(kThreads) void expand_quantize_in_kernel(
+    const float* __restrict__ X, int64_t ldx, int64_t M, int C, int g, int s,
+    const int32_t* __restrict__ chan_src, const int32_t* __restrict__ chan_depth,
+    const float* thr, float qmax, int8_t* __restrict__ Xq, int D, int Q, unsigned magic,
+    float* scale_out) {
+    __shared__ int tail_col[kTailTable];
+    __shared__ int tail_dep[HALVE ? kTailTable : 1];
+    const int Ke = (C + s) * g;
+    const int TD = D - Q;                          // appended + padding dwords per row
+    for (int e = threadIdx.x; e < 4 * TD; e += kThreads) {
+        const int k = 4 * Q + e;
+        int col = -1, dep = 0;
+        if (k < Ke) {
+            const int j = k / g, t = k - j * g;
+            int src = chan_src ? chan_src[j] : j;
+            src = src < 0 ? 0 : (src >= C ? C - 1 : src);
+            col = src * g + t;
+            if (HALVE) dep = chan_depth[j];
+        }
+        tail_col[e] = col;
+        if (HALVE) tail_dep[e] = dep;
+    }
+    const Index total = (Index)M * (Index)Q;
+    const Index stride = (Index)gridDim.x * kThreads;
+    unsigned* __restrict__ out = reinterpret_cast<unsigned*>(Xq);
+
+    auto locate = [&](Index o, Index& row, int& d) {
+        if (sizeof(Index) == 4) {
+            unsigned q = __umulhi((unsigned)o, magic);
+            unsigned r = (unsigned)o - q * (unsigned)Q;
+            if (r >= (unsigned)Q) { ++q; r -= (unsigned)Q; }
+            row = (Index)q;
+            d = (int)r;
+        } else {
+            row = o / (Index)Q;
+            d = (int)(o - row * (Index)Q);
+        }
+    };
+    auto fetch_main = [&](Index o, f32x4& v, Index& row, int& d) {
+        row = 0;
+        d = 0;
+        if (o < total) {
+            locate(o, row, d);
+            v = *(reinterpret_cast<const f32x4*>(X + (int64_t)row * ldx) + d);
+        }
+    };
+    auto fetch_tail = [&](Index o, Index row, int d, f32x4& tv) {
+        if (o < total && d < TD) {
+            const float* xrow = X + (int64_t)row * ldx;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int col = tail_col[4 * d + e];
+                tv[e] = col >= 0 ? xrow[col] : 0.0f;
+            }
+        }
+    };
+
+    const unsigned nwg = gridDim.x, xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    const unsigned vwg = xcd * (nwg / 8) + (xcd < nwg % 8 ? xcd : nwg % 8) + slot;
+
+    auto emit = [&](Index row, int d, f32x4 v, f32x4 tv, float inv) {
+        const Index base = row * (Index)D;
+        if (HALVE) {
+            int j = (4 * d) / g, t = 4 * d - j * g;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                v[e] = v[e] * ldexpf(1.0f, -chan_depth[j]);
+                if (++t == g) { t = 0; ++j; }
+            }
+        }
+        out[base + (Index)d] = pack4(code_bits(v[0], inv, qmax), code_bits(v[1], inv, qmax),
+                                     code_bits(v[2], inv, qmax), code_bits(v[3], inv, qmax));
+        if (d < TD) {
+            if (HALVE) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) tv[e] = tv[e] * ldexpf(1.0f, -tail_dep[4 * d + e]);
+            }
+            out[base + (Index)(Q + d)] =
+                pack4(code_bits(tv[0], inv, qmax), code_bits(tv[1], inv, qmax),
+                      code_bits(tv[2], inv, qmax), code_bits(tv[3], inv, qmax));
+        }
+    };
+
+    Index o = (Index)vwg * kThreads + threadIdx.x;
+    f32x4 cur = {}, nxt = {}, tcur = {}, tnxt = {};
+    Index row = 0, nrow = 0;
+    int d = 0, nd = 0;
+    fetch_main(o, cur, row, d);       // requested before anything waits on the threshold
+    const float T = *thr;
+    const float inv = inv_step_of(T, qmax);
+    if (scale_out != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
+        scale_out[0] = T;
+        scale_out[1] = T / qmax;
+    }
+    __syncthreads();                  // the column table is complete
+    fetch_tail(o, row, d, tcur);
+
+    for (; o < total; o += stride) {
+        fetch_main(o + stride, nxt, nrow, nd);
+        fetch_tail(o + stride, nrow, nd, tnxt);
+        emit(row, d, cur, tcur, inv);
+        cur = nxt;
+        tcur = tnxt;
+        row = nrow;
+        d = nd;
+    }
+}
+
 hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C, int g, int s,
                                   const int32_t* chan_src, const int32_t* chan_depth,
                                   const float* thr, float qmax, int8_t* Xq, int64_t ldq,
@@ -223,21 +339,54 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
     int64_t grid = 256 * 8;  // 8 workgroups of 4 waves on each of the 256 CUs
     if (tuning().act_grid > 0) grid = tuning().act_grid;
     if (grid > ceil_div(total, kThreads)) grid = ceil_div(total, kThreads);
-    const bool wide = total + 4 * grid * kThreads >= ((int64_t)1 << 32);
+    // Lanes dealt over the input when its rows allow it (see expand_quantize_in_kernel)
+    const int Q = main_units, TD = D - Q;
+    // Measured: it wins (up to 1.45x) once a quarter or more of a row's output dwords are
+    // appended columns or padding (rows of 64 to 128 values); for wider rows the two are level.
+    const int map = tuning().act_map;
+    const bool by_input = map < 0 ? 4 * TD >= D : map != 0;
+    if (by_input && vec_ok && Q >= 1 && TD <= Q && 4 * TD <= kTailTable) {
+        const int64_t total_in = M * Q;
+        int64_t gin = 256 * 8;
+        if (tuning().act_grid > 0) gin = tuning().act_grid;
+        if (gin > ceil_div(total_in, kThreads)) gin = ceil_div(total_in, kThreads);
+        // output dword indices reach M*D; the prefetch looks two strides past the item
+        const bool wide_in = total + 2 * gin * kThreads >= ((int64_t)1 << 32);
+        const unsigned magic_q = (unsigned)((((uint64_t)1) << 32) / (uint64_t)Q);
+#define OCS_LAUNCH_IN(H, I_)                                                                       \
+    launch_kernel(kTimeSplitQuantize, expand_quantize_in_kernel<H, I_>, dim3((unsigned)gin),      \
+                  dim3(kThreads), 0, stream, X, ldx, M, C, g, s, chan_src, chan_depth, thr, qmax,  \
+                  Xq, D, Q, magic_q, scale_out)
+        if (wide_in) return halve ? OCS_LAUNCH_IN(true, uint64_t) : OCS_LAUNCH_IN(false, uint64_t);
+        return halve ? OCS_LAUNCH_IN(true, uint32_t) : OCS_LAUNCH_IN(false, uint32_t);
+#undef OCS_LAUNCH_IN
+    }
+
+    int un = tuning().act_un;
+    if (un != 1 && un != 2 && un != 4) un = 1;
+    // the prefetch looks up to 2*un strides past the item being processed
+    const bool wide = total + 2 * un * grid * kThreads >= ((int64_t)1 << 32);
     const unsigned magic = (unsigned)((((uint64_t)1) << 32) / (uint64_t)D);  // D >= 16
 
     hipError_t err = hipSuccess;
-#define OCS_LAUNCH_EQ(H, N_, I_)                                                                  \
-    err = launch_kernel(kTimeSplitQuantize, expand_quantize_kernel<H, N_, 1, I_>, dim3((unsigned)grid), \
+#define OCS_LAUNCH_EQ(H, N_, U_, I_)                                                              \
+    err = launch_kernel(kTimeSplitQuantize, expand_quantize_kernel<H, N_, U_, I_>, dim3((unsigned)grid), \
                   dim3(kThreads), 0, stream, X, ldx, M, C, g, s, chan_src, chan_depth, thr, qmax,  \
                   Xq, D, main_units, magic, scale_out)
+#define OCS_LAUNCH_U(H, N_, I_)                                                                   \
+    do {                                                                                          \
+        if (un == 4) OCS_LAUNCH_EQ(H, N_, 4, I_);                                                 \
+        else if (un == 2) OCS_LAUNCH_EQ(H, N_, 2, I_);                                            \
+        else OCS_LAUNCH_EQ(H, N_, 1, I_);                                                         \
+    } while (0)
     if (wide) {
-        if (halve) { if (nt) OCS_LAUNCH_EQ(true, true, uint64_t); else OCS_LAUNCH_EQ(true, false, uint64_t); }
-        else       { if (nt) OCS_LAUNCH_EQ(false, true, uint64_t); else OCS_LAUNCH_EQ(false, false, uint64_t); }
+        if (halve) { if (nt) OCS_LAUNCH_U(true, true, uint64_t); else OCS_LAUNCH_U(true, false, uint64_t); }
+        else       { if (nt) OCS_LAUNCH_U(false, true, uint64_t); else OCS_LAUNCH_U(false, false, uint64_t); }
     } else {
-        if (halve) { if (nt) OCS_LAUNCH_EQ(true, true, uint32_t); else OCS_LAUNCH_EQ(true, false, uint32_t); }
-        else       { if (nt) OCS_LAUNCH_EQ(false, true, uint32_t); else OCS_LAUNCH_EQ(false, false, uint32_t); }
+        if (halve) { if (nt) OCS_LAUNCH_U(true, true, uint32_t); else OCS_LAUNCH_U(true, false, uint32_t); }
+        else       { if (nt) OCS_LAUNCH_U(false, true, uint32_t); else OCS_LAUNCH_U(false, false, uint32_t); }
     }
+#undef OCS_LAUNCH_U
 #undef OCS_LAUNCH_EQ
     return err;
 }

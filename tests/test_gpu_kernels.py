@@ -35,11 +35,16 @@ def _tensor(rng, rows, cols, kind):
 @pytest.mark.parametrize("rows,cols", [(1, 1), (3, 5), (7, 64), (33, 147), (130, 269), (65, 1000),
                                        (257, 2304), (19, 4099)])
 @pytest.mark.parametrize("bits", [2, 5, 8])
-def test_quantize_dynamic(rows, cols, bits):
+@pytest.mark.parametrize("act_map", [0, 1])   # lanes dealt over the output / over the input
+def test_quantize_dynamic(rows, cols, bits, act_map):
     rng = np.random.default_rng(rows * 1000 + cols + bits)
     x = _tensor(rng, rows, cols, "heavy")
     q_ref, s_ref = ref.quantize(x, bits, ldq=B.ocs_padded_cols(cols))
-    q, s = gpu_quantize(x, bits)
+    B.ocs_tune("act_map", act_map)
+    try:
+        q, s = gpu_quantize(x, bits)
+    finally:
+        B.ocs_tune("act_map", -1)
     assert np.array_equal(s, s_ref)
     assert np.array_equal(q, q_ref)
 
@@ -159,14 +164,19 @@ def test_split_weights_dup_mode():
                                      (77, 2048, 1, 205), (50, 64, 4, 300), (9, 512, 9, 26)])
 @pytest.mark.parametrize("halve", [False, True])
 @pytest.mark.parametrize("threshold", [None, 3.0])
-def test_split_act(M, C, g, s, halve, threshold):
+@pytest.mark.parametrize("act_map", [0, 1])   # lanes dealt over the output / over the input
+def test_split_act(M, C, g, s, halve, threshold, act_map):
     rng = np.random.default_rng(M + C + g + s)
     X = _tensor(rng, M, C * g, "heavy")
     sel = ref.split_weights(X if halve else _tensor(rng, 9, C * g, "heavy"), C, g, s)
     cs, cd = sel["chan_src"], (sel["chan_depth"] if halve else None)
     ldq = B.ocs_padded_cols((C + s) * g)
     q_ref, s_ref, _ = ref.split_act(X, C, g, cs, cd, s, 8, threshold=threshold, clip_ratio=0.9, ldq=ldq)
-    q, sc = gpu_split_act(X, C, g, cs, cd, s, 8, threshold=threshold, clip_ratio=0.9)
+    B.ocs_tune("act_map", act_map)
+    try:
+        q, sc = gpu_split_act(X, C, g, cs, cd, s, 8, threshold=threshold, clip_ratio=0.9)
+    finally:
+        B.ocs_tune("act_map", -1)
     assert np.array_equal(sc, s_ref)
     assert np.array_equal(q, q_ref)
 
