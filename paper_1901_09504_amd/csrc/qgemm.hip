@@ -244,8 +244,11 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
     static_assert((NBUF - 2) * LPS < 64, "prefetch ring exceeds the vmcnt range");
     constexpr int KS = BK / 32;
 
-    __shared__ __align__(1024) int8_t lds_a[NBUF][BM * BK];
-    __shared__ __align__(1024) int8_t lds_b[NBUF][BN * BK];
+    // one array: the A ring, then the B ring; the epilogue reuses all of it
+    constexpr int RING_BYTES = NBUF * (BM + BN) * BK;
+    __shared__ __align__(1024) int8_t lds[RING_BYTES];
+    int8_t (*lds_a)[BM * BK] = reinterpret_cast<int8_t (*)[BM * BK]>(&lds[0]);
+    int8_t (*lds_b)[BN * BK] = reinterpret_cast<int8_t (*)[BN * BK]>(&lds[NBUF * BM * BK]);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -377,24 +380,266 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
 #pragma unroll
     for (int p = 0; p < NBUF; ++p)
         if (kt0 + p < ksteps) step(p, kt0 + p);
-    wait_vmcnt<0>();  // surplus (clamped) loads must land before the workgroup's LDS is released
+    wait_vmcnt<0>();  // surplus (clamped) loads must land before the ring is reused below
+    __syncthreads();  // every wave has read its last fragments: the ring is free
 
+    // Epilogue.  An accumulator block leaves the MFMA with lane l holding ONE column and 16
+    // rows, which as stores would be 4 bytes per lane (measured: a CU retires such stores at
+    // ~16 B/clk, which made the output-bound shapes run at half the HBM write rate).  Each wave
+    // therefore turns its accumulators through a private piece of the free ring, 32 rows at a
+    // time, and reads them back with each lane holding four consecutive columns of one row:
+    // 16-byte stores, whole 128-byte lines per row.  Only this wave touches its piece and a
+    // wave's LDS accesses execute in issue order, so no barrier is needed.
+    constexpr int WAVE_STAGE = RING_BYTES / NW;          // bytes of LDS per wave
+    static_assert(WAVE_STAGE >= 32 * WN * 4, "ring too small to stage 32 rows of a wave's tile");
+    static_assert(WAVE_STAGE % 16 == 0, "staging area must keep 16-byte alignment");
+    int32_t* stage = reinterpret_cast<int32_t*>(&lds[wave * WAVE_STAGE]);
+    constexpr int LPR = WN / 4;            // lanes per row of the wave's tile (8, 16 or 32)
+    constexpr int RPI = 64 / LPR;          // rows per 16-byte access of the wave
     const float scale = scale_x[1] * scale_w[1];
+    const bool vec_y = (reinterpret_cast<uintptr_t>(Y) % 16 == 0) && (ldy % 4 == 0);
+    const bool vec_a = acc_out != nullptr && (reinterpret_cast<uintptr_t>(acc_out) % 16 == 0) &&
+                       (ldacc % 4 == 0);
+    const int srow = lane / LPR, scol = (lane % LPR) * 4;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int c = col0 + wn * WN + j * 32 + (lane & 31);
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int r = row0 + wm * WM + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-                if (r < M && c < N) {
-                    const int a = acc[i][j][v];
-                    Y[(int64_t)r * ldy + c] = (float)a * scale;
-                    if (acc_out) acc_out[(int64_t)r * ldacc + c] = a;
+            for (int v = 0; v < 16; ++v)
+                stage[((v >> 2) * 8 + (lane >> 5) * 4 + (v & 3)) * WN + j * 32 + (lane & 31)] =
+                    acc[i][j][v];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int it = 0; it < 32 / RPI; ++it) {
+            const int rr = it * RPI + srow;
+            const i32x4 a = *reinterpret_cast<const i32x4*>(&stage[rr * WN + scol]);
+            const int r = row0 + wm * WM + i * 32 + rr;
+            const int c = col0 + wn * WN + scol;
+            if (r < M && c < N) {
+                float* yp = Y + (int64_t)r * ldy + c;
+                if (vec_y && c + 3 < N) {
+                    f32x4 y;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) y[e] = (float)a[e] * scale;
+                    *reinterpret_cast<f32x4*>(yp) = y;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (c + e < N) yp[e] = (float)a[e] * scale;
+                }
+                if (acc_out) {
+                    int32_t* ap = acc_out + (int64_t)r * ldacc + c;
+                    if (vec_a && c + 3 < N) {
+                        *reinterpret_cast<i32x4*>(ap) = a;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (c + e < N) ap[e] = a[e];
+                    }
                 }
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();   // the reads are issued before the next block's writes
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Short-K variant: the whole K extent of the tile's operands (ksteps steps of 64 bytes) is
+// requested into LDS up front, with no ring and no surplus requests, multiplied after ONE wait
+// and barrier, and the workgroup keeps no more LDS than that (dynamic size).  For the layers
+// with a few hundred input channels the GEMM is a stream of 4*N output bytes per row: what
+// matters there is how many workgroups a CU holds, so that one's request latency hides behind
+// the others' stores.  Per K-step the LDS holds BM rows of A, then BN rows of B, 64 bytes each,
+// chunk-swizzled like the ring kernel's.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void lds_dma16(const int8_t* g, unsigned lds_addr) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    const unsigned m0 = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(g), "s"(m0)
+                 : "memory");
+#else
+    (void)g;
+    (void)lds_addr;
+#endif
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+__global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_wholek_kernel(
+    const int8_t* __restrict__ Xq, int64_t ldx, const int8_t* __restrict__ Wq, int64_t ldw, int M,
+    int N, int ksteps, const float* __restrict__ scale_x, const float* __restrict__ scale_w,
+    int32_t* __restrict__ acc_out, int64_t ldacc, float* __restrict__ Y, int64_t ldy, int tiles_n,
+    unsigned total_tiles) {
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int ROWS = BM + BN;          // LDS rows per K-step
+    constexpr int STEP_BYTES = ROWS * 64;
+    constexpr int BLOCKS = ROWS / 16;      // 1 KB pieces per K-step, 16 rows each
+    static_assert(BM % 16 == 0 && BN % 16 == 0, "a 1 KB piece must not straddle the operands");
+    static_assert(WM % 32 == 0 && WN % 32 == 0 && TM >= 1 && TN >= 1, "wave tile of 32x32 blocks");
+
+    extern __shared__ __align__(1024) int8_t dlds[];
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef __attribute__((address_space(3))) int8_t* lptr_t;
+    const unsigned lds0 = (unsigned)(uintptr_t)(lptr_t)&dlds[0];
+#else
+    const unsigned lds0 = 0;
+#endif
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const unsigned tile = xcd_remap(blockIdx.x, total_tiles);
+    const int bm = (int)(tile / tiles_n), bn = (int)(tile % tiles_n);
+    const int row0 = bm * BM, col0 = bn * BN;
+
+    // piece b of a K-step: LDS rows 16b .. 16b+15; lane l fills row 16b + l/4, chunk slot l%4
+    for (int b = wave; b < BLOCKS; b += NW) {
+        const int r = b * 16 + (lane >> 2), c = lane & 3;
+        const int8_t* src;
+        if (r < BM) {
+            int gr = row0 + r;
+            gr = gr < M ? gr : M - 1;      // rows past the edge re-read the last row; never stored
+            src = Xq + (int64_t)gr * ldx + swz<64>(r, c) * 16;
+        } else {
+            int gr = col0 + (r - BM);
+            gr = gr < N ? gr : N - 1;
+            src = Wq + (int64_t)gr * ldw + swz<64>(r - BM, c) * 16;
+        }
+        for (int kt = 0; kt < ksteps; ++kt)
+            lds_dma16(src + (int64_t)kt * 64, lds0 + kt * STEP_BYTES + b * 1024);
+    }
+
+    i32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    const int frag_row = lane & 31, frag_half = lane >> 5;
+    for (int kt = 0; kt < ksteps; ++kt) {
+        const int8_t* base = &dlds[kt * STEP_BYTES];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            i32x4 a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int r = wm * WM + i * 32 + frag_row;
+                a[i] = *reinterpret_cast<const i32x4*>(
+                    &base[r * 64 + swz<64>(r, ks * 2 + frag_half) * 16]);
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int r = wn * WN + j * 32 + frag_row;
+                b[j] = *reinterpret_cast<const i32x4*>(
+                    &base[(BM + r) * 64 + swz<64>(r, ks * 2 + frag_half) * 16]);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    }
+    __syncthreads();  // the operands are dead: their LDS becomes the staging area
+
+    // Epilogue as in the ring kernel (each wave turns its accumulators through a private piece
+    // of LDS into rows of 16-byte stores), 8 rows at a time to keep the footprint small.
+    int32_t* stage = reinterpret_cast<int32_t*>(&dlds[wave * (8 * WN * 4)]);
+    constexpr int LPR = WN / 4;
+    const float scale = scale_x[1] * scale_w[1];
+    const bool vec_y = (reinterpret_cast<uintptr_t>(Y) % 16 == 0) && (ldy % 4 == 0);
+    const bool vec_a = acc_out != nullptr && (reinterpret_cast<uintptr_t>(acc_out) % 16 == 0) &&
+                       (ldacc % 4 == 0);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    stage[((lane >> 5) * 4 + e) * WN + j * 32 + (lane & 31)] = acc[i][j][q * 4 + e];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int it = 0; it < (8 * LPR) / 64; ++it) {
+                const int idx = it * 64 + lane;
+                const int rr = idx / LPR, cc = (idx % LPR) * 4;
+                const i32x4 a = *reinterpret_cast<const i32x4*>(&stage[rr * WN + cc]);
+                const int r = row0 + wm * WM + i * 32 + q * 8 + rr;
+                const int c = col0 + wn * WN + cc;
+                if (r < M && c < N) {
+                    float* yp = Y + (int64_t)r * ldy + c;
+                    if (vec_y && c + 3 < N) {
+                        f32x4 y;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) y[e] = (float)a[e] * scale;
+                        *reinterpret_cast<f32x4*>(yp) = y;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (c + e < N) yp[e] = (float)a[e] * scale;
+                    }
+                    if (acc_out) {
+                        int32_t* ap = acc_out + (int64_t)r * ldacc + c;
+                        if (vec_a && c + 3 < N) {
+                            *reinterpret_cast<i32x4*>(ap) = a;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (c + e < N) ap[e] = a[e];
+                        }
+                    }
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+}
+
+constexpr int64_t kWholeKMaxLds = 160 * 1024;  // LDS of one CU
+
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+static int64_t wholek_lds_bytes(int64_t Kpad) {
+    const int64_t operands = (Kpad / 64) * (BM + BN) * 64;
+    const int64_t staging = (int64_t)WAVES_M * WAVES_N * 8 * (BN / WAVES_N) * 4;
+    return operands > staging ? operands : staging;
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+static hipError_t run_wholek(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw,
+                             int64_t M, int64_t N, int64_t Kpad, const float* scale_x,
+                             const float* scale_w, int32_t* acc_out, int64_t ldacc, float* Y,
+                             int64_t ldy, hipStream_t stream) {
+    const int64_t lds = wholek_lds_bytes<BM, BN, WAVES_M, WAVES_N>(Kpad);
+    if (Kpad < 64 || Kpad % 64 != 0 || lds > kWholeKMaxLds) return hipErrorInvalidValue;
+    // more than 64 KB of dynamic LDS has to be opted into, once per kernel
+    static bool opted_in = false;
+    if (lds > 65536 && !opted_in) {
+        hipError_t e = hipFuncSetAttribute(
+            reinterpret_cast<const void*>(&qgemm_wholek_kernel<BM, BN, WAVES_M, WAVES_N>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWholeKMaxLds);
+        if (e != hipSuccess) return e;
+        opted_in = true;
+    }
+    const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
+    const int64_t total = tiles_m * tiles_n;
+    return launch_kernel(kTimeGemm, qgemm_wholek_kernel<BM, BN, WAVES_M, WAVES_N>,
+                         dim3((unsigned)total), dim3(WAVES_M * WAVES_N * 64), (unsigned)lds, stream,
+                         Xq, ldx, Wq, ldw, (int)M, (int)N, (int)(Kpad / 64), scale_x, scale_w,
+                         acc_out, ldacc, Y, ldy, (int)tiles_n, (unsigned)total);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF>
@@ -437,17 +682,19 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
                         hipStream_t stream) {
     int tile = tuning().gemm_tile;
     if (tile < 0) {
-        // Measured on MI355X: a CU draws operands through its vector-memory path at only
-        // ~16-30 B/clk, rising with the number of waves that issue loads, so the largest tile
-        // that still gives most CUs a workgroup wins, and workgroups of 8 waves beat 4.
+        // Measured on MI355X.  A CU draws operands through its vector-memory path at only
+        // ~16-30 B/clk, rising with the number of waves that issue loads: the largest tile that
+        // still gives most CUs a workgroup wins, and workgroups of 8 waves beat 4.  Up to 320
+        // bytes of K the layer is a stream of output rows and the whole-K kernel wins (1.2-1.5x).
         const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 128);
         const int64_t t128 = ceil_div(M, 128) * ceil_div(N, 128);
         const int64_t t256sq = ceil_div(M, 256) * ceil_div(N, 256);
-        if (t256sq >= 512 && Kpad >= 2048) tile = 12;  // two full rounds of the largest tile
-        else if (t256 >= 128 && Kpad >= 2048) tile = 11;  // short K: the epilogue dominates, keep more tiles
+        if (Kpad <= 320) tile = (N <= 64 && Kpad > 128) ? 17 : 16;
+        else if (N <= 64) tile = 6;
+        else if (t256sq >= 512 && Kpad >= 2048) tile = 12;  // two full rounds of the largest tile
+        else if (t256 >= 128) tile = 11;
         else if (t128 >= 48) tile = 9;
         else tile = 6;
-        if (N <= 64) tile = 7;
     }
     // a 128-byte K-step needs the K extent to be a multiple of 128
     const bool k128 = Kpad % 128 == 0;
@@ -472,6 +719,18 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
         case 14: return run_dma<256, 256, 4, 4, 64, 4>(OCS_GEMM_ARGS);   // 16 waves
         case 15: return k128 ? run_dma<256, 128, 4, 4, 128, 3>(OCS_GEMM_ARGS)  // 16 waves
                              : run_dma<256, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);
+        // whole-K variants; a K extent too long for them falls back to a ring variant
+#define OCS_WHOLEK(BM_, BN_, WM_, WN_, FALLBACK)                                                   \
+    (wholek_lds_bytes<BM_, BN_, WM_, WN_>(Kpad) <= kWholeKMaxLds                                    \
+         ? run_wholek<BM_, BN_, WM_, WN_>(OCS_GEMM_ARGS)                                            \
+         : FALLBACK)
+        case 16: return OCS_WHOLEK(128, 128, 4, 2, (run_dma<128, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS)));
+        case 17: return OCS_WHOLEK(128, 64, 4, 1, (run_dma<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS)));
+        case 18: return OCS_WHOLEK(64, 64, 2, 2, (run_dma<64, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS)));
+        case 19: return OCS_WHOLEK(128, 256, 2, 4, (run_dma<128, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS)));
+        case 20: return OCS_WHOLEK(256, 128, 4, 2, (run_dma<256, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS)));
+        case 21: return OCS_WHOLEK(128, 128, 2, 2, (run_dma<128, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS)));
+#undef OCS_WHOLEK
         default: return run_dma<64, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
     }
 }

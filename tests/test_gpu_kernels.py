@@ -183,7 +183,7 @@ def test_split_act(M, C, g, s, halve, threshold, act_map):
 
 # ---- ocs_qgemm -------------------------------------------------------------------------------
 
-@pytest.mark.parametrize("tile", list(range(16)))
+@pytest.mark.parametrize("tile", list(range(22)))
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (64, 256, 269), (130, 70, 64), (257, 129, 200), (700, 300, 1035),
                                    (300, 520, 2358), (128, 128, 4842)])
 def test_qgemm(tile, M, N, K):
