@@ -33,8 +33,8 @@ METRIC = "expanded int8 GEMM TOPS (% MFMA peak); split+quantize GB/s (% HBM)"
 # runs (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for the plain
 # copy kernel of known size launched after the timed region (profiles/x2_config2_hbm_traffic.md).
 # Valid only for the kernel source it was measured on: reported as null once that file changes.
-X2_TRAFFIC = {"quantize_hip_sha256": "ab1208137231d7038cfe9b533458fd67442d9848ccfb3a4bf09381f3bdac9f6e",
-              "bytes_per_launch": 145615191}
+X2_TRAFFIC = {"quantize_hip_sha256": "5de5a62c3da25c0900a0e784b14ae286a7028db7090a783b8f09586406b472ee",
+              "bytes_per_launch": 145603201}
 
 
 def x2_traffic():
