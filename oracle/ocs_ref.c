@@ -15,6 +15,8 @@
  *   Sec. 1     clipping = narrowing the grid, i.e. saturating beyond a threshold
  *   Sec. 5.2   OCS first, clip afterwards
  *   Sec. 3.2   Eq. 2, the linear layer, evaluated on the integer codes
+ *   Sec. 3.3   quantization-aware splitting of the weights, with that section's
+ *              rounding function floor(x + 1/2)
  *
  * Precision.  A code is an integer decided by floating point, so the decision is taken
  * in the arithmetic the GPU kernels use: fp32, one correctly rounded division
@@ -24,8 +26,9 @@
  * Parity pins live in tests/test_oracle_pins.py (functional identity of the split
  * layer, halving of every split channel's maximum, greedy == brute force, the grid's
  * definition, the s = 0 case against a library matmul, the w = 3 example of Sec. 3.3,
- * Table 4's weight-size row).  Unpinned: nothing in this file; the paper's accuracy
- * tables are not reproduced (datasets and trained weights are needed for those).
+ * Table 4's weight-size row, the rounded QA pair adding up to the rounded original).
+ * Unpinned: nothing in this file; the paper's accuracy tables are not reproduced
+ * (datasets and trained weights are needed for those).
  *
  * Build: gcc -O2 -std=c99 -ffp-contract=off -fno-fast-math -fopenmp -shared -fPIC
  * OpenMP only partitions independent rows over threads; it changes no arithmetic.
@@ -183,6 +186,99 @@ int ref_quantize(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bi
     for (int64_t i = 0; i < rows; ++i) {
         for (int64_t k = 0; k < cols; ++k) q[i * ldq + k] = code_of(x[i * ldx + k], inv, qmax);
         for (int64_t k = cols; k < ldq; ++k) q[i * ldq + k] = 0;
+    }
+    return REF_OK;
+}
+
+/* Sec. 3.3's rounding function Q(x) = floor(x + 1/2) on the saturated fp32 product: one
+ * fp32 add, then floor.  Used for quantization-aware split weights only. */
+static int8_t code_of_half_up(float v, float inv_step, float qmax) {
+    float p = v * inv_step;
+    if (p > qmax) p = qmax;
+    if (p < -qmax) p = -qmax;
+    return (int8_t)floorf(p + 0.5f);
+}
+
+/*
+ * Sec. 3.3, quantization-aware (QA) splitting of the weights, followed by Eq. 1 with the
+ * rounding function of that section.
+ *
+ * In units of the grid step a QA split sends w to the pair ((w - 1/2)/2, (w + 1/2)/2), so
+ * that the two rounded members add up to the rounded original.  The paper leaves open how
+ * the grid step can be known before the splits that determine it, and which member stays
+ * in place.  Reading taken here:
+ *   1. the splits are chosen, and the threshold fixed, by the plain-halving procedure of
+ *      Sec. 3.4 / Eq. 3 on the same tensor: T = clip_ratio * max|halved tensor|,
+ *      step = T / qmax;
+ *   2. the same split list is then replayed on the original tensor with the QA pair, in
+ *      tensor units: the channel that keeps its index becomes (v - step/2)/2, the appended
+ *      copy (v + step/2)/2 (the order in which the pair is written);
+ *   3. fp32, one subtraction (or addition) and one exact halving per split step;
+ *   4. codes by Q(x) = floor(x + 1/2) with the threshold T of step 1.
+ * chan_path[j] records expanded channel j's history, one bit per split it went through,
+ * first split in bit 0: 0 = kept its index (minus member), 1 = was the appended copy (plus
+ * member).  A lineage grows only like log2(s) (equal copies are split in turn), so 32 bits
+ * are ample; more than 31 splits on one lineage is refused all the same.
+ * T_out [rows, (C+s)*g] receives the QA-split fp32 tensor, q its codes (pad columns zero),
+ * scale_out = {T, step}.
+ */
+int ref_split_weights_qa(const float *T, int64_t rows, int C, int g, int64_t ld, int s, int bits,
+                         float clip_ratio, int32_t *split_src, int32_t *chan_src,
+                         int32_t *chan_depth, uint32_t *chan_path, float *T_out, int64_t ldo,
+                         int8_t *q, int64_t ldq, float *scale_out) {
+    if (!T || !T_out || !chan_src || !chan_depth || !chan_path || !q || !scale_out) return REF_E_ARG;
+    if (s > 0 && !split_src) return REF_E_ARG;
+    if (rows <= 0 || C <= 0 || g <= 0 || s < 0 || bits < 2 || bits > 8) return REF_E_ARG;
+    int64_t K = (int64_t)C * g, Ke = (int64_t)(C + s) * g;
+    if (ld < K || ldo < Ke || ldq < Ke) return REF_E_ARG;
+    float qmax = (float)((1 << (bits - 1)) - 1);
+
+    /* 1. selection and threshold from the plain-halving procedure */
+    float *halved = (float *)malloc((size_t)rows * (size_t)Ke * sizeof(float));
+    if (!halved) return REF_E_NOMEM;
+    float m = 0.0f;
+    int rc = ref_split_weights(T, rows, C, g, ld, s, REF_MODE_HALVE, split_src, chan_src,
+                               chan_depth, halved, Ke, &m);
+    free(halved);
+    if (rc != REF_OK) return rc;
+    float Tthr = clip_ratio * m;
+    float step = Tthr / qmax;
+    float half_step = step * 0.5f;
+
+    /* 2./3. replay the list with the QA pair */
+    for (int64_t n = 0; n < rows; ++n)
+        for (int64_t k = 0; k < K; ++k) T_out[n * ldo + k] = T[n * ld + k];
+    int *len = (int *)calloc((size_t)(C + s), sizeof(int));
+    if (!len) return REF_E_NOMEM;
+    for (int j = 0; j < C + s; ++j) chan_path[j] = 0u;
+    for (int i = 0; i < s; ++i) {
+        int pick = split_src[i], cur = C + i;
+        if (len[pick] >= 31) {
+            free(len);
+            return REF_E_ARG;
+        }
+        for (int64_t n = 0; n < rows; ++n)
+            for (int t = 0; t < g; ++t) {
+                float v = T_out[n * ldo + (int64_t)pick * g + t];
+                float lo = v - half_step;
+                float hi = v + half_step;
+                T_out[n * ldo + (int64_t)pick * g + t] = lo * 0.5f;
+                T_out[n * ldo + (int64_t)cur * g + t] = hi * 0.5f;
+            }
+        chan_path[cur] = chan_path[pick] | (1u << len[pick]);
+        len[pick] += 1;
+        len[cur] = len[pick];
+    }
+    free(len);
+
+    /* 4. codes */
+    float inv = inv_step_of(Tthr, qmax);
+    scale_out[0] = Tthr;
+    scale_out[1] = step;
+    for (int64_t n = 0; n < rows; ++n) {
+        for (int64_t k = 0; k < Ke; ++k)
+            q[n * ldq + k] = code_of_half_up(T_out[n * ldo + k], inv, qmax);
+        for (int64_t k = Ke; k < ldq; ++k) q[n * ldq + k] = 0;
     }
     return REF_OK;
 }

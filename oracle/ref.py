@@ -85,6 +85,31 @@ def split_weights(T, Cn, g, s, mode=MODE_HALVE, split_src=None):
     return dict(split_src=ss[:s], chan_src=cs, chan_depth=cd, T_out=out, max=float(mx[0]))
 
 
+def split_weights_qa(T, Cn, g, s, bits, clip_ratio=1.0, ldq=None):
+    """Sec. 3.3: quantization-aware split of T [rows, C*g], then codes by floor(x + 1/2).
+
+    Returns dict(split_src, chan_src, chan_depth, chan_path, T_out, q [rows, ldq], scale)."""
+    T = np.ascontiguousarray(T, dtype=np.float32)
+    rows = T.shape[0]
+    assert T.shape[1] == Cn * g
+    Ke = (Cn + s) * g
+    ldq = Ke if ldq is None else int(ldq)
+    ss = np.zeros(max(s, 1), dtype=np.int32)
+    cs = np.zeros(Cn + s, dtype=np.int32)
+    cd = np.zeros(Cn + s, dtype=np.int32)
+    cp = np.zeros(Cn + s, dtype=np.uint32)
+    out = np.zeros((rows, Ke), dtype=np.float32)
+    q = np.full((rows, ldq), 99, dtype=np.int8)
+    sc = np.zeros(2, dtype=np.float32)
+    rc = lib().ref_split_weights_qa(
+        _p(T, C.c_float), C.c_int64(rows), C.c_int(Cn), C.c_int(g), C.c_int64(T.shape[1]),
+        C.c_int(s), C.c_int(bits), C.c_float(clip_ratio), _p(ss, C.c_int32), _p(cs, C.c_int32),
+        _p(cd, C.c_int32), _p(cp, C.c_uint32), _p(out, C.c_float), C.c_int64(Ke),
+        _p(q, C.c_int8), C.c_int64(ldq), _p(sc, C.c_float))
+    _check(rc, "ref_split_weights_qa")
+    return dict(split_src=ss[:s], chan_src=cs, chan_depth=cd, chan_path=cp, T_out=out, q=q, scale=sc)
+
+
 def quantize(x, bits, threshold=None, clip_ratio=1.0, ldq=None):
     """Eq. 1 (+ clip).  Returns (codes [rows, ldq] int8, scale float32[2] = {T, step})."""
     x = np.ascontiguousarray(x, dtype=np.float32)

@@ -385,3 +385,85 @@ def test_activation_ocs_threshold_follows_split_tensor():
     assert sx[0] < np.abs(X).max()
     q2, s2 = ref.quantize(Xf, 6)
     assert np.array_equal(q2, Xq) and np.array_equal(s2, sx)
+
+
+# ---- Sec. 3.3: quantization-aware splitting ----------------------------------------------
+
+def _step_one_layer(extra_rows, dominant=14.0, others=0.25):
+    """Two-channel weight tensor whose channel 0 holds `dominant` (and the extra rows' values)
+    and is the one that gets split; with 4 bits and one split of 14 the grid step is exactly 1."""
+    col0 = [dominant] + list(extra_rows)
+    return np.array([[v, others] for v in col0], dtype=np.float32)
+
+
+def test_qa_split_w3_example():
+    row = _read_table("sec3_3_qa_split_w3.txt")[0]
+    w, lo, hi = float(row["w"]), float(row["lo"]), float(row["hi"])
+    W = _step_one_layer([w])
+    r = ref.split_weights_qa(W, 2, 1, 1, 4)
+    assert r["scale"].tolist() == [7.0, 1.0]                 # T = 14/2, step = T/qmax = 1
+    assert r["split_src"].tolist() == [0] and r["chan_path"].tolist() == [0, 0, 1]
+    assert r["T_out"][1].tolist() == [lo, 0.25, hi]          # the member that stays takes "-"
+    assert r["q"][1].tolist() == [int(row["Qlo"]), 0, int(row["Qhi"])]
+    assert int(r["q"][1, 0]) + int(r["q"][1, 2]) == int(row["Qw"])
+
+
+def test_qa_members_add_up_to_the_rounded_original():
+    # Sec. 3.3's claim Q((w-1/2)/2) + Q((w+1/2)/2) = Q(w), Q(x) = floor(x + 1/2), also through
+    # repeated splits of the same lineage: channel 0 (max 28) is split into four quarter copies
+    # (three splits: 28 -> 14,14 -> 7,7,14 -> 7,7,7,7), T = 7, step 1.  Every value is a
+    # multiple of 1/16, so all fp32 steps are exact and the identity must hold for each row.
+    ws = np.arange(-27 * 16, 27 * 16 + 1, 3, dtype=np.float64) / 16.0     # includes exact ties
+    W = _step_one_layer(ws, dominant=28.0, others=2.5)
+    W[2, 1], W[3, 1], W[4, 1] = -2.5, 3.5, -0.5                         # ties in an unsplit channel
+    r = ref.split_weights_qa(W, 2, 1, 3, 4)
+    assert r["scale"].tolist() == [7.0, 1.0]
+    assert r["chan_src"].tolist() == [0, 1, 0, 0, 0] and r["chan_depth"].tolist() == [2, 0, 2, 2, 2]
+    copies = [0, 2, 3, 4]
+    total = r["q"][:, copies].astype(np.int64).sum(axis=1)
+    assert np.array_equal(total, np.floor(W[:, 0].astype(np.float64) + 0.5).astype(np.int64))
+    # the fp32 members add up to the original value exactly (the offsets cancel)
+    assert np.array_equal(r["T_out"][:, copies].astype(np.float64).sum(axis=1), W[:, 0].astype(np.float64))
+    # unsplit channel: plain floor(x + 1/2): 2.5 -> 3, -2.5 -> -2, 3.5 -> 4, -0.5 -> 0
+    assert r["q"][1:5, 1].tolist() == [3, -2, 4, 0]
+    assert np.array_equal(r["q"][:, 1], np.floor(W[:, 1].astype(np.float64) + 0.5).astype(np.int8))
+
+
+def test_qa_split_keeps_the_fp32_layer_and_the_plain_selection():
+    rng = np.random.default_rng(77)
+    M, C, g, N, s = 9, 12, 3, 7, 5
+    X = rng.integers(-8, 9, (M, C * g)).astype(np.float32)
+    W = (rng.integers(-60, 61, (N, C * g)) / 8.0).astype(np.float32)
+    W[2, 4 * g + 1] = 30.0             # 30 -> 15, 15 -> 7.5 x 4 takes three splits, -15 one more,
+    W[5, 9 * g] = -15.0                # the fifth splits a 7.5: T = 7.5, step = 7.5 / 15 = 1/2,
+    r = ref.split_weights_qa(W, C, g, s, 5)                          # so every fp32 step is exact
+    assert r["scale"].tolist() == [7.5, 0.5]
+    plain = ref.split_weights(W, C, g, s)
+    for k in ("split_src", "chan_src", "chan_depth"):
+        assert np.array_equal(r[k], plain[k])
+    assert r["scale"][0] == np.float32(plain["max"]) and r["scale"][1] == np.float32(plain["max"]) / np.float32(15)
+    # Eq. 3 with the QA members: duplicated activations times QA-split weights == the layer
+    Xe = X[:, _expand_cols(r["chan_src"], g)]
+    y = Xe.astype(np.float64) @ r["T_out"].astype(np.float64).T
+    assert np.array_equal(y, X.astype(np.float64) @ W.astype(np.float64).T)
+    # every code is on the grid; each lineage's record replays to its column
+    assert np.abs(r["q"].astype(np.int32)).max() <= 15
+    h = np.float32(r["scale"][1]) * np.float32(0.5)
+    for j in range(C + s):
+        v = W[:, r["chan_src"][j] * g:(r["chan_src"][j] + 1) * g].copy()
+        for b in range(r["chan_depth"][j]):
+            v = ((v + h) if (r["chan_path"][j] >> b) & 1 else (v - h)) * np.float32(0.5)
+        assert np.array_equal(v, r["T_out"][:, j * g:(j + 1) * g])
+
+
+def test_qa_split_saturates_under_a_clip_and_lineages_stay_short():
+    W = _step_one_layer([3.0, -9.0, 6.4])
+    r = ref.split_weights_qa(W, 2, 1, 1, 4, clip_ratio=0.5)          # T = 3.5, step 0.5
+    assert r["scale"].tolist() == [3.5, 0.5]
+    assert r["q"][0].tolist() == [7, 1, 7] and r["q"][2].tolist() == [-7, 1, -7]
+    # one channel dominating for ever: its copies are equal, so the greedy works through all of
+    # them before any is split again and a lineage's length grows only like log2(s)
+    dom = np.zeros((1, 2), dtype=np.float32)
+    dom[0, 0] = 1.0
+    r = ref.split_weights_qa(dom, 2, 1, 40, 8)
+    assert r["chan_depth"].max() == 6 and r["chan_depth"][r["chan_src"] == 0].min() == 5
