@@ -123,6 +123,32 @@ int ocs_split_weights(const float *W, int64_t N, int C, int g, int64_t ldw, int 
                       size_t ws_bytes, void *stream);
 
 /*
+ * Quantization-aware splitting of the weights (Sec. 3.3), done off-line like ocs_split_weights.
+ * In units of the grid step a QA split replaces w by the pair ((w - 1/2)/2, (w + 1/2)/2), whose
+ * members, rounded with that section's Q(x) = floor(x + 1/2), add up to Q(w).
+ *   Selection and threshold: as ocs_split_weights in mode OCS_MODE_HALVE on the same W
+ *        (split_src, chan_src, chan_depth are outputs with the same values);
+ *        T = clip_ratio * max|plainly halved W'|, step = T / qmax, qmax = 2^(bits-1) - 1.
+ *   Members: the split list is replayed on W; at each split the channel that keeps its index
+ *        becomes (v - step/2)/2 and the appended copy (v + step/2)/2, in fp32, one
+ *        add/subtract and one exact halving per split.
+ *   chan_path [C + num_splits] uint32, output: the history of expanded channel j, one bit per
+ *        split of its lineage, first split in bit 0 (0: kept its index, 1: appended copy);
+ *        chan_depth[j] bits are used.
+ *   W_out [N, (C+s)*g] fp32 (leading dimension ldo; may be NULL): the QA-split weights.
+ *   Wq [N, ldq] int8 (may be NULL): codes clamp(floor(w' * (qmax / T) + 1/2), -qmax, qmax), pad
+ *        columns zero.  At least one of W_out, Wq is required.
+ *   scale_w_out device float[2] = {T, step} (required).
+ * Activations are duplicated as for Eq. 3 (ocs_split_act with chan_depth = NULL).
+ * W is only read.
+ */
+int ocs_split_weights_qa(const float *W, int64_t N, int C, int g, int64_t ldw, int num_splits,
+                         int32_t *split_src, int32_t *chan_src, int32_t *chan_depth,
+                         uint32_t *chan_path, float *W_out, int64_t ldo, int bits,
+                         float clip_ratio, int8_t *Wq, int64_t ldq, float *scale_w_out,
+                         void *workspace, size_t ws_bytes, void *stream);
+
+/*
  * Linear quantization of Sec. 3.1 Eq. 1 with optional clipping (Sec. 1).
  *   x [rows, cols] fp32 -> q [rows, ldq] int8, q = clamp(rne(x * (qmax / T)), -qmax, qmax),
  *   qmax = 2^(bits-1) - 1 (a grid of 2^bits - 1 points), columns cols .. ldq-1 zero.

@@ -55,6 +55,9 @@ def lib():
     L.ocs_split_weights.restype = _i32
     L.ocs_split_weights.argtypes = [_vp, _i64, _i32, _i32, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _i64,
                                     _vp, _i32, _f32, _vp, _i64, _vp, _vp, _sz, _vp]
+    L.ocs_split_weights_qa.restype = _i32
+    L.ocs_split_weights_qa.argtypes = [_vp, _i64, _i32, _i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _i64,
+                                       _i32, _f32, _vp, _i64, _vp, _vp, _sz, _vp]
     L.ocs_quantize.restype = _i32
     L.ocs_quantize.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _f32, _vp, _i64, _vp, _vp, _sz, _vp]
     L.ocs_split_act.restype = _i32
@@ -152,6 +155,15 @@ def ocs_split_weights(W, N, Cn, g, ldw, num_splits, mode, split_src, chan_src, c
                                    _ptr(chan_src), _ptr(chan_depth), _ptr(W_out), ldo,
                                    _ptr(wmax_out), bits, clip_ratio, _ptr(Wq), ldq,
                                    _ptr(scale_w_out), w, wb, _stream(stream)), "ocs_split_weights")
+
+
+def ocs_split_weights_qa(W, N, Cn, g, ldw, num_splits, split_src, chan_src, chan_depth, chan_path,
+                         W_out, ldo, bits, clip_ratio, Wq, ldq, scale_w_out, workspace, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib().ocs_split_weights_qa(_ptr(W), N, Cn, g, ldw, num_splits, _ptr(split_src),
+                                      _ptr(chan_src), _ptr(chan_depth), _ptr(chan_path), _ptr(W_out),
+                                      ldo, bits, clip_ratio, _ptr(Wq), ldq, _ptr(scale_w_out), w, wb,
+                                      _stream(stream)), "ocs_split_weights_qa")
 
 
 def ocs_quantize(x, rows, cols, ldx, bits, threshold, clip_ratio, q, ldq, scale_out, workspace,

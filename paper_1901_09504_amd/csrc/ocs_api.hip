@@ -163,6 +163,47 @@ int ocs_split_weights(const float* W, int64_t N, int C, int g, int64_t ldw, int 
     return OCS_OK;
 }
 
+int ocs_split_weights_qa(const float* W, int64_t N, int C, int g, int64_t ldw, int num_splits,
+                         int32_t* split_src, int32_t* chan_src, int32_t* chan_depth,
+                         uint32_t* chan_path, float* W_out, int64_t ldo, int bits,
+                         float clip_ratio, int8_t* Wq, int64_t ldq, float* scale_w_out,
+                         void* workspace, size_t ws_bytes, void* stream) {
+    if (!W || !chan_src || !chan_depth || !chan_path || !scale_w_out) return OCS_E_NULL;
+    if (num_splits > 0 && !split_src) return OCS_E_NULL;
+    if (!W_out && !Wq) return OCS_E_NULL;
+    int rc = check_layer(N, C, g, ldw, num_splits);
+    if (rc) return rc;
+    const int64_t K = (int64_t)C * g, Ke = (int64_t)(C + num_splits) * g;
+    if (W_out && ldo < Ke) return OCS_E_SHAPE;
+    if (Wq) {
+        rc = check_codes(Wq, ldq, Ke);
+        if (rc) return rc;
+    }
+    if (!bits_ok(bits)) return OCS_E_BITS;   // the step depends on the grid even without codes
+    rc = check_workspace(workspace, ws_bytes, N, K);
+    if (rc) return rc;
+
+    Workspace w = plan_workspace(N, K);
+    char* base = static_cast<char*>(workspace);
+    float* colmax = reinterpret_cast<float*>(base + w.colmax_off);
+    float* partial = reinterpret_cast<float*>(base + w.partial_off);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    // selection and threshold exactly as for plain halving; then the histories; then the members
+    hipError_t e = launch_colmax(W, N, K, ldw, colmax, partial, st);
+    if (e != hipSuccess) return hip_fail(e);
+    const float qmax = qmax_of(bits);
+    e = launch_select(colmax, C, g, num_splits, OCS_MODE_HALVE, split_src, split_src, chan_src,
+                      chan_depth, nullptr, clip_ratio, qmax, scale_w_out, st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = launch_qa_paths(split_src, C, num_splits, chan_path, st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = launch_expand_quantize_qa(W, ldw, N, C, g, num_splits, chan_src, chan_depth, chan_path,
+                                  scale_w_out, qmax, W_out, ldo, Wq, ldq, st);
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
 int ocs_quantize(const float* x, int64_t rows, int64_t cols, int64_t ldx, int bits,
                  const float* threshold, float clip_ratio, int8_t* q, int64_t ldq,
                  float* scale_out, void* workspace, size_t ws_bytes, void* stream) {

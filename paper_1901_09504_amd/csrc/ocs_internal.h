@@ -77,6 +77,16 @@ hipError_t launch_expand_f32(const float* T, int64_t ld, int64_t rows, int C, in
                              const int32_t* chan_src, const int32_t* chan_depth, int halve,
                              float* out, int64_t ldo, hipStream_t stream);
 
+// Sec. 3.3: histories of the expanded channels from the split list, and the QA-split weights
+// (fp32 and / or codes rounded by floor(x + 1/2)); scale = {T, T/qmax} as the selector wrote it.
+hipError_t launch_qa_paths(const int32_t* split_src, int C, int s, uint32_t* chan_path,
+                           hipStream_t stream);
+hipError_t launch_expand_quantize_qa(const float* W, int64_t ldw, int64_t N, int C, int g, int s,
+                                     const int32_t* chan_src, const int32_t* chan_depth,
+                                     const uint32_t* chan_path, const float* scale, float qmax,
+                                     float* W_out, int64_t ldo, int8_t* Wq, int64_t ldq,
+                                     hipStream_t stream);
+
 // int8 x int8 -> int32 MFMA GEMM over Kpad (multiple of 64) with dequantizing epilogue.
 hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
                         int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,

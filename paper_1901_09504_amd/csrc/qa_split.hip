@@ -1,0 +1,108 @@
+// Quantization-aware splitting of the weights (Sec. 3.3), off-line.
+//
+// In units of the grid step a QA split replaces w by the pair ((w - 1/2)/2, (w + 1/2)/2);
+// rounded with that section's Q(x) = floor(x + 1/2) the two members add up to Q(w).  The
+// channels to split and the threshold are those of the plain-halving procedure (Sec. 3.4,
+// Eq. 3) on the same tensor, which fixes the step before any QA pair is formed; the channel
+// that keeps its index takes the "-" member, the appended copy the "+" member.  An expanded
+// channel is therefore its source channel pushed through its own short history of members
+// (chan_path, one bit per split, first split in bit 0), one fp32 add/subtract and one exact
+// halving per split, in the order the splits happened.
+#include "ocs_internal.h"
+
+namespace ocs {
+
+// Histories of the expanded channels from the split list.  The list is short and strictly
+// sequential (a split's parent may itself be a copy made a step earlier): one lane replays it
+// in LDS, then the workgroup writes the result out.
+__global__ __launch_bounds__(kThreads) void qa_paths_kernel(const int32_t* __restrict__ split_src,
+                                                            int C, int s,
+                                                            uint32_t* __restrict__ chan_path) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int E = C + s;
+    uint32_t* path = reinterpret_cast<uint32_t*>(smem);
+    unsigned char* len = reinterpret_cast<unsigned char*>(path + E);
+    for (int j = threadIdx.x; j < E; j += kThreads) {
+        path[j] = 0u;
+        len[j] = 0;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int i = 0; i < s; ++i) {
+            const int cur = C + i;
+            int p = split_src[i];
+            p = p < 0 ? 0 : (p >= cur ? cur - 1 : p);
+            const unsigned l = len[p] < 31 ? len[p] : 31;   // a history grows like log2(s): never 31
+            path[cur] = path[p] | (1u << l);
+            len[p] = (unsigned char)(l + 1);
+            len[cur] = (unsigned char)(l + 1);
+        }
+    }
+    __syncthreads();
+    for (int j = threadIdx.x; j < E; j += kThreads) chan_path[j] = path[j];
+}
+
+// One lane per packed dword of codes (four expanded columns of one row).  Weights are
+// prepared once, off-line: no attempt at streaming speed here.
+__global__ __launch_bounds__(kThreads) void expand_quantize_qa_kernel(
+    const float* __restrict__ W, int64_t ldw, int64_t N, int C, int g, int s,
+    const int32_t* __restrict__ chan_src, const int32_t* __restrict__ chan_depth,
+    const uint32_t* __restrict__ chan_path, const float* __restrict__ scale, float qmax,
+    float* __restrict__ W_out, int64_t ldo, int8_t* __restrict__ Wq, int D) {
+    const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (o >= N * (int64_t)D) return;
+    const int64_t n = o / D;
+    const int d = (int)(o - n * D);
+    const int Ke = (C + s) * g;
+    const float T = scale[0];
+    const float half_step = scale[1] * 0.5f;
+    float inv = 0.0f;
+    if (T > 0.0f) inv = __builtin_fminf(__fdiv_rn(qmax, T), 3.402823466e+38f);
+    unsigned packed = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int k = 4 * d + e;
+        int code = 0;
+        if (k < Ke) {
+            const int j = k / g, t = k - j * g;
+            int src = chan_src[j];
+            src = src < 0 ? 0 : (src >= C ? C - 1 : src);
+            float v = W[n * ldw + (int64_t)src * g + t];
+            const int depth = chan_depth[j] < 31 ? chan_depth[j] : 31;
+            const uint32_t path = chan_path[j];
+            for (int b = 0; b < depth; ++b) {
+                const float m = ((path >> b) & 1u) ? v + half_step : v - half_step;
+                v = m * 0.5f;
+            }
+            if (W_out) W_out[n * ldo + k] = v;
+            float p = v * inv;
+            p = __builtin_amdgcn_fmed3f(p, -qmax, qmax);
+            code = (int)floorf(p + 0.5f);        // Sec. 3.3's Q(x) = floor(x + 1/2)
+        }
+        packed |= ((unsigned)code & 0xFFu) << (8 * e);
+    }
+    if (Wq) reinterpret_cast<unsigned*>(Wq)[o] = packed;
+}
+
+hipError_t launch_qa_paths(const int32_t* split_src, int C, int s, uint32_t* chan_path,
+                           hipStream_t stream) {
+    const size_t lds = (size_t)(C + s) * 5 + 16;   // C + s <= kMaxExpanded: at most 40 KB
+    qa_paths_kernel<<<1, kThreads, lds, stream>>>(split_src, C, s, chan_path);
+    return hipGetLastError();
+}
+
+hipError_t launch_expand_quantize_qa(const float* W, int64_t ldw, int64_t N, int C, int g, int s,
+                                     const int32_t* chan_src, const int32_t* chan_depth,
+                                     const uint32_t* chan_path, const float* scale, float qmax,
+                                     float* W_out, int64_t ldo, int8_t* Wq, int64_t ldq,
+                                     hipStream_t stream) {
+    // without codes the fp32 tensor is still walked in groups of four columns
+    const int64_t Ke = (int64_t)(C + s) * g;
+    const int D = (int)(Wq ? ldq / 4 : ceil_div(Ke, 4));
+    const int64_t total = N * D;
+    expand_quantize_qa_kernel<<<dim3((unsigned)ceil_div(total, kThreads)), kThreads, 0, stream>>>(
+        W, ldw, N, C, g, s, chan_src, chan_depth, chan_path, scale, qmax, W_out, ldo, Wq, D);
+    return hipGetLastError();
+}
+
+}  // namespace ocs

@@ -6,6 +6,7 @@ arithmetic happens here.
 
   weight OCS (Sec. 3.2 Eq. 3, the variant the paper finds effective, Sec. 5.2):
       prepare_weights(W)           off-line: select on W, halve, quantize        (W1-W3)
+      prepare_weights(W, qa=True)  the same with the quantization-aware members of Sec. 3.3
       forward(X[, threshold])      per batch: duplicate channels + quantize, GEMM (X1/X2, G1, G2)
   activation OCS (Eq. 4) with the channels chosen on the batch itself (Sec. 5.3):
       forward_act_ocs(W, X)        select on X, duplicate weights, halve + quantize X, GEMM
@@ -31,6 +32,7 @@ class ExpandedLayer:
         self.split_src = torch.empty(max(self.s, 1), **i32)
         self.chan_src = torch.empty(E, **i32)
         self.chan_depth = torch.empty(E, **i32)
+        self.chan_path = None      # uint32 bits, allocated by the first QA preparation
         self.Wq = torch.empty((self.N, self.ldq), dtype=torch.int8, device=device)
         self.scale_w = torch.empty(2, dtype=torch.float32, device=device)
         self.scale_x = torch.empty(2, dtype=torch.float32, device=device)
@@ -49,10 +51,20 @@ class ExpandedLayer:
             self._rows = M
 
     # ---- off-line ---------------------------------------------------------------------------
-    def prepare_weights(self, W, W_out=None, clip_ratio_w=None, stream=None):
-        """W fp32 [N, C*g] on the device -> split lists, Wq, scale_w (and W' if W_out given)."""
+    def prepare_weights(self, W, W_out=None, clip_ratio_w=None, stream=None, qa=False):
+        """W fp32 [N, C*g] on the device -> split lists, Wq, scale_w (and W' if W_out given).
+        qa: quantization-aware split members and floor(x + 1/2) weight codes (Sec. 3.3) instead
+        of plain halves (Eq. 3); the activation side is the same either way."""
         assert W.dtype == torch.float32 and W.shape == (self.N, self.K)
         clip = self.clip_ratio_w if clip_ratio_w is None else float(clip_ratio_w)
+        if qa:
+            if self.chan_path is None:
+                self.chan_path = torch.empty(self.C + self.s, dtype=torch.int32, device=self.device)
+            B.ocs_split_weights_qa(W, self.N, self.C, self.g, W.stride(0), self.s, self.split_src,
+                                   self.chan_src, self.chan_depth, self.chan_path, W_out,
+                                   0 if W_out is None else W_out.stride(0), self.bits_w, clip,
+                                   self.Wq, self.ldq, self.scale_w, self.ws_w, stream)
+            return
         B.ocs_split_weights(W, self.N, self.C, self.g, W.stride(0), self.s, B.MODE_HALVE,
                             self.split_src, self.chan_src, self.chan_depth, W_out,
                             0 if W_out is None else W_out.stride(0), self.wmax, self.bits_w, clip,

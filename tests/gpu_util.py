@@ -73,6 +73,26 @@ def gpu_split_weights(W, Cn, g, s, mode=B.MODE_HALVE, split_src=None, bits=8, cl
                 scale=host(sc), max=float(host(mx)[0]))
 
 
+def gpu_split_weights_qa(W, Cn, g, s, bits=8, clip_ratio=1.0, want_f32=True, want_codes=True):
+    N = W.shape[0]
+    Wd = dev(W)
+    Ke = (Cn + s) * g
+    ldq = B.ocs_padded_cols(Ke)
+    ss = torch.full((max(s, 1),), -7, dtype=torch.int32, device="cuda")
+    cs = torch.full((Cn + s,), -7, dtype=torch.int32, device="cuda")
+    cd = torch.full((Cn + s,), -7, dtype=torch.int32, device="cuda")
+    cp = torch.full((Cn + s,), -7, dtype=torch.int32, device="cuda")     # uint32 bits
+    Wo = torch.full((N, Ke), 7.0, dtype=torch.float32, device="cuda") if want_f32 else None
+    Wq = torch.full((N, ldq), 77, dtype=torch.int8, device="cuda") if want_codes else None
+    sc = torch.zeros(2, dtype=torch.float32, device="cuda")
+    ws = B.alloc_workspace(N, Cn * g)
+    B.ocs_split_weights_qa(Wd, N, Cn, g, Wd.stride(0), s, ss, cs, cd, cp, Wo, Ke, bits, clip_ratio,
+                           Wq, ldq, sc, ws)
+    return dict(split_src=host(ss)[:s], chan_src=host(cs), chan_depth=host(cd),
+                chan_path=host(cp).view(np.uint32), T_out=None if Wo is None else host(Wo),
+                Wq=None if Wq is None else host(Wq), scale=host(sc))
+
+
 def gpu_split_act(X, Cn, g, chan_src, chan_depth, s, bits, threshold=None, clip_ratio=1.0):
     M = X.shape[0]
     Xd = dev(X)

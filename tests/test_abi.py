@@ -62,6 +62,10 @@ def test_argument_errors_are_reported_without_a_device():
     assert L.ocs_split_weights(A, 4, 4, 1, 4, 1, 0, None, A, A, None, 0, None, 8, 1.0, None, 0, None, A, ws, None) == -1
     assert L.ocs_split_weights(A, 4, 4, 1, 4, 1, 0, A, A, A, None, 0, None, 8, 1.0, A, 64, None, A, ws, None) == -1
     assert L.ocs_qgemm(A, 64, A, 64, 4, 4, 4, 8, 8, A, A, None, 0, None, 4, None, 0, None) == -1
+    assert L.ocs_split_weights_qa(A, 4, 4, 1, 4, 1, A, A, A, None, A, 8, 8, 1.0, A, 64, A, A, ws, None) == -1  # no chan_path
+    assert L.ocs_split_weights_qa(A, 4, 4, 1, 4, 1, A, A, A, A, None, 0, 8, 1.0, None, 0, A, A, ws, None) == -1  # no output
+    assert L.ocs_split_weights_qa(A, 4, 4, 1, 4, 1, A, A, A, A, A, 4, 8, 1.0, None, 0, A, A, ws, None) == -2    # ldo < (C+s)*g
+    assert L.ocs_split_weights_qa(A, 4, 4, 1, 4, 1, A, A, A, A, A, 8, 9, 1.0, None, 0, A, A, ws, None) == -4    # bits
     # shapes
     assert L.ocs_quantize(A, 0, 4, 4, 8, A, 1.0, A, 64, A, A, ws, None) == -2
     assert L.ocs_quantize(A, 4, 8, 4, 8, A, 1.0, A, 64, A, A, ws, None) == -2      # ldx < cols
