@@ -188,3 +188,43 @@ def test_config5_forward_batch32(idx):
 def test_config5_forward_batch256(name):
     (layer,) = [l for l in wl.config(5, batch=256) if l.name == name]
     run_layer(layer, clips=(0.8,), dynamic=False, static_threshold=5.0)
+
+
+# ---- quantization-aware weight split (Sec. 3.3) on the configs' layers ---------------------------
+
+def _check_qa_weights(layer, W, clip):
+    L = ExpandedLayer(layer.N, layer.C, layer.g, layer.r, layer.bits_w, layer.bits_x, clip_ratio_w=clip)
+    L.prepare_weights(dev(W), qa=True)
+    exp = ref.split_weights_qa(W, layer.C, layer.g, L.s, layer.bits_w, clip_ratio=clip, ldq=L.ldq)
+    assert np.array_equal(host(L.split_src)[:L.s], exp["split_src"])
+    assert np.array_equal(host(L.chan_src), exp["chan_src"])
+    assert np.array_equal(host(L.chan_depth), exp["chan_depth"])
+    assert np.array_equal(host(L.chan_path).view(np.uint32), exp["chan_path"])
+    assert np.array_equal(host(L.scale_w), exp["scale"])
+    assert np.array_equal(host(L.Wq), exp["q"])
+    return L, exp
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4])
+def test_qa_weights_on_configs(cfg):
+    for layer in wl.config(cfg):         # config 3: every expand ratio
+        _check_qa_weights(layer, wl.weights(layer), layer.clip_ratios[-1])
+
+
+def test_qa_weights_config5_all_shapes():
+    for layer in _unique(wl.config(5)):
+        _check_qa_weights(layer, wl.weights(layer), 0.9)
+
+
+def test_qa_forward_config1_and_lstm_gate():
+    for layer in (wl.config(1)[0], wl.shrink(wl.config(4)[0], 256)):
+        W, X = wl.weights(layer), wl.activations(layer)
+        L, exp = _check_qa_weights(layer, W, 1.0)
+        acc = torch.empty((layer.M, layer.N), dtype=torch.int32, device="cuda")
+        Y = L.forward(dev(X), acc_out=acc)
+        Xq_ref, sx_ref, _ = ref.split_act(X, layer.C, layer.g, exp["chan_src"], None, L.s, layer.bits_x,
+                                          ldq=L.ldq)
+        acc_ref, y_ref = ref.qgemm(Xq_ref, exp["q"], L.Ke, sx_ref[1], exp["scale"][1])
+        assert np.array_equal(host(L.Xq[:layer.M]), Xq_ref)
+        assert np.array_equal(host(acc), acc_ref)
+        assert_y_close(host(Y), y_ref)
