@@ -17,6 +17,7 @@
  *   Sec. 3.2   Eq. 2, the linear layer, evaluated on the integer codes
  *   Sec. 3.3   quantization-aware splitting of the weights, with that section's
  *              rounding function floor(x + 1/2)
+ *   Sec. 4.1   clip threshold of least mean squared error over a histogram
  *
  * Precision.  A code is an integer decided by floating point, so the decision is taken
  * in the arithmetic the GPU kernels use: fp32, one correctly rounded division
@@ -26,7 +27,8 @@
  * Parity pins live in tests/test_oracle_pins.py (functional identity of the split
  * layer, halving of every split channel's maximum, greedy == brute force, the grid's
  * definition, the s = 0 case against a library matmul, the w = 3 example of Sec. 3.3,
- * Table 4's weight-size row, the rounded QA pair adding up to the rounded original).
+ * Table 4's weight-size row, the rounded QA pair adding up to the rounded original, the
+ * histogram against a library histogram and the error against its element-wise definition).
  * Unpinned: nothing in this file; the paper's accuracy tables are not reproduced
  * (datasets and trained weights are needed for those).
  *
@@ -280,6 +282,76 @@ int ref_split_weights_qa(const float *T, int64_t rows, int C, int g, int64_t ld,
             q[n * ldq + k] = code_of_half_up(T_out[n * ldo + k], inv, qmax);
         for (int64_t k = Ke; k < ldq; ++k) q[n * ldq + k] = 0;
     }
+    return REF_OK;
+}
+
+/*
+ * Sec. 4.1: clip threshold by minimal mean squared error over a histogram.
+ *
+ * A histogram of the values is built (bin values x_i, frequencies h(x_i), i = 1..n), the
+ * error of a candidate threshold T is MSE(T) = 1/n * sum_i h(x_i) * (x_i - Q_T(x_i))^2 with
+ * Q_T the quantizer of Eq. 1 on the grid of range [-T, T], candidates are evenly spaced between
+ * 0 and max|x|, and the candidate with the least error is taken.  The paper fixes neither the
+ * number of bins nor the number of candidates ("a large number"), nor what a bin's value is.
+ * Reading taken here:
+ *   - the grid is symmetric, so the histogram is taken over |x|: n equal bins on [0, m],
+ *     m = max|x|; a value falls in bin min(n-1, floor(|x| * (n / m))), decided in fp32 with
+ *     one division n / m and one multiply;
+ *   - a bin's value is its centre, x_i = (i + 1/2) * (m / n) in fp32 (i counted from 0);
+ *   - candidates T_c = m * (c / n_cand), c = 1..n_cand, in fp32 (the last one is m itself);
+ *   - Q_T(x_i) = code * step with the code decided in fp32 exactly as everywhere else
+ *     (qmax / T, one multiply, saturate, round half to even) and step = T / qmax;
+ *   - the error and the sum are evaluated in fp64, bins in increasing order;
+ *   - the first candidate with the least error wins.
+ * hist [n] (may be NULL) receives the frequencies, mse [n_cand] (may be NULL) the errors,
+ * out = {chosen threshold, m}.  m = 0 gives threshold 0.
+ */
+int ref_mse_clip(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bits, int n_bins,
+                 int n_cand, uint64_t *hist, double *mse, float *out) {
+    if (!x || !out) return REF_E_ARG;
+    if (rows <= 0 || cols <= 0 || ldx < cols || bits < 2 || bits > 8) return REF_E_ARG;
+    if (n_bins < 1 || n_cand < 1) return REF_E_ARG;
+    float qmax = (float)((1 << (bits - 1)) - 1);
+    float m = 0.0f;
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t k = 0; k < cols; ++k) {
+            float a = fabsf(x[i * ldx + k]);
+            if (a > m) m = a;
+        }
+    uint64_t *h = (uint64_t *)calloc((size_t)n_bins, sizeof(uint64_t));
+    if (!h) return REF_E_NOMEM;
+    float to_bin = m > 0.0f ? (float)n_bins / m : 0.0f;
+    if (to_bin > FLT_MAX) to_bin = FLT_MAX;
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t k = 0; k < cols; ++k) {
+            float p = fabsf(x[i * ldx + k]) * to_bin;
+            int b = p >= (float)n_bins ? n_bins - 1 : (int)p;
+            h[b] += 1;
+        }
+    float width = m / (float)n_bins;
+    int best_c = 1;
+    double best = 0.0;
+    for (int c = 1; c <= n_cand; ++c) {
+        float T = m * ((float)c / (float)n_cand);
+        float inv = inv_step_of(T, qmax);
+        float step = T / qmax;
+        double sum = 0.0;
+        for (int i = 0; i < n_bins; ++i) {
+            float xi = ((float)i + 0.5f) * width;
+            double e = (double)xi - (double)code_of(xi, inv, qmax) * (double)step;
+            sum += (double)h[i] * (e * e);
+        }
+        double err = sum / (double)n_bins;
+        if (mse) mse[c - 1] = err;
+        if (c == 1 || err < best) {
+            best = err;
+            best_c = c;
+        }
+    }
+    if (hist) memcpy(hist, h, (size_t)n_bins * sizeof(uint64_t));
+    free(h);
+    out[0] = m * ((float)best_c / (float)n_cand);
+    out[1] = m;
     return REF_OK;
 }
 

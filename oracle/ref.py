@@ -110,6 +110,20 @@ def split_weights_qa(T, Cn, g, s, bits, clip_ratio=1.0, ldq=None):
     return dict(split_src=ss[:s], chan_src=cs, chan_depth=cd, chan_path=cp, T_out=out, q=q, scale=sc)
 
 
+def mse_clip(x, bits, n_bins=2048, n_cand=512):
+    """Sec. 4.1: threshold of least histogram MSE.  Returns dict(threshold, max, hist, mse)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    rows, cols = x.shape
+    hist = np.zeros(n_bins, dtype=np.uint64)
+    mse = np.zeros(n_cand, dtype=np.float64)
+    out = np.zeros(2, dtype=np.float32)
+    rc = lib().ref_mse_clip(_p(x, C.c_float), C.c_int64(rows), C.c_int64(cols), C.c_int64(cols),
+                            C.c_int(bits), C.c_int(n_bins), C.c_int(n_cand), _p(hist, C.c_uint64),
+                            _p(mse, C.c_double), _p(out, C.c_float))
+    _check(rc, "ref_mse_clip")
+    return dict(threshold=out[0], max=out[1], hist=hist, mse=mse)
+
+
 def quantize(x, bits, threshold=None, clip_ratio=1.0, ldq=None):
     """Eq. 1 (+ clip).  Returns (codes [rows, ldq] int8, scale float32[2] = {T, step})."""
     x = np.ascontiguousarray(x, dtype=np.float32)

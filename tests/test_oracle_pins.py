@@ -467,3 +467,57 @@ def test_qa_split_saturates_under_a_clip_and_lineages_stay_short():
     dom[0, 0] = 1.0
     r = ref.split_weights_qa(dom, 2, 1, 40, 8)
     assert r["chan_depth"].max() == 6 and r["chan_depth"][r["chan_src"] == 0].min() == 5
+
+
+# ---- Sec. 4.1: clip threshold of least histogram MSE ----------------------------------------
+
+def test_mse_clip_histogram_is_the_library_histogram():
+    # multiples of 1/1024 with max exactly 1 and 64 bins: every bin decision is exact in fp32
+    rng = np.random.default_rng(91)
+    x = (rng.integers(-1024, 1025, (37, 53)) / 1024.0).astype(np.float32)
+    x[5, 7] = -1.0
+    r = ref.mse_clip(x, 6, n_bins=64, n_cand=16)
+    expect, _ = np.histogram(np.abs(x.astype(np.float64)), bins=64, range=(0.0, 1.0))
+    assert r["max"] == 1.0 and np.array_equal(r["hist"], expect.astype(np.uint64))
+    assert r["hist"].sum() == x.size
+
+
+def test_mse_clip_error_is_its_elementwise_definition():
+    # every value except the maximum sits on a bin centre (odd multiples of 1/4, 16 bins on [0, 8]),
+    # and no centre is ever a rounding tie for thresholds 1..8 with qmax = 7, so the histogram
+    # error must equal the sum over elements of (x - Q(x))^2 / n, evaluated here with numpy
+    rng = np.random.default_rng(92)
+    x = ((2 * rng.integers(0, 16, (20, 30)) + 1) / 4.0 * rng.choice([-1.0, 1.0], (20, 30))).astype(np.float32)
+    x[3, 3] = 8.0                                       # the maximum: falls into the last bin (centre 7.75)
+    r = ref.mse_clip(x, 4, n_bins=16, n_cand=8)
+    v = np.abs(x.astype(np.float64)).ravel()
+    v[v == 8.0] = 7.75
+    expect = []
+    for c in range(1, 9):
+        step = np.float64(np.float32(c) / np.float32(7))
+        code = np.clip(np.rint(v * 7.0 / c), -7, 7)
+        expect.append(np.sum((v - code * step) ** 2) / 16.0)
+    assert np.allclose(r["mse"], expect, rtol=1e-12, atol=0)
+    assert r["threshold"] == np.float32(1 + int(np.argmin(expect))) and r["max"] == 8.0
+
+
+def test_mse_clip_single_bin_closed_form_and_outlier_behaviour():
+    # one bin: all N values count at the centre m/2; at T = m with qmax = 7 the centre's code is
+    # rne(3.5) = 4, so the error is N * (m/2 - 4m/7)^2 = N * m^2 / 196
+    x = np.full((10, 10), 0.3, dtype=np.float32)
+    x[0, 0] = 14.0
+    r = ref.mse_clip(x, 4, n_bins=1, n_cand=1)
+    assert np.isclose(r["mse"][0], 100 * 14.0 ** 2 / 196.0, rtol=1e-6)
+    # a bell with one far outlier: few bits clip it, many bits keep it; errors are non-negative,
+    # the chosen candidate is the first of the least ones, zero tensors give threshold 0
+    rng = np.random.default_rng(93)
+    g = rng.standard_normal((64, 256)).astype(np.float32)
+    g[0, 0] = 40.0
+    lo, hi = ref.mse_clip(g, 4), ref.mse_clip(g, 8)
+    assert 0 < lo["threshold"] < 0.2 * lo["max"] and hi["threshold"] > 0.5 * hi["max"]
+    for r in (lo, hi):
+        assert (r["mse"] >= 0).all() and r["max"] == 40.0
+        c = int(np.argmin(r["mse"]))
+        assert r["threshold"] == np.float32(40.0) * (np.float32(c + 1) / np.float32(512))
+    z = ref.mse_clip(np.zeros((3, 4), dtype=np.float32), 8, n_bins=8, n_cand=4)
+    assert z["threshold"] == 0.0 and z["max"] == 0.0 and z["hist"][0] == 12
