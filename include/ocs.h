@@ -149,6 +149,27 @@ int ocs_split_weights_qa(const float *W, int64_t N, int C, int g, int64_t ldw, i
                          void *workspace, size_t ws_bytes, void *stream);
 
 /*
+ * Clip threshold of least mean squared error over a histogram (Sec. 4.1), for calibration.
+ *   x [rows, cols] fp32 (leading dimension ldx), only read.
+ *   Histogram of |x|: num_bins (1..8192) equal bins on [0, m], m = max|x|; a value falls in bin
+ *        min(num_bins-1, floor(|x| * (num_bins / m))) (fp32: one division, one multiply); a bin
+ *        counts at its centre x_i = (i + 1/2) * (m / num_bins).
+ *   Candidates T_c = m * (c / num_candidates), c = 1..num_candidates (1..65536).
+ *   Error of a candidate: 1/num_bins * sum_i h_i * (x_i - code_i * T_c/qmax)^2 with code_i the
+ *        code of x_i under ocs_quantize's arithmetic contract for threshold T_c and `bits`;
+ *        evaluated in fp64, bins in increasing order.  The first candidate of least error wins.
+ *   threshold_out device float[2] = {chosen threshold, m}; element 0 can be handed to
+ *        ocs_quantize / ocs_split_act as their `threshold`.
+ *   hist_out device uint64[num_bins], required: the frequencies (also the routine's scratch).
+ *   mse_out device double[num_candidates], may be NULL: the error of every candidate.
+ * workspace as for ocs_quantize on the same shape.
+ */
+int ocs_mse_clip_threshold(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bits,
+                           int num_bins, int num_candidates, float *threshold_out,
+                           unsigned long long *hist_out, double *mse_out, void *workspace,
+                           size_t ws_bytes, void *stream);
+
+/*
  * Linear quantization of Sec. 3.1 Eq. 1 with optional clipping (Sec. 1).
  *   x [rows, cols] fp32 -> q [rows, ldq] int8, q = clamp(rne(x * (qmax / T)), -qmax, qmax),
  *   qmax = 2^(bits-1) - 1 (a grid of 2^bits - 1 points), columns cols .. ldq-1 zero.

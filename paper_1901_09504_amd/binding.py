@@ -58,6 +58,8 @@ def lib():
     L.ocs_split_weights_qa.restype = _i32
     L.ocs_split_weights_qa.argtypes = [_vp, _i64, _i32, _i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _i64,
                                        _i32, _f32, _vp, _i64, _vp, _vp, _sz, _vp]
+    L.ocs_mse_clip_threshold.restype = _i32
+    L.ocs_mse_clip_threshold.argtypes = [_vp, _i64, _i64, _i64, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]
     L.ocs_quantize.restype = _i32
     L.ocs_quantize.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _f32, _vp, _i64, _vp, _vp, _sz, _vp]
     L.ocs_split_act.restype = _i32
@@ -164,6 +166,14 @@ def ocs_split_weights_qa(W, N, Cn, g, ldw, num_splits, split_src, chan_src, chan
                                       _ptr(chan_src), _ptr(chan_depth), _ptr(chan_path), _ptr(W_out),
                                       ldo, bits, clip_ratio, _ptr(Wq), ldq, _ptr(scale_w_out), w, wb,
                                       _stream(stream)), "ocs_split_weights_qa")
+
+
+def ocs_mse_clip_threshold(x, rows, cols, ldx, bits, num_bins, num_candidates, threshold_out, hist_out,
+                           mse_out, workspace, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib().ocs_mse_clip_threshold(_ptr(x), rows, cols, ldx, bits, num_bins, num_candidates,
+                                        _ptr(threshold_out), _ptr(hist_out), _ptr(mse_out), w, wb,
+                                        _stream(stream)), "ocs_mse_clip_threshold")
 
 
 def ocs_quantize(x, rows, cols, ldx, bits, threshold, clip_ratio, q, ldq, scale_out, workspace,

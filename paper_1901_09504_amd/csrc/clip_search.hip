@@ -1,0 +1,114 @@
+// Clip threshold of least mean squared error (Sec. 4.1), a calibration-time routine.
+//
+// A histogram h of |x| over n equal bins on [0, m], m = max|x|; a bin counts at its centre
+// x_i; for each of n_cand thresholds T_c = m * c / n_cand the error
+// MSE(T_c) = 1/n * sum_i h_i * (x_i - Q_{T_c}(x_i))^2 with the quantizer of Eq. 1; the first
+// candidate with the least error is the result.  Bin decisions and codes are taken in fp32
+// with the same operation order as everywhere else in the library; errors are accumulated in
+// fp64 over the bins in increasing order, one candidate per lane, so that the choice does not
+// depend on how the work is spread.
+#include "ocs_internal.h"
+
+namespace ocs {
+
+__global__ __launch_bounds__(kThreads) void hist_zero_kernel(unsigned long long* hist, int n) {
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i < n) hist[i] = 0ull;
+}
+
+// Frequencies: each workgroup counts in LDS, then adds its counts to the global histogram
+// (integer sums: any order gives the same result).
+__global__ __launch_bounds__(kThreads) void hist_kernel(const float* __restrict__ x, int64_t ldx,
+                                                        int64_t rows, int64_t cols,
+                                                        const float* __restrict__ maxabs, int n_bins,
+                                                        unsigned long long* __restrict__ hist) {
+    extern __shared__ unsigned int lhist[];
+    for (int i = threadIdx.x; i < n_bins; i += kThreads) lhist[i] = 0u;
+    __syncthreads();
+    const float m = maxabs[0];
+    float to_bin = 0.0f;
+    if (m > 0.0f) to_bin = __builtin_fminf(__fdiv_rn((float)n_bins, m), 3.402823466e+38f);
+    const int64_t total = rows * cols;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < total; e += stride) {
+        const int64_t r = e / cols, c = e - r * cols;
+        const float p = fabsf(x[r * ldx + c]) * to_bin;
+        const int b = p >= (float)n_bins ? n_bins - 1 : (int)p;
+        atomicAdd(&lhist[b], 1u);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < n_bins; i += kThreads)
+        if (lhist[i] != 0u) atomicAdd(&hist[i], (unsigned long long)lhist[i]);
+}
+
+// One workgroup: lane t evaluates candidates t+1, t+1+256, ... over all bins, then the lanes'
+// best candidates are compared in candidate order.
+__global__ __launch_bounds__(kThreads) void mse_sweep_kernel(
+    const unsigned long long* __restrict__ hist, const float* __restrict__ maxabs, int n_bins,
+    int n_cand, float qmax, double* __restrict__ mse_out, float* __restrict__ out) {
+    __shared__ double best_err[kThreads];
+    __shared__ int best_c[kThreads];
+    const float m = maxabs[0];
+    const float width = __fdiv_rn(m, (float)n_bins);
+    double my_err = 0.0;
+    int my_c = 0;
+    for (int c = threadIdx.x + 1; c <= n_cand; c += kThreads) {
+        const float T = m * __fdiv_rn((float)c, (float)n_cand);
+        float inv = 0.0f;
+        if (T > 0.0f) inv = __builtin_fminf(__fdiv_rn(qmax, T), 3.402823466e+38f);
+        const float step = __fdiv_rn(T, qmax);
+        double sum = 0.0;
+        for (int i = 0; i < n_bins; ++i) {
+            const float xi = ((float)i + 0.5f) * width;
+            float code = rintf(xi * inv);
+            code = code > qmax ? qmax : code;
+            code = code < -qmax ? -qmax : code;
+            const double e = (double)xi - (double)code * (double)step;
+            sum += (double)hist[i] * (e * e);
+        }
+        const double err = __ddiv_rn(sum, (double)n_bins);
+        if (mse_out) mse_out[c - 1] = err;
+        if (my_c == 0 || err < my_err) {
+            my_err = err;
+            my_c = c;
+        }
+    }
+    best_err[threadIdx.x] = my_err;
+    best_c[threadIdx.x] = my_c;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double be = 0.0;
+        int bc = 0;
+        for (int t = 0; t < kThreads; ++t) {
+            const int c = best_c[t];
+            if (c == 0) continue;
+            const double e = best_err[t];
+            if (bc == 0 || e < be || (e == be && c < bc)) {
+                be = e;
+                bc = c;
+            }
+        }
+        out[0] = m * __fdiv_rn((float)bc, (float)n_cand);
+        out[1] = m;
+    }
+}
+
+hipError_t launch_mse_clip(const float* x, int64_t ldx, int64_t rows, int64_t cols,
+                           const float* maxabs, int n_bins, int n_cand, float qmax,
+                           unsigned long long* hist, double* mse_out, float* out,
+                           hipStream_t stream) {
+    hist_zero_kernel<<<dim3((unsigned)ceil_div(n_bins, kThreads)), kThreads, 0, stream>>>(hist, n_bins);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    int64_t grid = ceil_div(rows * cols, (int64_t)kThreads * 16);
+    if (grid > 1024) grid = 1024;
+    if (grid < 1) grid = 1;
+    hist_kernel<<<dim3((unsigned)grid), kThreads, (size_t)n_bins * sizeof(unsigned int), stream>>>(
+        x, ldx, rows, cols, maxabs, n_bins, hist);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    mse_sweep_kernel<<<1, kThreads, 0, stream>>>(hist, maxabs, n_bins, n_cand, qmax, mse_out, out);
+    return hipGetLastError();
+}
+
+}  // namespace ocs

@@ -268,6 +268,32 @@ int ocs_act_threshold(const float* X, int64_t M, int C, int g, int64_t ldx, cons
     return OCS_OK;
 }
 
+int ocs_mse_clip_threshold(const float* x, int64_t rows, int64_t cols, int64_t ldx, int bits,
+                           int num_bins, int num_candidates, float* threshold_out,
+                           unsigned long long* hist_out, double* mse_out, void* workspace,
+                           size_t ws_bytes, void* stream) {
+    if (!x || !threshold_out || !hist_out) return OCS_E_NULL;
+    if (rows <= 0 || cols <= 0 || cols > (int64_t)1 << 30 || rows > (int64_t)1 << 31 || ldx < cols)
+        return OCS_E_SHAPE;
+    if (num_bins < 1 || num_bins > 8192 || num_candidates < 1 || num_candidates > 65536)
+        return OCS_E_SHAPE;
+    if (!bits_ok(bits)) return OCS_E_BITS;
+    int rc = check_workspace(workspace, ws_bytes, rows, cols);
+    if (rc) return rc;
+    Workspace w = plan_workspace(rows, cols);
+    char* base = static_cast<char*>(workspace);
+    float* colmax = reinterpret_cast<float*>(base + w.colmax_off);   // two floats used: {max, step}
+    float* partial = reinterpret_cast<float*>(base + w.partial_off);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const float qmax = qmax_of(bits);
+    hipError_t e = launch_absmax_threshold(x, rows, cols, ldx, partial, 1.0f, qmax, colmax, st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = launch_mse_clip(x, ldx, rows, cols, colmax, num_bins, num_candidates, qmax, hist_out,
+                        mse_out, threshold_out, st);
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
 int ocs_split_act(const float* X, int64_t M, int C, int g, int64_t ldx, const int32_t* chan_src,
                   const int32_t* chan_depth, int num_splits, int bits, const float* threshold,
                   float clip_ratio, int8_t* Xq, int64_t ldq, float* scale_out, void* workspace,

@@ -87,6 +87,13 @@ hipError_t launch_expand_quantize_qa(const float* W, int64_t ldw, int64_t N, int
                                      float* W_out, int64_t ldo, int8_t* Wq, int64_t ldq,
                                      hipStream_t stream);
 
+// Sec. 4.1: histogram of |x| (n_bins <= 8192 bins on [0, *maxabs]), error of every candidate
+// threshold, out = {first candidate of least error, *maxabs}.
+hipError_t launch_mse_clip(const float* x, int64_t ldx, int64_t rows, int64_t cols,
+                           const float* maxabs, int n_bins, int n_cand, float qmax,
+                           unsigned long long* hist, double* mse_out, float* out,
+                           hipStream_t stream);
+
 // int8 x int8 -> int32 MFMA GEMM over Kpad (multiple of 64) with dequantizing epilogue.
 hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
                         int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,

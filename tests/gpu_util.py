@@ -93,6 +93,24 @@ def gpu_split_weights_qa(W, Cn, g, s, bits=8, clip_ratio=1.0, want_f32=True, wan
                 Wq=None if Wq is None else host(Wq), scale=host(sc))
 
 
+def gpu_mse_clip(x, bits, n_bins=2048, n_cand=512, want_mse=True, ld_extra=0):
+    rows, cols = x.shape
+    if ld_extra:
+        buf = torch.full((rows, cols + ld_extra), 1e30, dtype=torch.float32, device="cuda")
+        buf[:, :cols] = dev(x)
+        xd = buf[:, :cols]
+    else:
+        xd = dev(x)
+    out = torch.zeros(2, dtype=torch.float32, device="cuda")
+    hist = torch.full((n_bins,), 5, dtype=torch.int64, device="cuda")
+    mse = torch.full((n_cand,), -1.0, dtype=torch.float64, device="cuda") if want_mse else None
+    ws = B.alloc_workspace(rows, cols)
+    B.ocs_mse_clip_threshold(xd, rows, cols, xd.stride(0), bits, n_bins, n_cand, out, hist, mse, ws)
+    o = host(out)
+    return dict(threshold=o[0], max=o[1], hist=host(hist).view(np.uint64),
+                mse=None if mse is None else host(mse))
+
+
 def gpu_split_act(X, Cn, g, chan_src, chan_depth, s, bits, threshold=None, clip_ratio=1.0):
     M = X.shape[0]
     Xd = dev(X)

@@ -7,7 +7,7 @@ import pytest
 from oracle import ref
 from paper_1901_09504_amd import binding as B
 
-from gpu_util import (assert_y_close, gpu_qgemm, gpu_quantize, gpu_select, gpu_split_act,
+from gpu_util import (assert_y_close, gpu_mse_clip, gpu_qgemm, gpu_quantize, gpu_select, gpu_split_act,
                       gpu_split_weights, gpu_split_weights_qa, require_gpu)
 
 pytestmark = pytest.mark.gpu
@@ -210,6 +210,41 @@ def test_qa_layer_end_to_end():
     acc, Y = gpu_qgemm(xq, w_gpu["Wq"], (C + s) * g, sx, w_gpu["scale"], bits_w=5)
     assert np.array_equal(acc, acc_ref)
     assert_y_close(Y, y_ref)
+
+
+# ---- ocs_mse_clip_threshold (Sec. 4.1) ---------------------------------------------------------
+
+@pytest.mark.parametrize("rows,cols,ld_extra", [(1, 1, 0), (64, 256, 0), (33, 147, 5), (257, 2304, 0), (700, 333, 3)])
+@pytest.mark.parametrize("bits,n_bins,n_cand", [(4, 2048, 512), (8, 2048, 512), (6, 64, 7), (3, 1, 1), (5, 8192, 300)])
+def test_mse_clip_threshold(rows, cols, ld_extra, bits, n_bins, n_cand):
+    rng = np.random.default_rng(rows + cols + bits)
+    x = _tensor(rng, rows, cols, "heavy")
+    exp = ref.mse_clip(x, bits, n_bins=n_bins, n_cand=n_cand)
+    got = gpu_mse_clip(x, bits, n_bins=n_bins, n_cand=n_cand, ld_extra=ld_extra)
+    assert got["max"] == exp["max"]
+    assert np.array_equal(got["hist"], exp["hist"])
+    assert np.array_equal(got["mse"], exp["mse"])          # same operations in the same order
+    assert got["threshold"] == exp["threshold"]
+    assert gpu_mse_clip(x, bits, n_bins=n_bins, n_cand=n_cand, want_mse=False)["threshold"] == exp["threshold"]
+
+
+def test_mse_clip_threshold_degenerate_and_large():
+    z = np.zeros((5, 9), dtype=np.float32)
+    got = gpu_mse_clip(z, 8, n_bins=16, n_cand=4)
+    assert got["threshold"] == 0.0 and got["max"] == 0.0 and got["hist"][0] == 45 and not got["mse"].any()
+    ties = _tensor(np.random.default_rng(3), 61, 333, "ties")
+    exp, got = ref.mse_clip(ties, 5, n_bins=128, n_cand=64), gpu_mse_clip(ties, 5, n_bins=128, n_cand=64)
+    assert np.array_equal(got["hist"], exp["hist"]) and np.array_equal(got["mse"], exp["mse"])
+    assert got["threshold"] == exp["threshold"]
+    rng = np.random.default_rng(11)
+    big = np.abs(rng.standard_normal((12544, 2304))).astype(np.float32)      # the bench workload's shape
+    exp, got = ref.mse_clip(big, 4), gpu_mse_clip(big, 4)
+    assert np.array_equal(got["hist"], exp["hist"]) and np.array_equal(got["mse"], exp["mse"])
+    assert got["threshold"] == exp["threshold"] < exp["max"]
+    # the threshold feeds the quantizer
+    q_ref, s_ref = ref.quantize(big[:300], 4, threshold=float(exp["threshold"]), ldq=B.ocs_padded_cols(2304))
+    q, sc = gpu_quantize(big[:300], 4, threshold=float(got["threshold"]))
+    assert np.array_equal(q, q_ref) and np.array_equal(sc, s_ref)
 
 
 # ---- ocs_split_act ---------------------------------------------------------------------------
