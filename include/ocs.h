@@ -230,12 +230,15 @@ int ocs_qgemm(const int8_t *Xq, int64_t ldx, const int8_t *Wq, int64_t ldw, int6
  * Measurement helper (no passage of the paper).  Arms a pair of caller-created hipEvent_t
  * (created with timing enabled) for the calling thread's NEXT launch of one kernel family:
  * OCS_TIME_SPLIT_QUANTIZE (the streaming pass of ocs_split_act / ocs_quantize /
- * ocs_split_weights) or OCS_TIME_GEMM (ocs_qgemm).  That launch stamps the events with the
- * kernel's own begin and end, so hipEventElapsedTime(start, stop) is the kernel's duration
- * as a profiler reports it.  The pair is used once.  Returns OCS_E_MODE for an unknown family.
+ * ocs_split_weights), OCS_TIME_GEMM (ocs_qgemm) or OCS_TIME_ABSMAX (the pass that takes the
+ * largest magnitude for a per-batch grid).  That launch stamps the events with the kernel's
+ * own begin and end, so hipEventElapsedTime(start, stop) is the kernel's duration as a
+ * profiler reports it.  One pair may be pending per family; a pair is used once.  Returns
+ * OCS_E_MODE for an unknown family.
  */
 #define OCS_TIME_SPLIT_QUANTIZE 1
 #define OCS_TIME_GEMM 2
+#define OCS_TIME_ABSMAX 3
 int ocs_time_next(int family, void *start_event, void *stop_event);
 
 /*

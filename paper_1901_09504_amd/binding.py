@@ -121,6 +121,7 @@ def ocs_tune(key, value):
 
 TIME_SPLIT_QUANTIZE = 1
 TIME_GEMM = 2
+TIME_ABSMAX = 3
 
 
 def ocs_time_next(family, start_event, stop_event):

@@ -224,10 +224,11 @@ int ocs_quantize(const float* x, int64_t rows, int64_t cols, int64_t ldx, int bi
         float* colmax = reinterpret_cast<float*>(base + w.colmax_off);
         float* partial = reinterpret_cast<float*>(base + w.partial_off);
         (void)colmax;
-        e = launch_absmax_threshold(x, rows, cols, ldx, partial, clip_ratio, qmax, scale_out, st);
+        int n = 0;
+        e = launch_absmax_partials(x, rows, cols, ldx, partial, &n, st);
         if (e != hipSuccess) return hip_fail(e);
-        e = launch_expand_quantize(x, ldx, rows, (int)cols, 1, 0, nullptr, nullptr, scale_out, qmax,
-                                   q, ldq, nullptr, st);
+        e = launch_expand_quantize(x, ldx, rows, (int)cols, 1, 0, nullptr, nullptr, nullptr, qmax,
+                                   q, ldq, scale_out, st, partial, n, clip_ratio);
     } else {
         e = launch_expand_quantize(x, ldx, rows, (int)cols, 1, 0, nullptr, nullptr, threshold, qmax,
                                    q, ldq, scale_out, st);
@@ -307,6 +308,21 @@ int ocs_split_act(const float* X, int64_t M, int C, int g, int64_t ldx, const in
     if (!bits_ok(bits)) return OCS_E_BITS;
     const float qmax = qmax_of(bits);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (threshold == nullptr && chan_depth == nullptr) {
+        // X1 + X2 with Eq. 3 (copies are not scaled): the expanded tensor's largest magnitude is
+        // X's own.  One pass leaves per-workgroup maxima, the streaming pass folds them itself.
+        rc = check_workspace(workspace, ws_bytes, M, (int64_t)C * g);
+        if (rc) return rc;
+        Workspace w = plan_workspace(M, (int64_t)C * g);
+        float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.partial_off);
+        int n = 0;
+        hipError_t e = launch_absmax_partials(X, M, (int64_t)C * g, ldx, partial, &n, st);
+        if (e != hipSuccess) return hip_fail(e);
+        e = launch_expand_quantize(X, ldx, M, C, g, num_splits, chan_src, nullptr, nullptr, qmax, Xq,
+                                   ldq, scale_out, st, partial, n, clip_ratio);
+        if (e != hipSuccess) return hip_fail(e);
+        return OCS_OK;
+    }
     if (threshold == nullptr) {
         // X1: the dynamic grid needs max|expanded activations| before the streaming pass
         rc = ocs_act_threshold(X, M, C, g, ldx, chan_src, chan_depth, num_splits, bits, clip_ratio,
@@ -346,12 +362,11 @@ int ocs_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int6
 }
 
 int ocs_time_next(int family, void* start_event, void* stop_event) {
-    if (family != kTimeSplitQuantize && family != kTimeGemm) return OCS_E_MODE;
+    if (family != kTimeSplitQuantize && family != kTimeGemm && family != kTimeAbsmax) return OCS_E_MODE;
     if (!start_event || !stop_event) return OCS_E_NULL;
     KernelTimer& t = kernel_timer();
-    t.which = family;
-    t.start = static_cast<hipEvent_t>(start_event);
-    t.stop = static_cast<hipEvent_t>(stop_event);
+    t.start[family] = static_cast<hipEvent_t>(start_event);
+    t.stop[family] = static_cast<hipEvent_t>(stop_event);
     return OCS_OK;
 }
 

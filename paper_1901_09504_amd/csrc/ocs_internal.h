@@ -66,11 +66,19 @@ hipError_t launch_threshold(const float* colmax, int C, int g, int s, const int3
                             float* scale_out, hipStream_t stream);
 
 // Fused gather / halve / quantize / pack: the streaming pass over activations (or weights).
-// thr: device float threshold.  scale_out (may be NULL): receives {T, T/qmax}.
+// thr: device float threshold; or, with partials != NULL, the threshold is
+// clip_ratio * max(partials[0 .. n_partials)), which every workgroup folds for itself.
+// scale_out (may be NULL): receives {T, T/qmax}.
 hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C, int g, int s,
                                   const int32_t* chan_src, const int32_t* chan_depth,
                                   const float* thr, float qmax, int8_t* Xq, int64_t ldq,
-                                  float* scale_out, hipStream_t stream);
+                                  float* scale_out, hipStream_t stream,
+                                  const float* partials = nullptr, int n_partials = 0,
+                                  float clip_ratio = 1.0f);
+
+// Per-workgroup maxima of |T| (stage 1 of the scalar reduction only): partial[0 .. *entries).
+hipError_t launch_absmax_partials(const float* T, int64_t rows, int64_t cols, int64_t ld,
+                                  float* partial, int* entries, hipStream_t stream);
 
 // fp32 expanded tensor: out[r, j*g+t] = T[r, chan_src[j]*g+t] * (halve ? 2^-chan_depth[j] : 1).
 hipError_t launch_expand_f32(const float* T, int64_t ld, int64_t rows, int C, int g, int s,
@@ -108,9 +116,10 @@ hipError_t launch_calib_copy(const void* src, void* dst, size_t bytes, hipStream
 // begin and end (what a profiler reports), not with the time of markers around it.
 constexpr int kTimeSplitQuantize = 1;
 constexpr int kTimeGemm = 2;
+constexpr int kTimeAbsmax = 3;
+constexpr int kTimeFamilies = 4;
 struct KernelTimer {
-    int which = 0;
-    hipEvent_t start = nullptr, stop = nullptr;
+    hipEvent_t start[kTimeFamilies] = {}, stop[kTimeFamilies] = {};   // one pending pair per family
 };
 KernelTimer& kernel_timer();
 
@@ -118,13 +127,35 @@ template <typename F, typename... Args>
 inline hipError_t launch_kernel(int family, F kernel, dim3 grid, dim3 block, unsigned lds,
                                 hipStream_t stream, Args... args) {
     KernelTimer& t = kernel_timer();
-    if (t.which == family && t.start != nullptr && t.stop != nullptr) {
-        t.which = 0;
-        hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, t.start, t.stop, 0, args...);
+    if (family > 0 && family < kTimeFamilies && t.start[family] != nullptr) {
+        hipEvent_t a = t.start[family], b = t.stop[family];
+        t.start[family] = t.stop[family] = nullptr;
+        hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, a, b, 0, args...);
     } else {
         kernel<<<grid, block, lds, stream>>>(args...);
     }
     return hipGetLastError();
+}
+
+// Maximum of a 32-bit unsigned value over the 64 lanes of a wave, returned wave-uniform.  Four
+// DPP exchanges fold each row of 16 lanes (pairs, quads, half rows, row); the four row results
+// are then read through scalar registers.  Non-negative floats order like their bit patterns.
+__device__ __forceinline__ unsigned wave_umax32(unsigned v) {
+    unsigned o;
+    o = (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+    v = o > v ? o : v;
+    o = (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
+    v = o > v ? o : v;
+    o = (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x141, 0xF, 0xF, false);  // row_half_mirror
+    v = o > v ? o : v;
+    o = (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x140, 0xF, 0xF, false);  // row_mirror
+    v = o > v ? o : v;
+    const unsigned r0 = (unsigned)__builtin_amdgcn_readlane((int)v, 0);
+    const unsigned r1 = (unsigned)__builtin_amdgcn_readlane((int)v, 16);
+    const unsigned r2 = (unsigned)__builtin_amdgcn_readlane((int)v, 32);
+    const unsigned r3 = (unsigned)__builtin_amdgcn_readlane((int)v, 48);
+    const unsigned a = r0 > r1 ? r0 : r1, b = r2 > r3 ? r2 : r3;
+    return a > b ? a : b;
 }
 
 // Launch-shape overrides (benchmarking only); < 0 means "use the default".

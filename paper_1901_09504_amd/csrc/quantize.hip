@@ -36,6 +36,26 @@ __device__ __forceinline__ float inv_step_of(float T, float qmax) {
     return __builtin_fminf(__fdiv_rn(qmax, T), 3.402823466e+38f);
 }
 
+// The threshold of the pass: the given device float, or, for a per-batch grid, clip_ratio times
+// the largest of the per-workgroup maxima the preceding pass left behind (a few thousand
+// floats, folded by every workgroup for itself: cheaper than a separate launch that does only
+// that).  All lanes return the same value; contains a barrier.
+__device__ __forceinline__ float pass_threshold(const float* thr, const float* partials, int n,
+                                                float clip_ratio, float* red /* >= 4 floats of LDS */) {
+    if (partials == nullptr) {
+        const float T = *thr;
+        __syncthreads();
+        return T;
+    }
+    float m = 0.0f;
+    for (int i = threadIdx.x; i < n; i += kThreads) m = fmaxf(m, partials[i]);
+    const unsigned w = wave_umax32(__float_as_uint(m));      // maxima of magnitudes: non-negative
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = __uint_as_float(w);
+    __syncthreads();
+    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    return clip_ratio * m;
+}
+
 template <bool NT>
 __device__ __forceinline__ f32x4 load4(const f32x4* p) {
     if (NT) return __builtin_nontemporal_load(p);
@@ -60,7 +80,9 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
     const float* __restrict__ X, int64_t ldx, int64_t M, int C, int g, int s,
     const int32_t* __restrict__ chan_src, const int32_t* __restrict__ chan_depth,
     const float* thr, float qmax, int8_t* __restrict__ Xq, int D, int main_units,
-    unsigned magic, float* scale_out) {
+    unsigned magic, float* scale_out, const float* __restrict__ partials, int n_partials,
+    float clip_ratio) {
+    __shared__ float thr_red[kThreads / 64];
     // Source column (or -1 for padding) and halving depth of every column past the vector
     // region.  They do not depend on the row, so each workgroup resolves them once; a lane that
     // lands on such a column then needs a single trip to memory, like every other lane.
@@ -184,13 +206,12 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
     int d[UN] = {}, nd[UN] = {};
 #pragma unroll
     for (int u = 0; u < UN; ++u) fetch(o + (Index)u * stride, cur[u], row[u], d[u]);
-    const float T = *thr;
+    const float T = pass_threshold(thr, partials, n_partials, clip_ratio, thr_red);  // + barrier
     const float inv = inv_step_of(T, qmax);
     if (scale_out != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
         scale_out[0] = T;
         scale_out[1] = T / qmax;
     }
-    __syncthreads();
 
     for (; o < total; o += (Index)UN * stride) {
 #pragma unroll
@@ -220,7 +241,8 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_in_kernel(
     const float* __restrict__ X, int64_t ldx, int64_t M, int C, int g, int s,
     const int32_t* __restrict__ chan_src, const int32_t* __restrict__ chan_depth,
     const float* thr, float qmax, int8_t* __restrict__ Xq, int D, int Q, unsigned magic,
-    float* scale_out) {
+    float* scale_out, const float* __restrict__ partials, int n_partials, float clip_ratio) {
+    __shared__ float thr_red[kThreads / 64];
     __shared__ int tail_col[kTailTable];
     __shared__ int tail_dep[HALVE ? kTailTable : 1];
     const int Ke = (C + s) * g;
@@ -304,13 +326,13 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_in_kernel(
     Index row = 0, nrow = 0;
     int d = 0, nd = 0;
     fetch_main(o, cur, row, d);       // requested before anything waits on the threshold
-    const float T = *thr;
+    const float T = pass_threshold(thr, partials, n_partials, clip_ratio, thr_red);
     const float inv = inv_step_of(T, qmax);
     if (scale_out != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
         scale_out[0] = T;
         scale_out[1] = T / qmax;
     }
-    __syncthreads();                  // the column table is complete
+    // (the barrier inside pass_threshold also completes the column table)
     fetch_tail(o, row, d, tcur);
 
     for (; o < total; o += stride) {
@@ -327,7 +349,8 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_in_kernel(
 hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C, int g, int s,
                                   const int32_t* chan_src, const int32_t* chan_depth,
                                   const float* thr, float qmax, int8_t* Xq, int64_t ldq,
-                                  float* scale_out, hipStream_t stream) {
+                                  float* scale_out, hipStream_t stream, const float* partials,
+                                  int n_partials, float clip_ratio) {
     const int64_t K = (int64_t)C * g;
     const bool vec_ok = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 4 == 0);
     const int main_units = vec_ok ? (int)(K / 4) : 0;
@@ -356,7 +379,7 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
 #define OCS_LAUNCH_IN(H, I_)                                                                       \
     launch_kernel(kTimeSplitQuantize, expand_quantize_in_kernel<H, I_>, dim3((unsigned)gin),      \
                   dim3(kThreads), 0, stream, X, ldx, M, C, g, s, chan_src, chan_depth, thr, qmax,  \
-                  Xq, D, Q, magic_q, scale_out)
+                  Xq, D, Q, magic_q, scale_out, partials, n_partials, clip_ratio)
         if (wide_in) return halve ? OCS_LAUNCH_IN(true, uint64_t) : OCS_LAUNCH_IN(false, uint64_t);
         return halve ? OCS_LAUNCH_IN(true, uint32_t) : OCS_LAUNCH_IN(false, uint32_t);
 #undef OCS_LAUNCH_IN
@@ -372,7 +395,7 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
 #define OCS_LAUNCH_EQ(H, N_, U_, I_)                                                              \
     err = launch_kernel(kTimeSplitQuantize, expand_quantize_kernel<H, N_, U_, I_>, dim3((unsigned)grid), \
                   dim3(kThreads), 0, stream, X, ldx, M, C, g, s, chan_src, chan_depth, thr, qmax,  \
-                  Xq, D, main_units, magic, scale_out)
+                  Xq, D, main_units, magic, scale_out, partials, n_partials, clip_ratio)
 #define OCS_LAUNCH_U(H, N_, I_)                                                                   \
     do {                                                                                          \
         if (un == 4) OCS_LAUNCH_EQ(H, N_, 4, I_);                                                 \

@@ -136,10 +136,12 @@ static hipError_t launch_partials(const float* T, int64_t rows, int64_t cols, in
     if (p.vec == 4) {
         int64_t units = cols / 4;
         dim3 grid(p.col_strips, p.row_blocks);
-        if (scalar)
-            colmax_partial_kernel<4, true><<<grid, block, 0, stream>>>(T, ld, rows, 0, units,
-                                                                       p.rows_per_block, cols, partial);
-        else
+        if (scalar) {
+            hipError_t te = launch_kernel(kTimeAbsmax, colmax_partial_kernel<4, true>, grid, block, 0,
+                                          stream, T, ld, rows, (int64_t)0, units, p.rows_per_block,
+                                          cols, partial);
+            if (te != hipSuccess) return te;
+        } else
             colmax_partial_kernel<4, false><<<grid, block, 0, stream>>>(T, ld, rows, 0, units,
                                                                         p.rows_per_block, cols, partial);
         n = p.col_strips * p.row_blocks;
@@ -197,6 +199,13 @@ __global__ __launch_bounds__(kThreads) void threshold_scalar_kernel(const float*
         scale_out[0] = T;
         scale_out[1] = T / qmax;
     }
+}
+
+hipError_t launch_absmax_partials(const float* T, int64_t rows, int64_t cols, int64_t ld,
+                                  float* partial, int* entries, hipStream_t stream) {
+    bool vec_ok = (reinterpret_cast<uintptr_t>(T) % 16 == 0) && (ld % 4 == 0);
+    ReducePlan p = plan_reduce(rows, cols, vec_ok);
+    return launch_partials(T, rows, cols, ld, partial, true, p, entries, stream);
 }
 
 hipError_t launch_absmax_threshold(const float* T, int64_t rows, int64_t cols, int64_t ld,

@@ -16,28 +16,6 @@ __device__ inline unsigned long long key_of(float v, int j) {
     return ((unsigned long long)__float_as_uint(v) << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)j);
 }
 
-// Maximum of a 32-bit value over the 64 lanes of a wave, returned wave-uniform.  Four DPP
-// exchanges fold each row of 16 lanes (pairs, quads, half rows, row); the four row results
-// are then read through scalar registers.  Far cheaper than six rounds of cross-lane shuffles
-// through the LDS crossbar, which is what dominated a greedy step.
-__device__ __forceinline__ unsigned wave_umax32(unsigned v) {
-    unsigned o;
-    o = (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
-    v = o > v ? o : v;
-    o = (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
-    v = o > v ? o : v;
-    o = (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x141, 0xF, 0xF, false);  // row_half_mirror
-    v = o > v ? o : v;
-    o = (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x140, 0xF, 0xF, false);  // row_mirror
-    v = o > v ? o : v;
-    const unsigned r0 = (unsigned)__builtin_amdgcn_readlane((int)v, 0);
-    const unsigned r1 = (unsigned)__builtin_amdgcn_readlane((int)v, 16);
-    const unsigned r2 = (unsigned)__builtin_amdgcn_readlane((int)v, 32);
-    const unsigned r3 = (unsigned)__builtin_amdgcn_readlane((int)v, 48);
-    const unsigned a = r0 > r1 ? r0 : r1, b = r2 > r3 ? r2 : r3;
-    return a > b ? a : b;
-}
-
 // Largest key of the wave: largest value first, then (through the complemented index in the
 // low word) the lowest index among the lanes that hold it.
 __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long k) {
