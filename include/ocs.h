@@ -160,8 +160,8 @@ int ocs_split_weights_qa(const float *W, int64_t N, int C, int g, int64_t ldw, i
  *        evaluated in fp64, bins in increasing order.  The first candidate of least error wins.
  *   threshold_out device float[2] = {chosen threshold, m}; element 0 can be handed to
  *        ocs_quantize / ocs_split_act as their `threshold`.
- *   hist_out device uint64[num_bins], required: the frequencies (also the routine's scratch).
- *   mse_out device double[num_candidates], may be NULL: the error of every candidate.
+ *   hist_out device uint64[num_bins] and mse_out device double[num_candidates], both required:
+ *        the frequencies and the error of every candidate (outputs, and the routine's scratch).
  * workspace as for ocs_quantize on the same shape.
  */
 int ocs_mse_clip_threshold(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bits,

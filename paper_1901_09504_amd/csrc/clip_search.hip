@@ -6,7 +6,7 @@
 // candidate with the least error is the result.  Bin decisions and codes are taken in fp32
 // with the same operation order as everywhere else in the library; errors are accumulated in
 // fp64 over the bins in increasing order, one candidate per lane, so that the choice does not
-// depend on how the work is spread.
+// depend on how the work is spread over workgroups.
 #include "ocs_internal.h"
 
 namespace ocs {
@@ -30,44 +30,72 @@ __global__ __launch_bounds__(kThreads) void hist_kernel(const float* __restrict_
     if (m > 0.0f) to_bin = __builtin_fminf(__fdiv_rn((float)n_bins, m), 3.402823466e+38f);
     const int64_t total = rows * cols;
     const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < total; e += stride) {
-        const int64_t r = e / cols, c = e - r * cols;
-        const float p = fabsf(x[r * ldx + c]) * to_bin;
-        const int b = p >= (float)n_bins ? n_bins - 1 : (int)p;
-        atomicAdd(&lhist[b], 1u);
+    const bool flat16 = ldx == cols && total % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0;
+    if (flat16) {       // one contiguous, 16-byte aligned range: four values per load
+        const f32x4* x4 = reinterpret_cast<const f32x4*>(x);
+        for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < total / 4; e += stride) {
+            const f32x4 v = x4[e];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float p = fabsf(v[k]) * to_bin;
+                const int b = p >= (float)n_bins ? n_bins - 1 : (int)p;
+                atomicAdd(&lhist[b], 1u);
+            }
+        }
+    } else {
+        for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < total; e += stride) {
+            const int64_t r = e / cols, c = e - r * cols;
+            const float p = fabsf(x[r * ldx + c]) * to_bin;
+            const int b = p >= (float)n_bins ? n_bins - 1 : (int)p;
+            atomicAdd(&lhist[b], 1u);
+        }
     }
     __syncthreads();
     for (int i = threadIdx.x; i < n_bins; i += kThreads)
         if (lhist[i] != 0u) atomicAdd(&hist[i], (unsigned long long)lhist[i]);
 }
 
-// One workgroup: lane t evaluates candidates t+1, t+1+256, ... over all bins, then the lanes'
-// best candidates are compared in candidate order.
-__global__ __launch_bounds__(kThreads) void mse_sweep_kernel(
+// Error of every candidate: one candidate per lane, one wave per workgroup so that the
+// candidates spread over many CUs; each lane walks the bins in increasing order.
+__global__ __launch_bounds__(64) void mse_sweep_kernel(
     const unsigned long long* __restrict__ hist, const float* __restrict__ maxabs, int n_bins,
-    int n_cand, float qmax, double* __restrict__ mse_out, float* __restrict__ out) {
-    __shared__ double best_err[kThreads];
-    __shared__ int best_c[kThreads];
+    int n_cand, float qmax, double* __restrict__ mse_out) {
+    // the frequencies as doubles in LDS: every lane reads every bin
+    extern __shared__ double hd[];
+    for (int i = threadIdx.x; i < n_bins; i += 64) hd[i] = (double)hist[i];
+    __syncthreads();
+    const int c = blockIdx.x * 64 + threadIdx.x + 1;
+    if (c > n_cand) return;
     const float m = maxabs[0];
     const float width = __fdiv_rn(m, (float)n_bins);
+    const float T = m * __fdiv_rn((float)c, (float)n_cand);
+    float inv = 0.0f;
+    if (T > 0.0f) inv = __builtin_fminf(__fdiv_rn(qmax, T), 3.402823466e+38f);
+    const float step = __fdiv_rn(T, qmax);
+    double sum = 0.0;
+#pragma unroll 8
+    for (int i = 0; i < n_bins; ++i) {       // the additions stay in bin order
+        const float xi = ((float)i + 0.5f) * width;
+        float code = rintf(xi * inv);
+        code = code > qmax ? qmax : code;
+        code = code < -qmax ? -qmax : code;
+        const double e = (double)xi - (double)code * (double)step;
+        sum += hd[i] * (e * e);
+    }
+    mse_out[c - 1] = __ddiv_rn(sum, (double)n_bins);
+}
+
+// The first candidate of least error.  One workgroup; lane t looks at candidates t+1,
+// t+1+256, ... in increasing order, then the lanes' bests are compared in candidate order.
+__global__ __launch_bounds__(kThreads) void mse_argmin_kernel(const double* __restrict__ mse,
+                                                              const float* __restrict__ maxabs,
+                                                              int n_cand, float* __restrict__ out) {
+    __shared__ double best_err[kThreads];
+    __shared__ int best_c[kThreads];
     double my_err = 0.0;
     int my_c = 0;
     for (int c = threadIdx.x + 1; c <= n_cand; c += kThreads) {
-        const float T = m * __fdiv_rn((float)c, (float)n_cand);
-        float inv = 0.0f;
-        if (T > 0.0f) inv = __builtin_fminf(__fdiv_rn(qmax, T), 3.402823466e+38f);
-        const float step = __fdiv_rn(T, qmax);
-        double sum = 0.0;
-        for (int i = 0; i < n_bins; ++i) {
-            const float xi = ((float)i + 0.5f) * width;
-            float code = rintf(xi * inv);
-            code = code > qmax ? qmax : code;
-            code = code < -qmax ? -qmax : code;
-            const double e = (double)xi - (double)code * (double)step;
-            sum += (double)hist[i] * (e * e);
-        }
-        const double err = __ddiv_rn(sum, (double)n_bins);
-        if (mse_out) mse_out[c - 1] = err;
+        const double err = mse[c - 1];
         if (my_c == 0 || err < my_err) {
             my_err = err;
             my_c = c;
@@ -88,6 +116,7 @@ __global__ __launch_bounds__(kThreads) void mse_sweep_kernel(
                 bc = c;
             }
         }
+        const float m = maxabs[0];
         out[0] = m * __fdiv_rn((float)bc, (float)n_cand);
         out[1] = m;
     }
@@ -107,7 +136,11 @@ hipError_t launch_mse_clip(const float* x, int64_t ldx, int64_t rows, int64_t co
         x, ldx, rows, cols, maxabs, n_bins, hist);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    mse_sweep_kernel<<<1, kThreads, 0, stream>>>(hist, maxabs, n_bins, n_cand, qmax, mse_out, out);
+    mse_sweep_kernel<<<dim3((unsigned)ceil_div(n_cand, 64)), 64, (size_t)n_bins * sizeof(double), stream>>>(hist, maxabs, n_bins,
+                                                                              n_cand, qmax, mse_out);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    mse_argmin_kernel<<<1, kThreads, 0, stream>>>(mse_out, maxabs, n_cand, out);
     return hipGetLastError();
 }
 

@@ -273,7 +273,7 @@ int ocs_mse_clip_threshold(const float* x, int64_t rows, int64_t cols, int64_t l
                            int num_bins, int num_candidates, float* threshold_out,
                            unsigned long long* hist_out, double* mse_out, void* workspace,
                            size_t ws_bytes, void* stream) {
-    if (!x || !threshold_out || !hist_out) return OCS_E_NULL;
+    if (!x || !threshold_out || !hist_out || !mse_out) return OCS_E_NULL;
     if (rows <= 0 || cols <= 0 || cols > (int64_t)1 << 30 || rows > (int64_t)1 << 31 || ldx < cols)
         return OCS_E_SHAPE;
     if (num_bins < 1 || num_bins > 8192 || num_candidates < 1 || num_candidates > 65536)

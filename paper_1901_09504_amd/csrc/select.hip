@@ -87,11 +87,28 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
             }
             __syncthreads();
             if (owns_old || owns_new) {
-                local = 0;
-                for (int j = tid; j <= cur; j += kThreads) {
-                    unsigned long long kk = key_of(vals[j], j);
-                    local = kk > local ? kk : local;
+                // re-scan of this lane's slots: four independent LDS reads per trip, so their
+                // latencies overlap (with thousands of channels this loop is most of a step)
+                unsigned long long l0 = 0, l1 = 0, l2 = 0, l3 = 0;
+                int j = tid;
+                for (; j + 3 * kThreads <= cur; j += 4 * kThreads) {
+                    const float v0 = vals[j], v1 = vals[j + kThreads], v2 = vals[j + 2 * kThreads],
+                                v3 = vals[j + 3 * kThreads];
+                    const unsigned long long k0 = key_of(v0, j), k1 = key_of(v1, j + kThreads),
+                                             k2 = key_of(v2, j + 2 * kThreads),
+                                             k3 = key_of(v3, j + 3 * kThreads);
+                    l0 = k0 > l0 ? k0 : l0;
+                    l1 = k1 > l1 ? k1 : l1;
+                    l2 = k2 > l2 ? k2 : l2;
+                    l3 = k3 > l3 ? k3 : l3;
                 }
+                for (; j <= cur; j += kThreads) {
+                    const unsigned long long kk = key_of(vals[j], j);
+                    l0 = kk > l0 ? kk : l0;
+                }
+                l0 = l0 > l1 ? l0 : l1;
+                l2 = l2 > l3 ? l2 : l3;
+                local = l0 > l2 ? l0 : l2;
             }
         }
     } else {

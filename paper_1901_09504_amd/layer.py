@@ -102,8 +102,11 @@ class ExpandedLayer:
                             self.split_src, self.chan_src, self.chan_depth, None, 0, self.wmax,
                             self.bits_w, self.clip_ratio_w, self.Wq, self.ldq, self.scale_w,
                             self.ws_w, stream)
+        # the selector already returned the largest magnitude of the halved activations: with no
+        # clipping that is the threshold, and the pass over X that would recompute it is skipped
+        thr = xmax if self.clip_ratio_x == 1.0 else None
         B.ocs_split_act(X, M, self.C, self.g, X.stride(0), self.chan_src, self.chan_depth, self.s,
-                        self.bits_x, None, self.clip_ratio_x, self.Xq, self.ldq, self.scale_x,
+                        self.bits_x, thr, self.clip_ratio_x, self.Xq, self.ldq, self.scale_x,
                         self.ws_x, stream)
         self.qgemm(M, acc_out, stream)
         return self.Y[:M]

@@ -66,10 +66,11 @@ def test_argument_errors_are_reported_without_a_device():
     assert L.ocs_split_weights_qa(A, 4, 4, 1, 4, 1, A, A, A, A, None, 0, 8, 1.0, None, 0, A, A, ws, None) == -1  # no output
     assert L.ocs_split_weights_qa(A, 4, 4, 1, 4, 1, A, A, A, A, A, 4, 8, 1.0, None, 0, A, A, ws, None) == -2    # ldo < (C+s)*g
     assert L.ocs_split_weights_qa(A, 4, 4, 1, 4, 1, A, A, A, A, A, 8, 9, 1.0, None, 0, A, A, ws, None) == -4    # bits
-    assert L.ocs_mse_clip_threshold(A, 4, 4, 4, 8, 16, 4, A, None, None, A, ws, None) == -1   # no histogram
-    assert L.ocs_mse_clip_threshold(A, 4, 4, 4, 8, 0, 4, A, A, None, A, ws, None) == -2       # no bins
-    assert L.ocs_mse_clip_threshold(A, 4, 4, 4, 8, 9000, 4, A, A, None, A, ws, None) == -2
-    assert L.ocs_mse_clip_threshold(A, 4, 4, 4, 1, 16, 4, A, A, None, A, ws, None) == -4
+    assert L.ocs_mse_clip_threshold(A, 4, 4, 4, 8, 16, 4, A, None, A, A, ws, None) == -1   # no histogram
+    assert L.ocs_mse_clip_threshold(A, 4, 4, 4, 8, 16, 4, A, A, None, A, ws, None) == -1   # no error array
+    assert L.ocs_mse_clip_threshold(A, 4, 4, 4, 8, 0, 4, A, A, A, A, ws, None) == -2       # no bins
+    assert L.ocs_mse_clip_threshold(A, 4, 4, 4, 8, 9000, 4, A, A, A, A, ws, None) == -2
+    assert L.ocs_mse_clip_threshold(A, 4, 4, 4, 1, 16, 4, A, A, A, A, ws, None) == -4
     # shapes
     assert L.ocs_quantize(A, 0, 4, 4, 8, A, 1.0, A, 64, A, A, ws, None) == -2
     assert L.ocs_quantize(A, 4, 8, 4, 8, A, 1.0, A, 64, A, A, ws, None) == -2      # ldx < cols
