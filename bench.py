@@ -33,8 +33,8 @@ METRIC = "expanded int8 GEMM TOPS (% MFMA peak); split+quantize GB/s (% HBM)"
 # runs (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for the plain
 # copy kernel of known size launched after the timed region (profiles/x2_config2_hbm_traffic.md).
 # Valid only for the kernel source it was measured on: reported as null once that file changes.
-X2_TRAFFIC = {"quantize_hip_sha256": "5de5a62c3da25c0900a0e784b14ae286a7028db7090a783b8f09586406b472ee",
-              "bytes_per_launch": 145603201}
+X2_TRAFFIC = {"quantize_hip_sha256": "f520f034aa2206f86738eacd4a015f848468ce147da612af42033f8200c60063",
+              "bytes_per_launch": 145722929}
 
 
 def x2_traffic():
