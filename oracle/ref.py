@@ -124,6 +124,32 @@ def mse_clip(x, bits, n_bins=2048, n_cand=512):
     return dict(threshold=out[0], max=out[1], hist=hist, mse=mse)
 
 
+def conv_out_size(n, k, stride, pad):
+    return (n + 2 * pad - k) // stride + 1
+
+
+def im2col(A, kh, kw, stride=1, pad=0):
+    """The lowering of a convolution to the GEMM of Eq. 2, written out: A [B, H, W, C] (any
+    dtype) -> X [B*Ho*Wo, C*kh*kw] with X[(b, yo, xo), c*kh*kw + ky*kw + kx] =
+    A[b, yo*stride + ky - pad, xo*stride + kx - pad, c], zero outside the image.  Column order
+    matches a [N, C, kh, kw] weight reshaped to [N, C*kh*kw] (channel c owns kh*kw columns)."""
+    A = np.asarray(A)
+    Bn, H, W, Cn = A.shape
+    Ho, Wo = conv_out_size(H, kh, stride, pad), conv_out_size(W, kw, stride, pad)
+    X = np.zeros((Bn, Ho, Wo, Cn, kh * kw), dtype=A.dtype)
+    for ky in range(kh):
+        for kx in range(kw):
+            for yo in range(Ho):
+                iy = yo * stride + ky - pad
+                if iy < 0 or iy >= H:
+                    continue
+                for xo in range(Wo):
+                    ix = xo * stride + kx - pad
+                    if 0 <= ix < W:
+                        X[:, yo, xo, :, ky * kw + kx] = A[:, iy, ix, :]
+    return X.reshape(Bn * Ho * Wo, Cn * kh * kw)
+
+
 def quantize(x, bits, threshold=None, clip_ratio=1.0, ldq=None):
     """Eq. 1 (+ clip).  Returns (codes [rows, ldq] int8, scale float32[2] = {T, step})."""
     x = np.ascontiguousarray(x, dtype=np.float32)

@@ -521,3 +521,46 @@ def test_mse_clip_single_bin_closed_form_and_outlier_behaviour():
         assert r["threshold"] == np.float32(40.0) * (np.float32(c + 1) / np.float32(512))
     z = ref.mse_clip(np.zeros((3, 4), dtype=np.float32), 8, n_bins=8, n_cand=4)
     assert z["threshold"] == 0.0 and z["max"] == 0.0 and z["hist"][0] == 12
+
+
+# ---- convolution lowered to the GEMM of Eq. 2 ----------------------------------------------
+
+@pytest.mark.parametrize("kh,kw,stride,pad", [(3, 3, 1, 1), (1, 1, 2, 0), (3, 3, 2, 1), (7, 7, 2, 3), (2, 3, 1, 0)])
+def test_im2col_is_the_convolution_sum(kh, kw, stride, pad):
+    # the lowered GEMM against the convolution written as its defining sum
+    rng = np.random.default_rng(kh * 10 + stride)
+    Bn, H, W, Cn, N = 2, 6, 5, 3, 4
+    A = rng.integers(-5, 6, (Bn, H, W, Cn)).astype(np.float64)
+    Wt = rng.integers(-5, 6, (N, Cn, kh, kw)).astype(np.float64)
+    X = ref.im2col(A, kh, kw, stride, pad)
+    Ho, Wo = ref.conv_out_size(H, kh, stride, pad), ref.conv_out_size(W, kw, stride, pad)
+    assert X.shape == (Bn * Ho * Wo, Cn * kh * kw)
+    Y = (X @ Wt.reshape(N, -1).T).reshape(Bn, Ho, Wo, N)
+    for b in range(Bn):
+        for yo in range(Ho):
+            for xo in range(Wo):
+                for n in range(N):
+                    acc = 0.0
+                    for c in range(Cn):
+                        for ky in range(kh):
+                            for kx in range(kw):
+                                iy, ix = yo * stride + ky - pad, xo * stride + kx - pad
+                                if 0 <= iy < H and 0 <= ix < W:
+                                    acc += A[b, iy, ix, c] * Wt[n, c, ky, kx]
+                    assert Y[b, yo, xo, n] == acc
+
+
+def test_quantizing_before_or_after_the_lowering_gives_the_same_codes():
+    # Eq. 1 acts element by element and sends 0 to 0, so splitting + quantizing the un-lowered
+    # activation once and lowering the codes equals lowering first (g = kh*kw columns per channel)
+    rng = np.random.default_rng(123)
+    Bn, H, W, Cn, s, kh, kw = 2, 5, 4, 6, 3, 3, 3
+    A = rng.standard_normal((Bn, H, W, Cn)).astype(np.float32)
+    A[1, 2, 3, 4] = 9.0
+    Wt = rng.standard_normal((7, Cn * kh * kw)).astype(np.float32)
+    sel = ref.split_weights(Wt, Cn, kh * kw, s)
+    T = float(np.abs(A).max())
+    Aq, sa, _ = ref.split_act(A.reshape(-1, Cn), Cn, 1, sel["chan_src"], None, s, 8, threshold=T)
+    lowered_codes = ref.im2col(Aq.reshape(Bn, H, W, Cn + s), kh, kw, 1, 1)
+    Xq, sx, _ = ref.split_act(ref.im2col(A, kh, kw, 1, 1), Cn, kh * kw, sel["chan_src"], None, s, 8, threshold=T)
+    assert np.array_equal(sa, sx) and np.array_equal(lowered_codes, Xq)
