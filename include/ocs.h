@@ -227,6 +227,34 @@ int ocs_qgemm(const int8_t *Xq, int64_t ldx, const int8_t *Wq, int64_t ldw, int6
               size_t ws_bytes, void *stream);
 
 /*
+ * A convolution as the linear layer of Eq. 2 over its input channels (Sec. 3.2: a channel of a
+ * convolution is a whole 2-D activation plane with the 2-D filters attached to it), with the
+ * lowering to a GEMM done inside the kernel's operand loader instead of materialising the
+ * lowered (im2col) activation.  The activation is split and quantized ONCE, un-lowered, by
+ * ocs_split_act with g = 1 on its [B*H*W, C] view (kh*kw times less traffic than the lowered
+ * matrix); every code of the lowered matrix is a code of that tensor, or zero outside the image.
+ *
+ * ocs_conv_weights_tap_major: weight codes Wq [N, ldq] as ocs_split_weights writes them for
+ *   g = kh*kw (expanded channel j owns columns j*g .. j*g+g-1) -> Wt [N + 1, g*ldc] with
+ *   Wt[n, t*ldc + j] = Wq[n, j*g + t] for j < C_exp = C + num_splits, zero for j >= C_exp, and
+ *   row N all zeros (the kernel reads it for taps outside the image).  ldc: bytes per pixel of
+ *   the activation codes, a multiple of OCS_KALIGN, >= C_exp.
+ *
+ * ocs_qconv: Aq [B, H, W, ldc] int8 (channels C_exp .. ldc-1 zero, as ocs_split_act pads),
+ *   kernel kh x kw, stride, zero padding pad on every side; output pixel (b, yo, xo) is row
+ *   (b*Ho + yo)*Wo + xo of Y [B*Ho*Wo, N] fp32 (and of acc_out, optional int32), Ho = (H + 2*pad
+ *   - kh)/stride + 1.  acc = sum over taps and expanded channels of code products, exactly the
+ *   accumulator ocs_qgemm gives on the lowered codes; Y = float(acc) * (scale_x[1]*scale_w[1]).
+ * Both calls: device pointers, asynchronous on `stream`, 16-byte aligned code tensors.
+ */
+int ocs_conv_weights_tap_major(const int8_t *Wq, int64_t N, int C_exp, int g, int64_t ldq,
+                               int8_t *Wt, int64_t ldc, void *stream);
+int ocs_qconv(const int8_t *Aq, int64_t ldc, int B, int H, int W, int C_exp, int kh, int kw,
+              int stride, int pad, const int8_t *Wt, int64_t N, int bits_x, int bits_w,
+              const float *scale_x, const float *scale_w, int32_t *acc_out, int64_t ldacc,
+              float *Y, int64_t ldy, void *stream);
+
+/*
  * Measurement helper (no passage of the paper).  Arms a pair of caller-created hipEvent_t
  * (created with timing enabled) for the calling thread's NEXT launch of one kernel family:
  * OCS_TIME_SPLIT_QUANTIZE (the streaming pass of ocs_split_act / ocs_quantize /

@@ -60,6 +60,11 @@ def lib():
                                        _i32, _f32, _vp, _i64, _vp, _vp, _sz, _vp]
     L.ocs_mse_clip_threshold.restype = _i32
     L.ocs_mse_clip_threshold.argtypes = [_vp, _i64, _i64, _i64, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]
+    L.ocs_conv_weights_tap_major.restype = _i32
+    L.ocs_conv_weights_tap_major.argtypes = [_vp, _i64, _i32, _i32, _i64, _vp, _i64, _vp]
+    L.ocs_qconv.restype = _i32
+    L.ocs_qconv.argtypes = [_vp, _i64, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _i64, _i32,
+                            _i32, _vp, _vp, _vp, _i64, _vp, _i64, _vp]
     L.ocs_quantize.restype = _i32
     L.ocs_quantize.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _f32, _vp, _i64, _vp, _vp, _sz, _vp]
     L.ocs_split_act.restype = _i32
@@ -175,6 +180,18 @@ def ocs_mse_clip_threshold(x, rows, cols, ldx, bits, num_bins, num_candidates, t
     _check(lib().ocs_mse_clip_threshold(_ptr(x), rows, cols, ldx, bits, num_bins, num_candidates,
                                         _ptr(threshold_out), _ptr(hist_out), _ptr(mse_out), w, wb,
                                         _stream(stream)), "ocs_mse_clip_threshold")
+
+
+def ocs_conv_weights_tap_major(Wq, N, C_exp, g, ldq, Wt, ldc, stream=None):
+    _check(lib().ocs_conv_weights_tap_major(_ptr(Wq), N, C_exp, g, ldq, _ptr(Wt), ldc, _stream(stream)),
+           "ocs_conv_weights_tap_major")
+
+
+def ocs_qconv(Aq, ldc, Bn, H, W, C_exp, kh, kw, stride, pad, Wt, N, bits_x, bits_w, scale_x, scale_w,
+              acc_out, ldacc, Y, ldy, stream=None):
+    _check(lib().ocs_qconv(_ptr(Aq), ldc, Bn, H, W, C_exp, kh, kw, stride, pad, _ptr(Wt), N, bits_x,
+                           bits_w, _ptr(scale_x), _ptr(scale_w), _ptr(acc_out), ldacc, _ptr(Y), ldy,
+                           _stream(stream)), "ocs_qconv")
 
 
 def ocs_quantize(x, rows, cols, ldx, bits, threshold, clip_ratio, q, ldq, scale_out, workspace,

@@ -361,6 +361,42 @@ int ocs_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int6
     return OCS_OK;
 }
 
+int ocs_conv_weights_tap_major(const int8_t* Wq, int64_t N, int C_exp, int g, int64_t ldq,
+                               int8_t* Wt, int64_t ldc, void* stream) {
+    if (!Wq || !Wt) return OCS_E_NULL;
+    if (N <= 0 || C_exp <= 0 || g <= 0 || N > (int64_t)1 << 30) return OCS_E_SHAPE;
+    if (ldq < (int64_t)C_exp * g || ldc < C_exp || (int64_t)g * ldc > (int64_t)1 << 30) return OCS_E_SHAPE;
+    if (ldc % OCS_KALIGN != 0 || !aligned(Wt, 16)) return OCS_E_ALIGN;
+    hipError_t e = launch_tap_major(Wq, ldq, N, C_exp, g, ldc, Wt, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
+int ocs_qconv(const int8_t* Aq, int64_t ldc, int B, int H, int W, int C_exp, int kh, int kw,
+              int stride, int pad, const int8_t* Wt, int64_t N, int bits_x, int bits_w,
+              const float* scale_x, const float* scale_w, int32_t* acc_out, int64_t ldacc, float* Y,
+              int64_t ldy, void* stream) {
+    if (!Aq || !Wt || !scale_x || !scale_w || !Y) return OCS_E_NULL;
+    if (B <= 0 || H <= 0 || W <= 0 || C_exp <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0 ||
+        N <= 0 || N > (int64_t)1 << 30)
+        return OCS_E_SHAPE;
+    if (H + 2 * pad < kh || W + 2 * pad < kw) return OCS_E_SHAPE;
+    const int64_t Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
+    const int64_t M = (int64_t)B * Ho * Wo;
+    if (M > (int64_t)1 << 30 || (int64_t)B * H * W > (int64_t)1 << 31) return OCS_E_SHAPE;
+    if (ldc < C_exp || (int64_t)kh * kw * ldc > (int64_t)1 << 30) return OCS_E_SHAPE;
+    if (ldy < N || (acc_out && ldacc < N)) return OCS_E_SHAPE;
+    if (ldc % OCS_KALIGN != 0 || !aligned(Aq, 16) || !aligned(Wt, 16)) return OCS_E_ALIGN;
+    if (!bits_ok(bits_x) || !bits_ok(bits_w)) return OCS_E_BITS;
+    const int64_t qx = (1 << (bits_x - 1)) - 1, qw = (1 << (bits_w - 1)) - 1;
+    if ((int64_t)kh * kw * C_exp * qx * qw >= (int64_t)1 << 31) return OCS_E_OVERFLOW;
+    hipError_t e = launch_qconv(Aq, ldc, B, H, W, kh, kw, stride, pad, Wt, (int64_t)kh * kw * ldc, N,
+                                scale_x, scale_w, acc_out, ldacc, Y, ldy,
+                                static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
 int ocs_time_next(int family, void* start_event, void* stop_event) {
     if (family != kTimeSplitQuantize && family != kTimeGemm && family != kTimeAbsmax) return OCS_E_MODE;
     if (!start_event || !stop_event) return OCS_E_NULL;

@@ -108,6 +108,16 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
                         int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy,
                         hipStream_t stream);
 
+// Convolution with the lowering folded into the GEMM's A-operand loader: Aq [B, H, W, ldc]
+// codes of the un-lowered activation, Wt [N + 1, kh*kw*ldc] tap-major weight codes whose last
+// row is zeros (launch_tap_major builds it from channel-major codes).
+hipError_t launch_qconv(const int8_t* Aq, int64_t ldc, int B, int H, int W, int kh, int kw, int stride,
+                        int pad, const int8_t* Wt, int64_t ldw, int64_t N, const float* scale_x,
+                        const float* scale_w, int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy,
+                        hipStream_t stream);
+hipError_t launch_tap_major(const int8_t* Wq, int64_t ldq, int64_t N, int E, int g, int64_t ldc,
+                            int8_t* Wt, hipStream_t stream);
+
 // 16-byte copy of `bytes` (multiple of 16) device bytes: counter calibration only.
 hipError_t launch_calib_copy(const void* src, void* dst, size_t bytes, hipStream_t stream);
 

@@ -224,12 +224,24 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N_ & 15) | (7 << 4) | (15 << 8) | ((N_ >> 4) << 14));
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF>
+// Geometry of a convolution whose lowering to the GEMM is done by the A-operand loader itself
+// (CONV variant below): the un-lowered activation codes Aq [B, H, W, ldc] (ldc bytes per pixel,
+// the expanded channels first, zero padding after), kernel kh x kw, output Ho x Wo.  K is walked
+// tap by tap: K-step kt covers bytes (kt % spt) * BK .. of tap kt / spt, spt = ldc / BK steps
+// per tap, so a lane's 16 bytes are 16 consecutive channels of one input pixel; taps that fall
+// outside the image read a row of zeros instead.
+struct ConvGeom {
+    const int8_t* zero;   // at least BK bytes of zeros
+    int H, W, kw, spt, stride, pad, Ho, Wo;
+    int64_t ldc;
+};
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF, bool CONV = false>
 __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
     const int8_t* __restrict__ Xq, int64_t ldx, const int8_t* __restrict__ Wq, int64_t ldw, int M,
     int N, int ksteps, const float* __restrict__ scale_x, const float* __restrict__ scale_w,
     int32_t* __restrict__ acc_out, int64_t ldacc, float* __restrict__ Y, int64_t ldy, int tiles_n,
-    unsigned total_tiles) {
+    unsigned total_tiles, ConvGeom cg) {
     constexpr int NW = WAVES_M * WAVES_N;  // waves per workgroup (4, 8 or 16)
     constexpr int NT = NW * 64;
     static_assert(NW == 4 || NW == 8 || NW == 16, "4, 8 or 16 waves");
@@ -262,13 +274,28 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
     // chunk slot p % CPR, which receives global chunk slot ^ f(row).
     const int8_t* a_src[A_LOADS];
     const int8_t* b_src[B_LOADS];
+    // CONV: output pixel of each row this lane loads (top-left input coordinate of its window,
+    // byte offset of that input pixel, which may lie outside the tensor and is then never used)
+    int a_iy0[CONV ? A_LOADS : 1], a_ix0[CONV ? A_LOADS : 1];
 #pragma unroll
     for (int u = 0; u < A_LOADS; ++u) {
         int pslot = (u * NW + wave) * 64 + lane, r = pslot / CPR, c = pslot % CPR;
         int gr = row0 + r;
         gr = gr < M ? gr : M - 1;  // rows past the edge re-read the last row; never stored
-        a_src[u] = Xq + (int64_t)gr * ldx + swz<BK>(r, c) * 16;
+        if (CONV) {
+            const int per_img = cg.Ho * cg.Wo;
+            const int b = gr / per_img, rem = gr - b * per_img;
+            const int yo = rem / cg.Wo, xo = rem - yo * cg.Wo;
+            a_iy0[u] = yo * cg.stride - cg.pad;
+            a_ix0[u] = xo * cg.stride - cg.pad;
+            a_src[u] = Xq + (((int64_t)b * cg.H + a_iy0[u]) * cg.W + a_ix0[u]) * cg.ldc +
+                       swz<BK>(r, c) * 16;
+        } else {
+            a_src[u] = Xq + (int64_t)gr * ldx + swz<BK>(r, c) * 16;
+        }
     }
+    // lane-invariant position of the next K-step to request (CONV): tap (ky, kx), step in tap
+    int c_kt = 0, c_cs = 0, c_kx = 0, c_ky = 0;
 #pragma unroll
     for (int u = 0; u < B_LOADS; ++u) {
         int pslot = (u * NW + wave) * 64 + lane, r = pslot / CPR, c = pslot % CPR;
@@ -305,9 +332,35 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
     auto fetch = [&](int kt, int buf) {   // K index clamped: surplus steps refetch the last one
         const int kl = kt < ksteps ? kt : ksteps - 1;
         const int64_t koff = (int64_t)kl * BK;
+        if (CONV) {
+            // requests arrive in K order, so the tap position is kept incrementally (it stops
+            // at the last step, which surplus requests repeat)
+            const int64_t tap_off = ((int64_t)c_ky * cg.W + c_kx) * cg.ldc + (int64_t)c_cs * BK;
 #pragma unroll
-        for (int u = 0; u < A_LOADS; ++u)
-            dma16(a_src[u] + koff, lds_a0 + buf * (BM * BK) + (u * NW + wave) * 1024);
+            for (int u = 0; u < A_LOADS; ++u) {
+                const int iy = a_iy0[u] + c_ky, ix = a_ix0[u] + c_kx;
+                const bool inside = (unsigned)iy < (unsigned)cg.H && (unsigned)ix < (unsigned)cg.W;
+                // a_src carries the swizzled chunk offset; recover it for the zero row
+                const int pslot = (u * NW + wave) * 64 + lane;
+                const int8_t* src = inside ? a_src[u] + tap_off
+                                           : cg.zero + swz<BK>(pslot / CPR, pslot % CPR) * 16;
+                dma16(src, lds_a0 + buf * (BM * BK) + (u * NW + wave) * 1024);
+            }
+            if (c_kt + 1 < ksteps) {
+                ++c_kt;
+                if (++c_cs == cg.spt) {
+                    c_cs = 0;
+                    if (++c_kx == cg.kw) {
+                        c_kx = 0;
+                        ++c_ky;
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < A_LOADS; ++u)
+                dma16(a_src[u] + koff, lds_a0 + buf * (BM * BK) + (u * NW + wave) * 1024);
+        }
 #pragma unroll
         for (int u = 0; u < B_LOADS; ++u)
             dma16(b_src[u] + koff, lds_b0 + buf * (BN * BK) + (u * NW + wave) * 1024);
@@ -654,7 +707,92 @@ static hipError_t run_dma(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64
     return launch_kernel(kTimeGemm, qgemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, BK, NBUF>,
                          dim3((unsigned)total), dim3(WAVES_M * WAVES_N * 64), 0, stream, Xq, ldx, Wq, ldw, (int)M,
                          (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y, ldy,
-                         (int)tiles_n, (unsigned)total);
+                         (int)tiles_n, (unsigned)total, ConvGeom{});
+}
+
+// The same kernel with the lowering of a convolution done by its A-operand loader.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NBUF>
+static hipError_t run_dma_conv(const int8_t* Aq, const int8_t* Wt, int64_t ldw, int64_t M, int64_t N,
+                               int64_t Kpad, const ConvGeom& cg, const float* scale_x,
+                               const float* scale_w, int32_t* acc_out, int64_t ldacc, float* Y,
+                               int64_t ldy, hipStream_t stream) {
+    constexpr int BK = 64;
+    if (Kpad < BK || Kpad % BK != 0 || cg.ldc % BK != 0 || cg.spt < 1) return hipErrorInvalidValue;
+    const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
+    const int64_t total = tiles_m * tiles_n;
+    return launch_kernel(kTimeGemm, qgemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, BK, NBUF, true>,
+                         dim3((unsigned)total), dim3(WAVES_M * WAVES_N * 64), 0, stream, Aq, cg.ldc, Wt,
+                         ldw, (int)M, (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y,
+                         ldy, (int)tiles_n, (unsigned)total, cg);
+}
+
+hipError_t launch_qconv(const int8_t* Aq, int64_t ldc, int B, int H, int W, int kh, int kw, int stride,
+                        int pad, const int8_t* Wt, int64_t ldw, int64_t N, const float* scale_x,
+                        const float* scale_w, int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy,
+                        hipStream_t stream) {
+    ConvGeom cg;
+    cg.Ho = (H + 2 * pad - kh) / stride + 1;
+    cg.Wo = (W + 2 * pad - kw) / stride + 1;
+    cg.H = H;
+    cg.W = W;
+    cg.kw = kw;
+    cg.spt = (int)(ldc / 64);
+    cg.stride = stride;
+    cg.pad = pad;
+    cg.ldc = ldc;
+    cg.zero = Wt + N * ldw;            // the row of zeros that follows the N weight rows
+    const int64_t M = (int64_t)B * cg.Ho * cg.Wo;
+    const int64_t Kpad = (int64_t)kh * kw * ldc;
+    int tile = tuning().gemm_tile;
+    if (tile < 0) {
+        const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 128);
+        const int64_t t128 = ceil_div(M, 128) * ceil_div(N, 128);
+        if (N <= 64) tile = 6;
+        else if (t256 >= 128) tile = 10;
+        else if (t128 >= 48) tile = 9;
+        else tile = 6;
+    }
+#define OCS_CONV_ARGS Aq, Wt, ldw, M, N, Kpad, cg, scale_x, scale_w, acc_out, ldacc, Y, ldy, stream
+    switch (tile) {
+        case 6: return run_dma_conv<128, 64, 2, 2, 6>(OCS_CONV_ARGS);
+        case 7: return run_dma_conv<64, 64, 2, 2, 6>(OCS_CONV_ARGS);
+        case 10: return run_dma_conv<256, 128, 4, 2, 4>(OCS_CONV_ARGS);
+        case 12: return run_dma_conv<256, 256, 2, 4, 4>(OCS_CONV_ARGS);
+        default: return run_dma_conv<128, 128, 4, 2, 4>(OCS_CONV_ARGS);
+    }
+#undef OCS_CONV_ARGS
+}
+
+// Channel-major codes [N, ldq] (column j*g + t) -> tap-major [N + 1, g*ldc] (column t*ldc + j,
+// zero for j >= E), the extra row all zeros.  One lane per output byte quad.
+__global__ __launch_bounds__(kThreads) void tap_major_kernel(const int8_t* __restrict__ Wq, int64_t ldq,
+                                                             int64_t N, int E, int g, int64_t ldc,
+                                                             int8_t* __restrict__ Wt) {
+    const int64_t quads_per_row = (int64_t)g * ldc / 4;
+    const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (o >= (N + 1) * quads_per_row) return;
+    const int64_t n = o / quads_per_row;
+    const int64_t k = (o - n * quads_per_row) * 4;
+    const int t = (int)(k / ldc);
+    const int j0 = (int)(k - (int64_t)t * ldc);
+    unsigned packed = 0;
+    if (n < N) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int j = j0 + e;
+            const int code = j < E ? Wq[n * ldq + (int64_t)j * g + t] : 0;
+            packed |= ((unsigned)code & 0xFFu) << (8 * e);
+        }
+    }
+    reinterpret_cast<unsigned*>(Wt)[o] = packed;
+}
+
+hipError_t launch_tap_major(const int8_t* Wq, int64_t ldq, int64_t N, int E, int g, int64_t ldc,
+                            int8_t* Wt, hipStream_t stream) {
+    const int64_t total = (N + 1) * ((int64_t)g * ldc / 4);
+    tap_major_kernel<<<dim3((unsigned)ceil_div(total, kThreads)), kThreads, 0, stream>>>(Wq, ldq, N, E, g,
+                                                                                       ldc, Wt);
+    return hipGetLastError();
 }
 
 // Kpad is a multiple of 64.  With a 128-byte K-step and Kpad % 128 == 64 the last step would

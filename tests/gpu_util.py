@@ -125,6 +125,30 @@ def gpu_split_act(X, Cn, g, chan_src, chan_depth, s, bits, threshold=None, clip_
     return host(q), host(sc)
 
 
+def gpu_conv_layer(A, Wm, Cn, kh, kw, stride, pad, s, bits_x=8, bits_w=8, threshold=None):
+    """A [B, H, W, C] fp32, Wm [N, C*kh*kw] fp32 -> weight OCS, activation split+quantize on the
+    un-lowered tensor, convolution with the lowering inside the kernel.  Returns dict."""
+    Bn, H, W, _ = A.shape
+    N, g, E = Wm.shape[0], kh * kw, Cn + s
+    wts = gpu_split_weights(Wm, Cn, g, s, bits=bits_w, want_f32=False)
+    ldc = B.ocs_padded_cols(E)
+    Wq = dev(wts["Wq"])
+    Wt = torch.full(((N + 1), g * ldc), 77, dtype=torch.int8, device="cuda")
+    B.ocs_conv_weights_tap_major(Wq, N, E, g, Wq.stride(0), Wt, ldc)
+    Aq, sx = gpu_split_act(A.reshape(-1, Cn), Cn, 1, wts["chan_src"], None, s, bits_x, threshold=threshold)
+    Aqd, sxd, swd = dev(Aq), dev(sx), dev(wts["scale"])
+    Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+    M = Bn * Ho * Wo
+    acc = torch.full((M, N), -9, dtype=torch.int32, device="cuda")
+    Y = torch.full((M, N), 7.0, dtype=torch.float32, device="cuda")
+    B.ocs_qconv(Aqd, ldc, Bn, H, W, E, kh, kw, stride, pad, Wt, N, bits_x, bits_w, sxd, swd, acc, N, Y, N)
+    Y2 = torch.full((M, N), 7.0, dtype=torch.float32, device="cuda")
+    B.ocs_qconv(Aqd, ldc, Bn, H, W, E, kh, kw, stride, pad, Wt, N, bits_x, bits_w, sxd, swd, None, 0, Y2, N)
+    assert torch.equal(Y, Y2)
+    return dict(acc=host(acc), Y=host(Y), Aq=Aq, sx=sx, Wq=wts["Wq"], sw=wts["scale"], Wt=host(Wt),
+                chan_src=wts["chan_src"], ldc=ldc)
+
+
 def gpu_qgemm(Xq, Wq, Kexp, scale_x, scale_w, bits_x=8, bits_w=8, want_acc=True):
     M, N = Xq.shape[0], Wq.shape[0]
     Xd, Wd = dev(Xq), dev(Wq)

@@ -71,6 +71,11 @@ def test_argument_errors_are_reported_without_a_device():
     assert L.ocs_mse_clip_threshold(A, 4, 4, 4, 8, 0, 4, A, A, A, A, ws, None) == -2       # no bins
     assert L.ocs_mse_clip_threshold(A, 4, 4, 4, 8, 9000, 4, A, A, A, A, ws, None) == -2
     assert L.ocs_mse_clip_threshold(A, 4, 4, 4, 1, 16, 4, A, A, A, A, ws, None) == -4
+    assert L.ocs_qconv(A, 64, 1, 4, 4, 8, 3, 3, 1, 1, None, 4, 8, 8, A, A, None, 0, A, 4, None) == -1      # no weights
+    assert L.ocs_qconv(A, 64, 1, 2, 2, 8, 3, 3, 1, 0, A, 4, 8, 8, A, A, None, 0, A, 4, None) == -2         # kernel larger than image
+    assert L.ocs_qconv(A, 96, 1, 4, 4, 8, 3, 3, 1, 1, A, 4, 8, 8, A, A, None, 0, A, 4, None) == -3         # ldc % 64
+    assert L.ocs_qconv(A, 64, 1, 4, 4, 80, 3, 3, 1, 1, A, 4, 8, 8, A, A, None, 0, A, 4, None) == -2        # ldc < C_exp
+    assert L.ocs_conv_weights_tap_major(A, 4, 8, 9, 64, A, 64, None) == -2                                  # ldq < C_exp*g
     # shapes
     assert L.ocs_quantize(A, 0, 4, 4, 8, A, 1.0, A, 64, A, A, ws, None) == -2
     assert L.ocs_quantize(A, 4, 8, 4, 8, A, 1.0, A, 64, A, A, ws, None) == -2      # ldx < cols

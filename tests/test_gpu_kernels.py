@@ -7,7 +7,7 @@ import pytest
 from oracle import ref
 from paper_1901_09504_amd import binding as B
 
-from gpu_util import (assert_y_close, gpu_mse_clip, gpu_qgemm, gpu_quantize, gpu_select, gpu_split_act,
+from gpu_util import (assert_y_close, gpu_conv_layer, gpu_mse_clip, gpu_qgemm, gpu_quantize, gpu_select, gpu_split_act,
                       gpu_split_weights, gpu_split_weights_qa, require_gpu)
 
 pytestmark = pytest.mark.gpu
@@ -306,3 +306,64 @@ def test_qgemm_extreme_codes_do_not_overflow():
     acc, Y = gpu_qgemm(Xq, Wq, K, sx, sx)
     assert np.array_equal(acc, acc_ref)
     assert_y_close(Y, y_ref)
+
+
+# ---- ocs_qconv: the lowering of a convolution inside the GEMM's operand loader ---------------------
+
+def _conv_reference(A, Wm, Cn, kh, kw, stride, pad, s, bits_x, bits_w, threshold):
+    Bn, H, W, _ = A.shape
+    g, E = kh * kw, Cn + s
+    sp = ref.split_weights(Wm, Cn, g, s)
+    ldq = B.ocs_padded_cols(E * g)
+    Wq, sw = ref.quantize(sp["T_out"], bits_w, ldq=ldq)
+    Aq, sx, _ = ref.split_act(A.reshape(-1, Cn), Cn, 1, sp["chan_src"], None, s, bits_x, threshold=threshold)
+    Xq = np.zeros((ref.conv_out_size(H, kh, stride, pad) * ref.conv_out_size(W, kw, stride, pad) * Bn, ldq),
+                  dtype=np.int8)
+    Xq[:, :E * g] = ref.im2col(Aq.reshape(Bn, H, W, E), kh, kw, stride, pad)
+    acc, Y = ref.qgemm(Xq, Wq, E * g, sx[1], sw[1])
+    return dict(acc=acc, Y=Y, Aq=Aq, sx=sx, Wq=Wq, sw=sw)
+
+
+@pytest.mark.parametrize("tile", [-1, 6, 7, 9, 10, 12])
+@pytest.mark.parametrize("Bn,H,W,Cn,N,kh,kw,stride,pad,s", [
+    (2, 14, 14, 64, 96, 3, 3, 1, 1, 4),        # the common 3x3
+    (3, 9, 7, 20, 33, 3, 3, 2, 1, 2),          # stride 2, ragged everything
+    (2, 8, 8, 128, 70, 1, 1, 1, 0, 7),         # 1x1
+    (2, 9, 9, 64, 64, 1, 1, 2, 0, 4),          # 1x1 stride 2: skips pixels
+    (1, 23, 17, 3, 64, 7, 7, 2, 3, 1),         # stem-like: 3 channels, 7x7
+    (1, 5, 6, 130, 40, 2, 3, 1, 0, 0),         # no split, no padding, two K-steps per tap... (ldc 192)
+    (4, 14, 14, 256, 256, 3, 3, 1, 1, 6),      # config 2's layer at batch 4
+])
+def test_qconv(tile, Bn, H, W, Cn, N, kh, kw, stride, pad, s):
+    rng = np.random.default_rng(Bn + H + W + Cn + N + kh + stride + s)
+    A = _tensor(rng, Bn * H * W, Cn, "heavy").reshape(Bn, H, W, Cn)
+    Wm = _tensor(rng, N, Cn * kh * kw, "heavy")
+    exp = _conv_reference(A, Wm, Cn, kh, kw, stride, pad, s, 8, 6, None)
+    B.ocs_tune("gemm_tile", tile)
+    try:
+        got = gpu_conv_layer(A, Wm, Cn, kh, kw, stride, pad, s, bits_x=8, bits_w=6)
+    finally:
+        B.ocs_tune("gemm_tile", -1)
+    E, ldc = Cn + s, got["ldc"]
+    assert np.array_equal(got["sx"], exp["sx"]) and np.array_equal(got["sw"], exp["sw"])
+    assert np.array_equal(got["Aq"][:, :E], exp["Aq"][:, :E]) and not got["Aq"][:, E:].any()
+    # tap-major weights: Wt[n, t*ldc + j] = Wq[n, j*g + t], zero padding, zero last row
+    g = kh * kw
+    Wt = got["Wt"].reshape(N + 1, g, ldc)
+    assert np.array_equal(Wt[:N, :, :E], exp["Wq"][:, :E * g].reshape(N, E, g).transpose(0, 2, 1))
+    assert not Wt[:N, :, E:].any() and not Wt[N].any()
+    assert np.array_equal(got["acc"], exp["acc"])
+    assert_y_close(got["Y"], exp["Y"])
+
+
+def test_qconv_equals_the_lowered_gemm_path():
+    # same layer through ocs_split_act on the im2col matrix + ocs_qgemm, with a static grid
+    rng = np.random.default_rng(99)
+    Bn, H, W, Cn, N, s = 2, 10, 10, 48, 80, 3
+    A = np.abs(_tensor(rng, Bn * H * W, Cn, "normal")).reshape(Bn, H, W, Cn)
+    Wm = _tensor(rng, N, Cn * 9, "heavy")
+    got = gpu_conv_layer(A, Wm, Cn, 3, 3, 1, 1, s, threshold=4.0)
+    X = ref.im2col(A, 3, 3, 1, 1)
+    xq, sx = gpu_split_act(X, Cn, 9, got["chan_src"], None, s, 8, threshold=4.0)
+    acc, Y = gpu_qgemm(xq, got["Wq"], (Cn + s) * 9, sx, got["sw"])
+    assert np.array_equal(got["acc"], acc) and np.array_equal(got["Y"], Y)
