@@ -103,6 +103,37 @@ def mfma_bound_gemm(torch, B, wl, ExpandedLayer, launches, copies=5):
             "arithmetic_intensity_op_per_byte": ops / (M * L.Ke + N * L.Ke + 4.0 * M * N)}
 
 
+def conv_unlowered(torch, B, wl, layer, steps, copies=24):
+    """The workload's convolution given un-lowered (activation [64, 14, 14, 256] fp32, 12.8 MB,
+    instead of its 115.6 MB im2col image): weight path + tap-major weights, split+quantize of the
+    activation with a per-batch grid, convolution with the lowering inside the GEMM kernel's
+    loader.  Reported beside the headline, which is defined on the lowered GEMM."""
+    from paper_1901_09504_amd.layer import ExpandedConv
+
+    Bn, H, W = 64, 14, 14
+    Wd = torch.from_numpy(wl.weights(layer)).cuda()
+    gen = torch.Generator(device="cuda").manual_seed(layer.seed)
+    As = [torch.randn(Bn, H, W, layer.C, device="cuda", generator=gen).abs_() for _ in range(copies)]
+    L = ExpandedConv(layer.N, layer.C, 3, 3, 1, 1, layer.r, layer.bits_w, layer.bits_x)
+
+    def step(i):
+        L.prepare_weights(Wd)
+        L.forward(As[i % copies])
+
+    for i in range(10):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) / steps * 1e6
+    ops = 2.0 * Bn * H * W * layer.N * L.E * 9
+    return {"workload": f"the same layer un-lowered: A [{Bn},{H},{W},{layer.C}] fp32 x {copies} rotating copies, "
+                        f"3x3 stride 1 pad 1, K walked as 9 taps x {L.ldc} bytes",
+            "us_per_step": us, "tops_whole_step": ops / us / 1e6, "steps": steps}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -114,6 +145,8 @@ def main():
                     help="every n-th timed step carries the per-phase and per-kernel events")
     ap.add_argument("--mfma-gemm-launches", type=int, default=24,
                     help="launches of the GEMM on the MFMA-bound layer shape after the timed region (0: skip)")
+    ap.add_argument("--conv-steps", type=int, default=100,
+                    help="steps of the same layer given un-lowered, after the timed region (0: skip)")
     ap.add_argument("--calib-copies", type=int, default=6,
                     help="plain copies of X launched after the timed region (counter calibration)")
     args = ap.parse_args()
@@ -272,6 +305,8 @@ def main():
         "roof_tops_min_mfma_hbm": gemm_roof_tops, "frac_of_that_roof": gemm_tops / gemm_roof_tops})
     if args.mfma_gemm_launches > 0:
         out["gemm_mfma_bound"] = mfma_bound_gemm(torch, B, wl, ExpandedLayer, args.mfma_gemm_launches)
+    if args.conv_steps > 0:
+        out["conv_unlowered"] = conv_unlowered(torch, B, wl, layer, args.conv_steps)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layer, W, X)
     print(json.dumps(out))

@@ -110,3 +110,53 @@ class ExpandedLayer:
                         self.ws_x, stream)
         self.qgemm(M, acc_out, stream)
         return self.Y[:M]
+
+
+class ExpandedConv:
+    """The same layer for a convolution given un-lowered: activations A [B, H, W, C] fp32 (NHWC),
+    weights [N, C*kh*kw] (channel c owns kh*kw columns).  The activation is split and quantized
+    once on its [B*H*W, C] view and the lowering happens inside the GEMM kernel's loader
+    (ocs_qconv), so the kh*kw-times larger lowered matrix never exists.  Weight OCS only."""
+
+    def __init__(self, N, C, kh, kw, stride, pad, r, bits_w=8, bits_x=8, clip_ratio_w=1.0,
+                 device="cuda"):
+        self.kh, self.kw, self.stride, self.pad = int(kh), int(kw), int(stride), int(pad)
+        self.g = self.kh * self.kw
+        self.w = ExpandedLayer(N, C, self.g, r, bits_w, bits_x, clip_ratio_w=clip_ratio_w, device=device)
+        self.N, self.C, self.s = self.w.N, self.w.C, self.w.s
+        self.E = self.C + self.s
+        self.ldc = B.ocs_padded_cols(self.E)
+        self.Wt = torch.empty((self.N + 1, self.g * self.ldc), dtype=torch.int8, device=device)
+        self.scale_x = torch.empty(2, dtype=torch.float32, device=device)
+        self.device = device
+        self._pixels = 0
+        self.Aq = self.Y = self.ws_a = None
+
+    def prepare_weights(self, W, stream=None):
+        self.w.prepare_weights(W, stream=stream)
+        B.ocs_conv_weights_tap_major(self.w.Wq, self.N, self.E, self.g, self.w.ldq, self.Wt, self.ldc,
+                                     stream)
+
+    def out_size(self, H, W):
+        return ((H + 2 * self.pad - self.kh) // self.stride + 1,
+                (W + 2 * self.pad - self.kw) // self.stride + 1)
+
+    def forward(self, A, threshold=None, acc_out=None, stream=None):
+        """A fp32 [B, H, W, C] contiguous -> Y fp32 [B*Ho*Wo, N]."""
+        Bn, H, W, C = A.shape
+        assert C == self.C and A.is_contiguous()
+        P = Bn * H * W
+        Ho, Wo = self.out_size(H, W)
+        M = Bn * Ho * Wo
+        if P > self._pixels:
+            self.Aq = torch.empty((P, self.ldc), dtype=torch.int8, device=self.device)
+            self.ws_a = B.alloc_workspace(P, self.C, self.device)
+            self._pixels = P
+        if self.Y is None or self.Y.shape[0] < M:
+            self.Y = torch.empty((M, self.N), dtype=torch.float32, device=self.device)
+        B.ocs_split_act(A, P, self.C, 1, self.C, self.w.chan_src, None, self.s, self.w.bits_x, threshold,
+                        1.0, self.Aq, self.ldc, self.scale_x, self.ws_a, stream)
+        B.ocs_qconv(self.Aq, self.ldc, Bn, H, W, self.E, self.kh, self.kw, self.stride, self.pad, self.Wt,
+                    self.N, self.w.bits_x, self.w.bits_w, self.scale_x, self.w.scale_w, acc_out,
+                    0 if acc_out is None else acc_out.stride(0), self.Y, self.N, stream)
+        return self.Y[:M]

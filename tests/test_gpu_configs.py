@@ -228,3 +228,31 @@ def test_qa_forward_config1_and_lstm_gate():
         assert np.array_equal(host(L.Xq[:layer.M]), Xq_ref)
         assert np.array_equal(host(acc), acc_ref)
         assert_y_close(host(Y), y_ref)
+
+
+# ---- config 2's convolution given un-lowered: lowering inside the kernel, full size ---------------
+
+def test_config2_as_convolution_full_size():
+    from paper_1901_09504_amd.layer import ExpandedConv
+    (layer,) = wl.config(2)
+    Bn, H, Wd_, Cn, N = 64, 14, 14, layer.C, layer.N
+    W = wl.weights(layer)
+    rng = np.random.default_rng(layer.seed + 7)
+    A = np.abs(rng.standard_normal((Bn, H, Wd_, Cn))).astype(np.float32)      # post-ReLU half-normal
+    L = ExpandedConv(N, Cn, 3, 3, 1, 1, layer.r, layer.bits_w, layer.bits_x)
+    L.prepare_weights(dev(W))
+    M = Bn * H * Wd_
+    acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    Y = L.forward(dev(A), acc_out=acc)
+    sp = ref.split_weights(W, Cn, 9, L.s)
+    Wq_ref, sw_ref = ref.quantize(sp["T_out"], layer.bits_w, ldq=L.w.ldq)
+    Aq_ref, sx_ref, _ = ref.split_act(A.reshape(-1, Cn), Cn, 1, sp["chan_src"], None, L.s, layer.bits_x)
+    assert np.array_equal(host(L.scale_x), sx_ref) and np.array_equal(host(L.w.scale_w), sw_ref)
+    assert np.array_equal(host(L.Aq)[:, :L.E], Aq_ref)
+    Xq = np.zeros((M, L.w.ldq), dtype=np.int8)
+    Xq[:, :L.E * 9] = ref.im2col(Aq_ref.reshape(Bn, H, Wd_, L.E), 3, 3, 1, 1)
+    acc_ref, y_ref = ref.qgemm(Xq, Wq_ref, L.E * 9, sx_ref[1], sw_ref[1])
+    assert np.array_equal(host(acc), acc_ref)
+    assert_y_close(host(Y), y_ref)
+    Y1 = Y.clone()
+    assert torch.equal(Y1, L.forward(dev(A)))           # the timed configuration stores no accumulators
