@@ -26,9 +26,10 @@
  *    lowered by im2col; Sec. 3.2: a split duplicates a whole 2-D activation channel and
  *    every 2-D filter attached to it).  Activations X are [M, C*g], weights W are [N, C*g]
  *    (both operands K-contiguous), outputs Y are [M, N].
- *  - Code tensors (int8) have a leading dimension that is a multiple of OCS_KALIGN and a
- *    16-byte aligned base; the producer writes zeros into every pad column
- *    (columns (C+s)*g .. ld-1) and ocs_qgemm relies on those zeros.
+ *  - Code tensors (int8) have a 16-byte aligned base and a leading dimension that is a
+ *    multiple of OCS_CALIGN; ocs_qgemm additionally needs a multiple of OCS_KALIGN (its
+ *    K-step).  The producer writes zeros into every pad column (columns (C+s)*g .. ld-1)
+ *    and the consumers rely on those zeros.
  *  - fp32 inputs may have any leading dimension >= the row length; 16-byte aligned bases
  *    with a leading dimension that is a multiple of 4 take the vectorised path.
  *  - NaN / Inf inputs give unspecified codes (no fault).  Index arrays read from device
@@ -45,7 +46,8 @@
 extern "C" {
 #endif
 
-#define OCS_KALIGN 64 /* leading dimension of int8 code tensors is a multiple of this */
+#define OCS_KALIGN 64 /* leading dimension of the code tensors ocs_qgemm reads is a multiple of this */
+#define OCS_CALIGN 16 /* leading dimension of any int8 code tensor is a multiple of this */
 
 #define OCS_OK 0
 #define OCS_E_NULL (-1)      /* a required pointer is NULL                                  */
@@ -74,6 +76,9 @@ const char *ocs_last_hip_error(void);
  * r <= 0 or C <= 0 gives 0.  Host-only, no device work.
  */
 int ocs_num_splits(int C, double r);
+
+/* Bytes per pixel of un-lowered activation codes for ocs_qconv: channels rounded up to OCS_CALIGN. */
+int64_t ocs_padded_channels(int64_t channels);
 
 /* Leading dimension of the code tensor of an expanded layer: (C+s)*g rounded up to OCS_KALIGN. */
 int64_t ocs_padded_cols(int64_t cols);
@@ -235,16 +240,18 @@ int ocs_qgemm(const int8_t *Xq, int64_t ldx, const int8_t *Wq, int64_t ldw, int6
  * matrix); every code of the lowered matrix is a code of that tensor, or zero outside the image.
  *
  * ocs_conv_weights_tap_major: weight codes Wq [N, ldq] as ocs_split_weights writes them for
- *   g = kh*kw (expanded channel j owns columns j*g .. j*g+g-1) -> Wt [N + 1, g*ldc] with
- *   Wt[n, t*ldc + j] = Wq[n, j*g + t] for j < C_exp = C + num_splits, zero for j >= C_exp, and
- *   row N all zeros (the kernel reads it for taps outside the image).  ldc: bytes per pixel of
- *   the activation codes, a multiple of OCS_KALIGN, >= C_exp.
+ *   g = kh*kw (expanded channel j owns columns j*g .. j*g+g-1) -> Wt [N + 1, ldt],
+ *   ldt = g*ldc rounded up to OCS_KALIGN, with Wt[n, t*ldc + j] = Wq[n, j*g + t] for
+ *   j < C_exp = C + num_splits, zero everywhere else, and row N all zeros (the kernel reads it
+ *   for taps outside the image).  ldc: bytes per pixel of the activation codes, a multiple of
+ *   OCS_CALIGN, >= C_exp (ocs_padded_channels(C_exp) is the tightest).
  *
  * ocs_qconv: Aq [B, H, W, ldc] int8 (channels C_exp .. ldc-1 zero, as ocs_split_act pads),
  *   kernel kh x kw, stride, zero padding pad on every side; output pixel (b, yo, xo) is row
  *   (b*Ho + yo)*Wo + xo of Y [B*Ho*Wo, N] fp32 (and of acc_out, optional int32), Ho = (H + 2*pad
  *   - kh)/stride + 1.  acc = sum over taps and expanded channels of code products, exactly the
  *   accumulator ocs_qgemm gives on the lowered codes; Y = float(acc) * (scale_x[1]*scale_w[1]).
+ *   Wt as written by ocs_conv_weights_tap_major for the same ldc.
  * Both calls: device pointers, asynchronous on `stream`, 16-byte aligned code tensors.
  */
 int ocs_conv_weights_tap_major(const int8_t *Wq, int64_t N, int C_exp, int g, int64_t ldq,

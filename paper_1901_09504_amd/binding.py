@@ -48,6 +48,8 @@ def lib():
     L.ocs_num_splits.argtypes = [_i32, C.c_double]
     L.ocs_padded_cols.restype = _i64
     L.ocs_padded_cols.argtypes = [_i64]
+    L.ocs_padded_channels.restype = _i64
+    L.ocs_padded_channels.argtypes = [_i64]
     L.ocs_workspace_bytes.restype = _sz
     L.ocs_workspace_bytes.argtypes = [_i64, _i64]
     L.ocs_select_channels.restype = _i32
@@ -114,6 +116,10 @@ def ocs_num_splits(Cn, r):
 
 def ocs_padded_cols(cols):
     return int(lib().ocs_padded_cols(int(cols)))
+
+
+def ocs_padded_channels(channels):
+    return int(lib().ocs_padded_channels(int(channels)))
 
 
 def ocs_workspace_bytes(rows, cols):

@@ -32,7 +32,7 @@ static bool aligned(const void* p, size_t a) { return reinterpret_cast<uintptr_t
 
 static int check_codes(const void* q, int64_t ldq, int64_t cols) {
     if (ldq < cols) return OCS_E_SHAPE;
-    if (ldq % OCS_KALIGN != 0 || !aligned(q, 16)) return OCS_E_ALIGN;
+    if (ldq % OCS_CALIGN != 0 || !aligned(q, 16)) return OCS_E_ALIGN;
     return OCS_OK;
 }
 
@@ -84,6 +84,10 @@ int ocs_num_splits(int C, double r) {
 }
 
 int64_t ocs_padded_cols(int64_t cols) { return cols <= 0 ? 0 : round_up(cols, OCS_KALIGN); }
+
+int64_t ocs_padded_channels(int64_t channels) {
+    return channels <= 0 ? 0 : round_up(channels, OCS_CALIGN);
+}
 
 size_t ocs_workspace_bytes(int64_t rows, int64_t cols) {
     if (rows <= 0 || cols <= 0) return 0;
@@ -366,7 +370,7 @@ int ocs_conv_weights_tap_major(const int8_t* Wq, int64_t N, int C_exp, int g, in
     if (!Wq || !Wt) return OCS_E_NULL;
     if (N <= 0 || C_exp <= 0 || g <= 0 || N > (int64_t)1 << 30) return OCS_E_SHAPE;
     if (ldq < (int64_t)C_exp * g || ldc < C_exp || (int64_t)g * ldc > (int64_t)1 << 30) return OCS_E_SHAPE;
-    if (ldc % OCS_KALIGN != 0 || !aligned(Wt, 16)) return OCS_E_ALIGN;
+    if (ldc % OCS_CALIGN != 0 || !aligned(Wt, 16)) return OCS_E_ALIGN;
     hipError_t e = launch_tap_major(Wq, ldq, N, C_exp, g, ldc, Wt, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e);
     return OCS_OK;
@@ -386,11 +390,12 @@ int ocs_qconv(const int8_t* Aq, int64_t ldc, int B, int H, int W, int C_exp, int
     if (M > (int64_t)1 << 30 || (int64_t)B * H * W > (int64_t)1 << 31) return OCS_E_SHAPE;
     if (ldc < C_exp || (int64_t)kh * kw * ldc > (int64_t)1 << 30) return OCS_E_SHAPE;
     if (ldy < N || (acc_out && ldacc < N)) return OCS_E_SHAPE;
-    if (ldc % OCS_KALIGN != 0 || !aligned(Aq, 16) || !aligned(Wt, 16)) return OCS_E_ALIGN;
+    if (ldc % OCS_CALIGN != 0 || !aligned(Aq, 16) || !aligned(Wt, 16)) return OCS_E_ALIGN;
     if (!bits_ok(bits_x) || !bits_ok(bits_w)) return OCS_E_BITS;
     const int64_t qx = (1 << (bits_x - 1)) - 1, qw = (1 << (bits_w - 1)) - 1;
     if ((int64_t)kh * kw * C_exp * qx * qw >= (int64_t)1 << 31) return OCS_E_OVERFLOW;
-    hipError_t e = launch_qconv(Aq, ldc, B, H, W, kh, kw, stride, pad, Wt, (int64_t)kh * kw * ldc, N,
+    hipError_t e = launch_qconv(Aq, ldc, B, H, W, kh, kw, stride, pad, Wt,
+                                round_up((int64_t)kh * kw * ldc, OCS_KALIGN), N,
                                 scale_x, scale_w, acc_out, ldacc, Y, ldy,
                                 static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e);

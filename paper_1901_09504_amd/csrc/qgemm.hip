@@ -226,13 +226,14 @@ __device__ __forceinline__ void wait_vmcnt() {
 
 // Geometry of a convolution whose lowering to the GEMM is done by the A-operand loader itself
 // (CONV variant below): the un-lowered activation codes Aq [B, H, W, ldc] (ldc bytes per pixel,
-// the expanded channels first, zero padding after), kernel kh x kw, output Ho x Wo.  K is walked
-// tap by tap: K-step kt covers bytes (kt % spt) * BK .. of tap kt / spt, spt = ldc / BK steps
-// per tap, so a lane's 16 bytes are 16 consecutive channels of one input pixel; taps that fall
-// outside the image read a row of zeros instead.
+// a multiple of 16: the expanded channels first, zero padding after), kernel kh x kw, output
+// Ho x Wo.  K is walked tap by tap in 16-byte chunks: chunk G of a row is chunk G % cpp of tap
+// G / cpp, cpp = ldc / 16 chunks per pixel, so a lane's 16 bytes are 16 consecutive channels of
+// one input pixel.  Taps that fall outside the image, and the chunks that pad K up to a whole
+// K-step after the last tap, read a row of zeros instead.
 struct ConvGeom {
     const int8_t* zero;   // at least BK bytes of zeros
-    int H, W, kw, spt, stride, pad, Ho, Wo;
+    int H, W, kh, kw, cpp, stride, pad, Ho, Wo;
     int64_t ldc;
 };
 
@@ -275,8 +276,12 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
     const int8_t* a_src[A_LOADS];
     const int8_t* b_src[B_LOADS];
     // CONV: output pixel of each row this lane loads (top-left input coordinate of its window,
-    // byte offset of that input pixel, which may lie outside the tensor and is then never used)
+    // byte offset of that input pixel, which may lie outside the tensor and is then never used),
+    // and the tap position (ky, kx, chunk in pixel) of the chunk this lane will request next for
+    // that row: chunk kt*CPR + (its swizzled chunk slot) of the row's K extent.
     int a_iy0[CONV ? A_LOADS : 1], a_ix0[CONV ? A_LOADS : 1];
+    int a_ky[CONV ? A_LOADS : 1], a_kx[CONV ? A_LOADS : 1], a_cin[CONV ? A_LOADS : 1];
+    int a_zoff[CONV ? A_LOADS : 1];
 #pragma unroll
     for (int u = 0; u < A_LOADS; ++u) {
         int pslot = (u * NW + wave) * 64 + lane, r = pslot / CPR, c = pslot % CPR;
@@ -288,14 +293,21 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
             const int yo = rem / cg.Wo, xo = rem - yo * cg.Wo;
             a_iy0[u] = yo * cg.stride - cg.pad;
             a_ix0[u] = xo * cg.stride - cg.pad;
-            a_src[u] = Xq + (((int64_t)b * cg.H + a_iy0[u]) * cg.W + a_ix0[u]) * cg.ldc +
-                       swz<BK>(r, c) * 16;
+            a_src[u] = Xq + (((int64_t)b * cg.H + a_iy0[u]) * cg.W + a_ix0[u]) * cg.ldc;
+            a_zoff[u] = swz<BK>(r, c) * 16;
+            int cin = swz<BK>(r, c), kx = 0, ky = 0;
+            while (cin >= cg.cpp) {
+                cin -= cg.cpp;
+                if (++kx == cg.kw) { kx = 0; ++ky; }
+            }
+            a_cin[u] = cin;
+            a_kx[u] = kx;
+            a_ky[u] = ky;
         } else {
             a_src[u] = Xq + (int64_t)gr * ldx + swz<BK>(r, c) * 16;
         }
     }
-    // lane-invariant position of the next K-step to request (CONV): tap (ky, kx), step in tap
-    int c_kt = 0, c_cs = 0, c_kx = 0, c_ky = 0;
+    int c_kt = 0;   // CONV: K-step the next request is for (stops at the last one)
 #pragma unroll
     for (int u = 0; u < B_LOADS; ++u) {
         int pslot = (u * NW + wave) * 64 + lane, r = pslot / CPR, c = pslot % CPR;
@@ -333,29 +345,30 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
         const int kl = kt < ksteps ? kt : ksteps - 1;
         const int64_t koff = (int64_t)kl * BK;
         if (CONV) {
-            // requests arrive in K order, so the tap position is kept incrementally (it stops
-            // at the last step, which surplus requests repeat)
-            const int64_t tap_off = ((int64_t)c_ky * cg.W + c_kx) * cg.ldc + (int64_t)c_cs * BK;
+            // requests arrive in K order, so each lane keeps the tap position of its chunk
+            // incrementally; it stops at the last step, which surplus requests repeat
+            const bool advance = c_kt + 1 < ksteps;
 #pragma unroll
             for (int u = 0; u < A_LOADS; ++u) {
-                const int iy = a_iy0[u] + c_ky, ix = a_ix0[u] + c_kx;
-                const bool inside = (unsigned)iy < (unsigned)cg.H && (unsigned)ix < (unsigned)cg.W;
-                // a_src carries the swizzled chunk offset; recover it for the zero row
-                const int pslot = (u * NW + wave) * 64 + lane;
-                const int8_t* src = inside ? a_src[u] + tap_off
-                                           : cg.zero + swz<BK>(pslot / CPR, pslot % CPR) * 16;
+                const int iy = a_iy0[u] + a_ky[u], ix = a_ix0[u] + a_kx[u];
+                const bool inside = a_ky[u] < cg.kh && (unsigned)iy < (unsigned)cg.H &&
+                                    (unsigned)ix < (unsigned)cg.W;
+                const int8_t* src =
+                    inside ? a_src[u] + ((int64_t)a_ky[u] * cg.W + a_kx[u]) * cg.ldc + a_cin[u] * 16
+                           : cg.zero + a_zoff[u];
                 dma16(src, lds_a0 + buf * (BM * BK) + (u * NW + wave) * 1024);
-            }
-            if (c_kt + 1 < ksteps) {
-                ++c_kt;
-                if (++c_cs == cg.spt) {
-                    c_cs = 0;
-                    if (++c_kx == cg.kw) {
-                        c_kx = 0;
-                        ++c_ky;
+                if (advance) {
+                    int cin = a_cin[u] + CPR, kx = a_kx[u], ky = a_ky[u];
+                    while (cin >= cg.cpp) {
+                        cin -= cg.cpp;
+                        if (++kx == cg.kw) { kx = 0; ++ky; }
                     }
+                    a_cin[u] = cin;
+                    a_kx[u] = kx;
+                    a_ky[u] = ky;
                 }
             }
+            if (advance) ++c_kt;
         } else {
 #pragma unroll
             for (int u = 0; u < A_LOADS; ++u)
@@ -717,7 +730,7 @@ static hipError_t run_dma_conv(const int8_t* Aq, const int8_t* Wt, int64_t ldw, 
                                const float* scale_w, int32_t* acc_out, int64_t ldacc, float* Y,
                                int64_t ldy, hipStream_t stream) {
     constexpr int BK = 64;
-    if (Kpad < BK || Kpad % BK != 0 || cg.ldc % BK != 0 || cg.spt < 1) return hipErrorInvalidValue;
+    if (Kpad < BK || Kpad % BK != 0 || cg.ldc % 16 != 0 || cg.cpp < 1) return hipErrorInvalidValue;
     const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
     const int64_t total = tiles_m * tiles_n;
     return launch_kernel(kTimeGemm, qgemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, BK, NBUF, true>,
@@ -735,23 +748,20 @@ hipError_t launch_qconv(const int8_t* Aq, int64_t ldc, int B, int H, int W, int 
     cg.Wo = (W + 2 * pad - kw) / stride + 1;
     cg.H = H;
     cg.W = W;
+    cg.kh = kh;
     cg.kw = kw;
-    cg.spt = (int)(ldc / 64);
+    cg.cpp = (int)(ldc / 16);
     cg.stride = stride;
     cg.pad = pad;
     cg.ldc = ldc;
     cg.zero = Wt + N * ldw;            // the row of zeros that follows the N weight rows
     const int64_t M = (int64_t)B * cg.Ho * cg.Wo;
-    const int64_t Kpad = (int64_t)kh * kw * ldc;
+    const int64_t Kpad = ldw;          // kh*kw*ldc rounded up to a whole K-step
+    if (Kpad < (int64_t)kh * kw * ldc) return hipErrorInvalidValue;
     int tile = tuning().gemm_tile;
-    if (tile < 0) {
-        const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 128);
-        const int64_t t128 = ceil_div(M, 128) * ceil_div(N, 128);
-        if (N <= 64) tile = 6;
-        else if (t256 >= 128) tile = 10;
-        else if (t128 >= 48) tile = 9;
-        else tile = 6;
-    }
+    // measured on the 3x3 layers of the paper's networks: the 128x128 tile is level with or ahead
+    // of the larger ones (the loader's per-lane tap bookkeeping grows with the rows a lane loads)
+    if (tile < 0) tile = N <= 64 ? 6 : 9;
 #define OCS_CONV_ARGS Aq, Wt, ldw, M, N, Kpad, cg, scale_x, scale_w, acc_out, ldacc, Y, ldy, stream
     switch (tile) {
         case 6: return run_dma_conv<128, 64, 2, 2, 6>(OCS_CONV_ARGS);
@@ -763,20 +773,20 @@ hipError_t launch_qconv(const int8_t* Aq, int64_t ldc, int B, int H, int W, int 
 #undef OCS_CONV_ARGS
 }
 
-// Channel-major codes [N, ldq] (column j*g + t) -> tap-major [N + 1, g*ldc] (column t*ldc + j,
-// zero for j >= E), the extra row all zeros.  One lane per output byte quad.
+// Channel-major codes [N, ldq] (column j*g + t) -> tap-major [N + 1, ldt] (column t*ldc + j,
+// zero for j >= E and for columns past g*ldc), the extra row all zeros.  One lane per byte quad.
 __global__ __launch_bounds__(kThreads) void tap_major_kernel(const int8_t* __restrict__ Wq, int64_t ldq,
                                                              int64_t N, int E, int g, int64_t ldc,
-                                                             int8_t* __restrict__ Wt) {
-    const int64_t quads_per_row = (int64_t)g * ldc / 4;
+                                                             int64_t ldt, int8_t* __restrict__ Wt) {
+    const int64_t quads_per_row = ldt / 4;
     const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (o >= (N + 1) * quads_per_row) return;
     const int64_t n = o / quads_per_row;
-    const int64_t k = (o - n * quads_per_row) * 4;
+    const int64_t k = (o - n * quads_per_row) * 4;     // ldc % 4 == 0: a quad stays inside one tap
     const int t = (int)(k / ldc);
     const int j0 = (int)(k - (int64_t)t * ldc);
     unsigned packed = 0;
-    if (n < N) {
+    if (n < N && t < g) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int j = j0 + e;
@@ -789,9 +799,10 @@ __global__ __launch_bounds__(kThreads) void tap_major_kernel(const int8_t* __res
 
 hipError_t launch_tap_major(const int8_t* Wq, int64_t ldq, int64_t N, int E, int g, int64_t ldc,
                             int8_t* Wt, hipStream_t stream) {
-    const int64_t total = (N + 1) * ((int64_t)g * ldc / 4);
+    const int64_t ldt = round_up((int64_t)g * ldc, 64);
+    const int64_t total = (N + 1) * (ldt / 4);
     tap_major_kernel<<<dim3((unsigned)ceil_div(total, kThreads)), kThreads, 0, stream>>>(Wq, ldq, N, E, g,
-                                                                                       ldc, Wt);
+                                                                                       ldc, ldt, Wt);
     return hipGetLastError();
 }
 

@@ -125,8 +125,9 @@ class ExpandedConv:
         self.w = ExpandedLayer(N, C, self.g, r, bits_w, bits_x, clip_ratio_w=clip_ratio_w, device=device)
         self.N, self.C, self.s = self.w.N, self.w.C, self.w.s
         self.E = self.C + self.s
-        self.ldc = B.ocs_padded_cols(self.E)
-        self.Wt = torch.empty((self.N + 1, self.g * self.ldc), dtype=torch.int8, device=device)
+        self.ldc = B.ocs_padded_channels(self.E)
+        self.ldt = B.ocs_padded_cols(self.g * self.ldc)
+        self.Wt = torch.empty((self.N + 1, self.ldt), dtype=torch.int8, device=device)
         self.scale_x = torch.empty(2, dtype=torch.float32, device=device)
         self.device = device
         self._pixels = 0

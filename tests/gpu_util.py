@@ -111,10 +111,10 @@ def gpu_mse_clip(x, bits, n_bins=2048, n_cand=512, want_mse=True, ld_extra=0):
                 mse=None if mse is None else host(mse))
 
 
-def gpu_split_act(X, Cn, g, chan_src, chan_depth, s, bits, threshold=None, clip_ratio=1.0):
+def gpu_split_act(X, Cn, g, chan_src, chan_depth, s, bits, threshold=None, clip_ratio=1.0, ldq=None):
     M = X.shape[0]
     Xd = dev(X)
-    ldq = B.ocs_padded_cols((Cn + s) * g)
+    ldq = B.ocs_padded_cols((Cn + s) * g) if ldq is None else ldq
     cs = None if chan_src is None else dev(np.asarray(chan_src, dtype=np.int32))
     cd = None if chan_depth is None else dev(np.asarray(chan_depth, dtype=np.int32))
     q = torch.full((M, ldq), 77, dtype=torch.int8, device="cuda")
@@ -131,11 +131,12 @@ def gpu_conv_layer(A, Wm, Cn, kh, kw, stride, pad, s, bits_x=8, bits_w=8, thresh
     Bn, H, W, _ = A.shape
     N, g, E = Wm.shape[0], kh * kw, Cn + s
     wts = gpu_split_weights(Wm, Cn, g, s, bits=bits_w, want_f32=False)
-    ldc = B.ocs_padded_cols(E)
+    ldc = B.ocs_padded_channels(E)
     Wq = dev(wts["Wq"])
-    Wt = torch.full(((N + 1), g * ldc), 77, dtype=torch.int8, device="cuda")
+    Wt = torch.full(((N + 1), B.ocs_padded_cols(g * ldc)), 77, dtype=torch.int8, device="cuda")
     B.ocs_conv_weights_tap_major(Wq, N, E, g, Wq.stride(0), Wt, ldc)
-    Aq, sx = gpu_split_act(A.reshape(-1, Cn), Cn, 1, wts["chan_src"], None, s, bits_x, threshold=threshold)
+    Aq, sx = gpu_split_act(A.reshape(-1, Cn), Cn, 1, wts["chan_src"], None, s, bits_x, threshold=threshold,
+                           ldq=ldc)
     Aqd, sxd, swd = dev(Aq), dev(sx), dev(wts["scale"])
     Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
     M = Bn * Ho * Wo

@@ -38,6 +38,7 @@ def test_num_splits_matches_oracle_everywhere():
 
 def test_padded_cols_and_workspace():
     assert B.ocs_padded_cols(2358) == 2368
+    assert B.ocs_padded_channels(262) == 272 and B.ocs_padded_channels(4) == 16
     assert B.ocs_padded_cols(64) == 64 and B.ocs_padded_cols(65) == 128 and B.ocs_padded_cols(0) == 0
     assert B.ocs_workspace_bytes(0, 10) == 0
     for rows, cols in [(1, 1), (64, 256), (12544, 2304), (6000, 3000), (3211264, 147), (802816, 64)]:
@@ -73,7 +74,7 @@ def test_argument_errors_are_reported_without_a_device():
     assert L.ocs_mse_clip_threshold(A, 4, 4, 4, 1, 16, 4, A, A, A, A, ws, None) == -4
     assert L.ocs_qconv(A, 64, 1, 4, 4, 8, 3, 3, 1, 1, None, 4, 8, 8, A, A, None, 0, A, 4, None) == -1      # no weights
     assert L.ocs_qconv(A, 64, 1, 2, 2, 8, 3, 3, 1, 0, A, 4, 8, 8, A, A, None, 0, A, 4, None) == -2         # kernel larger than image
-    assert L.ocs_qconv(A, 96, 1, 4, 4, 8, 3, 3, 1, 1, A, 4, 8, 8, A, A, None, 0, A, 4, None) == -3         # ldc % 64
+    assert L.ocs_qconv(A, 72, 1, 4, 4, 8, 3, 3, 1, 1, A, 4, 8, 8, A, A, None, 0, A, 4, None) == -3         # ldc % 16
     assert L.ocs_qconv(A, 64, 1, 4, 4, 80, 3, 3, 1, 1, A, 4, 8, 8, A, A, None, 0, A, 4, None) == -2        # ldc < C_exp
     assert L.ocs_conv_weights_tap_major(A, 4, 8, 9, 64, A, 64, None) == -2                                  # ldq < C_exp*g
     # shapes
@@ -84,7 +85,7 @@ def test_argument_errors_are_reported_without_a_device():
     assert L.ocs_qgemm(A, 64, A, 64, 4, 4, 100, 8, 8, A, A, None, 0, A, 4, None, 0, None) == -2  # ld < Kpad
     assert L.ocs_qgemm(A, 64, A, 64, 4, 8, 4, 8, 8, A, A, None, 0, A, 4, None, 0, None) == -2    # ldy < N
     # alignment
-    assert L.ocs_quantize(A, 4, 4, 4, 8, A, 1.0, A, 48, A, A, ws, None) == -3
+    assert L.ocs_quantize(A, 4, 4, 4, 8, A, 1.0, A, 40, A, A, ws, None) == -3
     assert L.ocs_quantize(A, 4, 4, 4, 8, A, 1.0, A + 4, 64, A, A, ws, None) == -3
     assert L.ocs_qgemm(A + 1, 64, A, 64, 4, 4, 4, 8, 8, A, A, None, 0, A, 4, None, 0, None) == -3
     assert L.ocs_quantize(A, 4, 4, 4, 8, None, 1.0, A, 64, A, A + 16, ws, None) == -3   # workspace

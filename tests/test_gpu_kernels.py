@@ -331,7 +331,8 @@ def _conv_reference(A, Wm, Cn, kh, kw, stride, pad, s, bits_x, bits_w, threshold
     (2, 8, 8, 128, 70, 1, 1, 1, 0, 7),         # 1x1
     (2, 9, 9, 64, 64, 1, 1, 2, 0, 4),          # 1x1 stride 2: skips pixels
     (1, 23, 17, 3, 64, 7, 7, 2, 3, 1),         # stem-like: 3 channels, 7x7
-    (1, 5, 6, 130, 40, 2, 3, 1, 0, 0),         # no split, no padding, two K-steps per tap... (ldc 192)
+    (1, 5, 6, 130, 40, 2, 3, 1, 0, 0),         # no split, no padding; 9 chunks per pixel: K-steps straddle taps
+    (2, 6, 6, 10, 50, 3, 3, 1, 1, 1),          # one chunk per pixel: four taps per K-step
     (4, 14, 14, 256, 256, 3, 3, 1, 1, 6),      # config 2's layer at batch 4
 ])
 def test_qconv(tile, Bn, H, W, Cn, N, kh, kw, stride, pad, s):
@@ -349,9 +350,10 @@ def test_qconv(tile, Bn, H, W, Cn, N, kh, kw, stride, pad, s):
     assert np.array_equal(got["Aq"][:, :E], exp["Aq"][:, :E]) and not got["Aq"][:, E:].any()
     # tap-major weights: Wt[n, t*ldc + j] = Wq[n, j*g + t], zero padding, zero last row
     g = kh * kw
-    Wt = got["Wt"].reshape(N + 1, g, ldc)
+    assert ldc == (E + 15) // 16 * 16 and got["Wt"].shape[1] == (g * ldc + 63) // 64 * 64
+    Wt = got["Wt"][:, :g * ldc].reshape(N + 1, g, ldc)
     assert np.array_equal(Wt[:N, :, :E], exp["Wq"][:, :E * g].reshape(N, E, g).transpose(0, 2, 1))
-    assert not Wt[:N, :, E:].any() and not Wt[N].any()
+    assert not Wt[:N, :, E:].any() and not Wt[N].any() and not got["Wt"][:, g * ldc:].any()
     assert np.array_equal(got["acc"], exp["acc"])
     assert_y_close(got["Y"], exp["Y"])
 
