@@ -443,6 +443,39 @@ int ref_qgemm(const int8_t *Xq, int64_t ldx, const int8_t *Wq, int64_t ldw, int6
 }
 
 /*
+ * The layer's output handed to the next layer as codes instead of fp32: what Eq. 1 (and the
+ * activation side of Eq. 3 for the NEXT layer's split channels) makes of the dequantized
+ * output, with a static grid.  Per element, in fp32 as the GPU's epilogue computes it:
+ * y = float(acc) * (step_x * step_w); optionally y = max(y, 0); code = Q(y) on the grid of
+ * range [-T_next, T_next] with bits_next bits.  Expanded output channel j < N + s_next reads
+ * output channel chan_src_next[j] (NULL: identity, s_next = 0).  Columns N + s_next .. ldq-1
+ * are set to zero.  scale_out = {T_next, T_next / qmax}.
+ */
+int ref_requantize(const int32_t *acc, int64_t ldacc, int64_t M, int64_t N, float step_x, float step_w,
+                   int relu, int bits_next, float T_next, const int32_t *chan_src_next, int s_next,
+                   int8_t *Yq, int64_t ldq, float *scale_out) {
+    if (!acc || !Yq || !scale_out || M <= 0 || N <= 0 || s_next < 0 || ldacc < N) return REF_E_ARG;
+    if (ldq < N + s_next || bits_next < 2 || bits_next > 8) return REF_E_ARG;
+    if (s_next > 0 && !chan_src_next) return REF_E_ARG;
+    float qmax = (float)((1 << (bits_next - 1)) - 1);
+    float inv = inv_step_of(T_next, qmax);
+    float scale = step_x * step_w;
+    scale_out[0] = T_next;
+    scale_out[1] = T_next / qmax;
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j < N + s_next; ++j) {
+            int64_t src = chan_src_next ? chan_src_next[j] : j;
+            if (src < 0 || src >= N) return REF_E_ARG;
+            float y = (float)acc[i * ldacc + src] * scale;
+            if (relu && !(y > 0.0f)) y = 0.0f;
+            Yq[i * ldq + j] = code_of(y, inv, qmax);
+        }
+        for (int64_t j = N + s_next; j < ldq; ++j) Yq[i * ldq + j] = 0;
+    }
+    return REF_OK;
+}
+
+/*
  * Eq. 2 itself on real-valued operands, in fp64: Y[i,n] = sum_k X[i,k] * W[n,k].
  * Used to state the functional identity of Eq. 3 / Eq. 4 (split layer == unsplit layer).
  */

@@ -206,6 +206,22 @@ def qgemm(Xq, Wq, Kexp, step_x, step_w, want_acc=True, want_y=True):
     return acc, Y
 
 
+def requantize(acc, step_x, step_w, T_next, bits_next, chan_src_next=None, s_next=0, relu=False, ldq=None):
+    """The layer's output as the next layer's codes (static grid).  Returns (codes, scale)."""
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    M, N = acc.shape
+    ldq = N + s_next if ldq is None else int(ldq)
+    q = np.full((M, ldq), 99, dtype=np.int8)
+    sc = np.zeros(2, dtype=np.float32)
+    cs = None if chan_src_next is None else np.ascontiguousarray(chan_src_next, dtype=np.int32)
+    rc = lib().ref_requantize(_p(acc, C.c_int32), C.c_int64(N), C.c_int64(M), C.c_int64(N),
+                              C.c_float(step_x), C.c_float(step_w), C.c_int(1 if relu else 0),
+                              C.c_int(bits_next), C.c_float(T_next), _p(cs, C.c_int32), C.c_int(s_next),
+                              _p(q, C.c_int8), C.c_int64(ldq), _p(sc, C.c_float))
+    _check(rc, "ref_requantize")
+    return q, sc
+
+
 def layer_f64(X, W):
     """Eq. 2 on real operands in fp64: Y = X @ W.T."""
     X = np.ascontiguousarray(X, dtype=np.float32)

@@ -564,3 +564,29 @@ def test_quantizing_before_or_after_the_lowering_gives_the_same_codes():
     lowered_codes = ref.im2col(Aq.reshape(Bn, H, W, Cn + s), kh, kw, 1, 1)
     Xq, sx, _ = ref.split_act(ref.im2col(A, kh, kw, 1, 1), Cn, kh * kw, sel["chan_src"], None, s, 8, threshold=T)
     assert np.array_equal(sa, sx) and np.array_equal(lowered_codes, Xq)
+
+
+# ---- the output handed on as the next layer's codes ------------------------------------------
+
+@pytest.mark.parametrize("relu", [False, True])
+def test_requantized_output_is_the_next_layers_split_act(relu):
+    # it must be exactly what the (already pinned) activation pass of the next layer makes of
+    # the fp32 output float(acc) * (step_x * step_w), with a static grid
+    rng = np.random.default_rng(5 + relu)
+    M, N, s_next = 13, 24, 5
+    acc = rng.integers(-200000, 200001, (M, N)).astype(np.int32)
+    acc[2, 3] = 0
+    sx, sw = np.float32(3.0 / 127), np.float32(0.7 / 31)
+    y32 = acc.astype(np.float32) * (sx * sw)
+    if relu:
+        y32 = np.maximum(y32, np.float32(0))
+    nxt = ref.split_weights(rng.standard_normal((7, N)).astype(np.float32), N, 1, s_next)   # next layer's split list
+    T = float(np.float32(0.6) * np.abs(y32).max())                                          # a clipping static grid
+    expect, se, _ = ref.split_act(y32, N, 1, nxt["chan_src"], None, s_next, 6, threshold=T, ldq=64)
+    got, sg = ref.requantize(acc, sx, sw, T, 6, nxt["chan_src"], s_next, relu=relu, ldq=64)
+    assert np.array_equal(sg, se) and np.array_equal(got, expect)
+    assert np.abs(got.astype(np.int32)).max() == 31 and not got[:, N + s_next:].any()
+    if relu:
+        assert got.min() == 0
+    plain, _ = ref.requantize(acc, sx, sw, T, 6, relu=relu)
+    assert np.array_equal(plain, expect[:, :N])
