@@ -262,6 +262,34 @@ int ocs_qconv(const int8_t *Aq, int64_t ldc, int B, int H, int W, int C_exp, int
               float *Y, int64_t ldy, void *stream);
 
 /*
+ * ocs_qgemm / ocs_qconv with the output handed to the NEXT layer as codes instead of fp32: the
+ * epilogue applies Eq. 1 with the next layer's static grid to the dequantized output (and the
+ * activation side of the next layer's Eq. 3: the channels it splits are duplicated), so the
+ * 4-byte output and the next layer's pass over it never touch memory.  Per element, in fp32:
+ *   y = float(acc) * (scale_x[1] * scale_w[1]);  relu != 0: y = max(y, 0);
+ *   code = clamp(rne(y * (qmax / T)), -qmax, qmax), T = *next_threshold (device float, the grid
+ *   fixed from profiling as in Sec. 5), qmax = 2^(next_bits-1) - 1, arithmetic as in ocs_quantize.
+ *   Yq[i, j] = code of output channel next_chan_src[j] for j < N + next_splits (next_chan_src
+ *   device int32 [N + next_splits] as the next layer's ocs_split_weights wrote it; its first N
+ *   entries are the identity; NULL allowed when next_splits == 0).
+ *   Yq [M, ldyq] int8, ldyq a multiple of OCS_CALIGN and >= N + next_splits.  Columns
+ *   N + next_splits .. ldyq-1 are NOT written: zero them once when the buffer is allocated.
+ *   next_scale_out device float[2] = {T, T / qmax} (may be NULL; must not be next_threshold).
+ *   acc_out optional int32 [M, ldacc] as in ocs_qgemm.  Other arguments as in ocs_qgemm / ocs_qconv.
+ */
+int ocs_qgemm_requant(const int8_t *Xq, int64_t ldx, const int8_t *Wq, int64_t ldw, int64_t M,
+                      int64_t N, int64_t Kexp, int bits_x, int bits_w, const float *scale_x,
+                      const float *scale_w, int relu, const float *next_threshold, int next_bits,
+                      const int32_t *next_chan_src, int next_splits, int8_t *Yq, int64_t ldyq,
+                      float *next_scale_out, int32_t *acc_out, int64_t ldacc, void *stream);
+int ocs_qconv_requant(const int8_t *Aq, int64_t ldc, int B, int H, int W, int C_exp, int kh, int kw,
+                      int stride, int pad, const int8_t *Wt, int64_t N, int bits_x, int bits_w,
+                      const float *scale_x, const float *scale_w, int relu,
+                      const float *next_threshold, int next_bits, const int32_t *next_chan_src,
+                      int next_splits, int8_t *Yq, int64_t ldyq, float *next_scale_out,
+                      int32_t *acc_out, int64_t ldacc, void *stream);
+
+/*
  * Measurement helper (no passage of the paper).  Arms a pair of caller-created hipEvent_t
  * (created with timing enabled) for the calling thread's NEXT launch of one kernel family:
  * OCS_TIME_SPLIT_QUANTIZE (the streaming pass of ocs_split_act / ocs_quantize /

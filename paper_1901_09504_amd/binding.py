@@ -67,6 +67,12 @@ def lib():
     L.ocs_qconv.restype = _i32
     L.ocs_qconv.argtypes = [_vp, _i64, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _i64, _i32,
                             _i32, _vp, _vp, _vp, _i64, _vp, _i64, _vp]
+    L.ocs_qgemm_requant.restype = _i32
+    L.ocs_qgemm_requant.argtypes = [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _vp, _vp, _i32, _vp,
+                                    _i32, _vp, _i32, _vp, _i64, _vp, _vp, _i64, _vp]
+    L.ocs_qconv_requant.restype = _i32
+    L.ocs_qconv_requant.argtypes = [_vp, _i64, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _i64, _i32,
+                                    _i32, _vp, _vp, _i32, _vp, _i32, _vp, _i32, _vp, _i64, _vp, _vp, _i64, _vp]
     L.ocs_quantize.restype = _i32
     L.ocs_quantize.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _f32, _vp, _i64, _vp, _vp, _sz, _vp]
     L.ocs_split_act.restype = _i32
@@ -198,6 +204,25 @@ def ocs_qconv(Aq, ldc, Bn, H, W, C_exp, kh, kw, stride, pad, Wt, N, bits_x, bits
     _check(lib().ocs_qconv(_ptr(Aq), ldc, Bn, H, W, C_exp, kh, kw, stride, pad, _ptr(Wt), N, bits_x,
                            bits_w, _ptr(scale_x), _ptr(scale_w), _ptr(acc_out), ldacc, _ptr(Y), ldy,
                            _stream(stream)), "ocs_qconv")
+
+
+def ocs_qgemm_requant(Xq, ldx, Wq, ldw, M, N, Kexp, bits_x, bits_w, scale_x, scale_w, relu, next_threshold,
+                      next_bits, next_chan_src, next_splits, Yq, ldyq, next_scale_out, acc_out=None, ldacc=0,
+                      stream=None):
+    _check(lib().ocs_qgemm_requant(_ptr(Xq), ldx, _ptr(Wq), ldw, M, N, Kexp, bits_x, bits_w, _ptr(scale_x),
+                                   _ptr(scale_w), int(bool(relu)), _ptr(next_threshold), next_bits,
+                                   _ptr(next_chan_src), next_splits, _ptr(Yq), ldyq, _ptr(next_scale_out),
+                                   _ptr(acc_out), ldacc, _stream(stream)), "ocs_qgemm_requant")
+
+
+def ocs_qconv_requant(Aq, ldc, Bn, H, W, C_exp, kh, kw, stride, pad, Wt, N, bits_x, bits_w, scale_x, scale_w,
+                      relu, next_threshold, next_bits, next_chan_src, next_splits, Yq, ldyq, next_scale_out,
+                      acc_out=None, ldacc=0, stream=None):
+    _check(lib().ocs_qconv_requant(_ptr(Aq), ldc, Bn, H, W, C_exp, kh, kw, stride, pad, _ptr(Wt), N, bits_x,
+                                   bits_w, _ptr(scale_x), _ptr(scale_w), int(bool(relu)),
+                                   _ptr(next_threshold), next_bits, _ptr(next_chan_src), next_splits,
+                                   _ptr(Yq), ldyq, _ptr(next_scale_out), _ptr(acc_out), ldacc,
+                                   _stream(stream)), "ocs_qconv_requant")
 
 
 def ocs_quantize(x, rows, cols, ldx, bits, threshold, clip_ratio, q, ldq, scale_out, workspace,

@@ -402,6 +402,92 @@ int ocs_qconv(const int8_t* Aq, int64_t ldc, int B, int H, int W, int C_exp, int
     return OCS_OK;
 }
 
+static int check_requant(int N, const float* next_threshold, int next_bits,
+                         const int32_t* next_chan_src, int next_splits, const int8_t* Yq,
+                         int64_t ldyq, const float* next_scale_out) {
+    if (!next_threshold || !Yq) return OCS_E_NULL;
+    if (next_splits < 0 || (int64_t)N + next_splits > OCS_MAX_EXPANDED_CHANNELS) return OCS_E_SPLITS;
+    if (next_splits > 0 && !next_chan_src) return OCS_E_NULL;
+    if (ldyq < (int64_t)N + next_splits) return OCS_E_SHAPE;
+    if (ldyq % OCS_CALIGN != 0 || !aligned(Yq, 16)) return OCS_E_ALIGN;
+    if (!bits_ok(next_bits)) return OCS_E_BITS;
+    if (next_scale_out == next_threshold) return OCS_E_MODE;   // the kernel reads one while writing the other
+    return OCS_OK;
+}
+
+static Requant make_requant(int relu, const float* next_threshold, int next_bits,
+                            const int32_t* next_chan_src, int next_splits, int8_t* Yq,
+                            int64_t ldyq, float* next_scale_out) {
+    Requant rq;
+    rq.Yq = Yq;
+    rq.ldyq = ldyq;
+    rq.thr = next_threshold;
+    rq.qmax = qmax_of(next_bits);
+    rq.relu = relu != 0;
+    rq.chan_src = next_chan_src;
+    rq.s_next = next_splits;
+    rq.scale_out = next_scale_out;
+    return rq;
+}
+
+int ocs_qgemm_requant(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
+                      int64_t N, int64_t Kexp, int bits_x, int bits_w, const float* scale_x,
+                      const float* scale_w, int relu, const float* next_threshold, int next_bits,
+                      const int32_t* next_chan_src, int next_splits, int8_t* Yq, int64_t ldyq,
+                      float* next_scale_out, int32_t* acc_out, int64_t ldacc, void* stream) {
+    if (!Xq || !Wq || !scale_x || !scale_w) return OCS_E_NULL;
+    if (M <= 0 || N <= 0 || Kexp <= 0) return OCS_E_SHAPE;
+    if (M > (int64_t)1 << 30 || N > (int64_t)1 << 30 || Kexp > (int64_t)1 << 30) return OCS_E_SHAPE;
+    const int64_t Kpad = round_up(Kexp, OCS_KALIGN);
+    if (ldx < Kpad || ldw < Kpad || (acc_out && ldacc < N)) return OCS_E_SHAPE;
+    if (ldx % OCS_KALIGN != 0 || ldw % OCS_KALIGN != 0 || !aligned(Xq, 16) || !aligned(Wq, 16))
+        return OCS_E_ALIGN;
+    if (!bits_ok(bits_x) || !bits_ok(bits_w)) return OCS_E_BITS;
+    const int64_t qx = (1 << (bits_x - 1)) - 1, qw = (1 << (bits_w - 1)) - 1;
+    if (Kexp * qx * qw >= (int64_t)1 << 31) return OCS_E_OVERFLOW;
+    int rc = check_requant((int)N, next_threshold, next_bits, next_chan_src, next_splits, Yq, ldyq,
+                           next_scale_out);
+    if (rc) return rc;
+    hipError_t e = launch_qgemm(Xq, ldx, Wq, ldw, M, N, Kpad, scale_x, scale_w, acc_out, ldacc, nullptr,
+                                N, static_cast<hipStream_t>(stream),
+                                make_requant(relu, next_threshold, next_bits, next_chan_src,
+                                             next_splits, Yq, ldyq, next_scale_out));
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
+int ocs_qconv_requant(const int8_t* Aq, int64_t ldc, int B, int H, int W, int C_exp, int kh, int kw,
+                      int stride, int pad, const int8_t* Wt, int64_t N, int bits_x, int bits_w,
+                      const float* scale_x, const float* scale_w, int relu,
+                      const float* next_threshold, int next_bits, const int32_t* next_chan_src,
+                      int next_splits, int8_t* Yq, int64_t ldyq, float* next_scale_out,
+                      int32_t* acc_out, int64_t ldacc, void* stream) {
+    if (!Aq || !Wt || !scale_x || !scale_w) return OCS_E_NULL;
+    if (B <= 0 || H <= 0 || W <= 0 || C_exp <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0 ||
+        N <= 0 || N > (int64_t)1 << 30)
+        return OCS_E_SHAPE;
+    if (H + 2 * pad < kh || W + 2 * pad < kw) return OCS_E_SHAPE;
+    const int64_t Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
+    const int64_t M = (int64_t)B * Ho * Wo;
+    if (M > (int64_t)1 << 30 || (int64_t)B * H * W > (int64_t)1 << 31) return OCS_E_SHAPE;
+    if (ldc < C_exp || (int64_t)kh * kw * ldc > (int64_t)1 << 30) return OCS_E_SHAPE;
+    if (acc_out && ldacc < N) return OCS_E_SHAPE;
+    if (ldc % OCS_CALIGN != 0 || !aligned(Aq, 16) || !aligned(Wt, 16)) return OCS_E_ALIGN;
+    if (!bits_ok(bits_x) || !bits_ok(bits_w)) return OCS_E_BITS;
+    const int64_t qx = (1 << (bits_x - 1)) - 1, qw = (1 << (bits_w - 1)) - 1;
+    if ((int64_t)kh * kw * C_exp * qx * qw >= (int64_t)1 << 31) return OCS_E_OVERFLOW;
+    int rc = check_requant((int)N, next_threshold, next_bits, next_chan_src, next_splits, Yq, ldyq,
+                           next_scale_out);
+    if (rc) return rc;
+    hipError_t e = launch_qconv(Aq, ldc, B, H, W, kh, kw, stride, pad, Wt,
+                                round_up((int64_t)kh * kw * ldc, OCS_KALIGN), N, scale_x, scale_w,
+                                acc_out, ldacc, nullptr, N, static_cast<hipStream_t>(stream),
+                                make_requant(relu, next_threshold, next_bits, next_chan_src,
+                                             next_splits, Yq, ldyq, next_scale_out));
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
 int ocs_time_next(int family, void* start_event, void* stop_event) {
     if (family != kTimeSplitQuantize && family != kTimeGemm && family != kTimeAbsmax) return OCS_E_MODE;
     if (!start_event || !stop_event) return OCS_E_NULL;

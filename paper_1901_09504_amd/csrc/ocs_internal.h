@@ -102,11 +102,26 @@ hipError_t launch_mse_clip(const float* x, int64_t ldx, int64_t rows, int64_t co
                            unsigned long long* hist, double* mse_out, float* out,
                            hipStream_t stream);
 
+// What the GEMM / convolution epilogue may do instead of writing fp32: hand the output to the
+// next layer as codes (Eq. 1 with the next layer's static grid, after an optional ReLU, plus
+// the copies of the channels the next layer splits: the activation side of its Eq. 3).
+// Yq == NULL: plain fp32 output.
+struct Requant {
+    int8_t* Yq = nullptr;            // [M, ldyq]; columns N + s_next .. ldyq-1 are not written
+    int64_t ldyq = 0;
+    const float* thr = nullptr;      // device float: the next layer's threshold
+    float qmax = 0.0f;
+    int relu = 0;
+    const int32_t* chan_src = nullptr;   // [N + s_next] (NULL when s_next == 0)
+    int s_next = 0;
+    float* scale_out = nullptr;      // device float[2] = {T, T/qmax} (may be NULL)
+};
+
 // int8 x int8 -> int32 MFMA GEMM over Kpad (multiple of 64) with dequantizing epilogue.
 hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
                         int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,
                         int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy,
-                        hipStream_t stream);
+                        hipStream_t stream, const Requant& rq = Requant{});
 
 // Convolution with the lowering folded into the GEMM's A-operand loader: Aq [B, H, W, ldc]
 // codes of the un-lowered activation, Wt [N + 1, kh*kw*ldc] tap-major weight codes whose last
@@ -114,7 +129,7 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
 hipError_t launch_qconv(const int8_t* Aq, int64_t ldc, int B, int H, int W, int kh, int kw, int stride,
                         int pad, const int8_t* Wt, int64_t ldw, int64_t N, const float* scale_x,
                         const float* scale_w, int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy,
-                        hipStream_t stream);
+                        hipStream_t stream, const Requant& rq = Requant{});
 hipError_t launch_tap_major(const int8_t* Wq, int64_t ldq, int64_t N, int E, int g, int64_t ldc,
                             int8_t* Wt, hipStream_t stream);
 

@@ -224,6 +224,95 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N_ & 15) | (7 << 4) | (15 << 8) | ((N_ >> 4) << 14));
 }
 
+__device__ __forceinline__ unsigned out_code(int a, float scale, int relu, float inv, float qmax) {
+    float y = (float)a * scale;
+    if (relu) y = y > 0.0f ? y : 0.0f;
+    float p = y * inv;
+    p = __builtin_amdgcn_fmed3f(p, -qmax, qmax);
+    return __float_as_uint(p + 12582912.0f) & 0xFFu;   // round half to even; low byte = code
+}
+
+// ROWS x WN accumulators of one wave, staged row-major in its piece of LDS, go out to memory:
+// lane (row, four consecutive columns) per 16-byte LDS read.  rbase / cbase: global row and
+// column of the staged block's corner.
+template <int ROWS, int WN>
+__device__ __forceinline__ void emit_staged_rows(const int32_t* stage, int lane, int rbase, int cbase,
+                                                 int M, int N, float scale, float* __restrict__ Y,
+                                                 int64_t ldy, int32_t* __restrict__ acc_out,
+                                                 int64_t ldacc, bool vec_y, bool vec_a,
+                                                 const Requant& rq, float inv) {
+    constexpr int LPR = WN / 4;            // lanes per row (8, 16 or 32)
+    constexpr int SLOTS = ROWS * LPR;      // 16-byte reads of the block
+#pragma unroll
+    for (int it = 0; it < (SLOTS + 63) / 64; ++it) {
+        const int idx = it * 64 + lane;
+        if (SLOTS % 64 != 0 && idx >= SLOTS) break;
+        const int rr = idx / LPR, cc = (idx % LPR) * 4;
+        const i32x4 a = *reinterpret_cast<const i32x4*>(&stage[rr * WN + cc]);
+        const int r = rbase + rr, c = cbase + cc;
+        if (r >= M || c >= N) continue;
+        if (rq.Yq != nullptr) {
+            int8_t* qp = rq.Yq + (int64_t)r * rq.ldyq + c;
+            unsigned q[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) q[e] = out_code(a[e], scale, rq.relu, inv, rq.qmax);
+            if (c + 3 < N) {
+                *reinterpret_cast<unsigned*>(qp) = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (c + e < N) qp[e] = (int8_t)q[e];
+            }
+        } else {
+            float* yp = Y + (int64_t)r * ldy + c;
+            if (vec_y && c + 3 < N) {
+                f32x4 y;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) y[e] = (float)a[e] * scale;
+                *reinterpret_cast<f32x4*>(yp) = y;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (c + e < N) yp[e] = (float)a[e] * scale;
+            }
+        }
+        if (acc_out) {
+            int32_t* ap = acc_out + (int64_t)r * ldacc + c;
+            if (vec_a && c + 3 < N) {
+                *reinterpret_cast<i32x4*>(ap) = a;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (c + e < N) ap[e] = a[e];
+            }
+        }
+    }
+    // copies for the channels the next layer splits: appended column N + j repeats column
+    // chan_src[N + j]; the wave that holds that column writes it, one lane per staged row
+    if (rq.Yq != nullptr && rq.s_next > 0 && lane < ROWS) {
+        const int r = rbase + lane;
+        for (int j = 0; j < rq.s_next; ++j) {
+            int src = rq.chan_src[N + j];
+            src = src < 0 ? 0 : (src >= N ? N - 1 : src);
+            const int local = src - cbase;
+            if (local >= 0 && local < WN && r < M)
+                rq.Yq[(int64_t)r * rq.ldyq + N + j] =
+                    (int8_t)out_code(stage[lane * WN + local], scale, rq.relu, inv, rq.qmax);
+        }
+    }
+}
+
+__device__ __forceinline__ float requant_inv(const Requant& rq, bool writer) {
+    if (rq.Yq == nullptr) return 0.0f;
+    const float T = *rq.thr;
+    if (writer && rq.scale_out != nullptr) {
+        rq.scale_out[0] = T;
+        rq.scale_out[1] = T / rq.qmax;
+    }
+    if (!(T > 0.0f)) return 0.0f;
+    return __builtin_fminf(__fdiv_rn(rq.qmax, T), 3.402823466e+38f);
+}
+
 // Geometry of a convolution whose lowering to the GEMM is done by the A-operand loader itself
 // (CONV variant below): the un-lowered activation codes Aq [B, H, W, ldc] (ldc bytes per pixel,
 // a multiple of 16: the expanded channels first, zero padding after), kernel kh x kw, output
@@ -242,7 +331,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
     const int8_t* __restrict__ Xq, int64_t ldx, const int8_t* __restrict__ Wq, int64_t ldw, int M,
     int N, int ksteps, const float* __restrict__ scale_x, const float* __restrict__ scale_w,
     int32_t* __restrict__ acc_out, int64_t ldacc, float* __restrict__ Y, int64_t ldy, int tiles_n,
-    unsigned total_tiles, ConvGeom cg) {
+    unsigned total_tiles, ConvGeom cg, Requant rq) {
     constexpr int NW = WAVES_M * WAVES_N;  // waves per workgroup (4, 8 or 16)
     constexpr int NT = NW * 64;
     static_assert(NW == 4 || NW == 8 || NW == 16, "4, 8 or 16 waves");
@@ -460,13 +549,11 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
     static_assert(WAVE_STAGE >= 32 * WN * 4, "ring too small to stage 32 rows of a wave's tile");
     static_assert(WAVE_STAGE % 16 == 0, "staging area must keep 16-byte alignment");
     int32_t* stage = reinterpret_cast<int32_t*>(&lds[wave * WAVE_STAGE]);
-    constexpr int LPR = WN / 4;            // lanes per row of the wave's tile (8, 16 or 32)
-    constexpr int RPI = 64 / LPR;          // rows per 16-byte access of the wave
     const float scale = scale_x[1] * scale_w[1];
+    const float inv = requant_inv(rq, blockIdx.x == 0 && tid == 0);
     const bool vec_y = (reinterpret_cast<uintptr_t>(Y) % 16 == 0) && (ldy % 4 == 0);
     const bool vec_a = acc_out != nullptr && (reinterpret_cast<uintptr_t>(acc_out) % 16 == 0) &&
                        (ldacc % 4 == 0);
-    const int srow = lane / LPR, scol = (lane % LPR) * 4;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -477,36 +564,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
                     acc[i][j][v];
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int it = 0; it < 32 / RPI; ++it) {
-            const int rr = it * RPI + srow;
-            const i32x4 a = *reinterpret_cast<const i32x4*>(&stage[rr * WN + scol]);
-            const int r = row0 + wm * WM + i * 32 + rr;
-            const int c = col0 + wn * WN + scol;
-            if (r < M && c < N) {
-                float* yp = Y + (int64_t)r * ldy + c;
-                if (vec_y && c + 3 < N) {
-                    f32x4 y;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) y[e] = (float)a[e] * scale;
-                    *reinterpret_cast<f32x4*>(yp) = y;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (c + e < N) yp[e] = (float)a[e] * scale;
-                }
-                if (acc_out) {
-                    int32_t* ap = acc_out + (int64_t)r * ldacc + c;
-                    if (vec_a && c + 3 < N) {
-                        *reinterpret_cast<i32x4*>(ap) = a;
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (c + e < N) ap[e] = a[e];
-                    }
-                }
-            }
-        }
+        emit_staged_rows<32, WN>(stage, lane, row0 + wm * WM + i * 32, col0 + wn * WN, M, N, scale, Y,
+                                 ldy, acc_out, ldacc, vec_y, vec_a, rq, inv);
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         __builtin_amdgcn_wave_barrier();   // the reads are issued before the next block's writes
     }
@@ -539,7 +598,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_wholek_kernel(
     const int8_t* __restrict__ Xq, int64_t ldx, const int8_t* __restrict__ Wq, int64_t ldw, int M,
     int N, int ksteps, const float* __restrict__ scale_x, const float* __restrict__ scale_w,
     int32_t* __restrict__ acc_out, int64_t ldacc, float* __restrict__ Y, int64_t ldy, int tiles_n,
-    unsigned total_tiles) {
+    unsigned total_tiles, Requant rq) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int TM = WM / 32, TN = WN / 32;
@@ -622,8 +681,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_wholek_kernel(
     // Epilogue as in the ring kernel (each wave turns its accumulators through a private piece
     // of LDS into rows of 16-byte stores), 8 rows at a time to keep the footprint small.
     int32_t* stage = reinterpret_cast<int32_t*>(&dlds[wave * (8 * WN * 4)]);
-    constexpr int LPR = WN / 4;
     const float scale = scale_x[1] * scale_w[1];
+    const float inv = requant_inv(rq, blockIdx.x == 0 && tid == 0);
     const bool vec_y = (reinterpret_cast<uintptr_t>(Y) % 16 == 0) && (ldy % 4 == 0);
     const bool vec_a = acc_out != nullptr && (reinterpret_cast<uintptr_t>(acc_out) % 16 == 0) &&
                        (ldacc % 4 == 0);
@@ -638,37 +697,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_wholek_kernel(
                     stage[((lane >> 5) * 4 + e) * WN + j * 32 + (lane & 31)] = acc[i][j][q * 4 + e];
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int it = 0; it < (8 * LPR) / 64; ++it) {
-                const int idx = it * 64 + lane;
-                const int rr = idx / LPR, cc = (idx % LPR) * 4;
-                const i32x4 a = *reinterpret_cast<const i32x4*>(&stage[rr * WN + cc]);
-                const int r = row0 + wm * WM + i * 32 + q * 8 + rr;
-                const int c = col0 + wn * WN + cc;
-                if (r < M && c < N) {
-                    float* yp = Y + (int64_t)r * ldy + c;
-                    if (vec_y && c + 3 < N) {
-                        f32x4 y;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) y[e] = (float)a[e] * scale;
-                        *reinterpret_cast<f32x4*>(yp) = y;
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (c + e < N) yp[e] = (float)a[e] * scale;
-                    }
-                    if (acc_out) {
-                        int32_t* ap = acc_out + (int64_t)r * ldacc + c;
-                        if (vec_a && c + 3 < N) {
-                            *reinterpret_cast<i32x4*>(ap) = a;
-                        } else {
-#pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (c + e < N) ap[e] = a[e];
-                        }
-                    }
-                }
-            }
+            emit_staged_rows<8, WN>(stage, lane, row0 + wm * WM + i * 32 + q * 8, col0 + wn * WN, M, N,
+                                    scale, Y, ldy, acc_out, ldacc, vec_y, vec_a, rq, inv);
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             __builtin_amdgcn_wave_barrier();
         }
@@ -688,7 +718,7 @@ template <int BM, int BN, int WAVES_M, int WAVES_N>
 static hipError_t run_wholek(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw,
                              int64_t M, int64_t N, int64_t Kpad, const float* scale_x,
                              const float* scale_w, int32_t* acc_out, int64_t ldacc, float* Y,
-                             int64_t ldy, hipStream_t stream) {
+                             int64_t ldy, hipStream_t stream, const Requant& rq) {
     const int64_t lds = wholek_lds_bytes<BM, BN, WAVES_M, WAVES_N>(Kpad);
     if (Kpad < 64 || Kpad % 64 != 0 || lds > kWholeKMaxLds) return hipErrorInvalidValue;
     // more than 64 KB of dynamic LDS has to be opted into, once per kernel
@@ -705,14 +735,14 @@ static hipError_t run_wholek(const int8_t* Xq, int64_t ldx, const int8_t* Wq, in
     return launch_kernel(kTimeGemm, qgemm_wholek_kernel<BM, BN, WAVES_M, WAVES_N>,
                          dim3((unsigned)total), dim3(WAVES_M * WAVES_N * 64), (unsigned)lds, stream,
                          Xq, ldx, Wq, ldw, (int)M, (int)N, (int)(Kpad / 64), scale_x, scale_w,
-                         acc_out, ldacc, Y, ldy, (int)tiles_n, (unsigned)total);
+                         acc_out, ldacc, Y, ldy, (int)tiles_n, (unsigned)total, rq);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF>
 static hipError_t run_dma(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
                           int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,
                           int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy,
-                          hipStream_t stream) {
+                          hipStream_t stream, const Requant& rq) {
     // the kernel clamps its K index to ksteps - 1: it must never be launched with no K-step
     if (Kpad < BK || Kpad % BK != 0) return hipErrorInvalidValue;
     const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
@@ -720,7 +750,7 @@ static hipError_t run_dma(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64
     return launch_kernel(kTimeGemm, qgemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, BK, NBUF>,
                          dim3((unsigned)total), dim3(WAVES_M * WAVES_N * 64), 0, stream, Xq, ldx, Wq, ldw, (int)M,
                          (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y, ldy,
-                         (int)tiles_n, (unsigned)total, ConvGeom{});
+                         (int)tiles_n, (unsigned)total, ConvGeom{}, rq);
 }
 
 // The same kernel with the lowering of a convolution done by its A-operand loader.
@@ -728,7 +758,7 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, int NBUF>
 static hipError_t run_dma_conv(const int8_t* Aq, const int8_t* Wt, int64_t ldw, int64_t M, int64_t N,
                                int64_t Kpad, const ConvGeom& cg, const float* scale_x,
                                const float* scale_w, int32_t* acc_out, int64_t ldacc, float* Y,
-                               int64_t ldy, hipStream_t stream) {
+                               int64_t ldy, hipStream_t stream, const Requant& rq) {
     constexpr int BK = 64;
     if (Kpad < BK || Kpad % BK != 0 || cg.ldc % 16 != 0 || cg.cpp < 1) return hipErrorInvalidValue;
     const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
@@ -736,13 +766,13 @@ static hipError_t run_dma_conv(const int8_t* Aq, const int8_t* Wt, int64_t ldw, 
     return launch_kernel(kTimeGemm, qgemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, BK, NBUF, true>,
                          dim3((unsigned)total), dim3(WAVES_M * WAVES_N * 64), 0, stream, Aq, cg.ldc, Wt,
                          ldw, (int)M, (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y,
-                         ldy, (int)tiles_n, (unsigned)total, cg);
+                         ldy, (int)tiles_n, (unsigned)total, cg, rq);
 }
 
 hipError_t launch_qconv(const int8_t* Aq, int64_t ldc, int B, int H, int W, int kh, int kw, int stride,
                         int pad, const int8_t* Wt, int64_t ldw, int64_t N, const float* scale_x,
                         const float* scale_w, int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy,
-                        hipStream_t stream) {
+                        hipStream_t stream, const Requant& rq) {
     ConvGeom cg;
     cg.Ho = (H + 2 * pad - kh) / stride + 1;
     cg.Wo = (W + 2 * pad - kw) / stride + 1;
@@ -762,7 +792,7 @@ hipError_t launch_qconv(const int8_t* Aq, int64_t ldc, int B, int H, int W, int 
     // measured on the 3x3 layers of the paper's networks: the 128x128 tile is level with or ahead
     // of the larger ones (the loader's per-lane tap bookkeeping grows with the rows a lane loads)
     if (tile < 0) tile = N <= 64 ? 6 : 9;
-#define OCS_CONV_ARGS Aq, Wt, ldw, M, N, Kpad, cg, scale_x, scale_w, acc_out, ldacc, Y, ldy, stream
+#define OCS_CONV_ARGS Aq, Wt, ldw, M, N, Kpad, cg, scale_x, scale_w, acc_out, ldacc, Y, ldy, stream, rq
     switch (tile) {
         case 6: return run_dma_conv<128, 64, 2, 2, 6>(OCS_CONV_ARGS);
         case 7: return run_dma_conv<64, 64, 2, 2, 6>(OCS_CONV_ARGS);
@@ -823,12 +853,13 @@ static hipError_t run(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t l
                          (int)tiles_n, (unsigned)total);
 }
 
-#define OCS_GEMM_ARGS Xq, ldx, Wq, ldw, M, N, Kpad, scale_x, scale_w, acc_out, ldacc, Y, ldy, stream
+#define OCS_GEMM_ARGS_F32 Xq, ldx, Wq, ldw, M, N, Kpad, scale_x, scale_w, acc_out, ldacc, Y, ldy, stream
+#define OCS_GEMM_ARGS OCS_GEMM_ARGS_F32, rq
 
 hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
                         int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,
                         int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy,
-                        hipStream_t stream) {
+                        hipStream_t stream, const Requant& rq) {
     int tile = tuning().gemm_tile;
     if (tile < 0) {
         // Measured on MI355X.  A CU draws operands through its vector-memory path at only
@@ -848,8 +879,10 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
     // a 128-byte K-step needs the K extent to be a multiple of 128
     const bool k128 = Kpad % 128 == 0;
     switch (tile) {
-        case 0: return run<128, 128, 2, 2, 64, 6>(OCS_GEMM_ARGS);      // register-staged
-        case 1: return run<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);       // register-staged
+        case 0: if (rq.Yq == nullptr) return run<128, 128, 2, 2, 64, 6>(OCS_GEMM_ARGS_F32);  // register-staged
+                return run_dma<128, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS);
+        case 1: if (rq.Yq == nullptr) return run<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS_F32);   // register-staged
+                return run_dma<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
         case 2: return run_dma<128, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS);
         case 3: return k128 ? run_dma<128, 128, 2, 2, 128, 3>(OCS_GEMM_ARGS)
                             : run_dma<128, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS);

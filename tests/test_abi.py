@@ -77,6 +77,11 @@ def test_argument_errors_are_reported_without_a_device():
     assert L.ocs_qconv(A, 72, 1, 4, 4, 8, 3, 3, 1, 1, A, 4, 8, 8, A, A, None, 0, A, 4, None) == -3         # ldc % 16
     assert L.ocs_qconv(A, 64, 1, 4, 4, 80, 3, 3, 1, 1, A, 4, 8, 8, A, A, None, 0, A, 4, None) == -2        # ldc < C_exp
     assert L.ocs_conv_weights_tap_major(A, 4, 8, 9, 64, A, 64, None) == -2                                  # ldq < C_exp*g
+    assert L.ocs_qgemm_requant(A, 64, A, 64, 4, 4, 4, 8, 8, A, A, 0, None, 8, None, 0, A, 16, None, None, 0, None) == -1   # no grid
+    assert L.ocs_qgemm_requant(A, 64, A, 64, 4, 4, 4, 8, 8, A, A, 0, A, 8, None, 2, A, 16, None, None, 0, None) == -1      # no list
+    assert L.ocs_qgemm_requant(A, 64, A, 64, 4, 20, 4, 8, 8, A, A, 0, A, 8, None, 0, A, 16, None, None, 0, None) == -2     # ldyq < N
+    assert L.ocs_qgemm_requant(A, 64, A, 64, 4, 4, 4, 8, 8, A, A, 0, A, 8, None, 0, A, 24, None, None, 0, None) == -3      # ldyq % 16
+    assert L.ocs_qgemm_requant(A, 64, A, 64, 4, 4, 4, 8, 8, A, A, 0, A, 8, None, 0, A, 16, A, None, 0, None) == -9         # scale_out aliases the grid
     # shapes
     assert L.ocs_quantize(A, 0, 4, 4, 8, A, 1.0, A, 64, A, A, ws, None) == -2
     assert L.ocs_quantize(A, 4, 8, 4, 8, A, 1.0, A, 64, A, A, ws, None) == -2      # ldx < cols

@@ -3,12 +3,13 @@ same seeded inputs.  Integer results (codes, split lists, accumulators) must mat
 bit; fp32 scales must be identical; dequantized outputs agree within 1e-6 relative."""
 import numpy as np
 import pytest
+import torch
 
 from oracle import ref
 from paper_1901_09504_amd import binding as B
 
 from gpu_util import (assert_y_close, gpu_conv_layer, gpu_mse_clip, gpu_qgemm, gpu_quantize, gpu_select, gpu_split_act,
-                      gpu_split_weights, gpu_split_weights_qa, require_gpu)
+                      gpu_split_weights, gpu_split_weights_qa, dev, host, require_gpu)
 
 pytestmark = pytest.mark.gpu
 
@@ -369,3 +370,80 @@ def test_qconv_equals_the_lowered_gemm_path():
     xq, sx = gpu_split_act(X, Cn, 9, got["chan_src"], None, s, 8, threshold=4.0)
     acc, Y = gpu_qgemm(xq, got["Wq"], (Cn + s) * 9, sx, got["sw"])
     assert np.array_equal(got["acc"], acc) and np.array_equal(got["Y"], Y)
+
+
+# ---- output handed to the next layer as codes ----------------------------------------------------
+
+def _next_layer_list(rng, N, s_next):
+    nxt = ref.split_weights(rng.standard_normal((5, N)).astype(np.float32), N, 1, s_next)
+    return nxt["chan_src"]
+
+
+@pytest.mark.parametrize("tile", [-1, 0, 2, 6, 7, 9, 11, 12, 14, 16, 17, 18, 19])
+@pytest.mark.parametrize("M,N,K,s_next,relu", [(1, 1, 1, 0, False), (130, 70, 64, 9, True), (257, 129, 200, 0, False),
+                                               (300, 520, 2358, 26, True), (700, 300, 269, 15, False)])
+def test_qgemm_requant(tile, M, N, K, s_next, relu):
+    rng = np.random.default_rng(M + N + K + s_next)
+    ld = B.ocs_padded_cols(K)
+    Xq = np.zeros((M, ld), dtype=np.int8)
+    Wq = np.zeros((N, ld), dtype=np.int8)
+    Xq[:, :K] = rng.integers(-127, 128, (M, K))
+    Wq[:, :K] = rng.integers(-31, 32, (N, K))
+    sx = np.array([3.0, 3.0 / 127], dtype=np.float32)
+    sw = np.array([0.7, 0.7 / 31], dtype=np.float32)
+    acc_ref, y_ref = ref.qgemm(Xq, Wq, K, sx[1], sw[1])
+    T = float(np.float32(0.5 * np.abs(y_ref).max())) if np.abs(y_ref).max() > 0 else 1.0
+    cs = _next_layer_list(rng, N, s_next) if s_next else None
+    ldy = B.ocs_padded_channels(N + s_next) + 16
+    q_ref, sc_ref = ref.requantize(acc_ref, sx[1], sw[1], T, 5, cs, s_next, relu=relu, ldq=ldy)
+    Yq = torch.zeros((M, ldy), dtype=torch.int8, device="cuda")
+    Yq[:, :N + s_next] = 77
+    acc = torch.full((M, N), -9, dtype=torch.int32, device="cuda")
+    sc = torch.zeros(2, dtype=torch.float32, device="cuda")
+    thr = torch.tensor([T], dtype=torch.float32, device="cuda")
+    B.ocs_tune("gemm_tile", tile)
+    try:
+        B.ocs_qgemm_requant(dev(Xq), ld, dev(Wq), ld, M, N, K, 8, 6, dev(sx), dev(sw), relu, thr, 5,
+                            None if cs is None else dev(cs), s_next, Yq, ldy, sc, acc, N)
+    finally:
+        B.ocs_tune("gemm_tile", -1)
+    assert np.array_equal(host(acc), acc_ref)
+    assert np.array_equal(host(sc), sc_ref)
+    assert np.array_equal(host(Yq), q_ref)
+
+
+@pytest.mark.parametrize("tile", [-1, 6, 10])
+def test_conv_chain_with_codes_between_the_layers(tile):
+    # 3x3 convolution -> ReLU -> codes -> 1x1 layer (a GEMM on those codes), against the oracle
+    rng = np.random.default_rng(17 + tile)
+    Bn, H, W, C1, N1, N2, s1, s2 = 2, 9, 8, 24, 40, 36, 3, 4
+    A = _tensor(rng, Bn * H * W, C1, "heavy").reshape(Bn, H, W, C1)
+    W1 = _tensor(rng, N1, C1 * 9, "heavy")
+    W2 = _tensor(rng, N2, N1, "heavy")
+    # oracle: layer 1
+    first = _conv_reference(A, W1, C1, 3, 3, 1, 1, s1, 8, 6, None)
+    sp2 = ref.split_weights(W2, N1, 1, s2)
+    ld2 = B.ocs_padded_cols(N1 + s2)
+    W2q, sw2 = ref.quantize(sp2["T_out"], 6, ldq=ld2)
+    T2 = float(np.float32(0.4) * np.float32(np.abs(first["Y"]).max()))
+    X2q, sx2 = ref.requantize(first["acc"], first["sx"][1], first["sw"][1], T2, 8, sp2["chan_src"], s2, relu=True, ldq=ld2)
+    acc2_ref, y2_ref = ref.qgemm(X2q, W2q, N1 + s2, sx2[1], sw2[1])
+    # GPU: layer 1 with the re-quantizing epilogue, layer 2 a plain GEMM on its codes
+    g1 = gpu_conv_layer(A, W1, C1, 3, 3, 1, 1, s1, bits_x=8, bits_w=6)
+    w2 = gpu_split_weights(W2, N1, 1, s2, bits=6, want_f32=False)
+    assert np.array_equal(w2["Wq"], W2q) and np.array_equal(w2["chan_src"], sp2["chan_src"])
+    M = Bn * H * W
+    Yq = torch.zeros((M, ld2), dtype=torch.int8, device="cuda")
+    sc2 = torch.zeros(2, dtype=torch.float32, device="cuda")
+    thr = torch.tensor([T2], dtype=torch.float32, device="cuda")
+    Wt = dev(g1["Wt"])
+    B.ocs_tune("gemm_tile", tile)
+    try:
+        B.ocs_qconv_requant(dev(g1["Aq"]), g1["ldc"], Bn, H, W, C1 + s1, 3, 3, 1, 1, Wt, N1, 8, 6, dev(g1["sx"]),
+                            dev(g1["sw"]), True, thr, 8, dev(sp2["chan_src"]), s2, Yq, ld2, sc2)
+    finally:
+        B.ocs_tune("gemm_tile", -1)
+    assert np.array_equal(host(sc2), sx2) and np.array_equal(host(Yq), X2q)
+    acc2, Y2 = gpu_qgemm(host(Yq), w2["Wq"], N1 + s2, host(sc2), w2["scale"], bits_w=6)
+    assert np.array_equal(acc2, acc2_ref)
+    assert_y_close(Y2, y2_ref)
