@@ -232,71 +232,116 @@ __device__ __forceinline__ unsigned out_code(int a, float scale, int relu, float
     return __float_as_uint(p + 12582912.0f) & 0xFFu;   // round half to even; low byte = code
 }
 
-// ROWS x WN accumulators of one wave, staged row-major in its piece of LDS, go out to memory:
-// lane (row, four consecutive columns) per 16-byte LDS read.  rbase / cbase: global row and
-// column of the staged block's corner.
+// Copies the next layer wants of this workgroup's output columns: entries (j << 8 | column
+// inside the workgroup's BN columns) for every appended column N + j whose source lies in
+// [col0, col0 + BN).  Built once per workgroup (a handful of entries: a few percent of BN).
+constexpr int kDupCap = 2048;
+template <int NT>
+__device__ __forceinline__ void build_dup_list(const Requant& rq, int N, int col0, int BN_, int* list,
+                                               int* count) {
+    if (rq.Yq == nullptr || rq.s_next <= 0) return;   // uniform over the grid
+    if (threadIdx.x == 0) *count = 0;
+    __syncthreads();
+    for (int t = threadIdx.x; t < rq.s_next; t += NT) {
+        int src = rq.chan_src[N + t];
+        src = src < 0 ? 0 : (src >= N ? N - 1 : src);
+        const int local = src - col0;
+        if (local >= 0 && local < BN_) {
+            const int k = atomicAdd(count, 1);
+            if (k < kDupCap) list[k] = (t << 8) | local;
+        }
+    }
+    __syncthreads();
+}
+
+// ROWS x WN accumulators of one wave, staged row-major in its piece of LDS, go out to memory.
+// rbase / cbase: global row and column of the staged block's corner; wcol: its first column
+// inside the workgroup's tile.  fp32 (and the optional int32 dump): lane = (row, four
+// consecutive columns), 16-byte stores.  Codes: lane = (row, sixteen consecutive columns),
+// again 16-byte stores.
 template <int ROWS, int WN>
 __device__ __forceinline__ void emit_staged_rows(const int32_t* stage, int lane, int rbase, int cbase,
-                                                 int M, int N, float scale, float* __restrict__ Y,
-                                                 int64_t ldy, int32_t* __restrict__ acc_out,
-                                                 int64_t ldacc, bool vec_y, bool vec_a,
-                                                 const Requant& rq, float inv) {
+                                                 int wcol, int M, int N, float scale,
+                                                 float* __restrict__ Y, int64_t ldy,
+                                                 int32_t* __restrict__ acc_out, int64_t ldacc,
+                                                 bool vec_y, bool vec_a, const Requant& rq, float inv,
+                                                 const int* dup_list, int dup_n) {
     constexpr int LPR = WN / 4;            // lanes per row (8, 16 or 32)
     constexpr int SLOTS = ROWS * LPR;      // 16-byte reads of the block
+    static_assert(SLOTS % 64 == 0, "whole waves of slots");
+    if (rq.Yq == nullptr || acc_out != nullptr) {
 #pragma unroll
-    for (int it = 0; it < (SLOTS + 63) / 64; ++it) {
-        const int idx = it * 64 + lane;
-        if (SLOTS % 64 != 0 && idx >= SLOTS) break;
-        const int rr = idx / LPR, cc = (idx % LPR) * 4;
-        const i32x4 a = *reinterpret_cast<const i32x4*>(&stage[rr * WN + cc]);
-        const int r = rbase + rr, c = cbase + cc;
-        if (r >= M || c >= N) continue;
-        if (rq.Yq != nullptr) {
-            int8_t* qp = rq.Yq + (int64_t)r * rq.ldyq + c;
-            unsigned q[4];
+        for (int it = 0; it < SLOTS / 64; ++it) {
+            const int idx = it * 64 + lane;
+            const int rr = idx / LPR, cc = (idx % LPR) * 4;
+            const i32x4 a = *reinterpret_cast<const i32x4*>(&stage[rr * WN + cc]);
+            const int r = rbase + rr, c = cbase + cc;
+            if (r >= M || c >= N) continue;
+            if (rq.Yq == nullptr) {
+                float* yp = Y + (int64_t)r * ldy + c;
+                if (vec_y && c + 3 < N) {
+                    f32x4 y;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) q[e] = out_code(a[e], scale, rq.relu, inv, rq.qmax);
-            if (c + 3 < N) {
-                *reinterpret_cast<unsigned*>(qp) = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
-            } else {
+                    for (int e = 0; e < 4; ++e) y[e] = (float)a[e] * scale;
+                    *reinterpret_cast<f32x4*>(yp) = y;
+                } else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (c + e < N) qp[e] = (int8_t)q[e];
+                    for (int e = 0; e < 4; ++e)
+                        if (c + e < N) yp[e] = (float)a[e] * scale;
+                }
             }
-        } else {
-            float* yp = Y + (int64_t)r * ldy + c;
-            if (vec_y && c + 3 < N) {
-                f32x4 y;
+            if (acc_out) {
+                int32_t* ap = acc_out + (int64_t)r * ldacc + c;
+                if (vec_a && c + 3 < N) {
+                    *reinterpret_cast<i32x4*>(ap) = a;
+                } else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) y[e] = (float)a[e] * scale;
-                *reinterpret_cast<f32x4*>(yp) = y;
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (c + e < N) yp[e] = (float)a[e] * scale;
-            }
-        }
-        if (acc_out) {
-            int32_t* ap = acc_out + (int64_t)r * ldacc + c;
-            if (vec_a && c + 3 < N) {
-                *reinterpret_cast<i32x4*>(ap) = a;
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (c + e < N) ap[e] = a[e];
+                    for (int e = 0; e < 4; ++e)
+                        if (c + e < N) ap[e] = a[e];
+                }
             }
         }
     }
-    // copies for the channels the next layer splits: appended column N + j repeats column
-    // chan_src[N + j]; the wave that holds that column writes it, one lane per staged row
-    if (rq.Yq != nullptr && rq.s_next > 0 && lane < ROWS) {
+    if (rq.Yq == nullptr) return;
+
+    constexpr int LPR16 = WN / 16;         // lanes per row, sixteen columns each (2, 4 or 8)
+    constexpr int SLOTS16 = ROWS * LPR16;
+#pragma unroll
+    for (int it = 0; it < (SLOTS16 + 63) / 64; ++it) {
+        const int idx = it * 64 + lane;
+        if (idx >= SLOTS16) break;
+        const int rr = idx / LPR16, cc = (idx % LPR16) * 16;
+        const int r = rbase + rr, c = cbase + cc;
+        unsigned w[4];
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+            const i32x4 a = *reinterpret_cast<const i32x4*>(&stage[rr * WN + cc + 4 * g4]);
+            w[g4] = out_code(a[0], scale, rq.relu, inv, rq.qmax) |
+                    (out_code(a[1], scale, rq.relu, inv, rq.qmax) << 8) |
+                    (out_code(a[2], scale, rq.relu, inv, rq.qmax) << 16) |
+                    (out_code(a[3], scale, rq.relu, inv, rq.qmax) << 24);
+        }
+        if (r >= M || c >= N) continue;
+        int8_t* qp = rq.Yq + (int64_t)r * rq.ldyq + c;      // 16-byte aligned: ldyq % 16 == 0, c % 16 == 0
+        if (c + 15 < N) {
+            i32x4 v;
+            v[0] = (int)w[0]; v[1] = (int)w[1]; v[2] = (int)w[2]; v[3] = (int)w[3];
+            *reinterpret_cast<i32x4*>(qp) = v;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                if (c + e < N) qp[e] = (int8_t)((w[e >> 2] >> (8 * (e & 3))) & 0xFFu);
+        }
+    }
+    // copies for the channels the next layer splits: the wave that holds the source column
+    // writes appended column N + j, one lane per staged row
+    if (dup_n > 0 && lane < ROWS) {
         const int r = rbase + lane;
-        for (int j = 0; j < rq.s_next; ++j) {
-            int src = rq.chan_src[N + j];
-            src = src < 0 ? 0 : (src >= N ? N - 1 : src);
-            const int local = src - cbase;
+        for (int k = 0; k < dup_n; ++k) {
+            const int e = dup_list[k];
+            const int local = (e & 0xFF) - wcol;
             if (local >= 0 && local < WN && r < M)
-                rq.Yq[(int64_t)r * rq.ldyq + N + j] =
+                rq.Yq[(int64_t)r * rq.ldyq + N + (e >> 8)] =
                     (int8_t)out_code(stage[lane * WN + local], scale, rq.relu, inv, rq.qmax);
         }
     }
@@ -349,6 +394,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
     // one array: the A ring, then the B ring; the epilogue reuses all of it
     constexpr int RING_BYTES = NBUF * (BM + BN) * BK;
     __shared__ __align__(1024) int8_t lds[RING_BYTES];
+    __shared__ int dup_list[kDupCap];
+    __shared__ int dup_count;
     int8_t (*lds_a)[BM * BK] = reinterpret_cast<int8_t (*)[BM * BK]>(&lds[0]);
     int8_t (*lds_b)[BN * BK] = reinterpret_cast<int8_t (*)[BN * BK]>(&lds[NBUF * BM * BK]);
 
@@ -523,6 +570,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
 
 #pragma unroll
     for (int p = 0; p < NBUF - 1; ++p) fetch(p, p);
+    build_dup_list<NT>(rq, N, col0, BN, dup_list, &dup_count);   // behind the first requests
     wait_vmcnt<(NBUF - 2) * LPS>();
     __syncthreads();
     read_slice(0, 0, af[0], bf[0]);
@@ -551,6 +599,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
     int32_t* stage = reinterpret_cast<int32_t*>(&lds[wave * WAVE_STAGE]);
     const float scale = scale_x[1] * scale_w[1];
     const float inv = requant_inv(rq, blockIdx.x == 0 && tid == 0);
+    const int dup_n = (rq.Yq != nullptr && rq.s_next > 0) ? (dup_count < kDupCap ? dup_count : kDupCap) : 0;
     const bool vec_y = (reinterpret_cast<uintptr_t>(Y) % 16 == 0) && (ldy % 4 == 0);
     const bool vec_a = acc_out != nullptr && (reinterpret_cast<uintptr_t>(acc_out) % 16 == 0) &&
                        (ldacc % 4 == 0);
@@ -564,8 +613,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
                     acc[i][j][v];
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        emit_staged_rows<32, WN>(stage, lane, row0 + wm * WM + i * 32, col0 + wn * WN, M, N, scale, Y,
-                                 ldy, acc_out, ldacc, vec_y, vec_a, rq, inv);
+        emit_staged_rows<32, WN>(stage, lane, row0 + wm * WM + i * 32, col0 + wn * WN, wn * WN, M, N,
+                                 scale, Y, ldy, acc_out, ldacc, vec_y, vec_a, rq, inv, dup_list, dup_n);
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         __builtin_amdgcn_wave_barrier();   // the reads are issued before the next block's writes
     }
@@ -609,6 +658,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_wholek_kernel(
     static_assert(WM % 32 == 0 && WN % 32 == 0 && TM >= 1 && TN >= 1, "wave tile of 32x32 blocks");
 
     extern __shared__ __align__(1024) int8_t dlds[];
+    __shared__ int dup_list[kDupCap];
+    __shared__ int dup_count;
 #if defined(__HIP_DEVICE_COMPILE__)
     typedef __attribute__((address_space(3))) int8_t* lptr_t;
     const unsigned lds0 = (unsigned)(uintptr_t)(lptr_t)&dlds[0];
@@ -648,6 +699,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_wholek_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
+    build_dup_list<NW * 64>(rq, N, col0, BN, dup_list, &dup_count);   // behind the requests
     wait_vmcnt<0>();
     __syncthreads();
 
@@ -683,6 +735,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_wholek_kernel(
     int32_t* stage = reinterpret_cast<int32_t*>(&dlds[wave * (8 * WN * 4)]);
     const float scale = scale_x[1] * scale_w[1];
     const float inv = requant_inv(rq, blockIdx.x == 0 && tid == 0);
+    const int dup_n = (rq.Yq != nullptr && rq.s_next > 0) ? (dup_count < kDupCap ? dup_count : kDupCap) : 0;
     const bool vec_y = (reinterpret_cast<uintptr_t>(Y) % 16 == 0) && (ldy % 4 == 0);
     const bool vec_a = acc_out != nullptr && (reinterpret_cast<uintptr_t>(acc_out) % 16 == 0) &&
                        (ldacc % 4 == 0);
@@ -697,15 +750,16 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_wholek_kernel(
                     stage[((lane >> 5) * 4 + e) * WN + j * 32 + (lane & 31)] = acc[i][j][q * 4 + e];
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
-            emit_staged_rows<8, WN>(stage, lane, row0 + wm * WM + i * 32 + q * 8, col0 + wn * WN, M, N,
-                                    scale, Y, ldy, acc_out, ldacc, vec_y, vec_a, rq, inv);
+            emit_staged_rows<8, WN>(stage, lane, row0 + wm * WM + i * 32 + q * 8, col0 + wn * WN, wn * WN,
+                                    M, N, scale, Y, ldy, acc_out, ldacc, vec_y, vec_a, rq, inv, dup_list,
+                                    dup_n);
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             __builtin_amdgcn_wave_barrier();
         }
     }
 }
 
-constexpr int64_t kWholeKMaxLds = 160 * 1024;  // LDS of one CU
+constexpr int64_t kWholeKMaxLds = 150 * 1024;  // LDS of one CU less the static tables
 
 template <int BM, int BN, int WAVES_M, int WAVES_N>
 static int64_t wholek_lds_bytes(int64_t Kpad) {
