@@ -476,6 +476,41 @@ int ref_requantize(const int32_t *acc, int64_t ldacc, int64_t M, int64_t N, floa
 }
 
 /*
+ * The expanded layer of Eq. 3 run without expanding it.  In Eq. 2 on codes, a duplicated
+ * activation channel multiplies each of its weight copies by the same activation code, so
+ *   sum_j Xq[i, src(j)] * Wq[n, j]  =  sum_c Xq[i, c] * (sum over the copies j of c of Wq[n, j]):
+ * the integer accumulator of the expanded layer equals that of an un-expanded layer whose
+ * weight code for channel c is the SUM of the codes of c's copies.  The sum needs more range
+ * than one copy (up to copies * qmax), which int8 has to spare whenever the weights use fewer
+ * than 8 bits.  Wf[n, c*g + t] = sum_{j: chan_src[j] == c} Wq[n, j*g + t]; columns C*g .. ldf-1
+ * zero; *max_abs = the largest |sum|.  Sums beyond +-127 are stored saturated and make the
+ * result unusable: the caller checks *max_abs <= 127.
+ */
+int ref_fold_weights(const int8_t *Wq, int64_t ldq, int64_t N, int C, int g, int s,
+                     const int32_t *chan_src, int8_t *Wf, int64_t ldf, int32_t *max_abs) {
+    if (!Wq || !Wf || !max_abs || N <= 0 || C <= 0 || g <= 0 || s < 0) return REF_E_ARG;
+    if (s > 0 && !chan_src) return REF_E_ARG;
+    if (ldq < (int64_t)(C + s) * g || ldf < (int64_t)C * g) return REF_E_ARG;
+    int32_t worst = 0;
+    for (int64_t n = 0; n < N; ++n) {
+        for (int c = 0; c < C; ++c)
+            for (int t = 0; t < g; ++t) {
+                int32_t sum = 0;
+                for (int j = 0; j < C + s; ++j) {
+                    int src = chan_src ? chan_src[j] : j;
+                    if (src == c) sum += Wq[n * ldq + (int64_t)j * g + t];
+                }
+                int32_t a = sum < 0 ? -sum : sum;
+                if (a > worst) worst = a;
+                Wf[n * ldf + (int64_t)c * g + t] = (int8_t)(sum > 127 ? 127 : (sum < -127 ? -127 : sum));
+            }
+        for (int64_t k = (int64_t)C * g; k < ldf; ++k) Wf[n * ldf + k] = 0;
+    }
+    *max_abs = worst;
+    return REF_OK;
+}
+
+/*
  * Eq. 2 itself on real-valued operands, in fp64: Y[i,n] = sum_k X[i,k] * W[n,k].
  * Used to state the functional identity of Eq. 3 / Eq. 4 (split layer == unsplit layer).
  */

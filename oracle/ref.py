@@ -222,6 +222,22 @@ def requantize(acc, step_x, step_w, T_next, bits_next, chan_src_next=None, s_nex
     return q, sc
 
 
+def fold_weights(Wq, Cn, g, s, chan_src, ldf=None):
+    """Weight codes of the expanded layer folded back onto the C original channels.
+    Returns (Wf [N, ldf] int8, largest |folded code|)."""
+    Wq = np.ascontiguousarray(Wq, dtype=np.int8)
+    N, ldq = Wq.shape
+    ldf = Cn * g if ldf is None else int(ldf)
+    Wf = np.full((N, ldf), 99, dtype=np.int8)
+    mx = np.zeros(1, dtype=np.int32)
+    cs = None if chan_src is None else np.ascontiguousarray(chan_src, dtype=np.int32)
+    rc = lib().ref_fold_weights(_p(Wq, C.c_int8), C.c_int64(ldq), C.c_int64(N), C.c_int(Cn), C.c_int(g),
+                                C.c_int(s), _p(cs, C.c_int32), _p(Wf, C.c_int8), C.c_int64(ldf),
+                                _p(mx, C.c_int32))
+    _check(rc, "ref_fold_weights")
+    return Wf, int(mx[0])
+
+
 def layer_f64(X, W):
     """Eq. 2 on real operands in fp64: Y = X @ W.T."""
     X = np.ascontiguousarray(X, dtype=np.float32)

@@ -590,3 +590,44 @@ def test_requantized_output_is_the_next_layers_split_act(relu):
         assert got.min() == 0
     plain, _ = ref.requantize(acc, sx, sw, T, 6, relu=relu)
     assert np.array_equal(plain, expect[:, :N])
+
+
+# ---- the expanded layer run un-expanded: folded weight codes -----------------------------------
+
+@pytest.mark.parametrize("qa", [False, True])
+def test_folded_weights_give_the_expanded_layers_accumulators(qa):
+    # Eq. 3 on codes, both ways, with a library integer matmul: duplicated activation codes times
+    # expanded weight codes == original activation codes times folded weight codes
+    rng = np.random.default_rng(61 + qa)
+    M, C, g, N, s = 17, 20, 3, 9, 6
+    X, W = _rand_layer(rng, M, C, g, N)
+    W[3, 5 * g + 1] = 3.0                                     # outliers, so that channels are re-split
+    W[1, 11 * g] = -2.0
+    if qa:
+        w = ref.split_weights_qa(W, C, g, s, 5)
+        Wq, chan_src = w["q"], w["chan_src"]
+    else:
+        sp = ref.split_weights(W, C, g, s)
+        Wq, _ = ref.quantize(sp["T_out"], 5)
+        chan_src = sp["chan_src"]
+    assert np.bincount(chan_src, minlength=C).max() >= 3     # some channel has three copies or more
+    Wf, worst = ref.fold_weights(Wq, C, g, s, chan_src, ldf=64)
+    assert worst <= 127 and not Wf[:, C * g:].any()
+    Xq, _ = ref.quantize(X, 8)
+    expanded = Xq[:, _expand_cols(chan_src, g)].astype(np.int64) @ Wq[:, :(C + s) * g].astype(np.int64).T
+    folded = Xq.astype(np.int64) @ Wf[:, :C * g].astype(np.int64).T
+    assert np.array_equal(expanded, folded)
+    # channels that were never split keep their codes; a split channel's folded code is the sum
+    once = np.flatnonzero(np.bincount(chan_src, minlength=C) == 1)
+    assert np.array_equal(Wf[:, _expand_cols(once, g)], Wq[:, _expand_cols(once, g)])
+
+
+def test_folding_reports_codes_that_do_not_fit():
+    # 8-bit weights leave no headroom: the two halves of the outlier channel both sit at +-127
+    W = np.array([[4.0, 1.0, -0.5], [0.25, -2.0, 0.125]], dtype=np.float32)
+    sp = ref.split_weights(W, 3, 1, 1)
+    Wq, _ = ref.quantize(sp["T_out"], 8)
+    Wf, worst = ref.fold_weights(Wq, 3, 1, 1, sp["chan_src"])
+    assert worst == 254 and Wf[0, 0] == 127
+    Wq7, _ = ref.quantize(sp["T_out"], 7)
+    assert ref.fold_weights(Wq7, 3, 1, 1, sp["chan_src"])[1] == 126
