@@ -290,6 +290,25 @@ int ocs_qconv_requant(const int8_t *Aq, int64_t ldc, int B, int H, int W, int C_
                       int32_t *acc_out, int64_t ldacc, void *stream);
 
 /*
+ * The expanded layer of Eq. 3 run WITHOUT expanding it (off-line preparation).  In Eq. 2 on
+ * codes a duplicated activation channel multiplies each of its weight copies by the same
+ * activation code, so the expanded layer's int32 accumulator equals that of an un-expanded layer
+ * whose weight code for channel c is the sum of the codes of c's copies:
+ *   Wf[n, c*g + t] = sum over j with chan_src[j] == c of Wq[n, j*g + t],   c < C.
+ * Wq [N, ldq]: the expanded weight codes (ocs_split_weights or ocs_split_weights_qa) with their
+ * chan_src [C + num_splits].  Wf [N, ldf] int8, ldf >= C*g, pad columns zero.
+ * max_abs_out device int32: the largest |sum|.  The sums fit int8 whenever (copies of a channel)
+ * * qmax_w <= 127, which holds for every weight width below 8 bits at the paper's expansion
+ * ratios; a sum beyond +-127 is stored saturated and makes Wf unusable, so check *max_abs_out
+ * <= 127 once.  With Wf the layer is ocs_quantize (or ocs_split_act with num_splits = 0) on the
+ * un-expanded activations and ocs_qgemm with Kexp = C*g and the same scale_w: accumulators and
+ * outputs are bit-identical to the expanded layer's, with no duplicated channels anywhere.
+ */
+int ocs_fold_weights(const int8_t *Wq, int64_t ldq, int64_t N, int C, int g, int num_splits,
+                     const int32_t *chan_src, int8_t *Wf, int64_t ldf, int32_t *max_abs_out,
+                     void *stream);
+
+/*
  * Measurement helper (no passage of the paper).  Arms a pair of caller-created hipEvent_t
  * (created with timing enabled) for the calling thread's NEXT launch of one kernel family:
  * OCS_TIME_SPLIT_QUANTIZE (the streaming pass of ocs_split_act / ocs_quantize /

@@ -73,6 +73,8 @@ def lib():
     L.ocs_qconv_requant.restype = _i32
     L.ocs_qconv_requant.argtypes = [_vp, _i64, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _i64, _i32,
                                     _i32, _vp, _vp, _i32, _vp, _i32, _vp, _i32, _vp, _i64, _vp, _vp, _i64, _vp]
+    L.ocs_fold_weights.restype = _i32
+    L.ocs_fold_weights.argtypes = [_vp, _i64, _i64, _i32, _i32, _i32, _vp, _vp, _i64, _vp, _vp]
     L.ocs_quantize.restype = _i32
     L.ocs_quantize.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _f32, _vp, _i64, _vp, _vp, _sz, _vp]
     L.ocs_split_act.restype = _i32
@@ -223,6 +225,11 @@ def ocs_qconv_requant(Aq, ldc, Bn, H, W, C_exp, kh, kw, stride, pad, Wt, N, bits
                                    _ptr(next_threshold), next_bits, _ptr(next_chan_src), next_splits,
                                    _ptr(Yq), ldyq, _ptr(next_scale_out), _ptr(acc_out), ldacc,
                                    _stream(stream)), "ocs_qconv_requant")
+
+
+def ocs_fold_weights(Wq, ldq, N, Cn, g, num_splits, chan_src, Wf, ldf, max_abs_out, stream=None):
+    _check(lib().ocs_fold_weights(_ptr(Wq), ldq, N, Cn, g, num_splits, _ptr(chan_src), _ptr(Wf), ldf,
+                                  _ptr(max_abs_out), _stream(stream)), "ocs_fold_weights")
 
 
 def ocs_quantize(x, rows, cols, ldx, bits, threshold, clip_ratio, q, ldq, scale_out, workspace,

@@ -490,6 +490,21 @@ int ocs_qconv_requant(const int8_t* Aq, int64_t ldc, int B, int H, int W, int C_
     return OCS_OK;
 }
 
+int ocs_fold_weights(const int8_t* Wq, int64_t ldq, int64_t N, int C, int g, int num_splits,
+                     const int32_t* chan_src, int8_t* Wf, int64_t ldf, int32_t* max_abs_out,
+                     void* stream) {
+    if (!Wq || !Wf || !max_abs_out || (num_splits > 0 && !chan_src)) return OCS_E_NULL;
+    int rc = check_layer(N, C, g, ldf, num_splits);
+    if (rc) return rc;
+    if (ldq < (int64_t)(C + num_splits) * g) return OCS_E_SHAPE;
+    rc = check_codes(Wf, ldf, (int64_t)C * g);
+    if (rc) return rc;
+    hipError_t e = launch_fold_weights(Wq, ldq, N, C, g, num_splits, chan_src, Wf, ldf, max_abs_out,
+                                       static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
 int ocs_time_next(int family, void* start_event, void* stop_event) {
     if (family != kTimeSplitQuantize && family != kTimeGemm && family != kTimeAbsmax) return OCS_E_MODE;
     if (!start_event || !stop_event) return OCS_E_NULL;

@@ -117,6 +117,12 @@ struct Requant {
     float* scale_out = nullptr;      // device float[2] = {T, T/qmax} (may be NULL)
 };
 
+// Weight codes of the expanded layer folded onto the C original channels (sum over a channel's
+// copies, saturated to +-127); *max_abs = largest |sum|.
+hipError_t launch_fold_weights(const int8_t* Wq, int64_t ldq, int64_t N, int C, int g, int s,
+                               const int32_t* chan_src, int8_t* Wf, int64_t ldf, int32_t* max_abs,
+                               hipStream_t stream);
+
 // int8 x int8 -> int32 MFMA GEMM over Kpad (multiple of 64) with dequantizing epilogue.
 hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
                         int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,

@@ -105,4 +105,50 @@ hipError_t launch_expand_quantize_qa(const float* W, int64_t ldw, int64_t N, int
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// The expanded layer of Eq. 3 run without expanding it.  A duplicated activation channel
+// multiplies each of its weight copies by the same activation code, so the accumulator of the
+// expanded layer equals that of an un-expanded layer whose weight code for channel c is the sum
+// of the codes of c's copies.  int8 has room for that sum whenever copies * qmax <= 127, i.e.
+// for every weight width below 8 bits at the split counts the paper uses.  Off-line, small.
+// ---------------------------------------------------------------------------------------------
+__global__ void fold_init_kernel(int32_t* max_abs) { *max_abs = 0; }
+
+__global__ __launch_bounds__(kThreads) void fold_weights_kernel(
+    const int8_t* __restrict__ Wq, int64_t ldq, int64_t N, int C, int g, int s,
+    const int32_t* __restrict__ chan_src, int8_t* __restrict__ Wf, int64_t ldf,
+    int32_t* __restrict__ max_abs) {
+    const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    int worst = 0;
+    if (o < N * ldf) {
+        const int64_t n = o / ldf;
+        const int k = (int)(o - n * ldf);
+        int sum = 0;
+        if (k < C * g) {
+            const int c = k / g, t = k - c * g;
+            sum = Wq[n * ldq + k];                       // the channel's own slot
+            for (int j = C; j < C + s; ++j) {
+                int src = chan_src[j];
+                src = src < 0 ? 0 : (src >= C ? C - 1 : src);
+                if (src == c) sum += Wq[n * ldq + (int64_t)j * g + t];
+            }
+        }
+        worst = sum < 0 ? -sum : sum;
+        Wf[o] = (int8_t)(sum > 127 ? 127 : (sum < -127 ? -127 : sum));
+    }
+    const unsigned w = wave_umax32((unsigned)worst);
+    if ((threadIdx.x & 63) == 0 && w != 0u) atomicMax(max_abs, (int)w);
+}
+
+hipError_t launch_fold_weights(const int8_t* Wq, int64_t ldq, int64_t N, int C, int g, int s,
+                               const int32_t* chan_src, int8_t* Wf, int64_t ldf, int32_t* max_abs,
+                               hipStream_t stream) {
+    fold_init_kernel<<<1, 1, 0, stream>>>(max_abs);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    fold_weights_kernel<<<dim3((unsigned)ceil_div(N * ldf, kThreads)), kThreads, 0, stream>>>(
+        Wq, ldq, N, C, g, s, chan_src, Wf, ldf, max_abs);
+    return hipGetLastError();
+}
+
 }  // namespace ocs

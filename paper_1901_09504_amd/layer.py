@@ -70,6 +70,32 @@ class ExpandedLayer:
                             0 if W_out is None else W_out.stride(0), self.wmax, self.bits_w, clip,
                             self.Wq, self.ldq, self.scale_w, self.ws_w, stream)
 
+    def fold_weights(self, stream=None):
+        """After prepare_weights: fold the expanded weight codes back onto the C original channels
+        (sum over a channel's copies).  Returns a device int32 holding the largest |folded code|;
+        the folded path is valid when it is <= 127 (any weight width below 8 bits, in practice)."""
+        self.ldf = B.ocs_padded_cols(self.K)
+        if getattr(self, "Wf", None) is None:
+            self.Wf = torch.empty((self.N, self.ldf), dtype=torch.int8, device=self.device)
+            self.fold_max = torch.zeros(1, dtype=torch.int32, device=self.device)
+        B.ocs_fold_weights(self.Wq, self.ldq, self.N, self.C, self.g, self.s, self.chan_src, self.Wf,
+                           self.ldf, self.fold_max, stream)
+        return self.fold_max
+
+    def forward_folded(self, X, threshold=None, acc_out=None, stream=None):
+        """The same outputs as forward(), bit for bit, with no expansion at run time: plain
+        quantization of X and a GEMM over the original K against the folded weight codes."""
+        M = X.shape[0]
+        self._ensure_rows(M)
+        if getattr(self, "Xf", None) is None or self.Xf.shape[0] < M:
+            self.Xf = torch.empty((M, self.ldf), dtype=torch.int8, device=self.device)
+        B.ocs_quantize(X, M, self.K, X.stride(0), self.bits_x, threshold, self.clip_ratio_x, self.Xf,
+                       self.ldf, self.scale_x, self.ws_x, stream)
+        B.ocs_qgemm(self.Xf, self.ldf, self.Wf, self.ldf, M, self.N, self.K, self.bits_x, 8,
+                    self.scale_x, self.scale_w, acc_out, 0 if acc_out is None else acc_out.stride(0),
+                    self.Y, self.N, None, stream)
+        return self.Y[:M]
+
     # ---- per batch --------------------------------------------------------------------------
     def split_act(self, X, threshold=None, stream=None):
         M = X.shape[0]

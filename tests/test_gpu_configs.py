@@ -256,3 +256,45 @@ def test_config2_as_convolution_full_size():
     assert_y_close(host(Y), y_ref)
     Y1 = Y.clone()
     assert torch.equal(Y1, L.forward(dev(A)))           # the timed configuration stores no accumulators
+
+
+# ---- the expanded layer run un-expanded: folded weight codes ------------------------------------
+
+@pytest.mark.parametrize("cfg", [3, 4, 5])
+def test_folded_layer_equals_expanded_layer(cfg):
+    layers = wl.config(cfg) if cfg != 5 else _unique(wl.config(5))[::3]
+    fitted = []
+    for layer in layers:
+        layer = wl.shrink(layer, 640)
+        W, X = wl.weights(layer), wl.activations(layer)
+        for qa in (False, True):
+            L = ExpandedLayer(layer.N, layer.C, layer.g, layer.r, layer.bits_w, layer.bits_x)
+            L.prepare_weights(dev(W), qa=qa)
+            worst = int(host(L.fold_weights())[0])
+            Wf_ref, worst_ref = ref.fold_weights(host(L.Wq), layer.C, layer.g, L.s, host(L.chan_src), ldf=L.ldf)
+            assert worst == worst_ref, (layer.name, worst, worst_ref)
+            assert np.array_equal(host(L.Wf), Wf_ref)
+            if worst > 127:
+                # a channel with so many copies that their codes do not add up inside int8 (the
+                # LSTM layer's dominant channel: 16 copies at 5 bits): folding is reported unusable
+                assert cfg == 4
+                continue
+            fitted.append(layer.name)
+            acc_e = torch.empty((layer.M, layer.N), dtype=torch.int32, device="cuda")
+            acc_f = torch.empty((layer.M, layer.N), dtype=torch.int32, device="cuda")
+            Xd = dev(X)
+            Y_e = L.forward(Xd, acc_out=acc_e).clone()
+            sx_e = host(L.scale_x).copy()
+            Y_f = L.forward_folded(Xd, acc_out=acc_f)
+            assert np.array_equal(host(L.scale_x), sx_e)
+            assert torch.equal(acc_e, acc_f) and torch.equal(Y_e, Y_f)
+    assert fitted or cfg == 4
+
+
+def test_folding_eight_bit_weights_is_reported_as_not_fitting():
+    (layer,) = wl.config(2)
+    L = ExpandedLayer(layer.N, layer.C, layer.g, layer.r, layer.bits_w, layer.bits_x)
+    L.prepare_weights(dev(wl.weights(layer)))
+    worst = int(host(L.fold_weights())[0])
+    _, worst_ref = ref.fold_weights(host(L.Wq), layer.C, layer.g, L.s, host(L.chan_src))
+    assert worst == worst_ref > 127
