@@ -34,7 +34,7 @@ METRIC = "expanded int8 GEMM TOPS (% MFMA peak); split+quantize GB/s (% HBM)"
 # copy kernel of known size launched after the timed region (profiles/x2_config2_hbm_traffic.md).
 # Valid only for the kernel source it was measured on: reported as null once that file changes.
 X2_TRAFFIC = {"quantize_hip_sha256": "f520f034aa2206f86738eacd4a015f848468ce147da612af42033f8200c60063",
-              "bytes_per_launch": 145722929}
+              "bytes_per_launch": 145747503}
 
 
 def x2_traffic():

@@ -269,7 +269,7 @@ int ocs_qconv(const int8_t *Aq, int64_t ldc, int B, int H, int W, int C_exp, int
  *   y = float(acc) * (scale_x[1] * scale_w[1]);  relu != 0: y = max(y, 0);
  *   code = clamp(rne(y * (qmax / T)), -qmax, qmax), T = *next_threshold (device float, the grid
  *   fixed from profiling as in Sec. 5), qmax = 2^(next_bits-1) - 1, arithmetic as in ocs_quantize.
- *   Yq[i, j] = code of output channel next_chan_src[j] for j < N + next_splits (next_chan_src
+ *   Yq[i, j] = code of output channel next_chan_src[j] for j < N + next_splits <= N + 512 (next_chan_src
  *   device int32 [N + next_splits] as the next layer's ocs_split_weights wrote it; its first N
  *   entries are the identity; NULL allowed when next_splits == 0).
  *   Yq [M, ldyq] int8, ldyq a multiple of OCS_CALIGN and >= N + next_splits.  Columns

@@ -406,8 +406,8 @@ static int check_requant(int N, const float* next_threshold, int next_bits,
                          const int32_t* next_chan_src, int next_splits, const int8_t* Yq,
                          int64_t ldyq, const float* next_scale_out) {
     if (!next_threshold || !Yq) return OCS_E_NULL;
-    // the kernels keep a workgroup's share of the copies in a table of 2048 entries
-    if (next_splits < 0 || next_splits > 2048 || (int64_t)N + next_splits > OCS_MAX_EXPANDED_CHANNELS)
+    // the kernels keep a workgroup's share of the copies in a table of 512 entries
+    if (next_splits < 0 || next_splits > 512 || (int64_t)N + next_splits > OCS_MAX_EXPANDED_CHANNELS)
         return OCS_E_SPLITS;
     if (next_splits > 0 && !next_chan_src) return OCS_E_NULL;
     if (ldyq < (int64_t)N + next_splits) return OCS_E_SHAPE;

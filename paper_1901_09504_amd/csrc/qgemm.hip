@@ -235,7 +235,7 @@ __device__ __forceinline__ unsigned out_code(int a, float scale, int relu, float
 // Copies the next layer wants of this workgroup's output columns: entries (j << 8 | column
 // inside the workgroup's BN columns) for every appended column N + j whose source lies in
 // [col0, col0 + BN).  Built once per workgroup (a handful of entries: a few percent of BN).
-constexpr int kDupCap = 2048;
+constexpr int kDupCap = 512;
 template <int NT>
 __device__ __forceinline__ void build_dup_list(const Requant& rq, int N, int col0, int BN_, int* list,
                                                int* count) {
@@ -759,7 +759,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_wholek_kernel(
     }
 }
 
-constexpr int64_t kWholeKMaxLds = 150 * 1024;  // LDS of one CU less the static tables
+constexpr int64_t kWholeKMaxLds = 156 * 1024;  // LDS of one CU less the static tables
 
 template <int BM, int BN, int WAVES_M, int WAVES_N>
 static int64_t wholek_lds_bytes(int64_t Kpad) {
