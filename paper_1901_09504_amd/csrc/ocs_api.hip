@@ -51,6 +51,42 @@ static int check_layer(int64_t rows, int C, int g, int64_t ld, int num_splits) {
     return OCS_OK;
 }
 
+// Operands of the GEMM: shapes, leading dimensions, alignment, and that the int32 accumulator
+// cannot overflow for these bit widths.
+static int check_gemm_operands(const void* Xq, int64_t ldx, const void* Wq, int64_t ldw, int64_t M,
+                               int64_t N, int64_t Kexp, int bits_x, int bits_w, const void* acc_out,
+                               int64_t ldacc) {
+    if (M <= 0 || N <= 0 || Kexp <= 0) return OCS_E_SHAPE;
+    if (M > (int64_t)1 << 30 || N > (int64_t)1 << 30 || Kexp > (int64_t)1 << 30) return OCS_E_SHAPE;
+    const int64_t Kpad = round_up(Kexp, OCS_KALIGN);
+    if (ldx < Kpad || ldw < Kpad || (acc_out && ldacc < N)) return OCS_E_SHAPE;
+    if (ldx % OCS_KALIGN != 0 || ldw % OCS_KALIGN != 0 || !aligned(Xq, 16) || !aligned(Wq, 16))
+        return OCS_E_ALIGN;
+    if (!bits_ok(bits_x) || !bits_ok(bits_w)) return OCS_E_BITS;
+    const int64_t qx = (1 << (bits_x - 1)) - 1, qw = (1 << (bits_w - 1)) - 1;
+    if (Kexp * qx * qw >= (int64_t)1 << 31) return OCS_E_OVERFLOW;
+    return OCS_OK;
+}
+
+// The same for the convolution whose lowering happens inside the kernel.
+static int check_conv_operands(const void* Aq, int64_t ldc, int B, int H, int W, int C_exp, int kh,
+                               int kw, int stride, int pad, const void* Wt, int64_t N, int bits_x,
+                               int bits_w, const void* acc_out, int64_t ldacc) {
+    if (B <= 0 || H <= 0 || W <= 0 || C_exp <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0 ||
+        N <= 0 || N > (int64_t)1 << 30)
+        return OCS_E_SHAPE;
+    if (H + 2 * pad < kh || W + 2 * pad < kw) return OCS_E_SHAPE;
+    const int64_t Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
+    if ((int64_t)B * Ho * Wo > (int64_t)1 << 30 || (int64_t)B * H * W > (int64_t)1 << 31) return OCS_E_SHAPE;
+    if (ldc < C_exp || (int64_t)kh * kw * ldc > (int64_t)1 << 30) return OCS_E_SHAPE;
+    if (acc_out && ldacc < N) return OCS_E_SHAPE;
+    if (ldc % OCS_CALIGN != 0 || !aligned(Aq, 16) || !aligned(Wt, 16)) return OCS_E_ALIGN;
+    if (!bits_ok(bits_x) || !bits_ok(bits_w)) return OCS_E_BITS;
+    const int64_t qx = (1 << (bits_x - 1)) - 1, qw = (1 << (bits_w - 1)) - 1;
+    if ((int64_t)kh * kw * C_exp * qx * qw >= (int64_t)1 << 31) return OCS_E_OVERFLOW;
+    return OCS_OK;
+}
+
 }  // namespace ocs
 
 using namespace ocs;
@@ -350,15 +386,10 @@ int ocs_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int6
     (void)workspace;
     (void)ws_bytes;
     if (!Xq || !Wq || !scale_x || !scale_w || !Y) return OCS_E_NULL;
-    if (M <= 0 || N <= 0 || Kexp <= 0) return OCS_E_SHAPE;
-    if (M > (int64_t)1 << 30 || N > (int64_t)1 << 30 || Kexp > (int64_t)1 << 30) return OCS_E_SHAPE;
+    int rc = check_gemm_operands(Xq, ldx, Wq, ldw, M, N, Kexp, bits_x, bits_w, acc_out, ldacc);
+    if (rc) return rc;
+    if (ldy < N) return OCS_E_SHAPE;
     const int64_t Kpad = round_up(Kexp, OCS_KALIGN);
-    if (ldx < Kpad || ldw < Kpad || ldy < N || (acc_out && ldacc < N)) return OCS_E_SHAPE;
-    if (ldx % OCS_KALIGN != 0 || ldw % OCS_KALIGN != 0 || !aligned(Xq, 16) || !aligned(Wq, 16))
-        return OCS_E_ALIGN;
-    if (!bits_ok(bits_x) || !bits_ok(bits_w)) return OCS_E_BITS;
-    const int64_t qx = (1 << (bits_x - 1)) - 1, qw = (1 << (bits_w - 1)) - 1;
-    if (Kexp * qx * qw >= (int64_t)1 << 31) return OCS_E_OVERFLOW;
     hipError_t e = launch_qgemm(Xq, ldx, Wq, ldw, M, N, Kpad, scale_x, scale_w, acc_out, ldacc, Y,
                                 ldy, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e);
@@ -381,19 +412,10 @@ int ocs_qconv(const int8_t* Aq, int64_t ldc, int B, int H, int W, int C_exp, int
               const float* scale_x, const float* scale_w, int32_t* acc_out, int64_t ldacc, float* Y,
               int64_t ldy, void* stream) {
     if (!Aq || !Wt || !scale_x || !scale_w || !Y) return OCS_E_NULL;
-    if (B <= 0 || H <= 0 || W <= 0 || C_exp <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0 ||
-        N <= 0 || N > (int64_t)1 << 30)
-        return OCS_E_SHAPE;
-    if (H + 2 * pad < kh || W + 2 * pad < kw) return OCS_E_SHAPE;
-    const int64_t Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
-    const int64_t M = (int64_t)B * Ho * Wo;
-    if (M > (int64_t)1 << 30 || (int64_t)B * H * W > (int64_t)1 << 31) return OCS_E_SHAPE;
-    if (ldc < C_exp || (int64_t)kh * kw * ldc > (int64_t)1 << 30) return OCS_E_SHAPE;
-    if (ldy < N || (acc_out && ldacc < N)) return OCS_E_SHAPE;
-    if (ldc % OCS_CALIGN != 0 || !aligned(Aq, 16) || !aligned(Wt, 16)) return OCS_E_ALIGN;
-    if (!bits_ok(bits_x) || !bits_ok(bits_w)) return OCS_E_BITS;
-    const int64_t qx = (1 << (bits_x - 1)) - 1, qw = (1 << (bits_w - 1)) - 1;
-    if ((int64_t)kh * kw * C_exp * qx * qw >= (int64_t)1 << 31) return OCS_E_OVERFLOW;
+    int rc = check_conv_operands(Aq, ldc, B, H, W, C_exp, kh, kw, stride, pad, Wt, N, bits_x, bits_w,
+                                 acc_out, ldacc);
+    if (rc) return rc;
+    if (ldy < N) return OCS_E_SHAPE;
     hipError_t e = launch_qconv(Aq, ldc, B, H, W, kh, kw, stride, pad, Wt,
                                 round_up((int64_t)kh * kw * ldc, OCS_KALIGN), N,
                                 scale_x, scale_w, acc_out, ldacc, Y, ldy,
@@ -438,15 +460,9 @@ int ocs_qgemm_requant(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t l
                       const int32_t* next_chan_src, int next_splits, int8_t* Yq, int64_t ldyq,
                       float* next_scale_out, int32_t* acc_out, int64_t ldacc, void* stream) {
     if (!Xq || !Wq || !scale_x || !scale_w) return OCS_E_NULL;
-    if (M <= 0 || N <= 0 || Kexp <= 0) return OCS_E_SHAPE;
-    if (M > (int64_t)1 << 30 || N > (int64_t)1 << 30 || Kexp > (int64_t)1 << 30) return OCS_E_SHAPE;
+    int rc0 = check_gemm_operands(Xq, ldx, Wq, ldw, M, N, Kexp, bits_x, bits_w, acc_out, ldacc);
+    if (rc0) return rc0;
     const int64_t Kpad = round_up(Kexp, OCS_KALIGN);
-    if (ldx < Kpad || ldw < Kpad || (acc_out && ldacc < N)) return OCS_E_SHAPE;
-    if (ldx % OCS_KALIGN != 0 || ldw % OCS_KALIGN != 0 || !aligned(Xq, 16) || !aligned(Wq, 16))
-        return OCS_E_ALIGN;
-    if (!bits_ok(bits_x) || !bits_ok(bits_w)) return OCS_E_BITS;
-    const int64_t qx = (1 << (bits_x - 1)) - 1, qw = (1 << (bits_w - 1)) - 1;
-    if (Kexp * qx * qw >= (int64_t)1 << 31) return OCS_E_OVERFLOW;
     int rc = check_requant((int)N, next_threshold, next_bits, next_chan_src, next_splits, Yq, ldyq,
                            next_scale_out);
     if (rc) return rc;
@@ -465,19 +481,9 @@ int ocs_qconv_requant(const int8_t* Aq, int64_t ldc, int B, int H, int W, int C_
                       int next_splits, int8_t* Yq, int64_t ldyq, float* next_scale_out,
                       int32_t* acc_out, int64_t ldacc, void* stream) {
     if (!Aq || !Wt || !scale_x || !scale_w) return OCS_E_NULL;
-    if (B <= 0 || H <= 0 || W <= 0 || C_exp <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0 ||
-        N <= 0 || N > (int64_t)1 << 30)
-        return OCS_E_SHAPE;
-    if (H + 2 * pad < kh || W + 2 * pad < kw) return OCS_E_SHAPE;
-    const int64_t Ho = (H + 2 * pad - kh) / stride + 1, Wo = (W + 2 * pad - kw) / stride + 1;
-    const int64_t M = (int64_t)B * Ho * Wo;
-    if (M > (int64_t)1 << 30 || (int64_t)B * H * W > (int64_t)1 << 31) return OCS_E_SHAPE;
-    if (ldc < C_exp || (int64_t)kh * kw * ldc > (int64_t)1 << 30) return OCS_E_SHAPE;
-    if (acc_out && ldacc < N) return OCS_E_SHAPE;
-    if (ldc % OCS_CALIGN != 0 || !aligned(Aq, 16) || !aligned(Wt, 16)) return OCS_E_ALIGN;
-    if (!bits_ok(bits_x) || !bits_ok(bits_w)) return OCS_E_BITS;
-    const int64_t qx = (1 << (bits_x - 1)) - 1, qw = (1 << (bits_w - 1)) - 1;
-    if ((int64_t)kh * kw * C_exp * qx * qw >= (int64_t)1 << 31) return OCS_E_OVERFLOW;
+    int rc0 = check_conv_operands(Aq, ldc, B, H, W, C_exp, kh, kw, stride, pad, Wt, N, bits_x, bits_w,
+                                  acc_out, ldacc);
+    if (rc0) return rc0;
     int rc = check_requant((int)N, next_threshold, next_bits, next_chan_src, next_splits, Yq, ldyq,
                            next_scale_out);
     if (rc) return rc;
