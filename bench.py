@@ -264,7 +264,8 @@ def main():
         "unit": "TOPS (2*M*N*K' of the expanded layer per second of whole-step time)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int8 codes x int8 codes -> int32 (fp32 in, fp32 out)", "data": "synthetic",
+        "dtype": "int8", "dtype_detail": "int8 codes x int8 codes -> int32 accumulators; fp32 in, fp32 out",
+        "data": "synthetic",
         "config": {"workload": "configs[1]: 3x3 conv 256->256, 14x14, batch 64 as im2col GEMM "
                                f"M={M} K={K} N={N}, r={layer.r} (s={L.s}, K'={Ke}, padded {ldq}), "
                                "8-bit weights and activations, weight OCS, per-batch activation grid",
