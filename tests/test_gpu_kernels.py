@@ -447,3 +447,60 @@ def test_conv_chain_with_codes_between_the_layers(tile):
     acc2, Y2 = gpu_qgemm(host(Yq), w2["Wq"], N1 + s2, host(sc2), w2["scale"], bits_w=6)
     assert np.array_equal(acc2, acc2_ref)
     assert_y_close(Y2, y2_ref)
+
+
+# ---- seeded random layers through the whole chain -------------------------------------------------
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_layer_end_to_end(seed):
+    from paper_1901_09504_amd.layer import ExpandedLayer
+    rng = np.random.default_rng(1000 + seed)
+    M = int(rng.integers(1, 400))
+    C = int(rng.integers(1, 300))
+    g = int(rng.choice([1, 1, 2, 4, 9]))
+    N = int(rng.integers(1, 300))
+    r = float(rng.choice([0.0, 0.01, 0.05, 0.1, 0.3]))
+    bits_w, bits_x = int(rng.integers(2, 9)), int(rng.integers(2, 9))
+    clip = float(rng.choice([1.0, 0.9, 0.5]))
+    kind = str(rng.choice(["heavy", "normal", "ties"]))
+    X, W = _tensor(rng, M, C * g, kind), _tensor(rng, N, C * g, "heavy")
+    static = None if seed % 3 else float(np.float32(0.7 * np.abs(X).max() + 1e-3))
+    L = ExpandedLayer(N, C, g, r, bits_w, bits_x, clip_ratio_w=clip)
+    L.prepare_weights(dev(W))
+    acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    th = None if static is None else torch.tensor([static], dtype=torch.float32, device="cuda")
+    Y = L.forward(dev(X), threshold=th, acc_out=acc)
+    sp = ref.split_weights(W, C, g, L.s)
+    Wq, sw = ref.quantize(sp["T_out"], bits_w, clip_ratio=clip, ldq=L.ldq)
+    Xq, sx, _ = ref.split_act(X, C, g, sp["chan_src"], None, L.s, bits_x, threshold=static, ldq=L.ldq)
+    acc_ref, y_ref = ref.qgemm(Xq, Wq, L.Ke, sx[1], sw[1])
+    assert np.array_equal(host(L.split_src)[:L.s], sp["split_src"])
+    assert np.array_equal(host(L.Wq), Wq) and np.array_equal(host(L.Xq[:M]), Xq)
+    assert np.array_equal(host(L.scale_w), sw) and np.array_equal(host(L.scale_x), sx)
+    assert np.array_equal(host(acc), acc_ref)
+    assert_y_close(host(Y), y_ref)
+    # the same layer un-expanded on folded codes, when they fit
+    worst = int(host(L.fold_weights())[0])
+    Wf_ref, worst_ref = ref.fold_weights(Wq, C, g, L.s, sp["chan_src"], ldf=L.ldf)
+    assert worst == worst_ref and np.array_equal(host(L.Wf), Wf_ref)
+    if worst <= 127:
+        acc_f = torch.empty((M, N), dtype=torch.int32, device="cuda")
+        Y_e = Y.clone()
+        Y_f = L.forward_folded(dev(X), threshold=th, acc_out=acc_f)
+        assert torch.equal(acc, acc_f) and torch.equal(Y_e, Y_f)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_convolution(seed):
+    rng = np.random.default_rng(2000 + seed)
+    kh, kw = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+    stride, pad = int(rng.integers(1, 3)), int(rng.integers(0, 3))
+    H, W = int(rng.integers(max(1, kh - 2 * pad), 13)), int(rng.integers(max(1, kw - 2 * pad), 13))
+    Bn, Cn, N = int(rng.integers(1, 4)), int(rng.integers(1, 90)), int(rng.integers(1, 150))
+    s = int(rng.integers(0, 6))
+    A = _tensor(rng, Bn * H * W, Cn, "heavy").reshape(Bn, H, W, Cn)
+    Wm = _tensor(rng, N, Cn * kh * kw, "heavy")
+    exp = _conv_reference(A, Wm, Cn, kh, kw, stride, pad, s, 8, 5, None)
+    got = gpu_conv_layer(A, Wm, Cn, kh, kw, stride, pad, s, bits_x=8, bits_w=5)
+    assert np.array_equal(got["acc"], exp["acc"])
+    assert_y_close(got["Y"], exp["Y"])
