@@ -332,7 +332,7 @@ int ocs_calib_copy(const void *src, void *dst, size_t bytes, void *stream);
 
 /*
  * Launch-shape overrides for benchmarking (no passage of the paper; results never depend
- * on them).  key: "act_grid", "act_nt", "act_un", "act_map", "gemm_tile"; value < 0 restores the default.
+ * on them).  key: "act_grid", "act_nt", "act_un", "act_map", "act_wide", "gemm_tile"; value < 0 restores the default.
  * Returns OCS_OK or OCS_E_MODE for an unknown key.  Not thread-safe.
  */
 int ocs_tune(const char *key, int value);

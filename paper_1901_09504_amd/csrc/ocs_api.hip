@@ -535,6 +535,7 @@ int ocs_tune(const char* key, int value) {
     if (!strcmp(key, "act_grid")) t.act_grid = value;
     else if (!strcmp(key, "act_nt")) t.act_nt = value < 0 ? 0 : value;
     else if (!strcmp(key, "act_un")) t.act_un = value;
+    else if (!strcmp(key, "act_wide")) t.act_wide = value < 0 ? 0 : value;
     else if (!strcmp(key, "act_map")) t.act_map = value;
     else if (!strcmp(key, "gemm_tile")) t.gemm_tile = value;
     else return OCS_E_MODE;

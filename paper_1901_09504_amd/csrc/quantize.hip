@@ -374,7 +374,7 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
         if (tuning().act_grid > 0) gin = tuning().act_grid;
         if (gin > ceil_div(total_in, kThreads)) gin = ceil_div(total_in, kThreads);
         // output dword indices reach M*D; the prefetch looks two strides past the item
-        const bool wide_in = total + 2 * gin * kThreads >= ((int64_t)1 << 32);
+        const bool wide_in = tuning().act_wide > 0 || total + 2 * gin * kThreads >= ((int64_t)1 << 32);
         const unsigned magic_q = (unsigned)((((uint64_t)1) << 32) / (uint64_t)Q);
 #define OCS_LAUNCH_IN(H, I_)                                                                       \
     launch_kernel(kTimeSplitQuantize, expand_quantize_in_kernel<H, I_>, dim3((unsigned)gin),      \
@@ -388,7 +388,7 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
     int un = tuning().act_un;
     if (un != 1 && un != 2 && un != 4) un = 1;
     // the prefetch looks up to 2*un strides past the item being processed
-    const bool wide = total + 2 * un * grid * kThreads >= ((int64_t)1 << 32);
+    const bool wide = tuning().act_wide > 0 || total + 2 * un * grid * kThreads >= ((int64_t)1 << 32);
     const unsigned magic = (unsigned)((((uint64_t)1) << 32) / (uint64_t)D);  // D >= 16
 
     hipError_t err = hipSuccess;

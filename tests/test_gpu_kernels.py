@@ -254,7 +254,7 @@ def test_mse_clip_threshold_degenerate_and_large():
                                      (77, 2048, 1, 205), (50, 64, 4, 300), (9, 512, 9, 26)])
 @pytest.mark.parametrize("halve", [False, True])
 @pytest.mark.parametrize("threshold", [None, 3.0])
-@pytest.mark.parametrize("act_map", [0, 1])   # lanes dealt over the output / over the input
+@pytest.mark.parametrize("act_map", [0, 1, 2, 3])   # lanes over the output / the input; +2: 64-bit indices
 def test_split_act(M, C, g, s, halve, threshold, act_map):
     rng = np.random.default_rng(M + C + g + s)
     X = _tensor(rng, M, C * g, "heavy")
@@ -262,11 +262,13 @@ def test_split_act(M, C, g, s, halve, threshold, act_map):
     cs, cd = sel["chan_src"], (sel["chan_depth"] if halve else None)
     ldq = B.ocs_padded_cols((C + s) * g)
     q_ref, s_ref, _ = ref.split_act(X, C, g, cs, cd, s, 8, threshold=threshold, clip_ratio=0.9, ldq=ldq)
-    B.ocs_tune("act_map", act_map)
+    B.ocs_tune("act_map", act_map & 1)
+    B.ocs_tune("act_wide", act_map >> 1)
     try:
         q, sc = gpu_split_act(X, C, g, cs, cd, s, 8, threshold=threshold, clip_ratio=0.9)
     finally:
         B.ocs_tune("act_map", -1)
+        B.ocs_tune("act_wide", 0)
     assert np.array_equal(sc, s_ref)
     assert np.array_equal(q, q_ref)
 
