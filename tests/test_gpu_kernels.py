@@ -506,3 +506,52 @@ def test_random_convolution(seed):
     got = gpu_conv_layer(A, Wm, Cn, kh, kw, stride, pad, s, bits_x=8, bits_w=5)
     assert np.array_equal(got["acc"], exp["acc"])
     assert_y_close(got["Y"], exp["Y"])
+
+
+# ---- paths that ordinary shapes do not reach --------------------------------------------------------
+
+def test_expanded_channel_limit_and_long_tails():
+    # C + s at the library's limit of 8000 expanded channels (the selector's list fills its LDS)
+    rng = np.random.default_rng(7)
+    T = _tensor(rng, 3, 7000, "heavy")
+    exp = ref.split_weights(T, 7000, 1, 1000)
+    got = gpu_select(T, 7000, 1, 1000)
+    for k in ("split_src", "chan_src", "chan_depth"):
+        assert np.array_equal(got[k], exp[k]), k
+    # more appended + padded columns than the split+quantize kernels keep in their LDS table
+    M, C, g, s = 12, 30, 9, 260
+    X = _tensor(rng, M, C * g, "heavy")
+    sel = ref.split_weights(_tensor(rng, 5, C * g, "heavy"), C, g, s)
+    ldq = B.ocs_padded_cols((C + s) * g)
+    for cd in (None, sel["chan_depth"]):
+        q_ref, s_ref, _ = ref.split_act(X, C, g, sel["chan_src"], cd, s, 7, ldq=ldq)
+        for wide in (0, 1):
+            B.ocs_tune("act_wide", wide)
+            try:
+                q, sc = gpu_split_act(X, C, g, sel["chan_src"], cd, s, 7)
+            finally:
+                B.ocs_tune("act_wide", 0)
+            assert np.array_equal(sc, s_ref) and np.array_equal(q, q_ref)
+
+
+def test_streaming_hint_and_many_weight_rows():
+    rng = np.random.default_rng(8)
+    # non-temporal loads of X in the split+quantize pass (a launch option)
+    M, C, g, s = 200, 64, 9, 4
+    X = _tensor(rng, M, C * g, "heavy")
+    sel = ref.split_weights(_tensor(rng, 9, C * g, "heavy"), C, g, s)
+    q_ref, s_ref, _ = ref.split_act(X, C, g, sel["chan_src"], None, s, 8, ldq=B.ocs_padded_cols((C + s) * g))
+    B.ocs_tune("act_nt", 1)
+    try:
+        q, sc = gpu_split_act(X, C, g, sel["chan_src"], None, s, 8)
+    finally:
+        B.ocs_tune("act_nt", 0)
+    assert np.array_equal(sc, s_ref) and np.array_equal(q, q_ref)
+    # more weight rows than one launch of the fp32 expansion covers (65535 per launch)
+    N, C, g, s = 70000, 4, 1, 2
+    W = _tensor(rng, N, C * g, "normal")
+    exp = ref.split_weights(W, C, g, s)
+    got = gpu_split_weights(W, C, g, s, bits=6)
+    assert np.array_equal(got["T_out"], exp["T_out"])
+    q_ref, sw_ref = ref.quantize(exp["T_out"], 6, ldq=B.ocs_padded_cols((C + s) * g))
+    assert np.array_equal(got["Wq"], q_ref) and np.array_equal(got["scale"], sw_ref)
