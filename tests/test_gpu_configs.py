@@ -298,3 +298,35 @@ def test_folding_eight_bit_weights_is_reported_as_not_fitting():
     worst = int(host(L.fold_weights())[0])
     _, worst_ref = ref.fold_weights(host(L.Wq), layer.C, layer.g, L.s, host(L.chan_src))
     assert worst == worst_ref > 127
+
+
+# ---- the call chain inside a HIP graph ---------------------------------------------------------------
+
+def test_layer_replays_from_a_hip_graph():
+    # the library allocates nothing, never synchronises and keeps its scalars on the device, so
+    # the whole chain (weights, per-batch grid, split+quantize, GEMM) can be captured once and
+    # replayed; every replay is checked against the eager result on the same input
+    layer = wl.shrink(wl.config(2)[0], 1500)
+    W = wl.weights(layer)
+    L = ExpandedLayer(layer.N, layer.C, layer.g, layer.r, layer.bits_w, layer.bits_x, max_rows=layer.M)
+    Wd = dev(W)
+    Xd = dev(wl.activations(layer))
+    L.prepare_weights(Wd)
+    L.forward(Xd)                      # eager warm-up: buffers exist before the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        L.prepare_weights(Wd)
+        L.forward(Xd)
+    rng = np.random.default_rng(3)
+    for rep in range(4):
+        X = wl.activations(layer) * np.float32(1.0 + rep)
+        X[rng.integers(0, layer.M), rng.integers(0, layer.K)] = 40.0 + rep       # moves the per-batch grid
+        Xd.copy_(dev(X))
+        graph.replay()
+        torch.cuda.synchronize()
+        Y_graph, sx_graph, Xq_graph = L.Y[:layer.M].clone(), host(L.scale_x).copy(), L.Xq[:layer.M].clone()
+        Y_eager = L.forward(Xd).clone()
+        torch.cuda.synchronize()
+        assert np.array_equal(sx_graph, host(L.scale_x)) and sx_graph[0] == np.float32(40.0 + rep)
+        assert torch.equal(Xq_graph, L.Xq[:layer.M]) and torch.equal(Y_graph, Y_eager)
