@@ -145,6 +145,8 @@ def main():
                     help="every n-th timed step carries the per-phase and per-kernel events")
     ap.add_argument("--mfma-gemm-launches", type=int, default=24,
                     help="launches of the GEMM on the MFMA-bound layer shape after the timed region (0: skip)")
+    ap.add_argument("--graph-steps", type=int, default=200,
+                    help="steps replayed from HIP graphs after the timed region (0: skip)")
     ap.add_argument("--conv-steps", type=int, default=100,
                     help="steps of the same layer given un-lowered, after the timed region (0: skip)")
     ap.add_argument("--calib-copies", type=int, default=6,
@@ -306,6 +308,27 @@ def main():
         "roof_tops_min_mfma_hbm": gemm_roof_tops, "frac_of_that_roof": gemm_tops / gemm_roof_tops})
     if args.mfma_gemm_launches > 0:
         out["gemm_mfma_bound"] = mfma_bound_gemm(torch, B, wl, ExpandedLayer, args.mfma_gemm_launches)
+    if args.graph_steps > 0:
+        # the same step replayed from HIP graphs (one per rotating copy of X): what the dispatch
+        # gaps between the step's seven launches cost
+        graphs = []
+        for x in Xd:
+            g_ = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_):
+                L.prepare_weights(Wd)
+                B.ocs_split_act(x, M, L.C, L.g, K, L.chan_src, None, L.s, L.bits_x, None, 1.0, L.Xq, ldq,
+                                L.scale_x, L.ws_x)
+                L.qgemm(M)
+            graphs.append(g_)
+        for i in range(10):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        tg = time.perf_counter()
+        for i in range(args.graph_steps):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - tg) / args.graph_steps * 1e6
+        out["graph_replay"] = {"us_per_step": us, "tops_whole_step": ops / us / 1e6, "steps": args.graph_steps}
     if args.conv_steps > 0:
         out["conv_unlowered"] = conv_unlowered(torch, B, wl, layer, args.conv_steps)
     if not args.no_cpu_baseline:
