@@ -356,6 +356,56 @@ int ref_mse_clip(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bi
 }
 
 /*
+ * Sec. 3.3 on the activation side (Eq. 4 with the quantization-aware pair): the split list
+ * (chosen by the plain-halving procedure on the batch, as for the weights) is replayed on the
+ * activations; at each split the channel that keeps its index becomes (x - step/2)/2 and the
+ * appended copy (x + step/2)/2, step = T / qmax with the given threshold T of the activation
+ * grid; codes by Q(x) = floor(x + 1/2).  Same fp32 order as ref_split_weights_qa.
+ * Xf (may be NULL) receives the expanded fp32 activations [M, (C+s)*g].
+ */
+int ref_split_act_qa(const float *X, int64_t M, int C, int g, int64_t ldx, const int32_t *split_src,
+                     int s, int bits, float T, int8_t *Xq, int64_t ldq, float *scale_out, float *Xf,
+                     int64_t ldf) {
+    if (!X || !Xq || !scale_out || (s > 0 && !split_src)) return REF_E_ARG;
+    if (M <= 0 || C <= 0 || g <= 0 || s < 0 || bits < 2 || bits > 8) return REF_E_ARG;
+    int64_t K = (int64_t)C * g, Ke = (int64_t)(C + s) * g;
+    if (ldx < K || ldq < Ke || (Xf && ldf < Ke)) return REF_E_ARG;
+    float qmax = (float)((1 << (bits - 1)) - 1);
+    float step = T / qmax, half_step = step * 0.5f;
+    float inv = inv_step_of(T, qmax);
+    float *E = (float *)malloc((size_t)M * (size_t)Ke * sizeof(float));
+    if (!E) return REF_E_NOMEM;
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t k = 0; k < K; ++k) E[i * Ke + k] = X[i * ldx + k];
+    for (int i = 0; i < s; ++i) {
+        int pick = split_src[i], cur = C + i;
+        if (pick < 0 || pick >= cur) {
+            free(E);
+            return REF_E_ARG;
+        }
+        for (int64_t r = 0; r < M; ++r)
+            for (int t = 0; t < g; ++t) {
+                float v = E[r * Ke + (int64_t)pick * g + t];
+                float lo = v - half_step;
+                float hi = v + half_step;
+                E[r * Ke + (int64_t)pick * g + t] = lo * 0.5f;
+                E[r * Ke + (int64_t)cur * g + t] = hi * 0.5f;
+            }
+    }
+    scale_out[0] = T;
+    scale_out[1] = step;
+    for (int64_t r = 0; r < M; ++r) {
+        for (int64_t k = 0; k < Ke; ++k) {
+            Xq[r * ldq + k] = code_of_half_up(E[r * Ke + k], inv, qmax);
+            if (Xf) Xf[r * ldf + k] = E[r * Ke + k];
+        }
+        for (int64_t k = Ke; k < ldq; ++k) Xq[r * ldq + k] = 0;
+    }
+    free(E);
+    return REF_OK;
+}
+
+/*
  * The activation side of Eq. 3 / Eq. 4 followed by Eq. 1 (Sec. 3.5: a layer that copies
  * and scales the chosen channels).  Expanded channel j of the output reads original
  * channel chan_src[j]; with chan_depth != NULL it is multiplied by 2^-chan_depth[j]

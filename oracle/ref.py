@@ -191,6 +191,23 @@ def split_act(X, Cn, g, chan_src, chan_depth, s, bits, threshold=None, clip_rati
     return q, sc, Xf
 
 
+def split_act_qa(X, Cn, g, split_src, s, bits, T, ldq=None, want_f32=False):
+    """Sec. 3.3 on the activations (Eq. 4 with the QA pair).  Returns (codes, scale, Xf or None)."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    M = X.shape[0]
+    Ke = (Cn + s) * g
+    ldq = Ke if ldq is None else int(ldq)
+    q = np.full((M, ldq), 99, dtype=np.int8)
+    sc = np.zeros(2, dtype=np.float32)
+    ss = np.ascontiguousarray(split_src, dtype=np.int32) if s > 0 else None
+    Xf = np.zeros((M, Ke), dtype=np.float32) if want_f32 else None
+    rc = lib().ref_split_act_qa(_p(X, C.c_float), C.c_int64(M), C.c_int(Cn), C.c_int(g), C.c_int64(X.shape[1]),
+                                _p(ss, C.c_int32), C.c_int(s), C.c_int(bits), C.c_float(T), _p(q, C.c_int8),
+                                C.c_int64(ldq), _p(sc, C.c_float), _p(Xf, C.c_float), C.c_int64(Ke))
+    _check(rc, "ref_split_act_qa")
+    return q, sc, Xf
+
+
 def qgemm(Xq, Wq, Kexp, step_x, step_w, want_acc=True, want_y=True):
     """Eq. 2 on codes.  Returns (acc int32 [M,N] or None, Y float64 [M,N] or None)."""
     Xq = np.ascontiguousarray(Xq, dtype=np.int8)

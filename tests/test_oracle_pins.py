@@ -631,3 +631,31 @@ def test_folding_reports_codes_that_do_not_fit():
     assert worst == 254 and Wf[0, 0] == 127
     Wq7, _ = ref.quantize(sp["T_out"], 7)
     assert ref.fold_weights(Wq7, 3, 1, 1, sp["chan_src"])[1] == 126
+
+
+# ---- Sec. 3.3 on the activation side (Eq. 4 with the QA pair) ---------------------------------
+
+def test_qa_activation_members_add_up_and_keep_the_layer():
+    # channel 0 holds the batch's outlier (28) and is split into four quarter copies; threshold 7
+    # with 4 bits gives step 1; values are multiples of 1/16, so every fp32 step is exact
+    xs = np.concatenate([[28.0], np.arange(-27 * 16, 27 * 16 + 1, 5) / 16.0]).astype(np.float32)
+    X = np.stack([xs, np.full_like(xs, 2.5), np.full_like(xs, -1.25)], axis=1)
+    sel = ref.split_weights(X, 3, 1, 3)                          # the choice made on the batch
+    assert sel["chan_src"].tolist() == [0, 1, 2, 0, 0, 0] and sel["max"] == 7.0
+    q, sc, Xf = ref.split_act_qa(X, 3, 1, sel["split_src"], 3, 4, 7.0, want_f32=True)
+    assert sc.tolist() == [7.0, 1.0]
+    copies = [0, 3, 4, 5]
+    assert np.array_equal(q[:, copies].astype(np.int64).sum(axis=1),
+                          np.floor(xs.astype(np.float64) + 0.5).astype(np.int64))
+    assert np.array_equal(Xf[:, copies].astype(np.float64).sum(axis=1), xs.astype(np.float64))
+    assert q[0, 1] == 3 and q[0, 2] == -1                        # floor(2.5 + .5), floor(-1.25 + .5)
+    # Eq. 4: QA-split activations against duplicated (un-halved) weights give the layer back
+    W = (np.arange(12).reshape(4, 3) - 5).astype(np.float32)
+    dup = ref.split_weights(W, 3, 1, 3, mode=ref.MODE_DUP, split_src=sel["split_src"])
+    assert np.array_equal(Xf.astype(np.float64) @ dup["T_out"].astype(np.float64).T,
+                          X.astype(np.float64) @ W.astype(np.float64).T)
+    # the w = 3 example of the section, on the activation side
+    ex = np.array([[14.0, 0.25], [3.0, 0.25]], dtype=np.float32)
+    s1 = ref.split_weights(ex, 2, 1, 1)
+    q1, _, f1 = ref.split_act_qa(ex, 2, 1, s1["split_src"], 1, 4, 7.0, want_f32=True)
+    assert f1[1].tolist() == [1.25, 0.25, 1.75] and q1[1].tolist() == [1, 0, 2]
