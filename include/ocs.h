@@ -175,6 +175,25 @@ int ocs_mse_clip_threshold(const float *x, int64_t rows, int64_t cols, int64_t l
                            size_t ws_bytes, void *stream);
 
 /*
+ * Sec. 3.3 on the activation side (Eq. 4 with the quantization-aware pair), per batch.
+ * split_src / chan_src / chan_depth: the choice made on this batch by ocs_select_channels
+ * (plain halving); threshold: device float, the activation grid's range T (with no clipping:
+ * the max_out of that same call), step = T / qmax.  The split list is replayed on X: at each
+ * split the channel that keeps its index becomes (x - step/2)/2, the appended copy
+ * (x + step/2)/2 (fp32, one add/subtract and one exact halving per split); codes
+ * clamp(floor(x' * (qmax / T) + 1/2), -qmax, qmax).  chan_path [C + num_splits] uint32 is an
+ * output (the histories, as in ocs_split_weights_qa).  Xq [M, ldq] int8, pad columns zero;
+ * scale_out device float[2] = {T, step}, must not be `threshold`.  The weights are duplicated
+ * un-halved (ocs_split_weights, OCS_MODE_DUP) as for Eq. 4.  A plain, non-streaming kernel:
+ * the paper finds activation splitting ineffective (Sec. 5.3) and this variant is provided for
+ * completeness, not tuned.
+ */
+int ocs_split_act_qa(const float *X, int64_t M, int C, int g, int64_t ldx, const int32_t *split_src,
+                     const int32_t *chan_src, const int32_t *chan_depth, uint32_t *chan_path,
+                     int num_splits, int bits, const float *threshold, int8_t *Xq, int64_t ldq,
+                     float *scale_out, void *stream);
+
+/*
  * Linear quantization of Sec. 3.1 Eq. 1 with optional clipping (Sec. 1).
  *   x [rows, cols] fp32 -> q [rows, ldq] int8, q = clamp(rne(x * (qmax / T)), -qmax, qmax),
  *   qmax = 2^(bits-1) - 1 (a grid of 2^bits - 1 points), columns cols .. ldq-1 zero.

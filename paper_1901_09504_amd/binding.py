@@ -75,6 +75,9 @@ def lib():
                                     _i32, _vp, _vp, _i32, _vp, _i32, _vp, _i32, _vp, _i64, _vp, _vp, _i64, _vp]
     L.ocs_fold_weights.restype = _i32
     L.ocs_fold_weights.argtypes = [_vp, _i64, _i64, _i32, _i32, _i32, _vp, _vp, _i64, _vp, _vp]
+    L.ocs_split_act_qa.restype = _i32
+    L.ocs_split_act_qa.argtypes = [_vp, _i64, _i32, _i32, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _i64,
+                                   _vp, _vp]
     L.ocs_quantize.restype = _i32
     L.ocs_quantize.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _f32, _vp, _i64, _vp, _vp, _sz, _vp]
     L.ocs_split_act.restype = _i32
@@ -230,6 +233,13 @@ def ocs_qconv_requant(Aq, ldc, Bn, H, W, C_exp, kh, kw, stride, pad, Wt, N, bits
 def ocs_fold_weights(Wq, ldq, N, Cn, g, num_splits, chan_src, Wf, ldf, max_abs_out, stream=None):
     _check(lib().ocs_fold_weights(_ptr(Wq), ldq, N, Cn, g, num_splits, _ptr(chan_src), _ptr(Wf), ldf,
                                   _ptr(max_abs_out), _stream(stream)), "ocs_fold_weights")
+
+
+def ocs_split_act_qa(X, M, Cn, g, ldx, split_src, chan_src, chan_depth, chan_path, num_splits, bits, threshold,
+                     Xq, ldq, scale_out, stream=None):
+    _check(lib().ocs_split_act_qa(_ptr(X), M, Cn, g, ldx, _ptr(split_src), _ptr(chan_src), _ptr(chan_depth),
+                                  _ptr(chan_path), num_splits, bits, _ptr(threshold), _ptr(Xq), ldq,
+                                  _ptr(scale_out), _stream(stream)), "ocs_split_act_qa")
 
 
 def ocs_quantize(x, rows, cols, ldx, bits, threshold, clip_ratio, q, ldq, scale_out, workspace,

@@ -244,6 +244,30 @@ int ocs_split_weights_qa(const float* W, int64_t N, int C, int g, int64_t ldw, i
     return OCS_OK;
 }
 
+int ocs_split_act_qa(const float* X, int64_t M, int C, int g, int64_t ldx, const int32_t* split_src,
+                     const int32_t* chan_src, const int32_t* chan_depth, uint32_t* chan_path,
+                     int num_splits, int bits, const float* threshold, int8_t* Xq, int64_t ldq,
+                     float* scale_out, void* stream) {
+    if (!X || !Xq || !scale_out || !threshold || !chan_src || !chan_depth || !chan_path) return OCS_E_NULL;
+    if (num_splits > 0 && !split_src) return OCS_E_NULL;
+    if (threshold == scale_out) return OCS_E_MODE;
+    int rc = check_layer(M, C, g, ldx, num_splits);
+    if (rc) return rc;
+    rc = check_codes(Xq, ldq, (int64_t)(C + num_splits) * g);
+    if (rc) return rc;
+    if (!bits_ok(bits)) return OCS_E_BITS;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const float qmax = qmax_of(bits);
+    hipError_t e = launch_qa_scale(threshold, qmax, scale_out, st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = launch_qa_paths(split_src, C, num_splits, chan_path, st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = launch_expand_quantize_qa(X, ldx, M, C, g, num_splits, chan_src, chan_depth, chan_path, scale_out,
+                                  qmax, nullptr, 0, Xq, ldq, st);
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
 int ocs_quantize(const float* x, int64_t rows, int64_t cols, int64_t ldx, int bits,
                  const float* threshold, float clip_ratio, int8_t* q, int64_t ldq,
                  float* scale_out, void* workspace, size_t ws_bytes, void* stream) {

@@ -105,6 +105,19 @@ hipError_t launch_expand_quantize_qa(const float* W, int64_t ldw, int64_t N, int
     return hipGetLastError();
 }
 
+// {T, T/qmax} from a device threshold: what the QA kernel needs when the threshold is given
+// (activation side: the selector's maximum of the plainly halved batch).
+__global__ void qa_scale_kernel(const float* __restrict__ thr, float qmax, float* __restrict__ scale_out) {
+    const float T = *thr;
+    scale_out[0] = T;
+    scale_out[1] = T / qmax;
+}
+
+hipError_t launch_qa_scale(const float* thr, float qmax, float* scale_out, hipStream_t stream) {
+    qa_scale_kernel<<<1, 1, 0, stream>>>(thr, qmax, scale_out);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------------------------
 // The expanded layer of Eq. 3 run without expanding it.  A duplicated activation channel
 // multiplies each of its weight copies by the same activation code, so the accumulator of the

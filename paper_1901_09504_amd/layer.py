@@ -117,8 +117,9 @@ class ExpandedLayer:
         self.qgemm(M, acc_out, stream)
         return self.Y[:M]
 
-    def forward_act_ocs(self, W, X, acc_out=None, stream=None):
-        """Activation OCS with the channel choice made on this batch (Eq. 4, Sec. 5.3)."""
+    def forward_act_ocs(self, W, X, acc_out=None, stream=None, qa=False):
+        """Activation OCS with the channel choice made on this batch (Eq. 4, Sec. 5.3).
+        qa: quantization-aware members on the activations (Sec. 3.3) instead of plain halves."""
         M = X.shape[0]
         self._ensure_rows(M)
         xmax = torch.empty(1, dtype=torch.float32, device=self.device)
@@ -128,6 +129,14 @@ class ExpandedLayer:
                             self.split_src, self.chan_src, self.chan_depth, None, 0, self.wmax,
                             self.bits_w, self.clip_ratio_w, self.Wq, self.ldq, self.scale_w,
                             self.ws_w, stream)
+        if qa:
+            if self.chan_path is None:
+                self.chan_path = torch.empty(self.C + self.s, dtype=torch.int32, device=self.device)
+            B.ocs_split_act_qa(X, M, self.C, self.g, X.stride(0), self.split_src, self.chan_src,
+                               self.chan_depth, self.chan_path, self.s, self.bits_x, xmax, self.Xq,
+                               self.ldq, self.scale_x, stream)
+            self.qgemm(M, acc_out, stream)
+            return self.Y[:M]
         # the selector already returned the largest magnitude of the halved activations: with no
         # clipping that is the threshold, and the pass over X that would recompute it is skipped
         thr = xmax if self.clip_ratio_x == 1.0 else None

@@ -84,6 +84,8 @@ def test_argument_errors_are_reported_without_a_device():
     assert L.ocs_qgemm_requant(A, 64, A, 64, 4, 4, 4, 8, 8, A, A, 0, A, 8, None, 0, A, 16, A, None, 0, None) == -9         # scale_out aliases the grid
     assert L.ocs_fold_weights(A, 64, 4, 4, 1, 2, None, A, 64, A, None) == -1          # split list missing
     assert L.ocs_fold_weights(A, 4, 4, 4, 1, 2, A, A, 64, A, None) == -2             # ldq < (C+s)*g
+    assert L.ocs_split_act_qa(A, 4, 4, 1, 4, A, A, A, A, 1, 8, None, A, 64, A, None) == -1     # no threshold
+    assert L.ocs_split_act_qa(A, 4, 4, 1, 4, A, A, A, A, 1, 8, A, A, 64, A, None) == -9        # scale_out aliases it
     # shapes
     assert L.ocs_quantize(A, 0, 4, 4, 8, A, 1.0, A, 64, A, A, ws, None) == -2
     assert L.ocs_quantize(A, 4, 8, 4, 8, A, 1.0, A, 64, A, A, ws, None) == -2      # ldx < cols

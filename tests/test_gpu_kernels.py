@@ -555,3 +555,48 @@ def test_streaming_hint_and_many_weight_rows():
     assert np.array_equal(got["T_out"], exp["T_out"])
     q_ref, sw_ref = ref.quantize(exp["T_out"], 6, ldq=B.ocs_padded_cols((C + s) * g))
     assert np.array_equal(got["Wq"], q_ref) and np.array_equal(got["scale"], sw_ref)
+
+
+# ---- ocs_split_act_qa: Sec. 3.3 on the activation side -----------------------------------------------
+
+@pytest.mark.parametrize("M,C,g,s", [(5, 8, 1, 3), (70, 64, 9, 4), (129, 256, 1, 13), (33, 37, 4, 6), (17, 20, 3, 0),
+                                     (64, 500, 1, 25), (9, 12, 1, 30)])
+@pytest.mark.parametrize("bits", [4, 8])
+def test_split_act_qa(M, C, g, s, bits):
+    rng = np.random.default_rng(M + C + g + s + bits)
+    X = _tensor(rng, M, C * g, "heavy")
+    sel = ref.split_weights(X, C, g, s)                       # the choice made on the batch
+    T = float(np.float32(sel["max"]))
+    ldq = B.ocs_padded_cols((C + s) * g)
+    q_ref, s_ref, _ = ref.split_act_qa(X, C, g, sel["split_src"], s, bits, T, ldq=ldq)
+    Xd = dev(X)
+    cp = torch.full((C + s,), -7, dtype=torch.int32, device="cuda")
+    q = torch.full((M, ldq), 77, dtype=torch.int8, device="cuda")
+    sc = torch.zeros(2, dtype=torch.float32, device="cuda")
+    ss = dev(sel["split_src"]) if s > 0 else None
+    B.ocs_split_act_qa(Xd, M, C, g, Xd.stride(0), ss, dev(sel["chan_src"]), dev(sel["chan_depth"]), cp, s, bits,
+                       torch.tensor([T], dtype=torch.float32, device="cuda"), q, ldq, sc)
+    assert np.array_equal(host(sc), s_ref)
+    assert np.array_equal(host(q), q_ref)
+    wq = ref.split_weights_qa(X, C, g, s, bits)               # same list, same histories
+    assert np.array_equal(host(cp).view(np.uint32), wq["chan_path"])
+
+
+def test_activation_ocs_with_qa_members_end_to_end():
+    from paper_1901_09504_amd import workloads as wl
+    from paper_1901_09504_amd.layer import ExpandedLayer
+    (layer,) = wl.config(1)
+    W, X = wl.weights(layer), wl.activations(layer)
+    L = ExpandedLayer(layer.N, layer.C, layer.g, layer.r, layer.bits_w, layer.bits_x)
+    acc = torch.empty((layer.M, layer.N), dtype=torch.int32, device="cuda")
+    Y = L.forward_act_ocs(dev(W), dev(X), acc_out=acc, qa=True)
+    sel = ref.split_weights(X, layer.C, layer.g, L.s)
+    dup = ref.split_weights(W, layer.C, layer.g, L.s, mode=ref.MODE_DUP, split_src=sel["split_src"])
+    Xq_ref, sx_ref, _ = ref.split_act_qa(X, layer.C, layer.g, sel["split_src"], L.s, layer.bits_x,
+                                         float(np.float32(sel["max"])), ldq=L.ldq)
+    Wq_ref, sw_ref = ref.quantize(dup["T_out"], layer.bits_w, ldq=L.ldq)
+    assert np.array_equal(host(L.Xq[:layer.M]), Xq_ref) and np.array_equal(host(L.scale_x), sx_ref)
+    assert np.array_equal(host(L.Wq), Wq_ref)
+    acc_ref, y_ref = ref.qgemm(Xq_ref, Wq_ref, L.Ke, sx_ref[1], sw_ref[1])
+    assert np.array_equal(host(acc), acc_ref)
+    assert_y_close(host(Y), y_ref)
