@@ -309,6 +309,19 @@ int ocs_qconv_requant(const int8_t *Aq, int64_t ldc, int B, int H, int W, int C_
                       int32_t *acc_out, int64_t ldacc, void *stream);
 
 /*
+ * Weight side of Eq. 4 on codes, for a channel choice that changes with every batch (Sec. 5.3).
+ * The copies of a duplicated weight channel are not scaled, so max|W'| = max|W|, the codes of
+ * the first C*g columns are those of the un-expanded weights whatever the choice, and an appended
+ * channel's codes are byte copies of its source's.  Given Wq [N, ldq] whose first C*g columns hold
+ * the codes of W (ocs_quantize on W with ldq >= (C + num_splits)*g, once), this call rewrites
+ * only columns C*g .. ldq-1 for the batch's chan_src [C + num_splits] (device int32, from
+ * ocs_select_channels): Wq[n, j*g + t] = Wq[n, chan_src[j]*g + t] for C <= j < C + num_splits,
+ * zero beyond.  Result = what ocs_split_weights in OCS_MODE_DUP writes, without reading W.
+ */
+int ocs_duplicate_weight_codes(int8_t *Wq, int64_t ldq, int64_t N, int C, int g, int num_splits,
+                               const int32_t *chan_src, void *stream);
+
+/*
  * The expanded layer of Eq. 3 run WITHOUT expanding it (off-line preparation).  In Eq. 2 on
  * codes a duplicated activation channel multiplies each of its weight copies by the same
  * activation code, so the expanded layer's int32 accumulator equals that of an un-expanded layer

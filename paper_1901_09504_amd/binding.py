@@ -78,6 +78,8 @@ def lib():
     L.ocs_split_act_qa.restype = _i32
     L.ocs_split_act_qa.argtypes = [_vp, _i64, _i32, _i32, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _i64,
                                    _vp, _vp]
+    L.ocs_duplicate_weight_codes.restype = _i32
+    L.ocs_duplicate_weight_codes.argtypes = [_vp, _i64, _i64, _i32, _i32, _i32, _vp, _vp]
     L.ocs_quantize.restype = _i32
     L.ocs_quantize.argtypes = [_vp, _i64, _i64, _i64, _i32, _vp, _f32, _vp, _i64, _vp, _vp, _sz, _vp]
     L.ocs_split_act.restype = _i32
@@ -228,6 +230,11 @@ def ocs_qconv_requant(Aq, ldc, Bn, H, W, C_exp, kh, kw, stride, pad, Wt, N, bits
                                    _ptr(next_threshold), next_bits, _ptr(next_chan_src), next_splits,
                                    _ptr(Yq), ldyq, _ptr(next_scale_out), _ptr(acc_out), ldacc,
                                    _stream(stream)), "ocs_qconv_requant")
+
+
+def ocs_duplicate_weight_codes(Wq, ldq, N, Cn, g, num_splits, chan_src, stream=None):
+    _check(lib().ocs_duplicate_weight_codes(_ptr(Wq), ldq, N, Cn, g, num_splits, _ptr(chan_src),
+                                            _stream(stream)), "ocs_duplicate_weight_codes")
 
 
 def ocs_fold_weights(Wq, ldq, N, Cn, g, num_splits, chan_src, Wf, ldf, max_abs_out, stream=None):

@@ -520,6 +520,19 @@ int ocs_qconv_requant(const int8_t* Aq, int64_t ldc, int B, int H, int W, int C_
     return OCS_OK;
 }
 
+int ocs_duplicate_weight_codes(int8_t* Wq, int64_t ldq, int64_t N, int C, int g, int num_splits,
+                               const int32_t* chan_src, void* stream) {
+    if (!Wq || (num_splits > 0 && !chan_src)) return OCS_E_NULL;
+    int rc = check_layer(N, C, g, ldq, num_splits);
+    if (rc) return rc;
+    rc = check_codes(Wq, ldq, (int64_t)(C + num_splits) * g);
+    if (rc) return rc;
+    hipError_t e = launch_dup_code_columns(Wq, ldq, N, C, g, num_splits, chan_src,
+                                           static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
 int ocs_fold_weights(const int8_t* Wq, int64_t ldq, int64_t N, int C, int g, int num_splits,
                      const int32_t* chan_src, int8_t* Wf, int64_t ldf, int32_t* max_abs_out,
                      void* stream) {

@@ -89,6 +89,8 @@ hipError_t launch_expand_f32(const float* T, int64_t ld, int64_t rows, int C, in
 // (fp32 and / or codes rounded by floor(x + 1/2)); scale = {T, T/qmax} as the selector wrote it.
 hipError_t launch_qa_paths(const int32_t* split_src, int C, int s, uint32_t* chan_path,
                            hipStream_t stream);
+hipError_t launch_dup_code_columns(int8_t* Wq, int64_t ldq, int64_t N, int C, int g, int s,
+                                   const int32_t* chan_src, hipStream_t stream);
 hipError_t launch_qa_scale(const float* thr, float qmax, float* scale_out, hipStream_t stream);
 hipError_t launch_expand_quantize_qa(const float* W, int64_t ldw, int64_t N, int C, int g, int s,
                                      const int32_t* chan_src, const int32_t* chan_depth,

@@ -105,6 +105,36 @@ hipError_t launch_expand_quantize_qa(const float* W, int64_t ldw, int64_t N, int
     return hipGetLastError();
 }
 
+// Weight side of Eq. 4 on codes: the copies of a duplicated channel are un-scaled, so their
+// codes are byte copies of the source channel's codes, and the first C*g columns never change.
+// Per batch only the appended columns (and the padding) are rewritten.
+__global__ __launch_bounds__(kThreads) void dup_code_columns_kernel(int8_t* __restrict__ Wq, int64_t ldq,
+                                                                    int64_t N, int C, int g, int s,
+                                                                    const int32_t* __restrict__ chan_src) {
+    const int tail = (int)(ldq - (int64_t)C * g);                // appended + padding columns per row
+    const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (o >= N * tail) return;
+    const int64_t n = o / tail;
+    const int k = C * g + (int)(o - n * tail);
+    int8_t code = 0;
+    if (k < (C + s) * g) {
+        const int j = k / g, t = k - j * g;
+        int src = chan_src[j];
+        src = src < 0 ? 0 : (src >= C ? C - 1 : src);
+        code = Wq[n * ldq + (int64_t)src * g + t];
+    }
+    Wq[n * ldq + k] = code;
+}
+
+hipError_t launch_dup_code_columns(int8_t* Wq, int64_t ldq, int64_t N, int C, int g, int s,
+                                   const int32_t* chan_src, hipStream_t stream) {
+    const int64_t total = N * (ldq - (int64_t)C * g);
+    if (total <= 0) return hipSuccess;
+    dup_code_columns_kernel<<<dim3((unsigned)ceil_div(total, kThreads)), kThreads, 0, stream>>>(
+        Wq, ldq, N, C, g, s, chan_src);
+    return hipGetLastError();
+}
+
 // {T, T/qmax} from a device threshold: what the QA kernel needs when the threshold is given
 // (activation side: the selector's maximum of the plainly halved batch).
 __global__ void qa_scale_kernel(const float* __restrict__ thr, float qmax, float* __restrict__ scale_out) {

@@ -33,6 +33,7 @@ class ExpandedLayer:
         self.chan_src = torch.empty(E, **i32)
         self.chan_depth = torch.empty(E, **i32)
         self.chan_path = None      # uint32 bits, allocated by the first QA preparation
+        self._dup_base = None      # weight tensor whose codes sit in Wq's first C*g columns (Eq. 4)
         self.Wq = torch.empty((self.N, self.ldq), dtype=torch.int8, device=device)
         self.scale_w = torch.empty(2, dtype=torch.float32, device=device)
         self.scale_x = torch.empty(2, dtype=torch.float32, device=device)
@@ -57,6 +58,7 @@ class ExpandedLayer:
         of plain halves (Eq. 3); the activation side is the same either way."""
         assert W.dtype == torch.float32 and W.shape == (self.N, self.K)
         clip = self.clip_ratio_w if clip_ratio_w is None else float(clip_ratio_w)
+        self._dup_base = None
         if qa:
             if self.chan_path is None:
                 self.chan_path = torch.empty(self.C + self.s, dtype=torch.int32, device=self.device)
@@ -119,16 +121,22 @@ class ExpandedLayer:
 
     def forward_act_ocs(self, W, X, acc_out=None, stream=None, qa=False):
         """Activation OCS with the channel choice made on this batch (Eq. 4, Sec. 5.3).
-        qa: quantization-aware members on the activations (Sec. 3.3) instead of plain halves."""
+        qa: quantization-aware members on the activations (Sec. 3.3) instead of plain halves.
+        W's own codes are computed on the first call with a given tensor object and kept (an
+        in-place change of W needs prepare_weights() or a new tensor to be seen)."""
         M = X.shape[0]
         self._ensure_rows(M)
         xmax = torch.empty(1, dtype=torch.float32, device=self.device)
         B.ocs_select_channels(X, M, self.C, self.g, X.stride(0), self.s, self.split_src,
                               self.chan_src, self.chan_depth, xmax, self.ws_x, stream)
-        B.ocs_split_weights(W, self.N, self.C, self.g, W.stride(0), self.s, B.MODE_DUP,
-                            self.split_src, self.chan_src, self.chan_depth, None, 0, self.wmax,
-                            self.bits_w, self.clip_ratio_w, self.Wq, self.ldq, self.scale_w,
-                            self.ws_w, stream)
+        if self._dup_base is not W:
+            # once per weight tensor: its own codes in the first C*g columns (they do not depend
+            # on the batch's choice); afterwards only the appended columns are rewritten per batch
+            B.ocs_quantize(W, self.N, self.K, W.stride(0), self.bits_w, None, self.clip_ratio_w,
+                           self.Wq, self.ldq, self.scale_w, self.ws_w, stream)
+            self._dup_base = W
+        B.ocs_duplicate_weight_codes(self.Wq, self.ldq, self.N, self.C, self.g, self.s, self.chan_src,
+                                     stream)
         if qa:
             if self.chan_path is None:
                 self.chan_path = torch.empty(self.C + self.s, dtype=torch.int32, device=self.device)
