@@ -37,7 +37,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     float* vals = reinterpret_cast<float*>(smem);
     unsigned short* src = reinterpret_cast<unsigned short*>(vals + E);
     unsigned short* dep = src + E;
-    __shared__ unsigned long long wkey[kThreads / 64];
+    __shared__ unsigned long long wkey[2][kThreads / 64];
     __shared__ float red[kThreads];
     const int tid = threadIdx.x;
 
@@ -64,14 +64,21 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
             unsigned long long k = key_of(vals[j], j);
             local = k > local ? k : local;
         }
+        // One barrier per step: the waves exchange their maxima through wkey (two sets, used
+        // alternately, so that a fast wave cannot overwrite what a slow one still reads); every
+        // lane then knows the step's channel and value.  The lane that owns the split slot updates
+        // the list and re-scans its own slots; the lane that owns the new slot folds the new entry
+        // into its cached best from registers.  No lane reads a list entry another lane wrote
+        // during the same step, and later reads are separated from the write by a barrier.
         for (int i = 0; i < s; ++i) {
             const int cur = C + i;
             unsigned long long k = wave_max_u64(local);
-            if ((tid & 63) == 0) wkey[tid >> 6] = k;
+            unsigned long long* wk = wkey[i & 1];
+            if ((tid & 63) == 0) wk[tid >> 6] = k;
             __syncthreads();
-            k = wkey[0];
+            k = wk[0];
 #pragma unroll
-            for (int w = 1; w < kThreads / 64; ++w) k = wkey[w] > k ? wkey[w] : k;
+            for (int w = 1; w < kThreads / 64; ++w) k = wk[w] > k ? wk[w] : k;
             const int jstar = (int)(0xFFFFFFFFu - (unsigned)(k & 0xFFFFFFFFull));
             const float half = __uint_as_float((unsigned)(k >> 32)) * 0.5f;
             const bool owns_old = (jstar % kThreads) == tid;
@@ -84,11 +91,8 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
                 src[cur] = src[jstar];
                 dep[cur] = d;
                 split_src[i] = jstar;
-            }
-            __syncthreads();
-            if (owns_old || owns_new) {
-                // re-scan of this lane's slots: four independent LDS reads per trip, so their
-                // latencies overlap (with thousands of channels this loop is most of a step)
+                // re-scan of this lane's slots (the new slot too, if it is this lane's): four
+                // independent LDS reads per trip, so their latencies overlap
                 unsigned long long l0 = 0, l1 = 0, l2 = 0, l3 = 0;
                 int j = tid;
                 for (; j + 3 * kThreads <= cur; j += 4 * kThreads) {
@@ -109,8 +113,12 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
                 l0 = l0 > l1 ? l0 : l1;
                 l2 = l2 > l3 ? l2 : l3;
                 local = l0 > l2 ? l0 : l2;
+            } else if (owns_new) {
+                const unsigned long long kn = key_of(half, cur);
+                local = kn > local ? kn : local;
             }
         }
+        __syncthreads();
     } else {
         if (tid == 0) {
             for (int i = 0; i < s; ++i) {
