@@ -32,6 +32,9 @@
  *    and the consumers rely on those zeros.
  *  - fp32 inputs may have any leading dimension >= the row length; 16-byte aligned bases
  *    with a leading dimension that is a multiple of 4 take the vectorised path.
+ *  - `clip_ratio` (Sec. 4: the grid's threshold as a fraction of the largest magnitude) must be
+ *    positive and finite wherever the call derives the threshold itself: OCS_E_CLIP otherwise.
+ *    It is ignored when the caller passes a threshold.
  *  - NaN / Inf inputs give unspecified codes (no fault).  Index arrays read from device
  *    memory are clamped into range before use, so bad indices cannot cause a fault.
  *  - Two calls that share a workspace or an output must be ordered on one stream.
@@ -59,6 +62,7 @@ extern "C" {
 #define OCS_E_WORKSPACE (-7) /* workspace NULL or smaller than ocs_workspace_bytes()         */
 #define OCS_E_HIP (-8)       /* a HIP call failed; ocs_last_hip_error() has the text         */
 #define OCS_E_MODE (-9)      /* unknown mode                                                 */
+#define OCS_E_CLIP (-10)     /* clip_ratio is not a positive finite number                   */
 
 #define OCS_MODE_HALVE 0 /* choose channels on this tensor and halve both copies (Eq. 3)     */
 #define OCS_MODE_DUP 1   /* channel choice given; copy channels un-halved (Eq. 4, weights)   */

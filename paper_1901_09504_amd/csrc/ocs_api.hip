@@ -28,6 +28,8 @@ static int hip_fail(hipError_t e) {
 
 static bool bits_ok(int bits) { return bits >= 2 && bits <= 8; }
 static float qmax_of(int bits) { return (float)((1 << (bits - 1)) - 1); }
+// Sec. 4 clips at a fraction of the range; any positive finite factor gives a usable grid
+static bool clip_ok(float c) { return c > 0.0f && c <= 3.402823466e+38f; }
 static bool aligned(const void* p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a == 0; }
 
 static int check_codes(const void* q, int64_t ldq, int64_t cols) {
@@ -105,6 +107,7 @@ const char* ocs_strerror(int code) {
         case OCS_E_WORKSPACE: return "workspace NULL or smaller than ocs_workspace_bytes()";
         case OCS_E_HIP: return "a HIP call failed (see ocs_last_hip_error)";
         case OCS_E_MODE: return "unknown mode or key";
+        case OCS_E_CLIP: return "clip_ratio is not a positive finite number";
         default: return "unknown error code";
     }
 }
@@ -168,6 +171,7 @@ int ocs_split_weights(const float* W, int64_t N, int C, int g, int64_t ldw, int 
         rc = check_codes(Wq, ldq, Ke);
         if (rc) return rc;
         if (!bits_ok(bits)) return OCS_E_BITS;
+        if (!clip_ok(clip_ratio)) return OCS_E_CLIP;
     }
     rc = check_workspace(workspace, ws_bytes, N, K);
     if (rc) return rc;
@@ -220,6 +224,7 @@ int ocs_split_weights_qa(const float* W, int64_t N, int C, int g, int64_t ldw, i
         if (rc) return rc;
     }
     if (!bits_ok(bits)) return OCS_E_BITS;   // the step depends on the grid even without codes
+    if (!clip_ok(clip_ratio)) return OCS_E_CLIP;
     rc = check_workspace(workspace, ws_bytes, N, K);
     if (rc) return rc;
 
@@ -277,6 +282,7 @@ int ocs_quantize(const float* x, int64_t rows, int64_t cols, int64_t ldx, int bi
     int rc = check_codes(q, ldq, cols);
     if (rc) return rc;
     if (!bits_ok(bits)) return OCS_E_BITS;
+    if (!threshold && !clip_ok(clip_ratio)) return OCS_E_CLIP;
     const float qmax = qmax_of(bits);
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
@@ -308,6 +314,7 @@ int ocs_act_threshold(const float* X, int64_t M, int C, int g, int64_t ldx, cons
     int rc = check_layer(M, C, g, ldx, num_splits);
     if (rc) return rc;
     if (!bits_ok(bits)) return OCS_E_BITS;
+    if (!clip_ok(clip_ratio)) return OCS_E_CLIP;
     const int64_t K = (int64_t)C * g;
     rc = check_workspace(workspace, ws_bytes, M, K);
     if (rc) return rc;
@@ -370,6 +377,7 @@ int ocs_split_act(const float* X, int64_t M, int C, int g, int64_t ldx, const in
     rc = check_codes(Xq, ldq, Ke);
     if (rc) return rc;
     if (!bits_ok(bits)) return OCS_E_BITS;
+    if (!threshold && !clip_ok(clip_ratio)) return OCS_E_CLIP;
     const float qmax = qmax_of(bits);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (threshold == nullptr && chan_depth == nullptr) {

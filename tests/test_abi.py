@@ -115,7 +115,15 @@ def test_argument_errors_are_reported_without_a_device():
     # mode / key
     assert L.ocs_split_weights(A, 4, 4, 1, 4, 1, 7, A, A, A, None, 0, None, 8, 1.0, None, 0, None, A, ws, None) == -9
     assert L.ocs_tune(b"no_such_key", 1) == -9
-    for code in range(-9, 1):
+    # clip ratio
+    for bad in (0.0, -0.5, float("nan"), float("inf")):
+        assert L.ocs_quantize(A, 4, 4, 4, 8, None, bad, A, 64, A, A, ws, None) == -10
+        assert L.ocs_split_act(A, 4, 4, 1, 4, A, None, 1, 8, None, bad, A, 64, A, A, ws, None) == -10
+        assert L.ocs_act_threshold(A, 4, 4, 1, 4, A, None, 1, 8, bad, A, A, ws, None) == -10
+        assert L.ocs_split_weights(A, 4, 4, 1, 4, 1, 0, A, A, A, None, 0, None, 8, bad, A, 64, A, A, ws, None) == -10
+        assert L.ocs_split_weights_qa(A, 4, 4, 1, 4, 1, A, A, A, A, A, 8, 8, bad, None, 0, A, A, ws, None) == -10
+    assert L.ocs_quantize(A, 0, 4, 4, 8, A, -1.0, A, 64, A, A, ws, None) == -2   # a given threshold: the ratio is unused
+    for code in range(-10, 1):
         assert len(L.ocs_strerror(code)) > 1
     assert L.ocs_strerror(-99) == b"unknown error code"
 
