@@ -30,8 +30,8 @@
  *    multiple of OCS_CALIGN; ocs_qgemm additionally needs a multiple of OCS_KALIGN (its
  *    K-step).  The producer writes zeros into every pad column (columns (C+s)*g .. ld-1)
  *    and the consumers rely on those zeros.
- *  - fp32 inputs may have any leading dimension >= the row length; 16-byte aligned bases
- *    with a leading dimension that is a multiple of 4 take the vectorised path.
+ *  - fp32 inputs may have any leading dimension >= the row length and any float-aligned
+ *    base: rows are read with 16-byte loads at whatever alignment they have.
  *  - `clip_ratio` (Sec. 4: the grid's threshold as a fraction of the largest magnitude) must be
  *    positive and finite wherever the call derives the threshold itself: OCS_E_CLIP otherwise.
  *    It is ignored when the caller passes a threshold.

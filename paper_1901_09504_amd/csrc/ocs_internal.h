@@ -13,6 +13,10 @@ constexpr int kThreads = 256;      // every kernel here runs 256-thread workgrou
 constexpr int kMaxExpanded = 8000;  // C + s limit of the single-workgroup greedy selector
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+// Four consecutive floats at any float address.  Global memory serves a multi-dword access at
+// dword alignment, so rows whose length or base is not a multiple of 16 bytes (the 7x7 stem's
+// 147-float rows) take the same 16-byte loads as aligned ones.
+typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x16 __attribute__((ext_vector_type(16)));
 

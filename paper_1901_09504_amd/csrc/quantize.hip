@@ -57,7 +57,7 @@ __device__ __forceinline__ float pass_threshold(const float* thr, const float* p
 }
 
 template <bool NT>
-__device__ __forceinline__ f32x4 load4(const f32x4* p) {
+__device__ __forceinline__ f32x4 load4(const f32x4u* p) {
     if (NT) return __builtin_nontemporal_load(p);
     return *p;
 }
@@ -68,8 +68,8 @@ __device__ __forceinline__ f32x4 load4(const f32x4* p) {
 // whole chip works inside one compact window that slides over X front to back, which is the
 // access pattern HBM serves fastest (measured against row-per-wave and row-per-workgroup
 // layouts with LDS staging of the appended columns; those were 10-15 % slower).
-//   d <  main_units: the dword's four inputs are the contiguous, 16-byte aligned
-//                    X[r, 4d .. 4d+3] (main_units = 0 when X does not allow vector loads);
+//   d <  main_units: the dword's four inputs are the contiguous X[r, 4d .. 4d+3], one 16-byte
+//                    load at whatever alignment the row has (main_units = K / 4);
 //   d >= main_units: leftover columns, appended channels (their source values were fetched
 //                    moments ago by neighbouring lanes, so the re-read is served by the
 //                    caches, not by HBM) and the zero padding.
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
         if (o < total) {
             locate(o, row, d);
             if (d < main_units)
-                v = load4<NT>(reinterpret_cast<const f32x4*>(X + (int64_t)row * ldx) + d);
+                v = load4<NT>(reinterpret_cast<const f32x4u*>(X + (int64_t)row * ldx) + d);
         }
     };
 
@@ -234,8 +234,8 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
 // data (in the output-ordered kernel above the lanes that land on appended columns and on the
 // padding load nothing, which for narrow rows is half of them).  Lane (row, d) writes output
 // dword d of its row and, when d < TD = D - Q, also dword Q + d: an appended or padding dword,
-// whose sources it gathers from the same row.  Requires 16-byte loads of X (Q = K/4 groups
-// per row) and TD <= Q.
+// whose sources it gathers from the same row (the K % 4 leftover columns are among them).
+// Q = K/4 groups per row; requires 1 <= TD <= Q.
 template <bool HALVE, typename Index>
 __global__ __launch_bounds__(kThreads) void expand_quantize_in_kernel(
     const float* __restrict__ X, int64_t ldx, int64_t M, int C, int g, int s,
@@ -281,7 +281,7 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_in_kernel(
         d = 0;
         if (o < total) {
             locate(o, row, d);
-            v = *(reinterpret_cast<const f32x4*>(X + (int64_t)row * ldx) + d);
+            v = *(reinterpret_cast<const f32x4u*>(X + (int64_t)row * ldx) + d);
         }
     };
     auto fetch_tail = [&](Index o, Index row, int d, f32x4& tv) {
@@ -352,8 +352,8 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
                                   float* scale_out, hipStream_t stream, const float* partials,
                                   int n_partials, float clip_ratio) {
     const int64_t K = (int64_t)C * g;
-    const bool vec_ok = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 4 == 0);
-    const int main_units = vec_ok ? (int)(K / 4) : 0;
+    const bool vec_ok = true;   // 16-byte loads need only the float's own alignment
+    const int main_units = (int)(K / 4);
     const int D = (int)(ldq / 4);
     const int64_t total = M * D;
     const bool nt = tuning().act_nt != 0;
