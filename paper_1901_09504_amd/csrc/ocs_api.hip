@@ -583,6 +583,10 @@ int ocs_tune(const char* key, int value) {
     else if (!strcmp(key, "act_wide")) t.act_wide = value < 0 ? 0 : value;
     else if (!strcmp(key, "act_map")) t.act_map = value;
     else if (!strcmp(key, "gemm_tile")) t.gemm_tile = value;
+    else if (!strcmp(key, "max_flat")) t.max_flat = value;
+    else if (!strcmp(key, "max_grid")) t.max_grid = value;
+    else if (!strcmp(key, "max_un")) t.max_un = value;
+    else if (!strcmp(key, "max_bt")) t.max_bt = value;
     else return OCS_E_MODE;
     return OCS_OK;
 }

@@ -11,6 +11,7 @@ namespace ocs {
 
 constexpr int kThreads = 256;      // every kernel here runs 256-thread workgroups (4 wave64)
 constexpr int kMaxExpanded = 8000;  // C + s limit of the single-workgroup greedy selector
+constexpr int kFlatMaxGrid = 4096;  // most workgroups (= partial maxima) of the flat max|x| pass
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 // Four consecutive floats at any float address.  Global memory serves a multi-dword access at
@@ -38,7 +39,7 @@ ReducePlan plan_reduce(int64_t rows, int64_t cols, bool vec_ok);
 // Workspace layout (byte offsets from a 256-byte aligned base).
 struct Workspace {
     size_t colmax_off;   // float[round_up(cols, 64)]
-    size_t partial_off;  // float[row_blocks * (cols + 1)]
+    size_t partial_off;  // float[max(row_blocks * (cols + 1), kFlatMaxGrid)]
     size_t total;
 };
 Workspace plan_workspace(int64_t rows, int64_t cols);
@@ -204,6 +205,10 @@ struct Tuning {
     int act_wide = 0;   // force the 64-bit index variant of that pass (tests: tensors of 2^32 dwords do not fit a test)
     int act_nt = 0;     // non-temporal loads of X in that pass (off: appended columns re-read X through L2)
     int gemm_tile = -1;
+    int max_flat = -1;  // whole-tensor max|x| of a contiguous tensor as one flat stream (1), by columns (0), default (-1)
+    int max_grid = -1;  // workgroups of the flat pass
+    int max_un = -1;    // 16-byte loads in flight per lane in the flat pass (1, 2 or 4)
+    int max_bt = -1;    // threads per workgroup of the flat pass (256 or 1024)
 };
 Tuning& tuning();
 

@@ -40,7 +40,9 @@ Workspace plan_workspace(int64_t rows, int64_t cols) {
     int64_t rb = a.row_blocks > b.row_blocks ? a.row_blocks : b.row_blocks;
     w.colmax_off = 0;
     w.partial_off = (size_t)round_up(round_up(cols, 64) * 4, 256);
-    w.total = w.partial_off + (size_t)round_up(rb * (cols + 1) * 4, 256);
+    int64_t entries = rb * (cols + 1);
+    if (entries < kFlatMaxGrid) entries = kFlatMaxGrid;
+    w.total = w.partial_off + (size_t)round_up(entries * 4, 256);
     return w;
 }
 
@@ -105,6 +107,48 @@ __global__ __launch_bounds__(kThreads) void colmax_partial_kernel(
         float* dst = partial + (int64_t)blockIdx.y * out_cols + col0 + u * VEC;
 #pragma unroll
         for (int e = 0; e < VEC; ++e) dst[e] = acc[e];
+    }
+}
+
+// max|x| of a contiguous tensor as ONE flat stream: lane i of the grid reads 16-byte groups
+// i, i + G, i + 2G, ..., UN of them in flight, so that at any moment the chip reads one
+// compact window that slides over the tensor.  A read-only stream is fastest with about 8 MB
+// in flight (measured on 0.4 to 1.8 GB buffers: 6.1 TB/s; with four times as much in flight
+// 5.2-5.5 TB/s), which the row-block layout of the column pass above does not give.  One
+// value per workgroup, partial[blockIdx.x], and few workgroups (one of 1024 lanes per CU): the
+// pass that follows folds the partial maxima once per workgroup of its own, and 2000 of them
+// cost it 1.3 us more than 256 do.
+template <int UN, int BT>
+__global__ __launch_bounds__(BT) void absmax_flat_kernel(const float* __restrict__ x, int64_t n,
+                                                         float* __restrict__ partial) {
+    __shared__ float red[BT / 64];
+    const f32x4u* x4 = reinterpret_cast<const f32x4u*>(x);
+    const int64_t n4 = n / 4;
+    const int64_t stride = (int64_t)gridDim.x * BT;
+    float m = 0.0f;
+    int64_t i = (int64_t)blockIdx.x * BT + threadIdx.x;
+    for (; i + (UN - 1) * stride < n4; i += UN * stride) {
+        f32x4 v[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) v[u] = x4[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < UN; ++u)
+            m = fmaxf(fmaxf(fmaxf(m, fabsf(v[u][0])), fmaxf(fabsf(v[u][1]), fabsf(v[u][2]))), fabsf(v[u][3]));
+    }
+    for (; i < n4; i += stride) {
+        const f32x4 v = x4[i];
+        m = fmaxf(fmaxf(fmaxf(m, fabsf(v[0])), fmaxf(fabsf(v[1]), fabsf(v[2]))), fabsf(v[3]));
+    }
+    // the n % 4 last elements
+    if (blockIdx.x == 0 && threadIdx.x < (unsigned)(n - 4 * n4)) m = fmaxf(m, fabsf(x[4 * n4 + threadIdx.x]));
+    const unsigned w = wave_umax32(__float_as_uint(m));   // magnitudes: non-negative, order like unsigned
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = __uint_as_float(w);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float r = red[0];
+#pragma unroll
+        for (int k = 1; k < BT / 64; ++k) r = fmaxf(r, red[k]);
+        partial[blockIdx.x] = r;
     }
 }
 
@@ -201,8 +245,34 @@ __global__ __launch_bounds__(kThreads) void threshold_scalar_kernel(const float*
     }
 }
 
+// The flat pass when the tensor is one contiguous range (ld == cols); *entries = workgroups.
+static bool launch_absmax_flat(const float* T, int64_t rows, int64_t cols, int64_t ld, float* partial,
+                               int* entries, hipStream_t stream, hipError_t* err) {
+    const int want = tuning().max_flat;
+    if (ld != cols || want == 0) return false;
+    const int64_t n = rows * cols;
+    const int bt = tuning().max_bt == 256 ? 256 : 1024;
+    int64_t grid = tuning().max_grid > 0 ? tuning().max_grid : 256;
+    if (grid > kFlatMaxGrid) grid = kFlatMaxGrid;
+    if (grid > ceil_div(ceil_div(n, 4), bt)) grid = ceil_div(ceil_div(n, 4), bt);
+    if (grid < 1) grid = 1;
+    const int un = tuning().max_un < 0 ? 2 : tuning().max_un;
+    const dim3 g((unsigned)grid), b(bt);
+#define OCS_FLAT(U, T_) *err = launch_kernel(kTimeAbsmax, absmax_flat_kernel<U, T_>, g, b, 0, stream, T, n, partial)
+    if (bt == 256) {
+        if (un == 4) OCS_FLAT(4, 256); else if (un == 2) OCS_FLAT(2, 256); else OCS_FLAT(1, 256);
+    } else {
+        if (un == 4) OCS_FLAT(4, 1024); else if (un == 2) OCS_FLAT(2, 1024); else OCS_FLAT(1, 1024);
+    }
+#undef OCS_FLAT
+    if (entries) *entries = (int)grid;
+    return true;
+}
+
 hipError_t launch_absmax_partials(const float* T, int64_t rows, int64_t cols, int64_t ld,
                                   float* partial, int* entries, hipStream_t stream) {
+    hipError_t fe = hipSuccess;
+    if (launch_absmax_flat(T, rows, cols, ld, partial, entries, stream, &fe)) return fe;
     const bool vec_ok = true;   // 16-byte loads at the float's own alignment (f32x4u)
     ReducePlan p = plan_reduce(rows, cols, vec_ok);
     return launch_partials(T, rows, cols, ld, partial, true, p, entries, stream);
@@ -214,7 +284,9 @@ hipError_t launch_absmax_threshold(const float* T, int64_t rows, int64_t cols, i
     const bool vec_ok = true;   // 16-byte loads at the float's own alignment (f32x4u)
     ReducePlan p = plan_reduce(rows, cols, vec_ok);
     int n = 0;
-    hipError_t e = launch_partials(T, rows, cols, ld, partial, true, p, &n, stream);
+    hipError_t e = hipSuccess;
+    if (!launch_absmax_flat(T, rows, cols, ld, partial, &n, stream, &e))
+        e = launch_partials(T, rows, cols, ld, partial, true, p, &n, stream);
     if (e != hipSuccess) return e;
     threshold_scalar_kernel<<<1, kThreads, 0, stream>>>(partial, n, clip_ratio, qmax, scale_out);
     return hipGetLastError();

@@ -50,6 +50,26 @@ def test_quantize_dynamic(rows, cols, bits, act_map):
     assert np.array_equal(q, q_ref)
 
 
+@pytest.mark.parametrize("rows,cols", [(1, 1), (1, 3), (3, 5), (7, 65), (33, 147), (130, 269), (257, 1023),
+                                       (1031, 1030), (4100, 517)])
+@pytest.mark.parametrize("variant", [(0, 256, 1), (1, 256, 1), (1, 256, 4), (1, 1024, 1), (1, 1024, 2), (1, 1024, 4)])
+def test_absmax_pass_variants(rows, cols, variant):
+    """max|x| of a contiguous tensor: the column pass and every shape of the flat pass give the
+    oracle's grid (the largest magnitude sits in the last, partly filled group of four)."""
+    flat, bt, un = variant
+    rng = np.random.default_rng(rows * 31 + cols)
+    x = _tensor(rng, rows, cols, "normal")
+    x[-1, -1] = -9.5
+    q_ref, s_ref = ref.quantize(x, 8, ldq=B.ocs_padded_cols(cols))
+    B.ocs_tune("max_flat", flat); B.ocs_tune("max_bt", bt); B.ocs_tune("max_un", un)
+    try:
+        q, s = gpu_quantize(x, 8)
+    finally:
+        B.ocs_tune("max_flat", -1); B.ocs_tune("max_bt", -1); B.ocs_tune("max_un", -1)
+    assert np.array_equal(s, s_ref)
+    assert np.array_equal(q, q_ref)
+
+
 @pytest.mark.parametrize("kind,threshold,clip", [("ties", 16.0, 1.0), ("ties", 15.0, 1.0), ("normal", None, 0.8),
                                                   ("normal", 2.5, 1.0), ("zero", None, 1.0), ("zero", 0.0, 1.0),
                                                   ("heavy", None, 0.3)])
