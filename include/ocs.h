@@ -50,6 +50,8 @@ extern "C" {
 #endif
 
 #define OCS_KALIGN 64 /* leading dimension of the code tensors ocs_qgemm reads is a multiple of this */
+#define OCS_ROWALIGN 128 /* what ocs_padded_cols rounds to: rows then start on cache-line boundaries
+                            and ocs_qgemm can walk K in 128-byte steps (the zero padding joins in) */
 #define OCS_CALIGN 16 /* leading dimension of any int8 code tensor is a multiple of this */
 
 #define OCS_OK 0
@@ -84,8 +86,17 @@ int ocs_num_splits(int C, double r);
 /* Bytes per pixel of un-lowered activation codes for ocs_qconv: channels rounded up to OCS_CALIGN. */
 int64_t ocs_padded_channels(int64_t channels);
 
-/* Leading dimension of the code tensor of an expanded layer: (C+s)*g rounded up to OCS_KALIGN. */
+/*
+ * Recommended leading dimension of the code tensor of an expanded layer: (C+s)*g rounded up to
+ * OCS_ROWALIGN (to OCS_KALIGN for rows of at most 320 bytes, which the GEMM streams once: there
+ * padding only adds bytes).  Any multiple of OCS_KALIGN that holds the row is accepted by
+ * ocs_qgemm; with this one the rows of both operands are whole cache lines, which measured 10 %
+ * (operands in cache) to 25 % (operands in HBM) faster on the 3x3 layer shapes.
+ */
 int64_t ocs_padded_cols(int64_t cols);
+
+/* Row length of the tap-major weight tensor of ocs_qconv: g*ldc rounded up to OCS_KALIGN. */
+int64_t ocs_conv_weight_cols(int g, int64_t ldc);
 
 /*
  * Scratch bytes that any call below needs for a tensor of `rows` x `cols` fp32 elements

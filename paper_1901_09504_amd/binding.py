@@ -48,6 +48,8 @@ def lib():
     L.ocs_num_splits.argtypes = [_i32, C.c_double]
     L.ocs_padded_cols.restype = _i64
     L.ocs_padded_cols.argtypes = [_i64]
+    L.ocs_conv_weight_cols.restype = _i64
+    L.ocs_conv_weight_cols.argtypes = [C.c_int, _i64]
     L.ocs_padded_channels.restype = _i64
     L.ocs_padded_channels.argtypes = [_i64]
     L.ocs_workspace_bytes.restype = _sz
@@ -129,6 +131,10 @@ def ocs_num_splits(Cn, r):
 
 def ocs_padded_cols(cols):
     return int(lib().ocs_padded_cols(int(cols)))
+
+
+def ocs_conv_weight_cols(g, ldc):
+    return int(lib().ocs_conv_weight_cols(int(g), int(ldc)))
 
 
 def ocs_padded_channels(channels):

@@ -371,15 +371,20 @@ struct ConvGeom {
     int64_t ldc;
 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF, bool CONV = false>
-__global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF, bool CONV = false, int KG = 1>
+__global__ __launch_bounds__(WAVES_M * WAVES_N * 64 * KG) void qgemm_dma_kernel(
     const int8_t* __restrict__ Xq, int64_t ldx, const int8_t* __restrict__ Wq, int64_t ldw, int M,
     int N, int ksteps, const float* __restrict__ scale_x, const float* __restrict__ scale_w,
     int32_t* __restrict__ acc_out, int64_t ldacc, float* __restrict__ Y, int64_t ldy, int tiles_n,
     unsigned total_tiles, ConvGeom cg, Requant rq) {
-    constexpr int NW = WAVES_M * WAVES_N;  // waves per workgroup (4, 8 or 16)
+    // KG = 2: the workgroup is two such groups of waves, each with a ring of its own, which share
+    // the tile and split its K-steps between them (group g takes steps g, g + 2, ...); their
+    // accumulators meet in LDS before the epilogue.  For shapes with fewer tiles than CUs and a
+    // long K: twice the waves issue operand requests on every busy CU.
+    constexpr int NW = WAVES_M * WAVES_N;  // waves per group (4, 8 or 16)
     constexpr int NT = NW * 64;
     static_assert(NW == 4 || NW == 8 || NW == 16, "4, 8 or 16 waves");
+    static_assert(KG == 1 || (KG == 2 && !CONV && NW <= 8), "two K groups: plain GEMM, 16 waves in all");
     static_assert(BK == 64 || BK == 128, "K-step of 64 or 128 bytes");
     static_assert(NBUF >= 3, "ring of at least three buffers");
     constexpr int CPR = BK / 16;
@@ -393,13 +398,14 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
 
     // one array: the A ring, then the B ring; the epilogue reuses all of it
     constexpr int RING_BYTES = NBUF * (BM + BN) * BK;
-    __shared__ __align__(1024) int8_t lds[RING_BYTES];
+    __shared__ __align__(1024) int8_t lds[KG * RING_BYTES];
     __shared__ int dup_list[kDupCap];
     __shared__ int dup_count;
-    int8_t (*lds_a)[BM * BK] = reinterpret_cast<int8_t (*)[BM * BK]>(&lds[0]);
-    int8_t (*lds_b)[BN * BK] = reinterpret_cast<int8_t (*)[BN * BK]>(&lds[NBUF * BM * BK]);
+    const int grp = KG > 1 ? (int)threadIdx.x / NT : 0;   // wave-uniform
+    int8_t (*lds_a)[BM * BK] = reinterpret_cast<int8_t (*)[BM * BK]>(&lds[grp * RING_BYTES]);
+    int8_t (*lds_b)[BN * BK] = reinterpret_cast<int8_t (*)[BN * BK]>(&lds[grp * RING_BYTES + NBUF * BM * BK]);
 
-    const int tid = threadIdx.x;
+    const int tid = (int)threadIdx.x - grp * NT;   // thread, lane and wave inside the group
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
@@ -478,6 +484,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
 #endif
     };
     auto fetch = [&](int kt, int buf) {   // K index clamped: surplus steps refetch the last one
+        kt = kt * KG + grp;                // the group's kt-th step
         const int kl = kt < ksteps ? kt : ksteps - 1;
         const int64_t koff = (int64_t)kl * BK;
         if (CONV) {
@@ -563,28 +570,54 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
                 read_slice((buf + 1) % NBUF, 0, af[0], bf[0]);
             }
             __builtin_amdgcn_sched_barrier(0);
-            multiply(af[ks & 1], bf[ks & 1]);
+            // (with an odd number of K-steps the second group's last step has nothing to add;
+            // it still takes the step's barrier)
+            if (KG == 1 || kt * KG + grp < ksteps) multiply(af[ks & 1], bf[ks & 1]);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
 #pragma unroll
     for (int p = 0; p < NBUF - 1; ++p) fetch(p, p);
-    build_dup_list<NT>(rq, N, col0, BN, dup_list, &dup_count);   // behind the first requests
+    build_dup_list<NT * KG>(rq, N, col0, BN, dup_list, &dup_count);   // behind the first requests
     wait_vmcnt<(NBUF - 2) * LPS>();
     __syncthreads();
     read_slice(0, 0, af[0], bf[0]);
 
+    const int gsteps = (ksteps + KG - 1) / KG;   // steps per group (the same count for both)
     int kt0 = 0;
-    for (; kt0 + NBUF <= ksteps; kt0 += NBUF) {
+    for (; kt0 + NBUF <= gsteps; kt0 += NBUF) {
 #pragma unroll
         for (int p = 0; p < NBUF; ++p) step(p, kt0 + p);
     }
 #pragma unroll
     for (int p = 0; p < NBUF; ++p)
-        if (kt0 + p < ksteps) step(p, kt0 + p);
+        if (kt0 + p < gsteps) step(p, kt0 + p);
     wait_vmcnt<0>();  // surplus (clamped) loads must land before the ring is reused below
-    __syncthreads();  // every wave has read its last fragments: the ring is free
+    __syncthreads();  // every wave has read its last fragments: the rings are free
+
+    if constexpr (KG > 1) {
+        // the second group hands its accumulators over through its own (free) ring, lane-major:
+        // conflict-free on both sides; wave w of the first group adds wave w's of the second
+        static_assert(RING_BYTES >= NW * TM * TN * 16 * 64 * 4, "ring too small for the hand-over");
+        int32_t* xch = reinterpret_cast<int32_t*>(&lds[RING_BYTES]) + wave * (TM * TN * 16 * 64) + lane;
+        if (grp == 1) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) xch[((i * TN + j) * 16 + v) * 64] = acc[i][j][v];
+        }
+        __syncthreads();
+        if (grp == 1) return;   // no barrier follows
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] += xch[((i * TN + j) * 16 + v) * 64];
+    }
 
     // Epilogue.  An accumulator block leaves the MFMA with lane l holding ONE column and 16
     // rows, which as stores would be 4 bytes per lane (measured: a CU retires such stores at
@@ -598,7 +631,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
     static_assert(WAVE_STAGE % 16 == 0, "staging area must keep 16-byte alignment");
     int32_t* stage = reinterpret_cast<int32_t*>(&lds[wave * WAVE_STAGE]);
     const float scale = scale_x[1] * scale_w[1];
-    const float inv = requant_inv(rq, blockIdx.x == 0 && tid == 0);
+    const float inv = requant_inv(rq, blockIdx.x == 0 && threadIdx.x == 0);
     const int dup_n = (rq.Yq != nullptr && rq.s_next > 0) ? (dup_count < kDupCap ? dup_count : kDupCap) : 0;
     const bool vec_y = (reinterpret_cast<uintptr_t>(Y) % 16 == 0) && (ldy % 4 == 0);
     const bool vec_a = acc_out != nullptr && (reinterpret_cast<uintptr_t>(acc_out) % 16 == 0) &&
@@ -647,7 +680,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_wholek_kernel(
     const int8_t* __restrict__ Xq, int64_t ldx, const int8_t* __restrict__ Wq, int64_t ldw, int M,
     int N, int ksteps, const float* __restrict__ scale_x, const float* __restrict__ scale_w,
     int32_t* __restrict__ acc_out, int64_t ldacc, float* __restrict__ Y, int64_t ldy, int tiles_n,
-    unsigned total_tiles, Requant rq) {
+    unsigned total_tiles, int dup_off, Requant rq) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int TM = WM / 32, TN = WN / 32;
@@ -657,9 +690,12 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_wholek_kernel(
     static_assert(BM % 16 == 0 && BN % 16 == 0, "a 1 KB piece must not straddle the operands");
     static_assert(WM % 32 == 0 && WN % 32 == 0 && TM >= 1 && TN >= 1, "wave tile of 32x32 blocks");
 
+    // No static LDS here: at 320 bytes of K a 128x128 tile's operands are exactly half of a
+    // CU's LDS, and a few bytes more would halve the workgroups a CU holds.  The table of the
+    // next layer's copies follows the operands, and only when the epilogue needs it.
     extern __shared__ __align__(1024) int8_t dlds[];
-    __shared__ int dup_list[kDupCap];
-    __shared__ int dup_count;
+    int* dup_list = reinterpret_cast<int*>(&dlds[dup_off]);   // used only when dup_off > 0
+    int* dup_count = dup_list + kDupCap;
 #if defined(__HIP_DEVICE_COMPILE__)
     typedef __attribute__((address_space(3))) int8_t* lptr_t;
     const unsigned lds0 = (unsigned)(uintptr_t)(lptr_t)&dlds[0];
@@ -699,7 +735,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_wholek_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-    build_dup_list<NW * 64>(rq, N, col0, BN, dup_list, &dup_count);   // behind the requests
+    if (dup_off > 0) build_dup_list<NW * 64>(rq, N, col0, BN, dup_list, dup_count);   // behind the requests
     wait_vmcnt<0>();
     __syncthreads();
 
@@ -735,7 +771,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_wholek_kernel(
     int32_t* stage = reinterpret_cast<int32_t*>(&dlds[wave * (8 * WN * 4)]);
     const float scale = scale_x[1] * scale_w[1];
     const float inv = requant_inv(rq, blockIdx.x == 0 && tid == 0);
-    const int dup_n = (rq.Yq != nullptr && rq.s_next > 0) ? (dup_count < kDupCap ? dup_count : kDupCap) : 0;
+    const int dup_n = dup_off > 0 ? (*dup_count < kDupCap ? *dup_count : kDupCap) : 0;
     const bool vec_y = (reinterpret_cast<uintptr_t>(Y) % 16 == 0) && (ldy % 4 == 0);
     const bool vec_a = acc_out != nullptr && (reinterpret_cast<uintptr_t>(acc_out) % 16 == 0) &&
                        (ldacc % 4 == 0);
@@ -759,13 +795,23 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_wholek_kernel(
     }
 }
 
-constexpr int64_t kWholeKMaxLds = 156 * 1024;  // LDS of one CU less the static tables
+constexpr int64_t kWholeKMaxLds = 160 * 1024;  // LDS of one CU
 
+// Dynamic LDS of a whole-K launch: operands (or the epilogue's staging area, if larger) and,
+// when the output goes to the next layer as codes with copies, the table of those copies
+// behind them (*dup_off = its byte offset, 0 = none).
 template <int BM, int BN, int WAVES_M, int WAVES_N>
-static int64_t wholek_lds_bytes(int64_t Kpad) {
+static int64_t wholek_lds_bytes(int64_t Kpad, const Requant& rq, int* dup_off = nullptr) {
     const int64_t operands = (Kpad / 64) * (BM + BN) * 64;
     const int64_t staging = (int64_t)WAVES_M * WAVES_N * 8 * (BN / WAVES_N) * 4;
-    return operands > staging ? operands : staging;
+    int64_t lds = operands > staging ? operands : staging;
+    int off = 0;
+    if (rq.Yq != nullptr && rq.s_next > 0) {
+        off = (int)round_up(lds, 16);
+        lds = off + (kDupCap + 1) * 4;
+    }
+    if (dup_off) *dup_off = off;
+    return lds;
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N>
@@ -773,7 +819,8 @@ static hipError_t run_wholek(const int8_t* Xq, int64_t ldx, const int8_t* Wq, in
                              int64_t M, int64_t N, int64_t Kpad, const float* scale_x,
                              const float* scale_w, int32_t* acc_out, int64_t ldacc, float* Y,
                              int64_t ldy, hipStream_t stream, const Requant& rq) {
-    const int64_t lds = wholek_lds_bytes<BM, BN, WAVES_M, WAVES_N>(Kpad);
+    int dup_off = 0;
+    const int64_t lds = wholek_lds_bytes<BM, BN, WAVES_M, WAVES_N>(Kpad, rq, &dup_off);
     if (Kpad < 64 || Kpad % 64 != 0 || lds > kWholeKMaxLds) return hipErrorInvalidValue;
     // more than 64 KB of dynamic LDS has to be opted into, once per kernel
     static bool opted_in = false;
@@ -789,10 +836,10 @@ static hipError_t run_wholek(const int8_t* Xq, int64_t ldx, const int8_t* Wq, in
     return launch_kernel(kTimeGemm, qgemm_wholek_kernel<BM, BN, WAVES_M, WAVES_N>,
                          dim3((unsigned)total), dim3(WAVES_M * WAVES_N * 64), (unsigned)lds, stream,
                          Xq, ldx, Wq, ldw, (int)M, (int)N, (int)(Kpad / 64), scale_x, scale_w,
-                         acc_out, ldacc, Y, ldy, (int)tiles_n, (unsigned)total, rq);
+                         acc_out, ldacc, Y, ldy, (int)tiles_n, (unsigned)total, dup_off, rq);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF, int KG = 1>
 static hipError_t run_dma(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
                           int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,
                           int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy,
@@ -801,8 +848,8 @@ static hipError_t run_dma(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64
     if (Kpad < BK || Kpad % BK != 0) return hipErrorInvalidValue;
     const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
     const int64_t total = tiles_m * tiles_n;
-    return launch_kernel(kTimeGemm, qgemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, BK, NBUF>,
-                         dim3((unsigned)total), dim3(WAVES_M * WAVES_N * 64), 0, stream, Xq, ldx, Wq, ldw, (int)M,
+    return launch_kernel(kTimeGemm, qgemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, BK, NBUF, false, KG>,
+                         dim3((unsigned)total), dim3(WAVES_M * WAVES_N * 64 * KG), 0, stream, Xq, ldx, Wq, ldw, (int)M,
                          (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y, ldy,
                          (int)tiles_n, (unsigned)total, ConvGeom{}, rq);
 }
@@ -909,6 +956,7 @@ static hipError_t run(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t l
 
 #define OCS_GEMM_ARGS_F32 Xq, ldx, Wq, ldw, M, N, Kpad, scale_x, scale_w, acc_out, ldacc, Y, ldy, stream
 #define OCS_GEMM_ARGS OCS_GEMM_ARGS_F32, rq
+#define OCS_GEMM_ARGS128 Xq, ldx, Wq, ldw, M, N, K128, scale_x, scale_w, acc_out, ldacc, Y, ldy, stream, rq
 
 hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
                         int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,
@@ -916,31 +964,39 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
                         hipStream_t stream, const Requant& rq) {
     int tile = tuning().gemm_tile;
     if (tile < 0) {
-        // Measured on MI355X.  A CU draws operands through its vector-memory path at only
-        // ~16-30 B/clk, rising with the number of waves that issue loads: the largest tile that
-        // still gives most CUs a workgroup wins, and workgroups of 8 waves beat 4.  Up to 320
-        // bytes of K the layer is a stream of output rows and the whole-K kernel wins (1.2-1.5x).
+        // Measured on MI355X over the layer shapes of the paper's networks.  A CU draws operands
+        // through its vector-memory path at only ~16-30 B/clk, rising with the number of waves
+        // that issue loads: the largest tile that still gives most CUs a workgroup wins, and
+        // workgroups of 8 waves beat 4.  Up to 320 bytes of K the layer is a stream of output
+        // rows and the whole-K kernel wins (1.2-1.5x), except that a very wide N is better served
+        // by the ring kernel's tile order (one L2 fill of an X row panel for all its N tiles).
+        // With N >= 256 and enough tiles, 256 columns per tile halve the reads of X.
         const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 128);
         const int64_t t128 = ceil_div(M, 128) * ceil_div(N, 128);
         const int64_t t256sq = ceil_div(M, 256) * ceil_div(N, 256);
-        if (Kpad <= 320) tile = (N <= 64 && Kpad > 128) ? 17 : 16;
+        if (Kpad <= 320) tile = N <= 64 ? 17 : (N >= 1024 ? 9 : (N >= 512 ? 19 : 16));
         else if (N <= 64) tile = 6;
-        else if (t256sq >= 512 && Kpad >= 2048) tile = 12;  // two full rounds of the largest tile
+        else if (N >= 256 && t256sq >= 192 && Kpad >= 1024) tile = 12;
+        else if (N >= 1024 && Kpad < 1024) tile = 9;
+        else if (N >= 256 && t256sq >= 512) tile = 12;
         else if (t256 >= 128) tile = 11;
-        else if (t128 >= 48) tile = 9;
+        else if (t128 >= 48) tile = 23;   // 128-byte K-steps when the operands allow them
         else tile = 6;
     }
-    // a 128-byte K-step needs the K extent to be a multiple of 128
-    const bool k128 = Kpad % 128 == 0;
+    // A 128-byte K-step needs a K extent that is a multiple of 128.  The extent is the codes
+    // rounded up to 64; when both leading dimensions hold 64 bytes more, those are zero padding
+    // on both operands (the producers' contract) and the walk may include them.
+    const int64_t K128 = round_up(Kpad, 128);
+    const bool k128 = K128 == Kpad || (ldx >= K128 && ldw >= K128);
     switch (tile) {
         case 0: if (rq.Yq == nullptr) return run<128, 128, 2, 2, 64, 6>(OCS_GEMM_ARGS_F32);  // register-staged
                 return run_dma<128, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS);
         case 1: if (rq.Yq == nullptr) return run<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS_F32);   // register-staged
                 return run_dma<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
         case 2: return run_dma<128, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS);
-        case 3: return k128 ? run_dma<128, 128, 2, 2, 128, 3>(OCS_GEMM_ARGS)
+        case 3: return k128 ? run_dma<128, 128, 2, 2, 128, 3>(OCS_GEMM_ARGS128)
                             : run_dma<128, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS);
-        case 4: return k128 ? run_dma<256, 128, 2, 2, 128, 3>(OCS_GEMM_ARGS)
+        case 4: return k128 ? run_dma<256, 128, 2, 2, 128, 3>(OCS_GEMM_ARGS128)
                             : run_dma<256, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS);
         case 5: return run_dma<256, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS);
         case 6: return run_dma<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
@@ -948,16 +1004,16 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
         case 8: return run_dma<128, 128, 2, 4, 64, 4>(OCS_GEMM_ARGS);    // 8 waves
         case 9: return run_dma<128, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);    // 8 waves
         case 10: return run_dma<256, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);   // 8 waves
-        case 11: return k128 ? run_dma<256, 128, 4, 2, 128, 3>(OCS_GEMM_ARGS)  // 8 waves
+        case 11: return k128 ? run_dma<256, 128, 4, 2, 128, 3>(OCS_GEMM_ARGS128)  // 8 waves
                              : run_dma<256, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);
         case 12: return run_dma<256, 256, 2, 4, 64, 4>(OCS_GEMM_ARGS);   // 8 waves
         case 13: return run_dma<256, 256, 4, 2, 64, 4>(OCS_GEMM_ARGS);   // 8 waves
         case 14: return run_dma<256, 256, 4, 4, 64, 4>(OCS_GEMM_ARGS);   // 16 waves
-        case 15: return k128 ? run_dma<256, 128, 4, 4, 128, 3>(OCS_GEMM_ARGS)  // 16 waves
+        case 15: return k128 ? run_dma<256, 128, 4, 4, 128, 3>(OCS_GEMM_ARGS128)  // 16 waves
                              : run_dma<256, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);
         // whole-K variants; a K extent too long for them falls back to a ring variant
 #define OCS_WHOLEK(BM_, BN_, WM_, WN_, FALLBACK)                                                   \
-    (wholek_lds_bytes<BM_, BN_, WM_, WN_>(Kpad) <= kWholeKMaxLds                                    \
+    (wholek_lds_bytes<BM_, BN_, WM_, WN_>(Kpad, rq) <= kWholeKMaxLds                                   \
          ? run_wholek<BM_, BN_, WM_, WN_>(OCS_GEMM_ARGS)                                            \
          : FALLBACK)
         case 16: return OCS_WHOLEK(128, 128, 4, 2, (run_dma<128, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS)));
@@ -967,6 +1023,14 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
         case 20: return OCS_WHOLEK(256, 128, 4, 2, (run_dma<256, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS)));
         case 21: return OCS_WHOLEK(128, 128, 2, 2, (run_dma<128, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS)));
 #undef OCS_WHOLEK
+        // two K groups per workgroup (16 waves)
+        case 22: return run_dma<128, 128, 4, 2, 64, 4, 2>(OCS_GEMM_ARGS);
+        case 23: return k128 ? run_dma<128, 128, 4, 2, 128, 3>(OCS_GEMM_ARGS128)
+                             : run_dma<128, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);
+        case 24: return k128 ? run_dma<128, 128, 4, 2, 128, 4>(OCS_GEMM_ARGS128)
+                             : run_dma<128, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);
+        case 25: return run_dma<128, 128, 4, 2, 64, 6>(OCS_GEMM_ARGS);
+        case 26: return run_dma<128, 128, 4, 2, 64, 8>(OCS_GEMM_ARGS);
         default: return run_dma<64, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
     }
 }

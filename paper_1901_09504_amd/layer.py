@@ -169,7 +169,7 @@ class ExpandedConv:
         self.N, self.C, self.s = self.w.N, self.w.C, self.w.s
         self.E = self.C + self.s
         self.ldc = B.ocs_padded_channels(self.E)
-        self.ldt = B.ocs_padded_cols(self.g * self.ldc)
+        self.ldt = B.ocs_conv_weight_cols(self.g, self.ldc)
         self.Wt = torch.empty((self.N + 1, self.ldt), dtype=torch.int8, device=device)
         self.scale_x = torch.empty(2, dtype=torch.float32, device=device)
         self.device = device

@@ -133,7 +133,7 @@ def gpu_conv_layer(A, Wm, Cn, kh, kw, stride, pad, s, bits_x=8, bits_w=8, thresh
     wts = gpu_split_weights(Wm, Cn, g, s, bits=bits_w, want_f32=False)
     ldc = B.ocs_padded_channels(E)
     Wq = dev(wts["Wq"])
-    Wt = torch.full(((N + 1), B.ocs_padded_cols(g * ldc)), 77, dtype=torch.int8, device="cuda")
+    Wt = torch.full(((N + 1), B.ocs_conv_weight_cols(g, ldc)), 77, dtype=torch.int8, device="cuda")
     B.ocs_conv_weights_tap_major(Wq, N, E, g, Wq.stride(0), Wt, ldc)
     Aq, sx = gpu_split_act(A.reshape(-1, Cn), Cn, 1, wts["chan_src"], None, s, bits_x, threshold=threshold,
                            ldq=ldc)

@@ -37,9 +37,10 @@ def test_num_splits_matches_oracle_everywhere():
 
 
 def test_padded_cols_and_workspace():
-    assert B.ocs_padded_cols(2358) == 2368
+    assert B.ocs_padded_cols(2358) == 2432
+    assert B.ocs_conv_weight_cols(9, 272) == 2496 and B.ocs_conv_weight_cols(0, 16) == 0
     assert B.ocs_padded_channels(262) == 272 and B.ocs_padded_channels(4) == 16
-    assert B.ocs_padded_cols(64) == 64 and B.ocs_padded_cols(65) == 128 and B.ocs_padded_cols(0) == 0
+    assert B.ocs_padded_cols(64) == 64 and B.ocs_padded_cols(269) == 320 and B.ocs_padded_cols(321) == 384 and B.ocs_padded_cols(0) == 0
     assert B.ocs_workspace_bytes(0, 10) == 0
     for rows, cols in [(1, 1), (64, 256), (12544, 2304), (6000, 3000), (3211264, 147), (802816, 64)]:
         wb = B.ocs_workspace_bytes(rows, cols)

@@ -111,7 +111,7 @@ def test_quantize_scalar_sequence_sweep():
 
 def test_quantize_denormals():
     x = np.array([[1e-40, -3e-39, 1e-38, 0.0, 5e-45, -1.4e-45, 2e-38, 1.1754944e-38]], dtype=np.float32)
-    q_ref, s_ref = ref.quantize(x, 8, ldq=64)
+    q_ref, s_ref = ref.quantize(x, 8, ldq=B.ocs_padded_cols(8))
     q, s = gpu_quantize(x, 8)
     assert np.array_equal(s, s_ref) and np.array_equal(q, q_ref)
 
@@ -202,14 +202,14 @@ def test_split_weights_qa_ties_and_dominant_channel():
     col0 = np.concatenate([[28.0], np.arange(-27 * 16, 27 * 16 + 1, 3) / 16.0]).astype(np.float32)
     W = np.stack([col0, np.full_like(col0, 2.5)], axis=1)
     W[2:5, 1] = [-2.5, 3.5, -0.5]
-    exp = ref.split_weights_qa(W, 2, 1, 3, 4, ldq=64)
+    exp = ref.split_weights_qa(W, 2, 1, 3, 4, ldq=B.ocs_padded_cols(5))
     got = gpu_split_weights_qa(W, 2, 1, 3, bits=4)
     assert np.array_equal(got["Wq"], exp["q"]) and np.array_equal(got["T_out"], exp["T_out"])
     assert np.array_equal(got["Wq"][:, [0, 2, 3, 4]].astype(np.int64).sum(axis=1),
                           np.floor(W[:, 0].astype(np.float64) + 0.5).astype(np.int64))
     dom = np.zeros((4, 6), dtype=np.float32)
     dom[1, 2] = 1.0
-    exp = ref.split_weights_qa(dom, 6, 1, 40, 8, ldq=64)
+    exp = ref.split_weights_qa(dom, 6, 1, 40, 8, ldq=B.ocs_padded_cols(46))
     got = gpu_split_weights_qa(dom, 6, 1, 40, bits=8)
     for k in ("split_src", "chan_src", "chan_depth", "chan_path", "scale", "T_out"):
         assert np.array_equal(got[k], exp[k]), k
@@ -295,7 +295,7 @@ def test_split_act(M, C, g, s, halve, threshold, act_map):
 
 # ---- ocs_qgemm -------------------------------------------------------------------------------
 
-@pytest.mark.parametrize("tile", list(range(22)))
+@pytest.mark.parametrize("tile", list(range(27)))
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (64, 256, 269), (130, 70, 64), (257, 129, 200), (700, 300, 1035),
                                    (300, 520, 2358), (128, 128, 4842)])
 def test_qgemm(tile, M, N, K):
@@ -394,6 +394,33 @@ def test_qconv_equals_the_lowered_gemm_path():
     assert np.array_equal(got["acc"], acc) and np.array_equal(got["Y"], Y)
 
 
+@pytest.mark.parametrize("tile", [-1, 3, 4, 11, 15, 23, 24])
+@pytest.mark.parametrize("ldx_extra,ldw_extra", [(0, 0), (64, 0), (0, 64), (64, 64), (192, 128)])
+@pytest.mark.parametrize("M,N,K", [(130, 140, 180), (300, 260, 2358)])
+def test_qgemm_k_step_of_128_needs_both_paddings(tile, ldx_extra, ldw_extra, M, N, K):
+    """K rounded up to 64 is an odd multiple of 64 here.  The tiles with a 128-byte K-step may
+    take the next 64 bytes in only when both leading dimensions hold them (zero padding); the
+    rows of a tensor whose leading dimension stops at the 64-byte boundary are followed directly
+    by the next row's codes, which must not enter the sum."""
+    rng = np.random.default_rng(M + N + K + ldx_extra)
+    k64 = (K + 63) // 64 * 64
+    assert k64 % 128 == 64
+    Xq = np.zeros((M, k64 + ldx_extra), dtype=np.int8)
+    Wq = np.zeros((N, k64 + ldw_extra), dtype=np.int8)
+    Xq[:, :K] = rng.integers(-127, 128, (M, K))
+    Wq[:, :K] = rng.integers(-127, 128, (N, K))
+    sx = np.array([3.0, 3.0 / 127], dtype=np.float32)
+    sw = np.array([0.7, 0.7 / 127], dtype=np.float32)
+    acc_ref, y_ref = ref.qgemm(Xq, Wq, K, sx[1], sw[1])
+    B.ocs_tune("gemm_tile", tile)
+    try:
+        acc, Y = gpu_qgemm(Xq, Wq, K, sx, sw)
+    finally:
+        B.ocs_tune("gemm_tile", -1)
+    assert np.array_equal(acc, acc_ref)
+    assert_y_close(Y, y_ref)
+
+
 # ---- output handed to the next layer as codes ----------------------------------------------------
 
 def _next_layer_list(rng, N, s_next):
@@ -401,7 +428,7 @@ def _next_layer_list(rng, N, s_next):
     return nxt["chan_src"]
 
 
-@pytest.mark.parametrize("tile", [-1, 0, 2, 6, 7, 9, 11, 12, 14, 16, 17, 18, 19])
+@pytest.mark.parametrize("tile", [-1, 0, 2, 6, 7, 9, 11, 12, 14, 16, 17, 18, 19, 22, 23])
 @pytest.mark.parametrize("M,N,K,s_next,relu", [(1, 1, 1, 0, False), (130, 70, 64, 9, True), (257, 129, 200, 0, False),
                                                (300, 520, 2358, 26, True), (700, 300, 269, 15, False)])
 def test_qgemm_requant(tile, M, N, K, s_next, relu):
