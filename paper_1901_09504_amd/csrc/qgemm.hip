@@ -283,7 +283,7 @@ __device__ __forceinline__ void emit_staged_rows(const int32_t* stage, int lane,
                     f32x4 y;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) y[e] = (float)a[e] * scale;
-                    *reinterpret_cast<f32x4*>(yp) = y;
+                    __builtin_nontemporal_store(y, reinterpret_cast<f32x4*>(yp));
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
