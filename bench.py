@@ -44,26 +44,29 @@ def x2_traffic():
     return X2_TRAFFIC["bytes_per_launch"] if digest == X2_TRAFFIC["quantize_hip_sha256"] else None
 
 
-def cpu_baseline(layer, W, X, reps=3):
-    """The CPU oracle, as it stands, on the same workload on this machine's host cores."""
+def cpu_baseline(layer, W, X, budget_s=12.0, max_reps=100):
+    """The CPU oracle, as it stands, on the same workload on this machine's host cores: whole
+    steps on all rows, repeated for about budget_s seconds of CPU work."""
     from oracle import ref
 
     s = ref.num_splits(layer.C, layer.r)
     Ke = (layer.C + s) * layer.g
     ldq = (Ke + 63) // 64 * 64
-    best = None
-    for _ in range(reps):
+    times = []
+    t_all = time.perf_counter()
+    while len(times) < 3 or (time.perf_counter() - t_all < budget_s and len(times) < max_reps):
         t0 = time.perf_counter()
         sp = ref.split_weights(W, layer.C, layer.g, s)
         Wq, sw = ref.quantize(sp["T_out"], layer.bits_w, ldq=ldq)
         Xq, sx, _ = ref.split_act(X, layer.C, layer.g, sp["chan_src"], None, s, layer.bits_x, ldq=ldq)
         ref.qgemm(Xq, Wq, Ke, sx[1], sw[1], want_acc=False)
-        dt = time.perf_counter() - t0
-        best = dt if best is None else min(best, dt)
+        times.append(time.perf_counter() - t0)
+    best, med = min(times), float(np.median(times))
     tops = 2.0 * X.shape[0] * layer.N * Ke / best / 1e12
     return {"value": tops, "unit": "TOPS", "cores": ref.get_threads(), "kind": "oracle",
-            "sample": f"whole step on all {X.shape[0]} rows of the workload, best of {reps}",
-            "seconds_per_step": best}
+            "sample": f"whole step on all {X.shape[0]} rows of the workload, best of {len(times)} "
+                      f"({time.perf_counter() - t_all:.1f} s of CPU work)",
+            "seconds_per_step": best, "seconds_per_step_median": med}
 
 
 def mfma_bound_gemm(torch, B, wl, ExpandedLayer, launches, copies=5):
