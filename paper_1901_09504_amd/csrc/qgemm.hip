@@ -9,6 +9,8 @@
 // chunk index is XOR-swizzled with the row so that the 16-byte reads of consecutive rows
 // fall in different banks.  K is padded with zero codes to a multiple of 64 by the producers,
 // so the K loop has no tail; zeros add nothing to an integer sum.
+#include <atomic>
+
 #include "ocs_internal.h"
 
 namespace ocs {
@@ -796,6 +798,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_wholek_kernel(
 }
 
 constexpr int64_t kWholeKMaxLds = 160 * 1024;  // LDS of one CU
+constexpr int kMaxDevices = 64;
 
 // Dynamic LDS of a whole-K launch: operands (or the epilogue's staging area, if larger) and,
 // when the output goes to the next layer as codes with copies, the table of those copies
@@ -822,14 +825,21 @@ static hipError_t run_wholek(const int8_t* Xq, int64_t ldx, const int8_t* Wq, in
     int dup_off = 0;
     const int64_t lds = wholek_lds_bytes<BM, BN, WAVES_M, WAVES_N>(Kpad, rq, &dup_off);
     if (Kpad < 64 || Kpad % 64 != 0 || lds > kWholeKMaxLds) return hipErrorInvalidValue;
-    // more than 64 KB of dynamic LDS has to be opted into, once per kernel
-    static bool opted_in = false;
-    if (lds > 65536 && !opted_in) {
-        hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void*>(&qgemm_wholek_kernel<BM, BN, WAVES_M, WAVES_N>),
-            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWholeKMaxLds);
+    // more than 64 KB of dynamic LDS has to be opted into, once per kernel and device (setting
+    // it twice from two threads is harmless)
+    static std::atomic<bool> opted_in[kMaxDevices];
+    int dev = 0;
+    if (lds > 65536) {
+        hipError_t e = hipGetDevice(&dev);
         if (e != hipSuccess) return e;
-        opted_in = true;
+        if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+        if (!opted_in[dev].load(std::memory_order_acquire)) {
+            e = hipFuncSetAttribute(
+                reinterpret_cast<const void*>(&qgemm_wholek_kernel<BM, BN, WAVES_M, WAVES_N>),
+                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWholeKMaxLds);
+            if (e != hipSuccess) return e;
+            opted_in[dev].store(true, std::memory_order_release);
+        }
     }
     const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
     const int64_t total = tiles_m * tiles_n;

@@ -184,7 +184,11 @@ def test_config5_forward_batch32(idx):
     run_layer(layer, clips=(0.9,), dynamic=False, static_threshold=5.0)
 
 
-@pytest.mark.parametrize("name", ["stem_7x7", "s1b0_1x1b", "s4b0_3x3"])
+# one layer per GEMM tile family the dispatcher picks at this batch size: whole-K 128x64 and
+# 128x128, ring 256x128, ring 256x256 (long K, N >= 256), whole-K 128x256 (N = 512, short K),
+# ring 128x128 (N >= 1024, short K)
+@pytest.mark.parametrize("name", ["stem_7x7", "s1b0_1x1b", "s4b0_3x3", "s3b0_3x3", "s2b0_1x1b", "s3b0_1x1b",
+                                  "s4b0_proj"])
 def test_config5_forward_batch256(name):
     (layer,) = [l for l in wl.config(5, batch=256) if l.name == name]
     run_layer(layer, clips=(0.8,), dynamic=False, static_threshold=5.0)
