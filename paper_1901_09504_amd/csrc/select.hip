@@ -4,16 +4,18 @@
 // magnitude in the layer.  Halving a channel halves its maximum exactly and its copy has the
 // same maximum, so the whole sequence of choices depends only on the C channel maxima: the
 // tensor itself is never re-scanned.  One workgroup keeps the (growing) list of maxima in
-// LDS; each of its 256 lanes caches the best entry among the slots it owns (slot j belongs to
-// lane j mod 256), so a step is one cross-lane arg-max plus a re-scan by the at most two lanes
-// whose slots changed.  Ties go to the lowest expanded index: the key packs the value's bit
-// pattern (non-negative floats order like unsigned integers) above the complemented index.
+// LDS; each of its 256 lanes owns a block of S consecutive slots (S = 4, 8, 16 or 32, so that
+// 256 * S slots hold the C + s entries; slots that do not exist yet hold -1) and caches the best
+// entry of its block, so a step is one cross-lane arg-max plus a re-scan of one block by the
+// lane whose slot was split: S / 4 independent 16-byte LDS reads and S compares.  Ties go to the
+// lowest expanded index: the key packs the value's bit pattern (non-negative floats order like
+// unsigned integers) above the complemented index.
 #include "ocs_internal.h"
 
 namespace ocs {
 
-__device__ inline unsigned long long key_of(float v, int j) {
-    return ((unsigned long long)__float_as_uint(v) << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)j);
+__device__ inline unsigned long long key_of_bits(unsigned bits, int j) {
+    return ((unsigned long long)bits << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)j);
 }
 
 // Largest key of the wave: largest value first, then (through the complemented index in the
@@ -25,6 +27,32 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long k)
     return ((unsigned long long)mhi << 32) | mlo;
 }
 
+// Best entry of the block of S slots that starts at slot j0: the largest value, the lowest
+// slot among equals (slots are visited in ascending order and only a strictly larger value
+// replaces the best so far).  Values are compared as signed integers on their bit patterns:
+// existing entries are non-negative floats, slots that do not exist yet hold -1.0 (negative as
+// an integer) and can never win.  0 when the block holds no entry.
+template <int S>
+__device__ __forceinline__ unsigned long long block_best(const float* vals, int j0) {
+    const f32x4* p = reinterpret_cast<const f32x4*>(vals + j0);
+    f32x4 v[S / 4];
+#pragma unroll
+    for (int q = 0; q < S / 4; ++q) v[q] = p[q];     // all reads issued before the first compare
+    int bv = -1, bj = 0;
+#pragma unroll
+    for (int q = 0; q < S / 4; ++q) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int u = (int)__float_as_uint(v[q][e]);
+            const bool better = u > bv;
+            bv = better ? u : bv;
+            bj = better ? 4 * q + e : bj;
+        }
+    }
+    return bv < 0 ? 0ull : key_of_bits((unsigned)bv, j0 + bj);
+}
+
+template <int LOG2_S>
 __global__ __launch_bounds__(kThreads) void select_kernel(
     const float* __restrict__ colmax, int C, int g, int s, int mode,
     const int32_t* split_in, int32_t* split_src,
@@ -32,19 +60,20 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     float clip_ratio, float qmax, float* __restrict__ scale_out) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int E = C + s;
-    // 8 bytes per expanded channel: 8000 channels stay below the 64 KB a workgroup may use
-    // without opting in to more
+    constexpr int log2_S = LOG2_S, S = 1 << LOG2_S, P = S * kThreads;   // P >= E slots, the last P - E never exist
+    // 4 bytes per slot and 4 per expanded channel: 8000 channels stay below the 64 KB a
+    // workgroup may use without opting in to more
     float* vals = reinterpret_cast<float*>(smem);
-    unsigned short* src = reinterpret_cast<unsigned short*>(vals + E);
+    unsigned short* src = reinterpret_cast<unsigned short*>(vals + P);
     unsigned short* dep = src + E;
     __shared__ unsigned long long wkey[2][kThreads / 64];
-    __shared__ float red[kThreads];
+    __shared__ unsigned wred[kThreads / 64];
     const int tid = threadIdx.x;
 
     // channel maxima: one coalesced, independent load per column, folded per channel with LDS
     // atomics on the bit pattern (non-negative floats order like unsigned integers)
+    for (int j = tid; j < P; j += kThreads) vals[j] = j < C ? 0.0f : -1.0f;
     for (int j = tid; j < C; j += kThreads) {
-        vals[j] = 0.0f;
         src[j] = (unsigned short)j;
         dep[j] = 0;
     }
@@ -59,15 +88,11 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     __syncthreads();
 
     if (mode == 0) {
-        unsigned long long local = 0;
-        for (int j = tid; j < C; j += kThreads) {
-            unsigned long long k = key_of(vals[j], j);
-            local = k > local ? k : local;
-        }
+        unsigned long long local = block_best<S>(vals, tid * S);
         // One barrier per step: the waves exchange their maxima through wkey (two sets, used
         // alternately, so that a fast wave cannot overwrite what a slow one still reads); every
         // lane then knows the step's channel and value.  The lane that owns the split slot updates
-        // the list and re-scans its own slots; the lane that owns the new slot folds the new entry
+        // the list and re-scans its own block; the lane that owns the new slot folds the new entry
         // into its cached best from registers.  No lane reads a list entry another lane wrote
         // during the same step, and later reads are separated from the write by a barrier.
         for (int i = 0; i < s; ++i) {
@@ -81,8 +106,8 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
             for (int w = 1; w < kThreads / 64; ++w) k = wk[w] > k ? wk[w] : k;
             const int jstar = (int)(0xFFFFFFFFu - (unsigned)(k & 0xFFFFFFFFull));
             const float half = __uint_as_float((unsigned)(k >> 32)) * 0.5f;
-            const bool owns_old = (jstar % kThreads) == tid;
-            const bool owns_new = (cur % kThreads) == tid;
+            const bool owns_old = (jstar >> log2_S) == tid;
+            const bool owns_new = (cur >> log2_S) == tid;
             if (owns_old) {
                 vals[jstar] = half;
                 unsigned short d = (unsigned short)(dep[jstar] + 1);
@@ -91,30 +116,9 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
                 src[cur] = src[jstar];
                 dep[cur] = d;
                 split_src[i] = jstar;
-                // re-scan of this lane's slots (the new slot too, if it is this lane's): four
-                // independent LDS reads per trip, so their latencies overlap
-                unsigned long long l0 = 0, l1 = 0, l2 = 0, l3 = 0;
-                int j = tid;
-                for (; j + 3 * kThreads <= cur; j += 4 * kThreads) {
-                    const float v0 = vals[j], v1 = vals[j + kThreads], v2 = vals[j + 2 * kThreads],
-                                v3 = vals[j + 3 * kThreads];
-                    const unsigned long long k0 = key_of(v0, j), k1 = key_of(v1, j + kThreads),
-                                             k2 = key_of(v2, j + 2 * kThreads),
-                                             k3 = key_of(v3, j + 3 * kThreads);
-                    l0 = k0 > l0 ? k0 : l0;
-                    l1 = k1 > l1 ? k1 : l1;
-                    l2 = k2 > l2 ? k2 : l2;
-                    l3 = k3 > l3 ? k3 : l3;
-                }
-                for (; j <= cur; j += kThreads) {
-                    const unsigned long long kk = key_of(vals[j], j);
-                    l0 = kk > l0 ? kk : l0;
-                }
-                l0 = l0 > l1 ? l0 : l1;
-                l2 = l2 > l3 ? l2 : l3;
-                local = l0 > l2 ? l0 : l2;
+                local = block_best<S>(vals, tid * S);   // sees the new slot too, if it is this lane's
             } else if (owns_new) {
-                const unsigned long long kn = key_of(half, cur);
+                const unsigned long long kn = key_of_bits(__float_as_uint(half), cur);
                 local = kn > local ? kn : local;
             }
         }
@@ -135,22 +139,23 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     }
     __syncthreads();
 
-    float m = 0.0f;
+    unsigned m = 0;   // bit pattern of the largest entry (all entries are non-negative)
     for (int j = tid; j < E; j += kThreads) {
         chan_src[j] = src[j];
         chan_depth[j] = dep[j];
-        m = fmaxf(m, vals[j]);
+        const unsigned u = __float_as_uint(vals[j]);
+        m = u > m ? u : m;
     }
-    red[tid] = m;
+    m = wave_umax32(m);
+    if ((tid & 63) == 0) wred[tid >> 6] = m;
     __syncthreads();
-    for (int w = kThreads / 2; w > 0; w >>= 1) {
-        if (tid < w) red[tid] = fmaxf(red[tid], red[tid + w]);
-        __syncthreads();
-    }
     if (tid == 0) {
-        if (max_out) *max_out = red[0];
+#pragma unroll
+        for (int w = 1; w < kThreads / 64; ++w) m = wred[w] > m ? wred[w] : m;
+        const float mx = __uint_as_float(m);
+        if (max_out) *max_out = mx;
         if (scale_out) {
-            float T = clip_ratio * red[0];
+            float T = clip_ratio * mx;
             scale_out[0] = T;
             scale_out[1] = T / qmax;
         }
@@ -161,10 +166,22 @@ hipError_t launch_select(const float* colmax, int C, int g, int s, int mode,
                          const int32_t* split_in, int32_t* split_src, int32_t* chan_src,
                          int32_t* chan_depth, float* max_out, float clip_ratio, float qmax,
                          float* scale_out, hipStream_t stream) {
-    size_t lds = (size_t)(C + s) * 8;  // C + s <= kMaxExpanded is checked by the caller
-    select_kernel<<<1, kThreads, lds, stream>>>(colmax, C, g, s, mode, split_in, split_src,
-                                                chan_src, chan_depth, max_out, clip_ratio, qmax,
-                                                scale_out);
+    const int E = C + s;   // E <= kMaxExpanded is checked by the caller
+    int log2_S = 2;        // 256 lanes x S slots hold the E entries
+    while ((kThreads << log2_S) < E) ++log2_S;
+    if (log2_S > 5) return hipErrorInvalidValue;
+    const size_t lds = (size_t)(kThreads << log2_S) * 4 + (size_t)E * 4;
+#define OCS_SELECT(L_)                                                                             \
+    select_kernel<L_><<<1, kThreads, lds, stream>>>(colmax, C, g, s, mode, split_in, split_src,    \
+                                                    chan_src, chan_depth, max_out, clip_ratio,     \
+                                                    qmax, scale_out)
+    switch (log2_S) {
+        case 2: OCS_SELECT(2); break;
+        case 3: OCS_SELECT(3); break;
+        case 4: OCS_SELECT(4); break;
+        default: OCS_SELECT(5); break;
+    }
+#undef OCS_SELECT
     return hipGetLastError();
 }
 
