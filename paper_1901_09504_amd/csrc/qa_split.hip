@@ -17,20 +17,25 @@ namespace ocs {
 // in LDS, then the workgroup writes the result out.
 __global__ __launch_bounds__(kThreads) void qa_paths_kernel(const int32_t* __restrict__ split_src,
                                                             int C, int s,
-                                                            uint32_t* __restrict__ chan_path) {
+                                                            uint32_t* __restrict__ chan_path, int staged) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int E = C + s;
     uint32_t* path = reinterpret_cast<uint32_t*>(smem);
-    unsigned char* len = reinterpret_cast<unsigned char*>(path + E);
+    // the split list is staged in LDS when it fits beside the histories: the replay below is
+    // one dependent chain, and a global load per step would be most of it
+    int32_t* list = reinterpret_cast<int32_t*>(path + E);
+    unsigned char* len = reinterpret_cast<unsigned char*>(list + (staged ? s : 0));
     for (int j = threadIdx.x; j < E; j += kThreads) {
         path[j] = 0u;
         len[j] = 0;
     }
+    if (staged)
+        for (int i = threadIdx.x; i < s; i += kThreads) list[i] = split_src[i];
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int i = 0; i < s; ++i) {
             const int cur = C + i;
-            int p = split_src[i];
+            int p = staged ? list[i] : split_src[i];
             p = p < 0 ? 0 : (p >= cur ? cur - 1 : p);
             const unsigned l = len[p] < 31 ? len[p] : 31;   // a history grows like log2(s): never 31
             path[cur] = path[p] | (1u << l);
@@ -42,22 +47,23 @@ __global__ __launch_bounds__(kThreads) void qa_paths_kernel(const int32_t* __res
     for (int j = threadIdx.x; j < E; j += kThreads) chan_path[j] = path[j];
 }
 
-// One lane per packed dword of codes (four expanded columns of one row).  Weights are
-// prepared once, off-line: no attempt at streaming speed here.
-__global__ __launch_bounds__(kThreads) void expand_quantize_qa_kernel(
-    const float* __restrict__ W, int64_t ldw, int64_t N, int C, int g, int s,
+// One lane per packed dword of codes (four expanded columns of one row).  Which dwords of a row
+// touch a split or an appended channel does not depend on the row; each workgroup works that out
+// once (a bit per dword and the list of the dwords concerned, in LDS).  The kernel then makes two
+// passes over its share of the output: the plain dwords (nearly all of them: r is a few percent)
+// as one flat range with a grid stride, one 16-byte load and four roundings each, several in
+// flight per lane; then the listed dwords of every row, every lane busy with the element-by-element
+// replay of histories.  Mixed in one pass, a single listed dword in a wave made all 64 lanes wait
+// through the replay code, which nearly every wave had to.
+constexpr int kQaMaskDwords = 32768;   // rows of up to 128 KB of codes take the two-pass route
+constexpr int kQaListCap = 4096;       // listed (not plain) dwords per row it can hold
+
+// the element-by-element member: source value through its channel's history, fp32 out if wanted
+__device__ __forceinline__ unsigned qa_dword_generic(
+    const float* __restrict__ W, int64_t ldw, int64_t n, int d, int C, int g, int Ke,
     const int32_t* __restrict__ chan_src, const int32_t* __restrict__ chan_depth,
-    const uint32_t* __restrict__ chan_path, const float* __restrict__ scale, float qmax,
-    float* __restrict__ W_out, int64_t ldo, int8_t* __restrict__ Wq, int D) {
-    const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (o >= N * (int64_t)D) return;
-    const int64_t n = o / D;
-    const int d = (int)(o - n * D);
-    const int Ke = (C + s) * g;
-    const float T = scale[0];
-    const float half_step = scale[1] * 0.5f;
-    float inv = 0.0f;
-    if (T > 0.0f) inv = __builtin_fminf(__fdiv_rn(qmax, T), 3.402823466e+38f);
+    const uint32_t* __restrict__ chan_path, float half_step, float inv, float qmax,
+    float* __restrict__ W_out, int64_t ldo) {
     unsigned packed = 0;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -67,27 +73,144 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_qa_kernel(
             const int j = k / g, t = k - j * g;
             int src = chan_src[j];
             src = src < 0 ? 0 : (src >= C ? C - 1 : src);
-            float v = W[n * ldw + (int64_t)src * g + t];
+            float x = W[n * ldw + (int64_t)src * g + t];
             const int depth = chan_depth[j] < 31 ? chan_depth[j] : 31;
             const uint32_t path = chan_path[j];
             for (int b = 0; b < depth; ++b) {
-                const float m = ((path >> b) & 1u) ? v + half_step : v - half_step;
-                v = m * 0.5f;
+                const float m = ((path >> b) & 1u) ? x + half_step : x - half_step;
+                x = m * 0.5f;
             }
-            if (W_out) W_out[n * ldo + k] = v;
-            float p = v * inv;
+            if (W_out) W_out[n * ldo + k] = x;
+            float p = x * inv;
             p = __builtin_amdgcn_fmed3f(p, -qmax, qmax);
             code = (int)floorf(p + 0.5f);        // Sec. 3.3's Q(x) = floor(x + 1/2)
         }
         packed |= ((unsigned)code & 0xFFu) << (8 * e);
     }
-    if (Wq) reinterpret_cast<unsigned*>(Wq)[o] = packed;
+    return packed;
+}
+
+template <typename Index>
+__global__ __launch_bounds__(kThreads) void expand_quantize_qa_kernel(
+    const float* __restrict__ W, int64_t ldw, int64_t N, int C, int g, int s,
+    const int32_t* __restrict__ chan_src, const int32_t* __restrict__ chan_depth,
+    const uint32_t* __restrict__ chan_path, const float* __restrict__ scale, float qmax,
+    float* __restrict__ W_out, int64_t ldo, int8_t* __restrict__ Wq, int D, unsigned magic) {
+    __shared__ unsigned plain_mask[kQaMaskDwords / 32];
+    __shared__ unsigned short listed[kQaListCap];
+    __shared__ unsigned short plain_before[kQaMaskDwords / 32];   // plain dwords in the words before
+    __shared__ int n_listed;
+    const int Ke = (C + s) * g;
+    // two passes only when codes alone are wanted and a row's dwords fit the mask
+    const bool two_pass = W_out == nullptr && Wq != nullptr && D <= kQaMaskDwords;
+    if (two_pass) {
+        const int words = (D + 31) / 32;
+        for (int w = threadIdx.x; w < words; w += kThreads) plain_mask[w] = 0u;
+        __syncthreads();
+        for (int d = threadIdx.x; d < D; d += kThreads) {
+            bool plain = 4 * d + 3 < C * g;   // inside the identity region ...
+            if (plain) {
+                const int j0 = (4 * d) / g, j1 = (4 * d + 3) / g;   // ... and no channel of it split
+                for (int j = j0; j <= j1; ++j) plain = plain && chan_depth[j] == 0 && chan_src[j] == j;
+            }
+            if (plain) atomicOr(&plain_mask[d >> 5], 1u << (d & 31));
+        }
+        __syncthreads();
+        // The list must be the same in every workgroup (pass 2 deals (row, list entry) pairs over
+        // the whole grid): a listed dword's place is its rank among the listed ones.
+        if (threadIdx.x == 0) {
+            int before = 0;
+            for (int w = 0; w < words; ++w) {
+                plain_before[w] = (unsigned short)before;
+                before += __popc(plain_mask[w]);
+            }
+            n_listed = D - before;
+        }
+        __syncthreads();
+        for (int d = threadIdx.x; d < D; d += kThreads) {
+            const unsigned m = plain_mask[d >> 5];
+            if (!((m >> (d & 31)) & 1u)) {
+                const int rank = d - (int)plain_before[d >> 5] - __popc(m & ((1u << (d & 31)) - 1u));
+                if (rank < kQaListCap) listed[rank] = (unsigned short)d;
+            }
+        }
+        __syncthreads();
+    }
+    const int L = two_pass ? n_listed : 0;
+    const bool use_list = two_pass && L <= kQaListCap;   // else: listed dwords are done in pass 1
+
+    const float T = scale[0];
+    const float half_step = scale[1] * 0.5f;
+    float inv = 0.0f;
+    if (T > 0.0f) inv = __builtin_fminf(__fdiv_rn(qmax, T), 3.402823466e+38f);
+
+    const Index total = (Index)N * (Index)D;
+    const Index stride = (Index)gridDim.x * kThreads;
+    constexpr int UN = 4;   // items per trip: their 16-byte loads are all issued before any is used
+    for (Index o0 = (Index)blockIdx.x * kThreads + threadIdx.x; o0 < total; o0 += (Index)UN * stride) {
+        int64_t n[UN];
+        int d[UN];
+        bool plain[UN];
+        f32x4 v[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const Index o = o0 + (Index)u * stride;
+            n[u] = 0;
+            d[u] = 0;
+            plain[u] = false;
+            if (o < total) {
+                if (sizeof(Index) == 4) {   // division by D: multiply by floor(2^32 / D), one correction
+                    unsigned q = __umulhi((unsigned)o, magic);
+                    unsigned r = (unsigned)o - q * (unsigned)D;
+                    if (r >= (unsigned)D) { ++q; r -= (unsigned)D; }
+                    n[u] = q;
+                    d[u] = (int)r;
+                } else {
+                    n[u] = (int64_t)(o / (Index)D);
+                    d[u] = (int)(o - (Index)n[u] * (Index)D);
+                }
+                plain[u] = two_pass && ((plain_mask[d[u] >> 5] >> (d[u] & 31)) & 1u);
+                if (plain[u]) v[u] = *reinterpret_cast<const f32x4u*>(W + n[u] * ldw + 4 * d[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const Index o = o0 + (Index)u * stride;
+            if (o >= total) break;
+            if (plain[u]) {
+                unsigned packed = 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float p = v[u][e] * inv;
+                    p = __builtin_amdgcn_fmed3f(p, -qmax, qmax);
+                    packed |= ((unsigned)(int)floorf(p + 0.5f) & 0xFFu) << (8 * e);
+                }
+                reinterpret_cast<unsigned*>(Wq)[o] = packed;
+            } else if (!use_list) {
+                const unsigned packed = qa_dword_generic(W, ldw, n[u], d[u], C, g, Ke, chan_src, chan_depth,
+                                                         chan_path, half_step, inv, qmax, W_out, ldo);
+                if (Wq) reinterpret_cast<unsigned*>(Wq)[o] = packed;
+            }
+        }
+    }
+    if (!use_list || L == 0) return;
+    // pass 2: item t = (row t / L, listed dword t % L), dense
+    const int64_t items = N * (int64_t)L;
+    for (int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x; t < items; t += (int64_t)gridDim.x * kThreads) {
+        const int64_t n = t / L;
+        const int d = listed[(int)(t - n * L)];
+        reinterpret_cast<unsigned*>(Wq)[n * D + d] =
+            qa_dword_generic(W, ldw, n, d, C, g, Ke, chan_src, chan_depth, chan_path, half_step, inv, qmax,
+                             nullptr, 0);
+    }
 }
 
 hipError_t launch_qa_paths(const int32_t* split_src, int C, int s, uint32_t* chan_path,
                            hipStream_t stream) {
-    const size_t lds = (size_t)(C + s) * 5 + 16;   // C + s <= kMaxExpanded: at most 40 KB
-    qa_paths_kernel<<<1, kThreads, lds, stream>>>(split_src, C, s, chan_path);
+    size_t lds = (size_t)(C + s) * 5 + 16;   // C + s <= kMaxExpanded: at most 40 KB
+    const int staged = lds + (size_t)s * 4 <= 60 * 1024;
+    if (staged) lds += (size_t)s * 4;
+    qa_paths_kernel<<<1, kThreads, lds, stream>>>(split_src, C, s, chan_path, staged);
     return hipGetLastError();
 }
 
@@ -100,8 +223,15 @@ hipError_t launch_expand_quantize_qa(const float* W, int64_t ldw, int64_t N, int
     const int64_t Ke = (int64_t)(C + s) * g;
     const int D = (int)(Wq ? ldq / 4 : ceil_div(Ke, 4));
     const int64_t total = N * D;
-    expand_quantize_qa_kernel<<<dim3((unsigned)ceil_div(total, kThreads)), kThreads, 0, stream>>>(
-        W, ldw, N, C, g, s, chan_src, chan_depth, chan_path, scale, qmax, W_out, ldo, Wq, D);
+    int64_t grid = ceil_div(total, kThreads);
+    if (grid > 2048) grid = 2048;   // 8 workgroups per CU, each walking the range with a grid stride
+    const unsigned magic = (unsigned)((((uint64_t)1) << 32) / (uint64_t)D);   // D >= 1
+    if (D >= 2 && total + 4 * grid * kThreads < ((int64_t)1 << 32))   // the loop looks 4 strides ahead
+        expand_quantize_qa_kernel<uint32_t><<<dim3((unsigned)grid), kThreads, 0, stream>>>(
+            W, ldw, N, C, g, s, chan_src, chan_depth, chan_path, scale, qmax, W_out, ldo, Wq, D, magic);
+    else
+        expand_quantize_qa_kernel<uint64_t><<<dim3((unsigned)grid), kThreads, 0, stream>>>(
+            W, ldw, N, C, g, s, chan_src, chan_depth, chan_path, scale, qmax, W_out, ldo, Wq, D, magic);
     return hipGetLastError();
 }
 
