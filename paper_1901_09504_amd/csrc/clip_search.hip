@@ -55,17 +55,29 @@ __global__ __launch_bounds__(kThreads) void hist_kernel(const float* __restrict_
         if (lhist[i] != 0u) atomicAdd(&hist[i], (unsigned long long)lhist[i]);
 }
 
-// Error of every candidate: one candidate per lane, one wave per workgroup so that the
-// candidates spread over many CUs; each lane walks the bins in increasing order.
-__global__ __launch_bounds__(64) void mse_sweep_kernel(
+// Error of every candidate: 64 candidates per workgroup, one per lane.  A candidate's sum runs
+// over the bins in increasing order (that order is part of the result), but the terms of the sum
+// are independent: the 16 waves of the workgroup each work out the terms of two bins of a chunk
+// of 32 for all 64 candidates, leave them in LDS, and the first wave then adds the chunk's 32
+// terms to its running sums in bin order.  (With one wave doing both for all bins the sweep was
+// bound by that single wave's instruction issue: 2048 bins x 512 candidates took ~85 us on
+// eight busy waves in the whole chip.)
+constexpr int kSweepWaves = 16, kSweepBinsPerWave = 2, kSweepChunk = kSweepWaves * kSweepBinsPerWave;
+
+template <bool STAGED>
+__global__ __launch_bounds__(kSweepWaves * 64) void mse_sweep_kernel(
     const unsigned long long* __restrict__ hist, const float* __restrict__ maxabs, int n_bins,
     int n_cand, float qmax, double* __restrict__ mse_out) {
-    // the frequencies as doubles in LDS: every lane reads every bin
+    __shared__ double term[kSweepChunk][64];
+    // the frequencies as doubles in LDS, fetched once (a load per chunk on the spot, with its
+    // wait, cost more than the arithmetic); left in global memory only when they do not fit
     extern __shared__ double hd[];
-    for (int i = threadIdx.x; i < n_bins; i += 64) hd[i] = (double)hist[i];
-    __syncthreads();
-    const int c = blockIdx.x * 64 + threadIdx.x + 1;
-    if (c > n_cand) return;
+    if (STAGED) {
+        for (int i = threadIdx.x; i < n_bins; i += kSweepWaves * 64) hd[i] = (double)hist[i];
+        __syncthreads();
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + lane + 1;     // lanes past n_cand compute and store nothing useful
     const float m = maxabs[0];
     const float width = __fdiv_rn(m, (float)n_bins);
     const float T = m * __fdiv_rn((float)c, (float)n_cand);
@@ -73,27 +85,46 @@ __global__ __launch_bounds__(64) void mse_sweep_kernel(
     if (T > 0.0f) inv = __builtin_fminf(__fdiv_rn(qmax, T), 3.402823466e+38f);
     const float step = __fdiv_rn(T, qmax);
     double sum = 0.0;
-#pragma unroll 8
-    for (int i = 0; i < n_bins; ++i) {       // the additions stay in bin order
-        const float xi = ((float)i + 0.5f) * width;
-        float code = rintf(xi * inv);
-        code = code > qmax ? qmax : code;
-        code = code < -qmax ? -qmax : code;
-        const double e = (double)xi - (double)code * (double)step;
-        sum += hd[i] * (e * e);
+    for (int base = 0; base < n_bins; base += kSweepChunk) {
+#pragma unroll
+        for (int k = 0; k < kSweepBinsPerWave; ++k) {
+            const int b = wave * kSweepBinsPerWave + k, i = base + b;
+            double t = 0.0;
+            if (i < n_bins) {
+                const float xi = ((float)i + 0.5f) * width;
+                float code = rintf(xi * inv);
+                code = code > qmax ? qmax : code;
+                code = code < -qmax ? -qmax : code;
+                const double e = (double)xi - (double)code * (double)step;
+                t = (STAGED ? hd[i] : (double)hist[i]) * (e * e);
+            }
+            term[b][lane] = t;
+        }
+        __syncthreads();
+        if (wave == 0) {
+            double t[kSweepChunk];
+#pragma unroll
+            for (int b = 0; b < kSweepChunk; ++b) t[b] = term[b][lane];
+            // the additions stay in bin order; bins past the last one contribute +0.0, which
+            // leaves a sum of non-negative terms as it is
+#pragma unroll
+            for (int b = 0; b < kSweepChunk; ++b) sum += t[b];
+        }
+        __syncthreads();
     }
-    mse_out[c - 1] = __ddiv_rn(sum, (double)n_bins);
+    if (wave == 0 && c <= n_cand) mse_out[c - 1] = __ddiv_rn(sum, (double)n_bins);
 }
 
 // The first candidate of least error.  One workgroup; lane t looks at candidates t+1,
-// t+1+256, ... in increasing order, then the lanes' bests are compared in candidate order.
+// t+1+256, ... in increasing order; the lanes' bests then meet in a tree in LDS whose every
+// node keeps the smaller error and, among equal errors, the earlier candidate.
 __global__ __launch_bounds__(kThreads) void mse_argmin_kernel(const double* __restrict__ mse,
                                                               const float* __restrict__ maxabs,
                                                               int n_cand, float* __restrict__ out) {
     __shared__ double best_err[kThreads];
     __shared__ int best_c[kThreads];
     double my_err = 0.0;
-    int my_c = 0;
+    int my_c = 0;          // 0: this lane has seen no candidate
     for (int c = threadIdx.x + 1; c <= n_cand; c += kThreads) {
         const double err = mse[c - 1];
         if (my_c == 0 || err < my_err) {
@@ -104,20 +135,21 @@ __global__ __launch_bounds__(kThreads) void mse_argmin_kernel(const double* __re
     best_err[threadIdx.x] = my_err;
     best_c[threadIdx.x] = my_c;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        double be = 0.0;
-        int bc = 0;
-        for (int t = 0; t < kThreads; ++t) {
-            const int c = best_c[t];
-            if (c == 0) continue;
-            const double e = best_err[t];
-            if (bc == 0 || e < be || (e == be && c < bc)) {
-                be = e;
-                bc = c;
+    for (int w = kThreads / 2; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) {
+            const int ca = best_c[threadIdx.x], cb = best_c[threadIdx.x + w];
+            const double ea = best_err[threadIdx.x], eb = best_err[threadIdx.x + w];
+            const bool take_b = cb != 0 && (ca == 0 || eb < ea || (eb == ea && cb < ca));
+            if (take_b) {
+                best_err[threadIdx.x] = eb;
+                best_c[threadIdx.x] = cb;
             }
         }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
         const float m = maxabs[0];
-        out[0] = m * __fdiv_rn((float)bc, (float)n_cand);
+        out[0] = m * __fdiv_rn((float)best_c[0], (float)n_cand);
         out[1] = m;
     }
 }
@@ -136,8 +168,15 @@ hipError_t launch_mse_clip(const float* x, int64_t ldx, int64_t rows, int64_t co
         x, ldx, rows, cols, maxabs, n_bins, hist);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    mse_sweep_kernel<<<dim3((unsigned)ceil_div(n_cand, 64)), 64, (size_t)n_bins * sizeof(double), stream>>>(hist, maxabs, n_bins,
-                                                                              n_cand, qmax, mse_out);
+    // the staged frequencies and the 16 KB of terms share the 64 KB a workgroup gets without
+    // opting in to more
+    const size_t staged_bytes = (size_t)n_bins * sizeof(double);
+    if (staged_bytes + sizeof(double) * kSweepChunk * 64 + 256 <= 65536)
+        mse_sweep_kernel<true><<<dim3((unsigned)ceil_div(n_cand, 64)), kSweepWaves * 64, staged_bytes, stream>>>(
+            hist, maxabs, n_bins, n_cand, qmax, mse_out);
+    else
+        mse_sweep_kernel<false><<<dim3((unsigned)ceil_div(n_cand, 64)), kSweepWaves * 64, 0, stream>>>(
+            hist, maxabs, n_bins, n_cand, qmax, mse_out);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     mse_argmin_kernel<<<1, kThreads, 0, stream>>>(mse_out, maxabs, n_cand, out);
