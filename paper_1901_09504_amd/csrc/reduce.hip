@@ -27,6 +27,15 @@ ReducePlan plan_reduce(int64_t rows, int64_t cols, bool vec_ok) {
     int64_t max_rb = ceil_div(rows, p.ty);
     if (rb > max_rb) rb = max_rb;
     if (rb < 1) rb = 1;
+    // A layer's weights (few rows, long rows): narrow strips that each run down ALL rows give
+    // enough workgroups by themselves, and with a single row block stage 1 writes the column
+    // maxima directly: one launch instead of two launch-latency-bound ones.
+    if (p.vec == 4 && rows <= 2048 && ceil_div(units, 8) >= 32) {
+        p.tx = 8;                                  // 8 lanes x 16 B = one 128-byte line per row
+        p.ty = kThreads / p.tx;
+        p.col_strips = (int)ceil_div(units, p.tx);
+        rb = 1;
+    }
     p.rows_per_block = (int)ceil_div(rows, rb);
     p.row_blocks = (int)ceil_div(rows, p.rows_per_block);
     return p;
@@ -218,6 +227,8 @@ hipError_t launch_colmax(const float* T, int64_t rows, int64_t cols, int64_t ld,
                          float* partial, hipStream_t stream) {
     const bool vec_ok = true;   // 16-byte loads at the float's own alignment (f32x4u)
     ReducePlan p = plan_reduce(rows, cols, vec_ok);
+    if (p.row_blocks == 1)   // a single row block: stage 1's output is the result
+        return launch_partials(T, rows, cols, ld, colmax, false, p, nullptr, stream);
     hipError_t e = launch_partials(T, rows, cols, ld, partial, false, p, nullptr, stream);
     if (e != hipSuccess) return e;
     colmax_final_kernel<<<(unsigned)ceil_div(cols, 64), kThreads, 0, stream>>>(partial, p.row_blocks,

@@ -81,7 +81,9 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     {
         const int K = C * g;
         unsigned* vbits = reinterpret_cast<unsigned*>(vals);
-#pragma unroll 8
+        // (sixteen loads in flight per lane: the column maxima were written a moment ago by
+        // other CUs and every batch of loads waits a whole trip through the fabric)
+#pragma unroll 16
         for (int k = tid; k < K; k += kThreads)
             atomicMax(&vbits[k / g], __float_as_uint(colmax[k]));
     }
