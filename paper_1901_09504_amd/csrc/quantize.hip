@@ -86,7 +86,7 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
     // Source column (or -1 for padding) and halving depth of every column past the vector
     // region.  They do not depend on the row, so each workgroup resolves them once; a lane that
     // lands on such a column then needs a single trip to memory, like every other lane.
-    __shared__ int tail_col[kTailTable];
+    __shared__ __align__(16) int tail_col[kTailTable];
     __shared__ int tail_dep[HALVE ? kTailTable : 1];
     const int Ke = (C + s) * g;
     const int tail0 = 4 * main_units;              // first column of the gather region
@@ -165,11 +165,16 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
             int dep[4];
             const int e0 = 4 * (d - main_units);
             if (use_table) {
+                // one 16-byte read of the four source columns; the loads are unconditional
+                // (a padding column reads column 0 and discards it): branch-free, so that a wave
+                // with a few lanes here does not run four masked branches for all 64
+                const i32x4 cols = *reinterpret_cast<const i32x4*>(&tail_col[e0]);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const int col = tail_col[e0 + e];
+                    const int col = cols[e];
                     dep[e] = HALVE ? tail_dep[e0 + e] : 0;
-                    v[e] = col >= 0 ? xrow[col] : 0.0f;
+                    const float x = xrow[col < 0 ? 0 : col];
+                    v[e] = col >= 0 ? x : 0.0f;
                 }
             } else {
                 const int k = 4 * d;
@@ -243,7 +248,7 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_in_kernel(
     const float* thr, float qmax, int8_t* __restrict__ Xq, int D, int Q, unsigned magic,
     float* scale_out, const float* __restrict__ partials, int n_partials, float clip_ratio) {
     __shared__ float thr_red[kThreads / 64];
-    __shared__ int tail_col[kTailTable];
+    __shared__ __align__(16) int tail_col[kTailTable];
     __shared__ int tail_dep[HALVE ? kTailTable : 1];
     const int Ke = (C + s) * g;
     const int TD = D - Q;                          // appended + padding dwords per row
@@ -287,10 +292,12 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_in_kernel(
     auto fetch_tail = [&](Index o, Index row, int d, f32x4& tv) {
         if (o < total && d < TD) {
             const float* xrow = X + (int64_t)row * ldx;
+            const i32x4 cols = *reinterpret_cast<const i32x4*>(&tail_col[4 * d]);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int col = tail_col[4 * d + e];
-                tv[e] = col >= 0 ? xrow[col] : 0.0f;
+            for (int e = 0; e < 4; ++e) {     // unconditional loads: see the output-ordered kernel
+                const int col = cols[e];
+                const float x = xrow[col < 0 ? 0 : col];
+                tv[e] = col >= 0 ? x : 0.0f;
             }
         }
     };
