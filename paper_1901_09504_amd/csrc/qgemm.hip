@@ -900,9 +900,11 @@ hipError_t launch_qconv(const int8_t* Aq, int64_t ldc, int B, int H, int W, int 
     const int64_t Kpad = ldw;          // kh*kw*ldc rounded up to a whole K-step
     if (Kpad < (int64_t)kh * kw * ldc) return hipErrorInvalidValue;
     int tile = tuning().gemm_tile;
-    // measured on the 3x3 layers of the paper's networks: the 128x128 tile is level with or ahead
-    // of the larger ones (the loader's per-lane tap bookkeeping grows with the rows a lane loads)
-    if (tile < 0) tile = N <= 64 ? 6 : 9;
+    // measured on the stem and the 3x3 layers of the paper's networks: the 128x128 tile is level
+    // with or ahead of the larger ones (the loader's per-lane tap bookkeeping grows with the rows
+    // a lane loads; a 128-byte K-step, which doubles them, was 15-90 % slower) and, from 64
+    // output channels on, ahead of the 128x64 one as well
+    if (tile < 0) tile = N < 64 ? 6 : 9;
 #define OCS_CONV_ARGS Aq, Wt, ldw, M, N, Kpad, cg, scale_x, scale_w, acc_out, ldacc, Y, ldy, stream, rq
     switch (tile) {
         case 6: return run_dma_conv<128, 64, 2, 2, 6>(OCS_CONV_ARGS);
