@@ -52,7 +52,10 @@ __device__ __forceinline__ unsigned long long block_best(const float* vals, int 
     return bv < 0 ? 0ull : key_of_bits((unsigned)bv, j0 + bj);
 }
 
-template <int LOG2_S>
+// ONE_WAVE: up to 1024 expanded channels (most layers) are dealt over the 64 lanes of the first
+// wave alone, which then runs the greedy steps by itself: no barrier and no exchange through LDS
+// in a step (0.2 us instead of 0.55); the other waves help before and after.
+template <int LOG2_S, bool ONE_WAVE>
 __global__ __launch_bounds__(kThreads) void select_kernel(
     const float* __restrict__ colmax, int C, int g, int s, int mode,
     const int32_t* split_in, int32_t* split_src,
@@ -60,7 +63,8 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     float clip_ratio, float qmax, float* __restrict__ scale_out) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int E = C + s;
-    constexpr int log2_S = LOG2_S, S = 1 << LOG2_S, P = S * kThreads;   // P >= E slots, the last P - E never exist
+    constexpr int log2_S = LOG2_S, S = 1 << LOG2_S;
+    constexpr int P = S * (ONE_WAVE ? 64 : kThreads);   // P >= E slots, the last P - E never exist
     // 4 bytes per slot and 4 per expanded channel: 8000 channels stay below the 64 KB a
     // workgroup may use without opting in to more
     float* vals = reinterpret_cast<float*>(smem);
@@ -89,7 +93,33 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     }
     __syncthreads();
 
-    if (mode == 0) {
+    if (mode == 0 && ONE_WAVE) {
+        if (tid < 64) {
+            // a wave's LDS accesses execute in program order: a slot written in one step is
+            // seen by whichever lane re-scans its block in a later one
+            unsigned long long local = block_best<S>(vals, tid * S);
+            for (int i = 0; i < s; ++i) {
+                const int cur = C + i;
+                const unsigned long long k = wave_max_u64(local);
+                const int jstar = (int)(0xFFFFFFFFu - (unsigned)(k & 0xFFFFFFFFull));
+                const float half = __uint_as_float((unsigned)(k >> 32)) * 0.5f;
+                if ((jstar >> log2_S) == tid) {
+                    vals[jstar] = half;
+                    unsigned short d = (unsigned short)(dep[jstar] + 1);
+                    dep[jstar] = d;
+                    vals[cur] = half;
+                    src[cur] = src[jstar];
+                    dep[cur] = d;
+                    split_src[i] = jstar;
+                    local = block_best<S>(vals, tid * S);
+                } else if ((cur >> log2_S) == tid) {
+                    const unsigned long long kn = key_of_bits(__float_as_uint(half), cur);
+                    local = kn > local ? kn : local;
+                }
+            }
+        }
+        __syncthreads();
+    } else if (mode == 0) {
         unsigned long long local = block_best<S>(vals, tid * S);
         // One barrier per step: the waves exchange their maxima through wkey (two sets, used
         // alternately, so that a fast wave cannot overwrite what a slow one still reads); every
@@ -169,19 +199,29 @@ hipError_t launch_select(const float* colmax, int C, int g, int s, int mode,
                          int32_t* chan_depth, float* max_out, float clip_ratio, float qmax,
                          float* scale_out, hipStream_t stream) {
     const int E = C + s;   // E <= kMaxExpanded is checked by the caller
-    int log2_S = 2;        // 256 lanes x S slots hold the E entries
-    while ((kThreads << log2_S) < E) ++log2_S;
+    const bool one_wave = E <= 1024;
+    const int lanes = one_wave ? 64 : kThreads;
+    int log2_S = 2;        // lanes x S slots hold the E entries
+    while ((lanes << log2_S) < E) ++log2_S;
     if (log2_S > 5) return hipErrorInvalidValue;
-    const size_t lds = (size_t)(kThreads << log2_S) * 4 + (size_t)E * 4;
-#define OCS_SELECT(L_)                                                                             \
-    select_kernel<L_><<<1, kThreads, lds, stream>>>(colmax, C, g, s, mode, split_in, split_src,    \
-                                                    chan_src, chan_depth, max_out, clip_ratio,     \
-                                                    qmax, scale_out)
-    switch (log2_S) {
-        case 2: OCS_SELECT(2); break;
-        case 3: OCS_SELECT(3); break;
-        case 4: OCS_SELECT(4); break;
-        default: OCS_SELECT(5); break;
+    const size_t lds = (size_t)(lanes << log2_S) * 4 + (size_t)E * 4;
+#define OCS_SELECT(L_, W_)                                                                         \
+    select_kernel<L_, W_><<<1, kThreads, lds, stream>>>(colmax, C, g, s, mode, split_in, split_src, \
+                                                        chan_src, chan_depth, max_out, clip_ratio, \
+                                                        qmax, scale_out)
+    if (one_wave) {
+        switch (log2_S) {
+            case 2: OCS_SELECT(2, true); break;
+            case 3: OCS_SELECT(3, true); break;
+            default: OCS_SELECT(4, true); break;
+        }
+    } else {
+        switch (log2_S) {
+            case 2: OCS_SELECT(2, false); break;
+            case 3: OCS_SELECT(3, false); break;
+            case 4: OCS_SELECT(4, false); break;
+            default: OCS_SELECT(5, false); break;
+        }
     }
 #undef OCS_SELECT
     return hipGetLastError();
