@@ -133,6 +133,21 @@ def test_select_channels(rows, C, g, s, kind):
     assert got["max"] == exp["max"]
 
 
+@pytest.mark.parametrize("E", [64, 65, 256, 257, 512, 513, 1024, 1025, 2048, 2049, 4096, 4097])
+@pytest.mark.parametrize("kind", ["heavy", "ties"])
+def test_select_at_the_list_layout_boundaries(E, kind):
+    """C + s on either side of every size at which the selector changes how it deals the list
+    over its lanes (slots per lane, one wave or four)."""
+    s = 40
+    rng = np.random.default_rng(E)
+    T = _tensor(rng, 3, E - s, kind)
+    exp = ref.split_weights(T, E - s, 1, s)
+    got = gpu_select(T, E - s, 1, s)
+    for k in ("split_src", "chan_src", "chan_depth"):
+        assert np.array_equal(got[k], exp[k]), k
+    assert got["max"] == exp["max"]
+
+
 def test_select_resplits_one_dominant_channel():
     rng = np.random.default_rng(2)
     T = rng.standard_normal((10, 12)).astype(np.float32)
