@@ -212,6 +212,22 @@ def test_split_weights_qa(N, C, g, s, bits, clip):
     assert np.array_equal(only_f32["T_out"], exp["T_out"])
 
 
+@pytest.mark.parametrize("N,C,g,s,why", [
+    (3, 7000, 20, 5, "rows of 35,025 dwords: too long for the per-row bit mask, one pass"),
+    (3, 200, 49, 190, "more dwords touch a split channel than the workgroup's list holds"),
+    (5, 1000, 4, 1, "a single split: all but a handful of dwords on the vector path"),
+])
+def test_split_weights_qa_code_only_routes(N, C, g, s, why):
+    """The code-only call picks its route by the shape: every route gives the oracle's codes."""
+    rng = np.random.default_rng(C + g + s)
+    W = _tensor(rng, N, C * g, "heavy")
+    exp = ref.split_weights_qa(W, C, g, s, 6, ldq=B.ocs_padded_cols((C + s) * g))
+    got = gpu_split_weights_qa(W, C, g, s, bits=6, want_f32=False)
+    for k in ("split_src", "chan_src", "chan_depth", "chan_path", "scale"):
+        assert np.array_equal(got[k], exp[k]), k
+    assert np.array_equal(got["Wq"], exp["q"]), why
+
+
 def test_split_weights_qa_ties_and_dominant_channel():
     # exact ties of floor(x + 1/2) on a step-1 grid, and one channel split over and over
     col0 = np.concatenate([[28.0], np.arange(-27 * 16, 27 * 16 + 1, 3) / 16.0]).astype(np.float32)
