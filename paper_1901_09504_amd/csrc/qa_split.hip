@@ -260,6 +260,7 @@ hipError_t launch_dup_code_columns(int8_t* Wq, int64_t ldq, int64_t N, int C, in
                                    const int32_t* chan_src, hipStream_t stream) {
     const int64_t total = N * (ldq - (int64_t)C * g);
     if (total <= 0) return hipSuccess;
+    if (ceil_div(total, kThreads) > 0x7FFFFFFF) return hipErrorInvalidValue;   // one lane per byte: grid.x
     dup_code_columns_kernel<<<dim3((unsigned)ceil_div(total, kThreads)), kThreads, 0, stream>>>(
         Wq, ldq, N, C, g, s, chan_src);
     return hipGetLastError();
@@ -316,6 +317,7 @@ __global__ __launch_bounds__(kThreads) void fold_weights_kernel(
 hipError_t launch_fold_weights(const int8_t* Wq, int64_t ldq, int64_t N, int C, int g, int s,
                                const int32_t* chan_src, int8_t* Wf, int64_t ldf, int32_t* max_abs,
                                hipStream_t stream) {
+    if (ceil_div(N * ldf, kThreads) > 0x7FFFFFFF) return hipErrorInvalidValue;   // one lane per byte: grid.x
     fold_init_kernel<<<1, 1, 0, stream>>>(max_abs);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

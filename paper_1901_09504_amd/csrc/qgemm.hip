@@ -843,6 +843,7 @@ static hipError_t run_wholek(const int8_t* Xq, int64_t ldx, const int8_t* Wq, in
     }
     const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
     const int64_t total = tiles_m * tiles_n;
+    if (total > 0x7FFFFFFF) return hipErrorInvalidValue;   // one workgroup per tile: grid.x
     return launch_kernel(kTimeGemm, qgemm_wholek_kernel<BM, BN, WAVES_M, WAVES_N>,
                          dim3((unsigned)total), dim3(WAVES_M * WAVES_N * 64), (unsigned)lds, stream,
                          Xq, ldx, Wq, ldw, (int)M, (int)N, (int)(Kpad / 64), scale_x, scale_w,
@@ -858,6 +859,7 @@ static hipError_t run_dma(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64
     if (Kpad < BK || Kpad % BK != 0) return hipErrorInvalidValue;
     const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
     const int64_t total = tiles_m * tiles_n;
+    if (total > 0x7FFFFFFF) return hipErrorInvalidValue;   // one workgroup per tile: grid.x
     return launch_kernel(kTimeGemm, qgemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, BK, NBUF, false, KG>,
                          dim3((unsigned)total), dim3(WAVES_M * WAVES_N * 64 * KG), 0, stream, Xq, ldx, Wq, ldw, (int)M,
                          (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y, ldy,
@@ -874,6 +876,7 @@ static hipError_t run_dma_conv(const int8_t* Aq, const int8_t* Wt, int64_t ldw, 
     if (Kpad < BK || Kpad % BK != 0 || cg.ldc % 16 != 0 || cg.cpp < 1) return hipErrorInvalidValue;
     const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
     const int64_t total = tiles_m * tiles_n;
+    if (total > 0x7FFFFFFF) return hipErrorInvalidValue;   // one workgroup per tile: grid.x
     return launch_kernel(kTimeGemm, qgemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, BK, NBUF, true>,
                          dim3((unsigned)total), dim3(WAVES_M * WAVES_N * 64), 0, stream, Aq, cg.ldc, Wt,
                          ldw, (int)M, (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y,
@@ -944,6 +947,7 @@ hipError_t launch_tap_major(const int8_t* Wq, int64_t ldq, int64_t N, int E, int
                             int8_t* Wt, hipStream_t stream) {
     const int64_t ldt = round_up((int64_t)g * ldc, 64);
     const int64_t total = (N + 1) * (ldt / 4);
+    if (ceil_div(total, kThreads) > 0x7FFFFFFF) return hipErrorInvalidValue;   // one lane per byte quad: grid.x
     tap_major_kernel<<<dim3((unsigned)ceil_div(total, kThreads)), kThreads, 0, stream>>>(Wq, ldq, N, E, g,
                                                                                        ldc, ldt, Wt);
     return hipGetLastError();
@@ -960,6 +964,7 @@ static hipError_t run(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t l
     if (Kpad < BK || Kpad % BK != 0) return hipErrorInvalidValue;
     const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
     const int64_t total = tiles_m * tiles_n;
+    if (total > 0x7FFFFFFF) return hipErrorInvalidValue;   // one workgroup per tile: grid.x
     return launch_kernel(kTimeGemm, qgemm_kernel<BM, BN, WAVES_M, WAVES_N, BK, P>,
                          dim3((unsigned)total), dim3(kThreads), 0, stream, Xq, ldx, Wq, ldw, (int)M,
                          (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y, ldy,
