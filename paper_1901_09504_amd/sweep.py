@@ -30,15 +30,16 @@ def run(config, batch, reps=6, static_threshold=5.0):
     layers = wl.config(config, batch=batch) if config == 5 else wl.config(config)
     seen = {}
     for l in layers:
-        seen.setdefault((l.M, l.C, l.g, l.N), [l, 0])
-        seen[(l.M, l.C, l.g, l.N)][1] += 1
+        key = (l.M, l.C, l.g, l.N, l.r, l.bits_w, l.bits_x)
+        seen.setdefault(key, [l, 0])
+        seen[key][1] += 1
     thr = torch.tensor([static_threshold], device="cuda")
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
     for e in ev:
         e.record()
     torch.cuda.synchronize()
     rows = []
-    for (M, C, g, N), (l, count) in seen.items():
+    for (M, C, g, N, _r, _bw, _bx), (l, count) in seen.items():
         K = C * g
         L = ExpandedLayer(N, C, g, l.r, l.bits_w, l.bits_x, max_rows=M)
         L.prepare_weights(torch.from_numpy(wl.weights(l)).cuda())
@@ -54,7 +55,7 @@ def run(config, batch, reps=6, static_threshold=5.0):
             tx.append(ev[0].elapsed_time(ev[1]) * 1e3)
             tg.append(ev[2].elapsed_time(ev[3]) * 1e3)
         x_us, g_us = float(np.median(tx[1:])), float(np.median(tg[1:]))
-        rows.append({"layer": l.name, "M": M, "K": K, "N": N, "count": count, "Kexp": L.Ke, "ld": L.ldq,
+        rows.append({"layer": l.name, "M": M, "K": K, "N": N, "r": l.r, "count": count, "Kexp": L.Ke, "ld": L.ldq,
                      "split_quant_us": x_us, "split_quant_GBps": (4.0 * M * K + M * L.Ke) / x_us / 1e3,
                      "gemm_us": g_us, "gemm_tops": 2.0 * M * N * L.Ke / g_us / 1e6,
                      "gemm_GBps": (M * L.Ke + N * L.Ke + 4.0 * M * N) / g_us / 1e3})
@@ -78,9 +79,9 @@ def main():
     if args.json:
         print(json.dumps(out))
         return
-    print(f"{'layer':16s} {'M':>8s} {'K':>5s} {'N':>5s} cnt | split+quantize us  GB/s %HBM | GEMM us   TOPS   GB/s")
+    print(f"{'layer':30s} {'M':>8s} {'K':>5s} {'N':>5s} {'r':>5s} cnt | split+quantize us  GB/s %HBM | GEMM us   TOPS   GB/s")
     for r in out["layers"]:
-        print(f"{r['layer']:16s} {r['M']:8d} {r['K']:5d} {r['N']:5d} {r['count']:3d} | {r['split_quant_us']:9.1f} "
+        print(f"{r['layer']:30s} {r['M']:8d} {r['K']:5d} {r['N']:5d} {r['r']:5.2f} {r['count']:3d} | {r['split_quant_us']:9.1f} "
               f"{r['split_quant_GBps']:9.0f} {r['split_quant_GBps'] / 80:4.0f}% | {r['gemm_us']:7.1f} "
               f"{r['gemm_tops']:6.0f} {r['gemm_GBps']:6.0f}")
     a = out["aggregate"]
