@@ -196,6 +196,13 @@ int ocs_split_weights(const float* W, int64_t N, int C, int g, int64_t ldw, int 
     hipError_t e = launch_colmax(W, N, K, ldw, colmax, partial, st);
     if (e != hipSuccess) return hip_fail(e);
     const float qmax = Wq ? qmax_of(bits) : 1.0f;
+    if (Wq && !W_out && mode == OCS_MODE_HALVE && select_expand_quantize_fits(C, num_splits, N, ldq)) {
+        // few splits, codes only: W2 and W3 as one launch
+        e = launch_select_expand_quantize(W, ldw, N, C, g, num_splits, colmax, split_src, chan_src,
+                                          chan_depth, wmax_out, clip_ratio, qmax, scale_w_out, Wq,
+                                          ldq, st);
+        return e == hipSuccess ? OCS_OK : hip_fail(e);
+    }
     e = launch_select(colmax, C, g, num_splits, mode, split_src, split_src, chan_src, chan_depth,
                       wmax_out, clip_ratio, qmax, Wq ? scale_w_out : nullptr, st);
     if (e != hipSuccess) return hip_fail(e);
@@ -596,6 +603,7 @@ int ocs_tune(const char* key, int value) {
     else if (!strcmp(key, "max_grid")) t.max_grid = value;
     else if (!strcmp(key, "max_un")) t.max_un = value;
     else if (!strcmp(key, "max_bt")) t.max_bt = value;
+    else if (!strcmp(key, "sel_inline")) t.sel_inline = value;
     else return OCS_E_MODE;
     return OCS_OK;
 }

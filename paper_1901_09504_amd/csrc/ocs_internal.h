@@ -70,6 +70,16 @@ hipError_t launch_threshold(const float* colmax, int C, int g, int s, const int3
                             const int32_t* chan_depth, float clip_ratio, float qmax,
                             float* scale_out, hipStream_t stream);
 
+// W2 + W3 in one launch for weights (greedy selection repeated by every workgroup, then Eq. 3 and
+// Eq. 1): serves few splits on lists of at most 1024 expanded channels, see `..._fits`.  Writes
+// what launch_select and launch_expand_quantize together would.
+bool select_expand_quantize_fits(int C, int s, int64_t N, int64_t ldq);
+hipError_t launch_select_expand_quantize(const float* W, int64_t ldw, int64_t N, int C, int g, int s,
+                                         const float* colmax, int32_t* split_src, int32_t* chan_src,
+                                         int32_t* chan_depth, float* max_out, float clip_ratio,
+                                         float qmax, float* scale_out, int8_t* Wq, int64_t ldq,
+                                         hipStream_t stream);
+
 // Fused gather / halve / quantize / pack: the streaming pass over activations (or weights).
 // thr: device float threshold; or, with partials != NULL, the threshold is
 // clip_ratio * max(partials[0 .. n_partials)), which every workgroup folds for itself.
@@ -209,6 +219,7 @@ struct Tuning {
     int max_grid = -1;  // workgroups of the flat pass
     int max_un = -1;    // 16-byte loads in flight per lane in the flat pass (1, 2 or 4)
     int max_bt = -1;    // threads per workgroup of the flat pass (256 or 1024)
+    int sel_inline = -1; // most splits for which the weight pass runs the selection itself (0: never; default 16)
 };
 Tuning& tuning();
 

@@ -9,6 +9,7 @@
 // halving) the appended codes are byte copies of their source codes; with Eq. 4 every
 // expanded channel j is scaled by 2^-chan_depth[j] before it meets the grid.
 #include "ocs_internal.h"
+#include "select_lds.h"
 
 namespace ocs {
 
@@ -419,6 +420,145 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
 #undef OCS_LAUNCH_U
 #undef OCS_LAUNCH_EQ
     return err;
+}
+
+// The weight pass with the greedy selection of Sec. 3.4 in its prologue: W2 and W3 as one launch.
+// The selection needs only the column maxima (a few KB, already in memory) and a handful of
+// sequential steps on them, so every workgroup repeats it for itself in LDS, behind its first
+// 16-byte fetch of W, instead of waiting for a selector launch of its own: for few splits the
+// repeated work (0.2 us per step on one wave) costs less than the dependent launch it replaces.
+// The workgroup then expands and quantizes its share of W from the lists in LDS (Eq. 3: every
+// expanded channel j is scaled by 2^-dep[j]; Eq. 1 on the grid of clip_ratio * max|W'|), with
+// the arithmetic of expand_quantize_kernel.  Workgroup 0 also writes the lists, the maximum
+// and the grid for the caller.  32-bit indices; C + s <= 64 << LOG2_S.
+template <int LOG2_S>
+__global__ __launch_bounds__(kThreads) void select_expand_quantize_kernel(
+    const float* __restrict__ W, int64_t ldw, int64_t N, int C, int g, int s,
+    const float* __restrict__ colmax, int32_t* __restrict__ split_src,
+    int32_t* __restrict__ chan_src, int32_t* __restrict__ chan_depth, float* __restrict__ max_out,
+    float clip_ratio, float qmax, float* __restrict__ scale_out, int8_t* __restrict__ Wq, int D,
+    int main_units, unsigned magic) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int S = 1 << LOG2_S, P = 64 * S;
+    const int E = C + s, Ke = E * g;
+    float* vals = reinterpret_cast<float*>(smem);
+    unsigned short* src = reinterpret_cast<unsigned short*>(vals + P);
+    unsigned short* dep = src + E;
+    __shared__ unsigned wred[kThreads / 64];
+    const int tid = threadIdx.x;
+    const bool first = blockIdx.x == 0;
+    const unsigned total = (unsigned)(N * D);
+    const unsigned stride = gridDim.x * kThreads;
+    unsigned* __restrict__ out = reinterpret_cast<unsigned*>(Wq);
+
+    auto fetch = [&](unsigned o, f32x4& v, unsigned& row, int& d) {
+        row = 0;
+        d = 0;
+        if (o < total) {
+            unsigned q = __umulhi(o, magic);          // floor(o / D), at most one low
+            unsigned r = o - q * (unsigned)D;
+            if (r >= (unsigned)D) { ++q; r -= (unsigned)D; }
+            row = q;
+            d = (int)r;
+            if (d < main_units) v = *(reinterpret_cast<const f32x4u*>(W + (int64_t)row * ldw) + d);
+        }
+    };
+    unsigned o = blockIdx.x * kThreads + tid;
+    f32x4 cur = {}, nxt = {};
+    unsigned row = 0, nrow = 0;
+    int d = 0, nd = 0;
+    fetch(o, cur, row, d);
+
+    channel_maxima_to_lds(colmax, C, g, P, vals, src, dep);
+    if (tid < 64) greedy_one_wave<LOG2_S>(vals, src, dep, C, s, tid, first ? split_src : nullptr);
+    __syncthreads();
+    unsigned m = 0;   // bit pattern of the largest entry (all entries are non-negative)
+    for (int j = tid; j < E; j += kThreads) {
+        if (first) {
+            chan_src[j] = src[j];
+            chan_depth[j] = dep[j];
+        }
+        const unsigned u = __float_as_uint(vals[j]);
+        m = u > m ? u : m;
+    }
+    m = wave_umax32(m);
+    if ((tid & 63) == 0) wred[tid >> 6] = m;
+    __syncthreads();
+    m = wred[0];
+#pragma unroll
+    for (int w = 1; w < kThreads / 64; ++w) m = wred[w] > m ? wred[w] : m;
+    const float mx = __uint_as_float(m);
+    const float T = clip_ratio * mx;
+    if (first && tid == 0) {
+        if (max_out) *max_out = mx;
+        scale_out[0] = T;
+        scale_out[1] = T / qmax;
+    }
+    const float inv = inv_step_of(T, qmax);
+
+    for (; o < total; o += stride) {
+        fetch(o + stride, nxt, nrow, nd);
+        const float* wrow = W + (int64_t)row * ldw;
+        const int k = 4 * d;
+        int j = k / g, t = k - j * g;
+        float v[4];
+        if (d < main_units) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                v[e] = cur[e] * ldexpf(1.0f, -(int)dep[j]);
+                if (++t == g) { t = 0; ++j; }
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                v[e] = 0.0f;
+                if (k + e < Ke) v[e] = wrow[(int64_t)src[j] * g + t] * ldexpf(1.0f, -(int)dep[j]);
+                if (++t == g) { t = 0; ++j; }
+            }
+        }
+        out[o] = pack4(code_bits(v[0], inv, qmax), code_bits(v[1], inv, qmax),
+                       code_bits(v[2], inv, qmax), code_bits(v[3], inv, qmax));
+        cur = nxt;
+        row = nrow;
+        d = nd;
+    }
+}
+
+// Whether the one-launch form serves this shape: the one-wave selector's list size, few enough
+// steps for the repeated selection to be cheaper than a launch, 32-bit item indices.
+bool select_expand_quantize_fits(int C, int s, int64_t N, int64_t ldq) {
+    const int limit = tuning().sel_inline < 0 ? 16 : tuning().sel_inline;
+    if (C + s > 1024 || s > limit || limit == 0) return false;
+    return N * (ldq / 4) + 2 * 2048 * (int64_t)kThreads < ((int64_t)1 << 32);
+}
+
+hipError_t launch_select_expand_quantize(const float* W, int64_t ldw, int64_t N, int C, int g, int s,
+                                         const float* colmax, int32_t* split_src, int32_t* chan_src,
+                                         int32_t* chan_depth, float* max_out, float clip_ratio,
+                                         float qmax, float* scale_out, int8_t* Wq, int64_t ldq,
+                                         hipStream_t stream) {
+    if (!select_expand_quantize_fits(C, s, N, ldq)) return hipErrorInvalidValue;
+    const int E = C + s;
+    const int main_units = (int)((int64_t)C * g / 4);
+    const int D = (int)(ldq / 4);
+    const int64_t total = N * D;
+    int64_t grid = 256 * 2;   // every workgroup repeats the selection: few of them
+    if (tuning().act_grid > 0) grid = tuning().act_grid;
+    if (grid > ceil_div(total, kThreads)) grid = ceil_div(total, kThreads);
+    const unsigned magic = (unsigned)((((uint64_t)1) << 32) / (uint64_t)D);  // D >= 16
+    int log2_S = 2;        // 64 lanes x S slots hold the E entries
+    while ((64 << log2_S) < E) ++log2_S;
+    const unsigned lds = (unsigned)((64 << log2_S) * 4 + E * 4);
+#define OCS_LAUNCH_SEQ(L_)                                                                        \
+    launch_kernel(kTimeSplitQuantize, select_expand_quantize_kernel<L_>, dim3((unsigned)grid),   \
+                  dim3(kThreads), lds, stream, W, ldw, N, C, g, s, colmax, split_src, chan_src,   \
+                  chan_depth, max_out, clip_ratio, qmax, scale_out, Wq, D, main_units, magic)
+    switch (log2_S) {
+        case 2: return OCS_LAUNCH_SEQ(2);
+        case 3: return OCS_LAUNCH_SEQ(3);
+        default: return OCS_LAUNCH_SEQ(4);
+    }
+#undef OCS_LAUNCH_SEQ
 }
 
 // fp32 expanded tensor (Eq. 3 with halve != 0, the weight side of Eq. 4 with halve == 0).

@@ -11,46 +11,9 @@
 // lowest expanded index: the key packs the value's bit pattern (non-negative floats order like
 // unsigned integers) above the complemented index.
 #include "ocs_internal.h"
+#include "select_lds.h"
 
 namespace ocs {
-
-__device__ inline unsigned long long key_of_bits(unsigned bits, int j) {
-    return ((unsigned long long)bits << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)j);
-}
-
-// Largest key of the wave: largest value first, then (through the complemented index in the
-// low word) the lowest index among the lanes that hold it.
-__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long k) {
-    const unsigned hi = (unsigned)(k >> 32), lo = (unsigned)k;
-    const unsigned mhi = wave_umax32(hi);
-    const unsigned mlo = wave_umax32(hi == mhi ? lo : 0u);
-    return ((unsigned long long)mhi << 32) | mlo;
-}
-
-// Best entry of the block of S slots that starts at slot j0: the largest value, the lowest
-// slot among equals (slots are visited in ascending order and only a strictly larger value
-// replaces the best so far).  Values are compared as signed integers on their bit patterns:
-// existing entries are non-negative floats, slots that do not exist yet hold -1.0 (negative as
-// an integer) and can never win.  0 when the block holds no entry.
-template <int S>
-__device__ __forceinline__ unsigned long long block_best(const float* vals, int j0) {
-    const f32x4* p = reinterpret_cast<const f32x4*>(vals + j0);
-    f32x4 v[S / 4];
-#pragma unroll
-    for (int q = 0; q < S / 4; ++q) v[q] = p[q];     // all reads issued before the first compare
-    int bv = -1, bj = 0;
-#pragma unroll
-    for (int q = 0; q < S / 4; ++q) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int u = (int)__float_as_uint(v[q][e]);
-            const bool better = u > bv;
-            bv = better ? u : bv;
-            bj = better ? 4 * q + e : bj;
-        }
-    }
-    return bv < 0 ? 0ull : key_of_bits((unsigned)bv, j0 + bj);
-}
 
 // ONE_WAVE: up to 1024 expanded channels (most layers) are dealt over the 64 lanes of the first
 // wave alone, which then runs the greedy steps by itself: no barrier and no exchange through LDS
@@ -74,50 +37,10 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     __shared__ unsigned wred[kThreads / 64];
     const int tid = threadIdx.x;
 
-    // channel maxima: one coalesced, independent load per column, folded per channel with LDS
-    // atomics on the bit pattern (non-negative floats order like unsigned integers)
-    for (int j = tid; j < P; j += kThreads) vals[j] = j < C ? 0.0f : -1.0f;
-    for (int j = tid; j < C; j += kThreads) {
-        src[j] = (unsigned short)j;
-        dep[j] = 0;
-    }
-    __syncthreads();
-    {
-        const int K = C * g;
-        unsigned* vbits = reinterpret_cast<unsigned*>(vals);
-        // (sixteen loads in flight per lane: the column maxima were written a moment ago by
-        // other CUs and every batch of loads waits a whole trip through the fabric)
-#pragma unroll 16
-        for (int k = tid; k < K; k += kThreads)
-            atomicMax(&vbits[k / g], __float_as_uint(colmax[k]));
-    }
-    __syncthreads();
+    channel_maxima_to_lds(colmax, C, g, P, vals, src, dep);
 
     if (mode == 0 && ONE_WAVE) {
-        if (tid < 64) {
-            // a wave's LDS accesses execute in program order: a slot written in one step is
-            // seen by whichever lane re-scans its block in a later one
-            unsigned long long local = block_best<S>(vals, tid * S);
-            for (int i = 0; i < s; ++i) {
-                const int cur = C + i;
-                const unsigned long long k = wave_max_u64(local);
-                const int jstar = (int)(0xFFFFFFFFu - (unsigned)(k & 0xFFFFFFFFull));
-                const float half = __uint_as_float((unsigned)(k >> 32)) * 0.5f;
-                if ((jstar >> log2_S) == tid) {
-                    vals[jstar] = half;
-                    unsigned short d = (unsigned short)(dep[jstar] + 1);
-                    dep[jstar] = d;
-                    vals[cur] = half;
-                    src[cur] = src[jstar];
-                    dep[cur] = d;
-                    split_src[i] = jstar;
-                    local = block_best<S>(vals, tid * S);
-                } else if ((cur >> log2_S) == tid) {
-                    const unsigned long long kn = key_of_bits(__float_as_uint(half), cur);
-                    local = kn > local ? kn : local;
-                }
-            }
-        }
+        if (tid < 64) greedy_one_wave<LOG2_S>(vals, src, dep, C, s, tid, split_src);
         __syncthreads();
     } else if (mode == 0) {
         unsigned long long local = block_best<S>(vals, tid * S);

@@ -178,6 +178,31 @@ def test_split_weights_halve(N, C, g, s, bits, clip):
     assert np.array_equal(got["Wq"], q_ref)
 
 
+@pytest.mark.parametrize("sel_inline", [-1, 0, 64])   # default limit / selector launch / selection in the code pass
+@pytest.mark.parametrize("N,C,g,s,kind", [
+    (7, 12, 1, 5, "heavy"), (40, 64, 9, 4, "heavy"), (256, 256, 9, 6, "normal"), (100, 37, 4, 16, "heavy"),
+    (100, 37, 4, 17, "heavy"), (64, 3, 49, 1, "normal"), (33, 130, 1, 0, "normal"), (20, 250, 1, 6, "ties"),
+    (20, 251, 1, 6, "ties"), (9, 500, 2, 12, "heavy"), (9, 501, 1, 12, "heavy"), (5, 1010, 1, 14, "normal"),
+    (5, 1010, 1, 15, "normal"), (12, 16, 3, 40, "heavy"), (300, 8, 1, 9, "zero")])
+def test_split_weights_codes_only_routes(N, C, g, s, kind, sel_inline):
+    """Codes only (no fp32 copy): with few splits the selection runs inside the code pass, one launch
+    instead of two; both routes must write the same lists, maximum, grid and codes."""
+    rng = np.random.default_rng(N + C + g + s)
+    W = (_tensor(rng, N, C * g, kind) * 0.05).astype(np.float32)
+    exp = ref.split_weights(W, C, g, s)
+    B.ocs_tune("sel_inline", sel_inline)
+    try:
+        got = gpu_split_weights(W, C, g, s, bits=7, clip_ratio=0.9, want_f32=False)
+    finally:
+        B.ocs_tune("sel_inline", -1)
+    for k in ("split_src", "chan_src", "chan_depth"):
+        assert np.array_equal(got[k], exp[k]), k
+    assert got["max"] == exp["max"]
+    q_ref, s_ref = ref.quantize(exp["T_out"], 7, clip_ratio=0.9, ldq=B.ocs_padded_cols((C + s) * g))
+    assert np.array_equal(got["scale"], s_ref)
+    assert np.array_equal(got["Wq"], q_ref)
+
+
 def test_split_weights_dup_mode():
     rng = np.random.default_rng(8)
     N, C, g, s = 30, 20, 4, 6
