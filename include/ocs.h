@@ -379,10 +379,11 @@ int ocs_calib_copy(const void *src, void *dst, size_t bytes, void *stream);
 
 /*
  * Launch-shape overrides for benchmarking (no passage of the paper; results never depend
- * on them).  Keys: "act_grid", "act_nt", "act_un", "act_map", "act_wide" (the split+quantize
- * pass), "max_flat", "max_grid", "max_un", "max_bt" (the whole-tensor max|x| pass), "sel_inline"
- * (most splits for which ocs_split_weights runs the selection inside its code pass instead of
- * as a launch of its own; 0: never), "gemm_tile" (tile variant of ocs_qgemm / ocs_qconv, 0..26; an id a shape cannot use falls back to one it
+ * on them).  Keys: "act_grid", "act_nt", "act_un", "act_map", "act_wide", "act_dep" (the
+ * split+quantize pass), "max_flat", "max_grid", "max_un", "max_bt" (the whole-tensor max|x|
+ * pass), "sel_inline" (most splits for which ocs_split_weights runs the selection inside its
+ * code pass instead of as a launch of its own; 0: never), "gemm_tile" (tile variant of
+ * ocs_qgemm / ocs_qconv, 0..26; an id a shape cannot use falls back to one it
  * can).  value < 0 restores the default.  Returns OCS_OK or OCS_E_MODE for an unknown key.
  * Process-wide and not thread-safe: set them before the calls they affect, from one thread.
  */

@@ -604,6 +604,7 @@ int ocs_tune(const char* key, int value) {
     else if (!strcmp(key, "max_un")) t.max_un = value;
     else if (!strcmp(key, "max_bt")) t.max_bt = value;
     else if (!strcmp(key, "sel_inline")) t.sel_inline = value;
+    else if (!strcmp(key, "act_dep")) t.act_dep = value;
     else return OCS_E_MODE;
     return OCS_OK;
 }

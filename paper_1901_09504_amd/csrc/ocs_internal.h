@@ -213,6 +213,7 @@ struct Tuning {
     int act_map = -1;   // lanes of that pass dealt over the output (0), over the input (1), by row shape (-1)
     int act_un = -1;    // items in flight per lane in that pass (1, 2 or 4)
     int act_wide = 0;   // force the 64-bit index variant of that pass (tests: tensors of 2^32 dwords do not fit a test)
+    int act_dep = -1;   // Eq. 4 pass: per-column depths from a table in LDS (1), from global memory (0), by tensor size (-1)
     int act_nt = 0;     // non-temporal loads of X in that pass (off: appended columns re-read X through L2)
     int gemm_tile = -1;
     int max_flat = -1;  // whole-tensor max|x| of a contiguous tensor as one flat stream (1), by columns (0), default (-1)

@@ -57,6 +57,27 @@ __device__ __forceinline__ float pass_threshold(const float* thr, const float* p
     return clip_ratio * m;
 }
 
+// Eq. 4's per-channel factors for the contiguous region of a row, as one byte per column in LDS:
+// dep_col[k] = halvings of the channel that column k belongs to (255 stands for any larger count:
+// 2^-150 and below already round to zero as an fp32 factor).  Built once per workgroup, channel by
+// channel, so that the pass needs no division by g and no look-up in global memory per element.
+__device__ __forceinline__ void build_depth_table(unsigned char* dep_col, const int32_t* __restrict__ chan_depth,
+                                                  int C, int g) {
+    for (int j = threadIdx.x; j < C; j += kThreads) {
+        const int dj = chan_depth[j];
+        const unsigned char b = (unsigned char)(dj < 0 ? 0 : (dj > 255 ? 255 : dj));
+        for (int t = 0; t < g; ++t) dep_col[j * g + t] = b;
+    }
+}
+// v[e] * 2^-dep of columns 4d .. 4d+3 (a multiply by an exact power of two, as ldexpf(1, -dep) gives it)
+__device__ __forceinline__ void scale_by_depth(f32x4& v, const unsigned char* dep_col, int d) {
+    const unsigned dd = *reinterpret_cast<const unsigned*>(dep_col + 4 * d);
+    if (dd != 0) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = v[e] * ldexpf(1.0f, -(int)((dd >> (8 * e)) & 0xFFu));
+    }
+}
+
 template <bool NT>
 __device__ __forceinline__ f32x4 load4(const f32x4u* p) {
     if (NT) return __builtin_nontemporal_load(p);
@@ -75,6 +96,7 @@ __device__ __forceinline__ f32x4 load4(const f32x4u* p) {
 //                    moments ago by neighbouring lanes, so the re-read is served by the
 //                    caches, not by HBM) and the zero padding.
 constexpr int kTailTable = 2048;  // appended + padded columns whose sources are kept in LDS
+constexpr int kDepthTableMax = 16384;  // widest unexpanded row whose per-column depths are kept in LDS (1 B each)
 
 template <bool HALVE, bool NT, int UN, typename Index>
 __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
@@ -82,13 +104,15 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
     const int32_t* __restrict__ chan_src, const int32_t* __restrict__ chan_depth,
     const float* thr, float qmax, int8_t* __restrict__ Xq, int D, int main_units,
     unsigned magic, float* scale_out, const float* __restrict__ partials, int n_partials,
-    float clip_ratio) {
+    float clip_ratio, int dep_table) {
     __shared__ float thr_red[kThreads / 64];
     // Source column (or -1 for padding) and halving depth of every column past the vector
     // region.  They do not depend on the row, so each workgroup resolves them once; a lane that
     // lands on such a column then needs a single trip to memory, like every other lane.
     __shared__ __align__(16) int tail_col[kTailTable];
     __shared__ int tail_dep[HALVE ? kTailTable : 1];
+    extern __shared__ __align__(16) unsigned char dep_col[];   // HALVE and dep_table: one byte per column
+    if (HALVE && dep_table) build_depth_table(dep_col, chan_depth, C, g);
     const int Ke = (C + s) * g;
     const int tail0 = 4 * main_units;              // first column of the gather region
     const int tail_n = 4 * D - tail0;              // columns in it (appended, leftover, padding)
@@ -151,7 +175,9 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
         unsigned q;
         if (d < main_units) {
             f32x4 v = vin;
-            if (HALVE) {
+            if (HALVE && dep_table) {
+                scale_by_depth(v, dep_col, d);
+            } else if (HALVE) {
                 int j = (4 * d) / g, t = 4 * d - j * g;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -247,10 +273,13 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_in_kernel(
     const float* __restrict__ X, int64_t ldx, int64_t M, int C, int g, int s,
     const int32_t* __restrict__ chan_src, const int32_t* __restrict__ chan_depth,
     const float* thr, float qmax, int8_t* __restrict__ Xq, int D, int Q, unsigned magic,
-    float* scale_out, const float* __restrict__ partials, int n_partials, float clip_ratio) {
+    float* scale_out, const float* __restrict__ partials, int n_partials, float clip_ratio,
+    int dep_table) {
     __shared__ float thr_red[kThreads / 64];
     __shared__ __align__(16) int tail_col[kTailTable];
     __shared__ int tail_dep[HALVE ? kTailTable : 1];
+    extern __shared__ __align__(16) unsigned char dep_col[];   // HALVE and dep_table: one byte per column
+    if (HALVE && dep_table) build_depth_table(dep_col, chan_depth, C, g);
     const int Ke = (C + s) * g;
     const int TD = D - Q;                          // appended + padding dwords per row
     for (int e = threadIdx.x; e < 4 * TD; e += kThreads) {
@@ -308,7 +337,9 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_in_kernel(
 
     auto emit = [&](Index row, int d, f32x4 v, f32x4 tv, float inv) {
         const Index base = row * (Index)D;
-        if (HALVE) {
+        if (HALVE && dep_table) {
+            scale_by_depth(v, dep_col, d);
+        } else if (HALVE) {
             int j = (4 * d) / g, t = 4 * d - j * g;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -366,6 +397,12 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
     const int64_t total = M * D;
     const bool nt = tuning().act_nt != 0;
     const bool halve = chan_depth != nullptr;
+    // Eq. 4: the per-column depth table in LDS, one byte per column of the unexpanded row, when a
+    // lane has enough items for the table's set-up to pay (weights, with one or two items per lane,
+    // were 0.6-2.3 us slower with it; cfg 2's activations, with 14, are 5 us faster)
+    const bool dep_pays = tuning().act_dep < 0 ? M * (ldq / 4) >= (int64_t)8 * 2048 * kThreads : tuning().act_dep != 0;
+    const int dep_table = halve && K <= kDepthTableMax && dep_pays ? 1 : 0;
+    const unsigned dep_lds = dep_table ? (unsigned)round_up(K, 16) : 0;
 
     int64_t grid = 256 * 8;  // 8 workgroups of 4 waves on each of the 256 CUs
     if (tuning().act_grid > 0) grid = tuning().act_grid;
@@ -386,8 +423,8 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
         const unsigned magic_q = (unsigned)((((uint64_t)1) << 32) / (uint64_t)Q);
 #define OCS_LAUNCH_IN(H, I_)                                                                       \
     launch_kernel(kTimeSplitQuantize, expand_quantize_in_kernel<H, I_>, dim3((unsigned)gin),      \
-                  dim3(kThreads), 0, stream, X, ldx, M, C, g, s, chan_src, chan_depth, thr, qmax,  \
-                  Xq, D, Q, magic_q, scale_out, partials, n_partials, clip_ratio)
+                  dim3(kThreads), dep_lds, stream, X, ldx, M, C, g, s, chan_src, chan_depth, thr,  \
+                  qmax, Xq, D, Q, magic_q, scale_out, partials, n_partials, clip_ratio, dep_table)
         if (wide_in) return halve ? OCS_LAUNCH_IN(true, uint64_t) : OCS_LAUNCH_IN(false, uint64_t);
         return halve ? OCS_LAUNCH_IN(true, uint32_t) : OCS_LAUNCH_IN(false, uint32_t);
 #undef OCS_LAUNCH_IN
@@ -402,8 +439,8 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
     hipError_t err = hipSuccess;
 #define OCS_LAUNCH_EQ(H, N_, U_, I_)                                                              \
     err = launch_kernel(kTimeSplitQuantize, expand_quantize_kernel<H, N_, U_, I_>, dim3((unsigned)grid), \
-                  dim3(kThreads), 0, stream, X, ldx, M, C, g, s, chan_src, chan_depth, thr, qmax,  \
-                  Xq, D, main_units, magic, scale_out, partials, n_partials, clip_ratio)
+                  dim3(kThreads), dep_lds, stream, X, ldx, M, C, g, s, chan_src, chan_depth, thr,  \
+                  qmax, Xq, D, main_units, magic, scale_out, partials, n_partials, clip_ratio, dep_table)
 #define OCS_LAUNCH_U(H, N_, I_)                                                                   \
     do {                                                                                          \
         if (un == 4) OCS_LAUNCH_EQ(H, N_, 4, I_);                                                 \

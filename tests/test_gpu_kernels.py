@@ -330,8 +330,8 @@ def test_mse_clip_threshold_degenerate_and_large():
                                      (77, 2048, 1, 205), (50, 64, 4, 300), (9, 512, 9, 26)])
 @pytest.mark.parametrize("halve", [False, True])
 @pytest.mark.parametrize("threshold", [None, 3.0])
-@pytest.mark.parametrize("act_map", [0, 1, 2, 3])   # lanes over the output / the input; +2: 64-bit indices
-def test_split_act(M, C, g, s, halve, threshold, act_map):
+@pytest.mark.parametrize("act_map", [0, 1, 2, 3, 4, 5])   # lanes over the output / the input; +2: 64-bit indices;
+def test_split_act(M, C, g, s, halve, threshold, act_map):  # +4: Eq. 4's depths from the per-column table in LDS
     rng = np.random.default_rng(M + C + g + s)
     X = _tensor(rng, M, C * g, "heavy")
     sel = ref.split_weights(X if halve else _tensor(rng, 9, C * g, "heavy"), C, g, s)
@@ -339,12 +339,39 @@ def test_split_act(M, C, g, s, halve, threshold, act_map):
     ldq = B.ocs_padded_cols((C + s) * g)
     q_ref, s_ref, _ = ref.split_act(X, C, g, cs, cd, s, 8, threshold=threshold, clip_ratio=0.9, ldq=ldq)
     B.ocs_tune("act_map", act_map & 1)
-    B.ocs_tune("act_wide", act_map >> 1)
+    B.ocs_tune("act_wide", (act_map >> 1) & 1)
+    B.ocs_tune("act_dep", act_map >> 2)
     try:
         q, sc = gpu_split_act(X, C, g, cs, cd, s, 8, threshold=threshold, clip_ratio=0.9)
     finally:
         B.ocs_tune("act_map", -1)
         B.ocs_tune("act_wide", 0)
+        B.ocs_tune("act_dep", -1)
+    assert np.array_equal(sc, s_ref)
+    assert np.array_equal(q, q_ref)
+
+
+@pytest.mark.parametrize("act_dep", [0, 1])
+def test_split_act_deep_halvings(act_dep):
+    """Eq. 4 with depth lists no greedy run would produce (the call takes any list): factors down to
+    2^-126, the denormal 2^-127 .. 2^-149, and zero beyond, on values up to 2^125.  The per-column depth table (one byte per column, 255 standing for anything
+    larger) and the look-up in global memory agree with the oracle."""
+    rng = np.random.default_rng(31)
+    M, C, g, s = 40, 12, 3, 4
+    chan_src = np.array(list(range(C)) + [2, 5, 7, 11], dtype=np.int32)
+    chan_depth = np.array([0, 1, 50, 100, 126, 127, 130, 140, 150, 200, 255, 300, 50, 127, 140, 300], dtype=np.int32)
+    X = _tensor(rng, M, C * g, "normal")
+    for j in range(C):    # channel j holds values near 2^depth (up to 2^125), so its products spread over the grid
+        X[:, j * g:(j + 1) * g] *= np.float32(2.0 ** min(int(chan_depth[j]), 125))
+    ldq = B.ocs_padded_cols((C + s) * g)
+    q_ref, s_ref, _ = ref.split_act(X, C, g, chan_src, chan_depth, s, 8, threshold=3.0, ldq=ldq)
+    for j in (3, 4, 5, 13):   # factors 2^-100, 2^-126 and the denormal 2^-127 all spread over the grid
+        assert len(np.unique(q_ref[:, j * g:(j + 1) * g])) > 20
+    B.ocs_tune("act_dep", act_dep)
+    try:
+        q, sc = gpu_split_act(X, C, g, chan_src, chan_depth, s, 8, threshold=3.0)
+    finally:
+        B.ocs_tune("act_dep", -1)
     assert np.array_equal(sc, s_ref)
     assert np.array_equal(q, q_ref)
 
