@@ -52,7 +52,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
         // during the same step, and later reads are separated from the write by a barrier.
         for (int i = 0; i < s; ++i) {
             const int cur = C + i;
-            unsigned long long k = wave_max_u64(local);
+            unsigned long long k = wave_max_key(local);
             unsigned long long* wk = wkey[i & 1];
             if ((tid & 63) == 0) wk[tid >> 6] = k;
             __syncthreads();

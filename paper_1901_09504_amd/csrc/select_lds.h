@@ -15,13 +15,17 @@ __device__ inline unsigned long long key_of_bits(unsigned bits, int j) {
     return ((unsigned long long)bits << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)j);
 }
 
-// Largest key of the wave: largest value first, then (through the complemented index in the
-// low word) the lowest index among the lanes that hold it.
-__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long k) {
-    const unsigned hi = (unsigned)(k >> 32), lo = (unsigned)k;
+// Largest key of the wave: largest value first, then the lowest index among the lanes that hold
+// it.  One reduction, on the values alone: blocks lie in lane order and every lane caches the
+// lowest slot among the equals of its own block, so among the lanes that hold the largest value the
+// lowest lane holds the lowest index (lanes without entries carry key 0 and sit above all lanes
+// of the list that have some).
+__device__ __forceinline__ unsigned long long wave_max_key(unsigned long long k) {
+    const unsigned hi = (unsigned)(k >> 32);
     const unsigned mhi = wave_umax32(hi);
-    const unsigned mlo = wave_umax32(hi == mhi ? lo : 0u);
-    return ((unsigned long long)mhi << 32) | mlo;
+    const int winner = __ffsll((long long)__ballot(hi == mhi)) - 1;
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)k, winner);
+    return ((unsigned long long)mhi << 32) | lo;
 }
 
 // Best entry of a block of S slots held in registers (v[q][e] = slot j0 + 4q + e): the largest
@@ -96,16 +100,9 @@ __device__ __forceinline__ void greedy_one_wave(float* vals, unsigned short* src
     unsigned long long local = block_best<S>(vals, lane * S);
     for (int i = 0; i < s; ++i) {
         const int cur = C + i;
-        // One reduction, on the values alone: blocks lie in lane order and every lane caches the
-        // lowest slot among the equals of its own block, so among the lanes that hold the largest
-        // value the lowest lane holds the lowest index.  (Lanes without entries carry 0 and sit
-        // above all lanes that have some; lane 0 always has one.)
-        const unsigned hi = (unsigned)(local >> 32);
-        const unsigned mhi = wave_umax32(hi);
-        const int winner = __ffsll((long long)__ballot(hi == mhi)) - 1;
-        const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)local, winner);
-        const int jstar = (int)(0xFFFFFFFFu - lo);
-        const float half = __uint_as_float(mhi) * 0.5f;
+        const unsigned long long k = wave_max_key(local);   // lane 0 always has an entry
+        const int jstar = (int)(0xFFFFFFFFu - (unsigned)(k & 0xFFFFFFFFull));
+        const float half = __uint_as_float((unsigned)(k >> 32)) * 0.5f;
         if ((jstar >> LOG2_S) == lane) {
             vals[jstar] = half;
             unsigned short d = (unsigned short)(dep[jstar] + 1);
