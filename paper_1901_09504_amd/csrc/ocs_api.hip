@@ -260,7 +260,7 @@ int ocs_split_weights_qa(const float* W, int64_t N, int C, int g, int64_t ldw, i
     e = launch_qa_paths(split_src, C, num_splits, chan_path, st);
     if (e != hipSuccess) return hip_fail(e);
     e = launch_expand_quantize_qa(W, ldw, N, C, g, num_splits, chan_src, chan_depth, chan_path,
-                                  scale_w_out, qmax, W_out, ldo, Wq, ldq, st);
+                                  scale_w_out, nullptr, qmax, W_out, ldo, Wq, ldq, st);
     if (e != hipSuccess) return hip_fail(e);
     return OCS_OK;
 }
@@ -279,12 +279,10 @@ int ocs_split_act_qa(const float* X, int64_t M, int C, int g, int64_t ldx, const
     if (!bits_ok(bits)) return OCS_E_BITS;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const float qmax = qmax_of(bits);
-    hipError_t e = launch_qa_scale(threshold, qmax, scale_out, st);
+    hipError_t e = launch_qa_paths(split_src, C, num_splits, chan_path, st);
     if (e != hipSuccess) return hip_fail(e);
-    e = launch_qa_paths(split_src, C, num_splits, chan_path, st);
-    if (e != hipSuccess) return hip_fail(e);
-    e = launch_expand_quantize_qa(X, ldx, M, C, g, num_splits, chan_src, chan_depth, chan_path, scale_out,
-                                  qmax, nullptr, 0, Xq, ldq, st);
+    e = launch_expand_quantize_qa(X, ldx, M, C, g, num_splits, chan_src, chan_depth, chan_path, threshold,
+                                  scale_out, qmax, nullptr, 0, Xq, ldq, st);
     if (e != hipSuccess) return hip_fail(e);
     return OCS_OK;
 }

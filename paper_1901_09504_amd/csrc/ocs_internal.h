@@ -106,11 +106,10 @@ hipError_t launch_qa_paths(const int32_t* split_src, int C, int s, uint32_t* cha
                            hipStream_t stream);
 hipError_t launch_dup_code_columns(int8_t* Wq, int64_t ldq, int64_t N, int C, int g, int s,
                                    const int32_t* chan_src, hipStream_t stream);
-hipError_t launch_qa_scale(const float* thr, float qmax, float* scale_out, hipStream_t stream);
 hipError_t launch_expand_quantize_qa(const float* W, int64_t ldw, int64_t N, int C, int g, int s,
                                      const int32_t* chan_src, const int32_t* chan_depth,
-                                     const uint32_t* chan_path, const float* scale, float qmax,
-                                     float* W_out, int64_t ldo, int8_t* Wq, int64_t ldq,
+                                     const uint32_t* chan_path, const float* thr, float* scale_out,
+                                     float qmax, float* W_out, int64_t ldo, int8_t* Wq, int64_t ldq,
                                      hipStream_t stream);
 
 // Sec. 4.1: histogram of |x| (n_bins <= 8192 bins on [0, *maxabs]), error of every candidate
