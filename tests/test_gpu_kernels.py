@@ -241,6 +241,8 @@ def test_split_weights_qa(N, C, g, s, bits, clip):
     (3, 7000, 20, 5, "rows of 35,025 dwords: too long for the per-row bit mask, one pass"),
     (3, 200, 49, 190, "more dwords touch a split channel than the workgroup's list holds"),
     (5, 1000, 4, 1, "a single split: all but a handful of dwords on the vector path"),
+    (3, 1500, 2, 1400, "more listed dwords than the per-element table in LDS holds: list without it"),
+    (1000, 300, 4, 12, "enough workgroups for some of them to take the listed dwords beside the stream"),
 ])
 def test_split_weights_qa_code_only_routes(N, C, g, s, why):
     """The code-only call picks its route by the shape: every route gives the oracle's codes."""
