@@ -372,10 +372,11 @@ int ocs_mse_clip_threshold(const float* x, int64_t rows, int64_t cols, int64_t l
     float* partial = reinterpret_cast<float*>(base + w.partial_off);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const float qmax = qmax_of(bits);
-    hipError_t e = launch_absmax_threshold(x, rows, cols, ldx, partial, 1.0f, qmax, colmax, st);
+    int n = 0;
+    hipError_t e = launch_absmax_partials(x, rows, cols, ldx, partial, &n, st);
     if (e != hipSuccess) return hip_fail(e);
-    e = launch_mse_clip(x, ldx, rows, cols, colmax, num_bins, num_candidates, qmax, hist_out,
-                        mse_out, threshold_out, st);
+    e = launch_mse_clip(x, ldx, rows, cols, partial, n, colmax, num_bins, num_candidates, qmax,
+                        hist_out, mse_out, threshold_out, st);
     if (e != hipSuccess) return hip_fail(e);
     return OCS_OK;
 }

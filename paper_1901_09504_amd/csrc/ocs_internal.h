@@ -112,12 +112,13 @@ hipError_t launch_expand_quantize_qa(const float* W, int64_t ldw, int64_t N, int
                                      float qmax, float* W_out, int64_t ldo, int8_t* Wq, int64_t ldq,
                                      hipStream_t stream);
 
-// Sec. 4.1: histogram of |x| (n_bins <= 8192 bins on [0, *maxabs]), error of every candidate
-// threshold, out = {first candidate of least error, *maxabs}.
+// Sec. 4.1: maxabs = {m, m / qmax} with m the largest of the n_partials per-workgroup maxima of
+// |x| (launch_absmax_partials), histogram of |x| (n_bins <= 8192 bins on [0, m]), error of every
+// candidate threshold, out = {first candidate of least error, m}.
 hipError_t launch_mse_clip(const float* x, int64_t ldx, int64_t rows, int64_t cols,
-                           const float* maxabs, int n_bins, int n_cand, float qmax,
-                           unsigned long long* hist, double* mse_out, float* out,
-                           hipStream_t stream);
+                           const float* partials, int n_partials, float* maxabs, int n_bins,
+                           int n_cand, float qmax, unsigned long long* hist, double* mse_out,
+                           float* out, hipStream_t stream);
 
 // What the GEMM / convolution epilogue may do instead of writing fp32: hand the output to the
 // next layer as codes (Eq. 1 with the next layer's static grid, after an optional ReLU, plus
