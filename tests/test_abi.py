@@ -138,3 +138,8 @@ def test_binding_raises_on_error():
 def test_sweep_tool_imports_without_a_gpu():
     from paper_1901_09504_amd import sweep
     assert callable(sweep.run) and callable(sweep.main)
+
+
+def test_variants_tool_imports_without_a_gpu():
+    from paper_1901_09504_amd import variants
+    assert callable(variants.run) and callable(variants.main)
