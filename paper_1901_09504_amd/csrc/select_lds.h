@@ -80,11 +80,24 @@ __device__ __forceinline__ void channel_maxima_to_lds(const float* __restrict__ 
     __syncthreads();
     const int K = C * g;
     unsigned* vbits = reinterpret_cast<unsigned*>(vals);
-    // (sixteen loads in flight per lane: the column maxima were written a moment ago by
-    // other CUs and every batch of loads waits a whole trip through the fabric)
-#pragma unroll 16
-    for (int k = tid; k < K; k += kThreads)
-        atomicMax(&vbits[k / g], __float_as_uint(colmax[k]));
+    // Sixteen loads per lane are requested before the first value is used: the column maxima were
+    // written a moment ago by other CUs and every load waits a whole trip through the fabric.  (The
+    // compiler keeps a load behind the LDS atomic that precedes it in program order, so a plain
+    // loop, unrolled or not, made one trip per column of a lane: most of the selector's time.)
+    constexpr int UN = 16;
+    for (int k0 = tid; k0 < K; k0 += UN * kThreads) {
+        float v[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int k = k0 + u * kThreads;
+            v[u] = colmax[k < K ? k : K - 1];
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int k = k0 + u * kThreads;
+            if (k < K) atomicMax(&vbits[k / g], __float_as_uint(v[u]));
+        }
+    }
     __syncthreads();
 }
 
