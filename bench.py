@@ -33,8 +33,8 @@ METRIC = "expanded int8 GEMM TOPS (% MFMA peak); split+quantize GB/s (% HBM)"
 # runs (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for the plain
 # copy kernel of known size launched after the timed region (profiles/x2_config2_hbm_traffic.md).
 # Valid only for the kernel source it was measured on: reported as null once that file changes.
-X2_TRAFFIC = {"quantize_hip_sha256": "1f0ecd2c65c85e4953c30fa4945e30d276c583e4ae05b89dae255c57afc77c45",
-              "bytes_per_launch": 146889721}
+X2_TRAFFIC = {"quantize_hip_sha256": "2527850ecb873c487385f6d40049caf419255c03f6a8e79ae728be1884b8fa41",
+              "bytes_per_launch": 146888491}
 
 
 def x2_traffic():

@@ -546,12 +546,22 @@ __global__ __launch_bounds__(kThreads) void select_expand_quantize_kernel(
                 if (++t == g) { t = 0; ++j; }
             }
         } else {
+            // the four gathers are requested together and unconditionally (a column past the last
+            // expanded one reads column 0 and is dropped): under a condition each would wait for
+            // the one before it
+            int col[4], dp[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                v[e] = 0.0f;
-                if (k + e < Ke) v[e] = wrow[(int64_t)src[j] * g + t] * ldexpf(1.0f, -(int)dep[j]);
+                const bool in = k + e < Ke;
+                col[e] = in ? (int)src[in ? j : 0] * g + t : -1;
+                dp[e] = in ? (int)dep[in ? j : 0] : 0;
                 if (++t == g) { t = 0; ++j; }
             }
+            float x[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[e] = wrow[col[e] < 0 ? 0 : col[e]];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = col[e] >= 0 ? x[e] * ldexpf(1.0f, -dp[e]) : 0.0f;
         }
         out[o] = pack4(code_bits(v[0], inv, qmax), code_bits(v[1], inv, qmax),
                        code_bits(v[2], inv, qmax), code_bits(v[3], inv, qmax));
