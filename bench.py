@@ -33,8 +33,8 @@ METRIC = "expanded int8 GEMM TOPS (% MFMA peak); split+quantize GB/s (% HBM)"
 # runs (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for the plain
 # copy kernel of known size launched after the timed region (profiles/x2_config2_hbm_traffic.md).
 # Valid only for the kernel source it was measured on: reported as null once that file changes.
-X2_TRAFFIC = {"quantize_hip_sha256": "2527850ecb873c487385f6d40049caf419255c03f6a8e79ae728be1884b8fa41",
-              "bytes_per_launch": 146888491}
+X2_TRAFFIC = {"quantize_hip_sha256": "45a57b8aea8a8f6f2679f9a34efae37e9dacd2c5f5f7534957576038a29265f9",
+              "bytes_per_launch": 146916747}
 
 
 def x2_traffic():

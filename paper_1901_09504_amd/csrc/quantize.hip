@@ -323,11 +323,18 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_in_kernel(
         if (o < total && d < TD) {
             const float* xrow = X + (int64_t)row * ldx;
             const i32x4 cols = *reinterpret_cast<const i32x4*>(&tail_col[4 * d]);
+            // a dword of padding alone (all four columns -1) requests nothing: with narrow rows most
+            // tail dwords are that, and their lanes would all ask for their row's first element
+            if ((cols[0] & cols[1] & cols[2] & cols[3]) >= 0) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {     // unconditional loads: see the output-ordered kernel
-                const int col = cols[e];
-                const float x = xrow[col < 0 ? 0 : col];
-                tv[e] = col >= 0 ? x : 0.0f;
+                for (int e = 0; e < 4; ++e) {     // unconditional loads: see the output-ordered kernel
+                    const int col = cols[e];
+                    const float x = xrow[col < 0 ? 0 : col];
+                    tv[e] = col >= 0 ? x : 0.0f;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) tv[e] = 0.0f;
             }
         }
     };
