@@ -117,11 +117,13 @@ __device__ __forceinline__ void greedy_one_wave(float* vals, unsigned short* src
         const int jstar = (int)(0xFFFFFFFFu - (unsigned)(k & 0xFFFFFFFFull));
         const float half = __uint_as_float((unsigned)(k >> 32)) * 0.5f;
         if ((jstar >> LOG2_S) == lane) {
+            // both look-ups first (one trip to LDS for the two), then the stores, then the re-scan
+            const unsigned short s0 = src[jstar];
+            const unsigned short d = (unsigned short)(dep[jstar] + 1);
             vals[jstar] = half;
-            unsigned short d = (unsigned short)(dep[jstar] + 1);
-            dep[jstar] = d;
             vals[cur] = half;
-            src[cur] = src[jstar];
+            dep[jstar] = d;
+            src[cur] = s0;
             dep[cur] = d;
             if (split_src) split_src[i] = jstar;
             local = block_best<S>(vals, lane * S);
