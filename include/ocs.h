@@ -240,6 +240,27 @@ int ocs_split_act(const float *X, int64_t M, int C, int g, int64_t ldx, const in
                   size_t ws_bytes, void *stream);
 
 /*
+ * ocs_split_act for callers that cannot allocate device memory and so have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Arguments, arithmetic and results are those of ocs_split_act; the scratch space (partial and
+ * column maxima of the per-batch grid) is an array of OCS_STATIC_SCRATCH_BYTES bytes that is part
+ * of the library's device image: each GPU the library runs on holds its own copy from the first
+ * call on that GPU until the process ends.  The call allocates and frees nothing.
+ *  - A tensor whose scratch need, ocs_workspace_bytes(M, C*g), exceeds OCS_STATIC_SCRATCH_BYTES is
+ *    refused with OCS_E_WORKSPACE before any device work (every layer shape of the paper's
+ *    networks fits).
+ *  - All calls on one GPU share that GPU's array: two calls that may overlap there (different
+ *    streams, different threads) race and give undefined thresholds; order them on one stream.
+ *    Nothing in the array has to start at zero and nothing is carried from one call to the next.
+ *  - The first call on a device looks the array's address up (hipGetSymbolAddress); make that
+ *    call outside a graph capture.
+ */
+#define OCS_STATIC_SCRATCH_BYTES (2 * 1024 * 1024)
+int ocs_split_act_static(const float *X, int64_t M, int C, int g, int64_t ldx, const int32_t *chan_src,
+                         const int32_t *chan_depth, int num_splits, int bits, const float *threshold,
+                         float clip_ratio, int8_t *Xq, int64_t ldq, float *scale_out, void *stream);
+
+/*
  * The dynamic threshold of ocs_split_act on its own (Eq. 1's max|x| over the expanded
  * activations, times clip_ratio): scale_out device float[2] = {T, T / qmax}.  Calling this
  * and then ocs_split_act with threshold = scale_out is what ocs_split_act does by itself

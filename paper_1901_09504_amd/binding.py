@@ -87,6 +87,9 @@ def lib():
     L.ocs_split_act.restype = _i32
     L.ocs_split_act.argtypes = [_vp, _i64, _i32, _i32, _i64, _vp, _vp, _i32, _i32, _vp, _f32, _vp, _i64,
                                 _vp, _vp, _sz, _vp]
+    L.ocs_split_act_static.restype = _i32
+    L.ocs_split_act_static.argtypes = [_vp, _i64, _i32, _i32, _i64, _vp, _vp, _i32, _i32, _vp, _f32, _vp, _i64,
+                                       _vp, _vp]
     L.ocs_act_threshold.restype = _i32
     L.ocs_act_threshold.argtypes = [_vp, _i64, _i32, _i32, _i64, _vp, _vp, _i32, _i32, _f32, _vp, _vp, _sz, _vp]
     L.ocs_qgemm.restype = _i32
@@ -268,6 +271,16 @@ def ocs_split_act(X, M, Cn, g, ldx, chan_src, chan_depth, num_splits, bits, thre
     _check(lib().ocs_split_act(_ptr(X), M, Cn, g, ldx, _ptr(chan_src), _ptr(chan_depth), num_splits,
                                bits, _ptr(threshold), clip_ratio, _ptr(Xq), ldq, _ptr(scale_out), w,
                                wb, _stream(stream)), "ocs_split_act")
+
+
+STATIC_SCRATCH_BYTES = 2 * 1024 * 1024
+
+
+def ocs_split_act_static(X, M, Cn, g, ldx, chan_src, chan_depth, num_splits, bits, threshold, clip_ratio,
+                         Xq, ldq, scale_out, stream=None):
+    _check(lib().ocs_split_act_static(_ptr(X), M, Cn, g, ldx, _ptr(chan_src), _ptr(chan_depth),
+                                      num_splits, bits, _ptr(threshold), clip_ratio, _ptr(Xq), ldq,
+                                      _ptr(scale_out), _stream(stream)), "ocs_split_act_static")
 
 
 def ocs_act_threshold(X, M, Cn, g, ldx, chan_src, chan_depth, num_splits, bits, clip_ratio, scale_out,

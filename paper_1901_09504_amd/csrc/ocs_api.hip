@@ -2,6 +2,7 @@
 // carving, and the launch sequences.  See include/ocs.h for the contract of each call.
 #include <string.h>
 
+#include <atomic>
 #include <string>
 
 #include "../../include/ocs.h"
@@ -25,6 +26,8 @@ static int hip_fail(hipError_t e) {
     g_hip_error = hipGetErrorString(e);
     return OCS_E_HIP;
 }
+
+constexpr int kStaticScratchDevices = 64;   // devices a process can see
 
 static bool bits_ok(int bits) { return bits >= 2 && bits <= 8; }
 static float qmax_of(int bits) { return (float)((1 << (bits - 1)) - 1); }
@@ -381,18 +384,27 @@ int ocs_mse_clip_threshold(const float* x, int64_t rows, int64_t cols, int64_t l
     return OCS_OK;
 }
 
+// Argument checks of ocs_split_act that do not concern the scratch space.
+static int check_split_act(const float* X, int64_t M, int C, int g, int64_t ldx, const int32_t* chan_src,
+                           int num_splits, int bits, const float* threshold, float clip_ratio,
+                           const int8_t* Xq, int64_t ldq, const float* scale_out) {
+    if (!X || !Xq || !scale_out || (num_splits > 0 && !chan_src)) return OCS_E_NULL;
+    int rc = check_layer(M, C, g, ldx, num_splits);
+    if (rc) return rc;
+    rc = check_codes(Xq, ldq, (int64_t)(C + num_splits) * g);
+    if (rc) return rc;
+    if (!bits_ok(bits)) return OCS_E_BITS;
+    if (!threshold && !clip_ok(clip_ratio)) return OCS_E_CLIP;
+    return OCS_OK;
+}
+
 int ocs_split_act(const float* X, int64_t M, int C, int g, int64_t ldx, const int32_t* chan_src,
                   const int32_t* chan_depth, int num_splits, int bits, const float* threshold,
                   float clip_ratio, int8_t* Xq, int64_t ldq, float* scale_out, void* workspace,
                   size_t ws_bytes, void* stream) {
-    if (!X || !Xq || !scale_out || (num_splits > 0 && !chan_src)) return OCS_E_NULL;
-    int rc = check_layer(M, C, g, ldx, num_splits);
+    int rc = check_split_act(X, M, C, g, ldx, chan_src, num_splits, bits, threshold, clip_ratio, Xq, ldq,
+                             scale_out);
     if (rc) return rc;
-    const int64_t Ke = (int64_t)(C + num_splits) * g;
-    rc = check_codes(Xq, ldq, Ke);
-    if (rc) return rc;
-    if (!bits_ok(bits)) return OCS_E_BITS;
-    if (!threshold && !clip_ok(clip_ratio)) return OCS_E_CLIP;
     const float qmax = qmax_of(bits);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (threshold == nullptr && chan_depth == nullptr) {
@@ -424,6 +436,46 @@ int ocs_split_act(const float* X, int64_t M, int C, int g, int64_t ldx, const in
                                           threshold == scale_out ? nullptr : scale_out, st);
     if (e != hipSuccess) return hip_fail(e);
     return OCS_OK;
+}
+
+// Scratch space of ocs_split_act_static: one array per GPU, part of the library's device image,
+// so nothing is allocated at run time.  In host code the name `scratch` is only a handle for
+// hipGetSymbolAddress; the address each device holds its copy at is looked up once per device
+// (with that device current) and kept, and only that address is ever handed to a launch.
+static __device__ __align__(256) unsigned char scratch[OCS_STATIC_SCRATCH_BYTES];
+
+static int static_scratch(void** out) {
+    static std::atomic<void*> addr[kStaticScratchDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kStaticScratchDevices) return hip_fail(hipErrorInvalidDevice);
+    void* p = addr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e);
+        if (p == nullptr) return hip_fail(hipErrorInvalidSymbol);
+        addr[dev].store(p, std::memory_order_release);   // two threads racing here store the same value
+    }
+    *out = p;
+    return OCS_OK;
+}
+
+int ocs_split_act_static(const float* X, int64_t M, int C, int g, int64_t ldx, const int32_t* chan_src,
+                         const int32_t* chan_depth, int num_splits, int bits, const float* threshold,
+                         float clip_ratio, int8_t* Xq, int64_t ldq, float* scale_out, void* stream) {
+    int rc = check_split_act(X, M, C, g, ldx, chan_src, num_splits, bits, threshold, clip_ratio, Xq, ldq,
+                             scale_out);
+    if (rc) return rc;
+    if (plan_workspace(M, (int64_t)C * g).total > (size_t)OCS_STATIC_SCRATCH_BYTES) return OCS_E_WORKSPACE;
+    void* ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc) return rc;
+    // Every float of the scratch space that a pass reads was written by the pass before it in this
+    // same call (per-workgroup maxima, column maxima): nothing has to start at zero, and what an
+    // earlier call left behind is never read.
+    return ocs_split_act(X, M, C, g, ldx, chan_src, chan_depth, num_splits, bits, threshold, clip_ratio,
+                         Xq, ldq, scale_out, ws, (size_t)OCS_STATIC_SCRATCH_BYTES, stream);
 }
 
 int ocs_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M, int64_t N,

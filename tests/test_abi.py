@@ -129,6 +129,26 @@ def test_argument_errors_are_reported_without_a_device():
     assert L.ocs_strerror(-99) == b"unknown error code"
 
 
+def test_static_scratch_entry_point_checks_arguments_and_size_on_the_host():
+    L = B.lib()
+    # the same argument checks as ocs_split_act, in the same order
+    assert L.ocs_split_act_static(None, 4, 4, 1, 4, None, None, 0, 8, None, 1.0, A, 64, A, None) == -1
+    assert L.ocs_split_act_static(A, 4, 4, 0, 4, A, None, 0, 8, A, 1.0, A, 64, A, None) == -2
+    assert L.ocs_split_act_static(A, 4, 4, 1, 4, A, None, -1, 8, A, 1.0, A, 64, A, None) == -5
+    assert L.ocs_split_act_static(A, 4, 4, 1, 4, A, None, 1, 9, A, 1.0, A, 64, A, None) == -4
+    assert L.ocs_split_act_static(A, 4, 4, 1, 4, A, None, 1, 8, None, 0.0, A, 64, A, None) == -10
+    # a tensor whose scratch need is beyond the array: refused before any device work
+    M, Cn, g = 64, 4000, 256                      # the column maxima alone are 4 MB
+    assert B.ocs_workspace_bytes(M, Cn * g) > B.STATIC_SCRATCH_BYTES
+    assert L.ocs_split_act_static(A, M, Cn, g, Cn * g, None, None, 0, 8, None, 1.0, A, Cn * g, A, None) == -7
+    assert L.ocs_split_act_static(A, M, Cn, g, Cn * g, None, None, 0, 8, A, 1.0, A, Cn * g, A, None) == -7
+    # every layer shape of the five workloads fits
+    from paper_1901_09504_amd import workloads as wl
+    for cfg in range(1, 6):
+        for layer in wl.config(cfg):
+            assert B.ocs_workspace_bytes(layer.M, layer.C * layer.g) <= B.STATIC_SCRATCH_BYTES, layer
+
+
 def test_binding_raises_on_error():
     with pytest.raises(B.OcsError) as e:
         B._check(-4, "ocs_quantize")
