@@ -1,19 +1,24 @@
 #!/usr/bin/env python3
 """Benchmark of the OCS-expanded quantized layer on one MI355X.
 
-A step is one pass of the whole hot path over one batch of the ResNet-style 3x3 convolution
-(batch 64, 256->256 channels, 14x14, lowered by im2col: M=12544, K=2304, N=256, r=0.02,
-8-bit weights and activations):
+The workload is the ResNet-50-shaped sweep: all 53 convolution layers as im2col GEMMs at batch
+256, OCS at r = 0.05, 4-bit weights, 8-bit activations (2.22 tera-ops of expanded GEMM work per
+pass).  A step is one pass of the hot path over that batch, layer after layer:
 
-    ocs_split_weights   channel maxima of W, greedy selection, halve + quantize     (W1-W3)
-    ocs_split_act       max|X| for the per-batch activation grid, then duplicate
-                        the chosen channels, quantize, pack                         (X1, X2)
-    ocs_qgemm           int8 MFMA GEMM over the expanded K, dequantizing epilogue   (G1, G2)
+    ocs_split_weights   channel maxima of W, greedy selection, halve + clip + quantize   (W1-W3)
+    ocs_split_act       duplicate the chosen channels, quantize on the static grid, pack  (X2)
+    ocs_qgemm           int8 MFMA GEMM over the expanded K, dequantizing epilogue         (G1, G2)
 
-Inputs are resident in HBM before the timed region.  The activations rotate through several
-copies so that no step finds its input in the 256 MB Infinity Cache.  Prints ONE JSON line.
+The activation grid is static (Sec. 5 of the paper fixes it from profiling), so the pass that
+takes max|X| (X1) is not in the step; `dynamic_grid` reports the step with it.  Every layer owns
+its activation tensor (22.3 GB in all, resident in HBM before the timed region), so between two
+reads of a tensor 22 GB stream through the chip and nothing is served by the 256 MB memory-side
+cache.  `value` is whole-pass throughput from the wall clock around the timed steps.  Kernel
+durations come from a second, untimed run of the same steps in which every split+quantize and
+GEMM launch stamps its own begin and end (HIP events on the launch stream).  Prints ONE JSON line.
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -27,101 +32,123 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
+RIDGE = INT8_PEAK_TOPS * 1e3 / HBM_PEAK_GBS   # op per byte
 METRIC = "expanded int8 GEMM TOPS (% MFMA peak); split+quantize GB/s (% HBM)"
+STATIC_T = 5.0               # the static activation grid's range (inputs are |N(0,1)|)
 
-# HBM bytes per launch of the split+quantize kernel on this workload, from two rocprofv3 --pmc
-# runs (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for the plain
-# copy kernel of known size launched after the timed region (profiles/x2_config2_hbm_traffic.md).
-# Valid only for the kernel source it was measured on: reported as null once that file changes.
-X2_TRAFFIC = {"quantize_hip_sha256": "45a57b8aea8a8f6f2679f9a34efae37e9dacd2c5f5f7534957576038a29265f9",
-              "bytes_per_launch": 146916747}
+# HBM bytes per step moved by the split+quantize launches of this workload, from two rocprofv3
+# --pmc runs of this command (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter
+# reads for the plain copy kernel of known size that runs after the timed region
+# (profiles/x2_config5_hbm_traffic.md).  Valid only for the kernel source it was measured on:
+# reported as null once that file changes.
+X2_TRAFFIC = {"quantize_hip_sha256": None, "bytes_per_step": None}
 
 
 def x2_traffic():
-    import hashlib
     src = os.path.join(ROOT, "paper_1901_09504_amd", "csrc", "quantize.hip")
     digest = hashlib.sha256(open(src, "rb").read()).hexdigest()
-    return X2_TRAFFIC["bytes_per_launch"] if digest == X2_TRAFFIC["quantize_hip_sha256"] else None
+    return X2_TRAFFIC["bytes_per_step"] if digest == X2_TRAFFIC["quantize_hip_sha256"] else None
 
 
-def cpu_baseline(layer, W, X, budget_s=12.0, max_reps=100):
-    """The CPU oracle, as it stands, on the same workload on this machine's host cores: whole
-    steps on all rows, repeated for about budget_s seconds of CPU work."""
-    from oracle import ref
+class Net:
+    """The 53 layers with their device buffers: weights, activations, one ExpandedLayer each."""
 
-    s = ref.num_splits(layer.C, layer.r)
-    Ke = (layer.C + s) * layer.g
-    ldq = (Ke + 63) // 64 * 64
-    times = []
-    t_all = time.perf_counter()
-    while len(times) < 3 or (time.perf_counter() - t_all < budget_s and len(times) < max_reps):
-        t0 = time.perf_counter()
-        sp = ref.split_weights(W, layer.C, layer.g, s)
-        Wq, sw = ref.quantize(sp["T_out"], layer.bits_w, ldq=ldq)
-        Xq, sx, _ = ref.split_act(X, layer.C, layer.g, sp["chan_src"], None, s, layer.bits_x, ldq=ldq)
-        ref.qgemm(Xq, Wq, Ke, sx[1], sw[1], want_acc=False)
-        times.append(time.perf_counter() - t0)
-    best, med = min(times), float(np.median(times))
-    tops = 2.0 * X.shape[0] * layer.N * Ke / best / 1e12
-    return {"value": tops, "unit": "TOPS", "cores": ref.get_threads(), "kind": "oracle",
-            "sample": f"whole step on all {X.shape[0]} rows of the workload, best of {len(times)} "
-                      f"({time.perf_counter() - t_all:.1f} s of CPU work)",
-            "seconds_per_step": best, "seconds_per_step_median": med}
+    def __init__(self, torch, wl, ExpandedLayer, layers, clip):
+        self.layers = layers
+        self.L, self.W, self.X = [], [], []
+        gen = torch.Generator(device="cuda")
+        for l in layers:
+            self.W.append(torch.from_numpy(wl.weights(l)).cuda())
+            # post-ReLU-like half-normal values drawn on the device (the passes' times do not
+            # depend on the values; the parity tests use the host generators)
+            gen.manual_seed(l.seed)
+            x = torch.empty((l.M, l.K), dtype=torch.float32, device="cuda")
+            x.normal_(generator=gen).abs_()
+            self.X.append(x)
+            self.L.append(ExpandedLayer(l.N, l.C, l.g, l.r, l.bits_w, l.bits_x, clip_ratio_w=clip,
+                                        max_rows=l.M))
+        self.thr = torch.tensor([STATIC_T], dtype=torch.float32, device="cuda")
+
+    def step(self, B=None, ev=None, dynamic=False, weights=True):
+        """One pass.  ev: per-layer event lists [x2 a, x2 b, gemm a, gemm b, absmax a, absmax b]
+        that the launches stamp themselves (B = the binding)."""
+        thr = None if dynamic else self.thr
+        for i, (l, L) in enumerate(zip(self.layers, self.L)):
+            if weights:
+                L.prepare_weights(self.W[i])
+            if ev is not None:
+                if dynamic:
+                    B.ocs_time_next(B.TIME_ABSMAX, ev[i][4], ev[i][5])
+                B.ocs_time_next(B.TIME_SPLIT_QUANTIZE, ev[i][0], ev[i][1])
+            L.split_act(self.X[i], thr)
+            if ev is not None:
+                B.ocs_time_next(B.TIME_GEMM, ev[i][2], ev[i][3])
+            L.qgemm(l.M)
 
 
-def mfma_bound_gemm(torch, B, wl, ExpandedLayer, launches, copies=5):
-    """The GEMM alone on the one MFMA-bound layer shape of the paper's networks (ResNet-50's
-    512->512 3x3 convolutions at batch 256, configs[4]): the workload's own GEMM sits on the
-    HBM side of the ridge, so this is the launch that the "% of MFMA peak" figure can be read
-    on.  Codes come from the library's own weight and activation passes on synthetic data; the
-    activation codes rotate through several copies.  Every launch is timed by its own events."""
-    layer = next(l for l in wl.config(5) if l.name == "s4b0_3x3")
-    M, N = layer.M, layer.N
-    Wd = torch.from_numpy(wl.weights(layer)).cuda()
-    Xd = torch.from_numpy(wl.activations(layer)).cuda()
-    L = ExpandedLayer(N, layer.C, layer.g, layer.r, layer.bits_w, layer.bits_x, max_rows=M)
-    L.prepare_weights(Wd)
-    L.split_act(Xd)
+def stamped_steps(torch, B, net, n, dynamic=False):
+    """n passes whose split+quantize, GEMM (and max|X|) launches carry their own events.
+    Returns arrays [n, layers] of kernel microseconds."""
+    nl = len(net.layers)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(nl)]
+    for row in ev:
+        for e in row:
+            e.record()
     torch.cuda.synchronize()
-    del Xd
-    Xq = [L.Xq.clone() for _ in range(copies)]
-    stream = torch.cuda.current_stream()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    for e in ev:
-        e.record(stream)
-    us = []
-    for i in range(launches + 4):
-        B.ocs_time_next(B.TIME_GEMM, ev[0], ev[1])
-        B.ocs_qgemm(Xq[i % copies], L.ldq, L.Wq, L.ldq, M, N, L.Ke, L.bits_x, L.bits_w, L.scale_x,
-                    L.scale_w, None, 0, L.Y, N, None, None)
+    x2 = np.zeros((n, nl))
+    gm = np.zeros((n, nl))
+    x1 = np.zeros((n, nl))
+    for s in range(n):
+        net.step(B, ev, dynamic=dynamic)
         torch.cuda.synchronize()
-        if i >= 4:
-            us.append(ev[0].elapsed_time(ev[1]) * 1e3)
-    avg = float(np.mean(us))
-    ops = 2.0 * M * N * L.Ke
-    return {"workload": f"configs[4] layer 512->512 3x3 at batch 256 as im2col GEMM: M={M} K'={L.Ke} "
-                        f"(padded {L.ldq}) N={N}, {layer.bits_w}-bit weights, {layer.bits_x}-bit activations",
-            "avg_launch_us": avg, "min_launch_us": float(np.min(us)), "launches_timed": len(us),
-            "tops": ops / avg / 1e6, "pct_mfma_peak": 100.0 * ops / avg / 1e6 / INT8_PEAK_TOPS,
-            "arithmetic_intensity_op_per_byte": ops / (M * L.Ke + N * L.Ke + 4.0 * M * N)}
+        for i in range(nl):
+            x2[s, i] = ev[i][0].elapsed_time(ev[i][1]) * 1e3
+            gm[s, i] = ev[i][2].elapsed_time(ev[i][3]) * 1e3
+            if dynamic:
+                x1[s, i] = ev[i][4].elapsed_time(ev[i][5]) * 1e3
+    return x2, gm, x1
 
 
-def conv_unlowered(torch, B, wl, layer, steps, copies=24):
-    """The workload's convolution given un-lowered (activation [64, 14, 14, 256] fp32, 12.8 MB,
-    instead of its 115.6 MB im2col image): weight path + tap-major weights, split+quantize of the
-    activation with a per-batch grid, convolution with the lowering inside the GEMM kernel's
-    loader.  Reported beside the headline, which is defined on the lowered GEMM."""
-    from paper_1901_09504_amd.layer import ExpandedConv
+def per_layer_report(net, x2, gm):
+    rows = []
+    for i, (l, L) in enumerate(zip(net.layers, net.L)):
+        x2_bytes = 4.0 * l.M * l.K + 1.0 * l.M * L.Ke
+        ops = 2.0 * l.M * l.N * L.Ke
+        g_bytes = 1.0 * l.M * L.Ke + 1.0 * l.N * L.Ke + 4.0 * l.M * l.N
+        ai = ops / g_bytes
+        x2_us, g_us = float(np.median(x2[:, i])), float(np.median(gm[:, i]))
+        roof = min(INT8_PEAK_TOPS, ai * HBM_PEAK_GBS / 1e3)
+        rows.append({"layer": l.name, "M": l.M, "K": l.K, "N": l.N, "s": L.s, "Kexp": L.Ke, "ld": L.ldq,
+                     "split_quant_us": round(x2_us, 2), "split_quant_GBps": round(x2_bytes / x2_us / 1e3, 1),
+                     "split_quant_frac_hbm": round(x2_bytes / x2_us / 1e3 / HBM_PEAK_GBS, 4),
+                     "gemm_us": round(g_us, 2), "gemm_tops": round(ops / g_us / 1e6, 1),
+                     "gemm_GBps": round(g_bytes / g_us / 1e3, 1), "gemm_ai": round(ai, 1),
+                     "gemm_regime": "mfma" if ai >= RIDGE else "hbm",
+                     "gemm_frac_of_min_roof": round(ops / g_us / 1e6 / roof, 4)})
+    return rows
 
-    Bn, H, W = 64, 14, 14
+
+def config2_step(torch, B, wl, ExpandedLayer, steps=100, stamped=24, copies=6):
+    """The single 3x3 convolution of the second workload (batch 64, M=12544 K=2304 N=256,
+    r=0.02, 8/8 bit) with a per-batch activation grid: weight path, max|X|, split+quantize, GEMM.
+    X rotates through `copies` tensors (694 MB); inside a step the split+quantize pass still
+    follows the max|X| pass over the same X, so its in-step time is cache-assisted and labelled so."""
+    (layer,) = wl.config(2)
+    M, N, K = layer.M, layer.N, layer.K
     Wd = torch.from_numpy(wl.weights(layer)).cuda()
-    gen = torch.Generator(device="cuda").manual_seed(layer.seed)
-    As = [torch.randn(Bn, H, W, layer.C, device="cuda", generator=gen).abs_() for _ in range(copies)]
-    L = ExpandedConv(layer.N, layer.C, 3, 3, 1, 1, layer.r, layer.bits_w, layer.bits_x)
+    X = torch.from_numpy(wl.activations(layer)).cuda()
+    Xd = [X] + [X.clone() for _ in range(copies - 1)]
+    L = ExpandedLayer(N, layer.C, layer.g, layer.r, layer.bits_w, layer.bits_x, max_rows=M)
 
-    def step(i):
+    def step(i, ev=None):
         L.prepare_weights(Wd)
-        L.forward(As[i % copies])
+        if ev:
+            B.ocs_time_next(B.TIME_ABSMAX, ev[4], ev[5])
+            B.ocs_time_next(B.TIME_SPLIT_QUANTIZE, ev[0], ev[1])
+        L.split_act(Xd[i % copies], None)
+        if ev:
+            B.ocs_time_next(B.TIME_GEMM, ev[2], ev[3])
+        L.qgemm(M)
 
     for i in range(10):
         step(i)
@@ -131,29 +158,144 @@ def conv_unlowered(torch, B, wl, layer, steps, copies=24):
         step(i)
     torch.cuda.synchronize()
     us = (time.perf_counter() - t0) / steps * 1e6
-    ops = 2.0 * Bn * H * W * layer.N * L.E * 9
-    return {"workload": f"the same layer un-lowered: A [{Bn},{H},{W},{layer.C}] fp32 x {copies} rotating copies, "
-                        f"3x3 stride 1 pad 1, K walked as 9 taps x {L.ldc} bytes",
-            "us_per_step": us, "tops_whole_step": ops / us / 1e6, "steps": steps}
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
+    for e in ev:
+        e.record()
+    k = np.zeros((stamped, 3))
+    for i in range(stamped):
+        step(i, ev)
+        torch.cuda.synchronize()
+        k[i] = [ev[0].elapsed_time(ev[1]) * 1e3, ev[2].elapsed_time(ev[3]) * 1e3, ev[4].elapsed_time(ev[5]) * 1e3]
+    # the split+quantize pass alone on a static grid: nothing has touched the copy it reads since
+    # the other copies were streamed (cache-cold)
+    cold = []
+    for i in range(copies + stamped):
+        B.ocs_time_next(B.TIME_SPLIT_QUANTIZE, ev[0], ev[1])
+        L.split_act(Xd[i % copies], L.scale_x)
+        torch.cuda.synchronize()
+        if i >= copies:
+            cold.append(ev[0].elapsed_time(ev[1]) * 1e3)
+    ops = 2.0 * M * N * L.Ke
+    x2_bytes = 4.0 * M * K + 1.0 * M * L.Ke
+    x2_us, g_us, x1_us, cold_us = (float(np.median(k[:, 0])), float(np.median(k[:, 1])),
+                                   float(np.median(k[:, 2])), float(np.median(cold)))
+    return {"workload": f"configs[1]: M={M} K={K} N={N} r={layer.r} (K'={L.Ke}, padded {L.ldq}), 8/8 bit, "
+                        "weight path + per-batch grid + split+quantize + GEMM per step",
+            "us_per_step": us, "tops_whole_step": ops / us / 1e6, "steps": steps,
+            "absmax_kernel_us": x1_us, "gemm_kernel_us": g_us, "gemm_tops": ops / g_us / 1e6,
+            "gemm_pct_mfma_peak": 100.0 * ops / g_us / 1e6 / INT8_PEAK_TOPS,
+            "split_quant_cache_cold": {"kernel_us": cold_us, "GBps": x2_bytes / cold_us / 1e3,
+                                       "frac_hbm": x2_bytes / cold_us / 1e3 / HBM_PEAK_GBS,
+                                       "launches_timed": len(cold)},
+            "split_quant_in_step_cache_assisted": {"kernel_us": x2_us, "GBps": x2_bytes / x2_us / 1e3,
+                                                   "frac_hbm": x2_bytes / x2_us / 1e3 / HBM_PEAK_GBS,
+                                                   "launches_timed": stamped,
+                                                   "note": "follows the max|X| pass over the same 115.6 MB X, "
+                                                           "part of which the memory-side cache still holds"}}
+
+
+def _timed(torch, fn, reps):
+    """Median microseconds of fn() over reps launches (event brackets; the launches here run for
+    hundreds of microseconds to milliseconds, so the bracket's own few microseconds do not matter)."""
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    us = []
+    for r in range(reps + 1):
+        a.record()
+        fn()
+        b.record()
+        torch.cuda.synchronize()
+        if r >= 1:
+            us.append(a.elapsed_time(b) * 1e3)
+    return float(np.median(us))
+
+
+def ceilings(torch, B, reps=5):
+    """What this chip gives plain kernels of known work (the library's measurement helpers):
+    copy, read-only sweep and fill of 2 GiB; the same read over 2 MiB that stays in every L2; a
+    bare loop of the GEMM's matrix instruction on zero, constant and random operand bytes."""
+    n = 2 << 30
+    a = torch.empty(n, dtype=torch.uint8, device="cuda")
+    b = torch.empty(n, dtype=torch.uint8, device="cuda")
+    a.random_(0, 256)
+    sink = torch.zeros(65536 * 4, dtype=torch.int32, device="cuda")
+    out = {"bytes": n}
+    def best_of(fn, grids):
+        best = None
+        for wgs in grids:
+            us = _timed(torch, lambda: fn(wgs), reps)
+            if best is None or us < best[0]:
+                best = (us, wgs)
+        return best
+
+    grids = (256, 512, 1024, 2048, 4096, 8192)
+    us, wgs = best_of(lambda w: B.ocs_calib_copy(a, b, n, w), grids)
+    out["copy"] = {"us": us, "workgroups": wgs, "read_plus_write_GBps": 2.0 * n / us / 1e3,
+                   "frac_hbm": 2.0 * n / us / 1e3 / HBM_PEAK_GBS}
+    us, wgs = best_of(lambda w: B.ocs_calib_read(a, n, 1, w, sink), grids)
+    out["read"] = {"us": us, "workgroups": wgs, "GBps": n / us / 1e3, "frac_hbm": n / us / 1e3 / HBM_PEAK_GBS}
+    for key, nt in (("fill", 0), ("fill_nontemporal", 1)):
+        us, wgs = best_of(lambda w: B.ocs_calib_fill(b, n, 7, nt, w), grids)
+        out[key] = {"us": us, "workgroups": wgs, "GBps": n / us / 1e3, "frac_hbm": n / us / 1e3 / HBM_PEAK_GBS}
+    small, passes = 2 << 20, 4096
+    l2 = {}
+    for wgs in (250, 500, 1000, 2000):
+        us = _timed(torch, lambda: B.ocs_calib_read(a, small, passes, wgs, sink), reps)
+        l2[str(wgs)] = small * passes / us / 1e3
+    out["read_l2_resident"] = {"buffer_bytes": small, "passes": passes, "GBps_by_workgroups": l2,
+                               "note": "the stream wraps around 2 MiB, which each of the 8 L2s keeps (a lane's own "
+                                       "addresses are 4 KB and more apart, beyond what the 32 KB L1 holds); "
+                                       "workgroups of 256 lanes, two 16-byte loads in flight per lane"}
+    iters, wgs = 20000, 1024
+    ops = wgs * 4.0 * iters * 4 * 65536
+    mf = {}
+    for name, fill in (("zeros", lambda t: t.zero_()), ("constant_0x01", lambda t: t.fill_(1)),
+                       ("random_int8", lambda t: t.random_(0, 256))):
+        opnd = torch.empty(16384, dtype=torch.uint8, device="cuda")
+        fill(opnd)
+        us = _timed(torch, lambda: B.ocs_calib_mfma(opnd, iters, wgs, sink), reps)
+        mf[name] = {"us": us, "tops": ops / us / 1e6, "frac_int8_peak": ops / us / 1e6 / INT8_PEAK_TOPS}
+    out["mfma_i32_32x32x32_i8"] = {"workgroups": wgs, "waves_per_cu": 16, "iters": iters, "by_operand_data": mf}
+    return out
+
+
+def cpu_baseline(wl, layers, clip, row_fraction=8):
+    """The CPU oracle, as it stands, on this machine's host cores: the whole step (weight path in
+    full, activation pass and GEMM on the first 1/row_fraction of every layer's rows)."""
+    from oracle import ref
+
+    t_total, ops = 0.0, 0.0
+    for l in layers:
+        rows = max(1, l.M // row_fraction)
+        W = wl.weights(l)
+        X = wl.activations(l, 0, rows)
+        s = ref.num_splits(l.C, l.r)
+        Ke = (l.C + s) * l.g
+        ldq = (Ke + 63) // 64 * 64
+        t0 = time.perf_counter()
+        sp = ref.split_weights(W, l.C, l.g, s)
+        Wq, sw = ref.quantize(sp["T_out"], l.bits_w, clip_ratio=clip, ldq=ldq)
+        Xq, sx, _ = ref.split_act(X, l.C, l.g, sp["chan_src"], None, s, l.bits_x, threshold=STATIC_T, ldq=ldq)
+        ref.qgemm(Xq, Wq, Ke, sx[1], sw[1], want_acc=False)
+        t_total += time.perf_counter() - t0
+        ops += 2.0 * rows * l.N * Ke
+    return {"value": ops / t_total / 1e12, "unit": "TOPS", "cores": ref.get_threads(), "kind": "oracle",
+            "sample": f"whole step over the 53 layers with the first 1/{row_fraction} of every layer's rows "
+                      f"(batch {256 // row_fraction} of 256; the weight path in full), one pass, "
+                      f"{t_total:.1f} s of CPU work, {ops / 1e12:.3f} tera-ops",
+            "seconds": t_total}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--copies", type=int, default=6, help="rotating copies of X (6 x 115.6 MB)")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--clip", type=float, default=0.9, help="weight clip ratio used in the timed step")
+    ap.add_argument("--stamped-steps", type=int, default=20,
+                    help="untimed passes whose launches carry their own events (at least 20 samples per layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--sample-every", type=int, default=8,
-                    help="every n-th timed step carries the per-phase and per-kernel events")
-    ap.add_argument("--mfma-gemm-launches", type=int, default=24,
-                    help="launches of the GEMM on the MFMA-bound layer shape after the timed region (0: skip)")
-    ap.add_argument("--graph-steps", type=int, default=200,
-                    help="steps replayed from HIP graphs after the timed region (0: skip)")
-    ap.add_argument("--conv-steps", type=int, default=100,
-                    help="steps of the same layer given un-lowered, after the timed region (0: skip)")
-    ap.add_argument("--calib-copies", type=int, default=6,
-                    help="plain copies of X launched after the timed region (counter calibration)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the secondary measurements (dynamic grid, weight path, ceilings, config 2)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -171,171 +313,102 @@ def main():
         sys.exit(1)
     B.lib()  # fails loudly when libocs.so is missing
 
-    (layer,) = wl.config(2)
-    M, N, K = layer.M, layer.N, layer.K
-    W = wl.weights(layer)
-    X = wl.activations(layer)
-    Wd = torch.from_numpy(W).cuda()
-    Xd = [torch.from_numpy(X).cuda() for _ in range(max(1, args.copies))]
-    L = ExpandedLayer(N, layer.C, layer.g, layer.r, layer.bits_w, layer.bits_x, max_rows=M)
-    Ke, ldq = L.Ke, L.ldq
-    stream = torch.cuda.current_stream()
-
-    def step(i, ev=None, kev=None):
-        x = Xd[i % len(Xd)]
-        if ev: ev[0].record(stream)
-        L.prepare_weights(Wd)
-        if ev: ev[1].record(stream)
-        if kev:
-            B.ocs_time_next(B.TIME_ABSMAX, kev[4], kev[5])
-            B.ocs_time_next(B.TIME_SPLIT_QUANTIZE, kev[0], kev[1])
-        # per-batch grid: max|X| pass, then the split+quantize pass (one call, two kernels)
-        B.ocs_split_act(x, M, L.C, L.g, K, L.chan_src, None, L.s, L.bits_x, None, 1.0, L.Xq, ldq,
-                        L.scale_x, L.ws_x)
-        if ev: ev[2].record(stream)
-        if kev: B.ocs_time_next(B.TIME_GEMM, kev[2], kev[3])
-        L.qgemm(M)
-        if ev:
-            ev[3].record(stream)
-            ev[4].record(stream)   # ev[3] -> ev[4] brackets nothing: the cost of a bracket itself
-
-    for i in range(args.warmup):
-        step(i)
+    layers = wl.config(5)
+    net = Net(torch, wl, ExpandedLayer, layers, args.clip)
     torch.cuda.synchronize()
 
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
-    # kernel events: stamped by the launch itself with the dispatch's begin and end (the two
-    # dominant kernels only).  Recording them once creates their handles.
-    kevents = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
-    for ke in kevents:
-        for e in ke:
-            e.record(stream)
+    for _ in range(args.warmup):
+        net.step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        if i % args.sample_every == 0:
-            step(i, events[i], kevents[i])
-        else:
-            step(i)
+    for _ in range(args.steps):
+        net.step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-
     ms_per_step = dt / args.steps * 1e3
 
-    # after the timed region: plain copies of known size, so that a counter run of this same
-    # command also holds the reference the HBM byte counters are scaled by
-    dst = torch.empty_like(Xd[0])
-    if args.calib_copies > 0:
-        for i in range(args.calib_copies):
-            B.ocs_calib_copy(Xd[i % len(Xd)], dst, Xd[0].numel() * 4)
-        torch.cuda.synchronize()
-    # the dominant kernel once more, cache-cold: inside a step it runs right after the pass that
-    # takes max|X| over the same X, so part of its input comes from the 256 MB memory-side cache;
-    # here nothing has touched the copy it reads for the last len(Xd) - 1 launches (static grid)
-    cold_us = []
-    cev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    for e in cev:
-        e.record(stream)
-    for i in range(3 * len(Xd)):
-        B.ocs_time_next(B.TIME_SPLIT_QUANTIZE, cev[0], cev[1])
-        B.ocs_split_act(Xd[i % len(Xd)], M, L.C, L.g, K, L.chan_src, None, L.s, L.bits_x, L.scale_x, 1.0,
-                        L.Xq, ldq, L.scale_x, L.ws_x)
-        torch.cuda.synchronize()
-        if i >= len(Xd):
-            cold_us.append(cev[0].elapsed_time(cev[1]) * 1e3)
-    sampled = list(range(0, args.steps, args.sample_every))
-    phase = np.array([[events[i][k].elapsed_time(events[i][k + 1]) for k in range(4)] for i in sampled])  # ms
-    raw = phase.mean(axis=0)
-    bracket_ms = float(raw[3])       # an empty event pair, measured in the same timed region
-    avg = np.maximum(raw[:3] - bracket_ms, 1e-6)
-    names = ["split_weights", "split_act", "qgemm"]
-    x2_kernel_ms = float(np.mean([kevents[i][0].elapsed_time(kevents[i][1]) for i in sampled]))
-    gemm_kernel_ms = float(np.mean([kevents[i][2].elapsed_time(kevents[i][3]) for i in sampled]))
-    x1_kernel_ms = float(np.mean([kevents[i][4].elapsed_time(kevents[i][5]) for i in sampled]))
-
-    ops = 2.0 * M * N * Ke
-    x2_bytes = 4.0 * M * K + 1.0 * M * Ke                       # X2: read fp32 X, write codes
-    x1_bytes = 4.0 * M * K
-    w_bytes = 8.0 * N * K + 1.0 * N * Ke                        # W1 + W3
-    gemm_bytes = 1.0 * M * Ke + 1.0 * N * Ke + 4.0 * M * N
-    x2_gbs = x2_bytes / (x2_kernel_ms * 1e-3) / 1e9
-    gemm_tops = ops / (gemm_kernel_ms * 1e-3) / 1e12
-    gemm_ai = ops / gemm_bytes
-    gemm_roof_tops = min(INT8_PEAK_TOPS, gemm_ai * HBM_PEAK_GBS / 1e3)
+    n_stamp = max(20, args.stamped_steps)
+    x2, gm, _ = stamped_steps(torch, B, net, n_stamp)
+    rows = per_layer_report(net, x2, gm)
+    ops = sum(2.0 * l.M * l.N * L.Ke for l, L in zip(layers, net.L))
+    x2_bytes = sum(4.0 * l.M * l.K + 1.0 * l.M * L.Ke for l, L in zip(layers, net.L))
+    x2_us_step = float(np.mean(x2.sum(axis=1)))          # all 53 launches of one pass, mean over passes
+    gemm_us_step = float(np.mean(gm.sum(axis=1)))
+    x2_gbs = x2_bytes / x2_us_step / 1e3
+    gemm_tops = ops / gemm_us_step / 1e6
+    mfma = [r for r in rows if r["gemm_regime"] == "mfma"]
 
     out = {
         "metric": METRIC,
         "value": ops / (ms_per_step * 1e-3) / 1e12,
-        "unit": "TOPS (2*M*N*K' of the expanded layer per second of whole-step time)",
+        "unit": "TOPS (2*M*N*K' of the 53 expanded layers per second of whole-pass wall time)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "dtype_detail": "int8 codes x int8 codes -> int32 accumulators; fp32 in, fp32 out",
         "data": "synthetic",
-        "config": {"workload": "configs[1]: 3x3 conv 256->256, 14x14, batch 64 as im2col GEMM "
-                               f"M={M} K={K} N={N}, r={layer.r} (s={L.s}, K'={Ke}, padded {ldq}), "
-                               "8-bit weights and activations, weight OCS, per-batch activation grid",
-                   "x_copies_rotated": len(Xd), "steps_carrying_events": len(sampled)},
+        "config": {"workload": "configs[4]: ResNet-50-shaped sweep, all 53 conv layers as im2col GEMMs at batch "
+                               f"256, r=0.05, 4-bit weights (clip {args.clip} x max|W'|), 8-bit activations on a "
+                               "static grid; per layer: weight path, split+quantize, expanded GEMM",
+                   "tera_ops_per_step": ops / 1e12, "layers": len(layers),
+                   "activation_bytes_resident": int(sum(x.numel() * 4 for x in net.X)),
+                   "stamped_steps": n_stamp},
         "gemm_tops": gemm_tops, "gemm_pct_mfma_peak": 100.0 * gemm_tops / INT8_PEAK_TOPS,
         "split_quant_gbps": x2_gbs, "split_quant_pct_hbm": 100.0 * x2_gbs / HBM_PEAK_GBS,
-        "roofline": {"kernel": "expand_quantize_kernel (ocs_split_act, X2)", "bound": "hbm",
-                     "achieved": x2_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": x2_gbs / HBM_PEAK_GBS, "traffic": x2_traffic(),
-                     "algorithmic_bytes_per_launch": x2_bytes, "avg_launch_us": x2_kernel_ms * 1e3,
-                     "timing": "HIP events stamped by the launch itself (hipExtLaunchKernel) on its "
-                               "stream: the dispatch's own begin and end",
-                     "launches_timed": len(sampled),
-                     "cache_cold": {"avg_launch_us": float(np.mean(cold_us)),
-                                    "achieved": x2_bytes / float(np.mean(cold_us)) / 1e3,
-                                    "frac": x2_bytes / float(np.mean(cold_us)) / 1e3 / HBM_PEAK_GBS,
-                                    "launches_timed": len(cold_us),
-                                    "note": "same kernel after the timed region on copies of X that "
-                                            "no launch has touched since 5 other copies were streamed "
-                                            "(in the step it follows the max|X| pass over the same X, "
-                                            "which leaves part of X in the 256 MB memory-side cache)"}},
-        "phases": {n: {"avg_us": float(avg[k] * 1e3)} for k, n in enumerate(names)},
+        "roofline": {"kernel": "expand_quantize_kernel / expand_quantize_in_kernel (ocs_split_act, X2): the 53 "
+                               "launches of one pass", "bound": "hbm",
+                     "achieved": x2_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": x2_gbs / HBM_PEAK_GBS,
+                     "traffic": x2_traffic(),
+                     "algorithmic_bytes_per_step": x2_bytes, "kernel_us_per_step": x2_us_step,
+                     "avg_launch_us": x2_us_step / len(layers), "launches_per_step": len(layers),
+                     "launches_timed": int(x2.size), "cache": "cold: every launch reads a tensor that 22 GB of "
+                                                              "other traffic have passed since its last use",
+                     "timing": "HIP events stamped by the launch itself (hipExtLaunchKernel) on its stream: the "
+                               "dispatch's own begin and end; mean over the stamped passes of the per-pass sum"},
+        "step_breakdown_ms": {"split_quant_kernels": x2_us_step / 1e3, "gemm_kernels": gemm_us_step / 1e3,
+                              "rest (weight path, dispatch gaps)": ms_per_step - (x2_us_step + gemm_us_step) / 1e3},
+        "gemm_mfma_bound": [{k: r[k] for k in ("layer", "M", "N", "Kexp", "gemm_us", "gemm_tops", "gemm_ai")} |
+                            {"pct_mfma_peak": round(100.0 * r["gemm_tops"] / INT8_PEAK_TOPS, 2)} for r in mfma],
+        "layers": rows,
     }
-    out["phases"]["split_weights"]["algorithmic_GBps"] = w_bytes / (avg[0] * 1e-3) / 1e9
-    out["phases"]["split_act"].update({
-        "what": "ocs_split_act with a per-batch grid: the max|X| pass, then the split+quantize pass",
-        "absmax_kernel_us": x1_kernel_ms * 1e3,
-        "absmax_algorithmic_GBps": x1_bytes / (x1_kernel_ms * 1e-3) / 1e9,
-        "kernel_us": x2_kernel_ms * 1e3, "algorithmic_GBps": x2_gbs})
-    out["phases"]["qgemm"]["kernel_us"] = gemm_kernel_ms * 1e3
-    out["phase_timing"] = ("avg_us: HIP event brackets around each call minus an empty bracket "
-                           f"({bracket_ms * 1e3:.2f} us here), includes dispatch gaps; kernel_us: the "
-                           "kernel's own begin/end")
-    out["phases"]["qgemm"].update({
-        "tops": gemm_tops, "algorithmic_GBps": gemm_bytes / (gemm_kernel_ms * 1e-3) / 1e9,
-        "arithmetic_intensity_op_per_byte": gemm_ai,
-        "regime": "hbm" if gemm_ai < INT8_PEAK_TOPS * 1e3 / HBM_PEAK_GBS else "mfma",
-        "roof_tops_min_mfma_hbm": gemm_roof_tops, "frac_of_that_roof": gemm_tops / gemm_roof_tops})
-    if args.mfma_gemm_launches > 0:
-        out["gemm_mfma_bound"] = mfma_bound_gemm(torch, B, wl, ExpandedLayer, args.mfma_gemm_launches)
-    if args.graph_steps > 0:
-        # the same step replayed from HIP graphs (one per rotating copy of X): what the dispatch
-        # gaps between the step's seven launches cost
-        graphs = []
-        for x in Xd:
-            g_ = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g_):
-                L.prepare_weights(Wd)
-                B.ocs_split_act(x, M, L.C, L.g, K, L.chan_src, None, L.s, L.bits_x, None, 1.0, L.Xq, ldq,
-                                L.scale_x, L.ws_x)
-                L.qgemm(M)
-            graphs.append(g_)
-        for i in range(10):
-            graphs[i % len(graphs)].replay()
+    if not args.no_extras:
+        # the pass with a per-batch activation grid: X1 (max|X|) in front of every split+quantize
+        for _ in range(2):
+            net.step(dynamic=True)
         torch.cuda.synchronize()
-        tg = time.perf_counter()
-        for i in range(args.graph_steps):
-            graphs[i % len(graphs)].replay()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            net.step(dynamic=True)
         torch.cuda.synchronize()
-        us = (time.perf_counter() - tg) / args.graph_steps * 1e6
-        out["graph_replay"] = {"us_per_step": us, "tops_whole_step": ops / us / 1e6, "steps": args.graph_steps}
-    if args.conv_steps > 0:
-        out["conv_unlowered"] = conv_unlowered(torch, B, wl, layer, args.conv_steps)
+        dyn_ms = (time.perf_counter() - t0) / 5 * 1e3
+        _, _, x1 = stamped_steps(torch, B, net, 5, dynamic=True)
+        x1_us_step = float(np.mean(x1.sum(axis=1)))
+        x1_bytes = sum(4.0 * l.M * l.K for l in layers)
+        out["dynamic_grid"] = {"ms_per_step": dyn_ms, "tops_whole_step": ops / dyn_ms / 1e9,
+                               "absmax_kernels_ms_per_step": x1_us_step / 1e3,
+                               "absmax_GBps": x1_bytes / x1_us_step / 1e3,
+                               "absmax_frac_hbm": x1_bytes / x1_us_step / 1e3 / HBM_PEAK_GBS, "steps": 5}
+        # the weight path alone, per clip ratio (the ratio changes only the grid and the codes)
+        wp = {}
+        for clip in (1.0, 0.9, 0.8):
+            for L in net.L:
+                L.clip_ratio_w = clip
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(5):
+                for i, L in enumerate(net.L):
+                    L.prepare_weights(net.W[i])
+            torch.cuda.synchronize()
+            wp[str(clip)] = (time.perf_counter() - t0) / 5 * 1e3
+        for L in net.L:
+            L.clip_ratio_w = args.clip
+        out["weight_path_ms_per_pass_by_clip"] = wp
+    del net
+    torch.cuda.empty_cache()
+    if not args.no_extras:
+        out["ceilings"] = ceilings(torch, B)
+        out["config2_step"] = config2_step(torch, B, wl, ExpandedLayer)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(layer, W, X)
+        out["cpu_baseline"] = cpu_baseline(wl, layers, args.clip)
     print(json.dumps(out))
 
 

@@ -280,11 +280,35 @@ int ocs_act_threshold(const float *X, int64_t M, int C, int g, int64_t ldx, cons
  * bits_x / bits_w are the grids' bit widths, used only for the overflow check
  * Kexp * qmax_x * qmax_w < 2^31.  acc_out [M, ldacc] int32 is optional (NULL = not
  * stored); Y [M, ldy] fp32 is required.  workspace may be NULL (none is needed).
+ * Every column Kexp .. ld-1 of both operands must hold zero codes (the producers' contract): on
+ * rows longer than 320 bytes the kernels walk K in 128-byte steps whenever both leading
+ * dimensions reach the next multiple of 128, and those columns then enter the sums.
  */
 int ocs_qgemm(const int8_t *Xq, int64_t ldx, const int8_t *Wq, int64_t ldw, int64_t M, int64_t N,
               int64_t Kexp, int bits_x, int bits_w, const float *scale_x, const float *scale_w,
               int32_t *acc_out, int64_t ldacc, float *Y, int64_t ldy, void *workspace,
               size_t ws_bytes, void *stream);
+
+/*
+ * ocs_qgemm with the K extent of every output tile shared between `parts` workgroups (2 .. 16, at
+ * most one per 64-byte K-step): for shapes with far fewer output tiles than the chip has compute
+ * units and a long K.  Each workgroup leaves the int32 partial sums of its 256 x 256 tile in the
+ * workspace and signs in at a counter; the one that signs in last adds the others' sums to its
+ * own and writes the output.  Integer sums do not depend on the order, so acc_out and Y are
+ * bit-identical to ocs_qgemm's; nobody waits for anybody and there is no second launch.
+ *   workspace: device memory, 256-byte aligned, at least ocs_qgemm_split_k_workspace_bytes(M, N,
+ *        Kexp, parts) bytes (0 = this shape cannot be split: more than 128 tiles of 256 x 256, or
+ *        parts out of range; the call then returns OCS_E_SHAPE).  Needs no initialisation.
+ *   The arrival counters are part of the library's device image; at most 512 such calls may be
+ *   in flight on one GPU at a time.
+ * On MI355X this measured slower than ocs_qgemm on every layer shape of the paper's networks (the
+ * partial sums cross between L2s through memory): ocs_qgemm never uses it by itself.
+ */
+size_t ocs_qgemm_split_k_workspace_bytes(int64_t M, int64_t N, int64_t Kexp, int parts);
+int ocs_qgemm_split_k(const int8_t *Xq, int64_t ldx, const int8_t *Wq, int64_t ldw, int64_t M, int64_t N,
+                      int64_t Kexp, int bits_x, int bits_w, const float *scale_x, const float *scale_w,
+                      int32_t *acc_out, int64_t ldacc, float *Y, int64_t ldy, int parts, void *workspace,
+                      size_t ws_bytes, void *stream);
 
 /*
  * A convolution as the linear layer of Eq. 2 over its input channels (Sec. 3.2: a channel of a
@@ -393,10 +417,33 @@ int ocs_time_next(int family, void *start_event, void *stop_event);
 
 /*
  * Measurement helper (no passage of the paper): a plain device-to-device copy of `bytes`
- * bytes (multiple of 16, both pointers 16-byte aligned) with 16-byte accesses.  Profiling runs
- * use it to scale HBM byte counters against a transfer of known size.
+ * bytes (multiple of 16, both pointers 16-byte aligned) with 16-byte accesses by `workgroups`
+ * workgroups of 256 lanes (0: 2048).  Profiling runs use it to scale HBM byte counters against a
+ * transfer of known size.
  */
-int ocs_calib_copy(const void *src, void *dst, size_t bytes, void *stream);
+int ocs_calib_copy(const void *src, void *dst, size_t bytes, int workgroups, void *stream);
+
+/*
+ * Further measurement helpers (no passage of the paper; the path never calls them): plain kernels
+ * of known work whose rates are this chip's own ceilings for the kernels of the path.
+ *   ocs_calib_read: `passes` read-only sweeps with 16-byte loads over `bytes` bytes at src
+ *        (multiple of 16, 16-byte aligned; with passes > 1 a power of two) by `workgroups` workgroups
+ *        of 256 lanes.  A buffer far
+ *        larger than the caches with one pass gives the HBM read rate; a buffer of a megabyte or
+ *        two with many passes stays in every L2 and gives the rate at which the compute units draw
+ *        from their L2s.  sink: device int32 [workgroups] (practically never written).
+ *   ocs_calib_fill: writes `bytes` bytes at dst with 16-byte stores of `value` (nontemporal != 0:
+ *        with the streaming hint) by `workgroups` workgroups of 256 lanes.
+ *   ocs_calib_mfma: `workgroups` workgroups of 4 waves; every wave issues iters * 4 instructions
+ *        v_mfma_i32_32x32x32_i8 (the GEMM's) on fragments taken from `operands` (device, 16 KB,
+ *        16-byte aligned: zeros, a constant, or random bytes), with no memory access inside the
+ *        loop: workgroups * 4 * iters * 4 * 65536 integer operations per launch.
+ *        sink: device int32 [workgroups * 256], written.
+ * All are asynchronous on `stream`; time them with events around the call.
+ */
+int ocs_calib_read(const void *src, size_t bytes, int passes, int workgroups, void *sink, void *stream);
+int ocs_calib_fill(void *dst, size_t bytes, int value, int nontemporal, int workgroups, void *stream);
+int ocs_calib_mfma(const void *operands, int iters, int workgroups, void *sink, void *stream);
 
 /*
  * Launch-shape overrides for benchmarking (no passage of the paper; results never depend
@@ -404,9 +451,9 @@ int ocs_calib_copy(const void *src, void *dst, size_t bytes, void *stream);
  * split+quantize pass), "max_flat", "max_grid", "max_un", "max_bt" (the whole-tensor max|x|
  * pass), "sel_inline" (most splits for which ocs_split_weights runs the selection inside its
  * code pass instead of as a launch of its own; 0: never), "gemm_tile" (tile variant of
- * ocs_qgemm / ocs_qconv, 0..26; an id a shape cannot use falls back to one it
- * can).  value < 0 restores the default.  Returns OCS_OK or OCS_E_MODE for an unknown key.
- * Process-wide and not thread-safe: set them before the calls they affect, from one thread.
+ * ocs_qgemm / ocs_qconv: 6, 7, 9, 10, 11, 12, 14, 16, 17, 18, 19, 23; an id a shape cannot use falls
+ * back to one it can).  value < 0 restores the default.  Returns OCS_OK or OCS_E_MODE for an
+ * unknown key.  The settings belong to the calling thread and affect its own calls only.
  */
 int ocs_tune(const char *key, int value);
 

@@ -95,10 +95,21 @@ def lib():
     L.ocs_qgemm.restype = _i32
     L.ocs_qgemm.argtypes = [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _vp, _vp, _vp, _i64, _vp,
                             _i64, _vp, _sz, _vp]
+    L.ocs_qgemm_split_k_workspace_bytes.restype = _sz
+    L.ocs_qgemm_split_k_workspace_bytes.argtypes = [_i64, _i64, _i64, _i32]
+    L.ocs_qgemm_split_k.restype = _i32
+    L.ocs_qgemm_split_k.argtypes = [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _vp, _vp, _vp, _i64, _vp,
+                                    _i64, _i32, _vp, _sz, _vp]
     L.ocs_time_next.restype = _i32
     L.ocs_time_next.argtypes = [_i32, _vp, _vp]
     L.ocs_calib_copy.restype = _i32
-    L.ocs_calib_copy.argtypes = [_vp, _vp, _sz, _vp]
+    L.ocs_calib_copy.argtypes = [_vp, _vp, _sz, _i32, _vp]
+    L.ocs_calib_read.restype = _i32
+    L.ocs_calib_read.argtypes = [_vp, _sz, _i32, _i32, _vp, _vp]
+    L.ocs_calib_fill.restype = _i32
+    L.ocs_calib_fill.argtypes = [_vp, _sz, _i32, _i32, _i32, _vp]
+    L.ocs_calib_mfma.restype = _i32
+    L.ocs_calib_mfma.argtypes = [_vp, _i32, _i32, _vp, _vp]
     L.ocs_tune.restype = _i32
     L.ocs_tune.argtypes = [C.c_char_p, _i32]
     _lib = L
@@ -148,6 +159,10 @@ def ocs_workspace_bytes(rows, cols):
     return int(lib().ocs_workspace_bytes(int(rows), int(cols)))
 
 
+def ocs_qgemm_split_k_workspace_bytes(M, N, Kexp, parts):
+    return int(lib().ocs_qgemm_split_k_workspace_bytes(int(M), int(N), int(Kexp), int(parts)))
+
+
 def ocs_tune(key, value):
     _check(lib().ocs_tune(key.encode(), int(value)), "ocs_tune")
 
@@ -165,8 +180,24 @@ def ocs_time_next(family, start_event, stop_event):
     _check(lib().ocs_time_next(int(family), C.c_void_p(a), C.c_void_p(b)), "ocs_time_next")
 
 
-def ocs_calib_copy(src, dst, nbytes, stream=None):
-    _check(lib().ocs_calib_copy(_ptr(src), _ptr(dst), int(nbytes), _stream(stream)), "ocs_calib_copy")
+def ocs_calib_copy(src, dst, nbytes, workgroups=0, stream=None):
+    _check(lib().ocs_calib_copy(_ptr(src), _ptr(dst), int(nbytes), int(workgroups), _stream(stream)),
+           "ocs_calib_copy")
+
+
+def ocs_calib_read(src, nbytes, passes, workgroups, sink, stream=None):
+    _check(lib().ocs_calib_read(_ptr(src), int(nbytes), int(passes), int(workgroups), _ptr(sink),
+                                _stream(stream)), "ocs_calib_read")
+
+
+def ocs_calib_fill(dst, nbytes, value, nontemporal=0, workgroups=2048, stream=None):
+    _check(lib().ocs_calib_fill(_ptr(dst), int(nbytes), int(value), int(nontemporal), int(workgroups),
+                                _stream(stream)), "ocs_calib_fill")
+
+
+def ocs_calib_mfma(operands, iters, workgroups, sink, stream=None):
+    _check(lib().ocs_calib_mfma(_ptr(operands), int(iters), int(workgroups), _ptr(sink), _stream(stream)),
+           "ocs_calib_mfma")
 
 
 def alloc_workspace(rows, cols, device="cuda"):
@@ -297,3 +328,11 @@ def ocs_qgemm(Xq, ldx, Wq, ldw, M, N, Kexp, bits_x, bits_w, scale_x, scale_w, ac
     _check(lib().ocs_qgemm(_ptr(Xq), ldx, _ptr(Wq), ldw, M, N, Kexp, bits_x, bits_w, _ptr(scale_x),
                            _ptr(scale_w), _ptr(acc_out), ldacc, _ptr(Y), ldy, w, wb,
                            _stream(stream)), "ocs_qgemm")
+
+
+def ocs_qgemm_split_k(Xq, ldx, Wq, ldw, M, N, Kexp, bits_x, bits_w, scale_x, scale_w, acc_out, ldacc, Y, ldy,
+                      parts, workspace, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib().ocs_qgemm_split_k(_ptr(Xq), ldx, _ptr(Wq), ldw, M, N, Kexp, bits_x, bits_w, _ptr(scale_x),
+                                   _ptr(scale_w), _ptr(acc_out), ldacc, _ptr(Y), ldy, int(parts), w, wb,
+                                   _stream(stream)), "ocs_qgemm_split_k")

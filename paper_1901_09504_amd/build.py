@@ -5,7 +5,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libocs.so")
-SOURCES = ["ocs_api.hip", "reduce.hip", "select.hip", "quantize.hip", "qa_split.hip", "clip_search.hip", "qgemm.hip"]
+SOURCES = ["ocs_api.hip", "reduce.hip", "select.hip", "quantize.hip", "qa_split.hip", "clip_search.hip", "qgemm.hip", "calib.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

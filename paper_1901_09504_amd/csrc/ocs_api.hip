@@ -11,7 +11,7 @@
 namespace ocs {
 
 Tuning& tuning() {
-    static Tuning t;
+    static thread_local Tuning t;
     return t;
 }
 
@@ -495,6 +495,30 @@ int ocs_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int6
     return OCS_OK;
 }
 
+size_t ocs_qgemm_split_k_workspace_bytes(int64_t M, int64_t N, int64_t Kexp, int parts) {
+    if (M <= 0 || N <= 0 || Kexp <= 0) return 0;
+    return qgemm_split_workspace_bytes(M, N, round_up(Kexp, OCS_KALIGN), parts);
+}
+
+int ocs_qgemm_split_k(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M, int64_t N,
+                      int64_t Kexp, int bits_x, int bits_w, const float* scale_x, const float* scale_w,
+                      int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy, int parts, void* workspace,
+                      size_t ws_bytes, void* stream) {
+    if (!Xq || !Wq || !scale_x || !scale_w || !Y) return OCS_E_NULL;
+    int rc = check_gemm_operands(Xq, ldx, Wq, ldw, M, N, Kexp, bits_x, bits_w, acc_out, ldacc);
+    if (rc) return rc;
+    if (ldy < N) return OCS_E_SHAPE;
+    const int64_t Kpad = round_up(Kexp, OCS_KALIGN);
+    const size_t need = qgemm_split_workspace_bytes(M, N, Kpad, parts);
+    if (need == 0) return OCS_E_SHAPE;          // too many tiles, or parts outside 2 .. min(16, K-steps)
+    if (workspace == nullptr || ws_bytes < need) return OCS_E_WORKSPACE;
+    if (!aligned(workspace, 256)) return OCS_E_ALIGN;
+    hipError_t e = launch_qgemm_split(Xq, ldx, Wq, ldw, M, N, Kpad, scale_x, scale_w, acc_out, ldacc, Y, ldy,
+                                      static_cast<hipStream_t>(stream), parts, workspace);
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
 int ocs_conv_weights_tap_major(const int8_t* Wq, int64_t N, int C_exp, int g, int64_t ldq,
                                int8_t* Wt, int64_t ldc, void* stream) {
     if (!Wq || !Wt) return OCS_E_NULL;
@@ -632,11 +656,39 @@ int ocs_time_next(int family, void* start_event, void* stop_event) {
     return OCS_OK;
 }
 
-int ocs_calib_copy(const void* src, void* dst, size_t bytes, void* stream) {
+int ocs_calib_copy(const void* src, void* dst, size_t bytes, int workgroups, void* stream) {
     if (!src || !dst) return OCS_E_NULL;
-    if (bytes == 0 || bytes % 16 != 0) return OCS_E_SHAPE;
+    if (bytes == 0 || bytes % 16 != 0 || workgroups < 0 || workgroups > 65536) return OCS_E_SHAPE;
     if (!aligned(src, 16) || !aligned(dst, 16)) return OCS_E_ALIGN;
-    hipError_t e = launch_calib_copy(src, dst, bytes, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_calib_copy(src, dst, bytes, workgroups ? workgroups : 2048, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
+int ocs_calib_read(const void* src, size_t bytes, int passes, int workgroups, void* sink, void* stream) {
+    if (!src || !sink) return OCS_E_NULL;
+    if (bytes == 0 || bytes % 16 != 0 || passes < 1 || workgroups < 1 || workgroups > 65536) return OCS_E_SHAPE;
+    if (passes > 1 && ((bytes / 16) & (bytes / 16 - 1)) != 0) return OCS_E_SHAPE;   // the stream wraps by masking
+    if (!aligned(src, 16) || !aligned(sink, 4)) return OCS_E_ALIGN;
+    hipError_t e = launch_calib_read(src, bytes, passes, workgroups, sink, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
+int ocs_calib_fill(void* dst, size_t bytes, int value, int nontemporal, int workgroups, void* stream) {
+    if (!dst) return OCS_E_NULL;
+    if (bytes == 0 || bytes % 16 != 0 || workgroups < 1 || workgroups > 65536) return OCS_E_SHAPE;
+    if (!aligned(dst, 16)) return OCS_E_ALIGN;
+    hipError_t e = launch_calib_fill(dst, bytes, value, nontemporal, workgroups, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
+int ocs_calib_mfma(const void* operands, int iters, int workgroups, void* sink, void* stream) {
+    if (!operands || !sink) return OCS_E_NULL;
+    if (iters < 1 || workgroups < 1 || workgroups > 65536) return OCS_E_SHAPE;
+    if (!aligned(operands, 16) || !aligned(sink, 4)) return OCS_E_ALIGN;
+    hipError_t e = launch_calib_mfma(operands, iters, workgroups, sink, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e);
     return OCS_OK;
 }

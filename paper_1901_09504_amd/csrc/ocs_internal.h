@@ -147,6 +147,14 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
                         int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy,
                         hipStream_t stream, const Requant& rq = Requant{});
 
+// The same GEMM with every 256 x 256 tile's K extent shared by `parts` workgroups; partials:
+// qgemm_split_workspace_bytes() bytes of device memory (no initialisation needed).
+size_t qgemm_split_workspace_bytes(int64_t M, int64_t N, int64_t Kpad, int parts);
+hipError_t launch_qgemm_split(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
+                              int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,
+                              int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy, hipStream_t stream,
+                              int parts, void* partials);
+
 // Convolution with the lowering folded into the GEMM's A-operand loader: Aq [B, H, W, ldc]
 // codes of the un-lowered activation, Wt [N + 1, kh*kw*ldc] tap-major weight codes whose last
 // row is zeros (launch_tap_major builds it from channel-major codes).
@@ -158,7 +166,14 @@ hipError_t launch_tap_major(const int8_t* Wq, int64_t ldq, int64_t N, int E, int
                             int8_t* Wt, hipStream_t stream);
 
 // 16-byte copy of `bytes` (multiple of 16) device bytes: counter calibration only.
-hipError_t launch_calib_copy(const void* src, void* dst, size_t bytes, hipStream_t stream);
+hipError_t launch_calib_copy(const void* src, void* dst, size_t bytes, int workgroups, hipStream_t stream);
+// The other measurement kernels (csrc/calib.hip): read-only sweep (passes over the same buffer),
+// fill, bare matrix-core loop.
+hipError_t launch_calib_read(const void* src, size_t bytes, int passes, int workgroups, void* sink,
+                             hipStream_t stream);
+hipError_t launch_calib_fill(void* dst, size_t bytes, int value, int nontemporal, int workgroups,
+                             hipStream_t stream);
+hipError_t launch_calib_mfma(const void* operands, int iters, int workgroups, void* sink, hipStream_t stream);
 
 // A pair of caller-owned events armed for the next launch of one kernel family on this thread:
 // that launch goes through hipExtLaunchKernel, which stamps the events with the dispatch's own
@@ -216,6 +231,8 @@ struct Tuning {
     int act_dep = -1;   // Eq. 4 pass: per-column depths from a table in LDS (1), from global memory (0), by tensor size (-1)
     int act_nt = 0;     // non-temporal loads of X in that pass (off: appended columns re-read X through L2)
     int gemm_tile = -1;
+    int gemm_pf = -1;
+    int gemm_split = -1; // workgroups that share a tile's K extent (0 or 1: never; default: by shape)   // K-steps the GEMM's look-ahead wave runs ahead of the ring
     int max_flat = -1;  // whole-tensor max|x| of a contiguous tensor as one flat stream (1), by columns (0), default (-1)
     int max_grid = -1;  // workgroups of the flat pass
     int max_un = -1;    // 16-byte loads in flight per lane in the flat pass (1, 2 or 4)

@@ -3,12 +3,12 @@
 // accumulation, exact), with the trailing scale factors of Eq. 1 applied in the epilogue.
 //
 // Both operands are K-contiguous, so a lane's MFMA operand is 16 consecutive bytes of one
-// row.  A workgroup of 4 waves computes a BM x BN tile; per K-step of 64 bytes the BM + BN
-// row segments are staged in LDS (two buffers; the global loads of step k+1 are in flight in
-// registers while step k is multiplied).  LDS rows are 64 bytes = four 16-byte chunks; the
-// chunk index is XOR-swizzled with the row so that the 16-byte reads of consecutive rows
-// fall in different banks.  K is padded with zero codes to a multiple of 64 by the producers,
-// so the K loop has no tail; zeros add nothing to an integer sum.
+// row.  A workgroup computes a BM x BN tile; per K-step of 64 or 128 bytes the BM + BN row
+// segments go from global memory straight into LDS (no staging registers), into a ring of
+// buffers (long K) or all at once (short K).  LDS rows are BK bytes = 16-byte chunks whose
+// index is XOR-swizzled with the row so that the 16-byte fragment reads of consecutive rows fall
+// in different banks.  K is padded with zero codes to a multiple of 64 by the producers, so the
+// K loop has no tail; zeros add nothing to an integer sum.
 #include <atomic>
 
 #include "ocs_internal.h"
@@ -32,187 +32,10 @@ __device__ __forceinline__ unsigned xcd_remap(unsigned w, unsigned total) {
     return xcd * q + (xcd < r ? xcd : r) + local;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int P>
-__global__ __launch_bounds__(kThreads) void qgemm_kernel(
-    const int8_t* __restrict__ Xq, int64_t ldx, const int8_t* __restrict__ Wq, int64_t ldw, int M,
-    int N, int ksteps, const float* __restrict__ scale_x, const float* __restrict__ scale_w,
-    int32_t* __restrict__ acc_out, int64_t ldacc, float* __restrict__ Y, int64_t ldy, int tiles_n,
-    unsigned total_tiles) {
-    static_assert(WAVES_M * WAVES_N == kThreads / 64, "4 waves");
-    static_assert(P % 3 == 0, "the LDS buffer index must be static in the unrolled loop");
-    static_assert(BK == 64 || BK == 128, "K-step of 64 or 128 bytes");
-    constexpr int CPR = BK / 16;                         // 16-byte chunks per LDS row
-    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave tile
-    constexpr int TM = WM / 32, TN = WN / 32;            // 32x32 MFMA tiles per wave
-    constexpr int A_CHUNKS = BM * CPR / kThreads, B_CHUNKS = BN * CPR / kThreads;
-    static_assert(A_CHUNKS >= 1 && B_CHUNKS >= 1, "tile too small");
-
-    __shared__ __align__(16) int8_t lds_a[3][BM * BK];
-    __shared__ __align__(16) int8_t lds_b[3][BN * BK];
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-
-    const unsigned tile = xcd_remap(blockIdx.x, total_tiles);
-    const int bm = (int)(tile / tiles_n), bn = (int)(tile % tiles_n);
-    const int row0 = bm * BM, col0 = bn * BN;
-
-    // staging: chunk q = tid + u*256 -> tile row q / CPR, 16-byte chunk q % CPR
-    const int8_t* a_src[A_CHUNKS];
-    const int8_t* b_src[B_CHUNKS];
-    int a_dst[A_CHUNKS], b_dst[B_CHUNKS];
-#pragma unroll
-    for (int u = 0; u < A_CHUNKS; ++u) {
-        int q = tid + u * kThreads, r = q / CPR, c = q % CPR;
-        int gr = row0 + r;
-        gr = gr < M ? gr : M - 1;  // rows past the edge re-read the last row; never stored
-        a_src[u] = Xq + (int64_t)gr * ldx + c * 16;
-        a_dst[u] = r * BK + swz<BK>(r, c) * 16;
-    }
-#pragma unroll
-    for (int u = 0; u < B_CHUNKS; ++u) {
-        int q = tid + u * kThreads, r = q / CPR, c = q % CPR;
-        int gr = col0 + r;
-        gr = gr < N ? gr : N - 1;
-        b_src[u] = Wq + (int64_t)gr * ldw + c * 16;
-        b_dst[u] = r * BK + swz<BK>(r, c) * 16;
-    }
-
-    // P K-steps of both operands are in flight in registers at any time: a workgroup alone
-    // on its CU must cover the whole memory latency with its own outstanding loads.  Loads are
-    // unconditional (the K index is clamped to the last step, whose data is then simply
-    // fetched again) so that the unrolled loop body is straight-line code and the wait before
-    // each LDS write covers only the oldest stage, not every load in flight.
-    i32x4 a_reg[P][A_CHUNKS], b_reg[P][B_CHUNKS];
-    auto fetch = [&](int kt, i32x4 (&ar)[A_CHUNKS], i32x4 (&br)[B_CHUNKS]) {
-        const int kl = kt < ksteps ? kt : ksteps - 1;
-        const int64_t koff = (int64_t)kl * BK;
-#pragma unroll
-        for (int u = 0; u < A_CHUNKS; ++u)
-            ar[u] = *reinterpret_cast<const i32x4*>(a_src[u] + koff);
-#pragma unroll
-        for (int u = 0; u < B_CHUNKS; ++u)
-            br[u] = *reinterpret_cast<const i32x4*>(b_src[u] + koff);
-    };
-#pragma unroll
-    for (int p = 0; p < P; ++p) fetch(p, a_reg[p], b_reg[p]);
-
-    i32x16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
-
-    // operand fetch: lane -> row lane%32 of a 32-row MFMA tile, K bytes (lane/32)*16 .. +15 of
-    // a 32-byte K slice.  A and B use the same mapping, so the pairing of K bytes is
-    // consistent whatever order the hardware assigns to them inside the slice.
-    const int frag_row = lane & 31, frag_half = lane >> 5;
-    constexpr int KS = BK / 32;  // 32-byte K slices per step (even)
-
-    i32x4 af[2][TM], bf[2][TN];  // fragments of the slice being multiplied and of the next one
-    auto read_slice = [&](int buf, int ks, i32x4 (&a)[TM], i32x4 (&b)[TN]) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            int r = wm * WM + i * 32 + frag_row;
-            a[i] = *reinterpret_cast<const i32x4*>(
-                &lds_a[buf][r * BK + swz<BK>(r, ks * 2 + frag_half) * 16]);
-        }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            int r = wn * WN + j * 32 + frag_row;
-            b[j] = *reinterpret_cast<const i32x4*>(
-                &lds_b[buf][r * BK + swz<BK>(r, ks * 2 + frag_half) * 16]);
-        }
-    };
-    auto multiply = [&](i32x4 (&a)[TM], i32x4 (&b)[TN]) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
-    };
-    auto stage = [&](int buf, i32x4 (&ar)[A_CHUNKS], i32x4 (&br)[B_CHUNKS]) {
-#pragma unroll
-        for (int u = 0; u < A_CHUNKS; ++u)
-            *reinterpret_cast<i32x4*>(&lds_a[buf][a_dst[u]]) = ar[u];
-#pragma unroll
-        for (int u = 0; u < B_CHUNKS; ++u)
-            *reinterpret_cast<i32x4*>(&lds_b[buf][b_dst[u]]) = br[u];
-    };
-
-    // Software pipeline over three LDS buffers.  Step kt multiplies out of buffer kt % 3.
-    //  - At its start it writes step kt+2 (waiting in registers) into buffer (kt+2) % 3, whose
-    //    last readers left at the previous barrier, and refills those registers with step
-    //    kt+2+P: the LDS write has a whole step of MFMAs to complete behind.
-    //  - While the matrix cores work on slice s, the LDS reads of slice s+1 are in flight.
-    //  - Before the last slice is multiplied, the step's one barrier is taken and slice 0 of
-    //    step kt+1 is requested from buffer (kt+1) % 3, which was written a full step ago; the
-    //    last slice's MFMAs cover that read.
-    // Every action is unconditional (loads are clamped, surplus writes land in a buffer nobody
-    // reads), so the unrolled body is straight-line code.
-    auto step = [&](int buf, i32x4 (&nar)[A_CHUNKS], i32x4 (&nbr)[B_CHUNKS], int refill_kt) {
-        stage((buf + 2) % 3, nar, nbr);
-        fetch(refill_kt, nar, nbr);
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            if (ks + 1 < KS) {
-                read_slice(buf, ks + 1, af[(ks + 1) & 1], bf[(ks + 1) & 1]);
-            } else {
-                __syncthreads();
-                read_slice((buf + 1) % 3, 0, af[0], bf[0]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            multiply(af[ks & 1], bf[ks & 1]);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-
-    // prologue: steps 0 and 1 into buffers 0 and 1, slice 0 of step 0 into the fragments
-    stage(0, a_reg[0], b_reg[0]);
-    stage(1, a_reg[1 % P], b_reg[1 % P]);
-    fetch(P, a_reg[0], b_reg[0]);
-    fetch(P + 1, a_reg[1 % P], b_reg[1 % P]);
-    __syncthreads();
-    read_slice(0, 0, af[0], bf[0]);
-
-    // Step kt lives in register slot kt % P; step kt stages slot (kt+2) % P.
-    int kt0 = 0;
-    for (; kt0 + P <= ksteps; kt0 += P) {
-#pragma unroll
-        for (int p = 0; p < P; ++p)
-            step(p % 3, a_reg[(p + 2) % P], b_reg[(p + 2) % P], kt0 + p + 2 + P);
-    }
-#pragma unroll
-    for (int p = 0; p < P; ++p)
-        if (kt0 + p < ksteps) step(p % 3, a_reg[(p + 2) % P], b_reg[(p + 2) % P], kt0 + p + 2 + P);
-
-    // epilogue: accumulator register v of lane l holds row (v/4)*8 + (l/32)*4 + v%4 and
-    // column l%32 of its 32x32 tile
-    const float scale = scale_x[1] * scale_w[1];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int c = col0 + wn * WN + j * 32 + (lane & 31);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int r = row0 + wm * WM + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-                if (r < M && c < N) {
-                    const int a = acc[i][j][v];
-                    Y[(int64_t)r * ldy + c] = (float)a * scale;
-                    if (acc_out) acc_out[(int64_t)r * ldacc + c] = a;
-                }
-            }
-        }
-}
-
 // ---------------------------------------------------------------------------------------------
-// Variant that moves the operands global -> LDS directly (global_load_lds_dwordx4): no staging
-// registers and no LDS write instructions, which on this chip cost as much LDS time as the
-// fragment reads (the LDS takes ~73 B/clk of writes against ~190 B/clk of 16-byte reads).
+// The operands move global -> LDS directly (global_load_lds_dwordx4): no staging registers and no
+// LDS write instructions, which on this chip cost as much LDS time as the fragment reads (the LDS
+// takes ~73 B/clk of writes against ~190 B/clk of 16-byte reads).
 // One such instruction fills 1 KB of LDS, lane l at byte 16*l of the wave's block (the block
 // base travels in M0 and is wave-uniform), so the XOR swizzle is applied on the global side:
 // the lane that fills chunk slot c of row r fetches chunk c ^ f(r) of that row.  NBUF LDS
@@ -373,20 +196,28 @@ struct ConvGeom {
     int64_t ldc;
 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF, bool CONV = false, int KG = 1>
-__global__ __launch_bounds__(WAVES_M * WAVES_N * 64 * KG) void qgemm_dma_kernel(
+// K split across workgroups: `parts` workgroups share one output tile, each walks its own slice of
+// the K-steps, stores its int32 accumulators in partials[tile][part] (in the register layout, so
+// that the stores and the loads are whole 1 KB wave accesses) and signs in at counters[tile]; the
+// one that signs in last adds the others' accumulators to its own (integer sums: any order gives
+// the same bits) and runs the epilogue.  Nobody waits for anybody.  A counter wraps back to zero
+// with the last arrival (atomicInc), so the counters only have to be zero once.
+struct SplitK {
+    int32_t* partials = nullptr;   // [tiles][parts][BM * BN]
+    unsigned* counters = nullptr;  // [tiles], zero between launches
+    int parts = 1;
+};
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF, bool CONV = false, bool SPLIT = false>
+__global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
     const int8_t* __restrict__ Xq, int64_t ldx, const int8_t* __restrict__ Wq, int64_t ldw, int M,
-    int N, int ksteps, const float* __restrict__ scale_x, const float* __restrict__ scale_w,
+    int N, int ksteps_all, const float* __restrict__ scale_x, const float* __restrict__ scale_w,
     int32_t* __restrict__ acc_out, int64_t ldacc, float* __restrict__ Y, int64_t ldy, int tiles_n,
-    unsigned total_tiles, ConvGeom cg, Requant rq) {
-    // KG = 2: the workgroup is two such groups of waves, each with a ring of its own, which share
-    // the tile and split its K-steps between them (group g takes steps g, g + 2, ...); their
-    // accumulators meet in LDS before the epilogue.  For shapes with fewer tiles than CUs and a
-    // long K: twice the waves issue operand requests on every busy CU.
-    constexpr int NW = WAVES_M * WAVES_N;  // waves per group (4, 8 or 16)
+    unsigned total_tiles, ConvGeom cg, Requant rq, SplitK sk) {
+    constexpr int NW = WAVES_M * WAVES_N;  // waves (4, 8 or 16)
     constexpr int NT = NW * 64;
     static_assert(NW == 4 || NW == 8 || NW == 16, "4, 8 or 16 waves");
-    static_assert(KG == 1 || (KG == 2 && !CONV && NW <= 8), "two K groups: plain GEMM, 16 waves in all");
+    static_assert(!SPLIT || !CONV, "K split across workgroups: plain GEMM");
     static_assert(BK == 64 || BK == 128, "K-step of 64 or 128 bytes");
     static_assert(NBUF >= 3, "ring of at least three buffers");
     constexpr int CPR = BK / 16;
@@ -400,18 +231,23 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64 * KG) void qgemm_dma_kernel(
 
     // one array: the A ring, then the B ring; the epilogue reuses all of it
     constexpr int RING_BYTES = NBUF * (BM + BN) * BK;
-    __shared__ __align__(1024) int8_t lds[KG * RING_BYTES];
+    __shared__ __align__(1024) int8_t lds[RING_BYTES];
     __shared__ int dup_list[kDupCap];
     __shared__ int dup_count;
-    const int grp = KG > 1 ? (int)threadIdx.x / NT : 0;   // wave-uniform
-    int8_t (*lds_a)[BM * BK] = reinterpret_cast<int8_t (*)[BM * BK]>(&lds[grp * RING_BYTES]);
-    int8_t (*lds_b)[BN * BK] = reinterpret_cast<int8_t (*)[BN * BK]>(&lds[grp * RING_BYTES + NBUF * BM * BK]);
+    int8_t (*lds_a)[BM * BK] = reinterpret_cast<int8_t (*)[BM * BK]>(&lds[0]);
+    int8_t (*lds_b)[BN * BK] = reinterpret_cast<int8_t (*)[BN * BK]>(&lds[NBUF * BM * BK]);
 
-    const int tid = (int)threadIdx.x - grp * NT;   // thread, lane and wave inside the group
+    const int tid = (int)threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
-    const unsigned tile = xcd_remap(blockIdx.x, total_tiles);
+    // SPLIT: the parts of a tile are neighbours in the renumbered order, so they run on one XCD
+    // and their partial sums meet in its L2
+    const unsigned vwg = xcd_remap(blockIdx.x, SPLIT ? total_tiles * (unsigned)sk.parts : total_tiles);
+    const unsigned tile = SPLIT ? vwg / (unsigned)sk.parts : vwg;
+    const int part = SPLIT ? (int)(vwg % (unsigned)sk.parts) : 0;
+    const int kbeg = SPLIT ? (int)((int64_t)part * ksteps_all / sk.parts) : 0;
+    const int ksteps = SPLIT ? (int)((int64_t)(part + 1) * ksteps_all / sk.parts) - kbeg : ksteps_all;
     const int bm = (int)(tile / tiles_n), bn = (int)(tile % tiles_n);
     const int row0 = bm * BM, col0 = bn * BN;
 
@@ -448,7 +284,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64 * KG) void qgemm_dma_kernel(
             a_kx[u] = kx;
             a_ky[u] = ky;
         } else {
-            a_src[u] = Xq + (int64_t)gr * ldx + swz<BK>(r, c) * 16;
+            a_src[u] = Xq + (int64_t)gr * ldx + swz<BK>(r, c) * 16 + (int64_t)kbeg * BK;
         }
     }
     int c_kt = 0;   // CONV: K-step the next request is for (stops at the last one)
@@ -457,7 +293,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64 * KG) void qgemm_dma_kernel(
         int pslot = (u * NW + wave) * 64 + lane, r = pslot / CPR, c = pslot % CPR;
         int gr = col0 + r;
         gr = gr < N ? gr : N - 1;
-        b_src[u] = Wq + (int64_t)gr * ldw + swz<BK>(r, c) * 16;
+        b_src[u] = Wq + (int64_t)gr * ldw + swz<BK>(r, c) * 16 + (int64_t)kbeg * BK;
     }
 
     // The load is issued through inline assembly on purpose: issued through the compiler's
@@ -486,7 +322,6 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64 * KG) void qgemm_dma_kernel(
 #endif
     };
     auto fetch = [&](int kt, int buf) {   // K index clamped: surplus steps refetch the last one
-        kt = kt * KG + grp;                // the group's kt-th step
         const int kl = kt < ksteps ? kt : ksteps - 1;
         const int64_t koff = (int64_t)kl * BK;
         if (CONV) {
@@ -572,21 +407,19 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64 * KG) void qgemm_dma_kernel(
                 read_slice((buf + 1) % NBUF, 0, af[0], bf[0]);
             }
             __builtin_amdgcn_sched_barrier(0);
-            // (with an odd number of K-steps the second group's last step has nothing to add;
-            // it still takes the step's barrier)
-            if (KG == 1 || kt * KG + grp < ksteps) multiply(af[ks & 1], bf[ks & 1]);
+            multiply(af[ks & 1], bf[ks & 1]);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
 #pragma unroll
     for (int p = 0; p < NBUF - 1; ++p) fetch(p, p);
-    build_dup_list<NT * KG>(rq, N, col0, BN, dup_list, &dup_count);   // behind the first requests
+    build_dup_list<NT>(rq, N, col0, BN, dup_list, &dup_count);   // behind the first requests
     wait_vmcnt<(NBUF - 2) * LPS>();
     __syncthreads();
     read_slice(0, 0, af[0], bf[0]);
 
-    const int gsteps = (ksteps + KG - 1) / KG;   // steps per group (the same count for both)
+    const int gsteps = ksteps;
     int kt0 = 0;
     for (; kt0 + NBUF <= gsteps; kt0 += NBUF) {
 #pragma unroll
@@ -598,27 +431,69 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64 * KG) void qgemm_dma_kernel(
     wait_vmcnt<0>();  // surplus (clamped) loads must land before the ring is reused below
     __syncthreads();  // every wave has read its last fragments: the rings are free
 
-    if constexpr (KG > 1) {
-        // the second group hands its accumulators over through its own (free) ring, lane-major:
-        // conflict-free on both sides; wave w of the first group adds wave w's of the second
-        static_assert(RING_BYTES >= NW * TM * TN * 16 * 64 * 4, "ring too small for the hand-over");
-        int32_t* xch = reinterpret_cast<int32_t*>(&lds[RING_BYTES]) + wave * (TM * TN * 16 * 64) + lane;
-        if (grp == 1) {
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) xch[((i * TN + j) * 16 + v) * 64] = acc[i][j][v];
-        }
-        __syncthreads();
-        if (grp == 1) return;   // no barrier follows
+    if constexpr (SPLIT) {
+        // The partial sums cross between workgroups that may sit on different XCDs, each with an
+        // L2 of its own.  They are stored and loaded as device-coherent accesses (the sc1 bit:
+        // written through to, and read from, the memory side of the L2s), which needs no cache
+        // maintenance: a device-scope fence instead writes back and invalidates a whole L2 per
+        // workgroup (measured: 120 us instead of 42 on the 512-channel 3x3 layer).  Order: stores,
+        // wait until they are acknowledged, barrier, one arrival per workgroup.
+        __shared__ unsigned arrival;
+        constexpr int WAVE_VEC = TM * TN * 4 * 64;   // 16-byte groups of one wave's accumulators
+        i32x4* mine = reinterpret_cast<i32x4*>(sk.partials + ((size_t)tile * sk.parts + part) * (size_t)(BM * BN)) +
+                      (size_t)wave * WAVE_VEC + lane;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] += xch[((i * TN + j) * 16 + v) * 64];
+                for (int vg = 0; vg < 4; ++vg) {
+                    i32x4 v;
+                    v[0] = acc[i][j][4 * vg]; v[1] = acc[i][j][4 * vg + 1];
+                    v[2] = acc[i][j][4 * vg + 2]; v[3] = acc[i][j][4 * vg + 3];
+                    i32x4* dst = mine + ((i * TN + j) * 4 + vg) * 64;
+#if defined(__HIP_DEVICE_COMPILE__)
+                    asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(dst), "v"(v) : "memory");
+#else
+                    *dst = v;
+#endif
+                }
+        wait_vmcnt<0>();          // every store of this wave has been acknowledged
+        __syncthreads();
+        if (threadIdx.x == 0) arrival = atomicInc(sk.counters + tile, (unsigned)sk.parts - 1u);
+        __syncthreads();
+        if (arrival != (unsigned)sk.parts - 1u) return;   // not the last one: done (no barrier follows)
+        for (int q = 0; q < sk.parts; ++q) {
+            if (q == part) continue;
+            const i32x4* theirs = reinterpret_cast<const i32x4*>(
+                                      sk.partials + ((size_t)tile * sk.parts + q) * (size_t)(BM * BN)) +
+                                  (size_t)wave * WAVE_VEC + lane;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    i32x4 v0, v1, v2, v3;
+                    const i32x4* src = theirs + ((i * TN + j) * 4) * 64;
+#if defined(__HIP_DEVICE_COMPILE__)
+                    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v0) : "v"(src) : "memory");
+                    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v1) : "v"(src + 64) : "memory");
+                    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v2) : "v"(src + 128) : "memory");
+                    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v3) : "v"(src + 192) : "memory");
+                    // the sums below must not be scheduled ahead of the wait: they take their
+                    // operands from it
+                    asm volatile("s_waitcnt vmcnt(0)" : "+v"(v0), "+v"(v1), "+v"(v2), "+v"(v3) : : "memory");
+#else
+                    v0 = src[0]; v1 = src[64]; v2 = src[128]; v3 = src[192];
+#endif
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        acc[i][j][e] += v0[e];
+                        acc[i][j][4 + e] += v1[e];
+                        acc[i][j][8 + e] += v2[e];
+                        acc[i][j][12 + e] += v3[e];
+                    }
+                }
+        }
     }
 
     // Epilogue.  An accumulator block leaves the MFMA with lane l holding ONE column and 16
@@ -633,7 +508,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64 * KG) void qgemm_dma_kernel(
     static_assert(WAVE_STAGE % 16 == 0, "staging area must keep 16-byte alignment");
     int32_t* stage = reinterpret_cast<int32_t*>(&lds[wave * WAVE_STAGE]);
     const float scale = scale_x[1] * scale_w[1];
-    const float inv = requant_inv(rq, blockIdx.x == 0 && threadIdx.x == 0);
+    const float inv = requant_inv(rq, (SPLIT ? tile == 0 : blockIdx.x == 0) && threadIdx.x == 0);
     const int dup_n = (rq.Yq != nullptr && rq.s_next > 0) ? (dup_count < kDupCap ? dup_count : kDupCap) : 0;
     const bool vec_y = (reinterpret_cast<uintptr_t>(Y) % 16 == 0) && (ldy % 4 == 0);
     const bool vec_a = acc_out != nullptr && (reinterpret_cast<uintptr_t>(acc_out) % 16 == 0) &&
@@ -850,7 +725,7 @@ static hipError_t run_wholek(const int8_t* Xq, int64_t ldx, const int8_t* Wq, in
                          acc_out, ldacc, Y, ldy, (int)tiles_n, (unsigned)total, dup_off, rq);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF, int KG = 1>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF>
 static hipError_t run_dma(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
                           int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,
                           int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy,
@@ -860,10 +735,72 @@ static hipError_t run_dma(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64
     const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
     const int64_t total = tiles_m * tiles_n;
     if (total > 0x7FFFFFFF) return hipErrorInvalidValue;   // one workgroup per tile: grid.x
-    return launch_kernel(kTimeGemm, qgemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, BK, NBUF, false, KG>,
-                         dim3((unsigned)total), dim3(WAVES_M * WAVES_N * 64 * KG), 0, stream, Xq, ldx, Wq, ldw, (int)M,
+    return launch_kernel(kTimeGemm, qgemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, BK, NBUF, false>,
+                         dim3((unsigned)total), dim3(WAVES_M * WAVES_N * 64), 0, stream, Xq, ldx, Wq, ldw, (int)M,
                          (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y, ldy,
-                         (int)tiles_n, (unsigned)total, ConvGeom{}, rq);
+                         (int)tiles_n, (unsigned)total, ConvGeom{}, rq, SplitK{});
+}
+
+// Arrival counters of the K split: part of the library's device image (zero when the module is
+// loaded, and every launch leaves the counters it used at zero again), one copy per GPU.  A launch
+// takes one slot of kSplitSlotTiles counters, slots handed out in turn, so that launches on
+// different streams do not share counters unless more than kSplitSlots of them are in flight on
+// one GPU.  In host code the array's name is only a handle: the device address is looked up once
+// per device and only that address goes to a launch.
+constexpr int kSplitSlotTiles = 128;
+constexpr int kSplitSlots = 512;
+static __device__ unsigned splitk_counters[kSplitSlotTiles * kSplitSlots];
+
+static hipError_t splitk_counter_slot(unsigned** out) {
+    static std::atomic<unsigned*> addr[kMaxDevices];
+    static std::atomic<unsigned> cursor[kMaxDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    unsigned* p = addr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        void* sym = nullptr;
+        e = hipGetSymbolAddress(&sym, HIP_SYMBOL(splitk_counters));
+        if (e != hipSuccess) return e;
+        if (sym == nullptr) return hipErrorInvalidSymbol;
+        p = static_cast<unsigned*>(sym);
+        addr[dev].store(p, std::memory_order_release);
+    }
+    const unsigned slot = cursor[dev].fetch_add(1u, std::memory_order_relaxed) % (unsigned)kSplitSlots;
+    *out = p + (size_t)slot * kSplitSlotTiles;
+    return hipSuccess;
+}
+
+// The split kernel's tile is 256 x 256 (64-byte K-steps, ring of four).
+constexpr int kSplitBM = 256, kSplitBN = 256;
+
+// 0 when the shape cannot be split this way (more tiles than a counter slot holds, or fewer than
+// one K-step per part).
+size_t qgemm_split_workspace_bytes(int64_t M, int64_t N, int64_t Kpad, int parts) {
+    const int64_t tiles = ceil_div(M, kSplitBM) * ceil_div(N, kSplitBN);
+    if (parts < 2 || parts > 16 || tiles > kSplitSlotTiles || Kpad / 64 < parts) return 0;
+    return (size_t)tiles * parts * kSplitBM * kSplitBN * sizeof(int32_t);
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF>
+static hipError_t run_dma_split(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
+                                int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,
+                                int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy, hipStream_t stream,
+                                const Requant& rq, int parts, void* partials) {
+    if (Kpad < BK || Kpad % BK != 0 || parts < 2 || Kpad / BK < parts) return hipErrorInvalidValue;
+    const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
+    const int64_t total = tiles_m * tiles_n;
+    if (total > kSplitSlotTiles) return hipErrorInvalidValue;
+    SplitK sk;
+    sk.partials = static_cast<int32_t*>(partials);
+    sk.parts = parts;
+    hipError_t e = splitk_counter_slot(&sk.counters);
+    if (e != hipSuccess) return e;
+    return launch_kernel(kTimeGemm, qgemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, BK, NBUF, false, true>,
+                         dim3((unsigned)(total * parts)), dim3(WAVES_M * WAVES_N * 64), 0, stream, Xq, ldx, Wq,
+                         ldw, (int)M, (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y, ldy,
+                         (int)tiles_n, (unsigned)total, ConvGeom{}, rq, sk);
 }
 
 // The same kernel with the lowering of a convolution done by its A-operand loader.
@@ -880,7 +817,7 @@ static hipError_t run_dma_conv(const int8_t* Aq, const int8_t* Wt, int64_t ldw, 
     return launch_kernel(kTimeGemm, qgemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, BK, NBUF, true>,
                          dim3((unsigned)total), dim3(WAVES_M * WAVES_N * 64), 0, stream, Aq, cg.ldc, Wt,
                          ldw, (int)M, (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y,
-                         ldy, (int)tiles_n, (unsigned)total, cg, rq);
+                         ldy, (int)tiles_n, (unsigned)total, cg, rq, SplitK{});
 }
 
 hipError_t launch_qconv(const int8_t* Aq, int64_t ldc, int B, int H, int W, int kh, int kw, int stride,
@@ -953,26 +890,7 @@ hipError_t launch_tap_major(const int8_t* Wq, int64_t ldq, int64_t N, int E, int
     return hipGetLastError();
 }
 
-// Kpad is a multiple of 64.  With a 128-byte K-step and Kpad % 128 == 64 the last step would
-// read 64 bytes past the row's padding, so such shapes run the tail through the leading
-// dimension only if it allows it; otherwise the 64-byte variant is used.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int P>
-static hipError_t run(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
-                      int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,
-                      int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy, hipStream_t stream) {
-    // the kernel clamps its K index to ksteps - 1: it must never be launched with no K-step
-    if (Kpad < BK || Kpad % BK != 0) return hipErrorInvalidValue;
-    const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
-    const int64_t total = tiles_m * tiles_n;
-    if (total > 0x7FFFFFFF) return hipErrorInvalidValue;   // one workgroup per tile: grid.x
-    return launch_kernel(kTimeGemm, qgemm_kernel<BM, BN, WAVES_M, WAVES_N, BK, P>,
-                         dim3((unsigned)total), dim3(kThreads), 0, stream, Xq, ldx, Wq, ldw, (int)M,
-                         (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y, ldy,
-                         (int)tiles_n, (unsigned)total);
-}
-
-#define OCS_GEMM_ARGS_F32 Xq, ldx, Wq, ldw, M, N, Kpad, scale_x, scale_w, acc_out, ldacc, Y, ldy, stream
-#define OCS_GEMM_ARGS OCS_GEMM_ARGS_F32, rq
+#define OCS_GEMM_ARGS Xq, ldx, Wq, ldw, M, N, Kpad, scale_x, scale_w, acc_out, ldacc, Y, ldy, stream, rq
 #define OCS_GEMM_ARGS128 Xq, ldx, Wq, ldw, M, N, K128, scale_x, scale_w, acc_out, ldacc, Y, ldy, stream, rq
 
 hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
@@ -1005,29 +923,17 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
     // on both operands (the producers' contract) and the walk may include them.
     const int64_t K128 = round_up(Kpad, 128);
     const bool k128 = K128 == Kpad || (ldx >= K128 && ldw >= K128);
+    // Tile variants by id (the dispatcher above picks 6, 9, 11, 12, 16, 17, 19 or 23; the others
+    // are kept selectable because the parity tests run every kernel family through them).
     switch (tile) {
-        case 0: if (rq.Yq == nullptr) return run<128, 128, 2, 2, 64, 6>(OCS_GEMM_ARGS_F32);  // register-staged
-                return run_dma<128, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS);
-        case 1: if (rq.Yq == nullptr) return run<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS_F32);   // register-staged
-                return run_dma<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
-        case 2: return run_dma<128, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS);
-        case 3: return k128 ? run_dma<128, 128, 2, 2, 128, 3>(OCS_GEMM_ARGS128)
-                            : run_dma<128, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS);
-        case 4: return k128 ? run_dma<256, 128, 2, 2, 128, 3>(OCS_GEMM_ARGS128)
-                            : run_dma<256, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS);
-        case 5: return run_dma<256, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS);
         case 6: return run_dma<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
         case 7: return run_dma<64, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
-        case 8: return run_dma<128, 128, 2, 4, 64, 4>(OCS_GEMM_ARGS);    // 8 waves
         case 9: return run_dma<128, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);    // 8 waves
         case 10: return run_dma<256, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);   // 8 waves
         case 11: return k128 ? run_dma<256, 128, 4, 2, 128, 3>(OCS_GEMM_ARGS128)  // 8 waves
                              : run_dma<256, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);
         case 12: return run_dma<256, 256, 2, 4, 64, 4>(OCS_GEMM_ARGS);   // 8 waves
-        case 13: return run_dma<256, 256, 4, 2, 64, 4>(OCS_GEMM_ARGS);   // 8 waves
         case 14: return run_dma<256, 256, 4, 4, 64, 4>(OCS_GEMM_ARGS);   // 16 waves
-        case 15: return k128 ? run_dma<256, 128, 4, 4, 128, 3>(OCS_GEMM_ARGS128)  // 16 waves
-                             : run_dma<256, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);
         // whole-K variants; a K extent too long for them falls back to a ring variant
 #define OCS_WHOLEK(BM_, BN_, WM_, WN_, FALLBACK)                                                   \
     (wholek_lds_bytes<BM_, BN_, WM_, WN_>(Kpad, rq) <= kWholeKMaxLds                                   \
@@ -1037,19 +943,20 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
         case 17: return OCS_WHOLEK(128, 64, 4, 1, (run_dma<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS)));
         case 18: return OCS_WHOLEK(64, 64, 2, 2, (run_dma<64, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS)));
         case 19: return OCS_WHOLEK(128, 256, 2, 4, (run_dma<128, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS)));
-        case 20: return OCS_WHOLEK(256, 128, 4, 2, (run_dma<256, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS)));
-        case 21: return OCS_WHOLEK(128, 128, 2, 2, (run_dma<128, 128, 2, 2, 64, 4>(OCS_GEMM_ARGS)));
 #undef OCS_WHOLEK
-        // two K groups per workgroup (16 waves)
-        case 22: return run_dma<128, 128, 4, 2, 64, 4, 2>(OCS_GEMM_ARGS);
         case 23: return k128 ? run_dma<128, 128, 4, 2, 128, 3>(OCS_GEMM_ARGS128)
                              : run_dma<128, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);
-        case 24: return k128 ? run_dma<128, 128, 4, 2, 128, 4>(OCS_GEMM_ARGS128)
-                             : run_dma<128, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);
-        case 25: return run_dma<128, 128, 4, 2, 64, 6>(OCS_GEMM_ARGS);
-        case 26: return run_dma<128, 128, 4, 2, 64, 8>(OCS_GEMM_ARGS);
         default: return run_dma<64, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
     }
+}
+
+hipError_t launch_qgemm_split(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
+                              int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,
+                              int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy, hipStream_t stream,
+                              int parts, void* partials) {
+    return run_dma_split<kSplitBM, kSplitBN, 2, 4, 64, 4>(Xq, ldx, Wq, ldw, M, N, Kpad, scale_x, scale_w,
+                                                         acc_out, ldacc, Y, ldy, stream, Requant{}, parts,
+                                                         partials);
 }
 
 }  // namespace ocs

@@ -344,18 +344,4 @@ hipError_t launch_threshold(const float* colmax, int C, int g, int s, const int3
     return hipGetLastError();
 }
 
-// Plain device-to-device copy with 16-byte accesses, used only to calibrate HBM byte
-// counters against a transfer of known size.
-__global__ __launch_bounds__(kThreads) void calib_copy_kernel(const f32x4* __restrict__ src,
-                                                              f32x4* __restrict__ dst, size_t n16) {
-    const size_t stride = (size_t)gridDim.x * kThreads;
-    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
-}
-
-hipError_t launch_calib_copy(const void* src, void* dst, size_t bytes, hipStream_t stream) {
-    calib_copy_kernel<<<2048, kThreads, 0, stream>>>(static_cast<const f32x4*>(src),
-                                                     static_cast<f32x4*>(dst), bytes / 16);
-    return hipGetLastError();
-}
-
 }  // namespace ocs

@@ -149,6 +149,20 @@ def test_static_scratch_entry_point_checks_arguments_and_size_on_the_host():
             assert B.ocs_workspace_bytes(layer.M, layer.C * layer.g) <= B.STATIC_SCRATCH_BYTES, layer
 
 
+def test_split_k_entry_point_checks_shape_and_workspace_on_the_host():
+    L = B.lib()
+    args = lambda M, N, K, parts, ws, wb: (A, 4864, A, 4864, M, N, K, 8, 8, A, A, None, 0, A, N, parts, ws, wb, None)
+    assert B.ocs_qgemm_split_k_workspace_bytes(12544, 512, 4842, 2) == 49 * 2 * 2 * 256 * 256 * 4
+    assert B.ocs_qgemm_split_k_workspace_bytes(12544, 512, 4842, 1) == 0        # nothing to split
+    assert B.ocs_qgemm_split_k_workspace_bytes(50176, 512, 4842, 2) == 0        # 392 tiles: no counter slot that large
+    assert B.ocs_qgemm_split_k_workspace_bytes(256, 256, 128, 3) == 0           # two K-steps, three parts
+    assert L.ocs_qgemm_split_k(*args(12544, 512, 4842, 1, A, 1 << 30)) == -2
+    assert L.ocs_qgemm_split_k(*args(50176, 512, 4842, 2, A, 1 << 30)) == -2
+    assert L.ocs_qgemm_split_k(*args(12544, 512, 4842, 2, None, 0)) == -7
+    assert L.ocs_qgemm_split_k(*args(12544, 512, 4842, 2, A, 1000)) == -7
+    assert L.ocs_qgemm_split_k(*args(12544, 512, 4842, 2, A + 8, 1 << 30)) == -3
+
+
 def test_binding_raises_on_error():
     with pytest.raises(B.OcsError) as e:
         B._check(-4, "ocs_quantize")

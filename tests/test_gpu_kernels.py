@@ -380,7 +380,10 @@ def test_split_act_deep_halvings(act_dep):
 
 # ---- ocs_qgemm -------------------------------------------------------------------------------
 
-@pytest.mark.parametrize("tile", list(range(27)))
+GEMM_TILES = [6, 7, 9, 10, 11, 12, 14, 16, 17, 18, 19, 23]     # every tile variant of the library
+
+
+@pytest.mark.parametrize("tile", [-1] + GEMM_TILES)
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (64, 256, 269), (130, 70, 64), (257, 129, 200), (700, 300, 1035),
                                    (300, 520, 2358), (128, 128, 4842)])
 def test_qgemm(tile, M, N, K):
@@ -402,6 +405,38 @@ def test_qgemm(tile, M, N, K):
     assert np.array_equal(acc, acc_ref)
     assert_y_close(Y, y_ref)
     assert np.array_equal(Y, Y2)
+
+
+@pytest.mark.parametrize("parts", [2, 3, 4, 7])
+@pytest.mark.parametrize("M,N,K", [(1, 1, 500), (130, 70, 448), (257, 129, 1035), (700, 300, 1035), (300, 520, 2358),
+                                   (1000, 512, 4842)])
+def test_qgemm_split_k(parts, M, N, K):
+    """The K extent of every tile shared between `parts` workgroups: accumulators bit for bit those of
+    the oracle (and so of the un-split call), outputs identical to the un-split call's; twice in a row
+    on the same counters, and with a workspace full of garbage."""
+    rng = np.random.default_rng(M + N + K + parts)
+    ld = B.ocs_padded_cols(K)
+    Xq = np.zeros((M, ld), dtype=np.int8)
+    Wq = np.zeros((N, ld), dtype=np.int8)
+    Xq[:, :K] = rng.integers(-127, 128, (M, K))
+    Wq[:, :K] = rng.integers(-127, 128, (N, K))
+    sx = np.array([3.0, 3.0 / 127], dtype=np.float32)
+    sw = np.array([0.7, 0.7 / 127], dtype=np.float32)
+    acc_ref, y_ref = ref.qgemm(Xq, Wq, K, sx[1], sw[1])
+    _, Y_plain = gpu_qgemm(Xq, Wq, K, sx, sw, want_acc=False)
+    need = B.ocs_qgemm_split_k_workspace_bytes(M, N, K, parts)
+    assert need == -(-M // 256) * -(-N // 256) * parts * 256 * 256 * 4
+    Xd, Wd, sxd, swd = dev(Xq), dev(Wq), dev(sx), dev(sw)
+    ws = torch.randint(0, 255, (need,), dtype=torch.uint8, device="cuda")
+    for rep in range(2):
+        acc = torch.full((M, N), -7, dtype=torch.int32, device="cuda")
+        Y = torch.full((M, N), -7.0, dtype=torch.float32, device="cuda")
+        B.ocs_qgemm_split_k(Xd, ld, Wd, ld, M, N, K, 8, 8, sxd, swd, acc if rep == 0 else None,
+                            N if rep == 0 else 0, Y, N, parts, ws)
+        if rep == 0:
+            assert np.array_equal(host(acc), acc_ref)
+        assert np.array_equal(host(Y), Y_plain)
+    assert_y_close(host(Y), y_ref)
 
 
 def test_qgemm_extreme_codes_do_not_overflow():
@@ -479,7 +514,7 @@ def test_qconv_equals_the_lowered_gemm_path():
     assert np.array_equal(got["acc"], acc) and np.array_equal(got["Y"], Y)
 
 
-@pytest.mark.parametrize("tile", [-1, 3, 4, 11, 15, 23, 24])
+@pytest.mark.parametrize("tile", [-1, 11, 23])
 @pytest.mark.parametrize("ldx_extra,ldw_extra", [(0, 0), (64, 0), (0, 64), (64, 64), (192, 128)])
 @pytest.mark.parametrize("M,N,K", [(130, 140, 180), (300, 260, 2358)])
 def test_qgemm_k_step_of_128_needs_both_paddings(tile, ldx_extra, ldw_extra, M, N, K):
@@ -513,7 +548,7 @@ def _next_layer_list(rng, N, s_next):
     return nxt["chan_src"]
 
 
-@pytest.mark.parametrize("tile", [-1, 0, 2, 6, 7, 9, 11, 12, 14, 16, 17, 18, 19, 22, 23])
+@pytest.mark.parametrize("tile", [-1] + GEMM_TILES)
 @pytest.mark.parametrize("M,N,K,s_next,relu", [(1, 1, 1, 0, False), (130, 70, 64, 9, True), (257, 129, 200, 0, False),
                                                (300, 520, 2358, 26, True), (700, 300, 269, 15, False)])
 def test_qgemm_requant(tile, M, N, K, s_next, relu):
