@@ -352,7 +352,7 @@ int ocs_qconv(const int8_t *Aq, int64_t ldc, int B, int H, int W, int C_exp, int
  *   device int32 [N + next_splits] as the next layer's ocs_split_weights wrote it; its first N
  *   entries are the identity; NULL allowed when next_splits == 0).
  *   Yq [M, ldyq] int8, ldyq a multiple of OCS_CALIGN and >= N + next_splits.  Columns
- *   N + next_splits .. ldyq-1 are NOT written: zero them once when the buffer is allocated.
+ *   N + next_splits .. ldyq-1 are written as zero codes, like every producer's pad columns.
  *   next_scale_out device float[2] = {T, T / qmax} (may be NULL; must not be next_threshold).
  *   acc_out optional int32 [M, ldacc] as in ocs_qgemm.  Other arguments as in ocs_qgemm / ocs_qconv.
  */

@@ -220,7 +220,7 @@ int ocs_split_weights(const float* W, int64_t N, int C, int g, int64_t ldw, int 
     if (Wq) {
         e = launch_expand_quantize(W, ldw, N, C, g, num_splits, chan_src,
                                    halve ? chan_depth : nullptr, scale_w_out, qmax, Wq, ldq,
-                                   nullptr, st);
+                                   nullptr, st, nullptr, 0, 1.0f, /*stepwise=*/halve != 0);
         if (e != hipSuccess) return hip_fail(e);
     }
     return OCS_OK;

@@ -84,12 +84,15 @@ hipError_t launch_select_expand_quantize(const float* W, int64_t ldw, int64_t N,
 // thr: device float threshold; or, with partials != NULL, the threshold is
 // clip_ratio * max(partials[0 .. n_partials)), which every workgroup folds for itself.
 // scale_out (may be NULL): receives {T, T/qmax}.
+// stepwise: the 2^-depth of a channel is applied as `depth` successive halvings (the weights of
+// Eq. 3, halved once per split) instead of as one multiply (Eq. 4 on activations with the depth
+// given); the two differ only where a result leaves the normal range.
 hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C, int g, int s,
                                   const int32_t* chan_src, const int32_t* chan_depth,
                                   const float* thr, float qmax, int8_t* Xq, int64_t ldq,
                                   float* scale_out, hipStream_t stream,
                                   const float* partials = nullptr, int n_partials = 0,
-                                  float clip_ratio = 1.0f);
+                                  float clip_ratio = 1.0f, bool stepwise = false);
 
 // Per-workgroup maxima of |T| (stage 1 of the scalar reduction only): partial[0 .. *entries).
 hipError_t launch_absmax_partials(const float* T, int64_t rows, int64_t cols, int64_t ld,
@@ -125,7 +128,7 @@ hipError_t launch_mse_clip(const float* x, int64_t ldx, int64_t rows, int64_t co
 // the copies of the channels the next layer splits: the activation side of its Eq. 3).
 // Yq == NULL: plain fp32 output.
 struct Requant {
-    int8_t* Yq = nullptr;            // [M, ldyq]; columns N + s_next .. ldyq-1 are not written
+    int8_t* Yq = nullptr;            // [M, ldyq]; columns N + s_next .. ldyq-1 are written as zeros
     int64_t ldyq = 0;
     const float* thr = nullptr;      // device float: the next layer's threshold
     float qmax = 0.0f;

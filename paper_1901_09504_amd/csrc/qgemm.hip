@@ -90,7 +90,7 @@ __device__ __forceinline__ void emit_staged_rows(const int32_t* stage, int lane,
                                                  float* __restrict__ Y, int64_t ldy,
                                                  int32_t* __restrict__ acc_out, int64_t ldacc,
                                                  bool vec_y, bool vec_a, const Requant& rq, float inv,
-                                                 const int* dup_list, int dup_n) {
+                                                 const int* dup_list, int dup_n, bool pad_writer) {
     constexpr int LPR = WN / 4;            // lanes per row (8, 16 or 32)
     constexpr int SLOTS = ROWS * LPR;      // 16-byte reads of the block
     static_assert(SLOTS % 64 == 0, "whole waves of slots");
@@ -169,6 +169,13 @@ __device__ __forceinline__ void emit_staged_rows(const int32_t* stage, int lane,
                 rq.Yq[(int64_t)r * rq.ldyq + N + (e >> 8)] =
                     (int8_t)out_code(stage[lane * WN + local], scale, rq.relu, inv, rq.qmax);
         }
+    }
+    // the pad columns of the code tensor (past the last copy) are zero codes: written by one wave
+    // of the last tile column, one lane per staged row
+    if (pad_writer && lane < ROWS) {
+        const int r = rbase + lane;
+        if (r < M)
+            for (int64_t c = (int64_t)N + rq.s_next; c < rq.ldyq; ++c) rq.Yq[(int64_t)r * rq.ldyq + c] = 0;
     }
 }
 
@@ -524,7 +531,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         emit_staged_rows<32, WN>(stage, lane, row0 + wm * WM + i * 32, col0 + wn * WN, wn * WN, M, N,
-                                 scale, Y, ldy, acc_out, ldacc, vec_y, vec_a, rq, inv, dup_list, dup_n);
+                                 scale, Y, ldy, acc_out, ldacc, vec_y, vec_a, rq, inv, dup_list, dup_n,
+                                 rq.Yq != nullptr && bn == tiles_n - 1 && wn == 0);
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         __builtin_amdgcn_wave_barrier();   // the reads are issued before the next block's writes
     }
@@ -665,7 +673,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_wholek_kernel(
             __builtin_amdgcn_wave_barrier();
             emit_staged_rows<8, WN>(stage, lane, row0 + wm * WM + i * 32 + q * 8, col0 + wn * WN, wn * WN,
                                     M, N, scale, Y, ldy, acc_out, ldacc, vec_y, vec_a, rq, inv, dup_list,
-                                    dup_n);
+                                    dup_n, rq.Yq != nullptr && bn == tiles_n - 1 && wn == 0);
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             __builtin_amdgcn_wave_barrier();
         }

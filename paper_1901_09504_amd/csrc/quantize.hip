@@ -37,6 +37,26 @@ __device__ __forceinline__ float inv_step_of(float T, float qmax) {
     return __builtin_fminf(__fdiv_rn(qmax, T), 3.402823466e+38f);
 }
 
+// v halved d times, one halving after the other, as the splits of Sec. 3.4 are performed on the
+// weights (Eq. 3 per split).  While the result stays a normal number that is one exact multiply
+// by 2^-d; a result below the normal range rounds at every further halving, which a single
+// multiply would not reproduce.
+__device__ __forceinline__ float halved(float v, int d) {
+    const int e = (int)((__float_as_uint(v) >> 23) & 0xFFu);      // biased exponent
+    if (d <= 126 && e > d) return v * ldexpf(1.0f, -d);           // exponent e - d >= 1: exact
+    if (d <= 0) return v;
+    int h = e - 1;                                                // halvings that keep it normal
+    h = h < 0 ? 0 : (h > d ? d : h);
+    float r = v;
+    if (h > 0) {
+        const int h1 = h < 126 ? h : 126;
+        r = r * ldexpf(1.0f, -h1);
+        if (h > h1) r = r * ldexpf(1.0f, -(h - h1));
+    }
+    for (int i = h; i < d && r != 0.0f; ++i) r = r * 0.5f;       // at most ~25 roundings before zero
+    return r;
+}
+
 // The threshold of the pass: the given device float, or, for a per-batch grid, clip_ratio times
 // the largest of the per-workgroup maxima the preceding pass left behind (a few thousand
 // floats, folded by every workgroup for itself: cheaper than a separate launch that does only
@@ -104,7 +124,9 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
     const int32_t* __restrict__ chan_src, const int32_t* __restrict__ chan_depth,
     const float* thr, float qmax, int8_t* __restrict__ Xq, int D, int main_units,
     unsigned magic, float* scale_out, const float* __restrict__ partials, int n_partials,
-    float clip_ratio, int dep_table) {
+    float clip_ratio, int dep_table, int stepwise) {
+    // stepwise (weights, Eq. 3 applied split by split): 2^-depth as `halved` applies it; otherwise
+    // (activations, Eq. 4 with the depth given) one multiply by 2^-depth.  dep_table is then 0.
     __shared__ float thr_red[kThreads / 64];
     // Source column (or -1 for padding) and halving depth of every column past the vector
     // region.  They do not depend on the row, so each workgroup resolves them once; a lane that
@@ -181,7 +203,7 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
                 int j = (4 * d) / g, t = 4 * d - j * g;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    v[e] = v[e] * ldexpf(1.0f, -chan_depth[j]);
+                    v[e] = stepwise ? halved(v[e], chan_depth[j]) : v[e] * ldexpf(1.0f, -chan_depth[j]);
                     if (++t == g) { t = 0; ++j; }
                 }
             }
@@ -221,7 +243,7 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
             }
             if (HALVE) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = v[e] * ldexpf(1.0f, -dep[e]);
+                for (int e = 0; e < 4; ++e) v[e] = stepwise ? halved(v[e], dep[e]) : v[e] * ldexpf(1.0f, -dep[e]);
             }
             q = pack4(code_bits(v[0], inv, qmax), code_bits(v[1], inv, qmax),
                       code_bits(v[2], inv, qmax), code_bits(v[3], inv, qmax));
@@ -396,7 +418,7 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
                                   const int32_t* chan_src, const int32_t* chan_depth,
                                   const float* thr, float qmax, int8_t* Xq, int64_t ldq,
                                   float* scale_out, hipStream_t stream, const float* partials,
-                                  int n_partials, float clip_ratio) {
+                                  int n_partials, float clip_ratio, bool stepwise) {
     const int64_t K = (int64_t)C * g;
     const bool vec_ok = true;   // 16-byte loads need only the float's own alignment
     const int main_units = (int)(K / 4);
@@ -408,7 +430,7 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
     // lane has enough items for the table's set-up to pay (weights, with one or two items per lane,
     // were 0.6-2.3 us slower with it; cfg 2's activations, with 14, are 5 us faster)
     const bool dep_pays = tuning().act_dep < 0 ? M * (ldq / 4) >= (int64_t)8 * 2048 * kThreads : tuning().act_dep != 0;
-    const int dep_table = halve && K <= kDepthTableMax && dep_pays ? 1 : 0;
+    const int dep_table = halve && !stepwise && K <= kDepthTableMax && dep_pays ? 1 : 0;
     const unsigned dep_lds = dep_table ? (unsigned)round_up(K, 16) : 0;
 
     int64_t grid = 256 * 8;  // 8 workgroups of 4 waves on each of the 256 CUs
@@ -420,7 +442,7 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
     // appended columns or padding (rows of 64 to 128 values); for wider rows the two are level.
     const int map = tuning().act_map;
     const bool by_input = map < 0 ? 4 * TD >= D : map != 0;
-    if (by_input && vec_ok && Q >= 1 && TD <= Q && 4 * TD <= kTailTable) {
+    if (by_input && !stepwise && vec_ok && Q >= 1 && TD <= Q && 4 * TD <= kTailTable) {
         const int64_t total_in = M * Q;
         int64_t gin = 256 * 8;
         if (tuning().act_grid > 0) gin = tuning().act_grid;
@@ -447,7 +469,8 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
 #define OCS_LAUNCH_EQ(H, N_, U_, I_)                                                              \
     err = launch_kernel(kTimeSplitQuantize, expand_quantize_kernel<H, N_, U_, I_>, dim3((unsigned)grid), \
                   dim3(kThreads), dep_lds, stream, X, ldx, M, C, g, s, chan_src, chan_depth, thr,  \
-                  qmax, Xq, D, main_units, magic, scale_out, partials, n_partials, clip_ratio, dep_table)
+                  qmax, Xq, D, main_units, magic, scale_out, partials, n_partials, clip_ratio, dep_table, \
+                  stepwise ? 1 : 0)
 #define OCS_LAUNCH_U(H, N_, I_)                                                                   \
     do {                                                                                          \
         if (un == 4) OCS_LAUNCH_EQ(H, N_, 4, I_);                                                 \
@@ -549,7 +572,7 @@ __global__ __launch_bounds__(kThreads) void select_expand_quantize_kernel(
         if (d < main_units) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                v[e] = cur[e] * ldexpf(1.0f, -(int)dep[j]);
+                v[e] = halved(cur[e], (int)dep[j]);
                 if (++t == g) { t = 0; ++j; }
             }
         } else {
@@ -568,7 +591,7 @@ __global__ __launch_bounds__(kThreads) void select_expand_quantize_kernel(
 #pragma unroll
             for (int e = 0; e < 4; ++e) x[e] = wrow[col[e] < 0 ? 0 : col[e]];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = col[e] >= 0 ? x[e] * ldexpf(1.0f, -dp[e]) : 0.0f;
+            for (int e = 0; e < 4; ++e) v[e] = col[e] >= 0 ? halved(x[e], dp[e]) : 0.0f;
         }
         out[o] = pack4(code_bits(v[0], inv, qmax), code_bits(v[1], inv, qmax),
                        code_bits(v[2], inv, qmax), code_bits(v[3], inv, qmax));
@@ -630,7 +653,7 @@ __global__ __launch_bounds__(kThreads) void expand_f32_kernel(
         int src = chan_src[j];
         src = src < 0 ? 0 : (src >= C ? C - 1 : src);
         float v = trow[(int64_t)src * g + t];
-        if (halve) v = v * ldexpf(1.0f, -chan_depth[j]);
+        if (halve) v = halved(v, chan_depth[j]);
         orow[k] = v;
     }
 }

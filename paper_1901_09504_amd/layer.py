@@ -185,22 +185,81 @@ class ExpandedConv:
         return ((H + 2 * self.pad - self.kh) // self.stride + 1,
                 (W + 2 * self.pad - self.kw) // self.stride + 1)
 
-    def forward(self, A, threshold=None, acc_out=None, stream=None):
-        """A fp32 [B, H, W, C] contiguous -> Y fp32 [B*Ho*Wo, N]."""
-        Bn, H, W, C = A.shape
-        assert C == self.C and A.is_contiguous()
-        P = Bn * H * W
-        Ho, Wo = self.out_size(H, W)
-        M = Bn * Ho * Wo
+    def ensure_input(self, P):
+        """Room for the codes of P input pixels."""
         if P > self._pixels:
             self.Aq = torch.empty((P, self.ldc), dtype=torch.int8, device=self.device)
             self.ws_a = B.alloc_workspace(P, self.C, self.device)
             self._pixels = P
+
+    def ensure_output(self, M):
         if self.Y is None or self.Y.shape[0] < M:
             self.Y = torch.empty((M, self.N), dtype=torch.float32, device=self.device)
+
+    def split_act(self, A, threshold=None, stream=None):
+        """A fp32 [B, H, W, C] contiguous -> codes of the un-lowered activation in self.Aq."""
+        Bn, H, W, C = A.shape
+        assert C == self.C and A.is_contiguous()
+        P = Bn * H * W
+        self.ensure_input(P)
         B.ocs_split_act(A, P, self.C, 1, self.C, self.w.chan_src, None, self.s, self.w.bits_x, threshold,
                         1.0, self.Aq, self.ldc, self.scale_x, self.ws_a, stream)
+
+    def conv(self, Bn, H, W, acc_out=None, stream=None):
+        """The convolution on the codes in self.Aq -> Y fp32 [B*Ho*Wo, N]."""
+        Ho, Wo = self.out_size(H, W)
+        M = Bn * Ho * Wo
+        self.ensure_output(M)
         B.ocs_qconv(self.Aq, self.ldc, Bn, H, W, self.E, self.kh, self.kw, self.stride, self.pad, self.Wt,
                     self.N, self.w.bits_x, self.w.bits_w, self.scale_x, self.w.scale_w, acc_out,
                     0 if acc_out is None else acc_out.stride(0), self.Y, self.N, stream)
         return self.Y[:M]
+
+    def conv_to_codes(self, Bn, H, W, nxt, next_threshold, relu=True, acc_out=None, stream=None):
+        """The convolution on the codes in self.Aq, its output handed to the layer `nxt` as that
+        layer's input codes (nxt.Aq, nxt.scale_x): the next layer's static grid after an optional
+        ReLU, with the channels the next layer splits duplicated."""
+        Ho, Wo = self.out_size(H, W)
+        M = Bn * Ho * Wo
+        assert nxt.C == self.N
+        nxt.ensure_input(M)
+        B.ocs_qconv_requant(self.Aq, self.ldc, Bn, H, W, self.E, self.kh, self.kw, self.stride, self.pad,
+                            self.Wt, self.N, self.w.bits_x, self.w.bits_w, self.scale_x, self.w.scale_w, relu,
+                            next_threshold, nxt.w.bits_x, nxt.w.chan_src, nxt.s, nxt.Aq, nxt.ldc, nxt.scale_x,
+                            acc_out, 0 if acc_out is None else acc_out.stride(0), stream)
+        return Ho, Wo
+
+    def forward(self, A, threshold=None, acc_out=None, stream=None):
+        """A fp32 [B, H, W, C] contiguous -> Y fp32 [B*Ho*Wo, N]."""
+        Bn, H, W, _ = A.shape
+        self.split_act(A, threshold, stream)
+        return self.conv(Bn, H, W, acc_out, stream)
+
+
+class ConvChain:
+    """A run of convolutions whose activations travel from layer to layer as codes: weight OCS on
+    every layer, static activation grids (Sec. 5: fixed from profiling), ReLU between the layers.
+    The first layer's input is split and quantized once, un-lowered; every layer but the last hands
+    its output to the next one through the re-quantizing epilogue; the last writes fp32.
+    specs: [(N, k, stride, pad), ...]."""
+
+    def __init__(self, C_in, specs, r, bits_w=8, bits_x=8, clip_ratio_w=1.0, device="cuda"):
+        self.layers = []
+        c = C_in
+        for (N, k, stride, pad) in specs:
+            self.layers.append(ExpandedConv(N, c, k, k, stride, pad, r, bits_w, bits_x,
+                                            clip_ratio_w=clip_ratio_w, device=device))
+            c = N
+
+    def prepare_weights(self, weights, stream=None):
+        for L, W in zip(self.layers, weights):
+            L.prepare_weights(W, stream)
+
+    def forward(self, A, thresholds, acc_out=None, stream=None):
+        """A fp32 [B, H, W, C]; thresholds: one device float per layer (its input grid's range).
+        Returns Y fp32 [B*Ho*Wo, N_last]; acc_out (optional) receives the last layer's accumulators."""
+        Bn, H, W, _ = A.shape
+        self.layers[0].split_act(A, thresholds[0], stream)
+        for i, L in enumerate(self.layers[:-1]):
+            H, W = L.conv_to_codes(Bn, H, W, self.layers[i + 1], thresholds[i + 1], True, None, stream)
+        return self.layers[-1].conv(Bn, H, W, acc_out, stream)

@@ -275,6 +275,62 @@ def test_config2_as_convolution_full_size():
     assert torch.equal(Y1, L.forward(dev(A)))           # the timed configuration stores no accumulators
 
 
+# ---- one bottleneck of config 5 at batch 256 as a chain: codes from layer to layer ---------------------
+
+def test_config5_bottleneck_as_a_chain_batch256():
+    """The second bottleneck of stage 2 (512 -> 128 1x1, 128 -> 128 3x3, 128 -> 512 1x1 at 28 x 28, batch
+    256) with its convolutions given un-lowered and the activations handed on as codes (ReLU, the next
+    layer's static grid and duplicated channels): every code tensor between the layers, the last
+    layer's accumulators and its outputs, all 200704 rows, against the oracle's chain (split+quantize,
+    im2col of the codes, integer GEMM, re-quantization, layer by layer)."""
+    from paper_1901_09504_amd.layer import ConvChain
+    layers = {l.name: l for l in wl.config(5)}
+    la, lb, lc = layers["s2b1_1x1a"], layers["s2b1_3x3"], layers["s2b1_1x1b"]
+    Bn, H, Wd_ = 256, 28, 28
+    P = Bn * H * Wd_
+    assert la.M == P and la.C == 512 and lb.C == 128 and lb.g == 9 and lc.N == 512
+    Ws = [wl.weights(la), wl.weights(lb), wl.weights(lc)]
+    A = _activations(la)                                   # [P, 512] = the block's input, NHWC
+    chain = ConvChain(la.C, [(la.N, 1, 1, 0), (lb.N, 3, 1, 1), (lc.N, 1, 1, 0)], la.r, la.bits_w, la.bits_x,
+                      clip_ratio_w=0.9)
+    chain.prepare_weights([dev(w) for w in Ws])
+    La, Lb, Lc = chain.layers
+    # oracle, layer by layer
+    T0 = 5.0
+    spa = ref.split_weights(Ws[0], la.C, 1, La.s)
+    Wqa, swa = ref.quantize(spa["T_out"], la.bits_w, clip_ratio=0.9)
+    Aqa, sxa, _ = ref.split_act(A, la.C, 1, spa["chan_src"], None, La.s, la.bits_x, threshold=T0, ldq=La.ldc)
+    acca, ya = ref.qgemm(Aqa, Wqa, La.E, sxa[1], swa[1])
+    T1 = float(np.float32(0.6) * np.float32(np.abs(ya).max()))
+    del ya
+    spb = ref.split_weights(Ws[1], lb.C, 9, Lb.s)
+    Wqb, swb = ref.quantize(spb["T_out"], lb.bits_w, clip_ratio=0.9)
+    Aqb, sxb = ref.requantize(acca, sxa[1], swa[1], T1, lb.bits_x, spb["chan_src"], Lb.s, relu=True, ldq=Lb.ldc)
+    Xb = ref.im2col(Aqb[:, :Lb.E].reshape(Bn, H, Wd_, Lb.E), 3, 3, 1, 1)
+    accb, yb = ref.qgemm(Xb, Wqb, Lb.E * 9, sxb[1], swb[1])
+    T2 = float(np.float32(0.6) * np.float32(np.abs(yb).max()))
+    del yb, Xb
+    spc = ref.split_weights(Ws[2], lc.C, 1, Lc.s)
+    Wqc, swc = ref.quantize(spc["T_out"], lc.bits_w, clip_ratio=0.9)
+    Aqc, sxc = ref.requantize(accb, sxb[1], swb[1], T2, lc.bits_x, spc["chan_src"], Lc.s, relu=True, ldq=Lc.ldc)
+    accc, yc = ref.qgemm(Aqc, Wqc, Lc.E, sxc[1], swc[1])
+    assert (Aqb != 0).mean() > 0.2 and (Aqc != 0).mean() > 0.2      # the grids span the activations
+    # GPU
+    thr = [torch.tensor([t], dtype=torch.float32, device="cuda") for t in (T0, T1, T2)]
+    for L in (La, Lb, Lc):
+        L.ensure_input(P)
+        L.Aq.fill_(77)                                     # every byte, pad columns included, is the call's to write
+    acc = torch.empty((P, lc.N), dtype=torch.int32, device="cuda")
+    Y = chain.forward(dev(A).view(Bn, H, Wd_, la.C), thr, acc_out=acc)
+    assert np.array_equal(host(La.scale_x), sxa) and np.array_equal(host(La.Aq), Aqa)
+    assert np.array_equal(host(Lb.scale_x), sxb) and np.array_equal(host(Lb.Aq), Aqb)
+    assert np.array_equal(host(Lc.scale_x), sxc) and np.array_equal(host(Lc.Aq), Aqc)
+    assert np.array_equal(host(acc), accc)
+    assert_y_close(host(Y), yc)
+    Y1 = Y.clone()
+    assert torch.equal(Y1, chain.forward(dev(A).view(Bn, H, Wd_, la.C), thr))   # no accumulator dump: same outputs
+
+
 # ---- the expanded layer run un-expanded: folded weight codes ------------------------------------
 
 @pytest.mark.parametrize("cfg", [3, 4, 5])

@@ -378,6 +378,29 @@ def test_split_act_deep_halvings(act_dep):
     assert np.array_equal(q, q_ref)
 
 
+def test_split_weights_halvings_that_leave_the_normal_range():
+    """Weights of a few 1e-38: the halvings of Eq. 3 push them below the normal range, where every
+    halving rounds; the expanded fp32 weights and the codes equal the oracle's (which halves split by
+    split) on every route of the weight path: codes only (selection inside the code pass), fp32 and
+    codes (selector launch, streaming pass, fp32 materialisation)."""
+    rng = np.random.default_rng(5)
+    N, Cn, g, s = 23, 10, 3, 9
+    bits = rng.integers(1, 0x00040000, (N, Cn * g)).astype(np.uint32)
+    bits[:, 6:9] = rng.integers(0x01000000, 0x01800000, (N, g))
+    W = (bits | (rng.integers(0, 2, bits.shape).astype(np.uint32) << 31)).view(np.float32)
+    exp = ref.split_weights(W, Cn, g, s)
+    assert exp["chan_depth"].max() >= 3
+    for want_f32 in (False, True):
+        got = gpu_split_weights(W, Cn, g, s, bits=8, want_f32=want_f32)
+        q_ref, sc_ref = ref.quantize(exp["T_out"], 8, ldq=got["Wq"].shape[1])
+        assert np.array_equal(got["split_src"], exp["split_src"]) and np.array_equal(got["chan_depth"], exp["chan_depth"])
+        if want_f32:
+            assert np.array_equal(got["T_out"].view(np.uint32), exp["T_out"].view(np.uint32))
+        assert np.array_equal(got["scale"], sc_ref)
+        assert np.array_equal(got["Wq"], q_ref)
+        assert len(np.unique(got["Wq"])) > 3
+
+
 # ---- ocs_qgemm -------------------------------------------------------------------------------
 
 GEMM_TILES = [6, 7, 9, 10, 11, 12, 14, 16, 17, 18, 19, 23]     # every tile variant of the library
@@ -565,8 +588,7 @@ def test_qgemm_requant(tile, M, N, K, s_next, relu):
     cs = _next_layer_list(rng, N, s_next) if s_next else None
     ldy = B.ocs_padded_channels(N + s_next) + 16
     q_ref, sc_ref = ref.requantize(acc_ref, sx[1], sw[1], T, 5, cs, s_next, relu=relu, ldq=ldy)
-    Yq = torch.zeros((M, ldy), dtype=torch.int8, device="cuda")
-    Yq[:, :N + s_next] = 77
+    Yq = torch.full((M, ldy), 77, dtype=torch.int8, device="cuda")     # the call writes its pad columns itself
     acc = torch.full((M, N), -9, dtype=torch.int32, device="cuda")
     sc = torch.zeros(2, dtype=torch.float32, device="cuda")
     thr = torch.tensor([T], dtype=torch.float32, device="cuda")
@@ -602,7 +624,7 @@ def test_conv_chain_with_codes_between_the_layers(tile):
     w2 = gpu_split_weights(W2, N1, 1, s2, bits=6, want_f32=False)
     assert np.array_equal(w2["Wq"], W2q) and np.array_equal(w2["chan_src"], sp2["chan_src"])
     M = Bn * H * W
-    Yq = torch.zeros((M, ld2), dtype=torch.int8, device="cuda")
+    Yq = torch.full((M, ld2), 77, dtype=torch.int8, device="cuda")
     sc2 = torch.zeros(2, dtype=torch.float32, device="cuda")
     thr = torch.tensor([T2], dtype=torch.float32, device="cuda")
     Wt = dev(g1["Wt"])

@@ -659,3 +659,28 @@ def test_qa_activation_members_add_up_and_keep_the_layer():
     s1 = ref.split_weights(ex, 2, 1, 1)
     q1, _, f1 = ref.split_act_qa(ex, 2, 1, s1["split_src"], 1, 4, 7.0, want_f32=True)
     assert f1[1].tolist() == [1.25, 0.25, 1.75] and q1[1].tolist() == [1, 0, 2]
+
+
+def test_weights_are_halved_split_by_split_also_below_the_normal_range():
+    """Eq. 3 halves both copies at every split (Sec. 3.4: one split at a time).  While the values stay
+    normal numbers, d splits are an exact factor 2^-d; weights of a few 1e-38 leave the normal range on
+    the way, and every further halving then rounds.  The oracle's expanded tensor equals a replay of
+    its split list with numpy's own fp32 halvings, one per split, and differs from a single multiply
+    by 2^-depth on such data (so a GPU path that takes the shortcut is caught by the parity test)."""
+    rng = np.random.default_rng(5)
+    N, Cn, g, s = 23, 10, 3, 9
+    bits = rng.integers(1, 0x00040000, (N, Cn * g)).astype(np.uint32)          # small subnormals
+    bits[:, 6:9] = rng.integers(0x01000000, 0x01800000, (N, g))                 # one dominant channel just above 2^-125, re-split
+    W = (bits | (rng.integers(0, 2, bits.shape).astype(np.uint32) << 31)).view(np.float32)
+    out = ref.split_weights(W, Cn, g, s)
+    cols = [W[:, c * g:(c + 1) * g].copy() for c in range(Cn)]
+    for i, j in enumerate(out["split_src"]):
+        cols[j] = cols[j] * np.float32(0.5)                                      # one rounding per split
+        cols.append(cols[j].copy())
+    replay = np.concatenate(cols, axis=1)
+    assert replay.dtype == np.float32
+    assert np.array_equal(out["T_out"].view(np.uint32), replay.view(np.uint32))
+    assert out["chan_depth"].max() >= 3
+    shortcut = np.concatenate([W[:, c * g:(c + 1) * g] * np.ldexp(np.float32(1), -int(d))
+                               for c, d in zip(out["chan_src"], out["chan_depth"])], axis=1).astype(np.float32)
+    assert not np.array_equal(shortcut.view(np.uint32), replay.view(np.uint32))
