@@ -10,7 +10,9 @@ pass).  A step is one pass of the hot path over that batch, layer after layer:
     ocs_qgemm           int8 MFMA GEMM over the expanded K, dequantizing epilogue         (G1, G2)
 
 The activation grid is static (Sec. 5 of the paper fixes it from profiling), so the pass that
-takes max|X| (X1) is not in the step; `dynamic_grid` reports the step with it.  Every layer owns
+takes max|X| (X1) is not in the step; `dynamic_grid` reports the step with it.  The weight path
+depends on nothing the activation path produces and is queued on a second stream (`single_stream`
+reports the step with everything in order on one stream).  Every layer owns
 its activation tensor (22.3 GB in all, resident in HBM before the timed region), so between two
 reads of a tensor 22 GB stream through the chip and nothing is served by the 256 MB memory-side
 cache.  `value` is whole-pass throughput from the wall clock around the timed steps.  Kernel
@@ -55,6 +57,8 @@ class Net:
 
     def __init__(self, torch, wl, ExpandedLayer, layers, clip):
         self.layers = layers
+        self.torch = torch
+        self.wev = [torch.cuda.Event() for _ in layers]
         self.L, self.W, self.X = [], [], []
         gen = torch.Generator(device="cuda")
         for l in layers:
@@ -69,13 +73,26 @@ class Net:
                                         max_rows=l.M))
         self.thr = torch.tensor([STATIC_T], dtype=torch.float32, device="cuda")
 
-    def step(self, B=None, ev=None, dynamic=False, weights=True):
+    def step(self, B=None, ev=None, dynamic=False, weights=True, side=None):
         """One pass.  ev: per-layer event lists [x2 a, x2 b, gemm a, gemm b, absmax a, absmax b]
-        that the launches stamp themselves (B = the binding)."""
+        that the launches stamp themselves (B = the binding).  side: a second stream for the weight
+        path, which depends on nothing the activation path produces: every layer's weight
+        preparation is queued there, and the activation path waits, layer by layer, for the event
+        behind it."""
         thr = None if dynamic else self.thr
+        torch = self.torch
+        if side is not None and weights:
+            main = torch.cuda.current_stream()
+            side.wait_stream(main)             # the previous pass no longer reads the weight codes
+            with torch.cuda.stream(side):
+                for i, L in enumerate(self.L):
+                    L.prepare_weights(self.W[i])
+                    self.wev[i].record(side)
         for i, (l, L) in enumerate(zip(self.layers, self.L)):
-            if weights:
+            if weights and side is None:
                 L.prepare_weights(self.W[i])
+            elif weights:
+                torch.cuda.current_stream().wait_event(self.wev[i])
             if ev is not None:
                 if dynamic:
                     B.ocs_time_next(B.TIME_ABSMAX, ev[i][4], ev[i][5])
@@ -86,7 +103,7 @@ class Net:
             L.qgemm(l.M)
 
 
-def stamped_steps(torch, B, net, n, dynamic=False):
+def stamped_steps(torch, B, net, n, dynamic=False, side=None):
     """n passes whose split+quantize, GEMM (and max|X|) launches carry their own events.
     Returns arrays [n, layers] of kernel microseconds."""
     nl = len(net.layers)
@@ -99,7 +116,7 @@ def stamped_steps(torch, B, net, n, dynamic=False):
     gm = np.zeros((n, nl))
     x1 = np.zeros((n, nl))
     for s in range(n):
-        net.step(B, ev, dynamic=dynamic)
+        net.step(B, ev, dynamic=dynamic, side=side)
         torch.cuda.synchronize()
         for i in range(nl):
             x2[s, i] = ev[i][0].elapsed_time(ev[i][1]) * 1e3
@@ -338,7 +355,7 @@ def ceilings(torch, B, reps=5):
     return out
 
 
-def cpu_baseline(wl, layers, clip, row_fraction=8):
+def cpu_baseline(wl, layers, clip, row_fraction=4):
     """The CPU oracle, as it stands, on this machine's host cores: the whole step (weight path in
     full, activation pass and GEMM on the first 1/row_fraction of every layer's rows)."""
     from oracle import ref
@@ -373,6 +390,8 @@ def main():
     ap.add_argument("--clip", type=float, default=0.9, help="weight clip ratio used in the timed step")
     ap.add_argument("--stamped-steps", type=int, default=20,
                     help="untimed passes whose launches carry their own events (at least 20 samples per layer)")
+    ap.add_argument("--single-stream", action="store_true",
+                    help="queue the weight path in order on the activation path's stream instead of on a second one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the secondary measurements (dynamic grid, weight path, ceilings, config 2)")
@@ -397,18 +416,25 @@ def main():
     net = Net(torch, wl, ExpandedLayer, layers, args.clip)
     torch.cuda.synchronize()
 
-    for _ in range(args.warmup):
-        net.step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        net.step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
+    # the weight path depends on nothing the activation path produces: it is queued on a second
+    # stream (default priority), and each layer's activation pass waits for the event behind its
+    # weights; --single-stream keeps everything in order on one stream
+    side = None if args.single_stream else torch.cuda.Stream()
+
+    def timed(n, **kw):
+        for _ in range(max(1, args.warmup) if n == args.steps else 2):
+            net.step(**kw)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            net.step(**kw)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n * 1e3
+
+    ms_per_step = timed(args.steps, side=side)
 
     n_stamp = max(20, args.stamped_steps)
-    x2, gm, _ = stamped_steps(torch, B, net, n_stamp)
+    x2, gm, _ = stamped_steps(torch, B, net, n_stamp, side=side)
     # a plain copy of known size right behind the measured passes: the reference that the HBM byte
     # counters of a profiled run of this same command are scaled by, and this chip's own copy rate
     copy_ref = calib_copy(torch, B, net)
@@ -431,7 +457,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": "configs[4]: ResNet-50-shaped sweep, all 53 conv layers as im2col GEMMs at batch "
                                f"256, r=0.05, 4-bit weights (clip {args.clip} x max|W'|), 8-bit activations on a "
-                               "static grid; per layer: weight path, split+quantize, expanded GEMM",
+                               "static grid; per layer: weight path, split+quantize, expanded GEMM; weight path "
+                               + ("in order on the same stream" if side is None else "queued on a second stream"),
                    "tera_ops_per_step": ops / 1e12, "layers": len(layers),
                    "activation_bytes_resident": int(sum(x.numel() * 4 for x in net.X)),
                    "stamped_steps": n_stamp},
@@ -448,7 +475,8 @@ def main():
                      "timing": "HIP events stamped by the launch itself (hipExtLaunchKernel) on its stream: the "
                                "dispatch's own begin and end; mean over the stamped passes of the per-pass sum"},
         "step_breakdown_ms": {"split_quant_kernels": x2_us_step / 1e3, "gemm_kernels": gemm_us_step / 1e3,
-                              "rest (weight path, dispatch gaps)": ms_per_step - (x2_us_step + gemm_us_step) / 1e3},
+                              "rest (weight path not hidden behind them, dispatch gaps)":
+                                  ms_per_step - (x2_us_step + gemm_us_step) / 1e3},
         "gemm_mfma_bound": [{k: r[k] for k in ("layer", "M", "N", "Kexp", "gemm_us", "gemm_tops", "gemm_ai")} |
                             {"pct_mfma_peak": round(100.0 * r["gemm_tops"] / INT8_PEAK_TOPS, 2)} for r in mfma],
         "calib_copy": copy_ref,
@@ -456,21 +484,21 @@ def main():
     }
     if not args.no_extras:
         # the pass with a per-batch activation grid: X1 (max|X|) in front of every split+quantize
-        for _ in range(2):
-            net.step(dynamic=True)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(5):
-            net.step(dynamic=True)
-        torch.cuda.synchronize()
-        dyn_ms = (time.perf_counter() - t0) / 5 * 1e3
-        _, _, x1 = stamped_steps(torch, B, net, 5, dynamic=True)
+        dyn_ms = timed(5, dynamic=True, side=side)
+        _, _, x1 = stamped_steps(torch, B, net, 5, dynamic=True, side=side)
         x1_us_step = float(np.mean(x1.sum(axis=1)))
         x1_bytes = sum(4.0 * l.M * l.K for l in layers)
         out["dynamic_grid"] = {"ms_per_step": dyn_ms, "tops_whole_step": ops / dyn_ms / 1e9,
                                "absmax_kernels_ms_per_step": x1_us_step / 1e3,
                                "absmax_GBps": x1_bytes / x1_us_step / 1e3,
                                "absmax_frac_hbm": x1_bytes / x1_us_step / 1e3 / HBM_PEAK_GBS, "steps": 5}
+        # the same pass with everything in order on one stream
+        if side is not None:
+            ss_ms = timed(10)
+            out["single_stream"] = {"ms_per_step": ss_ms, "tops_whole_step": ops / ss_ms / 1e9, "steps": 10}
+        # the pass without the weight path (weights prepared once, off-line, as in Sec. 3.5)
+        nw_ms = timed(10, weights=False)
+        out["weights_prepared_off_line"] = {"ms_per_step": nw_ms, "tops_whole_step": ops / nw_ms / 1e9, "steps": 10}
         # the weight path alone, per clip ratio (the ratio changes only the grid and the codes)
         wp = {}
         for clip in (1.0, 0.9, 0.8):

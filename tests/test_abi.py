@@ -167,13 +167,3 @@ def test_binding_raises_on_error():
     with pytest.raises(B.OcsError) as e:
         B._check(-4, "ocs_quantize")
     assert "2..8" in str(e.value) and e.value.code == -4
-
-
-def test_sweep_tool_imports_without_a_gpu():
-    from paper_1901_09504_amd import sweep
-    assert callable(sweep.run) and callable(sweep.main)
-
-
-def test_variants_tool_imports_without_a_gpu():
-    from paper_1901_09504_amd import variants
-    assert callable(variants.run) and callable(variants.main)
