@@ -41,9 +41,10 @@ STATIC_T = 5.0               # the static activation grid's range (inputs are |N
 # HBM bytes per step moved by the split+quantize launches of this workload, from two rocprofv3
 # --pmc runs of this command (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter
 # reads for the plain copy kernel of known size that runs after the timed region
-# (profiles/x2_config5_hbm_traffic.md).  Valid only for the kernel source it was measured on:
+# (profiles/bench_config5_headline.md).  Valid only for the kernel source it was measured on:
 # reported as null once that file changes.
-X2_TRAFFIC = {"quantize_hip_sha256": None, "bytes_per_step": None}
+X2_TRAFFIC = {"quantize_hip_sha256": "e4b00290ce5f0e4d47eb2ead7216ec36be510a4bcaadc414826768850f23a359",
+              "bytes_per_step": 29930174715}
 
 
 def x2_traffic():
@@ -196,11 +197,38 @@ def config2_step(torch, B, wl, ExpandedLayer, steps=100, stamped=24, copies=6):
     x2_bytes = 4.0 * M * K + 1.0 * M * L.Ke
     x2_us, g_us, x1_us, cold_us = (float(np.median(k[:, 0])), float(np.median(k[:, 1])),
                                    float(np.median(k[:, 2])), float(np.median(cold)))
+
+    # the calibration-time and variant entry points on the same layer (wall clock per call)
+    def per_call(fn, n=50):
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(n):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / n * 1e6
+
+    hist = torch.empty(2048, dtype=torch.int64, device="cuda")
+    mse = torch.empty(512, dtype=torch.float64, device="cuda")
+    thr2 = torch.empty(2, dtype=torch.float32, device="cuda")
+    variants = {
+        "weights_plain_halves_us": per_call(lambda i: L.prepare_weights(Wd)),
+        "weights_qa_members_us (Sec. 3.3)": per_call(lambda i: L.prepare_weights(Wd, qa=True)),
+        "mse_clip_search_on_X_us (Sec. 4.1, 2048 bins, 512 candidates)":
+            per_call(lambda i: B.ocs_mse_clip_threshold(Xd[i % copies], M, K, K, 8, 2048, 512, thr2, hist, mse, L.ws_x)),
+        "mse_clip_search_on_W_us": per_call(lambda i: B.ocs_mse_clip_threshold(Wd, N, K, K, 8, 2048, 512, thr2, hist,
+                                                                              mse, L.ws_w)),
+        "forward_per_batch_activation_ocs_us (Sec. 5.3, Eq. 4)": per_call(lambda i: L.forward_act_ocs(Wd, Xd[i % copies])),
+        "forward_per_batch_activation_ocs_qa_us": per_call(lambda i: L.forward_act_ocs(Wd, Xd[i % copies], qa=True)),
+    }
+    L.prepare_weights(Wd)
     return {"workload": f"configs[1]: M={M} K={K} N={N} r={layer.r} (K'={L.Ke}, padded {L.ldq}), 8/8 bit, "
                         "weight path + per-batch grid + split+quantize + GEMM per step",
             "us_per_step": us, "tops_whole_step": ops / us / 1e6, "steps": steps,
             "absmax_kernel_us": x1_us, "gemm_kernel_us": g_us, "gemm_tops": ops / g_us / 1e6,
             "gemm_pct_mfma_peak": 100.0 * ops / g_us / 1e6 / INT8_PEAK_TOPS,
+            "variants": variants,
             "split_quant_cache_cold": {"kernel_us": cold_us, "GBps": x2_bytes / cold_us / 1e3,
                                        "frac_hbm": x2_bytes / cold_us / 1e3 / HBM_PEAK_GBS,
                                        "launches_timed": len(cold)},
@@ -278,6 +306,47 @@ def chained_pass(torch, wl, layers, clip, ops, steps=10):
                     "loader), codes handed from layer to layer inside each bottleneck (re-quantizing epilogue), "
                     "fp32 only at block outputs; weight path included; same 2.22 tera-ops",
             "ms_per_step": ms, "tops_whole_step": ops / ms / 1e9, "steps": steps}
+
+
+def split_k_compare(torch, B, wl, ExpandedLayer, launches=24, copies=5):
+    """The one layer shape above the MFMA ridge (512 -> 512 3x3 at batch 256: 196 tiles of 256 x 128 for
+    256 compute units) through ocs_qgemm and through ocs_qgemm_split_k (98 tiles of 256 x 256, K shared
+    by 2 or 3 workgroups each); the activation codes rotate through several copies."""
+    layer = next(l for l in wl.config(5) if l.name == "s4b0_3x3")
+    M, N = layer.M, layer.N
+    L = ExpandedLayer(N, layer.C, layer.g, layer.r, layer.bits_w, layer.bits_x, max_rows=M)
+    L.prepare_weights(torch.from_numpy(wl.weights(layer)).cuda())
+    L.split_act(torch.from_numpy(wl.activations(layer)).cuda())
+    torch.cuda.synchronize()
+    Xq = [L.Xq.clone() for _ in range(copies)]
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for e in ev:
+        e.record()
+    ops = 2.0 * M * N * L.Ke
+    out = {"workload": f"M={M} N={N} K'={L.Ke} (padded {L.ldq}), {copies} rotating copies of the activation codes"}
+    Y_ref = None
+    for parts in (1, 2, 3):
+        ws = torch.empty(max(256, B.ocs_qgemm_split_k_workspace_bytes(M, N, L.Ke, parts)), dtype=torch.uint8,
+                         device="cuda")
+        us = []
+        for i in range(launches + 4):
+            B.ocs_time_next(B.TIME_GEMM, ev[0], ev[1])
+            if parts == 1:
+                B.ocs_qgemm(Xq[i % copies], L.ldq, L.Wq, L.ldq, M, N, L.Ke, L.bits_x, L.bits_w, L.scale_x,
+                            L.scale_w, None, 0, L.Y, N, None)
+            else:
+                B.ocs_qgemm_split_k(Xq[i % copies], L.ldq, L.Wq, L.ldq, M, N, L.Ke, L.bits_x, L.bits_w, L.scale_x,
+                                    L.scale_w, None, 0, L.Y, N, parts, ws)
+            torch.cuda.synchronize()
+            if i >= 4:
+                us.append(ev[0].elapsed_time(ev[1]) * 1e3)
+        if Y_ref is None:
+            Y_ref = L.Y.clone()
+        med = float(np.median(us))
+        out["un-split" if parts == 1 else f"{parts} parts"] = {
+            "median_us": med, "tops": ops / med / 1e6, "pct_mfma_peak": 100.0 * ops / med / 1e6 / INT8_PEAK_TOPS,
+            "same_output_bits": bool(torch.equal(Y_ref, L.Y)), "launches_timed": len(us)}
+    return out
 
 
 def calib_copy(torch, B, net, reps=4):
@@ -393,6 +462,11 @@ def main():
     ap.add_argument("--single-stream", action="store_true",
                     help="queue the weight path in order on the activation path's stream instead of on a second one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extras", default="steps,chained,ceilings,config2,splitk",
+                    help="secondary measurements to run: steps (per-batch grid, single stream, off-line weights, "
+                         "weight path by clip), chained, ceilings, config2, splitk")
+    ap.add_argument("--only", choices=["chained", "ceilings", "config2", "splitk"], default=None,
+                    help="run one secondary measurement alone and print it (no headline)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the secondary measurements (dynamic grid, weight path, ceilings, config 2)")
     args = ap.parse_args()
@@ -413,6 +487,15 @@ def main():
     B.lib()  # fails loudly when libocs.so is missing
 
     layers = wl.config(5)
+    if args.only:
+        # one secondary measurement by itself (for profiler runs that should see only its kernels)
+        ops5 = sum(2.0 * l.M * l.N * (l.C + B.ocs_num_splits(l.C, l.r)) * l.g for l in layers)
+        res = {"chained": lambda: chained_pass(torch, wl, layers, args.clip, ops5),
+               "ceilings": lambda: ceilings(torch, B),
+               "config2": lambda: config2_step(torch, B, wl, ExpandedLayer),
+               "splitk": lambda: split_k_compare(torch, B, wl, ExpandedLayer)}[args.only]()
+        print(json.dumps({"only": args.only, args.only: res}))
+        return
     net = Net(torch, wl, ExpandedLayer, layers, args.clip)
     torch.cuda.synchronize()
 
@@ -467,7 +550,8 @@ def main():
         "roofline": {"kernel": "expand_quantize_kernel / expand_quantize_in_kernel (ocs_split_act, X2): the 53 "
                                "launches of one pass", "bound": "hbm",
                      "achieved": x2_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": x2_gbs / HBM_PEAK_GBS,
-                     "traffic": x2_traffic(),
+                     "traffic": None if x2_traffic() is None else x2_traffic() / len(layers),
+                     "traffic_bytes_per_step": x2_traffic(),
                      "algorithmic_bytes_per_step": x2_bytes, "kernel_us_per_step": x2_us_step,
                      "avg_launch_us": x2_us_step / len(layers), "launches_per_step": len(layers),
                      "launches_timed": int(x2.size), "cache": "cold: every launch reads a tensor that 22 GB of "
@@ -482,7 +566,8 @@ def main():
         "calib_copy": copy_ref,
         "layers": rows,
     }
-    if not args.no_extras:
+    extras = set() if args.no_extras else set(args.extras.split(","))
+    if "steps" in extras:
         # the pass with a per-batch activation grid: X1 (max|X|) in front of every split+quantize
         dyn_ms = timed(5, dynamic=True, side=side)
         _, _, x1 = stamped_steps(torch, B, net, 5, dynamic=True, side=side)
@@ -516,11 +601,15 @@ def main():
         out["weight_path_ms_per_pass_by_clip"] = wp
     del net
     torch.cuda.empty_cache()
-    if not args.no_extras:
+    if "chained" in extras:
         out["chained_unlowered"] = chained_pass(torch, wl, layers, args.clip, ops)
         torch.cuda.empty_cache()
+    if "ceilings" in extras:
         out["ceilings"] = ceilings(torch, B)
+    if "config2" in extras:
         out["config2_step"] = config2_step(torch, B, wl, ExpandedLayer)
+    if "splitk" in extras:
+        out["gemm_split_k"] = split_k_compare(torch, B, wl, ExpandedLayer)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, layers, args.clip)
     print(json.dumps(out))
