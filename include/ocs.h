@@ -451,7 +451,7 @@ int ocs_calib_mfma(const void *operands, int iters, int workgroups, void *sink, 
  * split+quantize pass), "max_flat", "max_grid", "max_un", "max_bt" (the whole-tensor max|x|
  * pass), "sel_inline" (most splits for which ocs_split_weights runs the selection inside its
  * code pass instead of as a launch of its own; 0: never), "gemm_tile" (tile variant of
- * ocs_qgemm / ocs_qconv: 6, 7, 9, 10, 11, 12, 14, 16, 17, 18, 19, 23; an id a shape cannot use falls
+ * ocs_qgemm / ocs_qconv: 6, 7, 9, 10, 11, 12, 14, 16, 17, 18, 19, 23, 24; an id a shape cannot use falls
  * back to one it can).  value < 0 restores the default.  Returns OCS_OK or OCS_E_MODE for an
  * unknown key.  The settings belong to the calling thread and affect its own calls only.
  */

@@ -907,22 +907,26 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
                         hipStream_t stream, const Requant& rq) {
     int tile = tuning().gemm_tile;
     if (tile < 0) {
-        // Measured on MI355X over the layer shapes of the paper's networks.  A CU draws operands
-        // through its vector-memory path at only ~16-30 B/clk, rising with the number of waves
-        // that issue loads: the largest tile that still gives most CUs a workgroup wins, and
-        // workgroups of 8 waves beat 4.  Up to 320 bytes of K the layer is a stream of output
-        // rows and the whole-K kernel wins (1.2-1.5x), except that a very wide N is better served
-        // by the ring kernel's tile order (one L2 fill of an X row panel for all its N tiles).
-        // With N >= 256 and enough tiles, 256 columns per tile halve the reads of X.
+        // Measured on MI355X over the layer shapes of the paper's networks.  What a CU can draw is
+        // set by the line requests its L1 can have outstanding times their latency, so requests
+        // count, not bytes: the largest tile that still gives most CUs a workgroup wins, a K-step
+        // of one whole 128-byte line per row beats two half-line steps, and workgroups of 8 waves
+        // beat 4.  Up to 320 bytes of K the layer is a stream of output rows and the whole-K kernel
+        // wins (1.2-1.5x), except that a very wide N is better served by the ring kernel's tile
+        // order (one L2 fill of an X row panel for all its N tiles).  With N >= 256 and enough
+        // tiles, 256 columns per tile halve the reads of X.
         const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 128);
         const int64_t t128 = ceil_div(M, 128) * ceil_div(N, 128);
         const int64_t t256sq = ceil_div(M, 256) * ceil_div(N, 256);
         if (Kpad <= 320) tile = N <= 64 ? 17 : (N >= 1024 ? 9 : (N >= 512 ? 19 : 16));
-        else if (N <= 64) tile = 6;
+        else if (N <= 64) tile = 24;    // 128 x 64 with whole-line (128-byte) K-steps: 134 against 155 us on
+                                        // the 64 -> 64 3x3 layers at M = 802,816
         else if (N >= 256 && t256sq >= 192 && Kpad >= 1024) tile = 12;
-        else if (N >= 1024 && Kpad < 1024) tile = 9;
-        else if (N >= 256 && t256sq >= 512) tile = 12;
-        else if (t256 >= 128) tile = 11;
+        else if (N >= 1024 && Kpad < 1024) tile = 9;     // (launched alone on cold operands the 256 x 256 tile
+                                                         // is ahead here; behind the pass that wrote the codes
+                                                         // it is 7-18 % behind)
+        else if (N >= 512 && t256sq >= 512) tile = 12;
+        else if (t256 >= 128) tile = 11;                 // N = 256 with K below 1024 included (89 against 92 us)
         else if (t128 >= 48) tile = 23;   // 128-byte K-steps when the operands allow them
         else tile = 6;
     }
@@ -931,7 +935,7 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
     // on both operands (the producers' contract) and the walk may include them.
     const int64_t K128 = round_up(Kpad, 128);
     const bool k128 = K128 == Kpad || (ldx >= K128 && ldw >= K128);
-    // Tile variants by id (the dispatcher above picks 6, 9, 11, 12, 16, 17, 19 or 23; the others
+    // Tile variants by id (the dispatcher above picks 6, 9, 11, 12, 16, 17, 19, 23 or 24; the others
     // are kept selectable because the parity tests run every kernel family through them).
     switch (tile) {
         case 6: return run_dma<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
@@ -954,6 +958,8 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
 #undef OCS_WHOLEK
         case 23: return k128 ? run_dma<128, 128, 4, 2, 128, 3>(OCS_GEMM_ARGS128)
                              : run_dma<128, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);
+        case 24: return k128 ? run_dma<128, 64, 2, 2, 128, 3>(OCS_GEMM_ARGS128)
+                             : run_dma<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
         default: return run_dma<64, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
     }
 }
