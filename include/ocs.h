@@ -27,9 +27,9 @@
  *    every 2-D filter attached to it).  Activations X are [M, C*g], weights W are [N, C*g]
  *    (both operands K-contiguous), outputs Y are [M, N].
  *  - Code tensors (int8) have a 16-byte aligned base and a leading dimension that is a
- *    multiple of OCS_CALIGN; ocs_qgemm additionally needs a multiple of OCS_KALIGN (its
- *    K-step).  The producer writes zeros into every pad column (columns (C+s)*g .. ld-1)
- *    and the consumers rely on those zeros.
+ *    multiple of OCS_CALIGN; for rows longer than OCS_SHORT_K bytes ocs_qgemm additionally
+ *    needs a multiple of OCS_KALIGN (its K-step).  The producer writes zeros into every pad
+ *    column (columns (C+s)*g .. ld-1) and the consumers rely on those zeros.
  *  - fp32 inputs may have any leading dimension >= the row length and any float-aligned
  *    base: rows are read with 16-byte loads at whatever alignment they have.
  *  - `clip_ratio` (Sec. 4: the grid's threshold as a fraction of the largest magnitude) must be
@@ -53,6 +53,9 @@ extern "C" {
 #define OCS_ROWALIGN 128 /* what ocs_padded_cols rounds to: rows then start on cache-line boundaries
                             and ocs_qgemm can walk K in 128-byte steps (the zero padding joins in) */
 #define OCS_CALIGN 16 /* leading dimension of any int8 code tensor is a multiple of this */
+#define OCS_SHORT_K 320 /* rows of at most this many bytes (rounded up to OCS_KALIGN): ocs_qgemm reads
+                           them in one go and accepts any leading dimension that is a multiple of
+                           OCS_CALIGN and holds the row */
 
 #define OCS_OK 0
 #define OCS_E_NULL (-1)      /* a required pointer is NULL                                  */
@@ -88,10 +91,12 @@ int64_t ocs_padded_channels(int64_t channels);
 
 /*
  * Recommended leading dimension of the code tensor of an expanded layer: (C+s)*g rounded up to
- * OCS_ROWALIGN (to OCS_KALIGN for rows of at most 320 bytes, which the GEMM streams once: there
- * padding only adds bytes).  Any multiple of OCS_KALIGN that holds the row is accepted by
- * ocs_qgemm; with this one the rows of both operands are whole cache lines, which measured 10 %
- * (operands in cache) to 25 % (operands in HBM) faster on the 3x3 layer shapes.
+ * OCS_ROWALIGN, or, for rows of at most OCS_SHORT_K bytes, only to OCS_CALIGN: the GEMM streams
+ * such rows once and the pass that writes them is bound by memory, so padding there is only more
+ * bytes (a 68-code row of the paper's 64-channel layers takes 80 bytes, not 128).  For longer rows
+ * any multiple of OCS_KALIGN that holds the row is accepted by ocs_qgemm; with this one the rows
+ * of both operands are whole cache lines, which measured 10 % (operands in cache) to 25 %
+ * (operands in HBM) faster on the 3x3 layer shapes.
  */
 int64_t ocs_padded_cols(int64_t cols);
 
@@ -275,8 +280,10 @@ int ocs_act_threshold(const float *X, int64_t M, int C, int g, int64_t ldx, cons
  * The expanded layer of Eq. 2 on integer codes, then the trailing factors of Eq. 1:
  *   acc[i,n] = sum_{k < Kexp} Xq[i,k] * Wq[n,k]   (int8 x int8 -> int32, exact)
  *   Y[i,n]   = float(acc[i,n]) * (scale_x[1] * scale_w[1])
- * Xq [M, ldx], Wq [N, ldw] int8 with zero pad columns up to the next multiple of
- * OCS_KALIGN; scale_x, scale_w are the device float[2] written by the producers;
+ * Xq [M, ldx], Wq [N, ldw] int8; ldx, ldw >= Kexp rounded up to OCS_KALIGN and multiples of it,
+ * or, when that rounded extent is at most OCS_SHORT_K, >= Kexp rounded up to OCS_CALIGN and
+ * multiples of that (OCS_E_SHAPE / OCS_E_ALIGN otherwise; what such a row lacks up to its last
+ * K-step counts as zero codes); scale_x, scale_w are the device float[2] written by the producers;
  * bits_x / bits_w are the grids' bit widths, used only for the overflow check
  * Kexp * qmax_x * qmax_w < 2^31.  acc_out [M, ldacc] int32 is optional (NULL = not
  * stored); Y [M, ldy] fp32 is required.  workspace may be NULL (none is needed).

@@ -64,8 +64,13 @@ static int check_gemm_operands(const void* Xq, int64_t ldx, const void* Wq, int6
     if (M <= 0 || N <= 0 || Kexp <= 0) return OCS_E_SHAPE;
     if (M > (int64_t)1 << 30 || N > (int64_t)1 << 30 || Kexp > (int64_t)1 << 30) return OCS_E_SHAPE;
     const int64_t Kpad = round_up(Kexp, OCS_KALIGN);
-    if (ldx < Kpad || ldw < Kpad || (acc_out && ldacc < N)) return OCS_E_SHAPE;
-    if (ldx % OCS_KALIGN != 0 || ldw % OCS_KALIGN != 0 || !aligned(Xq, 16) || !aligned(Wq, 16))
+    // up to OCS_SHORT_K bytes of K (rounded up to the K-step) the pitch only has to hold the row
+    // in whole 16-byte pieces; beyond, it holds whole K-steps
+    const bool short_k = Kpad <= OCS_SHORT_K;
+    const int64_t need = short_k ? round_up(Kexp, OCS_CALIGN) : Kpad;
+    const int64_t unit = short_k ? OCS_CALIGN : OCS_KALIGN;
+    if (ldx < need || ldw < need || (acc_out && ldacc < N)) return OCS_E_SHAPE;
+    if (ldx % unit != 0 || ldw % unit != 0 || !aligned(Xq, 16) || !aligned(Wq, 16))
         return OCS_E_ALIGN;
     if (!bits_ok(bits_x) || !bits_ok(bits_w)) return OCS_E_BITS;
     const int64_t qx = (1 << (bits_x - 1)) - 1, qw = (1 << (bits_w - 1)) - 1;
@@ -129,7 +134,7 @@ int64_t ocs_padded_cols(int64_t cols) {
     if (cols <= 0) return 0;
     // rows of at most 320 bytes go through the GEMM's whole-K kernel, which streams them once:
     // more padding there is only more bytes (measured: 128-byte rows cost those layers 5-25 %)
-    return cols <= 320 ? round_up(cols, OCS_KALIGN) : round_up(cols, OCS_ROWALIGN);
+    return round_up(cols, OCS_KALIGN) <= OCS_SHORT_K ? round_up(cols, OCS_CALIGN) : round_up(cols, OCS_ROWALIGN);
 }
 
 int64_t ocs_conv_weight_cols(int g, int64_t ldc) {
@@ -509,6 +514,9 @@ int ocs_qgemm_split_k(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t l
     if (rc) return rc;
     if (ldy < N) return OCS_E_SHAPE;
     const int64_t Kpad = round_up(Kexp, OCS_KALIGN);
+    // the K split walks whole K-steps of both operands, also for a short K
+    if (ldx < Kpad || ldw < Kpad) return OCS_E_SHAPE;
+    if (ldx % OCS_KALIGN != 0 || ldw % OCS_KALIGN != 0) return OCS_E_ALIGN;
     const size_t need = qgemm_split_workspace_bytes(M, N, Kpad, parts);
     if (need == 0) return OCS_E_SHAPE;          // too many tiles, or parts outside 2 .. min(16, K-steps)
     if (workspace == nullptr || ws_bytes < need) return OCS_E_WORKSPACE;

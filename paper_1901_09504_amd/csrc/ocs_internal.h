@@ -234,8 +234,6 @@ struct Tuning {
     int act_dep = -1;   // Eq. 4 pass: per-column depths from a table in LDS (1), from global memory (0), by tensor size (-1)
     int act_nt = 0;     // non-temporal loads of X in that pass (off: appended columns re-read X through L2)
     int gemm_tile = -1;
-    int gemm_pf = -1;
-    int gemm_split = -1; // workgroups that share a tile's K extent (0 or 1: never; default: by shape)   // K-steps the GEMM's look-ahead wave runs ahead of the ring
     int max_flat = -1;  // whole-tensor max|x| of a contiguous tensor as one flat stream (1), by columns (0), default (-1)
     int max_grid = -1;  // workgroups of the flat pass
     int max_un = -1;    // 16-byte loads in flight per lane in the flat pass (1, 2 or 4)

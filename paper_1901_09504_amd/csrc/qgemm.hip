@@ -215,7 +215,15 @@ struct SplitK {
     int parts = 1;
 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF, bool CONV = false, bool SPLIT = false>
+// Sixteen zero codes: what a row "holds" past its pitch.  With a short K the rows of the operands
+// need not fill their last K-step (a 68-byte row in an 80-byte pitch, walked as 128 bytes): the
+// 16-byte pieces that lie past the pitch are fetched from here instead of from the next row.
+__device__ __align__(16) const int8_t zero_chunk[16] = {};
+
+// MASK: the pitches may end inside the last K-step (see zero_chunk); every request then checks
+// its piece against the pitch.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF, bool CONV = false, bool SPLIT = false,
+          bool MASK = false>
 __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
     const int8_t* __restrict__ Xq, int64_t ldx, const int8_t* __restrict__ Wq, int64_t ldw, int M,
     int N, int ksteps_all, const float* __restrict__ scale_x, const float* __restrict__ scale_w,
@@ -225,6 +233,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
     constexpr int NT = NW * 64;
     static_assert(NW == 4 || NW == 8 || NW == 16, "4, 8 or 16 waves");
     static_assert(!SPLIT || !CONV, "K split across workgroups: plain GEMM");
+    static_assert(!MASK || (!SPLIT && !CONV), "pitch shorter than the K walk: plain GEMM");
     static_assert(BK == 64 || BK == 128, "K-step of 64 or 128 bytes");
     static_assert(NBUF >= 3, "ring of at least three buffers");
     constexpr int CPR = BK / 16;
@@ -269,9 +278,12 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
     int a_iy0[CONV ? A_LOADS : 1], a_ix0[CONV ? A_LOADS : 1];
     int a_ky[CONV ? A_LOADS : 1], a_kx[CONV ? A_LOADS : 1], a_cin[CONV ? A_LOADS : 1];
     int a_zoff[CONV ? A_LOADS : 1];
+    int a_piece[MASK ? A_LOADS : 1], b_piece[MASK ? B_LOADS : 1];   // MASK: the lane's piece of K-step 0
+    const int a_pieces = (int)(ldx / 16), b_pieces = (int)(ldw / 16);
 #pragma unroll
     for (int u = 0; u < A_LOADS; ++u) {
         int pslot = (u * NW + wave) * 64 + lane, r = pslot / CPR, c = pslot % CPR;
+        if (MASK) a_piece[u] = swz<BK>(r, c);
         int gr = row0 + r;
         gr = gr < M ? gr : M - 1;  // rows past the edge re-read the last row; never stored
         if (CONV) {
@@ -301,6 +313,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
         int gr = col0 + r;
         gr = gr < N ? gr : N - 1;
         b_src[u] = Wq + (int64_t)gr * ldw + swz<BK>(r, c) * 16 + (int64_t)kbeg * BK;
+        if (MASK) b_piece[u] = swz<BK>(r, c);
     }
 
     // The load is issued through inline assembly on purpose: issued through the compiler's
@@ -359,11 +372,13 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_dma_kernel(
         } else {
 #pragma unroll
             for (int u = 0; u < A_LOADS; ++u)
-                dma16(a_src[u] + koff, lds_a0 + buf * (BM * BK) + (u * NW + wave) * 1024);
+                dma16(!MASK || kl * CPR + a_piece[u] < a_pieces ? a_src[u] + koff : zero_chunk,
+                      lds_a0 + buf * (BM * BK) + (u * NW + wave) * 1024);
         }
 #pragma unroll
         for (int u = 0; u < B_LOADS; ++u)
-            dma16(b_src[u] + koff, lds_b0 + buf * (BN * BK) + (u * NW + wave) * 1024);
+            dma16(!MASK || kl * CPR + b_piece[u] < b_pieces ? b_src[u] + koff : zero_chunk,
+                  lds_b0 + buf * (BN * BK) + (u * NW + wave) * 1024);
     };
 
     i32x16 acc[TM][TN];
@@ -596,20 +611,26 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_wholek_kernel(
     const int row0 = bm * BM, col0 = bn * BN;
 
     // piece b of a K-step: LDS rows 16b .. 16b+15; lane l fills row 16b + l/4, chunk slot l%4
+    // (a row's pitch may end inside the last K-step: pieces past it come from zero_chunk)
     for (int b = wave; b < BLOCKS; b += NW) {
         const int r = b * 16 + (lane >> 2), c = lane & 3;
-        const int8_t* src;
+        const int8_t* rowp;
+        int piece, pieces;                 // this lane's 16-byte piece of K-step 0; pieces in the pitch
         if (r < BM) {
             int gr = row0 + r;
             gr = gr < M ? gr : M - 1;      // rows past the edge re-read the last row; never stored
-            src = Xq + (int64_t)gr * ldx + swz<64>(r, c) * 16;
+            rowp = Xq + (int64_t)gr * ldx;
+            piece = swz<64>(r, c);
+            pieces = (int)(ldx / 16);
         } else {
             int gr = col0 + (r - BM);
             gr = gr < N ? gr : N - 1;
-            src = Wq + (int64_t)gr * ldw + swz<64>(r - BM, c) * 16;
+            rowp = Wq + (int64_t)gr * ldw;
+            piece = swz<64>(r - BM, c);
+            pieces = (int)(ldw / 16);
         }
-        for (int kt = 0; kt < ksteps; ++kt)
-            lds_dma16(src + (int64_t)kt * 64, lds0 + kt * STEP_BYTES + b * 1024);
+        for (int kt = 0; kt < ksteps; ++kt, piece += 4)
+            lds_dma16(piece < pieces ? rowp + piece * 16 : zero_chunk, lds0 + kt * STEP_BYTES + b * 1024);
     }
 
     i32x16 acc[TM][TN];
@@ -733,17 +754,19 @@ static hipError_t run_wholek(const int8_t* Xq, int64_t ldx, const int8_t* Wq, in
                          acc_out, ldacc, Y, ldy, (int)tiles_n, (unsigned)total, dup_off, rq);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NBUF, bool MASK = false>
 static hipError_t run_dma(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int64_t M,
                           int64_t N, int64_t Kpad, const float* scale_x, const float* scale_w,
                           int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy,
                           hipStream_t stream, const Requant& rq) {
+    // without MASK the kernel walks whole K-steps of every row
+    if (!MASK && (ldx < Kpad || ldw < Kpad)) return hipErrorInvalidValue;
     // the kernel clamps its K index to ksteps - 1: it must never be launched with no K-step
     if (Kpad < BK || Kpad % BK != 0) return hipErrorInvalidValue;
     const int64_t tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
     const int64_t total = tiles_m * tiles_n;
     if (total > 0x7FFFFFFF) return hipErrorInvalidValue;   // one workgroup per tile: grid.x
-    return launch_kernel(kTimeGemm, qgemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, BK, NBUF, false>,
+    return launch_kernel(kTimeGemm, qgemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, BK, NBUF, false, false, MASK>,
                          dim3((unsigned)total), dim3(WAVES_M * WAVES_N * 64), 0, stream, Xq, ldx, Wq, ldw, (int)M,
                          (int)N, (int)(Kpad / BK), scale_x, scale_w, acc_out, ldacc, Y, ldy,
                          (int)tiles_n, (unsigned)total, ConvGeom{}, rq, SplitK{});
@@ -906,6 +929,17 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
                         int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy,
                         hipStream_t stream, const Requant& rq) {
     int tile = tuning().gemm_tile;
+    // A pitch that is not a whole number of 64-byte K-steps, or shorter than the K extent rounded
+    // up to one (allowed up to 320 bytes of K), is something only the whole-K kernel walks.
+    const bool ring_ok = ldx % 64 == 0 && ldw % 64 == 0 && ldx >= Kpad && ldw >= Kpad;
+    if (!ring_ok) {
+        if (Kpad > 320) return hipErrorInvalidValue;
+        // (the 128 x 128 ring variant checks its requests against the pitch for this case: a very
+        // wide N is better served by the ring kernel's tile order, see below)
+        if (tile == 9 || (tile < 0 && N >= 1024))
+            return run_dma<128, 128, 4, 2, 64, 4, true>(OCS_GEMM_ARGS);
+        if (tile != 16 && tile != 17 && tile != 18 && tile != 19) tile = N <= 64 ? 17 : (N >= 512 ? 19 : 16);
+    }
     if (tile < 0) {
         // Measured on MI355X over the layer shapes of the paper's networks.  What a CU can draw is
         // set by the line requests its L1 can have outstanding times their latency, so requests

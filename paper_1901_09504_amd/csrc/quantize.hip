@@ -441,7 +441,7 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
     // Measured: it wins (up to 1.45x) once a quarter or more of a row's output dwords are
     // appended columns or padding (rows of 64 to 128 values); for wider rows the two are level.
     const int map = tuning().act_map;
-    const bool by_input = map < 0 ? 4 * TD >= D : map != 0;
+    const bool by_input = map < 0 ? (4 * TD >= D || Q <= 16) : map != 0;
     if (by_input && !stepwise && vec_ok && Q >= 1 && TD <= Q && 4 * TD <= kTailTable) {
         const int64_t total_in = M * Q;
         int64_t gin = 256 * 8;

@@ -40,7 +40,7 @@ def test_padded_cols_and_workspace():
     assert B.ocs_padded_cols(2358) == 2432
     assert B.ocs_conv_weight_cols(9, 272) == 2496 and B.ocs_conv_weight_cols(0, 16) == 0
     assert B.ocs_padded_channels(262) == 272 and B.ocs_padded_channels(4) == 16
-    assert B.ocs_padded_cols(64) == 64 and B.ocs_padded_cols(269) == 320 and B.ocs_padded_cols(321) == 384 and B.ocs_padded_cols(0) == 0
+    assert B.ocs_padded_cols(64) == 64 and B.ocs_padded_cols(269) == 272 and B.ocs_padded_cols(68) == 80 and B.ocs_padded_cols(320) == 320 and B.ocs_padded_cols(321) == 384 and B.ocs_padded_cols(0) == 0
     assert B.ocs_workspace_bytes(0, 10) == 0
     for rows, cols in [(1, 1), (64, 256), (12544, 2304), (6000, 3000), (3211264, 147), (802816, 64)]:
         wb = B.ocs_workspace_bytes(rows, cols)
@@ -94,6 +94,11 @@ def test_argument_errors_are_reported_without_a_device():
     assert L.ocs_split_act(A, 4, 4, 0, 4, A, None, 0, 8, A, 1.0, A, 64, A, A, ws, None) == -2
     assert L.ocs_qgemm(A, 64, A, 64, 4, 4, 100, 8, 8, A, A, None, 0, A, 4, None, 0, None) == -2  # ld < Kpad
     assert L.ocs_qgemm(A, 64, A, 64, 4, 8, 4, 8, 8, A, A, None, 0, A, 4, None, 0, None) == -2    # ldy < N
+    # a short K: the pitch only has to hold the row in 16-byte pieces; a long K: whole K-steps
+    assert L.ocs_qgemm(A, 64, A, 80, 4, 4, 68, 8, 8, A, A, None, 0, A, 4, None, 0, None) == -2   # 64 < 68
+    assert L.ocs_qgemm(A, 88, A, 80, 4, 4, 68, 8, 8, A, A, None, 0, A, 4, None, 0, None) == -3   # 88 % 16
+    assert L.ocs_qgemm(A, 400, A, 448, 4, 4, 390, 8, 8, A, A, None, 0, A, 4, None, 0, None) == -2  # 400 < 448
+    assert L.ocs_qgemm(A, 464, A, 448, 4, 4, 390, 8, 8, A, A, None, 0, A, 4, None, 0, None) == -3  # 464 % 64
     # alignment
     assert L.ocs_quantize(A, 4, 4, 4, 8, A, 1.0, A, 40, A, A, ws, None) == -3
     assert L.ocs_quantize(A, 4, 4, 4, 8, A, 1.0, A + 4, 64, A, A, ws, None) == -3
@@ -161,6 +166,10 @@ def test_split_k_entry_point_checks_shape_and_workspace_on_the_host():
     assert L.ocs_qgemm_split_k(*args(12544, 512, 4842, 2, None, 0)) == -7
     assert L.ocs_qgemm_split_k(*args(12544, 512, 4842, 2, A, 1000)) == -7
     assert L.ocs_qgemm_split_k(*args(12544, 512, 4842, 2, A + 8, 1 << 30)) == -3
+    # the split walks whole K-steps: the tight pitch ocs_qgemm takes for a short K is refused
+    short = lambda ld: (A, ld, A, ld, 256, 256, 269, 8, 8, A, A, None, 0, A, 256, 2, A, 1 << 30, None)
+    assert L.ocs_qgemm_split_k(*short(272)) == -2
+    assert L.ocs_qgemm_split_k(*short(336)) == -3
 
 
 def test_binding_raises_on_error():

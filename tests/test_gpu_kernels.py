@@ -407,11 +407,17 @@ GEMM_TILES = [6, 7, 9, 10, 11, 12, 14, 16, 17, 18, 19, 23, 24]     # every tile 
 
 
 @pytest.mark.parametrize("tile", [-1] + GEMM_TILES)
-@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (64, 256, 269), (130, 70, 64), (257, 129, 200), (700, 300, 1035),
-                                   (300, 520, 2358), (128, 128, 4842)])
-def test_qgemm(tile, M, N, K):
+@pytest.mark.parametrize("pitch", ["tight", "lines"])
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (64, 256, 269), (130, 70, 64), (257, 129, 200), (300, 200, 80),
+                                   (70, 1100, 135), (700, 300, 1035), (300, 520, 2358), (128, 128, 4842)])
+def test_qgemm(tile, pitch, M, N, K):
+    """Rows at the recommended pitch (for a short K that is the row rounded up to 16 bytes only: the next
+    row's codes follow at once, and what the row lacks up to its last K-step must count as zeros) and at
+    whole 128-byte lines (every ring variant then walks the short shapes too)."""
     rng = np.random.default_rng(M + N + K)
-    ld = B.ocs_padded_cols(K)
+    ld = B.ocs_padded_cols(K) if pitch == "tight" else -(-K // 128) * 128
+    if pitch == "lines" and ld == B.ocs_padded_cols(K):
+        pytest.skip("same pitch as the tight case")
     Xq = np.zeros((M, ld), dtype=np.int8)
     Wq = np.zeros((N, ld), dtype=np.int8)
     Xq[:, :K] = rng.integers(-127, 128, (M, K))
