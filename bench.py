@@ -74,7 +74,7 @@ class Net:
                                         max_rows=l.M))
         self.thr = torch.tensor([STATIC_T], dtype=torch.float32, device="cuda")
 
-    def step(self, B=None, ev=None, dynamic=False, weights=True, side=None):
+    def step(self, B=None, ev=None, dynamic=False, weights=True, side=None, fused=None):
         """One pass.  ev: per-layer event lists [x2 a, x2 b, gemm a, gemm b, absmax a, absmax b]
         that the launches stamp themselves (B = the binding).  side: a second stream for the weight
         path, which depends on nothing the activation path produces: every layer's weight
@@ -94,6 +94,11 @@ class Net:
                 L.prepare_weights(self.W[i])
             elif weights:
                 torch.cuda.current_stream().wait_event(self.wev[i])
+            if fused is not None and not dynamic and fused[i]:
+                if ev is not None:
+                    B.ocs_time_next(B.TIME_GEMM, ev[i][2], ev[i][3])
+                L.forward_fused(self.X[i], thr)
+                continue
             if ev is not None:
                 if dynamic:
                     B.ocs_time_next(B.TIME_ABSMAX, ev[i][4], ev[i][5])
@@ -104,7 +109,7 @@ class Net:
             L.qgemm(l.M)
 
 
-def stamped_steps(torch, B, net, n, dynamic=False, side=None):
+def stamped_steps(torch, B, net, n, dynamic=False, side=None, fused=None):
     """n passes whose split+quantize, GEMM (and max|X|) launches carry their own events.
     Returns arrays [n, layers] of kernel microseconds."""
     nl = len(net.layers)
@@ -117,10 +122,11 @@ def stamped_steps(torch, B, net, n, dynamic=False, side=None):
     gm = np.zeros((n, nl))
     x1 = np.zeros((n, nl))
     for s in range(n):
-        net.step(B, ev, dynamic=dynamic, side=side)
+        net.step(B, ev, dynamic=dynamic, side=side, fused=fused)
         torch.cuda.synchronize()
         for i in range(nl):
-            x2[s, i] = ev[i][0].elapsed_time(ev[i][1]) * 1e3
+            if fused is None or not fused[i]:     # (a fused layer has no split+quantize launch)
+                x2[s, i] = ev[i][0].elapsed_time(ev[i][1]) * 1e3
             gm[s, i] = ev[i][2].elapsed_time(ev[i][3]) * 1e3
             if dynamic:
                 x1[s, i] = ev[i][4].elapsed_time(ev[i][5]) * 1e3
@@ -462,7 +468,9 @@ def main():
     ap.add_argument("--single-stream", action="store_true",
                     help="queue the weight path in order on the activation path's stream instead of on a second one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--extras", default="steps,chained,ceilings,config2,splitk",
+    ap.add_argument("--tune", default="", help="key=value[,key=value]: launch-shape overrides (ocs_tune) for experiments")
+    ap.add_argument("--fused-layers", default="", help="with the `fused` extra: only these layers take the one-launch path")
+    ap.add_argument("--extras", default="steps,fused,chained,ceilings,config2,splitk",
                     help="secondary measurements to run: steps (per-batch grid, single stream, off-line weights, "
                          "weight path by clip), chained, ceilings, config2, splitk")
     ap.add_argument("--only", choices=["chained", "ceilings", "config2", "splitk"], default=None,
@@ -498,6 +506,8 @@ def main():
         return
     net = Net(torch, wl, ExpandedLayer, layers, args.clip)
     torch.cuda.synchronize()
+    for kv in filter(None, args.tune.split(",")):
+        B.ocs_tune(kv.split("=")[0], int(kv.split("=")[1]))
 
     # the weight path depends on nothing the activation path produces: it is queued on a second
     # stream (default priority), and each layer's activation pass waits for the event behind its
@@ -567,6 +577,24 @@ def main():
         "layers": rows,
     }
     extras = set() if args.no_extras else set(args.extras.split(","))
+    if "fused" in extras:
+        # split+quantize and GEMM as one launch wherever that entry point serves the layer
+        fmap = [L.fused_pays(x) for L, x in zip(net.L, net.X)]
+        if args.fused_layers:
+            names = set(args.fused_layers.split(","))
+            fmap = [f and l.name in names for f, l in zip(fmap, layers)]
+        f_ms = timed(10, side=side, fused=fmap)
+        x2f, gmf, _ = stamped_steps(torch, B, net, 10, side=side, fused=fmap)
+        frows = []
+        for i, (l, L) in enumerate(zip(layers, net.L)):
+            if fmap[i]:
+                us = float(np.median(gmf[:, i]))
+                byt = 4.0 * l.M * l.K + 1.0 * l.N * L.Ke + 4.0 * l.M * l.N
+                frows.append({"layer": l.name, "M": l.M, "K": l.K, "N": l.N, "fused_us": round(us, 2),
+                              "two_launch_us": round(rows[i]["split_quant_us"] + rows[i]["gemm_us"], 2),
+                              "GBps": round(byt / us / 1e3, 1), "frac_hbm": round(byt / us / 1e3 / HBM_PEAK_GBS, 4)})
+        out["fused_split_gemm"] = {"ms_per_step": f_ms, "tops_whole_step": ops / f_ms / 1e9, "steps": 10,
+                                   "layers_fused": int(sum(fmap)), "layers": frows}
     if "steps" in extras:
         # the pass with a per-batch activation grid: X1 (max|X|) in front of every split+quantize
         dyn_ms = timed(5, dynamic=True, side=side)

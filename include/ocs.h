@@ -297,6 +297,31 @@ int ocs_qgemm(const int8_t *Xq, int64_t ldx, const int8_t *Wq, int64_t ldw, int6
               size_t ws_bytes, void *stream);
 
 /*
+ * ocs_split_act (static grid, copies un-scaled: the activation side of Eq. 3) and ocs_qgemm as ONE
+ * launch: the GEMM's loader reads the fp32 rows of X [M, C*g] itself, puts them on the grid of
+ * `threshold` (Eq. 1, the arithmetic of ocs_split_act: the codes are the same), and takes the
+ * copies of the split channels from the codes it has just produced, so the code tensor Xq never
+ * reaches memory: 4 bytes are read per element of X instead of 4 read + (1 + r) written + (1 + r)
+ * read again.  acc_out and Y are bit for bit those of the two calls.
+ *   chan_src [C + num_splits]: as written by the weight side; only the appended entries are used.
+ *   threshold: device float T > 0 (a profiled grid, Sec. 5).  scale_x_out: optional device
+ *        float[2], receives {T, T / qmax} as ocs_split_act's scale_out would; must not be `threshold`.
+ *   Wq [N, ldw], scale_w: the weight codes and grid of the expanded layer, ldw >= (C+num_splits)*g
+ *        rounded up to OCS_CALIGN and a multiple of it, pad columns zero.
+ * Serves the shapes ocs_split_act_qgemm_fits() accepts (host-only; 1 = yes): C*g a multiple of 64
+ * and at most 8192, at most 2048 appended columns num_splits*g, N <= 256 (one tile of output
+ * columns, so that X is read once), ldx a multiple of 4; X 16-byte aligned.  Other shapes:
+ * OCS_E_SHAPE, and the two calls do the same work.
+ */
+int ocs_split_act_qgemm_fits(int64_t M, int C, int g, int num_splits, int64_t N, int64_t ldx);
+/* 1 where it fits and was measured ahead of the two calls (rows of X of 256 values and more). */
+int ocs_split_act_qgemm_pays(int64_t M, int C, int g, int num_splits, int64_t N, int64_t ldx);
+int ocs_split_act_qgemm(const float *X, int64_t M, int C, int g, int64_t ldx, const int32_t *chan_src,
+                        int num_splits, int bits_x, const float *threshold, const int8_t *Wq, int64_t ldw,
+                        int64_t N, int bits_w, const float *scale_w, float *scale_x_out, int32_t *acc_out,
+                        int64_t ldacc, float *Y, int64_t ldy, void *stream);
+
+/*
  * ocs_qgemm with the K extent of every output tile shared between `parts` workgroups (2 .. 16, at
  * most one per 64-byte K-step): for shapes with far fewer output tiles than the chip has compute
  * units and a long K.  Each workgroup leaves the int32 partial sums of its 256 x 256 tile in the

@@ -100,6 +100,13 @@ def lib():
     L.ocs_qgemm_split_k.restype = _i32
     L.ocs_qgemm_split_k.argtypes = [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _i32, _i32, _vp, _vp, _vp, _i64, _vp,
                                     _i64, _i32, _vp, _sz, _vp]
+    L.ocs_split_act_qgemm_fits.restype = _i32
+    L.ocs_split_act_qgemm_fits.argtypes = [_i64, _i32, _i32, _i32, _i64, _i64]
+    L.ocs_split_act_qgemm_pays.restype = _i32
+    L.ocs_split_act_qgemm_pays.argtypes = [_i64, _i32, _i32, _i32, _i64, _i64]
+    L.ocs_split_act_qgemm.restype = _i32
+    L.ocs_split_act_qgemm.argtypes = [_vp, _i64, _i32, _i32, _i64, _vp, _i32, _i32, _vp, _vp, _i64, _i64, _i32, _vp,
+                                      _vp, _vp, _i64, _vp, _i64, _vp]
     L.ocs_time_next.restype = _i32
     L.ocs_time_next.argtypes = [_i32, _vp, _vp]
     L.ocs_calib_copy.restype = _i32
@@ -328,6 +335,21 @@ def ocs_qgemm(Xq, ldx, Wq, ldw, M, N, Kexp, bits_x, bits_w, scale_x, scale_w, ac
     _check(lib().ocs_qgemm(_ptr(Xq), ldx, _ptr(Wq), ldw, M, N, Kexp, bits_x, bits_w, _ptr(scale_x),
                            _ptr(scale_w), _ptr(acc_out), ldacc, _ptr(Y), ldy, w, wb,
                            _stream(stream)), "ocs_qgemm")
+
+
+def ocs_split_act_qgemm_fits(M, C, g, num_splits, N, ldx):
+    return bool(lib().ocs_split_act_qgemm_fits(int(M), int(C), int(g), int(num_splits), int(N), int(ldx)))
+
+
+def ocs_split_act_qgemm_pays(M, C, g, num_splits, N, ldx):
+    return bool(lib().ocs_split_act_qgemm_pays(int(M), int(C), int(g), int(num_splits), int(N), int(ldx)))
+
+
+def ocs_split_act_qgemm(X, M, C, g, ldx, chan_src, num_splits, bits_x, threshold, Wq, ldw, N, bits_w, scale_w,
+                        scale_x_out, acc_out, ldacc, Y, ldy, stream=None):
+    _check(lib().ocs_split_act_qgemm(_ptr(X), M, C, g, ldx, _ptr(chan_src), num_splits, bits_x, _ptr(threshold),
+                                     _ptr(Wq), ldw, N, bits_w, _ptr(scale_w), _ptr(scale_x_out), _ptr(acc_out),
+                                     ldacc, _ptr(Y), ldy, _stream(stream)), "ocs_split_act_qgemm")
 
 
 def ocs_qgemm_split_k(Xq, ldx, Wq, ldw, M, N, Kexp, bits_x, bits_w, scale_x, scale_w, acc_out, ldacc, Y, ldy,

@@ -500,6 +500,40 @@ int ocs_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t ldw, int6
     return OCS_OK;
 }
 
+int ocs_split_act_qgemm_fits(int64_t M, int C, int g, int num_splits, int64_t N, int64_t ldx) {
+    if (M <= 0 || C <= 0 || g <= 0 || num_splits < 0 || N <= 0) return 0;
+    if ((int64_t)C * g > (int64_t)1 << 30 || (int64_t)C + num_splits > OCS_MAX_EXPANDED_CHANNELS) return 0;
+    return split_act_qgemm_fits(M, C, g, num_splits, N, ldx) ? 1 : 0;
+}
+
+int ocs_split_act_qgemm_pays(int64_t M, int C, int g, int num_splits, int64_t N, int64_t ldx) {
+    if (!ocs_split_act_qgemm_fits(M, C, g, num_splits, N, ldx)) return 0;
+    return split_act_qgemm_pays(M, C, g, num_splits, N, ldx) ? 1 : 0;
+}
+
+int ocs_split_act_qgemm(const float* X, int64_t M, int C, int g, int64_t ldx, const int32_t* chan_src,
+                        int num_splits, int bits_x, const float* threshold, const int8_t* Wq, int64_t ldw,
+                        int64_t N, int bits_w, const float* scale_w, float* scale_x_out, int32_t* acc_out,
+                        int64_t ldacc, float* Y, int64_t ldy, void* stream) {
+    if (!X || !threshold || !Wq || !scale_w || !Y || (num_splits > 0 && !chan_src)) return OCS_E_NULL;
+    int rc = check_layer(M, C, g, ldx, num_splits);
+    if (rc) return rc;
+    if (N <= 0 || N > (int64_t)1 << 30 || ldy < N || (acc_out && ldacc < N)) return OCS_E_SHAPE;
+    const int64_t Kexp = (int64_t)(C + num_splits) * g;
+    if (ldw < round_up(Kexp, OCS_CALIGN)) return OCS_E_SHAPE;
+    if (ldw % OCS_CALIGN != 0 || !aligned(Wq, 16) || !aligned(X, 16)) return OCS_E_ALIGN;
+    if (!bits_ok(bits_x) || !bits_ok(bits_w)) return OCS_E_BITS;
+    const int64_t qx = (1 << (bits_x - 1)) - 1, qw = (1 << (bits_w - 1)) - 1;
+    if (Kexp * qx * qw >= (int64_t)1 << 31) return OCS_E_OVERFLOW;
+    if (scale_x_out == threshold) return OCS_E_MODE;   // the kernel reads one while writing the other
+    if (!split_act_qgemm_fits(M, C, g, num_splits, N, ldx)) return OCS_E_SHAPE;
+    hipError_t e = launch_split_act_qgemm(X, ldx, M, C, g, num_splits, chan_src, threshold, qmax_of(bits_x), Wq,
+                                          ldw, N, Kexp, scale_w, scale_x_out, acc_out, ldacc, Y, ldy,
+                                          static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
 size_t ocs_qgemm_split_k_workspace_bytes(int64_t M, int64_t N, int64_t Kexp, int parts) {
     if (M <= 0 || N <= 0 || Kexp <= 0) return 0;
     return qgemm_split_workspace_bytes(M, N, round_up(Kexp, OCS_KALIGN), parts);

@@ -158,6 +158,17 @@ hipError_t launch_qgemm_split(const int8_t* Xq, int64_t ldx, const int8_t* Wq, i
                               int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy, hipStream_t stream,
                               int parts, void* partials);
 
+// Split + quantize + GEMM in one launch (static grid thr, copies un-scaled as on the activation side
+// of Eq. 3): Y = (codes of the expanded X) x Wq^T scaled by (T/qmax) * scale_w[1], without the code
+// tensor ever reaching memory.  ..._fits: the shapes it serves (C*g a multiple of 64 up to 8192,
+// at most 2048 appended columns, N <= 256, 16-byte rows of X).
+bool split_act_qgemm_fits(int64_t M, int C, int g, int s, int64_t N, int64_t ldx);
+bool split_act_qgemm_pays(int64_t M, int C, int g, int s, int64_t N, int64_t ldx);
+hipError_t launch_split_act_qgemm(const float* X, int64_t ldx, int64_t M, int C, int g, int s,
+                                  const int32_t* chan_src, const float* thr, float qmax, const int8_t* Wq,
+                                  int64_t ldw, int64_t N, int64_t Kexp, const float* scale_w, float* scale_x_out,
+                                  int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy, hipStream_t stream);
+
 // Convolution with the lowering folded into the GEMM's A-operand loader: Aq [B, H, W, ldc]
 // codes of the un-lowered activation, Wt [N + 1, kh*kw*ldc] tap-major weight codes whose last
 // row is zeros (launch_tap_major builds it from channel-major codes).
@@ -223,6 +234,32 @@ __device__ __forceinline__ unsigned wave_umax32(unsigned v) {
     const unsigned r3 = (unsigned)__builtin_amdgcn_readlane((int)v, 48);
     const unsigned a = r0 > r1 ? r0 : r1, b = r2 > r3 ? r2 : r3;
     return a > b ? a : b;
+}
+
+// ---- Eq. 1 on the device: shared by the streaming pass and by the GEMM that quantizes its own A operand ----
+
+// One value onto the grid: one fp32 multiply by qmax/T, saturate, round half to even.
+// Saturating before rounding gives the same code as rounding first because qmax is an
+// integer.  Adding 1.5 * 2^23 rounds |p| <= 127 to an integer under the default rounding mode
+// (the sum's ulp is 1) and leaves that integer, in two's complement, in the low mantissa
+// bits: the low byte of the sum's bit pattern is the int8 code.
+__device__ __forceinline__ unsigned code_bits(float v, float inv_step, float qmax) {
+    float p = v * inv_step;
+    p = __builtin_amdgcn_fmed3f(p, -qmax, qmax);
+    return __float_as_uint(p + 12582912.0f);
+}
+
+// low bytes of four words -> one dword (a in byte 0)
+__device__ __forceinline__ unsigned pack4(unsigned a, unsigned b, unsigned c, unsigned d) {
+    unsigned lo = __builtin_amdgcn_perm(b, a, 0x0c0c0400u);  // {a.b0, b.b0, 0, 0}
+    unsigned hi = __builtin_amdgcn_perm(d, c, 0x04000c0cu);  // {0, 0, c.b0, d.b0}
+    return lo | hi;
+}
+
+// qmax / T as one correctly rounded division, kept finite so that 0 * inv_step stays 0.
+__device__ __forceinline__ float inv_step_of(float T, float qmax) {
+    if (!(T > 0.0f)) return 0.0f;
+    return __builtin_fminf(__fdiv_rn(qmax, T), 3.402823466e+38f);
 }
 
 // Launch-shape overrides (benchmarking only); < 0 means "use the default".

@@ -24,6 +24,9 @@ __device__ __forceinline__ int swz(int row, int chunk) {
     return chunk ^ (((row >> 1) & 7) ^ ((row & 1) << 2));
 }
 
+// index clamped into [0, n): index arrays and edge rows never send a load out of bounds
+__device__ __forceinline__ int col_clamp(int v, int n) { return v < 0 ? 0 : (v >= n ? n - 1 : v); }
+
 // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Renumber them so
 // that consecutive tile ids (which share an X row panel) run on the same XCD.
 __device__ __forceinline__ unsigned xcd_remap(unsigned w, unsigned total) {
@@ -704,6 +707,293 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_wholek_kernel(
 constexpr int64_t kWholeKMaxLds = 160 * 1024;  // LDS of one CU
 constexpr int kMaxDevices = 64;
 
+// ---------------------------------------------------------------------------------------------
+// Split + quantize + GEMM in one launch: the A operand is the fp32 activation matrix X [M, C*g]
+// itself.  A workgroup takes 128 rows of X and all N <= 256 output columns, walks K in steps of
+// 64 source columns, and per step turns its 128 x 64 floats (16-byte loads, two steps ahead, held
+// in registers) into codes on the static grid (Eq. 1, the arithmetic of the streaming pass) and
+// writes them into LDS in the layout the matrix cores read; the weight codes of the step come
+// through registers as well.  The expanded layer's appended channels (the activation side of
+// Eq. 3: un-scaled copies) cost no memory traffic at all: the copy of a column is the byte that
+// was just written into LDS, so after each step the copies whose sources lie in it are moved,
+// byte by byte, into a second LDS area laid out as the K-steps that follow the C*g columns, and
+// those steps are multiplied last.  The code tensor Xq never exists in memory: 4 bytes read per
+// element of X and 4 written per output, instead of 4 + 1 and 1 + 4 for the two launches.
+//
+// Per-workgroup set-up: the appended columns e = 0 .. s*g-1 (expanded column C*g + e, source
+// column chan_src[C + e/g]*g + e%g) are bucketed by the K-step of their source (counts, prefix,
+// fill: three short LDS passes).
+// ---------------------------------------------------------------------------------------------
+constexpr int kFusedMaxBM = 128;
+constexpr int kFusedMaxTail = 2048;    // appended columns s*g
+constexpr int kFusedMaxK = 8192;       // unexpanded columns C*g
+
+struct FusedLds {
+    int a_off, b_off, tail_off, first_off, cursor_off, ent_off, total;
+};
+static FusedLds fused_lds(int BM, int BN, int ksteps_main, int tail_steps, int T) {
+    FusedLds l;
+    l.a_off = 0;
+    l.b_off = 2 * BM * 64;
+    l.tail_off = l.b_off + 2 * BN * 64;
+    l.first_off = l.tail_off + tail_steps * BM * 64;
+    l.cursor_off = l.first_off + (ksteps_main + 1) * 4;
+    l.ent_off = l.cursor_off + ksteps_main * 4;
+    l.total = l.ent_off + (T > 0 ? T : 1) * 4;
+    return l;
+}
+
+template <int BN, int BM>
+__global__ __launch_bounds__(BM * 4) void split_act_qgemm_kernel(
+    const float* __restrict__ X, int64_t ldx, int M, int C, int g, int s,
+    const int32_t* __restrict__ chan_src, const float* __restrict__ thr, float qmax,
+    const int8_t* __restrict__ Wq, int64_t ldw, int N, int ksteps_main, int ksteps_all,
+    const float* __restrict__ scale_w, float* __restrict__ scale_x_out, int32_t* __restrict__ acc_out,
+    int64_t ldacc, float* __restrict__ Y, int64_t ldy, FusedLds L) {
+    constexpr int NT = BM * 4, NW = NT / 64;   // one thread per (row, 16-column piece) of a step
+    constexpr int WAVES_N = 2, WN = BN / WAVES_N, TN = WN / 32;
+    constexpr int B_SLOTS = BN * 4, B_PER = (B_SLOTS + NT - 1) / NT;
+    static_assert(BN == 64 || BN == 128 || BN == 256, "64, 128 or 256 output columns");
+    static_assert(NW * 8 * WN * 4 <= 2 * BM * 64 + 2 * BN * 64, "the epilogue's staging area is the operand buffers");
+
+    extern __shared__ __align__(1024) int8_t flds[];
+    int8_t* a_buf = flds + L.a_off;
+    int8_t* b_buf = flds + L.b_off;
+    int8_t* tail = flds + L.tail_off;
+    int* first = reinterpret_cast<int*>(flds + L.first_off);     // [ksteps_main + 1]
+    int* cursor = reinterpret_cast<int*>(flds + L.cursor_off);   // [ksteps_main]
+    int* ent = reinterpret_cast<int*>(flds + L.ent_off);         // [T]: (e << 6) | source column inside its step
+
+    const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int row0 = (int)blockIdx.x * BM;
+    const int T = s * g, tail_steps = ksteps_all - ksteps_main;
+
+    // A: load i of a lane is float4 number (lane & 15) of the step's 64 floats of row
+    // 16*wave + 4*i + (lane >> 4): each load instruction of a wave covers four rows' whole 256 bytes
+    const float* a_src[4];
+    int a_dst[4];       // byte offset of the resulting code dword inside an A buffer
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = 16 * wave + 4 * i + (lane >> 4), f4 = lane & 15;
+        int gr = row0 + r;
+        gr = gr < M ? gr : M - 1;          // rows past the edge re-read the last row; never stored
+        a_src[i] = X + (int64_t)gr * ldx + f4 * 4;
+        a_dst[i] = r * 64 + swz<64>(r, f4 >> 2) * 16 + (f4 & 3) * 4;
+    }
+    // B: 16-byte piece (slot & 3) of the step of weight row (slot >> 2)
+    const int8_t* b_src[B_PER];
+    int b_dst[B_PER], b_piece[B_PER];
+    bool b_on[B_PER];
+    const int b_pieces = (int)(ldw / 16);
+#pragma unroll
+    for (int u = 0; u < B_PER; ++u) {
+        const int slot = u * NT + tid, n = slot >> 2, c = slot & 3;
+        b_on[u] = slot < B_SLOTS;
+        const int gn = col_clamp(n, N);
+        b_src[u] = Wq + (int64_t)gn * ldw;
+        b_piece[u] = c;
+        b_dst[u] = n * 64 + swz<64>(n, c) * 16;
+    }
+
+    f32x4 av[3][4];
+    i32x4 bv[3][B_PER];
+    auto load_step = [&](int kt, f32x4 (&a)[4], i32x4 (&b)[B_PER]) {
+        if (kt < ksteps_main) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const f32x4*>(a_src[i] + (int64_t)kt * 64);
+        }
+        if (kt < ksteps_all) {
+#pragma unroll
+            for (int u = 0; u < B_PER; ++u) {
+                const int piece = kt * 4 + b_piece[u];
+                i32x4 z = {0, 0, 0, 0};
+                // a pitch may end inside the last K-step: what the row lacks counts as zero codes
+                b[u] = (b_on[u] && piece < b_pieces) ? *reinterpret_cast<const i32x4*>(b_src[u] + piece * 16) : z;
+            }
+        }
+    };
+    load_step(0, av[0], bv[0]);
+    load_step(1, av[1], bv[1]);
+
+    // set-up behind the first requests: clear the appended steps, bucket the appended columns
+    {
+        i32x4 z = {0, 0, 0, 0};
+        for (int o = tid; o < tail_steps * (BM * 64 / 16); o += NT) reinterpret_cast<i32x4*>(tail)[o] = z;
+        for (int k = tid; k <= ksteps_main; k += NT) first[k] = 0;
+        __syncthreads();
+        for (int e = tid; e < T; e += NT) {
+            const int j = e / g, t = e - j * g;
+            const int col = col_clamp(chan_src[C + j], C) * g + t;
+            atomicAdd(&first[(col >> 6) + 1], 1);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            int run = 0;
+            for (int k = 0; k < ksteps_main; ++k) {
+                run += first[k + 1];
+                first[k + 1] = run;
+            }
+        }
+        __syncthreads();
+        for (int k = tid; k < ksteps_main; k += NT) cursor[k] = first[k];
+        __syncthreads();
+        for (int e = tid; e < T; e += NT) {
+            const int j = e / g, t = e - j * g;
+            const int col = col_clamp(chan_src[C + j], C) * g + t;
+            const int pos = atomicAdd(&cursor[col >> 6], 1);
+            ent[pos] = (e << 6) | (col & 63);
+        }
+        // (the first step's barrier completes the table before anyone reads it)
+    }
+
+    const float Tx = *thr;
+    const float inv = inv_step_of(Tx, qmax);
+    if (scale_x_out != nullptr && blockIdx.x == 0 && tid == 0) {
+        scale_x_out[0] = Tx;
+        scale_x_out[1] = Tx / qmax;
+    }
+
+    i32x16 acc[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0;
+    const int frag_row = lane & 31, frag_half = lane >> 5;
+
+    auto process = [&](int kt, const f32x4 (&a)[4], const i32x4 (&b)[B_PER]) {
+        const int buf = kt & 1;
+        int8_t* ab = a_buf + buf * (BM * 64);
+        int8_t* bb = b_buf + buf * (BN * 64);
+        const bool main_step = kt < ksteps_main;
+        if (main_step) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                *reinterpret_cast<unsigned*>(ab + a_dst[i]) =
+                    pack4(code_bits(a[i][0], inv, qmax), code_bits(a[i][1], inv, qmax),
+                          code_bits(a[i][2], inv, qmax), code_bits(a[i][3], inv, qmax));
+        }
+#pragma unroll
+        for (int u = 0; u < B_PER; ++u)
+            if (b_on[u]) *reinterpret_cast<i32x4*>(bb + b_dst[u]) = b[u];
+        __syncthreads();
+        const int8_t* am = ab;
+        if (main_step) {
+            // the copies whose sources this step holds: one byte per (copy, row)
+            const int e0 = first[kt], n = first[kt + 1] - e0;
+            for (int idx = tid; idx < n * BM; idx += NT) {
+                const int q = idx / BM, r = idx - q * BM;
+                const int en = ent[e0 + q], e = en >> 6, c = en & 63;
+                const int8_t code = ab[r * 64 + swz<64>(r, c >> 4) * 16 + (c & 15)];
+                const int te = e & 63;
+                tail[(e >> 6) * (BM * 64) + r * 64 + swz<64>(r, te >> 4) * 16 + (te & 15)] = code;
+            }
+        } else {
+            am = tail + (kt - ksteps_main) * (BM * 64);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const int ra = wm * 32 + frag_row;
+            const i32x4 fa = *reinterpret_cast<const i32x4*>(&am[ra * 64 + swz<64>(ra, ks * 2 + frag_half) * 16]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int rb = wn * WN + j * 32 + frag_row;
+                const i32x4 fb = *reinterpret_cast<const i32x4*>(&bb[rb * 64 + swz<64>(rb, ks * 2 + frag_half) * 16]);
+                acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, fb, acc[j], 0, 0, 0);
+            }
+        }
+    };
+
+    // three register sets in rotation: while set p is processed, sets p+1 and p+2 are on their way
+    for (int kt0 = 0; kt0 < ksteps_all; kt0 += 3) {
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            const int kt = kt0 + p;
+            if (kt < ksteps_all) {
+                load_step(kt + 2, av[(p + 2) % 3], bv[(p + 2) % 3]);
+                process(kt, av[p], bv[p]);
+            }
+        }
+    }
+    __syncthreads();   // the operand buffers are dead: they become the staging area
+
+    int32_t* stage = reinterpret_cast<int32_t*>(flds + wave * (8 * WN * 4));
+    const float scale = (Tx / qmax) * scale_w[1];
+    const bool vec_y = (reinterpret_cast<uintptr_t>(Y) % 16 == 0) && (ldy % 4 == 0);
+    const bool vec_a = acc_out != nullptr && (reinterpret_cast<uintptr_t>(acc_out) % 16 == 0) && (ldacc % 4 == 0);
+    const Requant none{};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                stage[((lane >> 5) * 4 + e) * WN + j * 32 + (lane & 31)] = acc[j][q * 4 + e];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        emit_staged_rows<8, WN>(stage, lane, row0 + wm * 32 + q * 8, wn * WN, wn * WN, M, N, scale, Y, ldy,
+                                acc_out, ldacc, vec_y, vec_a, none, 0.0f, nullptr, 0, false);
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// Where the one launch is ahead of the two (measured on the same shapes): from 256 columns of X
+// on.  With 64 the pass over X is short either way and the output dominates.
+bool split_act_qgemm_pays(int64_t M, int C, int g, int s, int64_t N, int64_t ldx) {
+    return split_act_qgemm_fits(M, C, g, s, N, ldx) && (int64_t)C * g >= 256;
+}
+
+bool split_act_qgemm_fits(int64_t M, int C, int g, int s, int64_t N, int64_t ldx) {
+    const int64_t K = (int64_t)C * g, T = (int64_t)s * g;
+    return M >= 1 && M <= 0x7FFFFFFF - kFusedMaxBM && K >= 64 && K % 64 == 0 && K <= kFusedMaxK && T <= kFusedMaxTail &&
+           N >= 1 && N <= 256 && ldx % 4 == 0;
+}
+
+template <int BN, int BM>
+static hipError_t run_split_act_qgemm(const float* X, int64_t ldx, int64_t M, int C, int g, int s,
+                                      const int32_t* chan_src, const float* thr, float qmax, const int8_t* Wq,
+                                      int64_t ldw, int64_t N, int64_t Kexp, const float* scale_w,
+                                      float* scale_x_out, int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy,
+                                      hipStream_t stream) {
+    const int ksteps_main = (int)((int64_t)C * g / 64), ksteps_all = (int)ceil_div(Kexp, 64);
+    const FusedLds L = fused_lds(BM, BN, ksteps_main, ksteps_all - ksteps_main, s * g);
+    if (L.total > kWholeKMaxLds) return hipErrorInvalidValue;
+    static std::atomic<bool> opted_in[kMaxDevices];
+    if (L.total > 65536) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+        if (!opted_in[dev].load(std::memory_order_acquire)) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&split_act_qgemm_kernel<BN, BM>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWholeKMaxLds);
+            if (e != hipSuccess) return e;
+            opted_in[dev].store(true, std::memory_order_release);
+        }
+    }
+    return launch_kernel(kTimeGemm, split_act_qgemm_kernel<BN, BM>, dim3((unsigned)ceil_div(M, BM)),
+                         dim3(BM * 4), (unsigned)L.total, stream, X, ldx, (int)M, C, g, s, chan_src, thr, qmax,
+                         Wq, ldw, (int)N, ksteps_main, ksteps_all, scale_w, scale_x_out, acc_out, ldacc, Y, ldy, L);
+}
+
+hipError_t launch_split_act_qgemm(const float* X, int64_t ldx, int64_t M, int C, int g, int s,
+                                  const int32_t* chan_src, const float* thr, float qmax, const int8_t* Wq,
+                                  int64_t ldw, int64_t N, int64_t Kexp, const float* scale_w, float* scale_x_out,
+                                  int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy, hipStream_t stream) {
+    if (!split_act_qgemm_fits(M, C, g, s, N, ldx)) return hipErrorInvalidValue;
+#define OCS_FUSED_ARGS X, ldx, M, C, g, s, chan_src, thr, qmax, Wq, ldw, N, Kexp, scale_w, scale_x_out, acc_out, ldacc, Y, ldy, stream
+    // Measured on the paper's layer shapes at batch 256: up to 128 output columns, workgroups of 64
+    // rows (two or more per compute unit, each with its own barriers) are 10-20 % ahead of 128-row
+    // ones; with 256 columns the weight codes a workgroup pulls per step weigh as much as its 64 rows
+    // of X, and 128 rows are level or ahead.
+    if (N <= 64) return run_split_act_qgemm<64, 64>(OCS_FUSED_ARGS);
+    if (N <= 128) return run_split_act_qgemm<128, 64>(OCS_FUSED_ARGS);
+    return run_split_act_qgemm<256, 128>(OCS_FUSED_ARGS);
+#undef OCS_FUSED_ARGS
+}
+
+
 // Dynamic LDS of a whole-K launch: operands (or the epilogue's staging area, if larger) and,
 // when the output goes to the next layer as codes with copies, the table of those copies
 // behind them (*dup_off = its byte offset, 0 = none).
@@ -980,6 +1270,7 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
                              : run_dma<256, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);
         case 12: return run_dma<256, 256, 2, 4, 64, 4>(OCS_GEMM_ARGS);   // 8 waves
         case 14: return run_dma<256, 256, 4, 4, 64, 4>(OCS_GEMM_ARGS);   // 16 waves
+        case 25: return run_dma<256, 256, 2, 2, 64, 4>(OCS_GEMM_ARGS);   // 4 waves of 128 x 128
         // whole-K variants; a K extent too long for them falls back to a ring variant
 #define OCS_WHOLEK(BM_, BN_, WM_, WN_, FALLBACK)                                                   \
     (wholek_lds_bytes<BM_, BN_, WM_, WN_>(Kpad, rq) <= kWholeKMaxLds                                   \

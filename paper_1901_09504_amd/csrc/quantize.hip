@@ -13,30 +13,6 @@
 
 namespace ocs {
 
-// One value onto the grid: one fp32 multiply by qmax/T, saturate, round half to even.
-// Saturating before rounding gives the same code as rounding first because qmax is an
-// integer.  Adding 1.5 * 2^23 rounds |p| <= 127 to an integer under the default rounding mode
-// (the sum's ulp is 1) and leaves that integer, in two's complement, in the low mantissa
-// bits: the low byte of the sum's bit pattern is the int8 code.
-__device__ __forceinline__ unsigned code_bits(float v, float inv_step, float qmax) {
-    float p = v * inv_step;
-    p = __builtin_amdgcn_fmed3f(p, -qmax, qmax);
-    return __float_as_uint(p + 12582912.0f);
-}
-
-// low bytes of four words -> one dword (a in byte 0)
-__device__ __forceinline__ unsigned pack4(unsigned a, unsigned b, unsigned c, unsigned d) {
-    unsigned lo = __builtin_amdgcn_perm(b, a, 0x0c0c0400u);  // {a.b0, b.b0, 0, 0}
-    unsigned hi = __builtin_amdgcn_perm(d, c, 0x04000c0cu);  // {0, 0, c.b0, d.b0}
-    return lo | hi;
-}
-
-// qmax / T as one correctly rounded division, kept finite so that 0 * inv_step stays 0.
-__device__ __forceinline__ float inv_step_of(float T, float qmax) {
-    if (!(T > 0.0f)) return 0.0f;
-    return __builtin_fminf(__fdiv_rn(qmax, T), 3.402823466e+38f);
-}
-
 // v halved d times, one halving after the other, as the splits of Sec. 3.4 are performed on the
 // weights (Eq. 3 per split).  While the result stays a normal number that is one exact multiply
 // by 2^-d; a result below the normal range rounds at every further halving, which a single

@@ -111,6 +111,24 @@ class ExpandedLayer:
                     self.bits_w, self.scale_x, self.scale_w, acc_out,
                     0 if acc_out is None else acc_out.stride(0), self.Y, self.N, None, stream)
 
+    def fused_fits(self, X):
+        """Whether forward_fused serves this layer (one tile of output columns, whole K-steps of X)."""
+        return B.ocs_split_act_qgemm_fits(X.shape[0], self.C, self.g, self.s, self.N, X.stride(0))
+
+    def fused_pays(self, X):
+        """Whether the library expects forward_fused to be ahead of forward on this layer."""
+        return B.ocs_split_act_qgemm_pays(X.shape[0], self.C, self.g, self.s, self.N, X.stride(0))
+
+    def forward_fused(self, X, threshold, acc_out=None, stream=None):
+        """forward() on a static grid as one launch: the GEMM quantizes and duplicates X's channels
+        itself and the code tensor is never written.  Same outputs, bit for bit."""
+        M = X.shape[0]
+        self._ensure_rows(M)
+        B.ocs_split_act_qgemm(X, M, self.C, self.g, X.stride(0), self.chan_src, self.s, self.bits_x, threshold,
+                              self.Wq, self.ldq, self.N, self.bits_w, self.scale_w, self.scale_x, acc_out,
+                              0 if acc_out is None else acc_out.stride(0), self.Y, self.N, stream)
+        return self.Y[:M]
+
     def forward(self, X, threshold=None, acc_out=None, stream=None):
         """X fp32 [M, C*g] -> Y fp32 [M, N].  threshold: device float tensor for a static
         activation grid (Sec. 5: fixed from profiling), None for a per-batch dynamic one."""

@@ -82,6 +82,17 @@ def check_forward(layer, L, exp, Wq_ref, sw_ref, X_dev, X_rows, rows, threshold)
     Y1 = Y.clone()
     Y2 = L.forward(X_dev, threshold=th)
     assert torch.equal(Y1, Y2)
+    # split + quantize + GEMM as one launch, where that entry point serves the shape: the sampled
+    # accumulators against the oracle again, and every output bit against the two launches
+    if th is not None and L.fused_fits(X_dev):
+        acc.fill_(-7)
+        L.scale_x.zero_()
+        Y3 = L.forward_fused(X_dev, th, acc_out=acc)
+        assert np.array_equal(host(L.scale_x), sx_ref)
+        assert np.array_equal(host(acc[rows_t]), acc_ref)
+        assert torch.equal(Y1, Y3)
+        Y3.fill_(-7.0)
+        assert torch.equal(Y1, L.forward_fused(X_dev, th))      # no accumulators stored
     return sx_ref
 
 

@@ -468,6 +468,66 @@ def test_qgemm_split_k(parts, M, N, K):
     assert_y_close(host(Y), y_ref)
 
 
+# ---- ocs_split_act_qgemm: the two calls as one launch -----------------------------------------
+
+@pytest.mark.parametrize("M,C,g,s,N", [(1, 64, 1, 0, 1), (130, 64, 1, 4, 64), (300, 64, 9, 4, 64), (257, 256, 1, 13, 128),
+                                       (700, 128, 9, 7, 128), (129, 512, 1, 26, 256), (200, 256, 9, 13, 250),
+                                       (64, 1024, 1, 52, 70), (90, 64, 4, 200, 33), (128, 64, 2, 64, 256),
+                                       (500, 2048, 4, 103, 256)])
+@pytest.mark.parametrize("bits_w", [4, 8])
+def test_split_act_qgemm(M, C, g, s, N, bits_w):
+    """X -> codes -> accumulators in one launch: the accumulators are bit for bit the oracle's GEMM on the
+    oracle's codes of the expanded X, the outputs within the contract of the two-call path; weights at
+    the recommended pitch (for a short K the rows end inside the last K-step)."""
+    rng = np.random.default_rng(M + C + g + s + N)
+    K = C * g
+    X = np.abs(_tensor(rng, M, K, "heavy"))
+    W = _tensor(rng, N, K, "normal") * np.float32(0.05)
+    exp = ref.split_weights(W, C, g, s)
+    # (a split list with repeats of one channel, as the greedy produces on heavy tails)
+    Ke = (C + s) * g
+    ldq = B.ocs_padded_cols(Ke)
+    Wq, sw = ref.quantize(exp["T_out"], bits_w, clip_ratio=0.9, ldq=ldq)
+    T = 3.0
+    Xq, sx, _ = ref.split_act(X, C, g, exp["chan_src"], None, s, 8, threshold=T, ldq=ldq)
+    acc_ref, y_ref = ref.qgemm(Xq, Wq, Ke, sx[1], sw[1])
+    assert B.ocs_split_act_qgemm_fits(M, C, g, s, N, K)
+    Xd, Wd, swd = dev(X), dev(Wq), dev(sw)
+    cs = dev(exp["chan_src"])
+    th = torch.tensor([T], dtype=torch.float32, device="cuda")
+    for want_acc in (True, False):
+        acc = torch.full((M, N), -7, dtype=torch.int32, device="cuda") if want_acc else None
+        Y = torch.full((M, N), -7.0, dtype=torch.float32, device="cuda")
+        sxo = torch.zeros(2, dtype=torch.float32, device="cuda")
+        B.ocs_split_act_qgemm(Xd, M, C, g, K, cs, s, 8, th, Wd, ldq, N, bits_w, swd, sxo, acc, N if want_acc else 0,
+                              Y, N)
+        if want_acc:
+            assert np.array_equal(host(acc), acc_ref)
+        assert np.array_equal(host(sxo), sx)
+        assert_y_close(host(Y), y_ref)
+
+
+def test_split_act_qgemm_equals_the_two_calls_bit_for_bit():
+    """Same Y bits as ocs_split_act followed by ocs_qgemm, on a shape that spans several row tiles with a
+    ragged last one and has a channel split three times."""
+    rng = np.random.default_rng(77)
+    M, C, g, s, N = 1000, 128, 9, 9, 200
+    K, Ke = C * g, (C + s) * g
+    X = np.abs(_tensor(rng, M, K, "heavy"))
+    W = _tensor(rng, N, K, "normal")
+    W[:, 5 * g:6 * g] *= np.float32(40.0)          # one dominant channel: split again and again
+    wts = gpu_split_weights(W, C, g, s, bits=4, want_f32=False)
+    assert wts["chan_depth"].max() >= 3
+    ldq = wts["Wq"].shape[1]
+    Xq, sx = gpu_split_act(X, C, g, wts["chan_src"], None, s, 8, threshold=2.5, ldq=ldq)
+    _, Y2 = gpu_qgemm(Xq, wts["Wq"], Ke, sx, wts["scale"], want_acc=False)
+    Y = torch.full((M, N), -7.0, dtype=torch.float32, device="cuda")
+    B.ocs_split_act_qgemm(dev(X), M, C, g, K, dev(wts["chan_src"]), s, 8,
+                          torch.tensor([2.5], dtype=torch.float32, device="cuda"), dev(wts["Wq"]), ldq, N, 4,
+                          dev(wts["scale"]), None, None, 0, Y, N)
+    assert np.array_equal(host(Y), Y2)
+
+
 def test_qgemm_extreme_codes_do_not_overflow():
     K = 4096
     Xq = np.full((40, K), 127, dtype=np.int8)
