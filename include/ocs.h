@@ -308,10 +308,10 @@ int ocs_qgemm(const int8_t *Xq, int64_t ldx, const int8_t *Wq, int64_t ldw, int6
  *        float[2], receives {T, T / qmax} as ocs_split_act's scale_out would; must not be `threshold`.
  *   Wq [N, ldw], scale_w: the weight codes and grid of the expanded layer, ldw >= (C+num_splits)*g
  *        rounded up to OCS_CALIGN and a multiple of it, pad columns zero.
- * Serves the shapes ocs_split_act_qgemm_fits() accepts (host-only; 1 = yes): C*g a multiple of 64
- * and at most 8192, at most 2048 appended columns num_splits*g, N <= 256 (one tile of output
- * columns, so that X is read once), ldx a multiple of 4; X 16-byte aligned.  Other shapes:
- * OCS_E_SHAPE, and the two calls do the same work.
+ * Serves the shapes ocs_split_act_qgemm_fits() accepts (host-only; 1 = yes): 64 <= C*g <= 8192,
+ * at most 2048 appended columns num_splits*g, N <= 256 (one tile of output columns, so that X is
+ * read once); X needs only its float alignment, at any ldx.  Other shapes: OCS_E_SHAPE, and the
+ * two calls do the same work.
  */
 int ocs_split_act_qgemm_fits(int64_t M, int C, int g, int num_splits, int64_t N, int64_t ldx);
 /* 1 where it fits and was measured ahead of the two calls (rows of X of 256 values and more). */
@@ -484,7 +484,8 @@ int ocs_calib_mfma(const void *operands, int iters, int workgroups, void *sink, 
  * pass), "sel_inline" (most splits for which ocs_split_weights runs the selection inside its
  * code pass instead of as a launch of its own; 0: never), "gemm_tile" (tile variant of
  * ocs_qgemm / ocs_qconv: 6, 7, 9, 10, 11, 12, 14, 16, 17, 18, 19, 23, 24; an id a shape cannot use falls
- * back to one it can).  value < 0 restores the default.  Returns OCS_OK or OCS_E_MODE for an
+ * back to one it can), "fused_variant" (ocs_split_act_qgemm with more than 128 output columns:
+ * 1 = 64-row workgroups, 2 = 128-row ones).  value < 0 restores the default.  Returns OCS_OK or OCS_E_MODE for an
  * unknown key.  The settings belong to the calling thread and affect its own calls only.
  */
 int ocs_tune(const char *key, int value);

@@ -521,7 +521,7 @@ int ocs_split_act_qgemm(const float* X, int64_t M, int C, int g, int64_t ldx, co
     if (N <= 0 || N > (int64_t)1 << 30 || ldy < N || (acc_out && ldacc < N)) return OCS_E_SHAPE;
     const int64_t Kexp = (int64_t)(C + num_splits) * g;
     if (ldw < round_up(Kexp, OCS_CALIGN)) return OCS_E_SHAPE;
-    if (ldw % OCS_CALIGN != 0 || !aligned(Wq, 16) || !aligned(X, 16)) return OCS_E_ALIGN;
+    if (ldw % OCS_CALIGN != 0 || !aligned(Wq, 16)) return OCS_E_ALIGN;
     if (!bits_ok(bits_x) || !bits_ok(bits_w)) return OCS_E_BITS;
     const int64_t qx = (1 << (bits_x - 1)) - 1, qw = (1 << (bits_w - 1)) - 1;
     if (Kexp * qx * qw >= (int64_t)1 << 31) return OCS_E_OVERFLOW;
@@ -744,6 +744,7 @@ int ocs_tune(const char* key, int value) {
     else if (!strcmp(key, "act_wide")) t.act_wide = value < 0 ? 0 : value;
     else if (!strcmp(key, "act_map")) t.act_map = value;
     else if (!strcmp(key, "gemm_tile")) t.gemm_tile = value;
+    else if (!strcmp(key, "fused_variant")) t.fused_variant = value;
     else if (!strcmp(key, "max_flat")) t.max_flat = value;
     else if (!strcmp(key, "max_grid")) t.max_grid = value;
     else if (!strcmp(key, "max_un")) t.max_un = value;

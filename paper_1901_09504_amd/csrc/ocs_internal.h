@@ -160,8 +160,8 @@ hipError_t launch_qgemm_split(const int8_t* Xq, int64_t ldx, const int8_t* Wq, i
 
 // Split + quantize + GEMM in one launch (static grid thr, copies un-scaled as on the activation side
 // of Eq. 3): Y = (codes of the expanded X) x Wq^T scaled by (T/qmax) * scale_w[1], without the code
-// tensor ever reaching memory.  ..._fits: the shapes it serves (C*g a multiple of 64 up to 8192,
-// at most 2048 appended columns, N <= 256, 16-byte rows of X).
+// tensor ever reaching memory.  ..._fits: the shapes it serves (C*g from 64 to 8192, at most 2048
+// appended columns, N <= 256).
 bool split_act_qgemm_fits(int64_t M, int C, int g, int s, int64_t N, int64_t ldx);
 bool split_act_qgemm_pays(int64_t M, int C, int g, int s, int64_t N, int64_t ldx);
 hipError_t launch_split_act_qgemm(const float* X, int64_t ldx, int64_t M, int C, int g, int s,
@@ -271,6 +271,7 @@ struct Tuning {
     int act_dep = -1;   // Eq. 4 pass: per-column depths from a table in LDS (1), from global memory (0), by tensor size (-1)
     int act_nt = 0;     // non-temporal loads of X in that pass (off: appended columns re-read X through L2)
     int gemm_tile = -1;
+    int fused_variant = -1;  // workgroup shape / pipeline depth of the split+quantize+GEMM launch (default: by shape)
     int max_flat = -1;  // whole-tensor max|x| of a contiguous tensor as one flat stream (1), by columns (0), default (-1)
     int max_grid = -1;  // workgroups of the flat pass
     int max_un = -1;    // 16-byte loads in flight per lane in the flat pass (1, 2 or 4)

@@ -221,7 +221,7 @@ struct SplitK {
 // Sixteen zero codes: what a row "holds" past its pitch.  With a short K the rows of the operands
 // need not fill their last K-step (a 68-byte row in an 80-byte pitch, walked as 128 bytes): the
 // 16-byte pieces that lie past the pitch are fetched from here instead of from the next row.
-__device__ __align__(16) const int8_t zero_chunk[16] = {};
+__device__ __align__(16) int8_t zero_chunk[16] = {};   // (not declared const: it must stay in the global address space, like the rows it stands in for)
 
 // MASK: the pitches may end inside the last K-step (see zero_chunk); every request then checks
 // its piece against the pitch.
@@ -737,21 +737,27 @@ static FusedLds fused_lds(int BM, int BN, int ksteps_main, int tail_steps, int T
     l.b_off = 2 * BM * 64;
     l.tail_off = l.b_off + 2 * BN * 64;
     l.first_off = l.tail_off + tail_steps * BM * 64;
-    l.cursor_off = l.first_off + (ksteps_main + 1) * 4;
-    l.ent_off = l.cursor_off + ksteps_main * 4;
+    l.cursor_off = l.first_off + (ksteps_main + 2) * 4;
+    l.ent_off = l.cursor_off + (ksteps_main + 1) * 4;
     l.total = l.ent_off + (T > 0 ? T : 1) * 4;
     return l;
 }
 
-template <int BN, int BM>
-__global__ __launch_bounds__(BM * 4) void split_act_qgemm_kernel(
+template <int BN, int BM, int NT, int WPE, int SETS>
+__global__ __launch_bounds__(NT, WPE) void split_act_qgemm_kernel(
     const float* __restrict__ X, int64_t ldx, int M, int C, int g, int s,
     const int32_t* __restrict__ chan_src, const float* __restrict__ thr, float qmax,
-    const int8_t* __restrict__ Wq, int64_t ldw, int N, int ksteps_main, int ksteps_all,
+    const int8_t* __restrict__ Wq, int64_t ldw, int N, int ksteps_main, int ksteps_all, int rem,
     const float* __restrict__ scale_w, float* __restrict__ scale_x_out, int32_t* __restrict__ acc_out,
     int64_t ldacc, float* __restrict__ Y, int64_t ldy, FusedLds L) {
-    constexpr int NT = BM * 4, NW = NT / 64;   // one thread per (row, 16-column piece) of a step
-    constexpr int WAVES_N = 2, WN = BN / WAVES_N, TN = WN / 32;
+    // ksteps_main: whole 64-column steps of X; rem: the columns of X left over after them (< 64).
+    // They and the appended columns form the steps ksteps_main .. ksteps_all-1, which are assembled
+    // in LDS (`tail`): the left-over columns are quantized straight into its first step.
+    constexpr int NW = NT / 64;
+    constexpr int A_PER = BM * 16 / NT;        // 16-byte loads of X per thread and step (64 floats x BM rows)
+    constexpr int WAVES_M = BM / 32, WAVES_N = NW / WAVES_M, WN = BN / WAVES_N, TN = WN / 32;
+    static_assert(A_PER >= 1 && A_PER * NT == BM * 16 && WAVES_M * WAVES_N == NW && TN >= 1 && TN * 32 * WAVES_N == BN,
+                  "the threads tile a step of X, the waves tile the outputs in 32 x 32 blocks");
     constexpr int B_SLOTS = BN * 4, B_PER = (B_SLOTS + NT - 1) / NT;
     static_assert(BN == 64 || BN == 128 || BN == 256, "64, 128 or 256 output columns");
     static_assert(NW * 8 * WN * 4 <= 2 * BM * 64 + 2 * BN * 64, "the epilogue's staging area is the operand buffers");
@@ -760,8 +766,8 @@ __global__ __launch_bounds__(BM * 4) void split_act_qgemm_kernel(
     int8_t* a_buf = flds + L.a_off;
     int8_t* b_buf = flds + L.b_off;
     int8_t* tail = flds + L.tail_off;
-    int* first = reinterpret_cast<int*>(flds + L.first_off);     // [ksteps_main + 1]
-    int* cursor = reinterpret_cast<int*>(flds + L.cursor_off);   // [ksteps_main]
+    int* first = reinterpret_cast<int*>(flds + L.first_off);     // [ksteps_main + 2]
+    int* cursor = reinterpret_cast<int*>(flds + L.cursor_off);   // [ksteps_main + 1]
     int* ent = reinterpret_cast<int*>(flds + L.ent_off);         // [T]: (e << 6) | source column inside its step
 
     const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -769,58 +775,71 @@ __global__ __launch_bounds__(BM * 4) void split_act_qgemm_kernel(
     const int row0 = (int)blockIdx.x * BM;
     const int T = s * g, tail_steps = ksteps_all - ksteps_main;
 
-    // A: load i of a lane is float4 number (lane & 15) of the step's 64 floats of row
-    // 16*wave + 4*i + (lane >> 4): each load instruction of a wave covers four rows' whole 256 bytes
-    const float* a_src[4];
-    int a_dst[4];       // byte offset of the resulting code dword inside an A buffer
+    // A: the step's BM x 16 float4 numbered row-major; load i of thread t is number i*NT + t, so each
+    // load instruction of a wave covers four rows' whole 256 bytes
+    const float* a_src[A_PER];
+    int a_dst[A_PER];   // byte offset of the resulting code dword inside an A buffer
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r = 16 * wave + 4 * i + (lane >> 4), f4 = lane & 15;
+    for (int i = 0; i < A_PER; ++i) {
+        const int f = i * NT + tid, r = f >> 4, f4 = f & 15;
         int gr = row0 + r;
         gr = gr < M ? gr : M - 1;          // rows past the edge re-read the last row; never stored
         a_src[i] = X + (int64_t)gr * ldx + f4 * 4;
         a_dst[i] = r * 64 + swz<64>(r, f4 >> 2) * 16 + (f4 & 3) * 4;
     }
     // B: 16-byte piece (slot & 3) of the step of weight row (slot >> 2)
+    static_assert(B_PER * NT == B_SLOTS, "every thread moves the same number of weight pieces");
     const int8_t* b_src[B_PER];
     int b_dst[B_PER], b_piece[B_PER];
-    bool b_on[B_PER];
     const int b_pieces = (int)(ldw / 16);
 #pragma unroll
     for (int u = 0; u < B_PER; ++u) {
         const int slot = u * NT + tid, n = slot >> 2, c = slot & 3;
-        b_on[u] = slot < B_SLOTS;
         const int gn = col_clamp(n, N);
         b_src[u] = Wq + (int64_t)gn * ldw;
         b_piece[u] = c;
         b_dst[u] = n * 64 + swz<64>(n, c) * 16;
     }
 
-    f32x4 av[3][4];
-    i32x4 bv[3][B_PER];
-    auto load_step = [&](int kt, f32x4 (&a)[4], i32x4 (&b)[B_PER]) {
-        if (kt < ksteps_main) {
+    // SETS register sets in rotation: while one is processed, the next SETS-1 steps are on their way
+    static_assert(SETS == 2 || SETS == 3, "one or two steps ahead");
+    f32x4 av[SETS][A_PER];
+    i32x4 bv[SETS][B_PER];
+    auto load_step = [&](int kt, f32x4 (&a)[A_PER], i32x4 (&b)[B_PER]) {
+        // Every lane issues the same loads at every step, whatever the step holds for it: a lane with
+        // nothing to fetch (steps past the columns of X, pieces past a pitch, left-over columns that
+        // do not exist) reads the 16 zero bytes instead, which costs one request per wave.  With no
+        // branch around any load, the number of loads in flight is known at every wait, and the
+        // waits let the two steps that are on their way stay on their way.
+        const bool main_step = kt < ksteps_main, rest_step = kt == ksteps_main && rem > 0;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const f32x4*>(a_src[i] + (int64_t)kt * 64);
+        for (int i = 0; i < A_PER; ++i) {
+            const int c0 = ((i * NT + tid) & 15) * 4;
+            // left-over columns: a float4 that would cross the row's end starts four floats before
+            // the end instead, and is shifted into place afterwards (nothing is read past the row)
+            const bool whole = main_step || (rest_step && c0 + 3 < rem);
+            const bool part = rest_step && c0 < rem && !whole;
+            const float* src = whole ? a_src[i] + (int64_t)kt * 64
+                                     : (part ? a_src[i] + (int64_t)kt * 64 - c0 + (rem - 4)
+                                             : reinterpret_cast<const float*>(zero_chunk));
+            a[i] = *reinterpret_cast<const f32x4u*>(src);     // (shifted when it is used, not here)
         }
-        if (kt < ksteps_all) {
 #pragma unroll
-            for (int u = 0; u < B_PER; ++u) {
-                const int piece = kt * 4 + b_piece[u];
-                i32x4 z = {0, 0, 0, 0};
-                // a pitch may end inside the last K-step: what the row lacks counts as zero codes
-                b[u] = (b_on[u] && piece < b_pieces) ? *reinterpret_cast<const i32x4*>(b_src[u] + piece * 16) : z;
-            }
+        for (int u = 0; u < B_PER; ++u) {
+            const int piece = kt * 4 + b_piece[u];
+            // a pitch may end inside the last K-step: what the row lacks counts as zero codes
+            b[u] = *reinterpret_cast<const i32x4*>(kt < ksteps_all && piece < b_pieces ? b_src[u] + piece * 16
+                                                                                       : zero_chunk);
         }
     };
     load_step(0, av[0], bv[0]);
-    load_step(1, av[1], bv[1]);
+    if (SETS == 3) load_step(1, av[1], bv[1]);
 
     // set-up behind the first requests: clear the appended steps, bucket the appended columns
     {
         i32x4 z = {0, 0, 0, 0};
         for (int o = tid; o < tail_steps * (BM * 64 / 16); o += NT) reinterpret_cast<i32x4*>(tail)[o] = z;
-        for (int k = tid; k <= ksteps_main; k += NT) first[k] = 0;
+        for (int k = tid; k <= ksteps_main + 1; k += NT) first[k] = 0;
         __syncthreads();
         for (int e = tid; e < T; e += NT) {
             const int j = e / g, t = e - j * g;
@@ -830,13 +849,13 @@ __global__ __launch_bounds__(BM * 4) void split_act_qgemm_kernel(
         __syncthreads();
         if (tid == 0) {
             int run = 0;
-            for (int k = 0; k < ksteps_main; ++k) {
+            for (int k = 0; k <= ksteps_main; ++k) {
                 run += first[k + 1];
                 first[k + 1] = run;
             }
         }
         __syncthreads();
-        for (int k = tid; k < ksteps_main; k += NT) cursor[k] = first[k];
+        for (int k = tid; k <= ksteps_main; k += NT) cursor[k] = first[k];
         __syncthreads();
         for (int e = tid; e < T; e += NT) {
             const int j = e / g, t = e - j * g;
@@ -861,35 +880,51 @@ __global__ __launch_bounds__(BM * 4) void split_act_qgemm_kernel(
         for (int v = 0; v < 16; ++v) acc[j][v] = 0;
     const int frag_row = lane & 31, frag_half = lane >> 5;
 
-    auto process = [&](int kt, const f32x4 (&a)[4], const i32x4 (&b)[B_PER]) {
+    auto process = [&](int kt, const f32x4 (&a)[A_PER], const i32x4 (&b)[B_PER]) {
         const int buf = kt & 1;
         int8_t* ab = a_buf + buf * (BM * 64);
         int8_t* bb = b_buf + buf * (BN * 64);
         const bool main_step = kt < ksteps_main;
-        if (main_step) {
+        const bool rest_step = kt == ksteps_main && rem > 0;     // holds the left-over columns of X
+        if (main_step || rest_step) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                *reinterpret_cast<unsigned*>(ab + a_dst[i]) =
-                    pack4(code_bits(a[i][0], inv, qmax), code_bits(a[i][1], inv, qmax),
-                          code_bits(a[i][2], inv, qmax), code_bits(a[i][3], inv, qmax));
+            for (int i = 0; i < A_PER; ++i) {
+                const unsigned q4 = pack4(code_bits(a[i][0], inv, qmax), code_bits(a[i][1], inv, qmax),
+                                          code_bits(a[i][2], inv, qmax), code_bits(a[i][3], inv, qmax));
+                if (main_step) {
+                    *reinterpret_cast<unsigned*>(ab + a_dst[i]) = q4;
+                } else {
+                    // into the first assembled step, byte by byte where the dword also holds copies.
+                    // A float4 that straddled the row's end was fetched as columns rem-4 .. rem-1:
+                    // this lane's column c0 + e is its element c0 + e - (rem - 4)
+                    const int c0 = ((i * NT + tid) & 15) * 4;
+                    if (c0 + 3 < rem) {
+                        *reinterpret_cast<unsigned*>(tail + a_dst[i]) = q4;
+                    } else {
+                        const int d = c0 - (rem - 4);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (c0 + e < rem) tail[a_dst[i] + e] = (int8_t)((q4 >> (8 * (e + d))) & 0xFFu);
+                    }
+                }
+            }
         }
 #pragma unroll
-        for (int u = 0; u < B_PER; ++u)
-            if (b_on[u]) *reinterpret_cast<i32x4*>(bb + b_dst[u]) = b[u];
+        for (int u = 0; u < B_PER; ++u) *reinterpret_cast<i32x4*>(bb + b_dst[u]) = b[u];
         __syncthreads();
-        const int8_t* am = ab;
-        if (main_step) {
-            // the copies whose sources this step holds: one byte per (copy, row)
+        const int8_t* am = main_step ? ab : tail + (kt - ksteps_main) * (BM * 64);
+        if (main_step || rest_step) {
+            // the copies whose sources this step holds: one byte per (copy, row), to expanded column
+            // C*g + e, which is column rem + e of the assembled steps
             const int e0 = first[kt], n = first[kt + 1] - e0;
             for (int idx = tid; idx < n * BM; idx += NT) {
                 const int q = idx / BM, r = idx - q * BM;
-                const int en = ent[e0 + q], e = en >> 6, c = en & 63;
-                const int8_t code = ab[r * 64 + swz<64>(r, c >> 4) * 16 + (c & 15)];
+                const int en = ent[e0 + q], e = rem + (en >> 6), c = en & 63;
+                const int8_t code = am[r * 64 + swz<64>(r, c >> 4) * 16 + (c & 15)];
                 const int te = e & 63;
                 tail[(e >> 6) * (BM * 64) + r * 64 + swz<64>(r, te >> 4) * 16 + (te & 15)] = code;
             }
-        } else {
-            am = tail + (kt - ksteps_main) * (BM * 64);
+            if (rest_step) __syncthreads();    // this very step may hold some of those copies
         }
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
@@ -904,13 +939,12 @@ __global__ __launch_bounds__(BM * 4) void split_act_qgemm_kernel(
         }
     };
 
-    // three register sets in rotation: while set p is processed, sets p+1 and p+2 are on their way
-    for (int kt0 = 0; kt0 < ksteps_all; kt0 += 3) {
+    for (int kt0 = 0; kt0 < ksteps_all; kt0 += SETS) {
 #pragma unroll
-        for (int p = 0; p < 3; ++p) {
+        for (int p = 0; p < SETS; ++p) {
             const int kt = kt0 + p;
             if (kt < ksteps_all) {
-                load_step(kt + 2, av[(p + 2) % 3], bv[(p + 2) % 3]);
+                load_step(kt + SETS - 1, av[(p + SETS - 1) % SETS], bv[(p + SETS - 1) % SETS]);
                 process(kt, av[p], bv[p]);
             }
         }
@@ -941,22 +975,24 @@ __global__ __launch_bounds__(BM * 4) void split_act_qgemm_kernel(
 // Where the one launch is ahead of the two (measured on the same shapes): from 256 columns of X
 // on.  With 64 the pass over X is short either way and the output dominates.
 bool split_act_qgemm_pays(int64_t M, int C, int g, int s, int64_t N, int64_t ldx) {
-    return split_act_qgemm_fits(M, C, g, s, N, ldx) && (int64_t)C * g >= 256;
+    return split_act_qgemm_fits(M, C, g, s, N, ldx) && (int64_t)C * g >= 128;
 }
 
 bool split_act_qgemm_fits(int64_t M, int C, int g, int s, int64_t N, int64_t ldx) {
     const int64_t K = (int64_t)C * g, T = (int64_t)s * g;
-    return M >= 1 && M <= 0x7FFFFFFF - kFusedMaxBM && K >= 64 && K % 64 == 0 && K <= kFusedMaxK && T <= kFusedMaxTail &&
-           N >= 1 && N <= 256 && ldx % 4 == 0;
+    (void)ldx;
+    return M >= 1 && M <= 0x7FFFFFFF - kFusedMaxBM && K >= 64 && K <= kFusedMaxK && T <= kFusedMaxTail && N >= 1 &&
+           N <= 256;
 }
 
-template <int BN, int BM>
+template <int BN, int BM, int NT, int WPE, int SETS>
 static hipError_t run_split_act_qgemm(const float* X, int64_t ldx, int64_t M, int C, int g, int s,
                                       const int32_t* chan_src, const float* thr, float qmax, const int8_t* Wq,
                                       int64_t ldw, int64_t N, int64_t Kexp, const float* scale_w,
                                       float* scale_x_out, int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy,
                                       hipStream_t stream) {
     const int ksteps_main = (int)((int64_t)C * g / 64), ksteps_all = (int)ceil_div(Kexp, 64);
+    const int rem = (int)((int64_t)C * g - (int64_t)ksteps_main * 64);
     const FusedLds L = fused_lds(BM, BN, ksteps_main, ksteps_all - ksteps_main, s * g);
     if (L.total > kWholeKMaxLds) return hipErrorInvalidValue;
     static std::atomic<bool> opted_in[kMaxDevices];
@@ -966,15 +1002,15 @@ static hipError_t run_split_act_qgemm(const float* X, int64_t ldx, int64_t M, in
         if (e != hipSuccess) return e;
         if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
         if (!opted_in[dev].load(std::memory_order_acquire)) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&split_act_qgemm_kernel<BN, BM>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&split_act_qgemm_kernel<BN, BM, NT, WPE, SETS>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWholeKMaxLds);
             if (e != hipSuccess) return e;
             opted_in[dev].store(true, std::memory_order_release);
         }
     }
-    return launch_kernel(kTimeGemm, split_act_qgemm_kernel<BN, BM>, dim3((unsigned)ceil_div(M, BM)),
-                         dim3(BM * 4), (unsigned)L.total, stream, X, ldx, (int)M, C, g, s, chan_src, thr, qmax,
-                         Wq, ldw, (int)N, ksteps_main, ksteps_all, scale_w, scale_x_out, acc_out, ldacc, Y, ldy, L);
+    return launch_kernel(kTimeGemm, split_act_qgemm_kernel<BN, BM, NT, WPE, SETS>, dim3((unsigned)ceil_div(M, BM)),
+                         dim3(NT), (unsigned)L.total, stream, X, ldx, (int)M, C, g, s, chan_src, thr, qmax,
+                         Wq, ldw, (int)N, ksteps_main, ksteps_all, rem, scale_w, scale_x_out, acc_out, ldacc, Y, ldy, L);
 }
 
 hipError_t launch_split_act_qgemm(const float* X, int64_t ldx, int64_t M, int C, int g, int s,
@@ -983,13 +1019,17 @@ hipError_t launch_split_act_qgemm(const float* X, int64_t ldx, int64_t M, int C,
                                   int32_t* acc_out, int64_t ldacc, float* Y, int64_t ldy, hipStream_t stream) {
     if (!split_act_qgemm_fits(M, C, g, s, N, ldx)) return hipErrorInvalidValue;
 #define OCS_FUSED_ARGS X, ldx, M, C, g, s, chan_src, thr, qmax, Wq, ldw, N, Kexp, scale_w, scale_x_out, acc_out, ldacc, Y, ldy, stream
-    // Measured on the paper's layer shapes at batch 256: up to 128 output columns, workgroups of 64
-    // rows (two or more per compute unit, each with its own barriers) are 10-20 % ahead of 128-row
-    // ones; with 256 columns the weight codes a workgroup pulls per step weigh as much as its 64 rows
-    // of X, and 128 rows are level or ahead.
-    if (N <= 64) return run_split_act_qgemm<64, 64>(OCS_FUSED_ARGS);
-    if (N <= 128) return run_split_act_qgemm<128, 64>(OCS_FUSED_ARGS);
-    return run_split_act_qgemm<256, 128>(OCS_FUSED_ARGS);
+    // Measured on the paper's layer shapes at batch 256.  Up to 128 output columns: workgroups of 64
+    // rows on 4 waves, three or four of them per compute unit, each with its own barriers (10-20 %
+    // ahead of 128-row ones).  256 columns: the weight codes a workgroup pulls per step weigh as much
+    // as 64 rows of X, and 128 rows on 8 waves are ahead, except on very tall X, where two 64-row
+    // workgroups per compute unit win.  One step of look-ahead everywhere: a second one was level or
+    // behind (its registers cost a workgroup per compute unit).
+    const int v = tuning().fused_variant;     // tests: 1 / 2 force the 64- / 128-row shape for N > 128
+    if (N <= 64) return run_split_act_qgemm<64, 64, 256, 4, 2>(OCS_FUSED_ARGS);
+    if (N <= 128) return run_split_act_qgemm<128, 64, 256, 3, 2>(OCS_FUSED_ARGS);
+    if (v == 1 || (v != 2 && M >= 131072)) return run_split_act_qgemm<256, 64, 512, 4, 2>(OCS_FUSED_ARGS);
+    return run_split_act_qgemm<256, 128, 512, 2, 2>(OCS_FUSED_ARGS);
 #undef OCS_FUSED_ARGS
 }
 
@@ -1270,7 +1310,6 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
                              : run_dma<256, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);
         case 12: return run_dma<256, 256, 2, 4, 64, 4>(OCS_GEMM_ARGS);   // 8 waves
         case 14: return run_dma<256, 256, 4, 4, 64, 4>(OCS_GEMM_ARGS);   // 16 waves
-        case 25: return run_dma<256, 256, 2, 2, 64, 4>(OCS_GEMM_ARGS);   // 4 waves of 128 x 128
         // whole-K variants; a K extent too long for them falls back to a ring variant
 #define OCS_WHOLEK(BM_, BN_, WM_, WN_, FALLBACK)                                                   \
     (wholek_lds_bytes<BM_, BN_, WM_, WN_>(Kpad, rq) <= kWholeKMaxLds                                   \

@@ -176,9 +176,9 @@ def test_one_launch_entry_point_says_what_it_serves_and_checks_on_the_host():
     L = B.lib()
     assert B.ocs_split_act_qgemm_fits(802816, 64, 9, 4, 64, 576) and B.ocs_split_act_qgemm_pays(802816, 64, 9, 4, 64, 576)
     assert B.ocs_split_act_qgemm_fits(802816, 64, 1, 4, 256, 64) and not B.ocs_split_act_qgemm_pays(802816, 64, 1, 4, 256, 64)
-    assert not B.ocs_split_act_qgemm_fits(3211264, 3, 49, 1, 64, 147)      # 147 columns: not whole K-steps
+    assert B.ocs_split_act_qgemm_fits(3211264, 3, 49, 1, 64, 147)          # 147 columns: two whole K-steps and a rest
+    assert not B.ocs_split_act_qgemm_fits(100, 3, 9, 1, 64, 27)            # less than one K-step
     assert not B.ocs_split_act_qgemm_fits(12544, 512, 9, 26, 512, 4608)    # more than one tile of output columns
-    assert not B.ocs_split_act_qgemm_fits(100, 64, 1, 4, 64, 66)           # rows of X not 16-byte aligned
     assert not B.ocs_split_act_qgemm_fits(100, 64, 256, 4, 64, 16384)      # 16384 columns
     assert not B.ocs_split_act_qgemm_fits(100, 64, 64, 40, 64, 4096)       # 2560 appended columns
     call = lambda **k: L.ocs_split_act_qgemm(*[k.get(n, d) for n, d in (
@@ -187,8 +187,8 @@ def test_one_launch_entry_point_says_what_it_serves_and_checks_on_the_host():
         ("stream", None))])
     assert call(X=None) == -1 and call(thr=None) == -1 and call(Wq=None) == -1 and call(Y=None) == -1 and call(cs=None) == -1
     assert call(ldx=60) == -2 and call(ldy=63) == -2 and call(ldw=64) == -2 and call(acc=A, ldacc=8) == -2
-    assert call(N=300, ldy=300) == -2 and call(C=3, g=49, ldx=147, s=1, ldw=208) == -2     # not served
-    assert call(ldw=88) == -3 and call(X=A + 4) == -3
+    assert call(N=300, ldy=300) == -2 and call(C=3, g=9, ldx=27, s=1, ldw=48) == -2     # not served
+    assert call(ldw=88) == -3 and call(Wq=A + 4) == -3
     assert call(bx=9) == -4 and call(s=-1) == -5
     assert call(sxo=A, thr=A) == -9
 

@@ -473,9 +473,11 @@ def test_qgemm_split_k(parts, M, N, K):
 @pytest.mark.parametrize("M,C,g,s,N", [(1, 64, 1, 0, 1), (130, 64, 1, 4, 64), (300, 64, 9, 4, 64), (257, 256, 1, 13, 128),
                                        (700, 128, 9, 7, 128), (129, 512, 1, 26, 256), (200, 256, 9, 13, 250),
                                        (64, 1024, 1, 52, 70), (90, 64, 4, 200, 33), (128, 64, 2, 64, 256),
-                                       (500, 2048, 4, 103, 256)])
-@pytest.mark.parametrize("bits_w", [4, 8])
-def test_split_act_qgemm(M, C, g, s, N, bits_w):
+                                       (500, 2048, 4, 103, 256), (300, 3, 49, 1, 64), (100, 37, 4, 6, 70),
+                                       (77, 100, 1, 5, 128), (65, 67, 1, 0, 256), (130, 191, 1, 64, 200),
+                                       (70, 13, 9, 2, 64)])
+@pytest.mark.parametrize("bits_w,variant", [(4, -1), (8, 1), (8, 2)])    # variants: both workgroup shapes for N > 128
+def test_split_act_qgemm(M, C, g, s, N, bits_w, variant):
     """X -> codes -> accumulators in one launch: the accumulators are bit for bit the oracle's GEMM on the
     oracle's codes of the expanded X, the outputs within the contract of the two-call path; weights at
     the recommended pitch (for a short K the rows end inside the last K-step)."""
@@ -495,16 +497,20 @@ def test_split_act_qgemm(M, C, g, s, N, bits_w):
     Xd, Wd, swd = dev(X), dev(Wq), dev(sw)
     cs = dev(exp["chan_src"])
     th = torch.tensor([T], dtype=torch.float32, device="cuda")
-    for want_acc in (True, False):
-        acc = torch.full((M, N), -7, dtype=torch.int32, device="cuda") if want_acc else None
-        Y = torch.full((M, N), -7.0, dtype=torch.float32, device="cuda")
-        sxo = torch.zeros(2, dtype=torch.float32, device="cuda")
-        B.ocs_split_act_qgemm(Xd, M, C, g, K, cs, s, 8, th, Wd, ldq, N, bits_w, swd, sxo, acc, N if want_acc else 0,
-                              Y, N)
-        if want_acc:
-            assert np.array_equal(host(acc), acc_ref)
-        assert np.array_equal(host(sxo), sx)
-        assert_y_close(host(Y), y_ref)
+    B.ocs_tune("fused_variant", variant)
+    try:
+        for want_acc in (True, False):
+            acc = torch.full((M, N), -7, dtype=torch.int32, device="cuda") if want_acc else None
+            Y = torch.full((M, N), -7.0, dtype=torch.float32, device="cuda")
+            sxo = torch.zeros(2, dtype=torch.float32, device="cuda")
+            B.ocs_split_act_qgemm(Xd, M, C, g, K, cs, s, 8, th, Wd, ldq, N, bits_w, swd, sxo, acc,
+                                  N if want_acc else 0, Y, N)
+            if want_acc:
+                assert np.array_equal(host(acc), acc_ref)
+            assert np.array_equal(host(sxo), sx)
+            assert_y_close(host(Y), y_ref)
+    finally:
+        B.ocs_tune("fused_variant", -1)
 
 
 def test_split_act_qgemm_equals_the_two_calls_bit_for_bit():
