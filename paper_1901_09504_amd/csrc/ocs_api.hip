@@ -743,6 +743,7 @@ int ocs_tune(const char* key, int value) {
     else if (!strcmp(key, "act_un")) t.act_un = value;
     else if (!strcmp(key, "act_wide")) t.act_wide = value < 0 ? 0 : value;
     else if (!strcmp(key, "act_map")) t.act_map = value;
+    else if (!strcmp(key, "act_tile")) t.act_tile = value;
     else if (!strcmp(key, "gemm_tile")) t.gemm_tile = value;
     else if (!strcmp(key, "fused_variant")) t.fused_variant = value;
     else if (!strcmp(key, "max_flat")) t.max_flat = value;

@@ -270,6 +270,7 @@ struct Tuning {
     int act_wide = 0;   // force the 64-bit index variant of that pass (tests: tensors of 2^32 dwords do not fit a test)
     int act_dep = -1;   // Eq. 4 pass: per-column depths from a table in LDS (1), from global memory (0), by tensor size (-1)
     int act_nt = 0;     // non-temporal loads of X in that pass (off: appended columns re-read X through L2)
+    int act_tile = -1;  // static grid, un-scaled copies: tile-ordered pass always (1), never (0), by shape (-1)
     int gemm_tile = -1;
     int fused_variant = -1;  // workgroup shape / pipeline depth of the split+quantize+GEMM launch (default: by shape)
     int max_flat = -1;  // whole-tensor max|x| of a contiguous tensor as one flat stream (1), by columns (0), default (-1)

@@ -8,6 +8,8 @@
 // the caches, so no element of X is fetched from HBM twice.  With Eq. 3 (weights carry the
 // halving) the appended codes are byte copies of their source codes; with Eq. 4 every
 // expanded channel j is scaled by 2^-chan_depth[j] before it meets the grid.
+#include <atomic>
+
 #include "ocs_internal.h"
 #include "select_lds.h"
 
@@ -390,6 +392,215 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_in_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The pass in tile order, for a static grid with un-scaled copies (the activation side of Eq. 3):
+// a workgroup of 4 waves takes 64 rows and builds their expanded code rows in LDS, then writes
+// them out as one contiguous block (the rows of Xq follow each other at the pitch).  It walks the
+// columns of X in steps of 64: every lane requests four 16-byte pieces one step ahead (each load
+// instruction of a wave covers four rows' whole 256 bytes) and turns the previous step's 16
+// floats into codes at their place in the image.  The appended columns never touch memory on the
+// way: the copy of a column is the byte that has just been written into LDS, so after each step
+// the copies whose sources it holds are moved inside the image, byte by byte.
+// ---------------------------------------------------------------------------------------------
+__device__ __align__(16) int8_t tile_zero_chunk[16] = {};   // what a lane with nothing to fetch reads
+
+struct TileLds {
+    int pitch, first_off, cursor_off, ent_off, total;
+};
+constexpr int kTileNT = 256;
+constexpr int kTileMaxTail = 2048;
+constexpr int kTileMaxLds = 72 * 1024;     // two workgroups per compute unit
+
+static TileLds tile_lds(int BM, int64_t ldq, int ksteps_main, int T) {
+    TileLds l;
+    // image rows hold the pitch rounded up to whole steps, plus 16 bytes so that consecutive rows
+    // start in different banks
+    l.pitch = (int)round_up(ldq, 64) + 16;
+    l.first_off = BM * l.pitch;
+    l.cursor_off = l.first_off + (ksteps_main + 2) * 4;
+    l.ent_off = l.cursor_off + (ksteps_main + 1) * 4;
+    l.total = l.ent_off + (T > 0 ? T : 1) * 4;
+    return l;
+}
+
+template <int BM, int WPE, int SETS>
+__global__ __launch_bounds__(kTileNT, WPE) void expand_quantize_tile_kernel(
+    const float* __restrict__ X, int64_t ldx, int M, int C, int g, int s,
+    const int32_t* __restrict__ chan_src, const float* __restrict__ thr, float qmax,
+    int8_t* __restrict__ Xq, int64_t ldq, int ksteps_main, int rem, float* __restrict__ scale_out, TileLds L) {
+    // ksteps_main: whole 64-column steps of X; rem: columns of X left over after them (< 64)
+    constexpr int NT = kTileNT, A_PER = BM * 16 / NT;
+    static_assert(A_PER >= 1 && A_PER * NT == BM * 16, "the threads tile a step of X");
+    extern __shared__ __align__(1024) int8_t tlds[];
+    int8_t* img = tlds;                                          // [BM][pitch]: code of expanded column j at [r][j]
+    int* first = reinterpret_cast<int*>(tlds + L.first_off);     // [ksteps_main + 2]
+    int* cursor = reinterpret_cast<int*>(tlds + L.cursor_off);   // [ksteps_main + 1]
+    int* ent = reinterpret_cast<int*>(tlds + L.ent_off);         // [T]: (e << 6) | source column inside its step
+    const int P = L.pitch;
+
+    const int tid = (int)threadIdx.x;
+    const int row0 = (int)blockIdx.x * BM;
+    const int T = s * g, K = ksteps_main * 64 + rem;
+
+    // the step's BM x 16 float4 numbered row-major; load i of thread t is number i*NT + t
+    const float* a_src[A_PER];
+    int a_dst[A_PER];
+#pragma unroll
+    for (int i = 0; i < A_PER; ++i) {
+        const int f = i * NT + tid, r = f >> 4, f4 = f & 15;
+        int gr = row0 + r;
+        gr = gr < M ? gr : M - 1;          // rows past the edge re-read the last row; never stored
+        a_src[i] = X + (int64_t)gr * ldx + f4 * 4;
+        a_dst[i] = r * P + f4 * 4;
+    }
+    f32x4 av[SETS][A_PER];   // SETS register sets in rotation: SETS-1 steps are on their way while one is processed
+    auto load_step = [&](int kt, f32x4 (&a)[A_PER]) {
+        // every lane issues the same loads at every step (a lane with nothing to fetch reads the 16
+        // zero bytes): no branch around a load, so the look-ahead stays in flight across the waits
+        const bool main_step = kt < ksteps_main, rest_step = kt == ksteps_main && rem > 0;
+#pragma unroll
+        for (int i = 0; i < A_PER; ++i) {
+            const int c0 = ((i * NT + tid) & 15) * 4;
+            // left-over columns: a float4 that would cross the row's end starts four floats before
+            // the end instead and is shifted into place when it is used
+            const bool whole = main_step || (rest_step && c0 + 3 < rem);
+            const bool part = rest_step && c0 < rem && !whole;
+            const float* src = whole ? a_src[i] + (int64_t)kt * 64
+                                     : (part ? a_src[i] + (int64_t)kt * 64 - c0 + (rem - 4)
+                                             : reinterpret_cast<const float*>(tile_zero_chunk));
+            a[i] = *reinterpret_cast<const f32x4u*>(src);
+        }
+    };
+#pragma unroll
+    for (int p = 0; p + 1 < SETS; ++p) load_step(p, av[p]);
+
+    {   // behind the first requests: zero the rows' ends (columns past X's own: what no copy fills is
+        // padding), bucket the appended columns by the step of their source
+        const int z0 = ksteps_main * 64, zn = (P - 16 - z0) / 4;           // dwords per row from column z0 on
+        for (int o = tid; o < BM * zn; o += NT) {
+            const int r = o / zn, c = o - r * zn;
+            *reinterpret_cast<int*>(img + r * P + z0 + 4 * c) = 0;
+        }
+        for (int k = tid; k <= ksteps_main + 1; k += NT) first[k] = 0;
+        __syncthreads();
+        for (int e = tid; e < T; e += NT) {
+            const int j = e / g, t = e - j * g;
+            int src = chan_src[C + j];
+            src = src < 0 ? 0 : (src >= C ? C - 1 : src);
+            atomicAdd(&first[((src * g + t) >> 6) + 1], 1);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            int run = 0;
+            for (int k = 0; k <= ksteps_main; ++k) {
+                run += first[k + 1];
+                first[k + 1] = run;
+            }
+        }
+        __syncthreads();
+        for (int k = tid; k <= ksteps_main; k += NT) cursor[k] = first[k];
+        __syncthreads();
+        for (int e = tid; e < T; e += NT) {
+            const int j = e / g, t = e - j * g;
+            int src = chan_src[C + j];
+            src = src < 0 ? 0 : (src >= C ? C - 1 : src);
+            const int col = src * g + t;
+            const int pos = atomicAdd(&cursor[col >> 6], 1);
+            ent[pos] = (e << 6) | (col & 63);
+        }
+        // (the first step's barrier completes the table before anyone reads it)
+    }
+    const float Tx = *thr;
+    const float inv = inv_step_of(Tx, qmax);
+    if (scale_out != nullptr && blockIdx.x == 0 && tid == 0) {
+        scale_out[0] = Tx;
+        scale_out[1] = Tx / qmax;
+    }
+
+    auto process = [&](int kt, const f32x4 (&a)[A_PER]) {
+        const bool main_step = kt < ksteps_main;
+#pragma unroll
+        for (int i = 0; i < A_PER; ++i) {
+            const unsigned q4 = pack4(code_bits(a[i][0], inv, qmax), code_bits(a[i][1], inv, qmax),
+                                      code_bits(a[i][2], inv, qmax), code_bits(a[i][3], inv, qmax));
+            int8_t* dst = img + a_dst[i] + kt * 64;
+            const int c0 = ((i * NT + tid) & 15) * 4;
+            if (main_step || c0 + 3 < rem) {
+                *reinterpret_cast<unsigned*>(dst) = q4;
+            } else {
+                // left-over columns at the row's end: byte by byte (the dword also holds copies).  The
+                // float4 was fetched as columns rem-4 .. rem-1 of the step: this lane's column
+                // c0 + e is its element c0 + e - (rem - 4)
+                const int d = c0 - (rem - 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (c0 + e < rem) dst[e] = (int8_t)((q4 >> (8 * (e + d))) & 0xFFu);
+            }
+        }
+        __syncthreads();
+        // the copies whose sources this step holds: one byte per (copy, row), to expanded column K + e
+        const int e0 = first[kt], n = first[kt + 1] - e0;
+        for (int idx = tid; idx < n * BM; idx += NT) {
+            const int q = idx / BM, r = idx - q * BM;
+            const int en = ent[e0 + q];
+            img[r * P + K + (en >> 6)] = img[r * P + kt * 64 + (en & 63)];
+        }
+    };
+
+    const int steps = ksteps_main + (rem > 0 ? 1 : 0);
+    for (int kt0 = 0; kt0 < steps; kt0 += SETS) {
+#pragma unroll
+        for (int p = 0; p < SETS; ++p) {
+            const int kt = kt0 + p;
+            if (kt < steps) {
+                load_step(kt + SETS - 1, av[(p + SETS - 1) % SETS]);
+                process(kt, av[p]);
+            }
+        }
+    }
+    __syncthreads();   // the image is complete
+    // out as one contiguous block: 16-byte piece o of the block is piece o % (ldq/16) of row o / (ldq/16)
+    const int ppr = (int)(ldq / 16);
+    const int rows = M - row0 < BM ? M - row0 : BM;
+    i32x4* out = reinterpret_cast<i32x4*>(Xq + (int64_t)row0 * ldq);
+    for (int o = tid; o < rows * ppr; o += NT) {
+        const int r = o / ppr, c = o - r * ppr;
+        out[o] = *reinterpret_cast<const i32x4*>(img + r * P + c * 16);
+    }
+}
+
+// Shapes the tile-ordered pass serves: the image of 64 expanded rows has to leave room for two
+// workgroups per compute unit.
+static bool tile_fits(int64_t M, int64_t K, int64_t T, int64_t ldq) {
+    if (M < 1 || M > 0x7FFFFFFF - 64 || K < 64 || T > kTileMaxTail || ldq % 16 != 0 || ldq > 65536) return false;
+    return tile_lds(64, ldq, (int)(K / 64), (int)T).total <= kTileMaxLds;
+}
+
+template <int BM, int SETS>
+static hipError_t run_expand_quantize_tile(const float* X, int64_t ldx, int64_t M, int C, int g, int s,
+                                           const int32_t* chan_src, const float* thr, float qmax, int8_t* Xq,
+                                           int64_t ldq, float* scale_out, hipStream_t stream) {
+    const int64_t K = (int64_t)C * g;
+    const int ksteps_main = (int)(K / 64), rem = (int)(K - (int64_t)ksteps_main * 64);
+    const TileLds L = tile_lds(BM, ldq, ksteps_main, s * g);
+    static std::atomic<bool> opted_in[64];
+    if (L.total > 65536) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+        if (!opted_in[dev].load(std::memory_order_acquire)) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&expand_quantize_tile_kernel<BM, 4, SETS>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kTileMaxLds);
+            if (e != hipSuccess) return e;
+            opted_in[dev].store(true, std::memory_order_release);
+        }
+    }
+    return launch_kernel(kTimeSplitQuantize, expand_quantize_tile_kernel<BM, 4, SETS>, dim3((unsigned)ceil_div(M, BM)),
+                         dim3(kTileNT), (unsigned)L.total, stream, X, ldx, (int)M, C, g, s, chan_src, thr, qmax, Xq, ldq,
+                         ksteps_main, rem, scale_out, L);
+}
+
 hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C, int g, int s,
                                   const int32_t* chan_src, const int32_t* chan_depth,
                                   const float* thr, float qmax, int8_t* Xq, int64_t ldq,
@@ -412,6 +623,20 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
     int64_t grid = 256 * 8;  // 8 workgroups of 4 waves on each of the 256 CUs
     if (tuning().act_grid > 0) grid = tuning().act_grid;
     if (grid > ceil_div(total, kThreads)) grid = ceil_div(total, kThreads);
+    // Static grid, un-scaled copies: the tile-ordered pass.  Measured against the flat orders below on
+    // the paper's layer shapes at batch 256 (inside the whole pass over the network): 4-17 % ahead for
+    // rows of X up to 256 values, and up to 576 on very tall X (the flat pass's gather lanes stall
+    // their waves there, and a row's end is written as a few scattered bytes); level or behind for
+    // 512-value rows on shorter X, level at 1152, behind from 1024-value 1x1 rows on.
+    // Two steps of look-ahead (level with one), one for rows of a single step.
+    const int tile_mode = tuning().act_tile;
+    if (thr != nullptr && partials == nullptr && !halve && tile_mode != 0 &&
+        tile_fits(M, K, (int64_t)s * g, ldq) &&
+        (tile_mode > 0 || ldq <= 320 || (ldq <= 768 && M >= 400000))) {
+        if (K < 128) return run_expand_quantize_tile<64, 2>(X, ldx, M, C, g, s, chan_src, thr, qmax, Xq, ldq, scale_out, stream);
+        return run_expand_quantize_tile<64, 3>(X, ldx, M, C, g, s, chan_src, thr, qmax, Xq, ldq, scale_out, stream);
+    }
+
     // Lanes dealt over the input when its rows allow it (see expand_quantize_in_kernel)
     const int Q = main_units, TD = D - Q;
     // Measured: it wins (up to 1.45x) once a quarter or more of a row's output dwords are

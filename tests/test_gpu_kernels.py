@@ -332,23 +332,49 @@ def test_mse_clip_threshold_degenerate_and_large():
                                      (77, 2048, 1, 205), (50, 64, 4, 300), (9, 512, 9, 26)])
 @pytest.mark.parametrize("halve", [False, True])
 @pytest.mark.parametrize("threshold", [None, 3.0])
-@pytest.mark.parametrize("act_map", [0, 1, 2, 3, 4, 5])   # lanes over the output / the input; +2: 64-bit indices;
-def test_split_act(M, C, g, s, halve, threshold, act_map):  # +4: Eq. 4's depths from the per-column table in LDS
+@pytest.mark.parametrize("act_map", [0, 1, 2, 3, 4, 5, 6])   # lanes over the output / the input; +2: 64-bit indices;
+def test_split_act(M, C, g, s, halve, threshold, act_map):  # +4: Eq. 4's depths from the per-column table in LDS;
+    # 6: the tile-ordered pass wherever it serves the case (static grid, un-scaled copies, rows from 64 values)
     rng = np.random.default_rng(M + C + g + s)
     X = _tensor(rng, M, C * g, "heavy")
     sel = ref.split_weights(X if halve else _tensor(rng, 9, C * g, "heavy"), C, g, s)
     cs, cd = sel["chan_src"], (sel["chan_depth"] if halve else None)
     ldq = B.ocs_padded_cols((C + s) * g)
     q_ref, s_ref, _ = ref.split_act(X, C, g, cs, cd, s, 8, threshold=threshold, clip_ratio=0.9, ldq=ldq)
-    B.ocs_tune("act_map", act_map & 1)
-    B.ocs_tune("act_wide", (act_map >> 1) & 1)
-    B.ocs_tune("act_dep", act_map >> 2)
+    B.ocs_tune("act_tile", 1 if act_map == 6 else 0)
+    if act_map < 6:
+        B.ocs_tune("act_map", act_map & 1)
+        B.ocs_tune("act_wide", (act_map >> 1) & 1)
+        B.ocs_tune("act_dep", act_map >> 2)
     try:
         q, sc = gpu_split_act(X, C, g, cs, cd, s, 8, threshold=threshold, clip_ratio=0.9)
     finally:
         B.ocs_tune("act_map", -1)
         B.ocs_tune("act_wide", 0)
         B.ocs_tune("act_dep", -1)
+        B.ocs_tune("act_tile", -1)
+    assert np.array_equal(sc, s_ref)
+    assert np.array_equal(q, q_ref)
+
+
+@pytest.mark.parametrize("M,C,g,s,ld_extra", [(64, 64, 1, 0, 0), (65, 64, 1, 4, 0), (300, 3, 49, 1, 0), (130, 67, 1, 5, 48),
+                                              (257, 256, 1, 13, 112), (100, 128, 9, 7, 0), (63, 191, 1, 64, 16),
+                                              (70, 13, 9, 2, 64), (200, 512, 4, 26, 0), (90, 64, 4, 200, 0)])
+@pytest.mark.parametrize("tile", [0, 1])
+def test_split_act_tile_order(M, C, g, s, ld_extra, tile):
+    """The tile-ordered pass against the oracle (and so against the flat pass, run on the same cases):
+    left-over columns, ragged last row tile, pitches beyond the recommended one (zero padding up to
+    the pitch), a split list with repeats."""
+    rng = np.random.default_rng(M * 7 + C + g + s)
+    X = _tensor(rng, M, C * g, "heavy")
+    sel = ref.split_weights(_tensor(rng, 9, C * g, "heavy"), C, g, s)
+    ldq = B.ocs_padded_cols((C + s) * g) + ld_extra
+    q_ref, s_ref, _ = ref.split_act(X, C, g, sel["chan_src"], None, s, 8, threshold=2.0, ldq=ldq)
+    B.ocs_tune("act_tile", tile)
+    try:
+        q, sc = gpu_split_act(X, C, g, sel["chan_src"], None, s, 8, threshold=2.0, ldq=ldq)
+    finally:
+        B.ocs_tune("act_tile", -1)
     assert np.array_equal(sc, s_ref)
     assert np.array_equal(q, q_ref)
 
