@@ -43,8 +43,19 @@ STATIC_T = 5.0               # the static activation grid's range (inputs are |N
 # reads for the plain copy kernel of known size that runs after the timed region
 # (profiles/bench_config5_headline.md).  Valid only for the kernel source it was measured on:
 # reported as null once that file changes.
-X2_TRAFFIC = {"quantize_hip_sha256": "e4b00290ce5f0e4d47eb2ead7216ec36be510a4bcaadc414826768850f23a359",
-              "bytes_per_step": 29930174715}
+X2_TRAFFIC = {"quantize_hip_sha256": "ca888310f224a3893a64f838459a8fb762110aa5d20fd9bd37757b20a57fae9b",
+              "bytes_per_step": 29206800679}
+
+
+# The same for the launches of the one-launch pass (`--extras fused`), keyed on the GEMM source.
+FUSED_TRAFFIC = {"qgemm_hip_sha256": "8b40458b3252ba7c9d8798e2a22fa46985c9c57e5006214c295e74f66e2b8d15",
+                 "bytes_per_step": 22972960017}
+
+
+def fused_traffic():
+    src = os.path.join(ROOT, "paper_1901_09504_amd", "csrc", "qgemm.hip")
+    digest = hashlib.sha256(open(src, "rb").read()).hexdigest()
+    return FUSED_TRAFFIC["bytes_per_step"] if digest == FUSED_TRAFFIC["qgemm_hip_sha256"] else None
 
 
 def x2_traffic():
@@ -557,7 +568,7 @@ def main():
                    "stamped_steps": n_stamp},
         "gemm_tops": gemm_tops, "gemm_pct_mfma_peak": 100.0 * gemm_tops / INT8_PEAK_TOPS,
         "split_quant_gbps": x2_gbs, "split_quant_pct_hbm": 100.0 * x2_gbs / HBM_PEAK_GBS,
-        "roofline": {"kernel": "expand_quantize_kernel / expand_quantize_in_kernel (ocs_split_act, X2): the 53 "
+        "roofline": {"kernel": "expand_quantize_tile_kernel / expand_quantize_kernel / expand_quantize_in_kernel (ocs_split_act, X2): the 53 "
                                "launches of one pass", "bound": "hbm",
                      "achieved": x2_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": x2_gbs / HBM_PEAK_GBS,
                      "traffic": None if x2_traffic() is None else x2_traffic() / len(layers),
@@ -593,8 +604,22 @@ def main():
                 frows.append({"layer": l.name, "M": l.M, "K": l.K, "N": l.N, "fused_us": round(us, 2),
                               "two_launch_us": round(rows[i]["split_quant_us"] + rows[i]["gemm_us"], 2),
                               "GBps": round(byt / us / 1e3, 1), "frac_hbm": round(byt / us / 1e3 / HBM_PEAK_GBS, 4)})
-        out["fused_split_gemm"] = {"ms_per_step": f_ms, "tops_whole_step": ops / f_ms / 1e9, "steps": 10,
-                                   "layers_fused": int(sum(fmap)), "layers": frows}
+        f_bytes = sum(4.0 * l.M * l.K + 1.0 * l.N * L.Ke + 4.0 * l.M * l.N
+                      for l, L, f in zip(layers, net.L, fmap) if f)
+        f_us = float(np.mean(gmf[:, np.array(fmap)].sum(axis=1)))
+        out["fused_split_gemm"] = {
+            "what": "the same pass with ocs_split_act_qgemm (split+quantize and GEMM as one launch, no code tensor "
+                    "in memory) on every layer where the library expects it to be ahead; the other layers as above",
+            "ms_per_step": f_ms, "tops_whole_step": ops / f_ms / 1e9, "steps": 10, "layers_fused": int(sum(fmap)),
+            "roofline": {"kernel": "split_act_qgemm_kernel: its launches of one pass", "bound": "hbm",
+                         "achieved": f_bytes / f_us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": f_bytes / f_us / 1e3 / HBM_PEAK_GBS,
+                         "traffic": None if fused_traffic() is None else fused_traffic() / int(sum(fmap)),
+                         "traffic_bytes_per_step": fused_traffic(),
+                         "algorithmic_bytes_per_step": f_bytes, "bytes_per_unit": "4*M*K + N*K' + 4*M*N per layer",
+                         "kernel_us_per_step": f_us, "avg_launch_us": f_us / int(sum(fmap)),
+                         "launches_per_step": int(sum(fmap)), "launches_timed": int(gmf[:, np.array(fmap)].size)},
+            "layers": frows}
     if "steps" in extras:
         # the pass with a per-batch activation grid: X1 (max|X|) in front of every split+quantize
         dyn_ms = timed(5, dynamic=True, side=side)
