@@ -410,15 +410,20 @@ def ceilings(torch, B, reps=5):
                 best = (us, wgs)
         return best
 
-    grids = (256, 512, 1024, 2048, 4096, 8192)
-    us, wgs = best_of(lambda w: B.ocs_calib_copy(a, b, n, w), grids)
-    out["copy"] = {"us": us, "workgroups": wgs, "read_plus_write_GBps": 2.0 * n / us / 1e3,
-                   "frac_hbm": 2.0 * n / us / 1e3 / HBM_PEAK_GBS}
-    us, wgs = best_of(lambda w: B.ocs_calib_read(a, n, 1, w, sink), grids)
-    out["read"] = {"us": us, "workgroups": wgs, "GBps": n / us / 1e3, "frac_hbm": n / us / 1e3 / HBM_PEAK_GBS}
+    # each kernel in its one-shot form (one 16-byte group per lane, a workgroup per 4 KB, no loop:
+    # "workgroups": 0) and as a grid-stride loop with the best of several grid sizes
+    grids = (256, 512, 1024, 2048, 4096)
+    def both(fn, nbytes, key, rate_key):
+        us0 = _timed(torch, lambda: fn(0), reps)
+        usl, wgs = best_of(fn, grids)
+        out[key] = {"us": us0, "workgroups": 0, rate_key: nbytes / us0 / 1e3, "frac_hbm": nbytes / us0 / 1e3 / HBM_PEAK_GBS,
+                    "grid_stride_loop": {"us": usl, "workgroups": wgs, rate_key: nbytes / usl / 1e3,
+                                         "frac_hbm": nbytes / usl / 1e3 / HBM_PEAK_GBS}}
+    both(lambda w: B.ocs_calib_copy(a, b, n, w), 2.0 * n, "copy", "read_plus_write_GBps")
+    both(lambda w: B.ocs_calib_pack(a, b, n, w), 1.25 * n, "pack_16B_in_4B_out", "read_plus_write_GBps")
+    both(lambda w: B.ocs_calib_read(a, n, 1, w, sink), 1.0 * n, "read", "GBps")
     for key, nt in (("fill", 0), ("fill_nontemporal", 1)):
-        us, wgs = best_of(lambda w: B.ocs_calib_fill(b, n, 7, nt, w), grids)
-        out[key] = {"us": us, "workgroups": wgs, "GBps": n / us / 1e3, "frac_hbm": n / us / 1e3 / HBM_PEAK_GBS}
+        both(lambda w: B.ocs_calib_fill(b, n, 7, nt, w), 1.0 * n, key, "GBps")
     small, passes = 2 << 20, 4096
     l2 = {}
     for wgs in (250, 500, 1000, 2000):

@@ -449,38 +449,44 @@ int ocs_time_next(int family, void *start_event, void *stop_event);
 
 /*
  * Measurement helper (no passage of the paper): a plain device-to-device copy of `bytes`
- * bytes (multiple of 16, both pointers 16-byte aligned) with 16-byte accesses by `workgroups`
- * workgroups of 256 lanes (0: 2048).  Profiling runs use it to scale HBM byte counters against a
- * transfer of known size.
+ * bytes (multiple of 16, both pointers 16-byte aligned) with 16-byte accesses, as a grid-stride
+ * loop of `workgroups` workgroups of 256 lanes, or, with workgroups == 0, in the one-shot form:
+ * one 16-byte group per lane, one workgroup per 4 KB, no loop (the form the chip streams
+ * fastest; the split+quantize pass is built the same way).  Profiling runs use the copy to scale
+ * HBM byte counters against a transfer of known size.
  */
 int ocs_calib_copy(const void *src, void *dst, size_t bytes, int workgroups, void *stream);
 
 /*
  * Further measurement helpers (no passage of the paper; the path never calls them): plain kernels
- * of known work whose rates are this chip's own ceilings for the kernels of the path.
+ * of known work whose rates are this chip's own ceilings for the kernels of the path.  workgroups
+ * == 0 selects the one-shot form everywhere (see ocs_calib_copy).
+ *   ocs_calib_pack: the split+quantize pass's traffic pattern without its arithmetic: 16 bytes read
+ *        and 4 written per lane (`bytes` = bytes read, multiple of 16; dst holds bytes / 4).
  *   ocs_calib_read: `passes` read-only sweeps with 16-byte loads over `bytes` bytes at src
- *        (multiple of 16, 16-byte aligned; with passes > 1 a power of two) by `workgroups` workgroups
- *        of 256 lanes.  A buffer far
- *        larger than the caches with one pass gives the HBM read rate; a buffer of a megabyte or
- *        two with many passes stays in every L2 and gives the rate at which the compute units draw
- *        from their L2s.  sink: device int32 [workgroups] (practically never written).
+ *        (multiple of 16, 16-byte aligned; with passes > 1 a power of two, and workgroups >= 1).
+ *        A buffer far larger than the caches with one pass gives the HBM read rate; a buffer of a
+ *        megabyte or two with many passes stays in every L2 and gives the rate at which the compute
+ *        units draw from their L2s.  sink: device int32 [max(workgroups, 1)] (practically never
+ *        written).
  *   ocs_calib_fill: writes `bytes` bytes at dst with 16-byte stores of `value` (nontemporal != 0:
- *        with the streaming hint) by `workgroups` workgroups of 256 lanes.
- *   ocs_calib_mfma: `workgroups` workgroups of 4 waves; every wave issues iters * 4 instructions
- *        v_mfma_i32_32x32x32_i8 (the GEMM's) on fragments taken from `operands` (device, 16 KB,
- *        16-byte aligned: zeros, a constant, or random bytes), with no memory access inside the
- *        loop: workgroups * 4 * iters * 4 * 65536 integer operations per launch.
+ *        with the streaming hint).
+ *   ocs_calib_mfma: `workgroups` (>= 1) workgroups of 4 waves; every wave issues iters * 4
+ *        instructions v_mfma_i32_32x32x32_i8 (the GEMM's) on fragments taken from `operands`
+ *        (device, 16 KB, 16-byte aligned: zeros, a constant, or random bytes), with no memory access
+ *        inside the loop: workgroups * 4 * iters * 4 * 65536 integer operations per launch.
  *        sink: device int32 [workgroups * 256], written.
  * All are asynchronous on `stream`; time them with events around the call.
  */
+int ocs_calib_pack(const void *src, void *dst, size_t bytes, int workgroups, void *stream);
 int ocs_calib_read(const void *src, size_t bytes, int passes, int workgroups, void *sink, void *stream);
 int ocs_calib_fill(void *dst, size_t bytes, int value, int nontemporal, int workgroups, void *stream);
 int ocs_calib_mfma(const void *operands, int iters, int workgroups, void *sink, void *stream);
 
 /*
  * Launch-shape overrides for benchmarking (no passage of the paper; results never depend
- * on them).  Keys: "act_grid", "act_nt", "act_un", "act_map", "act_wide", "act_dep", "act_tile"
- * (the split+quantize pass; act_tile: the tile-ordered variant never (0) / wherever it fits (1)), "max_flat", "max_grid", "max_un", "max_bt" (the whole-tensor max|x|
+ * on them).  Keys: "act_grid", "act_nt", "act_un", "act_map", "act_wide", "act_dep", "act_tile", "act_np"
+ * (the split+quantize pass; act_tile: the tile-ordered variant never (0) / wherever it fits (1); act_np: the one-shot variant never (0) / with 1..8 loads per lane wherever they hold a row (1..8) / by shape (9 or default)), "max_flat", "max_grid", "max_un", "max_bt" (the whole-tensor max|x|
  * pass), "sel_inline" (most splits for which ocs_split_weights runs the selection inside its
  * code pass instead of as a launch of its own; 0: never), "gemm_tile" (tile variant of
  * ocs_qgemm / ocs_qconv: 6, 7, 9, 10, 11, 12, 14, 16, 17, 18, 19, 23, 24; an id a shape cannot use falls

@@ -111,6 +111,8 @@ def lib():
     L.ocs_time_next.argtypes = [_i32, _vp, _vp]
     L.ocs_calib_copy.restype = _i32
     L.ocs_calib_copy.argtypes = [_vp, _vp, _sz, _i32, _vp]
+    L.ocs_calib_pack.restype = _i32
+    L.ocs_calib_pack.argtypes = [_vp, _vp, _sz, _i32, _vp]
     L.ocs_calib_read.restype = _i32
     L.ocs_calib_read.argtypes = [_vp, _sz, _i32, _i32, _vp, _vp]
     L.ocs_calib_fill.restype = _i32
@@ -192,12 +194,17 @@ def ocs_calib_copy(src, dst, nbytes, workgroups=0, stream=None):
            "ocs_calib_copy")
 
 
+def ocs_calib_pack(src, dst, nbytes, workgroups=0, stream=None):
+    _check(lib().ocs_calib_pack(_ptr(src), _ptr(dst), int(nbytes), int(workgroups), _stream(stream)),
+           "ocs_calib_pack")
+
+
 def ocs_calib_read(src, nbytes, passes, workgroups, sink, stream=None):
     _check(lib().ocs_calib_read(_ptr(src), int(nbytes), int(passes), int(workgroups), _ptr(sink),
                                 _stream(stream)), "ocs_calib_read")
 
 
-def ocs_calib_fill(dst, nbytes, value, nontemporal=0, workgroups=2048, stream=None):
+def ocs_calib_fill(dst, nbytes, value, nontemporal=0, workgroups=0, stream=None):
     _check(lib().ocs_calib_fill(_ptr(dst), int(nbytes), int(value), int(nontemporal), int(workgroups),
                                 _stream(stream)), "ocs_calib_fill")
 

@@ -15,9 +15,50 @@ __global__ __launch_bounds__(kThreads) void calib_copy_kernel(const f32x4* __res
     for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+// The same work with no loop: one 16-byte group per lane, one workgroup per 4 KB, handed out in
+// order by the dispatcher (workgroups == 0 in the calls below selects this form).
+__global__ __launch_bounds__(kThreads) void calib_copy_shot_kernel(const f32x4* __restrict__ src,
+                                                                   f32x4* __restrict__ dst, size_t n16) {
+    const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < n16) dst[i] = src[i];
+}
+
+static unsigned shot_grid(size_t n16) { return (unsigned)((n16 + kThreads - 1) / kThreads); }
+
 hipError_t launch_calib_copy(const void* src, void* dst, size_t bytes, int workgroups, hipStream_t stream) {
-    calib_copy_kernel<<<(unsigned)workgroups, kThreads, 0, stream>>>(static_cast<const f32x4*>(src),
-                                                     static_cast<f32x4*>(dst), bytes / 16);
+    if (workgroups == 0)
+        calib_copy_shot_kernel<<<shot_grid(bytes / 16), kThreads, 0, stream>>>(static_cast<const f32x4*>(src),
+                                                                               static_cast<f32x4*>(dst), bytes / 16);
+    else
+        calib_copy_kernel<<<(unsigned)workgroups, kThreads, 0, stream>>>(static_cast<const f32x4*>(src),
+                                                                         static_cast<f32x4*>(dst), bytes / 16);
+    return hipGetLastError();
+}
+
+// The split+quantize pass's traffic pattern without its arithmetic: 16 bytes read and 4 written per
+// lane (the low byte of each of the four words), in the one-shot form or as a grid-stride loop.
+__device__ __forceinline__ unsigned low_bytes(const i32x4& v) {
+    return ((unsigned)v[0] & 0xFFu) | (((unsigned)v[1] & 0xFFu) << 8) | (((unsigned)v[2] & 0xFFu) << 16) |
+           ((unsigned)v[3] << 24);
+}
+__global__ __launch_bounds__(kThreads) void calib_pack_shot_kernel(const i32x4* __restrict__ src,
+                                                                   unsigned* __restrict__ dst, size_t n16) {
+    const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < n16) dst[i] = low_bytes(src[i]);
+}
+__global__ __launch_bounds__(kThreads) void calib_pack_kernel(const i32x4* __restrict__ src,
+                                                              unsigned* __restrict__ dst, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += stride) dst[i] = low_bytes(src[i]);
+}
+
+hipError_t launch_calib_pack(const void* src, void* dst, size_t bytes, int workgroups, hipStream_t stream) {
+    if (workgroups == 0)
+        calib_pack_shot_kernel<<<shot_grid(bytes / 16), kThreads, 0, stream>>>(static_cast<const i32x4*>(src),
+                                                                               static_cast<unsigned*>(dst), bytes / 16);
+    else
+        calib_pack_kernel<<<(unsigned)workgroups, kThreads, 0, stream>>>(static_cast<const i32x4*>(src),
+                                                                         static_cast<unsigned*>(dst), bytes / 16);
     return hipGetLastError();
 }
 
@@ -44,9 +85,22 @@ __global__ __launch_bounds__(kThreads) void calib_read_kernel(const i32x4* __res
     if (acc == 0x5a5a1234) sink[blockIdx.x] = acc;
 }
 
+__global__ __launch_bounds__(kThreads) void calib_read_shot_kernel(const i32x4* __restrict__ src, size_t n16,
+                                                                   int* __restrict__ sink) {
+    const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n16) return;
+    const i32x4 a = src[i];
+    if ((a[0] ^ a[1] ^ a[2] ^ a[3]) == 0x5a5a1234) sink[0] = 1;
+}
+
 hipError_t launch_calib_read(const void* src, size_t bytes, int passes, int workgroups, void* sink,
                              hipStream_t stream) {
     const size_t n16 = bytes / 16;
+    if (workgroups == 0) {     // one pass, one-shot form
+        calib_read_shot_kernel<<<shot_grid(n16), kThreads, 0, stream>>>(static_cast<const i32x4*>(src), n16,
+                                                                        static_cast<int*>(sink));
+        return hipGetLastError();
+    }
     // one pass: no wrap (mask of all ones); several: n16 is a power of two and the index wraps
     const size_t mask = passes > 1 ? n16 - 1 : ~(size_t)0;
     calib_read_kernel<<<(unsigned)workgroups, kThreads, 0, stream>>>(static_cast<const i32x4*>(src), n16,
@@ -66,8 +120,26 @@ __global__ __launch_bounds__(kThreads) void calib_fill_kernel(i32x4* __restrict_
     }
 }
 
+template <bool NT>
+__global__ __launch_bounds__(kThreads) void calib_fill_shot_kernel(i32x4* __restrict__ dst, size_t n16, int value) {
+    const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    const i32x4 v = {value, value, value, value};
+    if (i < n16) {
+        if (NT) __builtin_nontemporal_store(v, dst + i);
+        else dst[i] = v;
+    }
+}
+
 hipError_t launch_calib_fill(void* dst, size_t bytes, int value, int nontemporal, int workgroups,
                              hipStream_t stream) {
+    if (workgroups == 0) {
+        const unsigned sg = shot_grid(bytes / 16);
+        if (nontemporal)
+            calib_fill_shot_kernel<true><<<sg, kThreads, 0, stream>>>(static_cast<i32x4*>(dst), bytes / 16, value);
+        else
+            calib_fill_shot_kernel<false><<<sg, kThreads, 0, stream>>>(static_cast<i32x4*>(dst), bytes / 16, value);
+        return hipGetLastError();
+    }
     const unsigned g = (unsigned)workgroups;
     if (nontemporal)
         calib_fill_kernel<true><<<g, kThreads, 0, stream>>>(static_cast<i32x4*>(dst), bytes / 16, value);

@@ -702,14 +702,26 @@ int ocs_calib_copy(const void* src, void* dst, size_t bytes, int workgroups, voi
     if (!src || !dst) return OCS_E_NULL;
     if (bytes == 0 || bytes % 16 != 0 || workgroups < 0 || workgroups > 65536) return OCS_E_SHAPE;
     if (!aligned(src, 16) || !aligned(dst, 16)) return OCS_E_ALIGN;
-    hipError_t e = launch_calib_copy(src, dst, bytes, workgroups ? workgroups : 2048, static_cast<hipStream_t>(stream));
+    if (bytes / 16 / 256 > 0x7FFFFFFFull) return OCS_E_SHAPE;
+    hipError_t e = launch_calib_copy(src, dst, bytes, workgroups, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    return OCS_OK;
+}
+
+int ocs_calib_pack(const void* src, void* dst, size_t bytes, int workgroups, void* stream) {
+    if (!src || !dst) return OCS_E_NULL;
+    if (bytes == 0 || bytes % 16 != 0 || workgroups < 0 || workgroups > 65536) return OCS_E_SHAPE;
+    if (bytes / 16 / 256 > 0x7FFFFFFFull) return OCS_E_SHAPE;
+    if (!aligned(src, 16) || !aligned(dst, 4)) return OCS_E_ALIGN;
+    hipError_t e = launch_calib_pack(src, dst, bytes, workgroups, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e);
     return OCS_OK;
 }
 
 int ocs_calib_read(const void* src, size_t bytes, int passes, int workgroups, void* sink, void* stream) {
     if (!src || !sink) return OCS_E_NULL;
-    if (bytes == 0 || bytes % 16 != 0 || passes < 1 || workgroups < 1 || workgroups > 65536) return OCS_E_SHAPE;
+    if (bytes == 0 || bytes % 16 != 0 || passes < 1 || workgroups < 0 || workgroups > 65536) return OCS_E_SHAPE;
+    if (workgroups == 0 && (passes != 1 || bytes / 16 / 256 > 0x7FFFFFFFull)) return OCS_E_SHAPE;
     if (passes > 1 && ((bytes / 16) & (bytes / 16 - 1)) != 0) return OCS_E_SHAPE;   // the stream wraps by masking
     if (!aligned(src, 16) || !aligned(sink, 4)) return OCS_E_ALIGN;
     hipError_t e = launch_calib_read(src, bytes, passes, workgroups, sink, static_cast<hipStream_t>(stream));
@@ -719,7 +731,8 @@ int ocs_calib_read(const void* src, size_t bytes, int passes, int workgroups, vo
 
 int ocs_calib_fill(void* dst, size_t bytes, int value, int nontemporal, int workgroups, void* stream) {
     if (!dst) return OCS_E_NULL;
-    if (bytes == 0 || bytes % 16 != 0 || workgroups < 1 || workgroups > 65536) return OCS_E_SHAPE;
+    if (bytes == 0 || bytes % 16 != 0 || workgroups < 0 || workgroups > 65536) return OCS_E_SHAPE;
+    if (bytes / 16 / 256 > 0x7FFFFFFFull) return OCS_E_SHAPE;
     if (!aligned(dst, 16)) return OCS_E_ALIGN;
     hipError_t e = launch_calib_fill(dst, bytes, value, nontemporal, workgroups, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e);
@@ -744,6 +757,7 @@ int ocs_tune(const char* key, int value) {
     else if (!strcmp(key, "act_wide")) t.act_wide = value < 0 ? 0 : value;
     else if (!strcmp(key, "act_map")) t.act_map = value;
     else if (!strcmp(key, "act_tile")) t.act_tile = value;
+    else if (!strcmp(key, "act_np")) t.act_np = value;
     else if (!strcmp(key, "gemm_tile")) t.gemm_tile = value;
     else if (!strcmp(key, "fused_variant")) t.fused_variant = value;
     else if (!strcmp(key, "max_flat")) t.max_flat = value;

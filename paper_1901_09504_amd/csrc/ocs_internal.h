@@ -181,6 +181,7 @@ hipError_t launch_tap_major(const int8_t* Wq, int64_t ldq, int64_t N, int E, int
 
 // 16-byte copy of `bytes` (multiple of 16) device bytes: counter calibration only.
 hipError_t launch_calib_copy(const void* src, void* dst, size_t bytes, int workgroups, hipStream_t stream);
+hipError_t launch_calib_pack(const void* src, void* dst, size_t bytes, int workgroups, hipStream_t stream);
 // The other measurement kernels (csrc/calib.hip): read-only sweep (passes over the same buffer),
 // fill, bare matrix-core loop.
 hipError_t launch_calib_read(const void* src, size_t bytes, int passes, int workgroups, void* sink,
@@ -270,6 +271,7 @@ struct Tuning {
     int act_wide = 0;   // force the 64-bit index variant of that pass (tests: tensors of 2^32 dwords do not fit a test)
     int act_dep = -1;   // Eq. 4 pass: per-column depths from a table in LDS (1), from global memory (0), by tensor size (-1)
     int act_nt = 0;     // non-temporal loads of X in that pass (off: appended columns re-read X through L2)
+    int act_np = -1;    // static grid, un-scaled copies: the loop-free flat pass with this many pieces per XCD run (> 0), never (0), by shape (-1)
     int act_tile = -1;  // static grid, un-scaled copies: tile-ordered pass always (1), never (0), by shape (-1)
     int gemm_tile = -1;
     int fused_variant = -1;  // workgroup shape / pipeline depth of the split+quantize+GEMM launch (default: by shape)

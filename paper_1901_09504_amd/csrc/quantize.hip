@@ -261,6 +261,162 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The pass in one shot, for a static grid with un-scaled copies (the activation side of Eq. 3): a
+// workgroup takes R whole rows (a few KB of X), requests all of its input at once (U 16-byte loads
+// per lane), turns it into codes, and is done: no loop, no look-ahead registers, one barrier.  The
+// chip's dispatcher hands such workgroups out in order, so the chip works inside one tight window
+// that slides over X, tighter than persistent workgroups keep it (they drift apart): a plain copy
+// written this way moves 6.1 TB/s on this chip against 5.5 TB/s for the grid-stride form, and this
+// pass's 4:1 pattern 6.3 against 5.2.
+//   Main items: dword d < Qc = ceil(K/4) of a row, 16 bytes of X each; their codes go straight to
+//   memory (d < Q = floor(K/4)) and into an image of the rows in LDS.
+//   Tail: dwords Q .. D-1 of a row (left-over columns of X, the appended columns, zero padding)
+//   are assembled afterwards from the image, byte by byte: the copy of a column is the code just
+//   written, so the appended columns cost no second trip to memory.  Their source columns do not
+//   depend on the row: a table of 4 * TD entries, looked up in chan_src behind the requests for X.
+// ---------------------------------------------------------------------------------------------
+constexpr int kShotNT = 256;
+constexpr int kShotTabPer = 2;                       // table entries per lane
+constexpr int kShotMaxTail = kShotNT * kShotTabPer;  // tail columns 4 * TD served
+
+template <int U>
+__global__ __launch_bounds__(kShotNT) void expand_quantize_shot_kernel(
+    const float* __restrict__ X, int64_t ldx, int M, int C, int g, int s,
+    const int32_t* __restrict__ chan_src, const float* __restrict__ thr, float qmax,
+    int8_t* __restrict__ Xq, int64_t ldq, int R, unsigned magic_qc, unsigned magic_td,
+    float* __restrict__ scale_out) {
+    extern __shared__ __align__(16) int8_t slds[];
+    const int K = C * g, Q = K / 4, rem = K - 4 * Q, Qc = Q + (rem > 0 ? 1 : 0);
+    const int D = (int)(ldq / 4), TD = D - Q, Ke = (C + s) * g;
+    const int P = (int)ldq + 4;                       // image pitch: consecutive rows start one bank apart
+    int8_t* img = slds;
+    int* tcol = reinterpret_cast<int*>(slds + ((R * P + 15) & ~15));
+    const int tid = (int)threadIdx.x;
+    const int row0 = (int)blockIdx.x * R;
+    const int rows = M - row0 < R ? M - row0 : R;
+
+    // the table's look-ups first: they come back from the L2 while the rows are on their way
+    int tsrc[kShotTabPer];
+#pragma unroll
+    for (int i = 0; i < kShotTabPer; ++i) {
+        const int k = 4 * Q + tid + i * kShotNT;
+        const bool app = k >= K && k < Ke;
+        tsrc[i] = chan_src[app ? k / g : 0];
+    }
+    // main items: item i = (row i / Qc, dword i % Qc)
+    f32x4 v[U];
+    int r_[U], d_[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int i = tid + u * kShotNT;
+        unsigned q = __umulhi((unsigned)i, magic_qc);           // floor(i / Qc), at most one low
+        unsigned d = (unsigned)i - q * (unsigned)Qc;
+        if (d >= (unsigned)Qc) { ++q; d -= (unsigned)Qc; }
+        const bool ok = (int)q < rows;
+        r_[u] = ok ? (int)q : -1;
+        d_[u] = (int)d;
+        // a row's last dword may hold fewer than four columns of X: it is fetched as the row's last
+        // four floats and shifted into place when used (nothing is read past the row)
+        const float* src = X + (int64_t)(row0 + (ok ? (int)q : 0)) * ldx + (ok ? ((int)d < Q ? 4 * (int)d : K - 4) : 0);
+        v[u] = *reinterpret_cast<const f32x4u*>(src);
+    }
+#pragma unroll
+    for (int i = 0; i < kShotTabPer; ++i) {
+        const int e = tid + i * kShotNT, k = 4 * Q + e;
+        if (e < 4 * TD) {
+            int col = -1;
+            if (k < K) col = k;
+            else if (k < Ke) {
+                const int j = k / g, t = k - j * g;
+                const int c = tsrc[i] < 0 ? 0 : (tsrc[i] >= C ? C - 1 : tsrc[i]);
+                col = c * g + t;
+            }
+            tcol[e] = col;
+        }
+    }
+    const float T = *thr;
+    const float inv = inv_step_of(T, qmax);
+    if (scale_out != nullptr && blockIdx.x == 0 && tid == 0) {
+        scale_out[0] = T;
+        scale_out[1] = T / qmax;
+    }
+    unsigned* __restrict__ out = reinterpret_cast<unsigned*>(Xq);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (r_[u] < 0) continue;
+        unsigned q4 = pack4(code_bits(v[u][0], inv, qmax), code_bits(v[u][1], inv, qmax),
+                            code_bits(v[u][2], inv, qmax), code_bits(v[u][3], inv, qmax));
+        if (d_[u] < Q) out[(int64_t)(row0 + r_[u]) * D + d_[u]] = q4;
+        else q4 >>= 8 * (4 - rem);                     // columns 4Q .. K-1 are the fetched elements 4-rem .. 3
+        *reinterpret_cast<unsigned*>(img + r_[u] * P + 4 * d_[u]) = q4;
+    }
+    __syncthreads();
+    for (int it = tid; it < rows * TD; it += kShotNT) {
+        unsigned r = __umulhi((unsigned)it, magic_td);          // floor(it / TD), at most one low
+        unsigned td = (unsigned)it - r * (unsigned)TD;
+        if (td >= (unsigned)TD) { ++r; td -= (unsigned)TD; }
+        const i32x4 cols = *reinterpret_cast<const i32x4*>(&tcol[4 * td]);
+        const int8_t* irow = img + (int)r * P;
+        unsigned q4 = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const unsigned byte = (unsigned)(unsigned char)irow[cols[e] < 0 ? 0 : cols[e]];
+            q4 |= (cols[e] < 0 ? 0u : byte) << (8 * e);
+        }
+        out[(int64_t)(row0 + (int)r) * D + Q + (int)td] = q4;
+    }
+}
+
+struct ShotPlan {
+    int U = 0, R = 0;
+};
+// Rows per workgroup and loads per lane.  Measured on the paper's layer shapes at batch 256: a
+// workgroup is fastest with about 512 main items (two loads per lane, 8 KB of X); rows too long
+// for two of them to fit take three loads' worth (e.g. two rows of 288 items), and a single long
+// row whatever it needs, up to 8 loads per lane.  force_u > 0: that many loads per lane, with as
+// many rows as they hold (tests and tuning).
+constexpr int kShotMaxU = 8;
+static ShotPlan shot_plan(int64_t M, int64_t K, int64_t ldq, int force_u = 0) {
+    ShotPlan p;
+    if (M < 1 || M > 0x7FFFFFFF - 4096 || K < 4 || K > 4 * kShotNT * kShotMaxU || ldq % 16 != 0) return p;
+    const int64_t Q = K / 4, Qc = (K + 3) / 4, TD = ldq / 4 - Q;
+    if (TD < 0 || 4 * TD > kShotMaxTail) return p;
+    int64_t R;
+    if (force_u > 0) {
+        R = (int64_t)kShotNT * force_u / Qc;
+        if (R < 1) return p;
+    } else {
+        R = 512 / Qc;
+        if (R * Qc < 448) R = 768 / Qc;
+        if (R < 1) R = 1;
+    }
+    if (R > 64) R = 64;
+    p.R = (int)R;
+    p.U = force_u > 0 ? force_u : (int)ceil_div(R * Qc, kShotNT);
+    if (p.U > kShotMaxU) p = ShotPlan{};
+    return p;
+}
+
+template <int U>
+static hipError_t run_expand_quantize_shot(const ShotPlan& p, const float* X, int64_t ldx, int64_t M, int C, int g,
+                                           int s, const int32_t* chan_src, const float* thr, float qmax, int8_t* Xq,
+                                           int64_t ldq, float* scale_out, hipStream_t stream) {
+    const int64_t K = (int64_t)C * g, Q = K / 4, Qc = (K + 3) / 4, TD = ldq / 4 - Q;
+    // floor(2^32 / n), or 2^32 - 1 for n = 1: the quotient estimate is then at most one low, which
+    // the kernel's correction step absorbs
+    auto magic_of = [](int64_t n) {
+        const uint64_t m = (((uint64_t)1) << 32) / (uint64_t)n;
+        return (unsigned)(m > 0xFFFFFFFFull ? 0xFFFFFFFFull : m);
+    };
+    const unsigned magic_qc = magic_of(Qc);
+    const unsigned magic_td = TD > 0 ? magic_of(TD) : 0u;
+    const unsigned lds = (unsigned)(((p.R * (ldq + 4) + 15) & ~(int64_t)15) + (TD > 0 ? 4 * TD : 1) * 4);
+    return launch_kernel(kTimeSplitQuantize, expand_quantize_shot_kernel<U>, dim3((unsigned)ceil_div(M, p.R)),
+                         dim3(kShotNT), lds, stream, X, ldx, (int)M, C, g, s, chan_src, thr, qmax, Xq, ldq, p.R,
+                         magic_qc, magic_td, scale_out);
+}
+
 // The same pass with the lanes dealt over the INPUT instead: one lane per 16-byte group of X,
 // the whole of X walked as one flat range, so every lane of every load instruction carries
 // data (in the output-ordered kernel above the lanes that land on appended columns and on the
@@ -623,6 +779,31 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
     int64_t grid = 256 * 8;  // 8 workgroups of 4 waves on each of the 256 CUs
     if (tuning().act_grid > 0) grid = tuning().act_grid;
     if (grid > ceil_div(total, kThreads)) grid = ceil_div(total, kThreads);
+    // Static grid, un-scaled copies: the one-shot pass wherever it serves the shape (measured against
+    // the tile-ordered and the flat passes below on the paper's layer shapes at batch 256: 1-13 % ahead
+    // on every one of them)
+    // (except rows of fewer than 256 values that are not whole 16-byte groups, the 7x7 stem's 147: a
+    // third of such a workgroup's items are tail dwords, and the tile-ordered pass below, which writes
+    // its image out in 16-byte pieces, is 6 % ahead there)
+    const int np_mode = tuning().act_np;
+    const bool odd_narrow = K % 4 != 0 && K < 256 && tile_fits(M, K, (int64_t)s * g, ldq);
+    if (thr != nullptr && partials == nullptr && !halve && chan_src != nullptr && np_mode != 0 && tuning().act_tile <= 0 &&
+        tuning().act_map < 0 && (np_mode > 0 || !odd_narrow)) {
+        const ShotPlan p = shot_plan(M, K, ldq, np_mode > 0 && np_mode <= kShotMaxU ? np_mode : 0);
+#define OCS_SHOT_ARGS p, X, ldx, M, C, g, s, chan_src, thr, qmax, Xq, ldq, scale_out, stream
+        switch (p.U) {
+            case 1: return run_expand_quantize_shot<1>(OCS_SHOT_ARGS);
+            case 2: return run_expand_quantize_shot<2>(OCS_SHOT_ARGS);
+            case 3: return run_expand_quantize_shot<3>(OCS_SHOT_ARGS);
+            case 4: return run_expand_quantize_shot<4>(OCS_SHOT_ARGS);
+            case 5: return run_expand_quantize_shot<5>(OCS_SHOT_ARGS);
+            case 6: return run_expand_quantize_shot<6>(OCS_SHOT_ARGS);
+            case 7: return run_expand_quantize_shot<7>(OCS_SHOT_ARGS);
+            case 8: return run_expand_quantize_shot<8>(OCS_SHOT_ARGS);
+            default: break;     // a shape it does not serve: the passes below
+        }
+#undef OCS_SHOT_ARGS
+    }
     // Static grid, un-scaled copies: the tile-ordered pass.  Measured against the flat orders below on
     // the paper's layer shapes at batch 256 (inside the whole pass over the network): 4-17 % ahead for
     // rows of X up to 256 values, and up to 576 on very tall X (the flat pass's gather lanes stall

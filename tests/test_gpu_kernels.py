@@ -342,6 +342,7 @@ def test_split_act(M, C, g, s, halve, threshold, act_map):  # +4: Eq. 4's depths
     ldq = B.ocs_padded_cols((C + s) * g)
     q_ref, s_ref, _ = ref.split_act(X, C, g, cs, cd, s, 8, threshold=threshold, clip_ratio=0.9, ldq=ldq)
     B.ocs_tune("act_tile", 1 if act_map == 6 else 0)
+    B.ocs_tune("act_np", 0)
     if act_map < 6:
         B.ocs_tune("act_map", act_map & 1)
         B.ocs_tune("act_wide", (act_map >> 1) & 1)
@@ -353,6 +354,7 @@ def test_split_act(M, C, g, s, halve, threshold, act_map):  # +4: Eq. 4's depths
         B.ocs_tune("act_wide", 0)
         B.ocs_tune("act_dep", -1)
         B.ocs_tune("act_tile", -1)
+        B.ocs_tune("act_np", -1)
     assert np.array_equal(sc, s_ref)
     assert np.array_equal(q, q_ref)
 
@@ -371,10 +373,38 @@ def test_split_act_tile_order(M, C, g, s, ld_extra, tile):
     ldq = B.ocs_padded_cols((C + s) * g) + ld_extra
     q_ref, s_ref, _ = ref.split_act(X, C, g, sel["chan_src"], None, s, 8, threshold=2.0, ldq=ldq)
     B.ocs_tune("act_tile", tile)
+    B.ocs_tune("act_np", 0)
     try:
         q, sc = gpu_split_act(X, C, g, sel["chan_src"], None, s, 8, threshold=2.0, ldq=ldq)
     finally:
         B.ocs_tune("act_tile", -1)
+        B.ocs_tune("act_np", -1)
+    assert np.array_equal(sc, s_ref)
+    assert np.array_equal(q, q_ref)
+
+
+@pytest.mark.parametrize("M,C,g,s,ld_extra", [(64, 64, 1, 0, 0), (65, 64, 1, 4, 0), (300, 3, 49, 1, 0), (130, 67, 1, 5, 48),
+                                              (257, 256, 1, 13, 112), (100, 128, 9, 7, 0), (63, 191, 1, 64, 16),
+                                              (70, 13, 9, 2, 64), (200, 512, 4, 26, 0), (90, 64, 4, 100, 0),
+                                              (5, 1, 4, 0, 0), (3, 5, 1, 1, 0), (1000, 16, 1, 1, 0), (37, 512, 9, 26, 0),
+                                              (21, 2048, 4, 60, 0), (19, 1250, 1, 100, 32)])
+@pytest.mark.parametrize("loads", [-1, 1, 2, 3, 4, 5, 6, 7, 8])
+def test_split_act_one_shot(M, C, g, s, ld_extra, loads):
+    """The one-shot pass (whole rows per workgroup, all loads at once, tail from the codes in LDS)
+    against the oracle: by shape (-1) and with every number of loads per lane forced (a shape that a
+    given count cannot hold falls to the other passes, and is compared all the same): left-over
+    columns (K % 4), rows at odd alignment, a ragged last workgroup, fewer rows than a workgroup
+    takes, pitches beyond the recommended one, copies of copies' sources, the longest rows served."""
+    rng = np.random.default_rng(M * 11 + C + g + s)
+    X = _tensor(rng, M, C * g, "heavy")
+    sel = ref.split_weights(_tensor(rng, 9, C * g, "heavy"), C, g, s)
+    ldq = B.ocs_padded_cols((C + s) * g) + ld_extra
+    q_ref, s_ref, _ = ref.split_act(X, C, g, sel["chan_src"], None, s, 8, threshold=2.0, ldq=ldq)
+    B.ocs_tune("act_np", loads)
+    try:
+        q, sc = gpu_split_act(X, C, g, sel["chan_src"], None, s, 8, threshold=2.0, ldq=ldq)
+    finally:
+        B.ocs_tune("act_np", -1)
     assert np.array_equal(sc, s_ref)
     assert np.array_equal(q, q_ref)
 
