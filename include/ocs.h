@@ -491,7 +491,8 @@ int ocs_calib_mfma(const void *operands, int iters, int workgroups, void *sink, 
  * code pass instead of as a launch of its own; 0: never), "gemm_tile" (tile variant of
  * ocs_qgemm / ocs_qconv: 6, 7, 9, 10, 11, 12, 14, 16, 17, 18, 19, 23, 24; an id a shape cannot use falls
  * back to one it can), "fused_variant" (ocs_split_act_qgemm with more than 128 output columns:
- * 1 = 64-row workgroups, 2 = 128-row ones).  value < 0 restores the default.  Returns OCS_OK or OCS_E_MODE for an
+ * 1 = 64-row workgroups, 2 = 128-row ones), "fused_stride" (rows between that kernel's workgroups: 0 = a
+ * whole tile always, n > 0 = n).  value < 0 restores the default.  Returns OCS_OK or OCS_E_MODE for an
  * unknown key.  The settings belong to the calling thread and affect its own calls only.
  */
 int ocs_tune(const char *key, int value);

@@ -760,6 +760,7 @@ int ocs_tune(const char* key, int value) {
     else if (!strcmp(key, "act_np")) t.act_np = value;
     else if (!strcmp(key, "gemm_tile")) t.gemm_tile = value;
     else if (!strcmp(key, "fused_variant")) t.fused_variant = value;
+    else if (!strcmp(key, "fused_stride")) t.fused_stride = value;
     else if (!strcmp(key, "max_flat")) t.max_flat = value;
     else if (!strcmp(key, "max_grid")) t.max_grid = value;
     else if (!strcmp(key, "max_un")) t.max_un = value;

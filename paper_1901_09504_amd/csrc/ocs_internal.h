@@ -274,6 +274,7 @@ struct Tuning {
     int act_np = -1;    // static grid, un-scaled copies: the loop-free flat pass with this many pieces per XCD run (> 0), never (0), by shape (-1)
     int act_tile = -1;  // static grid, un-scaled copies: tile-ordered pass always (1), never (0), by shape (-1)
     int gemm_tile = -1;
+    int fused_stride = -1;   // rows between the one-launch kernel's workgroups: forced (> 0), a whole tile always (0), by shape (-1)
     int fused_variant = -1;  // workgroup shape / pipeline depth of the split+quantize+GEMM launch (default: by shape)
     int max_flat = -1;  // whole-tensor max|x| of a contiguous tensor as one flat stream (1), by columns (0), default (-1)
     int max_grid = -1;  // workgroups of the flat pass

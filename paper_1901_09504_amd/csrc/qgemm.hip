@@ -707,6 +707,19 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void qgemm_wholek_kernel(
 constexpr int64_t kWholeKMaxLds = 160 * 1024;  // LDS of one CU
 constexpr int kMaxDevices = 64;
 
+// Compute units of the current device (looked up once per device; 256 if the query fails).
+static int compute_units() {
+    static std::atomic<int> cached[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+    int n = cached[dev].load(std::memory_order_acquire);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+        cached[dev].store(n, std::memory_order_release);
+    }
+    return n;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Split + quantize + GEMM in one launch: the A operand is the fp32 activation matrix X [M, C*g]
 // itself.  A workgroup takes 128 rows of X and all N <= 256 output columns, walks K in steps of
@@ -749,7 +762,9 @@ __global__ __launch_bounds__(NT, WPE) void split_act_qgemm_kernel(
     const int32_t* __restrict__ chan_src, const float* __restrict__ thr, float qmax,
     const int8_t* __restrict__ Wq, int64_t ldw, int N, int ksteps_main, int ksteps_all, int rem,
     const float* __restrict__ scale_w, float* __restrict__ scale_x_out, int32_t* __restrict__ acc_out,
-    int64_t ldacc, float* __restrict__ Y, int64_t ldy, FusedLds L) {
+    int64_t ldacc, float* __restrict__ Y, int64_t ldy, FusedLds L, int bm_stride) {
+    // bm_stride: rows between consecutive workgroups' first rows (<= BM): a workgroup owns rows
+    // row0 .. row0 + bm_stride - 1 and the rest of its BM rows are idle (nothing fetched or stored).
     // ksteps_main: whole 64-column steps of X; rem: the columns of X left over after them (< 64).
     // They and the appended columns form the steps ksteps_main .. ksteps_all-1, which are assembled
     // in LDS (`tail`): the left-over columns are quantized straight into its first step.
@@ -772,18 +787,21 @@ __global__ __launch_bounds__(NT, WPE) void split_act_qgemm_kernel(
 
     const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-    const int row0 = (int)blockIdx.x * BM;
+    const int row0 = (int)blockIdx.x * bm_stride;
+    const int row_end = row0 + bm_stride < M ? row0 + bm_stride : M;
     const int T = s * g, tail_steps = ksteps_all - ksteps_main;
 
     // A: the step's BM x 16 float4 numbered row-major; load i of thread t is number i*NT + t, so each
     // load instruction of a wave covers four rows' whole 256 bytes
     const float* a_src[A_PER];
+    unsigned a_ok = 0;  // bit i: load i of this thread lies in a row the workgroup owns
     int a_dst[A_PER];   // byte offset of the resulting code dword inside an A buffer
 #pragma unroll
     for (int i = 0; i < A_PER; ++i) {
         const int f = i * NT + tid, r = f >> 4, f4 = f & 15;
         int gr = row0 + r;
-        gr = gr < M ? gr : M - 1;          // rows past the edge re-read the last row; never stored
+        if (gr < row_end) a_ok |= 1u << i;
+        gr = gr < row_end ? gr : row_end - 1;          // rows past the workgroup's own are never fetched or stored
         a_src[i] = X + (int64_t)gr * ldx + f4 * 4;
         a_dst[i] = r * 64 + swz<64>(r, f4 >> 2) * 16 + (f4 & 3) * 4;
     }
@@ -817,8 +835,9 @@ __global__ __launch_bounds__(NT, WPE) void split_act_qgemm_kernel(
             const int c0 = ((i * NT + tid) & 15) * 4;
             // left-over columns: a float4 that would cross the row's end starts four floats before
             // the end instead, and is shifted into place afterwards (nothing is read past the row)
-            const bool whole = main_step || (rest_step && c0 + 3 < rem);
-            const bool part = rest_step && c0 < rem && !whole;
+            const bool ok = (a_ok >> i) & 1u;
+            const bool whole = ok && (main_step || (rest_step && c0 + 3 < rem));
+            const bool part = ok && rest_step && c0 < rem && !whole;
             const float* src = whole ? a_src[i] + (int64_t)kt * 64
                                      : (part ? a_src[i] + (int64_t)kt * 64 - c0 + (rem - 4)
                                              : reinterpret_cast<const float*>(zero_chunk));
@@ -965,7 +984,7 @@ __global__ __launch_bounds__(NT, WPE) void split_act_qgemm_kernel(
                 stage[((lane >> 5) * 4 + e) * WN + j * 32 + (lane & 31)] = acc[j][q * 4 + e];
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        emit_staged_rows<8, WN>(stage, lane, row0 + wm * 32 + q * 8, wn * WN, wn * WN, M, N, scale, Y, ldy,
+        emit_staged_rows<8, WN>(stage, lane, row0 + wm * 32 + q * 8, wn * WN, wn * WN, row_end, N, scale, Y, ldy,
                                 acc_out, ldacc, vec_y, vec_a, none, 0.0f, nullptr, 0, false);
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -1008,9 +1027,24 @@ static hipError_t run_split_act_qgemm(const float* X, int64_t ldx, int64_t M, in
             opted_in[dev].store(true, std::memory_order_release);
         }
     }
-    return launch_kernel(kTimeGemm, split_act_qgemm_kernel<BN, BM, NT, WPE, SETS>, dim3((unsigned)ceil_div(M, BM)),
+    // When the row tiles would not even fill the chip's workgroup slots once, fewer rows per
+    // workgroup and a workgroup in every slot: the pass is bound by what a compute unit can draw
+    // from memory, so idle matrix rows cost nothing and idle compute units do (392 tiles of 128
+    // rows on 512 slots: 134 -> 122 us on the 256-channel 3x3 layers at 14 x 14, batch 256).
+    int64_t stride = BM;
+    {
+        int wpc = (int)(kWholeKMaxLds / L.total);
+        wpc = wpc > WPE ? WPE : (wpc < 1 ? 1 : wpc);
+        const int64_t slots = (int64_t)compute_units() * wpc;
+        const int ts = tuning().fused_stride;
+        if (ts > 0 && ts <= BM) stride = ts;
+        else if (ts != 0 && ceil_div(M, BM) < slots) stride = ceil_div(M, slots);
+        if (stride < BM / 2) stride = BM / 2;      // (never more than half of a tile idle)
+    }
+    return launch_kernel(kTimeGemm, split_act_qgemm_kernel<BN, BM, NT, WPE, SETS>, dim3((unsigned)ceil_div(M, stride)),
                          dim3(NT), (unsigned)L.total, stream, X, ldx, (int)M, C, g, s, chan_src, thr, qmax,
-                         Wq, ldw, (int)N, ksteps_main, ksteps_all, rem, scale_w, scale_x_out, acc_out, ldacc, Y, ldy, L);
+                         Wq, ldw, (int)N, ksteps_main, ksteps_all, rem, scale_w, scale_x_out, acc_out, ldacc, Y, ldy, L,
+                         (int)stride);
 }
 
 hipError_t launch_split_act_qgemm(const float* X, int64_t ldx, int64_t M, int C, int g, int s,

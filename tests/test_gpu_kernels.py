@@ -532,8 +532,9 @@ def test_qgemm_split_k(parts, M, N, K):
                                        (500, 2048, 4, 103, 256), (300, 3, 49, 1, 64), (100, 37, 4, 6, 70),
                                        (77, 100, 1, 5, 128), (65, 67, 1, 0, 256), (130, 191, 1, 64, 200),
                                        (70, 13, 9, 2, 64)])
-@pytest.mark.parametrize("bits_w,variant", [(4, -1), (8, 1), (8, 2)])    # variants: both workgroup shapes for N > 128
-def test_split_act_qgemm(M, C, g, s, N, bits_w, variant):
+@pytest.mark.parametrize("bits_w,variant,stride", [(4, -1, -1), (8, 1, 0), (8, 2, 0), (4, -1, 37), (8, 2, 100)])
+def test_split_act_qgemm(M, C, g, s, N, bits_w, variant, stride):   # variants: both workgroup shapes for N > 128;
+    # stride: rows between workgroups by shape (-1: with so few rows, half-idle tiles), whole tiles (0), forced
     """X -> codes -> accumulators in one launch: the accumulators are bit for bit the oracle's GEMM on the
     oracle's codes of the expanded X, the outputs within the contract of the two-call path; weights at
     the recommended pitch (for a short K the rows end inside the last K-step)."""
@@ -554,6 +555,7 @@ def test_split_act_qgemm(M, C, g, s, N, bits_w, variant):
     cs = dev(exp["chan_src"])
     th = torch.tensor([T], dtype=torch.float32, device="cuda")
     B.ocs_tune("fused_variant", variant)
+    B.ocs_tune("fused_stride", stride)
     try:
         for want_acc in (True, False):
             acc = torch.full((M, N), -7, dtype=torch.int32, device="cuda") if want_acc else None
@@ -567,6 +569,7 @@ def test_split_act_qgemm(M, C, g, s, N, bits_w, variant):
             assert_y_close(host(Y), y_ref)
     finally:
         B.ocs_tune("fused_variant", -1)
+        B.ocs_tune("fused_stride", -1)
 
 
 def test_split_act_qgemm_equals_the_two_calls_bit_for_bit():
