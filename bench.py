@@ -573,7 +573,7 @@ def main():
                    "stamped_steps": n_stamp},
         "gemm_tops": gemm_tops, "gemm_pct_mfma_peak": 100.0 * gemm_tops / INT8_PEAK_TOPS,
         "split_quant_gbps": x2_gbs, "split_quant_pct_hbm": 100.0 * x2_gbs / HBM_PEAK_GBS,
-        "roofline": {"kernel": "expand_quantize_tile_kernel / expand_quantize_kernel / expand_quantize_in_kernel (ocs_split_act, X2): the 53 "
+        "roofline": {"kernel": "expand_quantize_shot_kernel (expand_quantize_tile_kernel on the stem) (ocs_split_act, X2): the 53 "
                                "launches of one pass", "bound": "hbm",
                      "achieved": x2_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": x2_gbs / HBM_PEAK_GBS,
                      "traffic": None if x2_traffic() is None else x2_traffic() / len(layers),

@@ -302,7 +302,7 @@ __global__ __launch_bounds__(kShotNT) void expand_quantize_shot_kernel(
     for (int i = 0; i < kShotTabPer; ++i) {
         const int k = 4 * Q + tid + i * kShotNT;
         const bool app = k >= K && k < Ke;
-        tsrc[i] = chan_src[app ? k / g : 0];
+        tsrc[i] = chan_src != nullptr ? chan_src[app ? k / g : 0] : 0;     // (no list: no appended columns)
     }
     // main items: item i = (row i / Qc, dword i % Qc)
     f32x4 v[U];
@@ -787,7 +787,7 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
     // its image out in 16-byte pieces, is 6 % ahead there)
     const int np_mode = tuning().act_np;
     const bool odd_narrow = K % 4 != 0 && K < 256 && tile_fits(M, K, (int64_t)s * g, ldq);
-    if (thr != nullptr && partials == nullptr && !halve && chan_src != nullptr && np_mode != 0 && tuning().act_tile <= 0 &&
+    if (thr != nullptr && partials == nullptr && !halve && (chan_src != nullptr || s == 0) && np_mode != 0 && tuning().act_tile <= 0 &&
         tuning().act_map < 0 && (np_mode > 0 || !odd_narrow)) {
         const ShotPlan p = shot_plan(M, K, ldq, np_mode > 0 && np_mode <= kShotMaxU ? np_mode : 0);
 #define OCS_SHOT_ARGS p, X, ldx, M, C, g, s, chan_src, thr, qmax, Xq, ldq, scale_out, stream
