@@ -43,13 +43,13 @@ STATIC_T = 5.0               # the static activation grid's range (inputs are |N
 # reads for the plain copy kernel of known size that runs after the timed region
 # (profiles/bench_config5_headline.md).  Valid only for the kernel source it was measured on:
 # reported as null once that file changes.
-X2_TRAFFIC = {"quantize_hip_sha256": "ca888310f224a3893a64f838459a8fb762110aa5d20fd9bd37757b20a57fae9b",
-              "bytes_per_step": 29206800679}
+X2_TRAFFIC = {"quantize_hip_sha256": "bfc702008ec0f86365ec034fc95f5199ebd7423fb3c2272c93b5f6015af8752c",
+              "bytes_per_step": 28940218561}
 
 
 # The same for the launches of the one-launch pass (`--extras fused`), keyed on the GEMM source.
-FUSED_TRAFFIC = {"qgemm_hip_sha256": "8b40458b3252ba7c9d8798e2a22fa46985c9c57e5006214c295e74f66e2b8d15",
-                 "bytes_per_step": 22972960017}
+FUSED_TRAFFIC = {"qgemm_hip_sha256": "1ebda8dfef53b03a0b4cf29876bc297bfda8359f2ad49c4cace4b706cb0bc41c",
+                 "bytes_per_step": 22973221660}
 
 
 def fused_traffic():
