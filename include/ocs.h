@@ -489,7 +489,7 @@ int ocs_calib_mfma(const void *operands, int iters, int workgroups, void *sink, 
  * (the split+quantize pass; act_tile: the tile-ordered variant never (0) / wherever it fits (1); act_np: the one-shot variant never (0) / with 1..8 loads per lane wherever they hold a row (1..8) / by shape (9 or default)), "max_flat", "max_grid", "max_un", "max_bt" (the whole-tensor max|x|
  * pass), "sel_inline" (most splits for which ocs_split_weights runs the selection inside its
  * code pass instead of as a launch of its own; 0: never), "gemm_tile" (tile variant of
- * ocs_qgemm / ocs_qconv: 6, 7, 9, 10, 11, 12, 14, 16, 17, 18, 19, 23, 24; an id a shape cannot use falls
+ * ocs_qgemm / ocs_qconv: 6, 7, 9, 10, 11, 12, 14, 16, 17, 18, 19, 23, 24, 25; an id a shape cannot use falls
  * back to one it can), "fused_variant" (ocs_split_act_qgemm with more than 128 output columns:
  * 1 = 64-row workgroups, 2 = 128-row ones), "fused_stride" (rows between that kernel's workgroups: 0 = a
  * whole tile always, n > 0 = n).  value < 0 restores the default.  Returns OCS_OK or OCS_E_MODE for an

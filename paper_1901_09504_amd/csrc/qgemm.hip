@@ -1324,6 +1324,9 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
                                                          // is ahead here; behind the pass that wrote the codes
                                                          // it is 7-18 % behind)
         else if (N >= 512 && t256sq >= 512) tile = 12;
+        else if (N >= 512 && t256 >= 128 && t256 < 256 && Kpad >= 4096) tile = 25;   // fewer tiles than compute units and a very long K:
+                                        // 128 x 256 (X rows asked for by two tiles, not four; 43-46 against 45-47 us
+                                        // on the 512 -> 512 3x3 layers at M = 12544; behind at half that K)
         else if (t256 >= 128) tile = 11;                 // N = 256 with K below 1024 included (89 against 92 us)
         else if (t128 >= 48) tile = 23;   // 128-byte K-steps when the operands allow them
         else tile = 6;
@@ -1333,7 +1336,7 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
     // on both operands (the producers' contract) and the walk may include them.
     const int64_t K128 = round_up(Kpad, 128);
     const bool k128 = K128 == Kpad || (ldx >= K128 && ldw >= K128);
-    // Tile variants by id (the dispatcher above picks 6, 9, 11, 12, 16, 17, 19, 23 or 24; the others
+    // Tile variants by id (the dispatcher above picks 6, 9, 11, 12, 16, 17, 19, 23, 24 or 25; the others
     // are kept selectable because the parity tests run every kernel family through them).
     switch (tile) {
         case 6: return run_dma<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
@@ -1358,6 +1361,8 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
                              : run_dma<128, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);
         case 24: return k128 ? run_dma<128, 64, 2, 2, 128, 3>(OCS_GEMM_ARGS128)
                              : run_dma<128, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
+        case 25: return k128 ? run_dma<128, 256, 2, 4, 128, 3>(OCS_GEMM_ARGS128)
+                             : run_dma<256, 128, 4, 2, 64, 4>(OCS_GEMM_ARGS);
         default: return run_dma<64, 64, 2, 2, 64, 6>(OCS_GEMM_ARGS);
     }
 }

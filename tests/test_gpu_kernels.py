@@ -459,7 +459,7 @@ def test_split_weights_halvings_that_leave_the_normal_range():
 
 # ---- ocs_qgemm -------------------------------------------------------------------------------
 
-GEMM_TILES = [6, 7, 9, 10, 11, 12, 14, 16, 17, 18, 19, 23, 24]     # every tile variant of the library
+GEMM_TILES = [6, 7, 9, 10, 11, 12, 14, 16, 17, 18, 19, 23, 24, 25]     # every tile variant of the library
 
 
 @pytest.mark.parametrize("tile", [-1] + GEMM_TILES)
@@ -668,7 +668,7 @@ def test_qconv_equals_the_lowered_gemm_path():
     assert np.array_equal(got["acc"], acc) and np.array_equal(got["Y"], Y)
 
 
-@pytest.mark.parametrize("tile", [-1, 11, 23, 24])
+@pytest.mark.parametrize("tile", [-1, 11, 23, 24, 25])
 @pytest.mark.parametrize("ldx_extra,ldw_extra", [(0, 0), (64, 0), (0, 64), (64, 64), (192, 128)])
 @pytest.mark.parametrize("M,N,K", [(130, 140, 180), (300, 260, 2358)])
 def test_qgemm_k_step_of_128_needs_both_paddings(tile, ldx_extra, ldw_extra, M, N, K):
