@@ -372,9 +372,14 @@ def calib_copy(torch, B, net, reps=4):
     dst = torch.empty_like(src)
     n = src.numel() * 4 // 16 * 16
     us = _timed(torch, lambda: B.ocs_calib_copy(src, dst, n, 1024), reps)
-    return {"kernel": "calib_copy_kernel (16-byte loads and stores, 1024 workgroups)", "bytes_each_way": int(n),
+    us1 = _timed(torch, lambda: B.ocs_calib_copy(src, dst, n, 0), reps)
+    return {"kernel": "calib_copy_kernel (16-byte loads and stores, grid-stride loop of 1024 workgroups: the launches the "
+                      "HBM byte counters are scaled against)", "bytes_each_way": int(n),
             "median_us": us, "read_plus_write_GBps": 2.0 * n / us / 1e3,
-            "frac_hbm": 2.0 * n / us / 1e3 / HBM_PEAK_GBS, "launches": reps + 1}
+            "frac_hbm": 2.0 * n / us / 1e3 / HBM_PEAK_GBS, "launches": reps + 1,
+            "one_shot_form": {"kernel": "calib_copy_shot_kernel (one 16-byte group per lane, a workgroup per 4 KB, no loop)",
+                              "median_us": us1, "read_plus_write_GBps": 2.0 * n / us1 / 1e3,
+                              "frac_hbm": 2.0 * n / us1 / 1e3 / HBM_PEAK_GBS, "launches": reps + 1}}
 
 
 def _timed(torch, fn, reps):
