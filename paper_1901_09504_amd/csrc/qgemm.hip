@@ -1302,7 +1302,7 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
         // wide N is better served by the ring kernel's tile order, see below)
         if (tile == 9 || (tile < 0 && N >= 1024))
             return run_dma<128, 128, 4, 2, 64, 4, true>(OCS_GEMM_ARGS);
-        if (tile != 16 && tile != 17 && tile != 18 && tile != 19) tile = N <= 64 ? 17 : (N >= 512 ? 19 : 16);
+        if (tile != 16 && tile != 17 && tile != 18 && tile != 19) tile = N <= 64 ? 17 : (N >= 512 ? (Kpad <= 192 ? 17 : 19) : 16);
     }
     if (tile < 0) {
         // Measured on MI355X over the layer shapes of the paper's networks.  What a CU can draw is
@@ -1316,7 +1316,8 @@ hipError_t launch_qgemm(const int8_t* Xq, int64_t ldx, const int8_t* Wq, int64_t
         const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 128);
         const int64_t t128 = ceil_div(M, 128) * ceil_div(N, 128);
         const int64_t t256sq = ceil_div(M, 256) * ceil_div(N, 256);
-        if (Kpad <= 320) tile = N <= 64 ? 17 : (N >= 1024 ? 9 : (N >= 512 ? 19 : 16));
+        if (Kpad <= 320) tile = N <= 64 ? 17 : (N >= 1024 ? 9 : (N >= 512 ? (Kpad <= 192 ? 17 : 19) : 16));   // (512 outputs from
+                                        // 128 channels: the 128 x 64 tile, 70 against 83 us at M = 200,704)
         else if (N <= 64) tile = 24;    // 128 x 64 with whole-line (128-byte) K-steps: 134 against 155 us on
                                         // the 64 -> 64 3x3 layers at M = 802,816
         else if (N >= 256 && t256sq >= 192 && Kpad >= 1024) tile = 12;
