@@ -485,8 +485,11 @@ int ocs_calib_mfma(const void *operands, int iters, int workgroups, void *sink, 
 
 /*
  * Launch-shape overrides for benchmarking (no passage of the paper; results never depend
- * on them).  Keys: "act_grid", "act_nt", "act_un", "act_map", "act_wide", "act_dep", "act_tile", "act_np"
- * (the split+quantize pass; act_tile: the tile-ordered variant never (0) / wherever it fits (1); act_np: the one-shot variant never (0) / with 1..8 loads per lane wherever they hold a row (1..8) / by shape (9 or default)), "max_flat", "max_grid", "max_un", "max_bt" (the whole-tensor max|x|
+ * on them).  Keys: "act_grid", "act_nt", "act_un", "act_map", "act_wide", "act_dep", "act_tile",
+ * "act_np" (the split+quantize pass; act_tile: the tile-ordered variant never (0) / wherever it
+ * fits (1); act_np: the one-shot variant never (0) / with 1..8 loads per lane wherever that many
+ * hold a row (1..8) / wherever it serves the shape (9); default: by shape), "max_flat", "max_grid",
+ * "max_un", "max_bt" (the whole-tensor max|x|
  * pass), "sel_inline" (most splits for which ocs_split_weights runs the selection inside its
  * code pass instead of as a launch of its own; 0: never), "gemm_tile" (tile variant of
  * ocs_qgemm / ocs_qconv: 6, 7, 9, 10, 11, 12, 14, 16, 17, 18, 19, 23, 24, 25; an id a shape cannot use falls
