@@ -409,6 +409,28 @@ def test_split_act_one_shot(M, C, g, s, ld_extra, loads):
     assert np.array_equal(q, q_ref)
 
 
+@pytest.mark.parametrize("seed", list(range(24)))
+def test_split_act_static_grid_random_shapes(seed):
+    """The static-grid pass as the library dispatches it (one-shot, tile-ordered or flat, by shape) on
+    seeded random shapes against the oracle: row lengths of every residue modulo 4 and 64, group
+    sizes 1..9, split counts from none to more than the channels, pitches at and beyond the
+    recommended one, a threshold inside the data's range (so both clipping ends occur)."""
+    rng = np.random.default_rng(1000 + seed)
+    g = int(rng.choice([1, 1, 2, 3, 4, 7, 9]))
+    C = int(rng.integers(1, 700 // g + 2))
+    s = int(rng.choice([0, 1, max(1, C // 20), max(1, C // 8), C + 3]))
+    M = int(rng.choice([1, 7, 63, 64, 65, 200, 517, 1500]))
+    ld_extra = int(rng.choice([0, 0, 16, 64, 240]))
+    X = _tensor(rng, M, C * g, "heavy")
+    sel = ref.split_weights(_tensor(rng, 5, C * g, "heavy"), C, g, s)
+    ldq = B.ocs_padded_cols((C + s) * g) + ld_extra
+    thr = float(np.quantile(np.abs(X), 0.98)) if X.size > 4 else 1.0
+    q_ref, s_ref, _ = ref.split_act(X, C, g, sel["chan_src"], None, s, 8, threshold=thr, ldq=ldq)
+    q, sc = gpu_split_act(X, C, g, sel["chan_src"], None, s, 8, threshold=thr, ldq=ldq)
+    assert np.array_equal(sc, s_ref)
+    assert np.array_equal(q, q_ref)
+
+
 @pytest.mark.parametrize("act_dep", [0, 1])
 def test_split_act_deep_halvings(act_dep):
     """Eq. 4 with depth lists no greedy run would produce (the call takes any list): factors down to
