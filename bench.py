@@ -43,7 +43,7 @@ STATIC_T = 5.0               # the static activation grid's range (inputs are |N
 # reads for the plain copy kernel of known size that runs after the timed region
 # (profiles/bench_config5_headline.md).  Valid only for the kernel source it was measured on:
 # reported as null once that file changes.
-X2_TRAFFIC = {"quantize_hip_sha256": "bfc702008ec0f86365ec034fc95f5199ebd7423fb3c2272c93b5f6015af8752c",
+X2_TRAFFIC = {"quantize_hip_sha256": "c5ba9d1d704aee4798e524a931c7dde68afc55e883454bfb91cf43b550b73944",
               "bytes_per_step": 28940218561}
 
 

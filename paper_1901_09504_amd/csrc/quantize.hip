@@ -267,8 +267,9 @@ __global__ __launch_bounds__(kThreads) void expand_quantize_kernel(
 // per lane), turns it into codes, and is done: no loop, no look-ahead registers, one barrier.  The
 // chip's dispatcher hands such workgroups out in order, so the chip works inside one tight window
 // that slides over X, tighter than persistent workgroups keep it (they drift apart): a plain copy
-// written this way moves 6.1 TB/s on this chip against 5.5 TB/s for the grid-stride form, and this
-// pass's 4:1 pattern 6.3 against 5.2.
+// written this way moves 6.0 TB/s on this chip against 5.5 TB/s for the grid-stride form, and this
+// pass's pattern of 16 bytes in and 4 out per lane 6.1 against 5.5 (the library's measurement
+// kernels, calib.hip).
 //   Main items: dword d < Qc = ceil(K/4) of a row, 16 bytes of X each; their codes go straight to
 //   memory (d < Q = floor(K/4)) and into an image of the rows in LDS.
 //   Tail: dwords Q .. D-1 of a row (left-over columns of X, the appended columns, zero padding)
