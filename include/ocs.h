@@ -490,7 +490,7 @@ int ocs_calib_mfma(const void *operands, int iters, int workgroups, void *sink, 
  * fits (1); act_np: the one-shot variant never (0) / with 1..8 loads per lane wherever that many
  * hold a row (1..8) / wherever it serves the shape (9); default: by shape), "max_flat", "max_grid",
  * "max_un", "max_bt" (the whole-tensor max|x|
- * pass), "sel_inline" (most splits for which ocs_split_weights runs the selection inside its
+ * pass; max_flat 2: the flat pass, and ocs_split_act folds its maxima in a launch of its own whatever the tensor's size), "sel_inline" (most splits for which ocs_split_weights runs the selection inside its
  * code pass instead of as a launch of its own; 0: never), "gemm_tile" (tile variant of
  * ocs_qgemm / ocs_qconv: 6, 7, 9, 10, 11, 12, 14, 16, 17, 18, 19, 23, 24, 25; an id a shape cannot use falls
  * back to one it can), "fused_variant" (ocs_split_act_qgemm with more than 128 output columns:

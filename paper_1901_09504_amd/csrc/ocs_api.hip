@@ -422,6 +422,17 @@ int ocs_split_act(const float* X, int64_t M, int C, int g, int64_t ldx, const in
         int n = 0;
         hipError_t e = launch_absmax_partials(X, M, (int64_t)C * g, ldx, partial, &n, st);
         if (e != hipSuccess) return hip_fail(e);
+        // From 160 MB on the maxima are folded into one word by a launch of its own: the streaming
+        // pass then takes its one-shot form, whose workgroups are far too many and too short to fold
+        // a few hundred maxima each (config 5's per-batch pass: 13.4 -> 13.1 ms; on a 116 MB tensor the
+        // extra launch costs what the faster pass gains).
+        const int64_t cap = (int64_t)(w.total - w.partial_off) / 4;
+        if (n > 1 && n < cap && (tuning().max_flat == 2 || M * (int64_t)C * g >= ((int64_t)40 << 20))) {   // (max_flat 2: always, for tests)
+            e = launch_fold_max(partial, n, partial + n, st);
+            if (e != hipSuccess) return hip_fail(e);
+            partial += n;
+            n = 1;
+        }
         e = launch_expand_quantize(X, ldx, M, C, g, num_splits, chan_src, nullptr, nullptr, qmax, Xq,
                                    ldq, scale_out, st, partial, n, clip_ratio);
         if (e != hipSuccess) return hip_fail(e);

@@ -95,6 +95,7 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
                                   float clip_ratio = 1.0f, bool stepwise = false);
 
 // Per-workgroup maxima of |T| (stage 1 of the scalar reduction only): partial[0 .. *entries).
+hipError_t launch_fold_max(const float* in, int n, float* out, hipStream_t stream);
 hipError_t launch_absmax_partials(const float* T, int64_t rows, int64_t cols, int64_t ld,
                                   float* partial, int* entries, hipStream_t stream);
 

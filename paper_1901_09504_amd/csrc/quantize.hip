@@ -286,7 +286,9 @@ __global__ __launch_bounds__(kShotNT) void expand_quantize_shot_kernel(
     const float* __restrict__ X, int64_t ldx, int M, int C, int g, int s,
     const int32_t* __restrict__ chan_src, const float* __restrict__ thr, float qmax,
     int8_t* __restrict__ Xq, int64_t ldq, int R, unsigned magic_qc, unsigned magic_td,
-    float* __restrict__ scale_out) {
+    float* __restrict__ scale_out, float clip) {
+    // clip: the threshold is clip * *thr (1 for a given threshold; the clip ratio when *thr is the
+    // tensor's largest magnitude, left behind by the pass before this one)
     extern __shared__ __align__(16) int8_t slds[];
     const int K = C * g, Q = K / 4, rem = K - 4 * Q, Qc = Q + (rem > 0 ? 1 : 0);
     const int D = (int)(ldq / 4), TD = D - Q, Ke = (C + s) * g;
@@ -336,7 +338,7 @@ __global__ __launch_bounds__(kShotNT) void expand_quantize_shot_kernel(
             tcol[e] = col;
         }
     }
-    const float T = *thr;
+    const float T = clip * *thr;
     const float inv = inv_step_of(T, qmax);
     if (scale_out != nullptr && blockIdx.x == 0 && tid == 0) {
         scale_out[0] = T;
@@ -402,7 +404,7 @@ static ShotPlan shot_plan(int64_t M, int64_t K, int64_t ldq, int force_u = 0) {
 template <int U>
 static hipError_t run_expand_quantize_shot(const ShotPlan& p, const float* X, int64_t ldx, int64_t M, int C, int g,
                                            int s, const int32_t* chan_src, const float* thr, float qmax, int8_t* Xq,
-                                           int64_t ldq, float* scale_out, hipStream_t stream) {
+                                           int64_t ldq, float* scale_out, hipStream_t stream, float clip) {
     const int64_t K = (int64_t)C * g, Q = K / 4, Qc = (K + 3) / 4, TD = ldq / 4 - Q;
     // floor(2^32 / n), or 2^32 - 1 for n = 1: the quotient estimate is then at most one low, which
     // the kernel's correction step absorbs
@@ -415,7 +417,7 @@ static hipError_t run_expand_quantize_shot(const ShotPlan& p, const float* X, in
     const unsigned lds = (unsigned)(((p.R * (ldq + 4) + 15) & ~(int64_t)15) + (TD > 0 ? 4 * TD : 1) * 4);
     return launch_kernel(kTimeSplitQuantize, expand_quantize_shot_kernel<U>, dim3((unsigned)ceil_div(M, p.R)),
                          dim3(kShotNT), lds, stream, X, ldx, (int)M, C, g, s, chan_src, thr, qmax, Xq, ldq, p.R,
-                         magic_qc, magic_td, scale_out);
+                         magic_qc, magic_td, scale_out, clip);
 }
 
 // The same pass with the lanes dealt over the INPUT instead: one lane per 16-byte group of X,
@@ -788,10 +790,13 @@ hipError_t launch_expand_quantize(const float* X, int64_t ldx, int64_t M, int C,
     // its image out in 16-byte pieces, is 6 % ahead there)
     const int np_mode = tuning().act_np;
     const bool odd_narrow = K % 4 != 0 && K < 256 && tile_fits(M, K, (int64_t)s * g, ldq);
-    if (thr != nullptr && partials == nullptr && !halve && (chan_src != nullptr || s == 0) && np_mode != 0 && tuning().act_tile <= 0 &&
+    // (a per-batch grid whose pass before this one left the maximum itself behind, one entry, is served
+    // too: the threshold is then the clip ratio times that entry)
+    const bool given = thr != nullptr && partials == nullptr, one_max = thr == nullptr && partials != nullptr && n_partials == 1;
+    if ((given || one_max) && !halve && (chan_src != nullptr || s == 0) && np_mode != 0 && tuning().act_tile <= 0 &&
         tuning().act_map < 0 && (np_mode > 0 || !odd_narrow)) {
         const ShotPlan p = shot_plan(M, K, ldq, np_mode > 0 && np_mode <= kShotMaxU ? np_mode : 0);
-#define OCS_SHOT_ARGS p, X, ldx, M, C, g, s, chan_src, thr, qmax, Xq, ldq, scale_out, stream
+#define OCS_SHOT_ARGS p, X, ldx, M, C, g, s, chan_src, given ? thr : partials, qmax, Xq, ldq, scale_out, stream, given ? 1.0f : clip_ratio
         switch (p.U) {
             case 1: return run_expand_quantize_shot<1>(OCS_SHOT_ARGS);
             case 2: return run_expand_quantize_shot<2>(OCS_SHOT_ARGS);

@@ -161,6 +161,30 @@ __global__ __launch_bounds__(BT) void absmax_flat_kernel(const float* __restrict
     }
 }
 
+// out[0] = max of the n non-negative floats at in.  One workgroup: for a pass that would otherwise
+// fold the maxima once per workgroup of its own and has a great many small workgroups.
+constexpr int kFoldThreads = 1024;
+__global__ __launch_bounds__(kFoldThreads) void fold_max_kernel(const float* __restrict__ in, int n,
+                                                                float* __restrict__ out) {
+    __shared__ float red[kFoldThreads / 64];
+    float m = 0.0f;
+    for (int i = threadIdx.x; i < n; i += kFoldThreads) m = fmaxf(m, in[i]);
+    const unsigned w = wave_umax32(__float_as_uint(m));   // magnitudes: non-negative, order like unsigned
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = __uint_as_float(w);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float r = red[0];
+#pragma unroll
+        for (int k = 1; k < kFoldThreads / 64; ++k) r = fmaxf(r, red[k]);
+        out[0] = r;
+    }
+}
+
+hipError_t launch_fold_max(const float* in, int n, float* out, hipStream_t stream) {
+    fold_max_kernel<<<1, kFoldThreads, 0, stream>>>(in, n, out);
+    return hipGetLastError();
+}
+
 // Stage 2: colmax[c] = max over partial rows.  Workgroup = 64 columns x 4 row groups.
 __global__ __launch_bounds__(kThreads) void colmax_final_kernel(const float* __restrict__ partial,
                                                                 int row_blocks, int64_t cols,

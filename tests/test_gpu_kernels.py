@@ -409,6 +409,29 @@ def test_split_act_one_shot(M, C, g, s, ld_extra, loads):
     assert np.array_equal(q, q_ref)
 
 
+@pytest.mark.parametrize("M,C,g,s", [(5, 8, 1, 3), (70, 64, 9, 4), (300, 3, 49, 1), (1000, 16, 1, 1), (77, 2048, 1, 103),
+                                     (9, 512, 9, 26), (2100, 512, 1, 26), (4100, 1030, 1, 5)])
+@pytest.mark.parametrize("clip", [1.0, 0.7])
+def test_split_act_per_batch_grid_one_shot(M, C, g, s, clip):
+    """The per-batch grid as large tensors take it: max|X| as one value per workgroup, folded into one
+    word by a launch of its own, then the split+quantize pass in its one-shot form with the clip ratio
+    times that word as its threshold.  Twice in a row on the same scratch space, the second tensor
+    with a smaller maximum (anything left over from the first call would show)."""
+    rng = np.random.default_rng(M + 3 * C + g + s)
+    sel = ref.split_weights(_tensor(rng, 9, C * g, "heavy"), C, g, s)
+    ldq = B.ocs_padded_cols((C + s) * g)
+    B.ocs_tune("max_flat", 2)
+    try:
+        for scale in (1.0, 0.25):
+            X = _tensor(rng, M, C * g, "heavy") * np.float32(scale)
+            q_ref, s_ref, _ = ref.split_act(X, C, g, sel["chan_src"], None, s, 8, threshold=None, clip_ratio=clip, ldq=ldq)
+            q, sc = gpu_split_act(X, C, g, sel["chan_src"], None, s, 8, threshold=None, clip_ratio=clip)
+            assert np.array_equal(sc, s_ref)
+            assert np.array_equal(q, q_ref)
+    finally:
+        B.ocs_tune("max_flat", -1)
+
+
 @pytest.mark.parametrize("seed", list(range(24)))
 def test_split_act_static_grid_random_shapes(seed):
     """The static-grid pass as the library dispatches it (one-shot, tile-ordered or flat, by shape) on
