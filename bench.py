@@ -43,8 +43,8 @@ STATIC_T = 5.0               # the static activation grid's range (inputs are |N
 # reads for the plain copy kernel of known size that runs after the timed region
 # (profiles/bench_config5_headline.md).  Valid only for the kernel source it was measured on:
 # reported as null once that file changes.
-X2_TRAFFIC = {"quantize_hip_sha256": "c5ba9d1d704aee4798e524a931c7dde68afc55e883454bfb91cf43b550b73944",
-              "bytes_per_step": 28940218561}
+X2_TRAFFIC = {"quantize_hip_sha256": "af4bb4e0e029d50a5d0fd005ad943fb80f02f0f7054c896d3ab774679a02eb2c",
+              "bytes_per_step": 28940640069}
 
 
 # The same for the launches of the one-launch pass (`--extras fused`), keyed on the GEMM source.
