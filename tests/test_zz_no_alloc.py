@@ -49,3 +49,20 @@ def test_static_scratch_matches_workspace_call_twice_in_a_row():
             assert np.array_equal(q0, q1) and np.array_equal(s0.view(np.uint32), s1.view(np.uint32))
             qr, sr, _ = ref.split_act(X, Cn, g, cs, depth, s, 8, threshold=threshold, clip_ratio=clip, ldq=ldq)
             assert np.array_equal(q1, qr) and np.array_equal(s1.view(np.uint32), sr.view(np.uint32))
+
+
+def test_static_scratch_with_the_maxima_folded_by_a_launch_of_their_own():
+    """The per-batch grid as tensors from 160 MB on take it (the maxima of the max|X| pass folded into
+    one word of the scratch space, the one-shot pass behind it), forced here on small tensors: same
+    bits from both entry points and from the oracle, twice in a row, the second input smaller."""
+    G.require_gpu()
+    B.ocs_tune("max_flat", 2)
+    try:
+        for seed, (M, Cn, g, s) in enumerate([(3001, 96, 9, 5), (257, 40, 1, 3)]):
+            X, cs, _ = _inputs(2000 + seed, M, Cn, g, s)
+            q0, s0, q1, s1, ldq = _both(X, Cn, g, cs, None, s, 8, None, 0.8)
+            assert np.array_equal(q0, q1) and np.array_equal(s0.view(np.uint32), s1.view(np.uint32))
+            qr, sr, _ = ref.split_act(X, Cn, g, cs, None, s, 8, threshold=None, clip_ratio=0.8, ldq=ldq)
+            assert np.array_equal(q1, qr) and np.array_equal(s1.view(np.uint32), sr.view(np.uint32))
+    finally:
+        B.ocs_tune("max_flat", -1)
